@@ -1,0 +1,158 @@
+/*
+ * hg_attn.h -- C ABI of the partitioned decode-attention library for AMD MI355X (gfx950).
+ *
+ * The operation (paper Section 2.1 and Section 4.2): during decode, ONE new query token per
+ * sequence attends over that sequence's whole KV cache.  With per-head dimension d,
+ *
+ *     s_j = scale * (q . k_j),   p = softmax_j(s),   out = sum_j p_j v_j,      scale = 1/sqrt(d).
+ *
+ * The logit stage is independent per cached token, so the cache can be cut along the token axis
+ * into positional ranges held by different executors (Section 4.2; Section 4.2.3, Token Mapper),
+ * and the recombined result has to equal monolithic execution (Section 4.2.3, Token
+ * Concatenator; Section 4.6 step 5).  This library expresses one range's contribution as the
+ * softmax statistics
+ *
+ *     m = max_j s_j,    l = sum_j exp(s_j - m),    O = sum_j exp(s_j - m) v_j      (j in range)
+ *
+ * and recombines triples exactly:
+ *
+ *     M = max_p m_p,  w_p = exp(m_p - M),  L = sum_p w_p l_p,  out = sum_p w_p O_p / L.
+ *
+ * That is algebraically the same as concatenating the ranges' raw logits in token order and
+ * taking one softmax, but a range's result is d+2 numbers instead of one logit and one value
+ * row per token.
+ *
+ * General conventions
+ *   - Every pointer marked DEVICE is memory of the current HIP device, owned by the caller.
+ *     Every pointer marked HOST is ordinary host memory; it is consumed before the call returns
+ *     and may be freed or reused immediately afterwards.
+ *   - The library allocates nothing.  Scratch memory comes in through `workspace`
+ *     (DEVICE, 256-byte aligned, at least the size the matching *_workspace_size call reports).
+ *   - All device work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream).  No call synchronises with the device.
+ *   - Validation is finished on the host before anything is enqueued: on any error status
+ *     nothing has been launched and no output byte has been touched.
+ *   - The cache of sequence b holds seq_lens[b] valid tokens, the current token included (its
+ *     K and V are appended before attention, Section 2.1); no mask is applied.
+ *   - Grouped-query attention: query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - Arithmetic: K, V, q are read in `dtype`; products, sums, exponentials, the triples and
+ *     the outputs are fp32.  Inputs containing Inf or NaN give undefined results.
+ *   - Concurrent calls must not share a workspace.
+ */
+#ifndef HG_ATTN_H
+#define HG_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum hg_status {
+    HG_OK = 0,
+    HG_ERR_NULL = -1,      /* a required pointer is NULL                                        */
+    HG_ERR_SHAPE = -2,     /* batch/heads/head_dim/strides/alignment/counts not supported       */
+    HG_ERR_DTYPE = -3,     /* dtype is not HG_F16 or HG_F32                                     */
+    HG_ERR_RANGE = -4,     /* a range or CSR offset is malformed or exceeds its sequence        */
+    HG_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or smaller than required               */
+    HG_ERR_LAUNCH = -6     /* the HIP runtime refused a copy or a launch (details on stderr)    */
+} hg_status;
+
+typedef enum hg_dtype { HG_F16 = 0, HG_F32 = 1 } hg_dtype;
+
+/*
+ * One decode-attention problem: a batch of sequences, one query token each.
+ *   q   DEVICE  [batch][n_q_heads][head_dim], contiguous, 16-byte aligned.
+ *   k,v DEVICE  element (b, g, t, c) is at base + b*stride_b + g*stride_h + t*stride_t + c,
+ *               strides counted in ELEMENTS; the channel stride is 1.  Bases are 16-byte aligned
+ *               and every stride is a multiple of 16 bytes, so each row is 16-byte aligned.
+ *               K and V use the same strides.  Rows at t >= seq_lens[b] are never read.
+ *   seq_lens HOST [batch], 0 <= seq_lens[b].
+ *   head_dim 64 or 128.  n_q_heads % n_kv_heads == 0.
+ *   scale   multiplies q.k before the softmax (natural-log domain); callers pass 1/sqrt(head_dim).
+ */
+typedef struct hg_attn_desc {
+    const void *q;
+    const void *k;
+    const void *v;
+    int64_t stride_b, stride_h, stride_t;
+    const int32_t *seq_lens;
+    int32_t batch, n_q_heads, n_kv_heads, head_dim;
+    int32_t dtype; /* hg_dtype */
+    float scale;
+} hg_attn_desc;
+
+/* Tokens [begin, end) of sequence `seq` (the Token Mapper's positional range, Section 4.2.3).
+ * 0 <= begin <= end <= seq_lens[seq]; begin == end is an empty range. */
+typedef struct hg_range {
+    int32_t seq, begin, end;
+} hg_range;
+
+/* Text for a status code; never NULL; static storage. */
+const char *hg_strerror(hg_status status);
+
+/*
+ * hg_attn_partial -- partial softmax statistics of each listed range (Section 4.2: every
+ * executor computes the logits of the keys it holds; here it also folds them into (m, l, O)).
+ *
+ *   ranges   HOST   [n_ranges]; any order, may overlap or leave gaps; each is computed on its own.
+ *   m, l     DEVICE [n_ranges][n_q_heads] fp32.   m is the true maximum of the scaled logits in
+ *                   natural-log units; l and O are relative to that m.
+ *   o        DEVICE [n_ranges][n_q_heads][head_dim] fp32.
+ *   An empty range yields m = -inf, l = 0, O = 0.
+ *   workspace/ws_bytes  see hg_attn_partial_workspace_size (same desc and ranges).
+ *
+ * Merging the triples of ranges that tile [0, seq_lens[b]) exactly once reproduces hg_attn_full.
+ */
+hg_status hg_attn_partial_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges,
+                                         size_t *bytes);
+hg_status hg_attn_partial(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, float *m, float *l,
+                          float *o, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * hg_attn_merge -- exact recombination of triples (Section 4.2.3, Token Concatenator, in
+ * statistics form).
+ *
+ *   m, l, o    DEVICE triples laid out as hg_attn_partial writes them ([n_triples][n_q_heads]...).
+ *   group_ptr  HOST   CSR offsets [n_groups+1], non-decreasing, group_ptr[0] >= 0: group i merges
+ *                     triples group_ptr[i] .. group_ptr[i+1]-1, separately for every query head.
+ *                     The order of the triples inside a group does not matter.
+ *   out        DEVICE [n_groups][n_q_heads][head_dim] fp32.
+ *   lse_out    DEVICE [n_groups][n_q_heads] fp32 or NULL:  M + log L  (natural log).
+ *   Triples with l == 0 are ignored; a group with L == 0 gives out = 0, lse = -inf.
+ */
+hg_status hg_attn_merge_workspace_size(int32_t n_groups, size_t *bytes);
+hg_status hg_attn_merge(const float *m, const float *l, const float *o, const int32_t *group_ptr, int32_t n_groups,
+                        int32_t n_q_heads, int32_t head_dim, float *out, float *lse_out, void *workspace,
+                        size_t ws_bytes, void *stream);
+
+/*
+ * hg_attn_full -- the unsplit reference path ("monolithic execution", Section 4.2.3): softmax
+ * attention of every sequence over its whole cache [0, seq_lens[b]).
+ *
+ *   out      DEVICE [batch][n_q_heads][head_dim] fp32.
+ *   lse_out  DEVICE [batch][n_q_heads] fp32 or NULL.
+ *   A sequence with seq_lens[b] == 0 gives out = 0, lse = -inf.
+ */
+hg_status hg_attn_full_workspace_size(const hg_attn_desc *desc, size_t *bytes);
+hg_status hg_attn_full(const hg_attn_desc *desc, float *out, float *lse_out, void *workspace, size_t ws_bytes,
+                       void *stream);
+
+/*
+ * Host-side planning, exposed for inspection and tests.  The token axis of every range is cut
+ * into tiles (one workgroup each) so that long ranges fill the whole chip; tiles never cross a
+ * range boundary.  Reports the tile length the library would use for this problem and the
+ * number of tiles.  No device work.
+ */
+hg_status hg_attn_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, int32_t *tile_tokens,
+                       int64_t *n_tiles);
+
+/* Tuning knob: force the tile length in tokens (multiple of 64, 64..65536); 0 restores the
+ * built-in choice.  Process-wide; not thread-safe against concurrent calls. */
+hg_status hg_attn_set_tile_tokens(int32_t tile_tokens);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HG_ATTN_H */

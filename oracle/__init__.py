@@ -1,0 +1,13 @@
+"""fp64 CPU oracle for partitioned decode attention -- TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this package.
+The product path (the HIP library and its binding) never does.
+"""
+from .oracle import (  # noqa: F401
+    attn_concat,
+    attn_full,
+    attn_merge,
+    attn_partial,
+    build,
+    max_threads,
+)

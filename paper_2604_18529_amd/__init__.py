@@ -1,0 +1,25 @@
+"""Partitioned decode attention for AMD MI355X (gfx950): hand-written HIP kernels behind a
+C ABI (``include/hg_attn.h``) plus this thin Python binding.
+
+``hg_attn_partial`` / ``hg_attn_merge`` / ``hg_attn_full`` are resolved lazily so that importing
+the package (for example to reach ``workloads``) does not require the built library.
+"""
+
+_API = (
+    "hg_attn_partial",
+    "hg_attn_merge",
+    "hg_attn_full",
+    "hg_attn_plan",
+    "hg_attn_set_tile_tokens",
+    "hg_strerror",
+    "HgError",
+    "load_library",
+)
+
+
+def __getattr__(name):
+    if name in _API:
+        from . import hg_attn as _binding
+
+        return getattr(_binding, name)
+    raise AttributeError(name)

@@ -1,0 +1,226 @@
+"""Seeded synthetic inputs shaped like the paper's long-context decode workloads.
+
+This module holds input generation only -- none of the attention arithmetic.  Both the HIP path
+and the CPU oracle consume the tensors made here (the same bits), and neither is imported here.
+
+The five standard workloads mirror a tiny MHA case, three OPT-family decoder-layer shapes
+(heads x head_dim of the 6.7B / 13B / 30B models the paper's evaluation section draws on, here
+with longer contexts) and a 70B-class grouped-query layer.  Real model weights and evaluation
+data are replaced by N(0,1) tensors of those shapes; see ``WORKLOADS``.
+
+Recipe (every draw seeded; seed 0 unless stated):
+  * q, K, V are drawn as fp32 N(0,1), one (sequence, KV head) slab at a time, and rounded once
+    to the storage dtype.
+  * "outlier channels": per KV head, 4 distinct channels (seeded choice) are multiplied by 8
+    after rounding (exact in fp16).
+  * partition tables are positional ranges that tile [0, N_b) exactly once:
+      - "at": fixed cut points;  - "half": one cut at N_b // 2;
+      - "ratios": w_i ~ U[0.1, 0.8], cut points round(N_b * cumsum(w / sum w));
+      - "dirichlet": r ~ Dirichlet(1,...,1), cut points round(N_b * cumsum r); empty ranges kept.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+Range = Tuple[int, int, int]  # (seq, begin, end)
+
+
+@dataclasses.dataclass(frozen=True)
+class WorkloadSpec:
+    name: str
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    dtype: str  # "f16" | "f32"
+    n_min: int  # context length is uniform in [n_min, n_max]
+    n_max: int
+    partition: str  # "at" | "half" | "ratios" | "dirichlet" | "none"
+    n_parts: int = 1
+    cuts: Tuple[int, ...] = ()
+    outlier_k: bool = False
+    outlier_v: bool = False
+    seed: int = 0
+
+    def scaled(self, **kw) -> "WorkloadSpec":
+        return dataclasses.replace(self, **kw)
+
+
+# The benchmark configurations, in order.  Index 1 is the one the headline metric is timed on.
+WORKLOADS: List[WorkloadSpec] = [
+    WorkloadSpec("tiny-mha-512", 1, 4, 4, 64, "f32", 512, 512, "at", 2, cuts=(300,)),
+    WorkloadSpec("opt6.7b-b8-8k", 8, 32, 32, 128, "f16", 8192, 8192, "half", 2, outlier_k=True, outlier_v=True),
+    WorkloadSpec("opt13b-b16-ragged16k-32k", 16, 40, 40, 128, "f16", 16384, 32768, "ratios", 3),
+    WorkloadSpec("opt30b-b4-128k", 4, 56, 56, 128, "f16", 131072, 131072, "dirichlet", 8),
+    WorkloadSpec("gqa70b-b1-1m", 1, 64, 8, 128, "f16", 1048576, 1048576, "dirichlet", 16, outlier_k=True),
+]
+
+
+@dataclasses.dataclass
+class Workload:
+    spec: WorkloadSpec
+    q: torch.Tensor  # [B, Hq, d]
+    k: torch.Tensor  # [B, Hkv, Nmax, d]  (or a strided view, see layout)
+    v: torch.Tensor
+    seq_lens: np.ndarray  # int32 [B]
+    scale: float
+    ranges: List[Range]  # all sequences, grouped by sequence, ascending token order
+    group_ptr: np.ndarray  # int32 [B+1]: ranges[group_ptr[b]:group_ptr[b+1]] belong to sequence b
+
+    @property
+    def kv_bytes(self) -> int:
+        """K and V bytes inside the valid caches, each row counted once per KV head."""
+        es = self.k.element_size()
+        return int(2 * self.spec.n_kv_heads * int(self.seq_lens.sum()) * self.spec.head_dim * es)
+
+
+def _torch_dtype(name: str) -> torch.dtype:
+    return {"f16": torch.float16, "f32": torch.float32}[name]
+
+
+def _stream_seed(seed: int, *keys: int) -> int:
+    """Independent stream ids from small integer keys (no hashing of strings, no arithmetic of
+    the method): a fixed mixed-radix combination."""
+    s = seed
+    for key in keys:
+        s = (s * 1000003 + key + 1) % (2**31 - 1)
+    return s
+
+
+def make_seq_lens(spec: WorkloadSpec) -> np.ndarray:
+    rng = np.random.RandomState(_stream_seed(spec.seed, 11))
+    if spec.n_min == spec.n_max:
+        return np.full(spec.batch, spec.n_max, dtype=np.int32)
+    return rng.randint(spec.n_min, spec.n_max + 1, size=spec.batch).astype(np.int32)
+
+
+def make_partitions(spec: WorkloadSpec, seq_lens: np.ndarray) -> Tuple[List[Range], np.ndarray]:
+    """Positional ranges per sequence that tile [0, N_b) exactly once (empty ranges allowed)."""
+    rng = np.random.RandomState(_stream_seed(spec.seed, 13))
+    ranges: List[Range] = []
+    group_ptr = [0]
+    for b in range(spec.batch):
+        n = int(seq_lens[b])
+        if spec.partition == "none":
+            bounds = [0, n]
+        elif spec.partition == "at":
+            bounds = [0] + [min(int(c), n) for c in spec.cuts] + [n]
+        elif spec.partition == "half":
+            bounds = [0, n // 2, n]
+        elif spec.partition == "ratios":
+            w = rng.uniform(0.1, 0.8, size=spec.n_parts)
+            cum = np.cumsum(w / w.sum())
+            bounds = [0] + [int(round(n * c)) for c in cum]
+        elif spec.partition == "dirichlet":
+            r = rng.dirichlet(np.ones(spec.n_parts))
+            cum = np.cumsum(r)
+            bounds = [0] + [int(round(n * c)) for c in cum]
+        else:
+            raise ValueError(spec.partition)
+        bounds[-1] = n
+        for i in range(1, len(bounds)):  # keep the cut points monotone after rounding
+            bounds[i] = min(max(bounds[i], bounds[i - 1]), n)
+        for i in range(len(bounds) - 1):
+            ranges.append((b, bounds[i], bounds[i + 1]))
+        group_ptr.append(len(ranges))
+    return ranges, np.asarray(group_ptr, dtype=np.int32)
+
+
+def _outlier_channels(spec: WorkloadSpec, which: int) -> np.ndarray:
+    """[B, Hkv, 4] distinct channel indices per KV head."""
+    rng = np.random.RandomState(_stream_seed(spec.seed, 17, which))
+    idx = np.empty((spec.batch, spec.n_kv_heads, 4), dtype=np.int64)
+    for b in range(spec.batch):
+        for g in range(spec.n_kv_heads):
+            idx[b, g] = rng.choice(spec.head_dim, size=4, replace=False)
+    return idx
+
+
+def _fill_normal(dst: torch.Tensor, seed: int) -> None:
+    """dst[...] <- N(0,1) drawn in fp32 on dst's device, rounded once to dst's dtype.
+    Filled slab by slab over the leading axes so the fp32 temporary stays small."""
+    gen = torch.Generator(device=dst.device)
+    gen.manual_seed(seed)
+    if dst.ndim <= 2:
+        dst.copy_(torch.randn(dst.shape, generator=gen, device=dst.device, dtype=torch.float32))
+        return
+    flat = dst.reshape(-1, dst.shape[-2], dst.shape[-1]) if dst.is_contiguous() else None
+    if flat is None:
+        for i in range(dst.shape[0]):
+            _fill_normal(dst[i], _stream_seed(seed, i))
+        return
+    for i in range(flat.shape[0]):
+        flat[i].copy_(torch.randn(flat[i].shape, generator=gen, device=dst.device, dtype=torch.float32))
+
+
+def make_workload(spec: WorkloadSpec, device="cpu", layout: str = "bhtd") -> Workload:
+    """Build the tensors of a workload on ``device``.
+
+    layout "bhtd": K, V are contiguous [B, Hkv, Nmax, d] (stride_t = d).
+    layout "bthd": storage is [B, Nmax, Hkv, d]; the returned K, V are the [B, Hkv, Nmax, d]
+                   views of it (stride_t = Hkv * d, stride_h = d).
+    Rows at t >= seq_lens[b] hold finite filler that no correct reader touches.
+    """
+    dt = _torch_dtype(spec.dtype)
+    dev = torch.device(device)
+    B, Hq, Hkv, d, nmax = spec.batch, spec.n_q_heads, spec.n_kv_heads, spec.head_dim, spec.n_max
+    seq_lens = make_seq_lens(spec)
+    ranges, group_ptr = make_partitions(spec, seq_lens)
+
+    q = torch.empty((B, Hq, d), dtype=dt, device=dev)
+    _fill_normal(q, _stream_seed(spec.seed, 1))
+    if layout == "bhtd":
+        k = torch.empty((B, Hkv, nmax, d), dtype=dt, device=dev)
+        v = torch.empty((B, Hkv, nmax, d), dtype=dt, device=dev)
+        _fill_normal(k, _stream_seed(spec.seed, 2))
+        _fill_normal(v, _stream_seed(spec.seed, 3))
+    elif layout == "bthd":
+        ks = torch.empty((B, nmax, Hkv, d), dtype=dt, device=dev)
+        vs = torch.empty((B, nmax, Hkv, d), dtype=dt, device=dev)
+        _fill_normal(ks, _stream_seed(spec.seed, 2))
+        _fill_normal(vs, _stream_seed(spec.seed, 3))
+        k, v = ks.permute(0, 2, 1, 3), vs.permute(0, 2, 1, 3)
+    else:
+        raise ValueError(layout)
+
+    for flag, tensor, which in ((spec.outlier_k, k, 0), (spec.outlier_v, v, 1)):
+        if not flag:
+            continue
+        idx = _outlier_channels(spec, which)
+        for b in range(B):
+            for g in range(Hkv):
+                ch = torch.as_tensor(idx[b, g], device=dev)
+                tensor[b, g, :, ch] = tensor[b, g, :, ch] * 8
+    return Workload(spec, q, k, v, seq_lens, 1.0 / math.sqrt(d), ranges, group_ptr)
+
+
+def bitplane_values(n_tokens: int, head_dim: int, dtype: torch.dtype, device="cpu") -> torch.Tensor:
+    """[n_tokens, head_dim] with entry (j, c) = bit c of the token index j for c < 24, else 0.
+    With all-zero queries every softmax weight is equal, so the unnormalised value sum of a
+    range is, per channel, the COUNT of member tokens whose index has that bit set -- an integer
+    that pins exactly which tokens a range covered."""
+    j = torch.arange(n_tokens, device=device, dtype=torch.int64).unsqueeze(1)
+    c = torch.arange(head_dim, device=device, dtype=torch.int64).unsqueeze(0)
+    bits = torch.where(c < 24, (j >> torch.clamp(c, max=23)) & 1, torch.zeros_like(j))
+    return bits.to(dtype)
+
+
+def random_ranges(seq_lens: Sequence[int], n_ranges: int, seed: int, max_len: Optional[int] = None) -> List[Range]:
+    """Arbitrary (possibly overlapping, empty, unordered) ranges for stress tests."""
+    rng = np.random.RandomState(seed)
+    out: List[Range] = []
+    B = len(seq_lens)
+    for _ in range(n_ranges):
+        b = int(rng.randint(0, B))
+        n = int(seq_lens[b])
+        a = int(rng.randint(0, n + 1))
+        e = int(rng.randint(a, n + 1))
+        if max_len is not None:
+            e = min(e, a + max_len)
+        out.append((b, a, e))
+    return out

@@ -1,0 +1,396 @@
+"""Pins for the fp64 CPU oracle (no GPU).
+
+The paper prints no worked numeric example and no tensor values for this path, so the oracle is
+pinned to what the mathematics fixes: brute force in exact rational arithmetic on tiny inputs,
+closed forms (one key, identical keys, zero query, two tokens = logistic, constant values),
+invariances (key shift, partition choice, triple order), the library routines
+scipy.special.softmax / logsumexp, and exact integer counts (bit-plane values).  Each test
+names the mistake it is meant to catch.
+"""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.special
+
+import oracle
+
+RNG = np.random.RandomState
+
+
+def _rand(rng, shape, dtype):
+    return rng.standard_normal(shape).astype(dtype)
+
+
+def _case(seed, B, Hq, Hkv, N, d, dtype=np.float32):
+    rng = RNG(seed)
+    q = _rand(rng, (B, Hq, d), dtype)
+    k = _rand(rng, (B, Hkv, N, d), dtype)
+    v = _rand(rng, (B, Hkv, N, d), dtype)
+    return q, k, v
+
+
+# ---- exact widening of fp16 --------------------------------------------------------------------
+
+
+def test_fp16_bit_patterns_widen_exactly():
+    """Every finite binary16 pattern must reach the arithmetic unchanged (catches a wrong
+    exponent bias, subnormal or sign handling in the oracle's own decoder).  With d = 1,
+    q = 1, scale = 1 and one-token ranges, m is the key itself and O is the value itself."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = bits.view(np.float16)
+    keep = np.isfinite(vals)
+    vals = vals[keep]
+    n = vals.size
+    q = np.ones((1, 1, 1), dtype=np.float16)
+    k = vals.reshape(1, 1, n, 1).copy()
+    v = vals[::-1].reshape(1, 1, n, 1).copy()
+    ranges = [(0, j, j + 1) for j in range(n)]
+    m, l, o = oracle.attn_partial(q, k, v, [n], 1.0, ranges)
+    assert np.array_equal(m[:, 0], vals.astype(np.float64))
+    assert np.array_equal(o[:, 0, 0], vals[::-1].astype(np.float64))
+    assert np.all(l == 1.0)
+
+
+# ---- P1 brute force in rational arithmetic -----------------------------------------------------
+
+
+def _brute(q, k, v, scale, tokens):
+    """softmax(scale q.k) . v over the listed tokens for one head; dot products exact."""
+    qf = [Fraction(float(x)) for x in q]
+    s = []
+    for t in tokens:
+        dot = sum(a * Fraction(float(b)) for a, b in zip(qf, k[t]))
+        s.append(float(Fraction(scale) * dot))
+    mx = max(s)
+    w = [math.exp(x - mx) for x in s]
+    den = math.fsum(w)
+    out = [math.fsum(w[i] * float(v[t][c]) for i, t in enumerate(tokens)) / den for c in range(len(v[0]))]
+    return out, mx, den, mx + math.log(den)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_brute_force_tiny(seed, dtype):
+    """All four routines against the definition evaluated independently (N <= 8, d <= 4)."""
+    B, Hq, Hkv, N, d = 2, 4, 2, 8, 4
+    q, k, v = _case(seed, B, Hq, Hkv, N, d, dtype)
+    seq_lens = [8, 5]
+    scale = 0.5
+    out, lse = oracle.attn_full(q, k, v, seq_lens, scale)
+    ranges = [(0, 0, 3), (0, 3, 8), (1, 0, 1), (1, 1, 5), (1, 2, 2)]
+    m, l, o = oracle.attn_partial(q, k, v, seq_lens, scale, ranges)
+    mo, mlse = oracle.attn_merge(m, l, o, [0, 2, 5])
+    co = oracle.attn_concat(q, k, v, seq_lens, scale, ranges)
+    G = Hq // Hkv
+    for b in range(B):
+        for h in range(Hq):
+            ref, _, _, rlse = _brute(q[b, h], k[b, h // G], v[b, h // G], scale, list(range(seq_lens[b])))
+            assert np.allclose(out[b, h], ref, rtol=0, atol=1e-13)
+            assert abs(lse[b, h] - rlse) < 1e-13
+            assert np.allclose(mo[b, h], ref, rtol=0, atol=1e-13)
+            assert abs(mlse[b, h] - rlse) < 1e-13
+            assert np.allclose(co[b, h], ref, rtol=0, atol=1e-13)
+    for r, (b, s, e) in enumerate(ranges):
+        for h in range(Hq):
+            if s == e:
+                assert m[r, h] == -np.inf and l[r, h] == 0 and not o[r, h].any()
+                continue
+            ref, mx, den, _ = _brute(q[b, h], k[b, h // G], v[b, h // G], scale, list(range(s, e)))
+            assert abs(m[r, h] - mx) < 1e-14
+            assert abs(l[r, h] - den) < 1e-13
+            assert np.allclose(o[r, h] / l[r, h], ref, rtol=0, atol=1e-13)
+
+
+# ---- P2 / P3 / P4 / P8 closed forms ------------------------------------------------------------
+
+
+def test_one_key_returns_its_value():
+    q, k, v = _case(3, 2, 3, 3, 1, 8)
+    out, lse = oracle.attn_full(q, k, v, [1, 1], 0.7)
+    assert np.array_equal(out, v[:, :, 0, :].astype(np.float64))
+    m, l, o = oracle.attn_partial(q, k, v, [1, 1], 0.7, [(0, 0, 1), (1, 0, 1)])
+    s0 = 0.7 * np.einsum("bhd,bhd->bh", q.astype(np.float64), k[:, :, 0].astype(np.float64))
+    assert np.allclose(m, s0, rtol=0, atol=1e-15)
+    assert np.all(l == 1.0)
+    assert np.array_equal(o, v[:, :, 0, :].astype(np.float64))
+    assert np.allclose(lse, s0, rtol=0, atol=1e-15)
+
+
+def test_identical_keys_give_mean_of_values():
+    rng = RNG(4)
+    N, d = 37, 16
+    q = _rand(rng, (1, 2, d), np.float32)
+    krow = _rand(rng, (1, 2, 1, d), np.float32)
+    k = np.repeat(krow, N, axis=2)
+    v = _rand(rng, (1, 2, N, d), np.float32)
+    out, lse = oracle.attn_full(q, k, v, [N], 0.25)
+    assert np.allclose(out[0], v[0].astype(np.float64).mean(axis=1), rtol=0, atol=1e-14)
+    m, l, _ = oracle.attn_partial(q, k, v, [N], 0.25, [(0, 0, N)])
+    s = 0.25 * (q[0].astype(np.float64) * krow[0, :, 0].astype(np.float64)).sum(-1)
+    assert np.allclose(m[0], s, atol=1e-15) and np.all(l[0] == N)
+    assert np.allclose(lse[0], s + math.log(N), atol=1e-14)
+
+
+def test_zero_query_counts_tokens_exactly():
+    """q = 0: every logit is 0, so m = 0 and l is the range length as an exact integer
+    (catches an off-by-one in range membership)."""
+    _, k, v = _case(5, 1, 2, 2, 200, 8)
+    q = np.zeros((1, 2, 8), dtype=np.float32)
+    ranges = [(0, 0, 200), (0, 17, 118), (0, 199, 200), (0, 50, 50)]
+    m, l, o = oracle.attn_partial(q, k, v, [200], 1.0, ranges)
+    for r, (_, s, e) in enumerate(ranges):
+        if e > s:
+            assert np.all(m[r] == 0.0) and np.all(l[r] == e - s)
+            assert np.allclose(o[r], v[0, :, s:e].astype(np.float64).sum(axis=1), atol=1e-12)
+
+
+def _bit_count(n, c):
+    """#{j in [0, n): bit c of j set}, closed form."""
+    period = 1 << (c + 1)
+    return (n // period) * (1 << c) + max(0, n % period - (1 << c))
+
+
+def test_bitplane_values_pin_range_membership():
+    """V[j][c] = bit c of j and q = 0 make O_p[c] an integer count with a closed form; any token
+    wrongly included or dropped changes at least one count."""
+    N, d = 1500, 16
+    rng = RNG(6)
+    k = _rand(rng, (1, 1, N, d), np.float16)
+    j = np.arange(N)[:, None]
+    c = np.arange(d)[None, :]
+    v = ((j >> c) & 1).astype(np.float16).reshape(1, 1, N, d)
+    q = np.zeros((1, 1, d), dtype=np.float16)
+    ranges = [(0, 0, N), (0, 1, 1024), (0, 1023, 1025), (0, 777, 778), (0, 512, 1500)]
+    _, l, o = oracle.attn_partial(q, k, v, [N], 0.125, ranges)
+    for r, (_, s, e) in enumerate(ranges):
+        want = [_bit_count(e, cc) - _bit_count(s, cc) for cc in range(d)]
+        assert o[r, 0].tolist() == [float(w) for w in want]
+        assert l[r, 0] == e - s
+
+
+def test_constant_values_pass_through():
+    """V_j = c for all j gives out = c whatever K and q are (catches a missing 1/L)."""
+    q, k, _ = _case(7, 2, 4, 2, 33, 8)
+    cvec = RNG(8).standard_normal(8).astype(np.float32)
+    v = np.broadcast_to(cvec, (2, 2, 33, 8)).copy()
+    out, _ = oracle.attn_full(q, k, v, [33, 20], 0.3)
+    assert np.allclose(out, cvec.astype(np.float64), rtol=0, atol=1e-14)
+
+
+# ---- P6 spike at a range boundary --------------------------------------------------------------
+
+
+def test_spike_belongs_to_exactly_one_side_of_a_cut():
+    """One key aligned with q gives a logit far above the rest; m of the two ranges meeting at a
+    cut shows which side owns the token (catches end-inclusive or begin-exclusive ranges)."""
+    N, d = 64, 8
+    q, k, v = _case(9, 1, 1, 1, N, d)
+    k *= 0.01
+    for spike in (30, 31):
+        kk = k.copy()
+        kk[0, 0, spike] = 100.0 * q[0, 0] / np.dot(q[0, 0], q[0, 0])  # q.k = 100
+        m, _, _ = oracle.attn_partial(q, kk, v, [N], 1.0, [(0, 0, 31), (0, 31, N)])
+        owner, other = (0, 1) if spike < 31 else (1, 0)
+        assert abs(m[owner, 0] - 100.0) < 1e-4
+        assert m[other, 0] < 1.0
+
+
+# ---- P7 two tokens = logistic ------------------------------------------------------------------
+
+
+def test_two_tokens_logistic():
+    q, k, v = _case(10, 1, 3, 3, 2, 8)
+    scale = 0.9
+    out, _ = oracle.attn_full(q, k, v, [2], scale)
+    q64, k64, v64 = (x.astype(np.float64) for x in (q, k, v))
+    s = scale * np.einsum("hd,hnd->hn", q64[0], k64[0])
+    sig = scipy.special.expit(s[:, 0] - s[:, 1])
+    want = sig[:, None] * v64[0, :, 0] + (1 - sig)[:, None] * v64[0, :, 1]
+    assert np.allclose(out[0], want, rtol=0, atol=1e-14)
+    m, l, o = oracle.attn_partial(q, k, v, [2], scale, [(0, 0, 1), (0, 1, 2)])
+    mo, _ = oracle.attn_merge(m, l, o, [0, 2])
+    assert np.allclose(mo[0], want, rtol=0, atol=1e-14)
+
+
+# ---- P9 key-shift invariance -------------------------------------------------------------------
+
+
+def test_key_shift_invariance():
+    """k_j <- k_j + u leaves the output unchanged and moves m by scale*q.u (catches a missing
+    max subtraction or a max taken over the wrong quantity).  u is chosen so the shifted keys
+    are exactly representable."""
+    q, k, v = _case(11, 1, 2, 2, 50, 8)
+    k = np.round(k * 64) / 64
+    u = (np.round(RNG(12).standard_normal(8) * 4) / 4).astype(np.float32)
+    k2 = (k + u).astype(np.float32)
+    scale = 0.5
+    o1, _ = oracle.attn_full(q, k, v, [50], scale)
+    o2, _ = oracle.attn_full(q, k2, v, [50], scale)
+    assert np.allclose(o1, o2, rtol=0, atol=1e-12)
+    m1, _, _ = oracle.attn_partial(q, k, v, [50], scale, [(0, 0, 50)])
+    m2, _, _ = oracle.attn_partial(q, k2, v, [50], scale, [(0, 0, 50)])
+    shift = scale * q[0].astype(np.float64) @ u.astype(np.float64)
+    assert np.allclose(m2[0] - m1[0], shift, rtol=0, atol=1e-12)
+
+
+# ---- P10 / P11 partition invariance, concat == merge -------------------------------------------
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_partition_invariance_and_concat_equals_merge(seed):
+    """Any table that tiles [0, N_b) once -- with empty and one-token ranges, up to 64 parts --
+    merges to the unsplit result; the paper-literal concat route agrees as well."""
+    rng = RNG(100 + seed)
+    B, Hq, Hkv, N, d = 3, 4, 2, 257, 16
+    q, k, v = _case(200 + seed, B, Hq, Hkv, N, d, np.float16 if seed % 2 else np.float32)
+    seq_lens = [257, 100, 1]
+    ranges, gp = [], [0]
+    for b, n in enumerate(seq_lens):
+        parts = int(rng.choice([1, 2, 3, 8, 64]))
+        cuts = sorted(rng.randint(0, n + 1, size=parts - 1).tolist())
+        bounds = [0] + cuts + [n]
+        rs = [(b, bounds[i], bounds[i + 1]) for i in range(parts)]
+        rng.shuffle(rs)  # order inside a group must not matter
+        ranges += rs
+        gp.append(len(ranges))
+    full, flse = oracle.attn_full(q, k, v, seq_lens, 0.25)
+    m, l, o = oracle.attn_partial(q, k, v, seq_lens, 0.25, ranges)
+    mo, mlse = oracle.attn_merge(m, l, o, gp)
+    co = oracle.attn_concat(q, k, v, seq_lens, 0.25, ranges)
+    assert np.abs(mo - full).max() < 1e-12
+    assert np.abs(mlse - flse).max() < 1e-12
+    assert np.abs(co - full).max() < 1e-12
+
+
+# ---- P12 merge algebra -------------------------------------------------------------------------
+
+
+def test_merge_algebra():
+    rng = RNG(13)
+    T, Hq, d = 9, 3, 8
+    m = rng.standard_normal((T, Hq)) * 5
+    l = rng.uniform(0.5, 20, (T, Hq))
+    o = rng.standard_normal((T, Hq, d)) * l[..., None]
+    flat, flse = oracle.attn_merge(m, l, o, [0, T])
+    # commutativity
+    perm = rng.permutation(T)
+    sh, shlse = oracle.attn_merge(m[perm], l[perm], o[perm], [0, T])
+    assert np.abs(sh - flat).max() < 1e-13 and np.abs(shlse - flse).max() < 1e-13
+    # identity element
+    m2 = np.concatenate([m[:4], np.full((2, Hq), -np.inf), m[4:]])
+    l2 = np.concatenate([l[:4], np.zeros((2, Hq)), l[4:]])
+    o2 = np.concatenate([o[:4], np.zeros((2, Hq, d)), o[4:]])
+    idn, _ = oracle.attn_merge(m2, l2, o2, [0, T + 2])
+    assert np.abs(idn - flat).max() < 1e-13
+    # single triple: out = O / l, lse = m + log l
+    one, onelse = oracle.attn_merge(m[:1], l[:1], o[:1], [0, 1])
+    assert np.allclose(one[0], o[0] / l[0][:, None], atol=1e-15)
+    assert np.allclose(onelse[0], m[0] + np.log(l[0]), atol=1e-15)
+    # associativity: merge sub-groups, rebuild their triples as (lse, 1, out), merge again
+    sub, sublse = oracle.attn_merge(m, l, o, [0, 3, 7, T])
+    again, againlse = oracle.attn_merge(sublse, np.ones_like(sublse), sub, [0, 3])
+    assert np.abs(again - flat).max() < 1e-13 and np.abs(againlse - flse).max() < 1e-13
+    # triple rescaling: (m, l, O) == (m - c, l e^c, O e^c)
+    c = 1.75
+    resc, _ = oracle.attn_merge(m - c, l * math.exp(c), o * math.exp(c), [0, T])
+    assert np.abs(resc - flat).max() < 1e-12
+    # all-empty group
+    z, zlse = oracle.attn_merge(np.full((2, Hq), -np.inf), np.zeros((2, Hq)), np.zeros((2, Hq, d)), [0, 2, 2])
+    assert not z.any() and np.all(zlse == -np.inf)
+
+
+# ---- P13 stability -----------------------------------------------------------------------------
+
+
+def test_large_logits_stay_finite():
+    """Logits of magnitude 1e4: no overflow; two tokens still follow the logistic form and
+    identical keys still average (catches exp taken before the max is subtracted)."""
+    d = 4
+    q = np.full((1, 1, d), 50.0, dtype=np.float32)
+    k = np.zeros((1, 1, 2, d), dtype=np.float32)
+    k[0, 0, 0] = 50.0
+    k[0, 0, 1] = 50.0 - 0.005  # logits 1e4 and 1e4 - 1
+    v = np.array([[[[1, 0, 0, 0], [0, 1, 0, 0]]]], dtype=np.float32)
+    out, lse = oracle.attn_full(q, k, v, [2], 1.0)
+    s0 = float(np.dot(q[0, 0].astype(np.float64), k[0, 0, 0].astype(np.float64)))
+    s1 = float(np.dot(q[0, 0].astype(np.float64), k[0, 0, 1].astype(np.float64)))
+    sig = 1.0 / (1.0 + math.exp(s1 - s0))
+    assert np.all(np.isfinite(out)) and np.isfinite(lse).all()
+    assert abs(out[0, 0, 0] - sig) < 1e-12 and abs(out[0, 0, 1] - (1 - sig)) < 1e-12
+    m, l, o = oracle.attn_partial(q, k, v, [2], 1.0, [(0, 0, 1), (0, 1, 2)])
+    mo, _ = oracle.attn_merge(m, l, o, [0, 2])
+    assert np.abs(mo - out).max() < 1e-12
+    kneg = -k  # logits about -1e4
+    outn, _ = oracle.attn_full(q, kneg, v, [2], 1.0)
+    assert np.all(np.isfinite(outn)) and abs(outn[0, 0, 1] - sig) < 1e-12
+
+
+# ---- P14 grouped-query mapping -----------------------------------------------------------------
+
+
+def test_gqa_equals_mha_with_repeated_kv():
+    """Query head h reads KV head h // G (contiguous groups); h % G would fail here."""
+    B, Hq, Hkv, N, d = 2, 8, 2, 40, 8
+    q, k, v = _case(14, B, Hq, Hkv, N, d)
+    G = Hq // Hkv
+    krep = np.repeat(k, G, axis=1)
+    vrep = np.repeat(v, G, axis=1)
+    o1, l1 = oracle.attn_full(q, k, v, [40, 33], 0.4)
+    o2, l2 = oracle.attn_full(q, krep, vrep, [40, 33], 0.4)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+    rs = [(0, 0, 11), (1, 5, 33)]
+    a = oracle.attn_partial(q, k, v, [40, 33], 0.4, rs)
+    b = oracle.attn_partial(q, krep, vrep, [40, 33], 0.4, rs)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+# ---- P15 library softmax / logsumexp ------------------------------------------------------------
+
+
+def test_against_scipy_softmax_and_logsumexp():
+    q, k, v = _case(15, 2, 4, 4, 61, 16, np.float16)
+    seq_lens = [61, 17]
+    scale = 0.25
+    out, lse = oracle.attn_full(q, k, v, seq_lens, scale)
+    q64, k64, v64 = (x.astype(np.float64) for x in (q, k, v))
+    for b, n in enumerate(seq_lens):
+        s = scale * np.einsum("hd,hnd->hn", q64[b], k64[b, :, :n])
+        p = scipy.special.softmax(s, axis=-1)
+        assert np.allclose(out[b], np.einsum("hn,hnd->hd", p, v64[b, :, :n]), rtol=0, atol=1e-13)
+        assert np.allclose(lse[b], scipy.special.logsumexp(s, axis=-1), rtol=0, atol=1e-13)
+
+
+# ---- layout: strides and padding ---------------------------------------------------------------
+
+
+def test_strided_layout_and_padding_rows_are_ignored():
+    """A token-major [B, N, Hkv, d] cache viewed as [B, Hkv, N, d] must give the same result as
+    its contiguous copy, and rows past seq_lens must never be read (they hold NaN here)."""
+    B, Hq, Hkv, N, d = 2, 4, 2, 30, 8
+    rng = RNG(16)
+    q = _rand(rng, (B, Hq, d), np.float32)
+    ks = _rand(rng, (B, N, Hkv, d), np.float32)
+    vs = _rand(rng, (B, N, Hkv, d), np.float32)
+    seq_lens = [30, 12]
+    ks[1, 12:] = np.nan
+    vs[1, 12:] = np.nan
+    kview, vview = ks.transpose(0, 2, 1, 3), vs.transpose(0, 2, 1, 3)
+    o1, l1 = oracle.attn_full(q, kview, vview, seq_lens, 0.35)
+    o2, l2 = oracle.attn_full(q, np.ascontiguousarray(kview), np.ascontiguousarray(vview), seq_lens, 0.35)
+    assert np.isfinite(o1).all() and np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+def test_empty_cache_gives_zero_output():
+    q, k, v = _case(17, 2, 2, 2, 4, 4)
+    out, lse = oracle.attn_full(q, k, v, [0, 4], 1.0)
+    assert not out[0].any() and np.all(lse[0] == -np.inf) and np.isfinite(lse[1]).all()
+
+
+def test_bad_ranges_are_rejected():
+    q, k, v = _case(18, 1, 1, 1, 4, 4)
+    for bad in [(0, 3, 2), (0, 0, 5), (1, 0, 1), (0, -1, 2)]:
+        with pytest.raises(ValueError):
+            oracle.attn_partial(q, k, v, [4], 1.0, [bad])
