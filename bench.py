@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of partitioned decode attention on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input that is already
+resident in HBM:  hg_attn_partial over every range of every sequence (streams K and V once,
+tile statistics, tile reduce)  ->  hg_attn_merge over each sequence's triples.  The headline
+workload is the OPT-6.7B-shaped decode layer (batch 8, 32 heads, head_dim 128, 8192 cached
+tokens per sequence, fp16 K/V, two partitions per sequence); the longer workloads are timed the
+same way and reported under "other_workloads".
+
+Prints ONE JSON line.  `value` = effective KV GB/s = bytes of K and V inside the processed
+ranges (each row once per KV head) / wall time per step.  `roofline` prices the streaming
+kernel alone against the 8 TB/s HBM peak, timed with HIP events recorded around its launches.
+`cpu_baseline` is the fp64 oracle on the host cores over the same tensors.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+PAPER_CONTEXT = (
+    "paper reports only end-to-end generation speedups (1.41x-3.2x on average over six baselines; "
+    "Xeon Gold 5320 + A100 80GB, Xeon Gold 6530 + H100 NVL, Xeon 6960P + RTX 5090 + CXL); "
+    "no kernel-level number exists for this path"
+)
+
+
+def _time_steps(step, steps, warmup, torch):
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+
+def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
+    spec = W.WORKLOADS[index]
+    w = W.make_workload(spec, "cuda:0")
+    desc, keep = hg.make_desc(w.q, w.k, w.v, w.seq_lens, w.scale)
+    packed = hg.pack_ranges(w.ranges)
+    R = len(w.ranges)
+    dev = w.q.device
+    Hq, d = spec.n_q_heads, spec.head_dim
+    m = torch.empty((R, Hq), dtype=torch.float32, device=dev)
+    l = torch.empty((R, Hq), dtype=torch.float32, device=dev)
+    o = torch.empty((R, Hq, d), dtype=torch.float32, device=dev)
+    out = torch.empty((spec.batch, Hq, d), dtype=torch.float32, device=dev)
+    lse = torch.empty((spec.batch, Hq), dtype=torch.float32, device=dev)
+    from paper_2604_18529_amd import hg_attn as binding
+
+    ws = torch.empty(max(binding.hg_attn_partial_workspace_size(desc, packed), 256), dtype=torch.uint8, device=dev)
+    tile_tokens, n_tiles = hg.hg_attn_plan(w.q, w.k, w.v, w.seq_lens, packed, w.scale)
+
+    def step():
+        hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, packed, w.scale, m=m, l=l, o=o, workspace=ws, desc=desc)
+        hg.hg_attn_merge(m, l, o, w.group_ptr, out=out, lse=lse)
+
+    ms, wall_ms = _time_steps(step, steps, warmup, torch)
+
+    # second pass of the same K steps with event pairs around the streaming kernel alone
+    hg.hg_attn_profile_start(steps)
+    for _ in range(steps):
+        step()
+    kernel_ms_total, launches = hg.hg_attn_profile_stop()
+    kernel_ms = kernel_ms_total / max(launches, 1)
+
+    # the unsplit path, for reference
+    fws = torch.empty(max(binding.hg_attn_full_workspace_size(desc), 256), dtype=torch.uint8, device=dev)
+
+    def full_step():
+        hg.hg_attn_full(w.q, w.k, w.v, w.seq_lens, w.scale, out=out, lse=lse, workspace=fws, desc=desc)
+
+    full_ms, _ = _time_steps(full_step, max(steps // 2, 1), max(warmup // 2, 1), torch)
+
+    kv_bytes = w.kv_bytes
+    res = {
+        "workload": spec.name,
+        "batch": spec.batch,
+        "n_q_heads": spec.n_q_heads,
+        "n_kv_heads": spec.n_kv_heads,
+        "head_dim": spec.head_dim,
+        "kv_dtype": spec.dtype,
+        "tokens_total": int(w.seq_lens.sum()),
+        "partitions": R,
+        "tile_tokens": tile_tokens,
+        "n_tiles": n_tiles,
+        "kv_bytes": kv_bytes,
+        "us_per_layer": ms * 1e3,
+        "gbps": kv_bytes / (ms * 1e-3) / 1e9,
+        "frac_hbm_peak": kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "full_path_us": full_ms * 1e3,
+        "full_path_gbps": kv_bytes / (full_ms * 1e-3) / 1e9,
+        "stream_kernel_us": kernel_ms * 1e3,
+        "stream_kernel_gbps": kv_bytes / (kernel_ms * 1e-3) / 1e9,
+        "host_wall_us_per_step": wall_ms * 1e3,
+    }
+
+    cpu = None
+    if with_cpu_baseline:
+        import numpy as np
+
+        import oracle
+
+        qn, kn, vn = (t.cpu().numpy() for t in (w.q, w.k, w.v))
+        threads = oracle.max_threads()
+        t0 = time.perf_counter()
+        mo, lo, oo = oracle.attn_partial(qn, kn, vn, w.seq_lens, w.scale, w.ranges)
+        ref, _ = oracle.attn_merge(mo, lo, oo, w.group_ptr)
+        secs = time.perf_counter() - t0
+        err = float(np.abs(out.cpu().numpy() - ref).max())
+        cpu = {
+            "value": kv_bytes / secs / 1e9,
+            "unit": "GB/s",
+            "cores": threads,
+            "kind": "oracle",
+            "sample": "whole workload %s once (partial + merge, fp64, OpenMP over (range, head)); %.2f s" % (spec.name, secs),
+            "seconds": secs,
+            "gpu_max_abs_err_vs_oracle": err,
+        }
+    del keep
+    return res, cpu
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=1, help="index into the standard workloads (headline: 1)")
+    ap.add_argument("--others", type=str, default="2,3,4", help="comma list of further workloads to time ('' for none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tile-tokens", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU only (the path shards by (sequence, KV head) or by "
+                 "token range across GPUs, see DESIGN.md); run with --gpus 1")
+
+    import torch
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    import paper_2604_18529_amd as hg
+    from paper_2604_18529_amd import workloads as W
+
+    hg.load_library()
+    hg.hg_attn_set_tile_tokens(args.tile_tokens)
+
+    head, cpu = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, torch, hg, W)
+    others = []
+    for tok in [t for t in args.others.split(",") if t.strip()]:
+        i = int(tok)
+        if i == args.workload:
+            continue
+        torch.cuda.empty_cache()
+        k = max(args.steps // 10, 5)
+        r, _ = run_workload(i, k, max(args.warmup // 10, 2), False, torch, hg, W)
+        r["steps"] = k
+        others.append(r)
+
+    line = {
+        "metric": "decode attention effective KV GB/s (% of HBM peak) and us/layer at 1 GPU",
+        "value": head["gbps"],
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["us_per_layer"] / 1e3,
+        "us_per_layer": head["us_per_layer"],
+        "frac_hbm_peak": head["frac_hbm_peak"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",  # fp16 K/V/q storage, fp32 products, sums and exponentials
+        "data": "synthetic",
+        "config": {k: head[k] for k in ("workload", "batch", "n_q_heads", "n_kv_heads", "head_dim", "kv_dtype",
+                                        "tokens_total", "partitions", "tile_tokens", "n_tiles", "kv_bytes")},
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "hg_partial_kernel",
+            "achieved": head["stream_kernel_gbps"],
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": head["stream_kernel_gbps"] / HBM_PEAK_GBS,
+            "traffic": None,
+            "kernel_us": head["stream_kernel_us"],
+            "algorithmic_bytes_per_launch": head["kv_bytes"],
+        },
+        "cpu_baseline": cpu,
+        "full_path": {"us": head["full_path_us"], "gbps": head["full_path_gbps"]},
+        "other_workloads": others,
+        "paper_context": PAPER_CONTEXT,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

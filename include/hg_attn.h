@@ -152,6 +152,17 @@ hg_status hg_attn_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t
  * built-in choice.  Process-wide; not thread-safe against concurrent calls. */
 hg_status hg_attn_set_tile_tokens(int32_t tile_tokens);
 
+/*
+ * Measurement aid: time the streaming kernel (the one that reads K and V) by itself.  After
+ * hg_attn_profile_start(n), each of the next n hg_attn_partial / hg_attn_full calls records a
+ * pair of HIP events on the caller's stream directly around that kernel's launch.
+ * hg_attn_profile_stop waits for those events (the only call in this library that blocks),
+ * returns the summed elapsed milliseconds and the number of launches timed, and switches the
+ * mode off.  Process-wide; not thread-safe.
+ */
+hg_status hg_attn_profile_start(int32_t max_launches);
+hg_status hg_attn_profile_stop(float *total_ms, int32_t *launches);
+
 #ifdef __cplusplus
 }
 #endif

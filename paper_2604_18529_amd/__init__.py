@@ -11,6 +11,10 @@ _API = (
     "hg_attn_full",
     "hg_attn_plan",
     "hg_attn_set_tile_tokens",
+    "hg_attn_profile_start",
+    "hg_attn_profile_stop",
+    "pack_ranges",
+    "make_desc",
     "hg_strerror",
     "HgError",
     "load_library",

@@ -1,0 +1,439 @@
+// Host side of the C ABI declared in include/hg_attn.h: validation, tile planning, launches.
+// Nothing here allocates device memory or synchronises with the device; host tables reach the
+// GPU inside kernel arguments (small tables) or through chunked upload kernels (large tables),
+// so no memcpy semantics are relied upon and every call is safe to record into a HIP graph.
+
+#include "hg_attn_kernels.hip.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "../../include/hg_attn.h"
+
+namespace {
+
+using namespace hg;
+
+int g_forced_tile_tokens = 0;
+
+// Optional timing of the streaming kernel alone: event pairs recorded on the caller's stream
+// right around its launch (hg_attn_profile_start / hg_attn_profile_stop).
+std::vector<hipEvent_t> g_prof_events;  // 2 per slot
+int g_prof_used = 0;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Plan {
+    int32_t tile_tokens = 0;
+    int64_t n_tiles = 0;
+    std::vector<RangeEntry> entries;  // n_ranges + 1 (sentinel)
+    int32_t gt = 1;                   // query heads of one KV head handled per workgroup
+    int32_t n_chunks = 1;
+    // workspace sections (byte offsets)
+    size_t off_m = 0, off_l = 0, off_o = 0, off_tab = 0, total = 0;
+};
+
+hg_status check_desc(const hg_attn_desc *d)
+{
+    if (!d) return HG_ERR_NULL;
+    if (d->dtype != HG_F16 && d->dtype != HG_F32) return HG_ERR_DTYPE;
+    if (d->batch < 0 || d->n_q_heads <= 0 || d->n_q_heads > 65535 || d->n_kv_heads <= 0) return HG_ERR_SHAPE;
+    if (d->n_q_heads % d->n_kv_heads) return HG_ERR_SHAPE;
+    if (d->head_dim != 64 && d->head_dim != 128) return HG_ERR_SHAPE;
+    if (d->batch == 0) return HG_OK;
+    if (!d->q || !d->k || !d->v || !d->seq_lens) return HG_ERR_NULL;
+    const int64_t es = d->dtype == HG_F16 ? 2 : 4;
+    if (d->stride_t < d->head_dim || d->stride_b < 0 || d->stride_h < 0) return HG_ERR_SHAPE;
+    if ((d->stride_t * es) % 16 || (d->stride_b * es) % 16 || (d->stride_h * es) % 16) return HG_ERR_SHAPE;
+    if (((uintptr_t)d->q | (uintptr_t)d->k | (uintptr_t)d->v) % 16) return HG_ERR_SHAPE;
+    if (!std::isfinite(d->scale)) return HG_ERR_SHAPE;
+    for (int32_t b = 0; b < d->batch; ++b)
+        if (d->seq_lens[b] < 0) return HG_ERR_RANGE;
+    return HG_OK;
+}
+
+hg_status check_ranges(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges)
+{
+    if (n_ranges < 0) return HG_ERR_SHAPE;
+    if (n_ranges && !ranges) return HG_ERR_NULL;
+    for (int32_t r = 0; r < n_ranges; ++r) {
+        const hg_range &g = ranges[r];
+        if (g.seq < 0 || g.seq >= d->batch) return HG_ERR_RANGE;
+        if (g.begin < 0 || g.begin > g.end || g.end > d->seq_lens[g.seq]) return HG_ERR_RANGE;
+    }
+    return HG_OK;
+}
+
+int32_t pick_group_tile(int32_t group)
+{
+    if (group >= 8) return 8;
+    if (group > 2) return 4;
+    return group;  // 1 or 2
+}
+
+// Tile length: long enough to amortise a workgroup's set-up and its (m, l, O) write-back,
+// short enough that the launch has a few thousand workgroups for 256 compute units.
+int32_t pick_tile_tokens(int64_t total_tokens, int64_t streams)
+{
+    if (g_forced_tile_tokens) return g_forced_tile_tokens;
+    const int64_t target_blocks = 4096;
+    int64_t t = (total_tokens * streams + target_blocks - 1) / target_blocks;
+    t = (t + 63) / 64 * 64;
+    if (t < 64) t = 64;
+    if (t > 1024) t = 1024;
+    return (int32_t)t;
+}
+
+hg_status make_plan(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, Plan &p)
+{
+    const int32_t group = d->n_q_heads / d->n_kv_heads;
+    p.gt = pick_group_tile(group);
+    p.n_chunks = (group + p.gt - 1) / p.gt;
+    if ((int64_t)d->n_kv_heads * p.n_chunks > 65535) return HG_ERR_SHAPE;
+    int64_t total_tokens = 0;
+    for (int32_t r = 0; r < n_ranges; ++r) total_tokens += ranges[r].end - ranges[r].begin;
+    p.tile_tokens = pick_tile_tokens(total_tokens, (int64_t)d->n_kv_heads * p.n_chunks);
+    p.entries.resize((size_t)n_ranges + 1);
+    int64_t tiles = 0;
+    for (int32_t r = 0; r < n_ranges; ++r) {
+        const int64_t len = ranges[r].end - ranges[r].begin;
+        p.entries[r] = RangeEntry{ranges[r].seq, ranges[r].begin, ranges[r].end, (int32_t)tiles};
+        tiles += (len + p.tile_tokens - 1) / p.tile_tokens;
+        if (tiles > 0x7fffffff) return HG_ERR_SHAPE;
+    }
+    p.entries[n_ranges] = RangeEntry{0, 0, 0, (int32_t)tiles};
+    p.n_tiles = tiles;
+    const size_t th = (size_t)tiles * (size_t)d->n_q_heads;
+    size_t off = 0;
+    p.off_m = off;
+    off += align_up(th * sizeof(float));
+    p.off_l = off;
+    off += align_up(th * sizeof(float));
+    p.off_o = off;
+    off += align_up(th * (size_t)d->head_dim * sizeof(float));
+    p.off_tab = off;
+    if (n_ranges > kInlineRanges) off += align_up(p.entries.size() * sizeof(RangeEntry));
+    p.total = off;
+    return HG_OK;
+}
+
+hg_status check_workspace(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return HG_OK;
+    if (!ws || (uintptr_t)ws % kAlign || have < need) return HG_ERR_WORKSPACE;
+    return HG_OK;
+}
+
+hg_status launch_status(const char *what)
+{
+    hipError_t err = hipGetLastError();
+    if (err == hipSuccess) return HG_OK;
+    std::fprintf(stderr, "hg_attn: %s failed: %s\n", what, hipGetErrorString(err));
+    return HG_ERR_LAUNCH;
+}
+
+// Fill the by-value table; large tables go to the workspace through upload kernels.
+hg_status stage_table(const Plan &p, int32_t n_ranges, char *ws, hipStream_t stream, RangeTable &tab)
+{
+    tab.n_ranges = n_ranges;
+    tab.n_tiles = (int32_t)p.n_tiles;
+    tab.ext = nullptr;
+    if (n_ranges <= kInlineRanges) {
+        std::memcpy(tab.inl, p.entries.data(), p.entries.size() * sizeof(RangeEntry));
+        return HG_OK;
+    }
+    RangeEntry *dst = reinterpret_cast<RangeEntry *>(ws + p.off_tab);
+    tab.ext = dst;
+    const size_t n = p.entries.size();
+    for (size_t i = 0; i < n; i += kUploadRanges) {
+        RangeChunk chunk;
+        const int cnt = (int)std::min<size_t>(kUploadRanges, n - i);
+        std::memcpy(chunk.e, p.entries.data() + i, (size_t)cnt * sizeof(RangeEntry));
+        hipLaunchKernelGGL(hg_upload_ranges_kernel, dim3(1), dim3(kUploadRanges), 0, stream, dst + i, cnt, chunk);
+    }
+    return launch_status("range table upload");
+}
+
+template <typename TR>
+void launch_partial_gt(const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
+{
+    switch (gt) {
+    case 1: hipLaunchKernelGGL((hg_partial_kernel<TR, 1, 4>), grid, dim3(kBlock), 0, stream, a); break;
+    case 2: hipLaunchKernelGGL((hg_partial_kernel<TR, 2, 4>), grid, dim3(kBlock), 0, stream, a); break;
+    case 4: hipLaunchKernelGGL((hg_partial_kernel<TR, 4, 2>), grid, dim3(kBlock), 0, stream, a); break;
+    default: hipLaunchKernelGGL((hg_partial_kernel<TR, 8, 2>), grid, dim3(kBlock), 0, stream, a); break;
+    }
+}
+
+void launch_partial(const hg_attn_desc *d, const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
+{
+    const bool f16 = d->dtype == HG_F16;
+    if (d->head_dim == 128) {
+        if (f16)
+            launch_partial_gt<Traits<128, true>>(a, gt, grid, stream);
+        else
+            launch_partial_gt<Traits<128, false>>(a, gt, grid, stream);
+    } else {
+        if (f16)
+            launch_partial_gt<Traits<64, true>>(a, gt, grid, stream);
+        else
+            launch_partial_gt<Traits<64, false>>(a, gt, grid, stream);
+    }
+}
+
+// Shared by hg_attn_partial (normalise = 0) and hg_attn_full (normalise = 1).
+hg_status run(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, int normalise, float *m, float *l,
+              float *o, void *workspace, size_t ws_bytes, void *stream_v)
+{
+    Plan p;
+    hg_status st = make_plan(d, ranges, n_ranges, p);
+    if (st != HG_OK) return st;
+    st = check_workspace(workspace, ws_bytes, p.total);
+    if (st != HG_OK) return st;
+    if (n_ranges == 0) return HG_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char *ws = static_cast<char *>(workspace);
+
+    PartialArgs pa;
+    std::memset(&pa, 0, sizeof(pa));
+    st = stage_table(p, n_ranges, ws, stream, pa.tab);
+    if (st != HG_OK) return st;
+    pa.q = d->q;
+    pa.k = d->k;
+    pa.v = d->v;
+    pa.stride_b = d->stride_b;
+    pa.stride_h = d->stride_h;
+    pa.stride_t = d->stride_t;
+    pa.n_q_heads = d->n_q_heads;
+    pa.group = d->n_q_heads / d->n_kv_heads;
+    pa.n_chunks = p.n_chunks;
+    pa.scale_log2 = d->scale * kLog2e;
+    pa.ws_m = reinterpret_cast<float *>(ws + p.off_m);
+    pa.ws_l = reinterpret_cast<float *>(ws + p.off_l);
+    pa.ws_o = reinterpret_cast<float *>(ws + p.off_o);
+    if (p.n_tiles > 0) {
+        dim3 grid((unsigned)p.n_tiles, (unsigned)(d->n_kv_heads * p.n_chunks));
+        const bool timed = (size_t)(2 * g_prof_used + 2) <= g_prof_events.size();
+        if (timed) (void)hipEventRecord(g_prof_events[2 * g_prof_used], stream);
+        launch_partial(d, pa, p.gt, grid, stream);
+        if (timed) (void)hipEventRecord(g_prof_events[2 * g_prof_used++ + 1], stream);
+        st = launch_status("partial kernel");
+        if (st != HG_OK) return st;
+    }
+
+    ReduceArgs ra;
+    std::memset(&ra, 0, sizeof(ra));
+    ra.tab = pa.tab;
+    ra.ws_m = pa.ws_m;
+    ra.ws_l = pa.ws_l;
+    ra.ws_o = pa.ws_o;
+    ra.n_q_heads = d->n_q_heads;
+    ra.normalise = normalise;
+    ra.m_out = m;
+    ra.l_out = l;
+    ra.o_out = o;
+    dim3 rgrid((unsigned)n_ranges, (unsigned)d->n_q_heads);
+    if (d->head_dim == 128)
+        hipLaunchKernelGGL(hg_tile_reduce_kernel<128>, rgrid, dim3(128), 0, stream, ra);
+    else
+        hipLaunchKernelGGL(hg_tile_reduce_kernel<64>, rgrid, dim3(64), 0, stream, ra);
+    return launch_status("tile reduce kernel");
+}
+
+hg_status full_ranges(const hg_attn_desc *d, std::vector<hg_range> &ranges)
+{
+    hg_status st = check_desc(d);
+    if (st != HG_OK) return st;
+    ranges.resize((size_t)d->batch);
+    for (int32_t b = 0; b < d->batch; ++b) ranges[b] = hg_range{b, 0, d->seq_lens[b]};
+    return HG_OK;
+}
+
+size_t merge_ws_bytes(int32_t n_groups)
+{
+    return n_groups > kInlineGroups ? align_up(((size_t)n_groups + 1) * sizeof(int32_t)) : 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *hg_strerror(hg_status status)
+{
+    switch (status) {
+    case HG_OK: return "ok";
+    case HG_ERR_NULL: return "a required pointer is NULL";
+    case HG_ERR_SHAPE: return "unsupported shape, stride, alignment or count";
+    case HG_ERR_DTYPE: return "unsupported dtype";
+    case HG_ERR_RANGE: return "malformed range or offset";
+    case HG_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case HG_ERR_LAUNCH: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+hg_status hg_attn_set_tile_tokens(int32_t tile_tokens)
+{
+    if (tile_tokens != 0 && (tile_tokens < 64 || tile_tokens > 65536 || tile_tokens % 64)) return HG_ERR_SHAPE;
+    g_forced_tile_tokens = tile_tokens;
+    return HG_OK;
+}
+
+hg_status hg_attn_profile_start(int32_t max_launches)
+{
+    if (max_launches < 0 || max_launches > 65536) return HG_ERR_SHAPE;
+    for (hipEvent_t ev : g_prof_events) (void)hipEventDestroy(ev);
+    g_prof_events.clear();
+    g_prof_used = 0;
+    for (int i = 0; i < 2 * max_launches; ++i) {
+        hipEvent_t ev;
+        if (hipEventCreate(&ev) != hipSuccess) return launch_status("event creation");
+        g_prof_events.push_back(ev);
+    }
+    return HG_OK;
+}
+
+hg_status hg_attn_profile_stop(float *total_ms, int32_t *launches)
+{
+    float sum = 0.f;
+    hg_status st = HG_OK;
+    for (int i = 0; i < g_prof_used; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_prof_events[2 * i + 1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_prof_events[2 * i], g_prof_events[2 * i + 1]) != hipSuccess)
+            st = launch_status("event read-out");
+        sum += ms;
+    }
+    if (total_ms) *total_ms = sum;
+    if (launches) *launches = g_prof_used;
+    for (hipEvent_t ev : g_prof_events) (void)hipEventDestroy(ev);
+    g_prof_events.clear();
+    g_prof_used = 0;
+    return st;
+}
+
+hg_status hg_attn_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, int32_t *tile_tokens,
+                       int64_t *n_tiles)
+{
+    hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = check_ranges(desc, ranges, n_ranges);
+    if (st != HG_OK) return st;
+    Plan p;
+    st = make_plan(desc, ranges, n_ranges, p);
+    if (st != HG_OK) return st;
+    if (tile_tokens) *tile_tokens = p.tile_tokens;
+    if (n_tiles) *n_tiles = p.n_tiles;
+    return HG_OK;
+}
+
+hg_status hg_attn_partial_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges,
+                                         size_t *bytes)
+{
+    if (!bytes) return HG_ERR_NULL;
+    hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = check_ranges(desc, ranges, n_ranges);
+    if (st != HG_OK) return st;
+    Plan p;
+    st = make_plan(desc, ranges, n_ranges, p);
+    if (st != HG_OK) return st;
+    *bytes = p.total;
+    return HG_OK;
+}
+
+hg_status hg_attn_partial(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, float *m, float *l,
+                          float *o, void *workspace, size_t ws_bytes, void *stream)
+{
+    hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = check_ranges(desc, ranges, n_ranges);
+    if (st != HG_OK) return st;
+    if (n_ranges && (!m || !l || !o)) return HG_ERR_NULL;
+    return run(desc, ranges, n_ranges, 0, m, l, o, workspace, ws_bytes, stream);
+}
+
+hg_status hg_attn_full_workspace_size(const hg_attn_desc *desc, size_t *bytes)
+{
+    if (!bytes) return HG_ERR_NULL;
+    std::vector<hg_range> ranges;
+    hg_status st = full_ranges(desc, ranges);
+    if (st != HG_OK) return st;
+    Plan p;
+    st = make_plan(desc, ranges.data(), (int32_t)ranges.size(), p);
+    if (st != HG_OK) return st;
+    *bytes = p.total;
+    return HG_OK;
+}
+
+hg_status hg_attn_full(const hg_attn_desc *desc, float *out, float *lse_out, void *workspace, size_t ws_bytes,
+                       void *stream)
+{
+    std::vector<hg_range> ranges;
+    hg_status st = full_ranges(desc, ranges);
+    if (st != HG_OK) return st;
+    if (desc->batch && !out) return HG_ERR_NULL;
+    return run(desc, ranges.data(), (int32_t)ranges.size(), 1, lse_out, nullptr, out, workspace, ws_bytes, stream);
+}
+
+hg_status hg_attn_merge_workspace_size(int32_t n_groups, size_t *bytes)
+{
+    if (!bytes) return HG_ERR_NULL;
+    if (n_groups < 0) return HG_ERR_SHAPE;
+    *bytes = merge_ws_bytes(n_groups);
+    return HG_OK;
+}
+
+hg_status hg_attn_merge(const float *m, const float *l, const float *o, const int32_t *group_ptr, int32_t n_groups,
+                        int32_t n_q_heads, int32_t head_dim, float *out, float *lse_out, void *workspace,
+                        size_t ws_bytes, void *stream_v)
+{
+    if (n_groups < 0 || n_q_heads <= 0 || n_q_heads > 65535) return HG_ERR_SHAPE;
+    if (head_dim != 64 && head_dim != 128) return HG_ERR_SHAPE;
+    if (n_groups == 0) return HG_OK;
+    if (!group_ptr || !out) return HG_ERR_NULL;
+    if (group_ptr[0] < 0) return HG_ERR_RANGE;
+    for (int32_t i = 0; i < n_groups; ++i)
+        if (group_ptr[i] > group_ptr[i + 1]) return HG_ERR_RANGE;
+    if (group_ptr[n_groups] > group_ptr[0] && (!m || !l || !o)) return HG_ERR_NULL;
+    const size_t need = merge_ws_bytes(n_groups);
+    hg_status st = check_workspace(workspace, ws_bytes, need);
+    if (st != HG_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+
+    MergeArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.m = m;
+    a.l = l;
+    a.o = o;
+    a.out = out;
+    a.lse = lse_out;
+    a.n_q_heads = n_q_heads;
+    a.tab.n_groups = n_groups;
+    if (n_groups <= kInlineGroups) {
+        std::memcpy(a.tab.inl, group_ptr, ((size_t)n_groups + 1) * sizeof(int32_t));
+    } else {
+        int32_t *dst = static_cast<int32_t *>(workspace);
+        a.tab.ext = dst;
+        const size_t n = (size_t)n_groups + 1;
+        for (size_t i = 0; i < n; i += kUploadInts) {
+            IntChunk chunk;
+            const int cnt = (int)std::min<size_t>(kUploadInts, n - i);
+            std::memcpy(chunk.e, group_ptr + i, (size_t)cnt * sizeof(int32_t));
+            hipLaunchKernelGGL(hg_upload_ints_kernel, dim3(1), dim3(kUploadInts), 0, stream, dst + i, cnt, chunk);
+        }
+        st = launch_status("group table upload");
+        if (st != HG_OK) return st;
+    }
+    dim3 grid((unsigned)n_groups, (unsigned)n_q_heads);
+    if (head_dim == 128)
+        hipLaunchKernelGGL(hg_merge_kernel<128>, grid, dim3(128), 0, stream, a);
+    else
+        hipLaunchKernelGGL(hg_merge_kernel<64>, grid, dim3(64), 0, stream, a);
+    return launch_status("merge kernel");
+}
+
+}  // extern "C"

@@ -1,0 +1,445 @@
+// Device code of the partitioned decode-attention library (gfx950, wave64).
+//
+// Three kernels:
+//   hg_partial_kernel      streams the K and V rows of one token tile once and folds them into
+//                          softmax statistics (m, l, O) per query head (paper Section 4.2: the
+//                          per-token logit stage, run here per positional range).
+//   hg_tile_reduce_kernel  merges the tile statistics of a range into the range's triple, or,
+//                          for the unsplit path, into the normalised output.
+//   hg_merge_kernel        exact recombination of range triples (Section 4.2.3, Token
+//                          Concatenator, in statistics form).
+//
+// Lane layout of the streaming kernel.  One K or V row (head_dim elements, 128..512 bytes) is
+// spread over the 16 lanes of a DPP row, each lane holding 8..32 contiguous bytes per 256-byte
+// segment, so one wave load instruction fetches four whole rows (1 KiB, fully coalesced).  A
+// lane keeps the matching channels of q (pre-multiplied by scale*log2 e) and of the O
+// accumulator, so P.V is lane-local and the only cross-lane work is the 16-lane sum of the dot
+// product (four DPP adds).  The four 16-lane groups of a wave and the four waves of a
+// workgroup run independent online-softmax streams that are merged once per tile.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hg {
+
+constexpr int kInlineRanges = 64;   // range-table entries carried inside the kernel arguments
+constexpr int kInlineGroups = 256;  // CSR offsets carried inside the merge kernel's arguments
+constexpr int kUploadRanges = 128;  // entries per table-upload launch
+constexpr int kUploadInts = 512;
+constexpr int kBlock = 256;         // threads per streaming workgroup (4 waves)
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+// "no token seen yet" marker for running maxima (log2 domain).  Finite, so that
+// exp2(marker - marker) = 1 multiplies an all-zero state instead of producing NaN.
+constexpr float kNegBig = -3.0e38f;
+
+struct RangeEntry {
+    int32_t seq, begin, end, tile_start;
+};
+
+// The range table travels by value in the kernel arguments when it is small; otherwise `ext`
+// points at a device copy.  Entry n_ranges is a sentinel whose tile_start is n_tiles.
+struct RangeTable {
+    const RangeEntry *ext;
+    int32_t n_ranges;
+    int32_t n_tiles;
+    RangeEntry inl[kInlineRanges + 1];
+};
+
+struct PartialArgs {
+    const void *q, *k, *v;
+    int64_t stride_b, stride_h, stride_t;  // elements
+    int32_t n_q_heads, group, n_chunks;    // group = query heads per KV head; chunks of GT heads
+    float scale_log2;                      // scale * log2(e)
+    float *ws_m, *ws_l, *ws_o;             // tile statistics [n_tiles][Hq], [n_tiles][Hq][D]; m in log2 units
+    RangeTable tab;
+};
+
+struct ReduceArgs {
+    const float *ws_m, *ws_l, *ws_o;
+    int32_t n_q_heads;
+    int32_t normalise;  // 0: write the range triple (m, l, o); 1: write out = O/L and lse
+    float *m_out, *l_out, *o_out;  // [n_ranges][Hq](..[D])  or  out/lse when normalise
+    RangeTable tab;
+};
+
+struct GroupTable {
+    const int32_t *ext;
+    int32_t n_groups;
+    int32_t inl[kInlineGroups + 1];
+};
+
+struct MergeArgs {
+    const float *m, *l, *o;
+    float *out, *lse;
+    int32_t n_q_heads;
+    GroupTable tab;
+};
+
+struct RangeChunk {
+    RangeEntry e[kUploadRanges];
+};
+struct IntChunk {
+    int32_t e[kUploadInts];
+};
+
+// ---- small device helpers ----------------------------------------------------------------------
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row ends with the total.
+__device__ __forceinline__ float row16_sum(float x)
+{
+    x += dpp_move<0xB1>(x);   // quad_perm [1,0,3,2]
+    x += dpp_move<0x4E>(x);   // quad_perm [2,3,0,1]
+    x += dpp_move<0x141>(x);  // row_half_mirror: quads 0<->1, 2<->3
+    x += dpp_move<0x140>(x);  // row_mirror: halves swap
+    return x;
+}
+
+__device__ __forceinline__ RangeEntry table_entry(const RangeTable &tab, int i)
+{
+    return tab.ext ? tab.ext[i] : tab.inl[i];
+}
+
+// Largest r with tile_start[r] <= tile; it owns the tile because empty ranges own no tiles.
+__device__ __forceinline__ int find_range(const RangeTable &tab, int tile)
+{
+    int lo = 0, hi = tab.n_ranges;  // invariant: tile_start[lo] <= tile < tile_start[hi]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (table_entry(tab, mid).tile_start <= tile)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    return lo;
+}
+
+// Token sub-range of tile j (0-based inside its range).  Tiles of a range have equal length,
+// rounded up to 64 tokens, except the last.
+__device__ __forceinline__ void tile_bounds(const RangeEntry &e, int n_tiles_in_range, int j, int &t0, int &t1)
+{
+    int len = e.end - e.begin;
+    int per = (len + n_tiles_in_range - 1) / n_tiles_in_range;
+    per = (per + 63) & ~63;
+    int64_t a = (int64_t)e.begin + (int64_t)j * per;
+    int64_t b = a + per;
+    t0 = (int)(a < e.end ? a : e.end);
+    t1 = (int)(b < e.end ? b : e.end);
+}
+
+// ---- storage traits ----------------------------------------------------------------------------
+
+template <int VB>
+struct RawVec;
+template <>
+struct RawVec<16> {
+    uint4 d;
+};
+template <>
+struct RawVec<8> {
+    uint2 d;
+};
+
+template <int D_, bool F16_>
+struct Traits {
+    static constexpr int D = D_;
+    static constexpr bool F16 = F16_;
+    static constexpr int ES = F16_ ? 2 : 4;
+    static constexpr int LANE_BYTES = D_ * ES / 16;           // bytes of a row held by one lane
+    static constexpr int VB = LANE_BYTES >= 16 ? 16 : 8;      // bytes per load
+    static constexpr int NV = LANE_BYTES / VB;                // loads per row per lane
+    static constexpr int EPV = VB / ES;                       // elements per load
+    static constexpr int EPL = NV * EPV;                      // elements per lane
+    static constexpr int SEG = 16 * EPV;                      // elements covered by one wave-row load
+    using Raw = RawVec<VB>;
+
+    // element offset inside a row of lane `sub`'s vector j
+    __device__ static __forceinline__ int vec_offset(int sub, int j) { return j * SEG + sub * EPV; }
+
+    __device__ static __forceinline__ Raw load(const char *row_ptr, int sub, int j)
+    {
+        Raw r;
+        const char *p = row_ptr + (size_t)vec_offset(sub, j) * ES;
+        if constexpr (VB == 16)
+            r.d = *reinterpret_cast<const uint4 *>(p);
+        else
+            r.d = *reinterpret_cast<const uint2 *>(p);
+        return r;
+    }
+
+    __device__ static __forceinline__ void widen(const Raw &r, float *out)
+    {
+        if constexpr (F16_) {
+            typedef _Float16 hvec __attribute__((ext_vector_type(EPV)));
+            hvec h = __builtin_bit_cast(hvec, r.d);
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) out[i] = (float)h[i];
+        } else {
+            typedef float fvec __attribute__((ext_vector_type(EPV)));
+            fvec f = __builtin_bit_cast(fvec, r.d);
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) out[i] = f[i];
+        }
+    }
+};
+
+// ---- streaming kernel --------------------------------------------------------------------------
+
+// Merge (m_b, l_b, acc_b) into (m, l, acc); all maxima in log2 units, kNegBig = empty.
+template <int N>
+__device__ __forceinline__ void merge_state(float &m, float &l, float *acc, float m_b, float l_b, const float *acc_b)
+{
+    float mx = fmaxf(m, m_b);
+    float wa = fast_exp2(m - mx), wb = fast_exp2(m_b - mx);
+    m = mx;
+    l = l * wa + l_b * wb;
+#pragma unroll
+    for (int i = 0; i < N; ++i) acc[i] = acc[i] * wa + acc_b[i] * wb;
+}
+
+template <typename TR, int GT, int U>
+__global__ __launch_bounds__(kBlock) void hg_partial_kernel(const PartialArgs a)
+{
+    constexpr int D = TR::D, EPL = TR::EPL, NV = TR::NV, EPV = TR::EPV, ES = TR::ES;
+    constexpr int CH = 4 * U;  // tokens one wave takes per iteration
+
+    __shared__ float sm[4][GT][D + 2];
+
+    const int tile = blockIdx.x;
+    const int hk = blockIdx.y / a.n_chunks;
+    const int chunk = blockIdx.y - hk * a.n_chunks;
+    const int g0 = chunk * GT;                              // first head of this chunk inside its group
+    const int nh = min(GT, a.group - g0);                   // valid heads in this chunk
+    const int h0 = hk * a.group + g0;                       // first query head
+
+    const int r = find_range(a.tab, tile);
+    const RangeEntry e = table_entry(a.tab, r);
+    const int nt = table_entry(a.tab, r + 1).tile_start - e.tile_start;
+    int t0, t1;
+    tile_bounds(e, nt, tile - e.tile_start, t0, t1);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane & 15, grp = lane >> 4;
+
+    // q fragments, scaled into the log2 domain
+    float qf[GT][EPL];
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+        const int h = h0 + (g < nh ? g : 0);
+        const char *qrow = static_cast<const char *>(a.q) + ((int64_t)e.seq * a.n_q_heads + h) * (int64_t)(D * ES);
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            typename TR::Raw raw = TR::load(qrow, sub, j);
+            TR::widen(raw, &qf[g][j * EPV]);
+        }
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) qf[g][i] *= a.scale_log2;
+    }
+
+    float m[GT], l[GT], acc[GT][EPL];
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+        m[g] = kNegBig;
+        l[g] = 0.f;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[g][i] = 0.f;
+    }
+
+    const int64_t slab = (int64_t)e.seq * a.stride_b + (int64_t)hk * a.stride_h;
+    const char *kbase = static_cast<const char *>(a.k) + slab * ES;
+    const char *vbase = static_cast<const char *>(a.v) + slab * ES;
+    const int64_t row_bytes = a.stride_t * ES;
+
+    for (int tb = t0 + wave * CH; tb < t1; tb += 4 * CH) {
+        typename TR::Raw kraw[U][NV], vraw[U][NV];
+        bool valid[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int tok = tb + 4 * u + grp;
+            valid[u] = tok < t1;
+            const int64_t off = (int64_t)(valid[u] ? tok : t1 - 1) * row_bytes;  // clamp: never read past the tile
+#pragma unroll
+            for (int j = 0; j < NV; ++j) kraw[u][j] = TR::load(kbase + off, sub, j);
+#pragma unroll
+            for (int j = 0; j < NV; ++j) vraw[u][j] = TR::load(vbase + off, sub, j);
+        }
+
+        // logits (log2 domain) of the U tokens of this lane group, for every head of the chunk
+        float s[GT][U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float kf[EPL];
+#pragma unroll
+            for (int j = 0; j < NV; ++j) TR::widen(kraw[u][j], &kf[j * EPV]);
+#pragma unroll
+            for (int g = 0; g < GT; ++g) {
+                float d = 0.f;
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) d = fmaf(qf[g][i], kf[i], d);
+                d = row16_sum(d);
+                s[g][u] = valid[u] ? d : -INFINITY;
+            }
+        }
+
+        // online softmax update
+        float p[GT][U];
+#pragma unroll
+        for (int g = 0; g < GT; ++g) {
+            float mx = m[g];
+#pragma unroll
+            for (int u = 0; u < U; ++u) mx = fmaxf(mx, s[g][u]);
+            const float alpha = fast_exp2(m[g] - mx);
+            m[g] = mx;
+            float ls = 0.f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                p[g][u] = fast_exp2(s[g][u] - mx);
+                ls += p[g][u];
+            }
+            l[g] = l[g] * alpha + ls;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[g][i] *= alpha;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float vf[EPL];
+#pragma unroll
+            for (int j = 0; j < NV; ++j) TR::widen(vraw[u][j], &vf[j * EPV]);
+#pragma unroll
+            for (int g = 0; g < GT; ++g)
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) acc[g][i] = fmaf(p[g][u], vf[i], acc[g][i]);
+        }
+    }
+
+    // merge the four lane groups of the wave (lanes xor 16, xor 32)
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+#pragma unroll
+        for (int step = 16; step <= 32; step <<= 1) {
+            float m_b = __shfl_xor(m[g], step, 64);
+            float l_b = __shfl_xor(l[g], step, 64);
+            float acc_b[EPL];
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc_b[i] = __shfl_xor(acc[g][i], step, 64);
+            merge_state<EPL>(m[g], l[g], acc[g], m_b, l_b, acc_b);
+        }
+        if (grp == 0) {
+#pragma unroll
+            for (int j = 0; j < NV; ++j)
+#pragma unroll
+                for (int i = 0; i < EPV; ++i) sm[wave][g][TR::vec_offset(sub, j) + i] = acc[g][j * EPV + i];
+            if (sub == 0) {
+                sm[wave][g][D] = m[g];
+                sm[wave][g][D + 1] = l[g];
+            }
+        }
+    }
+    __syncthreads();
+
+    // merge the four waves; one thread per (head, channel)
+    for (int idx = threadIdx.x; idx < GT * D; idx += kBlock) {
+        const int g = idx / D, c = idx - g * D;
+        if (g >= nh) continue;
+        float mx = kNegBig;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mx = fmaxf(mx, sm[w][g][D]);
+        float lt = 0.f, ot = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float wt = fast_exp2(sm[w][g][D] - mx);
+            lt += wt * sm[w][g][D + 1];
+            ot += wt * sm[w][g][c];
+        }
+        const int64_t th = (int64_t)tile * a.n_q_heads + (h0 + g);
+        a.ws_o[th * D + c] = ot;
+        if (c == 0) {
+            a.ws_m[th] = mx;
+            a.ws_l[th] = lt;
+        }
+    }
+}
+
+// ---- tile statistics -> range triple (or normalised output) -----------------------------------
+
+template <int D>
+__global__ __launch_bounds__(D) void hg_tile_reduce_kernel(const ReduceArgs a)
+{
+    const int r = blockIdx.x, h = blockIdx.y, c = threadIdx.x;
+    const int ts = table_entry(a.tab, r).tile_start;
+    const int te = table_entry(a.tab, r + 1).tile_start;
+    float mx = kNegBig;
+    for (int t = ts; t < te; ++t) mx = fmaxf(mx, a.ws_m[(int64_t)t * a.n_q_heads + h]);
+    float lt = 0.f, ot = 0.f;
+    for (int t = ts; t < te; ++t) {
+        const int64_t th = (int64_t)t * a.n_q_heads + h;
+        const float wt = fast_exp2(a.ws_m[th] - mx);
+        lt += wt * a.ws_l[th];
+        ot += wt * a.ws_o[th * D + c];
+    }
+    const int64_t rh = (int64_t)r * a.n_q_heads + h;
+    const bool empty = !(lt > 0.f);
+    if (a.normalise) {
+        a.o_out[rh * D + c] = empty ? 0.f : ot / lt;
+        if (c == 0 && a.m_out) a.m_out[rh] = empty ? -INFINITY : mx * kLn2 + logf(lt);
+    } else {
+        a.o_out[rh * D + c] = empty ? 0.f : ot;
+        if (c == 0) {
+            a.m_out[rh] = empty ? -INFINITY : mx * kLn2;
+            a.l_out[rh] = empty ? 0.f : lt;
+        }
+    }
+}
+
+// ---- exact merge of range triples ---------------------------------------------------------------
+
+template <int D>
+__global__ __launch_bounds__(D) void hg_merge_kernel(const MergeArgs a)
+{
+    const int gidx = blockIdx.x, h = blockIdx.y, c = threadIdx.x;
+    const int ts = a.tab.ext ? a.tab.ext[gidx] : a.tab.inl[gidx];
+    const int te = a.tab.ext ? a.tab.ext[gidx + 1] : a.tab.inl[gidx + 1];
+    float mx = -INFINITY;
+    for (int t = ts; t < te; ++t) {
+        const int64_t th = (int64_t)t * a.n_q_heads + h;
+        if (a.l[th] != 0.f) mx = fmaxf(mx, a.m[th]);
+    }
+    float lt = 0.f, ot = 0.f;
+    for (int t = ts; t < te; ++t) {
+        const int64_t th = (int64_t)t * a.n_q_heads + h;
+        const float lv = a.l[th];
+        if (lv == 0.f) continue;  // identity element
+        const float wt = fast_exp2((a.m[th] - mx) * kLog2e);
+        lt += wt * lv;
+        ot += wt * a.o[th * D + c];
+    }
+    const int64_t gh = (int64_t)gidx * a.n_q_heads + h;
+    const bool empty = !(lt > 0.f);
+    a.out[gh * D + c] = empty ? 0.f : ot / lt;
+    if (c == 0 && a.lse) a.lse[gh] = empty ? -INFINITY : mx + logf(lt);
+}
+
+// ---- table upload (host tables reach the device through kernel arguments only) ----------------
+
+__global__ void hg_upload_ranges_kernel(RangeEntry *dst, int count, const RangeChunk chunk)
+{
+    const int i = threadIdx.x;
+    if (i < count) dst[i] = chunk.e[i];
+}
+
+__global__ void hg_upload_ints_kernel(int32_t *dst, int count, const IntChunk chunk)
+{
+    const int i = threadIdx.x;
+    if (i < count) dst[i] = chunk.e[i];
+}
+
+}  // namespace hg

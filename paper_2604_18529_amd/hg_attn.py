@@ -1,0 +1,289 @@
+"""Thin Python binding of the C ABI in ``include/hg_attn.h``.
+
+Argument marshalling only: every step of the attention path runs inside the HIP library.
+PyTorch supplies device memory (tensors) and the stream; nothing here computes.
+There is no fallback: if the library is missing and cannot be built, importing fails loudly.
+
+Shapes (see the header for the full contract):
+  q [B, Hq, d]; k, v [B, Hkv, N, d] (any strides over the first three axes, channel stride 1);
+  seq_lens: host int32 [B]; ranges: sequence of (seq, begin, end) or a packed table from
+  ``pack_ranges``; triples m, l [R, Hq] and o [R, Hq, d] in fp32.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+from . import _build
+
+HG_OK = 0
+HG_F16, HG_F32 = 0, 1
+
+
+class HgError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (what, hg_strerror(status), status))
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [
+        ("q", ctypes.c_void_p),
+        ("k", ctypes.c_void_p),
+        ("v", ctypes.c_void_p),
+        ("stride_b", ctypes.c_int64),
+        ("stride_h", ctypes.c_int64),
+        ("stride_t", ctypes.c_int64),
+        ("seq_lens", ctypes.c_void_p),
+        ("batch", ctypes.c_int32),
+        ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+    ]
+
+
+class _Range(ctypes.Structure):
+    _fields_ = [("seq", ctypes.c_int32), ("begin", ctypes.c_int32), ("end", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load ``libhg_attn.so`` (building it with hipcc first if it was never built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build_library()
+    lib = ctypes.CDLL(_build.LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    D, R = ctypes.POINTER(_Desc), ctypes.POINTER(_Range)
+    lib.hg_strerror.argtypes = [ctypes.c_int]
+    lib.hg_strerror.restype = ctypes.c_char_p
+    lib.hg_attn_partial_workspace_size.argtypes = [D, R, i32, ctypes.POINTER(sz)]
+    lib.hg_attn_partial.argtypes = [D, R, i32, vp, vp, vp, vp, sz, vp]
+    lib.hg_attn_merge_workspace_size.argtypes = [i32, ctypes.POINTER(sz)]
+    lib.hg_attn_merge.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.hg_attn_full_workspace_size.argtypes = [D, ctypes.POINTER(sz)]
+    lib.hg_attn_full.argtypes = [D, vp, vp, vp, sz, vp]
+    lib.hg_attn_plan.argtypes = [D, R, i32, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_int64)]
+    lib.hg_attn_set_tile_tokens.argtypes = [i32]
+    lib.hg_attn_profile_start.argtypes = [i32]
+    lib.hg_attn_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+    for name in (
+        "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_merge_workspace_size", "hg_attn_merge",
+        "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_tile_tokens",
+        "hg_attn_profile_start", "hg_attn_profile_stop",
+    ):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def hg_strerror(status: int) -> str:
+    return load_library().hg_strerror(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != HG_OK:
+        raise HgError(status, what)
+
+
+def pack_ranges(ranges):
+    """(seq, begin, end) triples -> packed hg_range array (reusable across calls)."""
+    if isinstance(ranges, ctypes.Array):
+        return ranges
+    arr = (_Range * max(len(ranges), 1))()
+    for i, (s, b, e) in enumerate(ranges):
+        arr[i].seq, arr[i].begin, arr[i].end = int(s), int(b), int(e)
+    arr.n = len(ranges)
+    return arr
+
+
+def _n_ranges(packed) -> int:
+    return getattr(packed, "n", len(packed))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream or None
+    return int(stream) or None
+
+
+def make_desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seq_lens, scale: Optional[float] = None):
+    """Describe a problem.  Returns (desc, keepalive); keepalive must outlive the calls using desc."""
+    if q.dtype not in (torch.float16, torch.float32) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise TypeError("q, k, v must share dtype float16 or float32")
+    if q.dim() != 3 or k.dim() != 4 or v.dim() != 4 or k.shape != v.shape:
+        raise ValueError("q must be [B,Hq,d]; k and v [B,Hkv,N,d] of equal shape")
+    if not q.is_contiguous():
+        raise ValueError("q must be contiguous")
+    B, Hq, d = q.shape
+    if k.shape[0] != B or k.shape[3] != d:
+        raise ValueError("k/v do not match q")
+    if k.stride() != v.stride() or (k.numel() and k.stride(3) != 1):
+        raise ValueError("k and v must share strides and have a contiguous channel axis")
+    if not (q.device == k.device == v.device):
+        raise ValueError("q, k, v must live on one device")
+    seq = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    if seq.shape != (B,):
+        raise ValueError("seq_lens must be [B]")
+    if B and int(seq.max()) > k.shape[2]:
+        raise ValueError("seq_lens exceeds the cache length")
+    desc = _Desc(
+        q.data_ptr(), k.data_ptr(), v.data_ptr(), k.stride(0), k.stride(1), k.stride(2), seq.ctypes.data,
+        B, Hq, k.shape[1], d, HG_F16 if q.dtype == torch.float16 else HG_F32,
+        float(scale if scale is not None else 1.0 / math.sqrt(d)),
+    )
+    return desc, (q, k, v, seq)
+
+
+def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> Tuple[Optional[torch.Tensor], int]:
+    if workspace is not None:
+        return workspace, workspace.numel() * workspace.element_size()
+    if nbytes == 0:
+        return None, 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    return ws, nbytes
+
+
+def hg_attn_plan(q, k, v, seq_lens, ranges, scale=None) -> Tuple[int, int]:
+    """(tile_tokens, n_tiles) the library would use; host only."""
+    lib = load_library()
+    desc, keep = make_desc(q, k, v, seq_lens, scale)
+    packed = pack_ranges(ranges)
+    tile = ctypes.c_int32()
+    n = ctypes.c_int64()
+    _check(lib.hg_attn_plan(ctypes.byref(desc), packed, _n_ranges(packed), ctypes.byref(tile), ctypes.byref(n)), "hg_attn_plan")
+    del keep
+    return tile.value, n.value
+
+
+def hg_attn_set_tile_tokens(tile_tokens: int) -> None:
+    _check(load_library().hg_attn_set_tile_tokens(int(tile_tokens)), "hg_attn_set_tile_tokens")
+
+
+def hg_attn_profile_start(max_launches: int) -> None:
+    _check(load_library().hg_attn_profile_start(int(max_launches)), "hg_attn_profile_start")
+
+
+def hg_attn_profile_stop() -> Tuple[float, int]:
+    """(summed milliseconds of the streaming kernel, launches timed)."""
+    ms, n = ctypes.c_float(), ctypes.c_int32()
+    _check(load_library().hg_attn_profile_stop(ctypes.byref(ms), ctypes.byref(n)), "hg_attn_profile_stop")
+    return ms.value, n.value
+
+
+def hg_attn_partial_workspace_size(desc, packed) -> int:
+    sz = ctypes.c_size_t()
+    _check(load_library().hg_attn_partial_workspace_size(ctypes.byref(desc), packed, _n_ranges(packed), ctypes.byref(sz)),
+           "hg_attn_partial_workspace_size")
+    return sz.value
+
+
+def hg_attn_partial(q, k, v, seq_lens, ranges, scale=None, *, m=None, l=None, o=None, workspace=None, stream=None,
+                    desc=None):
+    """Per-range statistics.  Returns (m [R,Hq], l [R,Hq], o [R,Hq,d]) fp32 device tensors."""
+    lib = load_library()
+    if desc is None:
+        desc, keep = make_desc(q, k, v, seq_lens, scale)
+    else:
+        keep = None
+    packed = pack_ranges(ranges)
+    R = _n_ranges(packed)
+    dev = q.device
+    Hq, d = q.shape[1], q.shape[2]
+    if m is None:
+        m = torch.empty((R, Hq), dtype=torch.float32, device=dev)
+    if l is None:
+        l = torch.empty((R, Hq), dtype=torch.float32, device=dev)
+    if o is None:
+        o = torch.empty((R, Hq, d), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace, ws_bytes = _workspace(hg_attn_partial_workspace_size(desc, packed), dev, None)
+    else:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        st = lib.hg_attn_partial(ctypes.byref(desc), packed, R, _ptr(m), _ptr(l), _ptr(o), _ptr(workspace), ws_bytes,
+                                 _stream_handle(stream))
+    _check(st, "hg_attn_partial")
+    del keep
+    return m, l, o
+
+
+def hg_attn_merge(m, l, o, group_ptr, *, out=None, lse=None, want_lse=True, workspace=None, stream=None):
+    """Exact merge of triples per CSR group.  Returns (out [n_groups,Hq,d], lse [n_groups,Hq] or None)."""
+    lib = load_library()
+    gp = np.ascontiguousarray(group_ptr, dtype=np.int32)
+    if gp.ndim != 1 or gp.size < 1:
+        raise ValueError("group_ptr must be CSR offsets [n_groups+1]")
+    if o.dim() != 3 or tuple(m.shape) != tuple(o.shape[:2]) or m.shape != l.shape:
+        raise ValueError("m, l must be [T,Hq] and o [T,Hq,d]")
+    for t in (m, l, o):
+        if t.dtype != torch.float32 or not t.is_contiguous():
+            raise ValueError("triples must be contiguous fp32")
+    if gp[-1] > m.shape[0]:
+        raise ValueError("group_ptr runs past the triples")
+    n_groups = gp.size - 1
+    _, Hq, d = o.shape
+    dev = o.device
+    if out is None:
+        out = torch.empty((n_groups, Hq, d), dtype=torch.float32, device=dev)
+    if lse is None and want_lse:
+        lse = torch.empty((n_groups, Hq), dtype=torch.float32, device=dev)
+    if workspace is None:
+        sz = ctypes.c_size_t()
+        _check(lib.hg_attn_merge_workspace_size(n_groups, ctypes.byref(sz)), "hg_attn_merge_workspace_size")
+        workspace, ws_bytes = _workspace(sz.value, dev, None)
+    else:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        st = lib.hg_attn_merge(_ptr(m), _ptr(l), _ptr(o), gp.ctypes.data, n_groups, Hq, d, _ptr(out), _ptr(lse),
+                               _ptr(workspace), ws_bytes, _stream_handle(stream))
+    _check(st, "hg_attn_merge")
+    return out, lse
+
+
+def hg_attn_full_workspace_size(desc) -> int:
+    sz = ctypes.c_size_t()
+    _check(load_library().hg_attn_full_workspace_size(ctypes.byref(desc), ctypes.byref(sz)), "hg_attn_full_workspace_size")
+    return sz.value
+
+
+def hg_attn_full(q, k, v, seq_lens, scale=None, *, out=None, lse=None, want_lse=True, workspace=None, stream=None,
+                 desc=None):
+    """Unsplit attention over the whole cache.  Returns (out [B,Hq,d], lse [B,Hq] or None)."""
+    lib = load_library()
+    if desc is None:
+        desc, keep = make_desc(q, k, v, seq_lens, scale)
+    else:
+        keep = None
+    dev = q.device
+    B, Hq, d = q.shape
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=torch.float32, device=dev)
+    if lse is None and want_lse:
+        lse = torch.empty((B, Hq), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace, ws_bytes = _workspace(hg_attn_full_workspace_size(desc), dev, None)
+    else:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        st = lib.hg_attn_full(ctypes.byref(desc), _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, _stream_handle(stream))
+    _check(st, "hg_attn_full")
+    del keep
+    return out, lse

@@ -1,0 +1,145 @@
+"""Host-side checks of the C ABI (no GPU, no device work).
+
+The library must load, export every function the header declares, reject malformed arguments
+with the documented status before anything is enqueued, and plan tiles that cover every range
+exactly.  Pointers handed over here are fake non-NULL addresses: only calls that fail validation
+(or that are host-only by contract) are made, so nothing is ever dereferenced on a device.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2604_18529_amd import _build
+from paper_2604_18529_amd import hg_attn as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "hg_attn.h")
+
+FAKE = 0x10000  # 16- and 256-byte aligned, never dereferenced
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if _build.is_stale():
+        _build.build_library()
+    return B.load_library()
+
+
+def _desc(seq_lens, batch=None, hq=4, hkv=2, d=128, dtype=0, stride_t=None, q=FAKE, k=FAKE, v=FAKE, scale=0.1):
+    seq = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    batch = len(seq) if batch is None else batch
+    stride_t = d if stride_t is None else stride_t
+    nmax = max(int(seq.max()), 1) if len(seq) else 1
+    desc = B._Desc(q, k, v, hkv * nmax * stride_t, nmax * stride_t, stride_t, seq.ctypes.data, batch, hq, hkv, d, dtype, scale)
+    desc._keep = seq
+    return desc
+
+
+def test_exports_every_declared_function(lib):
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(hg_[a-z_0-9]+)\s*\(", text))
+    assert {"hg_attn_partial", "hg_attn_merge", "hg_attn_full", "hg_strerror"} <= names
+    for n in sorted(names):
+        assert hasattr(lib, n), "library does not export %s" % n
+
+
+def test_strerror_is_total(lib):
+    for code in range(-8, 2):
+        assert isinstance(B.hg_strerror(code), str) and B.hg_strerror(code)
+    assert B.hg_strerror(0) == "ok"
+
+
+def _partial(lib, desc, ranges, m=FAKE, l=FAKE, o=FAKE, ws=FAKE * 16, ws_bytes=1 << 40):
+    packed = B.pack_ranges(ranges)
+    return lib.hg_attn_partial(ctypes.byref(desc), packed, len(ranges), m, l, o, ws, ws_bytes, None)
+
+
+def test_partial_rejects_bad_arguments_before_any_launch(lib):
+    good = [(0, 0, 10)]
+    assert _partial(lib, _desc([10], dtype=7), good) == -3
+    assert _partial(lib, _desc([10], d=96), good) == -2
+    assert _partial(lib, _desc([10], hq=5, hkv=2), good) == -2
+    assert _partial(lib, _desc([10], q=0), good) == -1
+    assert _partial(lib, _desc([10], k=FAKE + 8), good) == -2  # misaligned base
+    assert _partial(lib, _desc([10], stride_t=64), good) == -2  # rows overlap
+    assert _partial(lib, _desc([10], stride_t=132), good) == -2  # rows not 16-byte aligned
+    assert _partial(lib, _desc([10], scale=float("nan")), good) == -2
+    assert _partial(lib, _desc([-1]), good) == -4
+    for bad in [(0, 5, 4), (0, 0, 11), (1, 0, 1), (-1, 0, 1), (0, -1, 3)]:
+        assert _partial(lib, _desc([10]), [bad]) == -4
+    assert _partial(lib, _desc([10]), good, m=None) == -1
+    assert _partial(lib, _desc([10]), good, ws=None) == -5
+    assert _partial(lib, _desc([10]), good, ws=FAKE + 16) == -5  # not 256-byte aligned
+    assert _partial(lib, _desc([10]), good, ws_bytes=8) == -5
+    assert lib.hg_attn_partial(None, None, 0, None, None, None, None, 0, None) == -1
+    # nothing to do is fine and touches nothing
+    assert _partial(lib, _desc([10]), [], m=None, l=None, o=None, ws=None, ws_bytes=0) == 0
+
+
+def test_full_and_merge_reject_bad_arguments(lib):
+    d = _desc([10, 20])
+    assert lib.hg_attn_full(ctypes.byref(d), None, None, FAKE * 16, 1 << 40, None) == -1
+    assert lib.hg_attn_full(ctypes.byref(d), FAKE, None, None, 0, None) == -5
+    gp = np.array([0, 2, 1], dtype=np.int32)
+    assert lib.hg_attn_merge(FAKE, FAKE, FAKE, gp.ctypes.data, 2, 4, 128, FAKE, None, None, 0, None) == -4
+    gp = np.array([-1, 2], dtype=np.int32)
+    assert lib.hg_attn_merge(FAKE, FAKE, FAKE, gp.ctypes.data, 1, 4, 128, FAKE, None, None, 0, None) == -4
+    gp = np.array([0, 2], dtype=np.int32)
+    assert lib.hg_attn_merge(FAKE, FAKE, FAKE, gp.ctypes.data, 1, 4, 100, FAKE, None, None, 0, None) == -2
+    assert lib.hg_attn_merge(FAKE, FAKE, FAKE, gp.ctypes.data, 1, 4, 128, None, None, None, 0, None) == -1
+    assert lib.hg_attn_merge(None, FAKE, FAKE, gp.ctypes.data, 1, 4, 128, FAKE, None, None, 0, None) == -1
+    assert lib.hg_attn_merge(FAKE, FAKE, FAKE, None, 1, 4, 128, FAKE, None, None, 0, None) == -1
+    assert lib.hg_attn_merge(None, None, None, None, 0, 4, 128, None, None, None, 0, None) == 0
+    big = np.arange(1000, dtype=np.int32)  # more groups than fit in kernel arguments: needs workspace
+    sz = ctypes.c_size_t()
+    assert lib.hg_attn_merge_workspace_size(999, ctypes.byref(sz)) == 0 and sz.value >= 4000
+    assert lib.hg_attn_merge(FAKE, FAKE, FAKE, big.ctypes.data, 999, 4, 128, FAKE, None, None, 0, None) == -5
+
+
+def _plan(lib, desc, ranges):
+    packed = B.pack_ranges(ranges)
+    tile, n = ctypes.c_int32(), ctypes.c_int64()
+    st = lib.hg_attn_plan(ctypes.byref(desc), packed, len(ranges), ctypes.byref(tile), ctypes.byref(n))
+    assert st == 0
+    return tile.value, n.value
+
+
+def test_tile_plan_covers_ranges(lib):
+    try:
+        seq = [5000, 70, 0, 1 << 20]
+        ranges = [(0, 0, 5000), (0, 17, 17), (1, 3, 70), (3, 0, 1 << 20), (3, 1000, 1001), (0, 4999, 5000)]
+        for forced in (0, 64, 128, 1024, 4096):
+            assert lib.hg_attn_set_tile_tokens(forced) == 0
+            tile, n = _plan(lib, _desc(seq), ranges)
+            assert tile % 64 == 0 and 64 <= tile
+            if forced:
+                assert tile == forced
+            want = sum((e - b + tile - 1) // tile for _, b, e in ranges)
+            assert n == want
+        for bad in (63, 100, -64, 1 << 20):
+            assert lib.hg_attn_set_tile_tokens(bad) == -2
+        # workspace grows with tiles * heads * (d + 2) floats
+        lib.hg_attn_set_tile_tokens(64)
+        d = _desc(seq)
+        sz = ctypes.c_size_t()
+        packed = B.pack_ranges(ranges)
+        assert lib.hg_attn_partial_workspace_size(ctypes.byref(d), packed, len(ranges), ctypes.byref(sz)) == 0
+        tile, n = _plan(lib, d, ranges)
+        assert sz.value >= n * 4 * (128 + 2) * 4
+    finally:
+        lib.hg_attn_set_tile_tokens(0)
+
+
+def test_large_range_tables_need_table_space(lib):
+    seq = [100000]
+    many = [(0, i, i + 1) for i in range(500)]
+    d = _desc(seq)
+    sz_many, sz_few = ctypes.c_size_t(), ctypes.c_size_t()
+    pm, pf = B.pack_ranges(many), B.pack_ranges(many[:10])
+    assert lib.hg_attn_partial_workspace_size(ctypes.byref(d), pm, 500, ctypes.byref(sz_many)) == 0
+    assert lib.hg_attn_partial_workspace_size(ctypes.byref(d), pf, 10, ctypes.byref(sz_few)) == 0
+    assert sz_many.value > sz_few.value

@@ -1,0 +1,182 @@
+"""GPU parity: the HIP path, called through the C ABI binding, against the fp64 oracle on the
+same seeded bits -- element by element, at sizes the oracle finishes in seconds that still span
+several tiles and a ragged tail.  Full-size configurations are in test_parity_fullsize_gpu.py."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_18529_amd as hg
+from paper_2604_18529_amd import workloads as W
+
+from parity_utils import check_out, check_triples, kv_np, run_all_and_check, to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(autouse=True)
+def _default_tiles():
+    hg.hg_attn_set_tile_tokens(0)
+    yield
+    hg.hg_attn_set_tile_tokens(0)
+
+
+def test_config0_tiny_mha_exact_shape():
+    w = W.make_workload(W.WORKLOADS[0], DEV)
+    assert w.ranges == [(0, 0, 300), (0, 300, 512)]
+    run_all_and_check(w, what="config0")
+
+
+# reduced versions of the four large configurations: same heads structure, dtype, outliers and
+# partition recipe; batch and context cut down so the oracle takes seconds
+REDUCED = [
+    W.WORKLOADS[1].scaled(name="r1", batch=2, n_q_heads=8, n_kv_heads=8, n_min=3000, n_max=3000),
+    W.WORKLOADS[2].scaled(name="r2", batch=4, n_q_heads=5, n_kv_heads=5, n_min=1500, n_max=3100),
+    W.WORKLOADS[3].scaled(name="r3", batch=2, n_q_heads=7, n_kv_heads=7, n_min=5000, n_max=5000),
+    W.WORKLOADS[4].scaled(name="r4", batch=1, n_q_heads=16, n_kv_heads=2, n_min=9001, n_max=9001),
+]
+
+
+@pytest.mark.parametrize("spec", REDUCED, ids=lambda s: s.name)
+@pytest.mark.parametrize("tile", [0, 64, 1024])
+def test_reduced_configs(spec, tile):
+    hg.hg_attn_set_tile_tokens(tile)
+    w = W.make_workload(spec, DEV)
+    run_all_and_check(w, what="%s tile=%d" % (spec.name, tile))
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("group", [1, 2, 3, 4, 5, 8, 16])
+def test_every_kernel_instance(dtype, d, group):
+    """Every (storage type, head_dim, heads-per-KV-head) code path, with ragged lengths."""
+    spec = W.WorkloadSpec("inst", 3, 2 * group, 2, d, dtype, 1, 700, "ratios", 3, seed=group + d)
+    w = W.make_workload(spec, DEV)
+    run_all_and_check(w, what="%s d=%d G=%d" % (dtype, d, group))
+
+
+@pytest.mark.parametrize("tile", [64, 128])
+def test_edge_ranges(tile):
+    """Empty, one-token, tile-edge, unsorted and overlapping ranges; a zero-length sequence."""
+    hg.hg_attn_set_tile_tokens(tile)
+    spec = W.WorkloadSpec("edge", 3, 4, 2, 128, "f16", 0, 1000, "none", seed=5)
+    w = W.make_workload(spec, DEV)
+    w.seq_lens[:] = [1000, 0, 257]
+    T = tile
+    ranges = [
+        (0, 0, 0), (0, 1000, 1000), (0, 0, 1), (0, 999, 1000), (0, T - 1, T), (0, T, T + 1), (0, T - 1, T + 1),
+        (0, 0, T), (0, 0, T + 1), (0, 1, 2 * T), (0, 3 * T, 3 * T), (2, 0, 257), (2, 256, 257), (0, 500, 900),
+        (0, 100, 600), (1, 0, 0), (0, 0, 1000), (2, 5, 6),
+    ]
+    kn, vn = kv_np(w)
+    m, l, o = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, ranges, w.scale)
+    mo, lo, oo = oracle.attn_partial(to_np(w.q), kn, vn, w.seq_lens, w.scale, ranges)
+    check_triples(m, l, o, mo, lo, oo, "edge")
+    # groups with empty members, an all-empty group and an empty group
+    gp = [0, 2, 2, 5, 18]
+    out, lse = hg.hg_attn_merge(m, l, o, gp)
+    ref, rlse = oracle.attn_merge(mo, lo, oo, gp)
+    check_out(out, lse, ref, rlse, "edge merge")
+    assert not to_np(out[0]).any() and np.isneginf(to_np(lse[0])).all()
+    fout, flse = hg.hg_attn_full(w.q, w.k, w.v, w.seq_lens, w.scale)
+    fref, frlse = oracle.attn_full(to_np(w.q), kn, vn, w.seq_lens, w.scale)
+    check_out(fout, flse, fref, frlse, "edge full")
+    assert not to_np(fout[1]).any() and np.isneginf(to_np(flse[1])).all()
+
+
+def test_zero_query_counts_tokens_bit_exact():
+    """q = 0: m = 0 and l = range length exactly; with bit-plane values O is an exact integer
+    count per channel, which pins the membership of every range and tile."""
+    hg.hg_attn_set_tile_tokens(128)
+    N, d = 5000, 128
+    spec = W.WorkloadSpec("bits", 1, 2, 1, d, "f16", N, N, "none", seed=9)
+    w = W.make_workload(spec, DEV)
+    w.q.zero_()
+    w.v[0, 0] = W.bitplane_values(N, d, torch.float16, DEV)
+    ranges = [(0, 0, N), (0, 1, 4999), (0, 127, 129), (0, 128, 256), (0, 1000, 1001), (0, 63, 4097), (0, 4990, 5000)]
+    ranges += W.random_ranges([N], 40, seed=3)
+    m, l, o = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, ranges, w.scale)
+    mo, lo, oo = oracle.attn_partial(to_np(w.q), *kv_np(w), w.seq_lens, w.scale, ranges)
+    m, l, o = to_np(m), to_np(l), to_np(o)
+    ne = lo[:, 0] > 0
+    assert np.array_equal(l.astype(np.float64), lo)
+    assert np.all(m[ne] == 0.0)
+    assert np.array_equal(o.astype(np.float64), oo)
+
+
+def test_many_ranges_take_the_table_upload_path():
+    """More ranges than fit in kernel arguments (table in workspace), and more merge groups than
+    fit (CSR in workspace)."""
+    spec = W.WorkloadSpec("many", 2, 4, 4, 64, "f16", 2000, 2000, "none", seed=11)
+    w = W.make_workload(spec, DEV)
+    ranges = W.random_ranges(w.seq_lens, 700, seed=4, max_len=300)
+    m, l, o = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, ranges, w.scale)
+    mo, lo, oo = oracle.attn_partial(to_np(w.q), *kv_np(w), w.seq_lens, w.scale, ranges)
+    check_triples(m, l, o, mo, lo, oo, "many ranges")
+    gp = np.arange(0, 701, 2, dtype=np.int32)  # 350 groups of 2
+    out, lse = hg.hg_attn_merge(m, l, o, gp)
+    ref, rlse = oracle.attn_merge(mo, lo, oo, gp)
+    check_out(out, lse, ref, rlse, "many groups")
+
+
+def test_batch_larger_than_inline_table():
+    spec = W.WorkloadSpec("b100", 100, 2, 2, 64, "f32", 1, 90, "half", 2, seed=12)
+    w = W.make_workload(spec, DEV)
+    run_all_and_check(w, what="batch 100")
+
+
+def test_token_major_layout():
+    """K, V stored [B, N, Hkv, d] (stride_t = Hkv*d): same results as the head-major layout."""
+    spec = W.WorkloadSpec("bthd", 2, 8, 4, 128, "f16", 300, 1200, "dirichlet", 5, seed=13)
+    w = W.make_workload(spec, DEV, layout="bthd")
+    assert not w.k.is_contiguous()
+    run_all_and_check(w, what="token-major")
+
+
+def test_partition_invariance_on_gpu():
+    """Any table that tiles the cache once merges to the unsplit result (the method's claim),
+    and the order of triples inside a group does not matter."""
+    spec = W.WorkloadSpec("inv", 2, 4, 4, 128, "f16", 4000, 4000, "none", seed=14)
+    w = W.make_workload(spec, DEV)
+    fout, flse = hg.hg_attn_full(w.q, w.k, w.v, w.seq_lens, w.scale)
+    rng = np.random.RandomState(0)
+    for parts in (1, 2, 7, 64):
+        ranges, gp = [], [0]
+        for b in range(2):
+            cuts = sorted(rng.randint(0, 4001, size=parts - 1).tolist())
+            bounds = [0] + cuts + [4000]
+            rs = [(b, bounds[i], bounds[i + 1]) for i in range(parts)]
+            rng.shuffle(rs)
+            ranges += rs
+            gp.append(len(ranges))
+        m, l, o = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, ranges, w.scale)
+        out, lse = hg.hg_attn_merge(m, l, o, gp)
+        assert (out - fout).abs().max().item() <= 2e-5
+        assert (lse - flse).abs().max().item() <= 2e-5
+
+
+def test_outputs_untouched_on_error():
+    spec = W.WorkloadSpec("err", 1, 2, 2, 64, "f16", 100, 100, "none", seed=15)
+    w = W.make_workload(spec, DEV)
+    m = torch.full((1, 2), 7.0, device=DEV)
+    l = torch.full((1, 2), 7.0, device=DEV)
+    o = torch.full((1, 2, 64), 7.0, device=DEV)
+    with pytest.raises(hg.HgError) as ei:
+        hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, [(0, 50, 101)], w.scale, m=m, l=l, o=o)
+    assert ei.value.status == -4
+    torch.cuda.synchronize()
+    assert (m == 7).all() and (l == 7).all() and (o == 7).all()
+
+
+def test_runs_on_a_side_stream():
+    spec = W.WorkloadSpec("stream", 2, 4, 2, 128, "f16", 2500, 2500, "half", 2, seed=16)
+    w = W.make_workload(spec, DEV)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        m, l, o = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, w.ranges, w.scale)
+        out, lse = hg.hg_attn_merge(m, l, o, w.group_ptr)
+    s.synchronize()
+    ref, rlse = oracle.attn_full(to_np(w.q), *kv_np(w), w.seq_lens, w.scale)
+    check_out(out, lse, ref, rlse, "side stream")
