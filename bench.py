@@ -144,6 +144,8 @@ def main():
     ap.add_argument("--others", type=str, default="2,3,4", help="comma list of further workloads to time ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile-tokens", type=int, default=0)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (known traffic, to scale profiler counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path shards by (sequence, KV head) or by "
@@ -158,6 +160,14 @@ def main():
 
     hg.load_library()
     hg.hg_attn_set_tile_tokens(args.tile_tokens)
+
+    if args.calibration_copy:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     head, cpu = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, torch, hg, W)
     others = []

@@ -79,11 +79,11 @@ int32_t pick_group_tile(int32_t group)
 int32_t pick_tile_tokens(int64_t total_tokens, int64_t streams)
 {
     if (g_forced_tile_tokens) return g_forced_tile_tokens;
-    const int64_t target_blocks = 4096;
+    const int64_t target_blocks = 2048;
     int64_t t = (total_tokens * streams + target_blocks - 1) / target_blocks;
     t = (t + 63) / 64 * 64;
     if (t < 64) t = 64;
-    if (t > 1024) t = 1024;
+    if (t > 2048) t = 2048;
     return (int32_t)t;
 }
 
@@ -237,9 +237,9 @@ hg_status run(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, i
     ra.o_out = o;
     dim3 rgrid((unsigned)n_ranges, (unsigned)d->n_q_heads);
     if (d->head_dim == 128)
-        hipLaunchKernelGGL(hg_tile_reduce_kernel<128>, rgrid, dim3(128), 0, stream, ra);
+        hipLaunchKernelGGL(hg_tile_reduce_kernel<128>, rgrid, dim3(kReduceBlock), 0, stream, ra);
     else
-        hipLaunchKernelGGL(hg_tile_reduce_kernel<64>, rgrid, dim3(64), 0, stream, ra);
+        hipLaunchKernelGGL(hg_tile_reduce_kernel<64>, rgrid, dim3(kReduceBlock), 0, stream, ra);
     return launch_status("tile reduce kernel");
 }
 
