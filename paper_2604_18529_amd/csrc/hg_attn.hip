@@ -67,8 +67,16 @@ hg_status check_ranges(const hg_attn_desc *d, const hg_range *ranges, int32_t n_
     return HG_OK;
 }
 
-int32_t pick_group_tile(int32_t group)
+// The matrix-core kernel takes fp16, head_dim 128 and at least 4 query heads per KV head.
+bool use_gqa_kernel(const hg_attn_desc *d)
 {
+    return d->dtype == HG_F16 && d->head_dim == 128 && d->n_q_heads / d->n_kv_heads >= 4;
+}
+
+int32_t pick_group_tile(const hg_attn_desc *d)
+{
+    const int32_t group = d->n_q_heads / d->n_kv_heads;
+    if (use_gqa_kernel(d)) return kGqaHeads;
     if (group >= 8) return 8;
     if (group > 2) return 4;
     return group;  // 1 or 2
@@ -90,7 +98,7 @@ int32_t pick_tile_tokens(int64_t total_tokens, int64_t streams)
 hg_status make_plan(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, Plan &p)
 {
     const int32_t group = d->n_q_heads / d->n_kv_heads;
-    p.gt = pick_group_tile(group);
+    p.gt = pick_group_tile(d);
     p.n_chunks = (group + p.gt - 1) / p.gt;
     if ((int64_t)d->n_kv_heads * p.n_chunks > 65535) return HG_ERR_SHAPE;
     int64_t total_tokens = 0;
@@ -218,7 +226,10 @@ hg_status run(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, i
         dim3 grid((unsigned)p.n_tiles, (unsigned)(d->n_kv_heads * p.n_chunks));
         const bool timed = (size_t)(2 * g_prof_used + 2) <= g_prof_events.size();
         if (timed) (void)hipEventRecord(g_prof_events[2 * g_prof_used], stream);
-        launch_partial(d, pa, p.gt, grid, stream);
+        if (use_gqa_kernel(d))
+            hipLaunchKernelGGL(hg_partial_gqa_kernel, grid, dim3(kBlock), 0, stream, pa);
+        else
+            launch_partial(d, pa, p.gt, grid, stream);
         if (timed) (void)hipEventRecord(g_prof_events[2 * g_prof_used++ + 1], stream);
         st = launch_status("partial kernel");
         if (st != HG_OK) return st;

@@ -381,6 +381,228 @@ __global__ __launch_bounds__(kBlock) void hg_partial_kernel(const PartialArgs a)
     }
 }
 
+// ---- streaming kernel for grouped-query attention (fp16, head_dim 128) on the matrix cores -----
+//
+// With G query heads sharing one KV head, every K and V byte feeds G dot products; on the
+// vector ALU that makes the scan arithmetic-bound from G = 4 upwards.  Here up to 16 query heads
+// of a KV head form the M dimension of v_mfma_f32_16x16x32_f16, so the arithmetic is a few
+// percent of the matrix cores and the kernel is bandwidth-bound again.
+//
+// Per wave and per block of 32 tokens:
+//   K   8 coalesced 16-byte loads per lane (4 whole rows per instruction) -> wave-private LDS
+//       (rows padded to 272 bytes) -> read back "token per lane": lane l gets token l%16,
+//       channels 8*(4kk + l/16)..+7, which IS the B operand of MFMA kk (the contraction runs
+//       over channels, and Q is laid out with the same channel grouping as A operand).
+//       S = Q.K^T lands as: lane (n = l%16, rg = l/16) holds heads 4rg..4rg+3 of token n.
+//   softmax  row max over the 16 token lanes by DPP, running (m, l) per head, P = exp2(S - m).
+//       P is split into an fp16 head and an fp16 remainder (p = ph + pl to ~22 bits), so the
+//       fp16 MFMA does not cost precision in the weights.
+//   P   goes through 2 KiB of LDS to become the A operand (lane l: head l%16, tokens of group l/16).
+//   V   8 coalesced 16-byte loads per lane; the contraction now runs over tokens, which sit in a
+//       lane's own registers (8 tokens x 8 channels), so an in-lane 8x8 transpose of halves
+//       (32 v_perm_b32) yields the B operands: no LDS, no cross-lane traffic.  Token j of lane
+//       group g is block token 16*(j%2) + 4*(j/2) + g, so that each load instruction still
+//       fetches 4 adjacent rows and the two halves of a P word come from one lane.
+//       O[nb] (nb = 0..7) holds out[head 4rg + r][channel 8n + nb].
+
+constexpr int kGqaHeads = 16;            // query heads per workgroup (M of the MFMA)
+constexpr int kGqaBlockTokens = 32;      // tokens per wave iteration (K of the P.V MFMA)
+constexpr int kGqaKRow = 272;            // padded LDS row: 256 bytes + 16 so that 16 rows spread over all banks
+constexpr int kGqaKBytes = kGqaBlockTokens * kGqaKRow;
+constexpr int kGqaPBytes = kGqaHeads * kGqaBlockTokens * 2;
+constexpr int kGqaWaveBytes = kGqaKBytes + 2 * kGqaPBytes;
+
+typedef _Float16 hg_h8 __attribute__((ext_vector_type(8)));
+typedef float hg_f4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float row16_max(float x)
+{
+    x = fmaxf(x, dpp_move<0xB1>(x));
+    x = fmaxf(x, dpp_move<0x4E>(x));
+    x = fmaxf(x, dpp_move<0x141>(x));
+    x = fmaxf(x, dpp_move<0x140>(x));
+    return x;
+}
+
+// LDS traffic between the lanes of ONE wave: the hardware keeps a wave's LDS operations in
+// order; this only stops the compiler from moving accesses across the hand-over point.
+__device__ __forceinline__ void wave_lds_handover()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__global__ __launch_bounds__(kBlock) void hg_partial_gqa_kernel(const PartialArgs a)
+{
+    constexpr int D = 128;
+    constexpr int kMergeBytes = 4 * kGqaHeads * (D + 2) * 4;
+    constexpr int kSmemBytes = 4 * kGqaWaveBytes > kMergeBytes ? 4 * kGqaWaveBytes : kMergeBytes;
+    __shared__ __align__(16) char smem[kSmemBytes];
+
+    const int tile = blockIdx.x;
+    const int hk = blockIdx.y / a.n_chunks;
+    const int chunk = blockIdx.y - hk * a.n_chunks;
+    const int g0 = chunk * kGqaHeads;
+    const int nh = min(kGqaHeads, a.group - g0);
+    const int h0 = hk * a.group + g0;
+
+    const int r_idx = find_range(a.tab, tile);
+    const RangeEntry e = table_entry(a.tab, r_idx);
+    const int nt = table_entry(a.tab, r_idx + 1).tile_start - e.tile_start;
+    int t0, t1;
+    tile_bounds(e, nt, tile - e.tile_start, t0, t1);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, rg = lane >> 4;
+
+    char *kls = smem + wave * kGqaWaveBytes;
+    char *pls = kls + kGqaKBytes;
+
+    // Q as A operand: lane l holds head l%16, channels 8*(4kk + l/16)..+7 for kk = 0..3
+    hg_h8 qa[4];
+    {
+        const _Float16 *qrow = static_cast<const _Float16 *>(a.q) + ((int64_t)e.seq * a.n_q_heads + h0 + (n < nh ? n : 0)) * D;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            hg_u32x4 raw = *reinterpret_cast<const hg_u32x4 *>(qrow + 8 * (4 * kk + rg));
+            if (n >= nh) raw = hg_u32x4{0u, 0u, 0u, 0u};
+            qa[kk] = __builtin_bit_cast(hg_h8, raw);
+        }
+    }
+
+    float m[4], lsum[4];
+    hg_f4 o[8];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        m[r] = kNegBig;
+        lsum[r] = 0.f;
+    }
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) o[nb] = hg_f4{0.f, 0.f, 0.f, 0.f};
+
+    const int64_t slab = (int64_t)e.seq * a.stride_b + (int64_t)hk * a.stride_h;
+    const char *kbase = static_cast<const char *>(a.k) + slab * 2 + n * 16;
+    const char *vbase = static_cast<const char *>(a.v) + slab * 2 + n * 16;
+    const int64_t row_bytes = a.stride_t * 2;
+
+    for (int tb = t0 + wave * kGqaBlockTokens; tb < t1; tb += 4 * kGqaBlockTokens) {
+        hg_u32x4 kreg[8], vreg[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int tok = tb + 4 * i + rg;
+            tok = tok < t1 ? tok : t1 - 1;  // clamp: never read past the tile
+            kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(kbase + (int64_t)tok * row_bytes));
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            int tok = tb + 16 * (j & 1) + 4 * (j >> 1) + rg;
+            tok = tok < t1 ? tok : t1 - 1;
+            vreg[j] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(vbase + (int64_t)tok * row_bytes));
+        }
+
+        // K: registers -> LDS (row per token) -> B operands (token per lane)
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            *reinterpret_cast<hg_u32x4 *>(kls + (4 * i + rg) * kGqaKRow + n * 16) = kreg[i];
+        wave_lds_handover();
+        hg_f4 s[2];
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+            s[hf] = hg_f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                hg_u32x4 raw = *reinterpret_cast<const hg_u32x4 *>(kls + (16 * hf + n) * kGqaKRow + (4 * kk + rg) * 16);
+                s[hf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[kk], __builtin_bit_cast(hg_h8, raw), s[hf], 0, 0, 0);
+            }
+        }
+
+        // online softmax on S (lane: token n of each half, heads 4rg..4rg+3)
+        const bool ok0 = tb + n < t1, ok1 = tb + 16 + n < t1;
+        float alpha[4];
+        uint32_t ph[4], pl[4];  // packed (half 0, half 1) weights: fp16 head and fp16 remainder
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float s0 = ok0 ? s[0][r] * a.scale_log2 : -INFINITY;
+            const float s1 = ok1 ? s[1][r] * a.scale_log2 : -INFINITY;
+            const float mx = fmaxf(m[r], row16_max(fmaxf(s0, s1)));
+            alpha[r] = fast_exp2(m[r] - mx);
+            m[r] = mx;
+            const float p0 = fast_exp2(s0 - mx), p1 = fast_exp2(s1 - mx);
+            lsum[r] = lsum[r] * alpha[r] + (p0 + p1);
+            const _Float16 h0f = (_Float16)p0, h1f = (_Float16)p1;
+            const _Float16 l0f = (_Float16)(p0 - (float)h0f), l1f = (_Float16)(p1 - (float)h1f);
+            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+            ph[r] = __builtin_bit_cast(uint32_t, h2{h0f, h1f});
+            pl[r] = __builtin_bit_cast(uint32_t, h2{l0f, l1f});
+        }
+        // P -> LDS as [head][group g = n%4][j = 2*(n/4) + half], then read as A operand
+        {
+            const int col = (n & 3) * 16 + (n >> 2) * 4;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                *reinterpret_cast<uint32_t *>(pls + (4 * rg + r) * 64 + col) = ph[r];
+                *reinterpret_cast<uint32_t *>(pls + kGqaPBytes + (4 * rg + r) * 64 + col) = pl[r];
+            }
+        }
+        wave_lds_handover();
+        const hg_h8 pa_hi = __builtin_bit_cast(hg_h8, *reinterpret_cast<const hg_u32x4 *>(pls + n * 64 + rg * 16));
+        const hg_h8 pa_lo =
+            __builtin_bit_cast(hg_h8, *reinterpret_cast<const hg_u32x4 *>(pls + kGqaPBytes + n * 64 + rg * 16));
+
+        // V: in-lane transpose of halves, then O[nb] = alpha * O[nb] + P . V[:, channel 8n + nb]
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) {
+            const uint32_t sel = (nb & 1) ? 0x07060302u : 0x05040100u;
+            hg_u32x4 braw;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                braw[jj] = __builtin_amdgcn_perm(vreg[2 * jj + 1][nb >> 1], vreg[2 * jj][nb >> 1], sel);
+            const hg_h8 b = __builtin_bit_cast(hg_h8, braw);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[nb][r] *= alpha[r];
+            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
+            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
+        }
+        wave_lds_handover();  // the next iteration overwrites the K and P staging areas
+    }
+
+    // per-wave state -> LDS (staging areas are dead now), then merge the four waves
+    __syncthreads();
+    float(*sm)[kGqaHeads][D + 2] = reinterpret_cast<float(*)[kGqaHeads][D + 2]>(smem);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float lrow = row16_sum(lsum[r]);
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) sm[wave][4 * rg + r][8 * n + nb] = o[nb][r];
+        if (n == 0) {
+            sm[wave][4 * rg + r][D] = m[r];
+            sm[wave][4 * rg + r][D + 1] = lrow;
+        }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < kGqaHeads * D; idx += kBlock) {
+        const int g = idx / D, c = idx - g * D;
+        if (g >= nh) continue;
+        float mx = kNegBig;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mx = fmaxf(mx, sm[w][g][D]);
+        float lt = 0.f, ot = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float wt = fast_exp2(sm[w][g][D] - mx);
+            lt += wt * sm[w][g][D + 1];
+            ot += wt * sm[w][g][c];
+        }
+        const int64_t th = (int64_t)tile * a.n_q_heads + (h0 + g);
+        a.ws_o[th * D + c] = ot;
+        if (c == 0) {
+            a.ws_m[th] = mx;
+            a.ws_l[th] = lt;
+        }
+    }
+}
+
 // ---- tile statistics -> range triple (or normalised output) -----------------------------------
 
 constexpr int kReduceBlock = 512;
