@@ -72,7 +72,8 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
     ms, wall_ms = _time_steps(step, steps, warmup, torch)
 
     # second pass of the same K steps with event pairs around the streaming kernel alone
-    hg.hg_attn_profile_start(steps)
+    # (8 back-to-back launches per pair, so the cost of the event records is amortised)
+    hg.hg_attn_profile_start(steps, 8)
     for _ in range(steps):
         step()
     kernel_ms_total, launches = hg.hg_attn_profile_stop()
@@ -145,7 +146,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile-tokens", type=int, default=0)
     ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run a plain 1 GiB device copy three times (known traffic, to scale profiler counters)")
+                    help="also run the library's plain 1 GiB device copy three times (known traffic: the "
+                         "yardstick profiler byte counters are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path shards by (sequence, KV head) or by "
@@ -165,7 +167,7 @@ def main():
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            hg.hg_attn_calibration_copy(dst, src)
         torch.cuda.synchronize()
         del src, dst
 

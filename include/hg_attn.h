@@ -154,14 +154,23 @@ hg_status hg_attn_set_tile_tokens(int32_t tile_tokens);
 
 /*
  * Measurement aid: time the streaming kernel (the one that reads K and V) by itself.  After
- * hg_attn_profile_start(n), each of the next n hg_attn_partial / hg_attn_full calls records a
- * pair of HIP events on the caller's stream directly around that kernel's launch.
+ * hg_attn_profile_start(n, repeat), each of the next n hg_attn_partial / hg_attn_full calls
+ * records a pair of HIP events on the caller's stream directly around that kernel, which is
+ * launched `repeat` times back to back between the two events (it is idempotent), so that the
+ * fixed cost of recording events is spread over several launches; results are unchanged.
  * hg_attn_profile_stop waits for those events (the only call in this library that blocks),
- * returns the summed elapsed milliseconds and the number of launches timed, and switches the
- * mode off.  Process-wide; not thread-safe.
+ * returns the summed elapsed milliseconds and the number of kernel launches timed, and switches
+ * the mode off.  Process-wide; not thread-safe.
  */
-hg_status hg_attn_profile_start(int32_t max_launches);
+hg_status hg_attn_profile_start(int32_t max_calls, int32_t repeat);
 hg_status hg_attn_profile_stop(float *total_ms, int32_t *launches);
+
+/*
+ * Measurement aid: a plain device copy of `bytes` bytes (multiple of 16; dst, src DEVICE,
+ * 16-byte aligned, not overlapping).  Its HBM traffic is known exactly (bytes read, bytes
+ * written), which makes it the reference that profiler byte counters are scaled by.
+ */
+hg_status hg_attn_calibration_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

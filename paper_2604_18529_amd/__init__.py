@@ -13,6 +13,7 @@ _API = (
     "hg_attn_set_tile_tokens",
     "hg_attn_profile_start",
     "hg_attn_profile_stop",
+    "hg_attn_calibration_copy",
     "pack_ranges",
     "make_desc",
     "hg_strerror",

@@ -709,4 +709,11 @@ __global__ void hg_upload_ints_kernel(int32_t *dst, int count, const IntChunk ch
     if (i < count) dst[i] = chunk.e[i];
 }
 
+// Plain copy of known traffic (n bytes read, n bytes written): the yardstick that profiler byte
+// counters are scaled by.
+__global__ __launch_bounds__(256) void hg_calibration_copy_kernel(hg_u32x4 *dst, const hg_u32x4 *src, size_t n_vec)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 }  // namespace hg

@@ -76,12 +76,13 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_full.argtypes = [D, vp, vp, vp, sz, vp]
     lib.hg_attn_plan.argtypes = [D, R, i32, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_int64)]
     lib.hg_attn_set_tile_tokens.argtypes = [i32]
-    lib.hg_attn_profile_start.argtypes = [i32]
+    lib.hg_attn_profile_start.argtypes = [i32, i32]
+    lib.hg_attn_calibration_copy.argtypes = [vp, vp, sz, vp]
     lib.hg_attn_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
     for name in (
         "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_merge_workspace_size", "hg_attn_merge",
         "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_tile_tokens",
-        "hg_attn_profile_start", "hg_attn_profile_stop",
+        "hg_attn_profile_start", "hg_attn_profile_stop", "hg_attn_calibration_copy",
     ):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -177,8 +178,8 @@ def hg_attn_set_tile_tokens(tile_tokens: int) -> None:
     _check(load_library().hg_attn_set_tile_tokens(int(tile_tokens)), "hg_attn_set_tile_tokens")
 
 
-def hg_attn_profile_start(max_launches: int) -> None:
-    _check(load_library().hg_attn_profile_start(int(max_launches)), "hg_attn_profile_start")
+def hg_attn_profile_start(max_calls: int, repeat: int = 1) -> None:
+    _check(load_library().hg_attn_profile_start(int(max_calls), int(repeat)), "hg_attn_profile_start")
 
 
 def hg_attn_profile_stop() -> Tuple[float, int]:
@@ -186,6 +187,16 @@ def hg_attn_profile_stop() -> Tuple[float, int]:
     ms, n = ctypes.c_float(), ctypes.c_int32()
     _check(load_library().hg_attn_profile_stop(ctypes.byref(ms), ctypes.byref(n)), "hg_attn_profile_stop")
     return ms.value, n.value
+
+
+def hg_attn_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """Plain device copy of known traffic (profiler yardstick)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (dst.is_contiguous() and src.is_contiguous()):
+        raise ValueError("dst and src must be contiguous and of equal size")
+    with torch.cuda.device(src.device):
+        st = load_library().hg_attn_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_handle(stream))
+    _check(st, "hg_attn_calibration_copy")
 
 
 def hg_attn_partial_workspace_size(desc, packed) -> int:
