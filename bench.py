@@ -97,8 +97,8 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
         "kv_dtype": spec.dtype,
         "tokens_total": int(w.seq_lens.sum()),
         "partitions": R,
-        "tile_tokens": tile_tokens,
-        "n_tiles": n_tiles,
+        "span_tokens": tile_tokens,
+        "workgroups": n_tiles,
         "kv_bytes": kv_bytes,
         "us_per_layer": ms * 1e3,
         "gbps": kv_bytes / (ms * 1e-3) / 1e9,
@@ -199,7 +199,7 @@ def main():
         "dtype": "f32",  # fp16 K/V/q storage, fp32 products, sums and exponentials
         "data": "synthetic",
         "config": {k: head[k] for k in ("workload", "batch", "n_q_heads", "n_kv_heads", "head_dim", "kv_dtype",
-                                        "tokens_total", "partitions", "tile_tokens", "n_tiles", "kv_bytes")},
+                                        "tokens_total", "partitions", "span_tokens", "workgroups", "kv_bytes")},
         "roofline": {
             "bound": "hbm",
             "kernel": "hg_partial_kernel",

@@ -100,7 +100,7 @@ const char *hg_strerror(hg_status status);
  *   m, l     DEVICE [n_ranges][n_q_heads] fp32.   m is the true maximum of the scaled logits in
  *                   natural-log units; l and O are relative to that m.
  *   o        DEVICE [n_ranges][n_q_heads][head_dim] fp32.
- *   An empty range yields m = -inf, l = 0, O = 0.
+ *   An empty range yields m = -inf, l = 0, O = 0.  At most 2^31-1 tokens in all ranges together.
  *   workspace/ws_bytes  see hg_attn_partial_workspace_size (same desc and ranges).
  *
  * Merging the triples of ranges that tile [0, seq_lens[b]) exactly once reproduces hg_attn_full.
@@ -140,16 +140,18 @@ hg_status hg_attn_full(const hg_attn_desc *desc, float *out, float *lse_out, voi
                        void *stream);
 
 /*
- * Host-side planning, exposed for inspection and tests.  The token axis of every range is cut
- * into tiles (one workgroup each) so that long ranges fill the whole chip; tiles never cross a
- * range boundary.  Reports the tile length the library would use for this problem and the
- * number of tiles.  No device work.
+ * Host-side planning, exposed for inspection and tests.  The tokens of all ranges, repeated for
+ * every stream (KV head x chunk of query heads sharing it), form one linear work space that is
+ * cut into equal spans, one workgroup each, so that every workgroup streams the same number of
+ * bytes whatever the shape of the partition table.  Reports the span length in tokens and the
+ * number of workgroups the library would launch for this problem.  No device work.
  */
-hg_status hg_attn_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, int32_t *tile_tokens,
-                       int64_t *n_tiles);
+hg_status hg_attn_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, int32_t *span_tokens,
+                       int64_t *n_workgroups);
 
-/* Tuning knob: force the tile length in tokens (multiple of 64, 64..65536); 0 restores the
- * built-in choice.  Process-wide; not thread-safe against concurrent calls. */
+/* Tuning knob: force the span length in tokens (multiple of 64, 64..2^24); 0 restores the
+ * built-in choice (one workgroup per compute unit on long inputs).  Process-wide; not
+ * thread-safe against concurrent calls. */
 hg_status hg_attn_set_tile_tokens(int32_t tile_tokens);
 
 /*

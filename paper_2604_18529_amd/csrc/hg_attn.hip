@@ -28,14 +28,29 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
-    int32_t tile_tokens = 0;
-    int64_t n_tiles = 0;
+    WorkSplit ws{};
+    int64_t n_workgroups = 0;
+    int64_t n_slots = 0;              // segment records: n_workgroups + n_streams * n_ranges
     std::vector<RangeEntry> entries;  // n_ranges + 1 (sentinel)
-    int32_t gt = 1;                   // query heads of one KV head handled per workgroup
-    int32_t n_chunks = 1;
     // workspace sections (byte offsets)
     size_t off_m = 0, off_l = 0, off_o = 0, off_tab = 0, total = 0;
 };
+
+// Compute units of the current device (256 on MI355X); 256 when no device can be queried, so
+// that planning also works on a host without a GPU.
+int compute_units()
+{
+    static int cached = 0;
+    if (cached) return cached;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) {
+        cached = cus;
+        return cus;
+    }
+    (void)hipGetLastError();
+    return 256;
+}
 
 hg_status check_desc(const hg_attn_desc *d)
 {
@@ -83,46 +98,52 @@ int32_t pick_group_tile(const hg_attn_desc *d)
     return group;  // 1 or 2
 }
 
-// Tile length: long enough to amortise a workgroup's set-up and its (m, l, O) write-back,
-// short enough that the launch has a few thousand workgroups for 256 compute units.
-int32_t pick_tile_tokens(int64_t total_tokens, int64_t streams)
+// Positions per workgroup.  Long inputs get one workgroup (four waves) per compute unit, each
+// streaming an equal share: measured on MI355X, about 32 KiB of loads in flight per compute unit
+// from as few waves as possible gives the highest HBM read rate (more resident waves lose 4-5 %),
+// and the launch ends without a tail.  Short inputs get 64-token spans so that they still spread
+// over the chip.
+int32_t pick_span(int64_t total)
 {
     if (g_forced_tile_tokens) return g_forced_tile_tokens;
-    const int64_t target_blocks = 2048;
-    int64_t t = (total_tokens * streams + target_blocks - 1) / target_blocks;
+    const int64_t target = (int64_t)kWorkgroupsPerCu * compute_units();
+    int64_t t = (total + target - 1) / target;
     t = (t + 63) / 64 * 64;
     if (t < 64) t = 64;
-    if (t > 2048) t = 2048;
+    if (t > 0x40000000) t = 0x40000000;
     return (int32_t)t;
 }
 
 hg_status make_plan(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, Plan &p)
 {
     const int32_t group = d->n_q_heads / d->n_kv_heads;
-    p.gt = pick_group_tile(d);
-    p.n_chunks = (group + p.gt - 1) / p.gt;
-    if ((int64_t)d->n_kv_heads * p.n_chunks > 65535) return HG_ERR_SHAPE;
-    int64_t total_tokens = 0;
-    for (int32_t r = 0; r < n_ranges; ++r) total_tokens += ranges[r].end - ranges[r].begin;
-    p.tile_tokens = pick_tile_tokens(total_tokens, (int64_t)d->n_kv_heads * p.n_chunks);
+    p.ws.group = group;
+    p.ws.gt = pick_group_tile(d);
+    p.ws.n_chunks = (group + p.ws.gt - 1) / p.ws.gt;
+    p.ws.n_q_heads = d->n_q_heads;
+    const int64_t n_streams = (int64_t)d->n_kv_heads * p.ws.n_chunks;
     p.entries.resize((size_t)n_ranges + 1);
-    int64_t tiles = 0;
+    int64_t ltok = 0;
     for (int32_t r = 0; r < n_ranges; ++r) {
-        const int64_t len = ranges[r].end - ranges[r].begin;
-        p.entries[r] = RangeEntry{ranges[r].seq, ranges[r].begin, ranges[r].end, (int32_t)tiles};
-        tiles += (len + p.tile_tokens - 1) / p.tile_tokens;
-        if (tiles > 0x7fffffff) return HG_ERR_SHAPE;
+        p.entries[r] = RangeEntry{ranges[r].seq, ranges[r].begin, ranges[r].end, (int32_t)ltok};
+        ltok += ranges[r].end - ranges[r].begin;
+        if (ltok > 0x7fffffff) return HG_ERR_SHAPE;  // more than 2^31-1 tokens in one call
     }
-    p.entries[n_ranges] = RangeEntry{0, 0, 0, (int32_t)tiles};
-    p.n_tiles = tiles;
-    const size_t th = (size_t)tiles * (size_t)d->n_q_heads;
+    p.entries[n_ranges] = RangeEntry{0, 0, 0, (int32_t)ltok};
+    p.ws.ltok = (int32_t)ltok;
+    p.ws.total = n_streams * ltok;
+    p.ws.span = pick_span(p.ws.total);
+    p.n_workgroups = (p.ws.total + p.ws.span - 1) / p.ws.span;
+    if (p.n_workgroups > 0x7fffffff) return HG_ERR_SHAPE;
+    p.n_slots = p.ws.total ? p.n_workgroups + n_streams * n_ranges : 0;
+    const size_t recs = (size_t)p.n_slots * (size_t)p.ws.gt;
     size_t off = 0;
     p.off_m = off;
-    off += align_up(th * sizeof(float));
+    off += align_up(recs * sizeof(float));
     p.off_l = off;
-    off += align_up(th * sizeof(float));
+    off += align_up(recs * sizeof(float));
     p.off_o = off;
-    off += align_up(th * (size_t)d->head_dim * sizeof(float));
+    off += align_up(recs * (size_t)d->head_dim * sizeof(float));
     p.off_tab = off;
     if (n_ranges > kInlineRanges) off += align_up(p.entries.size() * sizeof(RangeEntry));
     p.total = off;
@@ -148,7 +169,7 @@ hg_status launch_status(const char *what)
 hg_status stage_table(const Plan &p, int32_t n_ranges, char *ws, hipStream_t stream, RangeTable &tab)
 {
     tab.n_ranges = n_ranges;
-    tab.n_tiles = (int32_t)p.n_tiles;
+    tab.pad = 0;
     tab.ext = nullptr;
     if (n_ranges <= kInlineRanges) {
         std::memcpy(tab.inl, p.entries.data(), p.entries.size() * sizeof(RangeEntry));
@@ -170,10 +191,10 @@ template <typename TR>
 void launch_partial_gt(const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
 {
     switch (gt) {
-    case 1: hipLaunchKernelGGL((hg_partial_kernel<TR, 1, 4>), grid, dim3(kBlock), 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((hg_partial_kernel<TR, 2, 4>), grid, dim3(kBlock), 0, stream, a); break;
-    case 4: hipLaunchKernelGGL((hg_partial_kernel<TR, 4, 2>), grid, dim3(kBlock), 0, stream, a); break;
-    default: hipLaunchKernelGGL((hg_partial_kernel<TR, 8, 2>), grid, dim3(kBlock), 0, stream, a); break;
+    case 1: hipLaunchKernelGGL((hg_partial_kernel<TR, 1, HG_VALU_U>), grid, dim3(kValuBlock), 0, stream, a); break;
+    case 2: hipLaunchKernelGGL((hg_partial_kernel<TR, 2, HG_VALU_U>), grid, dim3(kValuBlock), 0, stream, a); break;
+    case 4: hipLaunchKernelGGL((hg_partial_kernel<TR, 4, 2>), grid, dim3(kValuBlock), 0, stream, a); break;
+    default: hipLaunchKernelGGL((hg_partial_kernel<TR, 8, 2>), grid, dim3(kValuBlock), 0, stream, a); break;
     }
 }
 
@@ -216,15 +237,13 @@ hg_status run(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, i
     pa.stride_b = d->stride_b;
     pa.stride_h = d->stride_h;
     pa.stride_t = d->stride_t;
-    pa.n_q_heads = d->n_q_heads;
-    pa.group = d->n_q_heads / d->n_kv_heads;
-    pa.n_chunks = p.n_chunks;
+    pa.ws = p.ws;
     pa.scale_log2 = d->scale * kLog2e;
     pa.ws_m = reinterpret_cast<float *>(ws + p.off_m);
     pa.ws_l = reinterpret_cast<float *>(ws + p.off_l);
     pa.ws_o = reinterpret_cast<float *>(ws + p.off_o);
-    if (p.n_tiles > 0) {
-        dim3 grid((unsigned)p.n_tiles, (unsigned)(d->n_kv_heads * p.n_chunks));
+    if (p.n_workgroups > 0) {
+        dim3 grid((unsigned)p.n_workgroups);
         // In timing mode the kernel is launched g_prof_repeat times back to back between one pair
         // of events (it is idempotent: every launch writes the same tile statistics), so that the
         // fixed cost of the event records is spread over several launches.
@@ -233,9 +252,9 @@ hg_status run(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, i
         if (timed) (void)hipEventRecord(g_prof_events[2 * g_prof_used], stream);
         for (int rep = 0; rep < reps; ++rep) {
             if (use_gqa_kernel(d))
-                hipLaunchKernelGGL(hg_partial_gqa_kernel, grid, dim3(kBlock), 0, stream, pa);
+                hipLaunchKernelGGL(hg_partial_gqa_kernel, grid, dim3(kGqaBlock), 0, stream, pa);
             else
-                launch_partial(d, pa, p.gt, grid, stream);
+                launch_partial(d, pa, p.ws.gt, grid, stream);
         }
         if (timed) (void)hipEventRecord(g_prof_events[2 * g_prof_used++ + 1], stream);
         st = launch_status("partial kernel");
@@ -248,17 +267,17 @@ hg_status run(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, i
     ra.ws_m = pa.ws_m;
     ra.ws_l = pa.ws_l;
     ra.ws_o = pa.ws_o;
-    ra.n_q_heads = d->n_q_heads;
+    ra.ws = p.ws;
     ra.normalise = normalise;
     ra.m_out = m;
     ra.l_out = l;
     ra.o_out = o;
     dim3 rgrid((unsigned)n_ranges, (unsigned)d->n_q_heads);
     if (d->head_dim == 128)
-        hipLaunchKernelGGL(hg_tile_reduce_kernel<128>, rgrid, dim3(kReduceBlock), 0, stream, ra);
+        hipLaunchKernelGGL(hg_segment_reduce_kernel<128>, rgrid, dim3(kReduceBlock), 0, stream, ra);
     else
-        hipLaunchKernelGGL(hg_tile_reduce_kernel<64>, rgrid, dim3(kReduceBlock), 0, stream, ra);
-    return launch_status("tile reduce kernel");
+        hipLaunchKernelGGL(hg_segment_reduce_kernel<64>, rgrid, dim3(kReduceBlock), 0, stream, ra);
+    return launch_status("segment reduce kernel");
 }
 
 hg_status full_ranges(const hg_attn_desc *d, std::vector<hg_range> &ranges)
@@ -295,7 +314,7 @@ const char *hg_strerror(hg_status status)
 
 hg_status hg_attn_set_tile_tokens(int32_t tile_tokens)
 {
-    if (tile_tokens != 0 && (tile_tokens < 64 || tile_tokens > 65536 || tile_tokens % 64)) return HG_ERR_SHAPE;
+    if (tile_tokens != 0 && (tile_tokens < 64 || tile_tokens > (1 << 24) || tile_tokens % 64)) return HG_ERR_SHAPE;
     g_forced_tile_tokens = tile_tokens;
     return HG_OK;
 }
@@ -345,8 +364,8 @@ hg_status hg_attn_profile_stop(float *total_ms, int32_t *launches)
     return st;
 }
 
-hg_status hg_attn_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, int32_t *tile_tokens,
-                       int64_t *n_tiles)
+hg_status hg_attn_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, int32_t *span_tokens,
+                       int64_t *n_workgroups)
 {
     hg_status st = check_desc(desc);
     if (st != HG_OK) return st;
@@ -355,8 +374,8 @@ hg_status hg_attn_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t
     Plan p;
     st = make_plan(desc, ranges, n_ranges, p);
     if (st != HG_OK) return st;
-    if (tile_tokens) *tile_tokens = p.tile_tokens;
-    if (n_tiles) *n_tiles = p.n_tiles;
+    if (span_tokens) *span_tokens = p.ws.span;
+    if (n_workgroups) *n_workgroups = p.n_workgroups;
     return HG_OK;
 }
 

@@ -1,13 +1,22 @@
 // Device code of the partitioned decode-attention library (gfx950, wave64).
 //
 // Three kernels:
-//   hg_partial_kernel      streams the K and V rows of one token tile once and folds them into
+//   hg_partial_kernel      streams the K and V rows of a span of tokens once and folds them into
 //                          softmax statistics (m, l, O) per query head (paper Section 4.2: the
 //                          per-token logit stage, run here per positional range).
-//   hg_tile_reduce_kernel  merges the tile statistics of a range into the range's triple, or,
+//   hg_segment_reduce_kernel  merges the segment records of a range into the range's triple, or,
 //                          for the unsplit path, into the normalised output.
 //   hg_merge_kernel        exact recombination of range triples (Section 4.2.3, Token
 //                          Concatenator, in statistics form).
+//
+// Work distribution.  The tokens of all ranges, repeated for every stream (KV head x chunk of
+// query heads), form one linear space of `total` positions: position p = s * ltok + x, where
+// x runs over the concatenated ranges.  Workgroup w owns positions [w * span, (w+1) * span), so
+// every workgroup streams the same number of bytes whatever the shape of the partition table,
+// and the launch is sized to the chip (one workgroup per compute unit for long inputs).  A
+// workgroup's span is cut into segments at range and stream boundaries; each segment yields one
+// (m, l, O) record in slot  w + s * n_ranges + r  (strictly increasing along the linear order,
+// hence unique), and the records of a (range, stream) pair occupy a contiguous run of slots.
 //
 // Lane layout of the streaming kernel.  One K or V row (head_dim elements, 128..512 bytes) is
 // spread over the 16 lanes of a DPP row, each lane holding 8..32 contiguous bytes per 256-byte
@@ -15,7 +24,7 @@
 // lane keeps the matching channels of q (pre-multiplied by scale*log2 e) and of the O
 // accumulator, so P.V is lane-local and the only cross-lane work is the 16-lane sum of the dot
 // product (four DPP adds).  The four 16-lane groups of a wave and the four waves of a
-// workgroup run independent online-softmax streams that are merged once per tile.
+// workgroup run independent online-softmax streams that are merged once per segment.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -27,40 +36,69 @@ constexpr int kInlineRanges = 64;   // range-table entries carried inside the ke
 constexpr int kInlineGroups = 256;  // CSR offsets carried inside the merge kernel's arguments
 constexpr int kUploadRanges = 128;  // entries per table-upload launch
 constexpr int kUploadInts = 512;
-constexpr int kBlock = 256;         // threads per streaming workgroup (4 waves)
+// Waves per streaming workgroup and workgroups per compute unit (tuning constants).
+#ifndef HG_VALU_WAVES
+#define HG_VALU_WAVES 4
+#endif
+#ifndef HG_GQA_WAVES
+#define HG_GQA_WAVES 4
+#endif
+#ifndef HG_VALU_U
+#define HG_VALU_U 4  // rows in flight per 16-lane group (kernels with 1 or 2 heads per stream)
+#endif
+#ifndef HG_WG_PER_CU
+#define HG_WG_PER_CU 1
+#endif
+constexpr int kValuWaves = HG_VALU_WAVES;
+constexpr int kGqaWaves = HG_GQA_WAVES;
+constexpr int kValuBlock = 64 * kValuWaves;
+constexpr int kGqaBlock = 64 * kGqaWaves;
+constexpr int kWorkgroupsPerCu = HG_WG_PER_CU;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 // "no token seen yet" marker for running maxima (log2 domain).  Finite, so that
 // exp2(marker - marker) = 1 multiplies an all-zero state instead of producing NaN.
 constexpr float kNegBig = -3.0e38f;
 
+// pre = number of tokens in the ranges before this one (prefix sum of the range lengths).
 struct RangeEntry {
-    int32_t seq, begin, end, tile_start;
+    int32_t seq, begin, end, pre;
 };
 
 // The range table travels by value in the kernel arguments when it is small; otherwise `ext`
-// points at a device copy.  Entry n_ranges is a sentinel whose tile_start is n_tiles.
+// points at a device copy.  Entry n_ranges is a sentinel whose pre is ltok.
 struct RangeTable {
     const RangeEntry *ext;
     int32_t n_ranges;
-    int32_t n_tiles;
+    int32_t pad;
     RangeEntry inl[kInlineRanges + 1];
+};
+
+// How the linear work space is laid out and cut (shared by the streaming and reduce kernels).
+struct WorkSplit {
+    int64_t total;    // n_streams * ltok
+    int32_t ltok;     // tokens in all ranges together
+    int32_t span;     // positions per workgroup
+    int32_t group;    // query heads per KV head
+    int32_t gt;       // query heads per stream (chunk of a group)
+    int32_t n_chunks; // streams per KV head
+    int32_t n_q_heads;
 };
 
 struct PartialArgs {
     const void *q, *k, *v;
     int64_t stride_b, stride_h, stride_t;  // elements
-    int32_t n_q_heads, group, n_chunks;    // group = query heads per KV head; chunks of GT heads
     float scale_log2;                      // scale * log2(e)
-    float *ws_m, *ws_l, *ws_o;             // tile statistics [n_tiles][Hq], [n_tiles][Hq][D]; m in log2 units
+    float *ws_m, *ws_l, *ws_o;             // segment records [slot][gt], [slot][gt][D]; m in log2 units
+    WorkSplit ws;
     RangeTable tab;
 };
 
 struct ReduceArgs {
     const float *ws_m, *ws_l, *ws_o;
-    int32_t n_q_heads;
     int32_t normalise;  // 0: write the range triple (m, l, o); 1: write out = O/L and lse
     float *m_out, *l_out, *o_out;  // [n_ranges][Hq](..[D])  or  out/lse when normalise
+    WorkSplit ws;
     RangeTable tab;
 };
 
@@ -109,13 +147,14 @@ __device__ __forceinline__ RangeEntry table_entry(const RangeTable &tab, int i)
     return tab.ext ? tab.ext[i] : tab.inl[i];
 }
 
-// Largest r with tile_start[r] <= tile; it owns the tile because empty ranges own no tiles.
-__device__ __forceinline__ int find_range(const RangeTable &tab, int tile)
+// Largest r with pre[r] <= x (0 <= x < ltok); it contains x because empty ranges share their
+// successor's prefix.
+__device__ __forceinline__ int find_range(const RangeTable &tab, int x)
 {
-    int lo = 0, hi = tab.n_ranges;  // invariant: tile_start[lo] <= tile < tile_start[hi]
+    int lo = 0, hi = tab.n_ranges;  // invariant: pre[lo] <= x < pre[hi]
     while (hi - lo > 1) {
         int mid = (lo + hi) >> 1;
-        if (table_entry(tab, mid).tile_start <= tile)
+        if (table_entry(tab, mid).pre <= x)
             lo = mid;
         else
             hi = mid;
@@ -123,17 +162,35 @@ __device__ __forceinline__ int find_range(const RangeTable &tab, int tile)
     return lo;
 }
 
-// Token sub-range of tile j (0-based inside its range).  Tiles of a range have equal length,
-// rounded up to 64 tokens, except the last.
-__device__ __forceinline__ void tile_bounds(const RangeEntry &e, int n_tiles_in_range, int j, int &t0, int &t1)
+// Walk the segments of this workgroup's span.  f(stream, seq, t0, t1, slot) is called by every
+// thread of the workgroup, in the same order (the control flow is uniform).
+template <typename F>
+__device__ __forceinline__ void for_each_segment(const WorkSplit &ws, const RangeTable &tab, F &&f)
 {
-    int len = e.end - e.begin;
-    int per = (len + n_tiles_in_range - 1) / n_tiles_in_range;
-    per = (per + 63) & ~63;
-    int64_t a = (int64_t)e.begin + (int64_t)j * per;
-    int64_t b = a + per;
-    t0 = (int)(a < e.end ? a : e.end);
-    t1 = (int)(b < e.end ? b : e.end);
+    int64_t p = (int64_t)blockIdx.x * ws.span;
+    const int64_t p_end = p + ws.span < ws.total ? p + ws.span : ws.total;
+    int s = (int)(p / ws.ltok);
+    int x = (int)(p - (int64_t)s * ws.ltok);
+    int r = find_range(tab, x);
+    while (p < p_end) {
+        const RangeEntry e = table_entry(tab, r);
+        const int r_end = table_entry(tab, r + 1).pre;
+        const int64_t left = p_end - p;
+        const int len = left < (int64_t)(r_end - x) ? (int)left : r_end - x;
+        const int t0 = e.begin + (x - e.pre);
+        f(s, e.seq, t0, t0 + len, (int64_t)blockIdx.x + (int64_t)s * tab.n_ranges + r);
+        p += len;
+        x += len;
+        if (x == r_end) {
+            if (x == ws.ltok) {  // next stream, first non-empty range
+                ++s;
+                x = 0;
+                r = find_range(tab, 0);
+            } else {
+                r = find_range(tab, x);
+            }
+        }
+    }
 }
 
 // ---- storage traits ----------------------------------------------------------------------------
@@ -174,7 +231,7 @@ struct Traits {
     // element offset inside a row of lane `sub`'s vector j
     __device__ static __forceinline__ int vec_offset(int sub, int j) { return j * SEG + sub * EPV; }
 
-    // STREAM = true for K and V (read once), false for q (re-read by every tile of the head)
+    // STREAM = true for K and V (read once), false for q (re-read by every workgroup of the head)
     template <bool STREAM>
     __device__ static __forceinline__ Raw load(const char *row_ptr, int sub, int j)
     {
@@ -219,35 +276,29 @@ __device__ __forceinline__ void merge_state(float &m, float &l, float *acc, floa
 }
 
 template <typename TR, int GT, int U>
-__global__ __launch_bounds__(kBlock) void hg_partial_kernel(const PartialArgs a)
+__global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArgs a)
 {
     constexpr int D = TR::D, EPL = TR::EPL, NV = TR::NV, EPV = TR::EPV, ES = TR::ES;
     constexpr int CH = 4 * U;  // tokens one wave takes per iteration
 
-    __shared__ float sm[4][GT][D + 2];
-
-    const int tile = blockIdx.x;
-    const int hk = blockIdx.y / a.n_chunks;
-    const int chunk = blockIdx.y - hk * a.n_chunks;
-    const int g0 = chunk * GT;                              // first head of this chunk inside its group
-    const int nh = min(GT, a.group - g0);                   // valid heads in this chunk
-    const int h0 = hk * a.group + g0;                       // first query head
-
-    const int r = find_range(a.tab, tile);
-    const RangeEntry e = table_entry(a.tab, r);
-    const int nt = table_entry(a.tab, r + 1).tile_start - e.tile_start;
-    int t0, t1;
-    tile_bounds(e, nt, tile - e.tile_start, t0, t1);
+    __shared__ float sm[kValuWaves][GT][D + 2];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane & 15, grp = lane >> 4;
+
+    for_each_segment(a.ws, a.tab, [&](int stream, int seq, int t0, int t1, int64_t slot) __attribute__((always_inline)) {
+    const int hk = stream / a.ws.n_chunks;
+    const int chunk = stream - hk * a.ws.n_chunks;
+    const int g0 = chunk * GT;                              // first head of this chunk inside its group
+    const int nh = min(GT, a.ws.group - g0);                // valid heads in this chunk
+    const int h0 = hk * a.ws.group + g0;                    // first query head
 
     // q fragments, scaled into the log2 domain
     float qf[GT][EPL];
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
         const int h = h0 + (g < nh ? g : 0);
-        const char *qrow = static_cast<const char *>(a.q) + ((int64_t)e.seq * a.n_q_heads + h) * (int64_t)(D * ES);
+        const char *qrow = static_cast<const char *>(a.q) + ((int64_t)seq * a.ws.n_q_heads + h) * (int64_t)(D * ES);
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
             typename TR::Raw raw = TR::template load<false>(qrow, sub, j);
@@ -266,19 +317,19 @@ __global__ __launch_bounds__(kBlock) void hg_partial_kernel(const PartialArgs a)
         for (int i = 0; i < EPL; ++i) acc[g][i] = 0.f;
     }
 
-    const int64_t slab = (int64_t)e.seq * a.stride_b + (int64_t)hk * a.stride_h;
+    const int64_t slab = (int64_t)seq * a.stride_b + (int64_t)hk * a.stride_h;
     const char *kbase = static_cast<const char *>(a.k) + slab * ES;
     const char *vbase = static_cast<const char *>(a.v) + slab * ES;
     const int64_t row_bytes = a.stride_t * ES;
 
-    for (int tb = t0 + wave * CH; tb < t1; tb += 4 * CH) {
+    for (int tb = t0 + wave * CH; tb < t1; tb += kValuWaves * CH) {
         typename TR::Raw kraw[U][NV], vraw[U][NV];
         bool valid[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int tok = tb + 4 * u + grp;
             valid[u] = tok < t1;
-            const int64_t off = (int64_t)(valid[u] ? tok : t1 - 1) * row_bytes;  // clamp: never read past the tile
+            const int64_t off = (int64_t)(valid[u] ? tok : t1 - 1) * row_bytes;  // clamp: never read past the segment
 #pragma unroll
             for (int j = 0; j < NV; ++j) kraw[u][j] = TR::template load<true>(kbase + off, sub, j);
 #pragma unroll
@@ -359,26 +410,28 @@ __global__ __launch_bounds__(kBlock) void hg_partial_kernel(const PartialArgs a)
     __syncthreads();
 
     // merge the four waves; one thread per (head, channel)
-    for (int idx = threadIdx.x; idx < GT * D; idx += kBlock) {
+    for (int idx = threadIdx.x; idx < GT * D; idx += kValuBlock) {
         const int g = idx / D, c = idx - g * D;
         if (g >= nh) continue;
         float mx = kNegBig;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) mx = fmaxf(mx, sm[w][g][D]);
+        for (int w = 0; w < kValuWaves; ++w) mx = fmaxf(mx, sm[w][g][D]);
         float lt = 0.f, ot = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < kValuWaves; ++w) {
             const float wt = fast_exp2(sm[w][g][D] - mx);
             lt += wt * sm[w][g][D + 1];
             ot += wt * sm[w][g][c];
         }
-        const int64_t th = (int64_t)tile * a.n_q_heads + (h0 + g);
+        const int64_t th = slot * GT + g;
         a.ws_o[th * D + c] = ot;
         if (c == 0) {
             a.ws_m[th] = mx;
             a.ws_l[th] = lt;
         }
     }
+    __syncthreads();  // the next segment reuses sm
+    });
 }
 
 // ---- streaming kernel for grouped-query attention (fp16, head_dim 128) on the matrix cores -----
@@ -433,25 +486,12 @@ __device__ __forceinline__ void wave_lds_handover()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__global__ __launch_bounds__(kBlock) void hg_partial_gqa_kernel(const PartialArgs a)
+__global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_gqa_kernel(const PartialArgs a)
 {
     constexpr int D = 128;
-    constexpr int kMergeBytes = 4 * kGqaHeads * (D + 2) * 4;
-    constexpr int kSmemBytes = 4 * kGqaWaveBytes > kMergeBytes ? 4 * kGqaWaveBytes : kMergeBytes;
+    constexpr int kMergeBytes = kGqaWaves * kGqaHeads * (D + 2) * 4;
+    constexpr int kSmemBytes = kGqaWaves * kGqaWaveBytes > kMergeBytes ? kGqaWaves * kGqaWaveBytes : kMergeBytes;
     __shared__ __align__(16) char smem[kSmemBytes];
-
-    const int tile = blockIdx.x;
-    const int hk = blockIdx.y / a.n_chunks;
-    const int chunk = blockIdx.y - hk * a.n_chunks;
-    const int g0 = chunk * kGqaHeads;
-    const int nh = min(kGqaHeads, a.group - g0);
-    const int h0 = hk * a.group + g0;
-
-    const int r_idx = find_range(a.tab, tile);
-    const RangeEntry e = table_entry(a.tab, r_idx);
-    const int nt = table_entry(a.tab, r_idx + 1).tile_start - e.tile_start;
-    int t0, t1;
-    tile_bounds(e, nt, tile - e.tile_start, t0, t1);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, rg = lane >> 4;
@@ -459,10 +499,17 @@ __global__ __launch_bounds__(kBlock) void hg_partial_gqa_kernel(const PartialArg
     char *kls = smem + wave * kGqaWaveBytes;
     char *pls = kls + kGqaKBytes;
 
+    for_each_segment(a.ws, a.tab, [&](int stream, int seq, int t0, int t1, int64_t slot) __attribute__((always_inline)) {
+    const int hk = stream / a.ws.n_chunks;
+    const int chunk = stream - hk * a.ws.n_chunks;
+    const int g0 = chunk * kGqaHeads;
+    const int nh = min(kGqaHeads, a.ws.group - g0);
+    const int h0 = hk * a.ws.group + g0;
+
     // Q as A operand: lane l holds head l%16, channels 8*(4kk + l/16)..+7 for kk = 0..3
     hg_h8 qa[4];
     {
-        const _Float16 *qrow = static_cast<const _Float16 *>(a.q) + ((int64_t)e.seq * a.n_q_heads + h0 + (n < nh ? n : 0)) * D;
+        const _Float16 *qrow = static_cast<const _Float16 *>(a.q) + ((int64_t)seq * a.ws.n_q_heads + h0 + (n < nh ? n : 0)) * D;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             hg_u32x4 raw = *reinterpret_cast<const hg_u32x4 *>(qrow + 8 * (4 * kk + rg));
@@ -481,31 +528,39 @@ __global__ __launch_bounds__(kBlock) void hg_partial_gqa_kernel(const PartialArg
 #pragma unroll
     for (int nb = 0; nb < 8; ++nb) o[nb] = hg_f4{0.f, 0.f, 0.f, 0.f};
 
-    const int64_t slab = (int64_t)e.seq * a.stride_b + (int64_t)hk * a.stride_h;
+    const int64_t slab = (int64_t)seq * a.stride_b + (int64_t)hk * a.stride_h;
     const char *kbase = static_cast<const char *>(a.k) + slab * 2 + n * 16;
     const char *vbase = static_cast<const char *>(a.v) + slab * 2 + n * 16;
     const int64_t row_bytes = a.stride_t * 2;
 
-    for (int tb = t0 + wave * kGqaBlockTokens; tb < t1; tb += 4 * kGqaBlockTokens) {
-        hg_u32x4 kreg[8], vreg[8];
+    // The 8 K-row loads and the 8 V-row loads of one 32-token block (8 KiB each per wave).
+    auto load_k = [&](int tb, hg_u32x4(&kreg)[8]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             int tok = tb + 4 * i + rg;
-            tok = tok < t1 ? tok : t1 - 1;  // clamp: never read past the tile
+            tok = tok < t1 ? tok : t1 - 1;  // clamp: never read past the segment
             kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(kbase + (int64_t)tok * row_bytes));
         }
+    };
+    auto load_v = [&](int tb, hg_u32x4(&vreg)[8]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             int tok = tb + 16 * (j & 1) + 4 * (j >> 1) + rg;
             tok = tok < t1 ? tok : t1 - 1;
             vreg[j] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(vbase + (int64_t)tok * row_bytes));
         }
+    };
 
+    // One block.  Software pipeline with a single register buffer: the K rows of the next block
+    // are requested as soon as this block's K sits in LDS, its V rows as soon as this block's V
+    // has been consumed, so a wave always has 8-16 KiB in flight while it computes.
+    auto compute_block = [&](int tb, int tb_next, hg_u32x4(&kreg)[8], hg_u32x4(&vreg)[8]) __attribute__((always_inline)) {
         // K: registers -> LDS (row per token) -> B operands (token per lane)
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             *reinterpret_cast<hg_u32x4 *>(kls + (4 * i + rg) * kGqaKRow + n * 16) = kreg[i];
         wave_lds_handover();
+        if (tb_next < t1) load_k(tb_next, kreg);
         hg_f4 s[2];
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {
@@ -564,7 +619,22 @@ __global__ __launch_bounds__(kBlock) void hg_partial_gqa_kernel(const PartialArg
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
         }
-        wave_lds_handover();  // the next iteration overwrites the K and P staging areas
+        if (tb_next < t1) load_v(tb_next, vreg);
+        wave_lds_handover();  // the next block overwrites the K and P staging areas
+    };
+
+    {
+        constexpr int kStride = kGqaWaves * kGqaBlockTokens;
+        hg_u32x4 kreg[8], vreg[8];
+        int tb = t0 + wave * kGqaBlockTokens;
+        if (tb < t1) {
+            load_k(tb, kreg);
+            load_v(tb, vreg);
+        }
+        while (tb < t1) {
+            compute_block(tb, tb + kStride, kreg, vreg);
+            tb += kStride;
+        }
     }
 
     // per-wave state -> LDS (staging areas are dead now), then merge the four waves
@@ -581,37 +651,39 @@ __global__ __launch_bounds__(kBlock) void hg_partial_gqa_kernel(const PartialArg
         }
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < kGqaHeads * D; idx += kBlock) {
+    for (int idx = threadIdx.x; idx < kGqaHeads * D; idx += kGqaBlock) {
         const int g = idx / D, c = idx - g * D;
         if (g >= nh) continue;
         float mx = kNegBig;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) mx = fmaxf(mx, sm[w][g][D]);
+        for (int w = 0; w < kGqaWaves; ++w) mx = fmaxf(mx, sm[w][g][D]);
         float lt = 0.f, ot = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < kGqaWaves; ++w) {
             const float wt = fast_exp2(sm[w][g][D] - mx);
             lt += wt * sm[w][g][D + 1];
             ot += wt * sm[w][g][c];
         }
-        const int64_t th = (int64_t)tile * a.n_q_heads + (h0 + g);
+        const int64_t th = slot * kGqaHeads + g;
         a.ws_o[th * D + c] = ot;
         if (c == 0) {
             a.ws_m[th] = mx;
             a.ws_l[th] = lt;
         }
     }
+    __syncthreads();  // the next segment reuses the staging areas
+    });
 }
 
-// ---- tile statistics -> range triple (or normalised output) -----------------------------------
+// ---- segment records -> range triple (or normalised output) -----------------------------------
 
 constexpr int kReduceBlock = 512;
 
-// One workgroup per (range, query head).  The tiles of the range are dealt round-robin to
-// kReduceBlock / D slices of D threads (one thread per channel), so that a range of a million
-// tokens (a thousand tiles) is not one long chain of dependent loads.
+// One workgroup per (range, query head).  The segment records of the range are dealt round-robin
+// to kReduceBlock / D slices of D threads (one thread per channel), so that a range cut into
+// hundreds of segments is not one long chain of dependent loads.
 template <int D>
-__global__ __launch_bounds__(kReduceBlock) void hg_tile_reduce_kernel(const ReduceArgs a)
+__global__ __launch_bounds__(kReduceBlock) void hg_segment_reduce_kernel(const ReduceArgs a)
 {
     constexpr int S = kReduceBlock / D;
     constexpr int NW = kReduceBlock / 64;
@@ -621,11 +693,20 @@ __global__ __launch_bounds__(kReduceBlock) void hg_tile_reduce_kernel(const Redu
 
     const int r = blockIdx.x, h = blockIdx.y;
     const int c = threadIdx.x % D, sl = threadIdx.x / D;
-    const int ts = table_entry(a.tab, r).tile_start;
-    const int te = table_entry(a.tab, r + 1).tile_start;
+
+    // the records of (range r, stream of head h) sit in slots w + stream * n_ranges + r for the
+    // workgroups w whose span overlaps the pair's positions [p0, p1)
+    const int hk = h / a.ws.group, gi = h - hk * a.ws.group;
+    const int chunk = gi / a.ws.gt, gl = gi - chunk * a.ws.gt;
+    const int stream = hk * a.ws.n_chunks + chunk;
+    const int pre0 = table_entry(a.tab, r).pre, pre1 = table_entry(a.tab, r + 1).pre;
+    const int64_t p0 = (int64_t)stream * a.ws.ltok + pre0, p1 = (int64_t)stream * a.ws.ltok + pre1;
+    const int64_t w0 = pre1 > pre0 ? p0 / a.ws.span : 0;
+    const int n_rec = pre1 > pre0 ? (int)((p1 - 1) / a.ws.span - w0) + 1 : 0;
+    const int64_t rec0 = (w0 + (int64_t)stream * a.tab.n_ranges + r) * a.ws.gt + gl;  // record i at rec0 + i * gt
 
     float mx = kNegBig;
-    for (int t = ts + (int)threadIdx.x; t < te; t += kReduceBlock) mx = fmaxf(mx, a.ws_m[(int64_t)t * a.n_q_heads + h]);
+    for (int i = (int)threadIdx.x; i < n_rec; i += kReduceBlock) mx = fmaxf(mx, a.ws_m[rec0 + (int64_t)i * a.ws.gt]);
 #pragma unroll
     for (int step = 32; step >= 1; step >>= 1) mx = fmaxf(mx, __shfl_xor(mx, step, 64));
     if ((threadIdx.x & 63) == 0) s_max[threadIdx.x >> 6] = mx;
@@ -635,8 +716,8 @@ __global__ __launch_bounds__(kReduceBlock) void hg_tile_reduce_kernel(const Redu
 
     float lt = 0.f, ot = 0.f;
 #pragma unroll 4
-    for (int t = ts + sl; t < te; t += S) {
-        const int64_t th = (int64_t)t * a.n_q_heads + h;
+    for (int i = sl; i < n_rec; i += S) {
+        const int64_t th = rec0 + (int64_t)i * a.ws.gt;
         const float wt = fast_exp2(a.ws_m[th] - mx);
         lt += wt * a.ws_l[th];
         ot += wt * a.ws_o[th * D + c];
@@ -653,7 +734,7 @@ __global__ __launch_bounds__(kReduceBlock) void hg_tile_reduce_kernel(const Redu
         ot += s_o[i][c];
     }
 
-    const int64_t rh = (int64_t)r * a.n_q_heads + h;
+    const int64_t rh = (int64_t)r * a.ws.n_q_heads + h;
     const bool empty = !(lt > 0.f);
     if (a.normalise) {
         a.o_out[rh * D + c] = empty ? 0.f : ot / lt;

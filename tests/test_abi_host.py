@@ -2,7 +2,7 @@
 
 The library must load, export every function the header declares, reject malformed arguments
 with the documented status before anything is enqueued, and plan tiles that cover every range
-exactly.  Pointers handed over here are fake non-NULL addresses: only calls that fail validation
+exactly once.  Pointers handed over here are fake non-NULL addresses: only calls that fail validation
 (or that are host-only by contract) are made, so nothing is ever dereferenced on a device.
 """
 import ctypes
@@ -108,28 +108,35 @@ def _plan(lib, desc, ranges):
     return tile.value, n.value
 
 
-def test_tile_plan_covers_ranges(lib):
+def test_span_plan_covers_the_work(lib):
+    """Equal spans over the linear work space: streams x tokens-in-all-ranges positions."""
     try:
         seq = [5000, 70, 0, 1 << 20]
         ranges = [(0, 0, 5000), (0, 17, 17), (1, 3, 70), (3, 0, 1 << 20), (3, 1000, 1001), (0, 4999, 5000)]
-        for forced in (0, 64, 128, 1024, 4096):
+        ltok = sum(e - b for _, b, e in ranges)
+        streams = 2  # hkv = 2, both query heads of a KV head travel together
+        for forced in (0, 64, 128, 1024, 4096, 1 << 20):
             assert lib.hg_attn_set_tile_tokens(forced) == 0
-            tile, n = _plan(lib, _desc(seq), ranges)
-            assert tile % 64 == 0 and 64 <= tile
+            span, n = _plan(lib, _desc(seq), ranges)
+            assert span % 64 == 0 and 64 <= span
             if forced:
-                assert tile == forced
-            want = sum((e - b + tile - 1) // tile for _, b, e in ranges)
-            assert n == want
-        for bad in (63, 100, -64, 1 << 20):
+                assert span == forced
+            else:
+                assert n <= 256  # one workgroup per compute unit (256 assumed without a GPU)
+            assert n == (streams * ltok + span - 1) // span
+        for bad in (63, 100, -64, (1 << 24) + 64):
             assert lib.hg_attn_set_tile_tokens(bad) == -2
-        # workspace grows with tiles * heads * (d + 2) floats
+        # workspace holds one record of (d + 2) floats per head for every possible segment
         lib.hg_attn_set_tile_tokens(64)
         d = _desc(seq)
         sz = ctypes.c_size_t()
         packed = B.pack_ranges(ranges)
         assert lib.hg_attn_partial_workspace_size(ctypes.byref(d), packed, len(ranges), ctypes.byref(sz)) == 0
-        tile, n = _plan(lib, d, ranges)
-        assert sz.value >= n * 4 * (128 + 2) * 4
+        span, n = _plan(lib, d, ranges)
+        assert sz.value >= (n + streams * len(ranges)) * 2 * (128 + 2) * 4
+        # nothing to stream: no workgroups, and only empty ranges still plan fine
+        span, n = _plan(lib, _desc(seq), [(0, 5, 5), (2, 0, 0)])
+        assert n == 0
     finally:
         lib.hg_attn_set_tile_tokens(0)
 
