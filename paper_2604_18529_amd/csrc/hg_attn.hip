@@ -103,10 +103,10 @@ int32_t pick_group_tile(const hg_attn_desc *d)
 // from as few waves as possible gives the highest HBM read rate (more resident waves lose 4-5 %),
 // and the launch ends without a tail.  Short inputs get 64-token spans so that they still spread
 // over the chip.
-int32_t pick_span(int64_t total)
+int32_t pick_span(int64_t total, bool gqa)
 {
     if (g_forced_tile_tokens) return g_forced_tile_tokens;
-    const int64_t target = (int64_t)kWorkgroupsPerCu * compute_units();
+    const int64_t target = (int64_t)(gqa ? kGqaWorkgroupsPerCu : kValuWorkgroupsPerCu) * compute_units();
     int64_t t = (total + target - 1) / target;
     t = (t + 63) / 64 * 64;
     if (t < 64) t = 64;
@@ -132,7 +132,7 @@ hg_status make_plan(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ran
     p.entries[n_ranges] = RangeEntry{0, 0, 0, (int32_t)ltok};
     p.ws.ltok = (int32_t)ltok;
     p.ws.total = n_streams * ltok;
-    p.ws.span = pick_span(p.ws.total);
+    p.ws.span = pick_span(p.ws.total, use_gqa_kernel(d));
     p.n_workgroups = (p.ws.total + p.ws.span - 1) / p.ws.span;
     if (p.n_workgroups > 0x7fffffff) return HG_ERR_SHAPE;
     p.n_slots = p.ws.total ? p.n_workgroups + n_streams * n_ranges : 0;
@@ -479,9 +479,9 @@ hg_status hg_attn_merge(const float *m, const float *l, const float *o, const in
     }
     dim3 grid((unsigned)n_groups, (unsigned)n_q_heads);
     if (head_dim == 128)
-        hipLaunchKernelGGL(hg_merge_kernel<128>, grid, dim3(128), 0, stream, a);
+        hipLaunchKernelGGL(hg_merge_kernel<128>, grid, dim3(kReduceBlock), 0, stream, a);
     else
-        hipLaunchKernelGGL(hg_merge_kernel<64>, grid, dim3(64), 0, stream, a);
+        hipLaunchKernelGGL(hg_merge_kernel<64>, grid, dim3(kReduceBlock), 0, stream, a);
     return launch_status("merge kernel");
 }
 

@@ -46,14 +46,18 @@ constexpr int kUploadInts = 512;
 #ifndef HG_VALU_U
 #define HG_VALU_U 4  // rows in flight per 16-lane group (kernels with 1 or 2 heads per stream)
 #endif
-#ifndef HG_WG_PER_CU
-#define HG_WG_PER_CU 1
+#ifndef HG_VALU_WG_PER_CU
+#define HG_VALU_WG_PER_CU 1
+#endif
+#ifndef HG_GQA_WG_PER_CU
+#define HG_GQA_WG_PER_CU 1
 #endif
 constexpr int kValuWaves = HG_VALU_WAVES;
 constexpr int kGqaWaves = HG_GQA_WAVES;
 constexpr int kValuBlock = 64 * kValuWaves;
 constexpr int kGqaBlock = 64 * kGqaWaves;
-constexpr int kWorkgroupsPerCu = HG_WG_PER_CU;
+constexpr int kValuWorkgroupsPerCu = HG_VALU_WG_PER_CU;
+constexpr int kGqaWorkgroupsPerCu = HG_GQA_WG_PER_CU;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 // "no token seen yet" marker for running maxima (log2 domain).  Finite, so that
@@ -679,6 +683,38 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 
 constexpr int kReduceBlock = 512;
 
+// Shared tail of the two combining kernels.  Each of the S = kReduceBlock / D slices has folded
+// its share of the records into a running (mx, lt, ot) in ONE pass (independent loads, no
+// max pre-pass, so the kernel costs a single memory round trip); the slices are merged here.
+// Returns true in the threads of slice 0, which then hold the total (mx, lt, ot[c]).
+template <int D>
+__device__ __forceinline__ bool combine_slices(float &mx, float &lt, float &ot, int c, int sl)
+{
+    constexpr int S = kReduceBlock / D;
+    __shared__ float s_o[S][D];
+    __shared__ float s_m[S], s_l[S];
+    s_o[sl][c] = ot;
+    if (c == 0) {
+        s_m[sl] = mx;
+        s_l[sl] = lt;
+    }
+    __syncthreads();
+    if (sl != 0) return false;
+    float M = s_m[0];
+#pragma unroll
+    for (int i = 1; i < S; ++i) M = fmaxf(M, s_m[i]);
+    lt = 0.f;
+    ot = 0.f;
+#pragma unroll
+    for (int i = 0; i < S; ++i) {
+        const float wt = fast_exp2(s_m[i] - M);
+        lt += wt * s_l[i];
+        ot += wt * s_o[i][c];
+    }
+    mx = M;
+    return true;
+}
+
 // One workgroup per (range, query head).  The segment records of the range are dealt round-robin
 // to kReduceBlock / D slices of D threads (one thread per channel), so that a range cut into
 // hundreds of segments is not one long chain of dependent loads.
@@ -686,11 +722,6 @@ template <int D>
 __global__ __launch_bounds__(kReduceBlock) void hg_segment_reduce_kernel(const ReduceArgs a)
 {
     constexpr int S = kReduceBlock / D;
-    constexpr int NW = kReduceBlock / 64;
-    __shared__ float s_max[NW];
-    __shared__ float s_o[S][D];
-    __shared__ float s_l[S];
-
     const int r = blockIdx.x, h = blockIdx.y;
     const int c = threadIdx.x % D, sl = threadIdx.x / D;
 
@@ -705,34 +736,18 @@ __global__ __launch_bounds__(kReduceBlock) void hg_segment_reduce_kernel(const R
     const int n_rec = pre1 > pre0 ? (int)((p1 - 1) / a.ws.span - w0) + 1 : 0;
     const int64_t rec0 = (w0 + (int64_t)stream * a.tab.n_ranges + r) * a.ws.gt + gl;  // record i at rec0 + i * gt
 
-    float mx = kNegBig;
-    for (int i = (int)threadIdx.x; i < n_rec; i += kReduceBlock) mx = fmaxf(mx, a.ws_m[rec0 + (int64_t)i * a.ws.gt]);
-#pragma unroll
-    for (int step = 32; step >= 1; step >>= 1) mx = fmaxf(mx, __shfl_xor(mx, step, 64));
-    if ((threadIdx.x & 63) == 0) s_max[threadIdx.x >> 6] = mx;
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < NW; ++w) mx = fmaxf(mx, s_max[w]);
-
-    float lt = 0.f, ot = 0.f;
+    float mx = kNegBig, lt = 0.f, ot = 0.f;  // log2 units
 #pragma unroll 4
     for (int i = sl; i < n_rec; i += S) {
         const int64_t th = rec0 + (int64_t)i * a.ws.gt;
-        const float wt = fast_exp2(a.ws_m[th] - mx);
-        lt += wt * a.ws_l[th];
-        ot += wt * a.ws_o[th * D + c];
+        const float mi = a.ws_m[th], li = a.ws_l[th], oi = a.ws_o[th * D + c];
+        const float mn = fmaxf(mx, mi);
+        const float wa = fast_exp2(mx - mn), wb = fast_exp2(mi - mn);
+        lt = lt * wa + li * wb;
+        ot = ot * wa + oi * wb;
+        mx = mn;
     }
-    s_o[sl][c] = ot;
-    if (c == 0) s_l[sl] = lt;
-    __syncthreads();
-    if (sl != 0) return;
-    lt = 0.f;
-    ot = 0.f;
-#pragma unroll
-    for (int i = 0; i < S; ++i) {
-        lt += s_l[i];
-        ot += s_o[i][c];
-    }
+    if (!combine_slices<D>(mx, lt, ot, c, sl)) return;
 
     const int64_t rh = (int64_t)r * a.ws.n_q_heads + h;
     const bool empty = !(lt > 0.f);
@@ -750,30 +765,35 @@ __global__ __launch_bounds__(kReduceBlock) void hg_segment_reduce_kernel(const R
 
 // ---- exact merge of range triples ---------------------------------------------------------------
 
+// One workgroup per (group, query head); the group's triples are dealt to the slices as above.
+// Triples arrive in natural-log units and are folded in log2 units.
 template <int D>
-__global__ __launch_bounds__(D) void hg_merge_kernel(const MergeArgs a)
+__global__ __launch_bounds__(kReduceBlock) void hg_merge_kernel(const MergeArgs a)
 {
-    const int gidx = blockIdx.x, h = blockIdx.y, c = threadIdx.x;
+    constexpr int S = kReduceBlock / D;
+    const int gidx = blockIdx.x, h = blockIdx.y;
+    const int c = threadIdx.x % D, sl = threadIdx.x / D;
     const int ts = a.tab.ext ? a.tab.ext[gidx] : a.tab.inl[gidx];
     const int te = a.tab.ext ? a.tab.ext[gidx + 1] : a.tab.inl[gidx + 1];
-    float mx = -INFINITY;
-    for (int t = ts; t < te; ++t) {
+
+    float mx = kNegBig, lt = 0.f, ot = 0.f;
+#pragma unroll 4
+    for (int t = ts + sl; t < te; t += S) {
         const int64_t th = (int64_t)t * a.n_q_heads + h;
-        if (a.l[th] != 0.f) mx = fmaxf(mx, a.m[th]);
+        const float li = a.l[th], oi = a.o[th * D + c];
+        const float mi = li != 0.f ? a.m[th] * kLog2e : kNegBig;  // identity element: ignored
+        const float mn = fmaxf(mx, mi);
+        const float wa = fast_exp2(mx - mn), wb = li != 0.f ? fast_exp2(mi - mn) : 0.f;
+        lt = lt * wa + li * wb;
+        ot = ot * wa + oi * wb;
+        mx = mn;
     }
-    float lt = 0.f, ot = 0.f;
-    for (int t = ts; t < te; ++t) {
-        const int64_t th = (int64_t)t * a.n_q_heads + h;
-        const float lv = a.l[th];
-        if (lv == 0.f) continue;  // identity element
-        const float wt = fast_exp2((a.m[th] - mx) * kLog2e);
-        lt += wt * lv;
-        ot += wt * a.o[th * D + c];
-    }
+    if (!combine_slices<D>(mx, lt, ot, c, sl)) return;
+
     const int64_t gh = (int64_t)gidx * a.n_q_heads + h;
     const bool empty = !(lt > 0.f);
     a.out[gh * D + c] = empty ? 0.f : ot / lt;
-    if (c == 0 && a.lse) a.lse[gh] = empty ? -INFINITY : mx + logf(lt);
+    if (c == 0 && a.lse) a.lse[gh] = empty ? -INFINITY : mx * kLn2 + logf(lt);
 }
 
 // ---- table upload (host tables reach the device through kernel arguments only) ----------------
