@@ -24,6 +24,20 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def _profiled_traffic(kernel, workload):
+    """HBM bytes per launch of the streaming kernel as measured by the committed rocprofv3 --pmc
+    runs (FETCH_SIZE + WRITE_SIZE, each scaled by the calibration copy); None if no summary."""
+    path = os.path.join(PROFILES, "%s__%s.md" % (kernel, workload))
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1]), os.path.relpath(path, ROOT)
+    except OSError:
+        pass
+    return None, None
 PAPER_CONTEXT = (
     "paper reports only end-to-end generation speedups (1.41x-3.2x on average over six baselines; "
     "Xeon Gold 5320 + A100 80GB, Xeon Gold 6530 + H100 NVL, Xeon 6960P + RTX 5090 + CXL); "
@@ -183,6 +197,9 @@ def main():
         r["steps"] = k
         others.append(r)
 
+    kernel_name = "hg_partial_gqa_kernel" if (head["kv_dtype"] == "f16" and head["head_dim"] == 128
+                                               and head["n_q_heads"] // head["n_kv_heads"] >= 4) else "hg_partial_kernel"
+    traffic, traffic_src = _profiled_traffic(kernel_name, head["workload"])
     line = {
         "metric": "decode attention effective KV GB/s (% of HBM peak) and us/layer at 1 GPU",
         "value": head["gbps"],
@@ -202,12 +219,13 @@ def main():
                                         "tokens_total", "partitions", "span_tokens", "workgroups", "kv_bytes")},
         "roofline": {
             "bound": "hbm",
-            "kernel": "hg_partial_kernel",
+            "kernel": kernel_name,
             "achieved": head["stream_kernel_gbps"],
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": head["stream_kernel_gbps"] / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": traffic,
+            "traffic_source": traffic_src,
             "kernel_us": head["stream_kernel_us"],
             "algorithmic_bytes_per_launch": head["kv_bytes"],
         },
