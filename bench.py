@@ -156,7 +156,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=1, help="index into the standard workloads (headline: 1)")
-    ap.add_argument("--others", type=str, default="2,3,4", help="comma list of further workloads to time ('' for none)")
+    ap.add_argument("--others", type=str, default="0,2,3,4", help="comma list of further workloads to time ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile-tokens", type=int, default=0)
     ap.add_argument("--calibration-copy", action="store_true",

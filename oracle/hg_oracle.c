@@ -21,6 +21,9 @@
  *   hgo_attn_concat   the paper-literal route: raw logits per range, concatenated in ascending
  *                     token order, ONE global softmax, then P.V (Section 4.6 step 5).
  *
+ *   hgo_attn_logits   the raw scaled logits of each range, the quantity an executor ships in the
+ *                     paper's own wire format (Section 4.2.2, Logits Calculator).
+ *
  * All arithmetic is fp64, plain sequential sums in token order, libm exp/log.  Inputs are the
  * caller's fp16 / fp32 bit patterns widened exactly; nothing is re-rounded.  The only parallelism
  * is an OpenMP loop over independent (sequence, query head) pairs; there is no blocking, fusion
@@ -209,6 +212,33 @@ int hgo_attn_partial(const hgo_problem *p, const hgo_range *ranges, int32_t n_ra
         }
     }
     return failed ? -7 : 0;
+}
+
+/* ---- 2b. raw logits per range (the paper's wire format) ------------------------------------ */
+
+/* logits is [Hq][ltok] with ltok = sum of range lengths; the logits of range r occupy columns
+ * pre[r] .. pre[r] + len_r - 1, pre[r] = total length of the ranges before r (table order). */
+int hgo_attn_logits(const hgo_problem *p, const hgo_range *ranges, int32_t n_ranges, double *logits, int nthreads)
+{
+    int rc = check_problem(p);
+    if (rc) return rc;
+    if (n_ranges < 0) return -2;
+    if (n_ranges && (!ranges || !logits)) return -1;
+    int64_t ltok = 0;
+    for (int r = 0; r < n_ranges; ++r) {
+        if (ranges[r].seq < 0 || ranges[r].seq >= p->B) return -4;
+        if (ranges[r].begin < 0 || ranges[r].begin > ranges[r].end) return -4;
+        if (ranges[r].end > p->seq_lens[ranges[r].seq]) return -4;
+        ltok += ranges[r].end - ranges[r].begin;
+    }
+    set_threads(nthreads);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int h = 0; h < p->Hq; ++h) {
+        int64_t col = 0;
+        for (int r = 0; r < n_ranges; ++r)
+            for (int64_t t = ranges[r].begin; t < ranges[r].end; ++t) logits[(int64_t)h * ltok + col++] = logit(p, ranges[r].seq, h, t);
+    }
+    return 0;
 }
 
 /* ---- 3. exact merge of (m, l, O) triples --------------------------------------------------- */

@@ -67,7 +67,9 @@ def _load():
         lib.hgo_attn_partial.argtypes = [P, ctypes.POINTER(_Range), ctypes.c_int32, dp, dp, dp, ctypes.c_int]
         lib.hgo_attn_merge.argtypes = [dp, dp, dp, dp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, dp, dp]
         lib.hgo_attn_concat.argtypes = [P, ctypes.POINTER(_Range), ctypes.c_int32, dp, ctypes.c_int]
-        for f in (lib.hgo_attn_full, lib.hgo_attn_partial, lib.hgo_attn_merge, lib.hgo_attn_concat, lib.hgo_max_threads):
+        lib.hgo_attn_logits.argtypes = [P, ctypes.POINTER(_Range), ctypes.c_int32, dp, ctypes.c_int]
+        for f in (lib.hgo_attn_full, lib.hgo_attn_partial, lib.hgo_attn_merge, lib.hgo_attn_concat, lib.hgo_attn_logits,
+                  lib.hgo_max_threads):
             f.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -171,5 +173,17 @@ def attn_concat(q, k, v, seq_lens, scale, ranges, nthreads: int = 0):
     out = np.zeros((prob.B, prob.Hq, prob.d), dtype=np.float64)
     arr = _ranges(ranges)
     _check(_load().hgo_attn_concat(ctypes.byref(prob), arr, len(ranges), out.ctypes.data, nthreads), "attn_concat")
+    del keep
+    return out
+
+
+def attn_logits(q, k, v, seq_lens, scale, ranges, nthreads: int = 0):
+    """Raw scaled logits of the listed ranges, concatenated in table order.
+    Returns logits [Hq, ltok] in float64 (ltok = total length of the ranges)."""
+    prob, keep = _problem(q, k, v, seq_lens, scale)
+    ltok = sum(int(e) - int(b) for (_, b, e) in ranges)
+    out = np.zeros((prob.Hq, ltok), dtype=np.float64)
+    arr = _ranges(ranges)
+    _check(_load().hgo_attn_logits(ctypes.byref(prob), arr, len(ranges), out.ctypes.data, nthreads), "attn_logits")
     del keep
     return out

@@ -394,3 +394,36 @@ def test_bad_ranges_are_rejected():
     for bad in [(0, 3, 2), (0, 0, 5), (1, 0, 1), (0, -1, 2)]:
         with pytest.raises(ValueError):
             oracle.attn_partial(q, k, v, [4], 1.0, [bad])
+
+
+# ---- raw logits (the paper's wire format) ------------------------------------------------------
+
+
+def test_logits_match_exact_dot_products_and_rebuild_the_attention():
+    """Every exported logit equals scale * q.k evaluated in rational arithmetic (catches a wrong
+    column offset, head mapping or range order), and library softmax over the concatenated
+    logits times the matching V rows reproduces the unsplit output (the paper's route)."""
+    B, Hq, Hkv, N, d = 2, 4, 2, 12, 4
+    q, k, v = _case(21, B, Hq, Hkv, N, d, np.float16)
+    seq_lens = [12, 7]
+    scale = 0.5
+    ranges = [(1, 2, 7), (0, 0, 5), (0, 5, 5), (0, 5, 12), (1, 0, 2)]
+    lg = oracle.attn_logits(q, k, v, seq_lens, scale, ranges)
+    assert lg.shape == (Hq, 5 + 5 + 0 + 7 + 2)
+    G = Hq // Hkv
+    col = 0
+    for (b, s, e) in ranges:
+        for t in range(s, e):
+            for h in range(Hq):
+                dot = sum(Fraction(float(a)) * Fraction(float(c)) for a, c in zip(q[b, h], k[b, h // G, t]))
+                assert lg[h, col] == float(Fraction(scale) * dot)
+            col += 1
+    full, _ = oracle.attn_full(q, k, v, seq_lens, scale)
+    v64 = v.astype(np.float64)
+    # sequence 0 is covered by ranges 1..3 (columns 5..16), sequence 1 by ranges 4 then 0
+    for h in range(Hq):
+        p0 = scipy.special.softmax(lg[h, 5:17])
+        assert np.allclose(p0 @ v64[0, h // G, :12], full[0, h], rtol=0, atol=1e-13)
+        s1 = np.concatenate([lg[h, 17:19], lg[h, 0:5]])
+        p1 = scipy.special.softmax(s1)
+        assert np.allclose(p1 @ v64[1, h // G, :7], full[1, h], rtol=0, atol=1e-13)
