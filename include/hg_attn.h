@@ -140,6 +140,42 @@ hg_status hg_attn_full(const hg_attn_desc *desc, float *out, float *lse_out, voi
                        void *stream);
 
 /*
+ * hg_attn_logits -- the raw scaled logits of each listed range: what an executor ships in the
+ * paper's own wire format (Section 4.2.2, Logits Calculator: logits as a compact vector, the
+ * matching V rows travel separately).
+ *
+ *   logits  DEVICE [n_q_heads][ltok] fp32, ltok = total length of the ranges; the logits of range
+ *           r occupy columns pre[r] .. pre[r] + len_r - 1, pre[r] = total length of the ranges
+ *           listed before r.  Natural-log units: scale * (q . k_j).  Reads K only.
+ */
+hg_status hg_attn_logits_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges,
+                                        size_t *bytes);
+hg_status hg_attn_logits(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, float *logits,
+                         void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * hg_attn_concat -- the paper-literal Token Concatenator (Section 4.2.3; Section 4.6 step 5):
+ * the logits of a group's ranges are taken as ONE vector (they are adjacent columns of `logits`
+ * because a group's ranges are consecutive table entries), ONE softmax is applied over it, and
+ * the scores weight the V rows of those ranges.  Reads V and the logits; K and q are not read.
+ *
+ *   ranges     HOST  the table the logits were produced with (same order).
+ *   logits     DEVICE [n_q_heads][ltok] fp32 as written by hg_attn_logits (or by any other
+ *              executor: a CPU, another GPU).
+ *   group_ptr  HOST  CSR [n_groups+1] over the RANGES, group_ptr[0] == 0 and
+ *              group_ptr[n_groups] == n_ranges; all ranges of a group belong to one sequence.
+ *              List a group's ranges in ascending token order to restore the original order;
+ *              the result does not depend on it.  n_groups <= 65535.
+ *   out        DEVICE [n_groups][n_q_heads][head_dim] fp32;  lse_out DEVICE [n_groups][n_q_heads] or NULL.
+ *   A group without tokens gives out = 0, lse = -inf.
+ */
+hg_status hg_attn_concat_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges,
+                                        int32_t n_groups, size_t *bytes);
+hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, const float *logits,
+                         const int32_t *group_ptr, int32_t n_groups, float *out, float *lse_out, void *workspace,
+                         size_t ws_bytes, void *stream);
+
+/*
  * Host-side planning, exposed for inspection and tests.  The tokens of all ranges, repeated for
  * every stream (KV head x chunk of query heads sharing it), form one linear work space that is
  * cut into equal spans, one workgroup each, so that every workgroup streams the same number of

@@ -9,6 +9,8 @@ _API = (
     "hg_attn_partial",
     "hg_attn_merge",
     "hg_attn_full",
+    "hg_attn_logits",
+    "hg_attn_concat",
     "hg_attn_plan",
     "hg_attn_set_tile_tokens",
     "hg_attn_profile_start",

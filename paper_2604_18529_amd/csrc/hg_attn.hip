@@ -34,6 +34,7 @@ struct Plan {
     std::vector<RangeEntry> entries;  // n_ranges + 1 (sentinel)
     // workspace sections (byte offsets)
     size_t off_m = 0, off_l = 0, off_o = 0, off_tab = 0, total = 0;
+    size_t off_gs_m = 0, off_gs_l = 0, off_groups = 0;  // concat path only
 };
 
 // Compute units of the current device (256 on MI355X); 256 when no device can be queried, so
@@ -125,11 +126,11 @@ hg_status make_plan(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ran
     p.entries.resize((size_t)n_ranges + 1);
     int64_t ltok = 0;
     for (int32_t r = 0; r < n_ranges; ++r) {
-        p.entries[r] = RangeEntry{ranges[r].seq, ranges[r].begin, ranges[r].end, (int32_t)ltok};
+        p.entries[r] = RangeEntry{ranges[r].seq, ranges[r].begin, ranges[r].end, (int32_t)ltok, 0};
         ltok += ranges[r].end - ranges[r].begin;
         if (ltok > 0x7fffffff) return HG_ERR_SHAPE;  // more than 2^31-1 tokens in one call
     }
-    p.entries[n_ranges] = RangeEntry{0, 0, 0, (int32_t)ltok};
+    p.entries[n_ranges] = RangeEntry{0, 0, 0, (int32_t)ltok, 0};
     p.ws.ltok = (int32_t)ltok;
     p.ws.total = n_streams * ltok;
     p.ws.span = pick_span(p.ws.total, use_gqa_kernel(d));
@@ -187,31 +188,74 @@ hg_status stage_table(const Plan &p, int32_t n_ranges, char *ws, hipStream_t str
     return launch_status("range table upload");
 }
 
-template <typename TR>
-void launch_partial_gt(const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
+template <typename TR, int MODE>
+void launch_valu_gt(const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
 {
     switch (gt) {
-    case 1: hipLaunchKernelGGL((hg_partial_kernel<TR, 1, HG_VALU_U>), grid, dim3(kValuBlock), 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((hg_partial_kernel<TR, 2, HG_VALU_U>), grid, dim3(kValuBlock), 0, stream, a); break;
-    case 4: hipLaunchKernelGGL((hg_partial_kernel<TR, 4, 2>), grid, dim3(kValuBlock), 0, stream, a); break;
-    default: hipLaunchKernelGGL((hg_partial_kernel<TR, 8, 2>), grid, dim3(kValuBlock), 0, stream, a); break;
+    case 1: hipLaunchKernelGGL((hg_partial_kernel<TR, 1, HG_VALU_U, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
+    case 2: hipLaunchKernelGGL((hg_partial_kernel<TR, 2, HG_VALU_U, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
+    case 4: hipLaunchKernelGGL((hg_partial_kernel<TR, 4, 2, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
+    default: hipLaunchKernelGGL((hg_partial_kernel<TR, 8, 2, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
     }
 }
 
-void launch_partial(const hg_attn_desc *d, const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
+// One launch of the streaming kernel that fits the problem, in the given mode.
+template <int MODE>
+void launch_stream(const hg_attn_desc *d, const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
 {
+    if (use_gqa_kernel(d)) {
+        hipLaunchKernelGGL(hg_partial_gqa_kernel<MODE>, grid, dim3(kGqaBlock), 0, stream, a);
+        return;
+    }
     const bool f16 = d->dtype == HG_F16;
     if (d->head_dim == 128) {
         if (f16)
-            launch_partial_gt<Traits<128, true>>(a, gt, grid, stream);
+            launch_valu_gt<Traits<128, true>, MODE>(a, gt, grid, stream);
         else
-            launch_partial_gt<Traits<128, false>>(a, gt, grid, stream);
+            launch_valu_gt<Traits<128, false>, MODE>(a, gt, grid, stream);
     } else {
         if (f16)
-            launch_partial_gt<Traits<64, true>>(a, gt, grid, stream);
+            launch_valu_gt<Traits<64, true>, MODE>(a, gt, grid, stream);
         else
-            launch_partial_gt<Traits<64, false>>(a, gt, grid, stream);
+            launch_valu_gt<Traits<64, false>, MODE>(a, gt, grid, stream);
     }
+}
+
+void fill_stream_args(const hg_attn_desc *d, const Plan &p, char *ws, PartialArgs &pa)
+{
+    pa.q = d->q;
+    pa.k = d->k;
+    pa.v = d->v;
+    pa.stride_b = d->stride_b;
+    pa.stride_h = d->stride_h;
+    pa.stride_t = d->stride_t;
+    pa.ws = p.ws;
+    pa.qscale = d->scale * kLog2e;
+    if (ws) {
+        pa.ws_m = reinterpret_cast<float *>(ws + p.off_m);
+        pa.ws_l = reinterpret_cast<float *>(ws + p.off_l);
+        pa.ws_o = reinterpret_cast<float *>(ws + p.off_o);
+    }
+}
+
+// Group CSR: by value in the kernel arguments when small, else uploaded to `dst`.
+hg_status stage_groups(const int32_t *group_ptr, int32_t n_groups, int32_t *dst, hipStream_t stream, GroupTable &tab)
+{
+    tab.n_groups = n_groups;
+    tab.ext = nullptr;
+    if (n_groups <= kInlineGroups) {
+        std::memcpy(tab.inl, group_ptr, ((size_t)n_groups + 1) * sizeof(int32_t));
+        return HG_OK;
+    }
+    tab.ext = dst;
+    const size_t n = (size_t)n_groups + 1;
+    for (size_t i = 0; i < n; i += kUploadInts) {
+        IntChunk chunk;
+        const int cnt = (int)std::min<size_t>(kUploadInts, n - i);
+        std::memcpy(chunk.e, group_ptr + i, (size_t)cnt * sizeof(int32_t));
+        hipLaunchKernelGGL(hg_upload_ints_kernel, dim3(1), dim3(kUploadInts), 0, stream, dst + i, cnt, chunk);
+    }
+    return launch_status("group table upload");
 }
 
 // Shared by hg_attn_partial (normalise = 0) and hg_attn_full (normalise = 1).
@@ -231,31 +275,16 @@ hg_status run(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, i
     std::memset(&pa, 0, sizeof(pa));
     st = stage_table(p, n_ranges, ws, stream, pa.tab);
     if (st != HG_OK) return st;
-    pa.q = d->q;
-    pa.k = d->k;
-    pa.v = d->v;
-    pa.stride_b = d->stride_b;
-    pa.stride_h = d->stride_h;
-    pa.stride_t = d->stride_t;
-    pa.ws = p.ws;
-    pa.scale_log2 = d->scale * kLog2e;
-    pa.ws_m = reinterpret_cast<float *>(ws + p.off_m);
-    pa.ws_l = reinterpret_cast<float *>(ws + p.off_l);
-    pa.ws_o = reinterpret_cast<float *>(ws + p.off_o);
+    fill_stream_args(d, p, ws, pa);
     if (p.n_workgroups > 0) {
         dim3 grid((unsigned)p.n_workgroups);
         // In timing mode the kernel is launched g_prof_repeat times back to back between one pair
-        // of events (it is idempotent: every launch writes the same tile statistics), so that the
+        // of events (it is idempotent: every launch writes the same segment records), so that the
         // fixed cost of the event records is spread over several launches.
         const bool timed = (size_t)(2 * g_prof_used + 2) <= g_prof_events.size();
         const int reps = timed ? g_prof_repeat : 1;
         if (timed) (void)hipEventRecord(g_prof_events[2 * g_prof_used], stream);
-        for (int rep = 0; rep < reps; ++rep) {
-            if (use_gqa_kernel(d))
-                hipLaunchKernelGGL(hg_partial_gqa_kernel, grid, dim3(kGqaBlock), 0, stream, pa);
-            else
-                launch_partial(d, pa, p.ws.gt, grid, stream);
-        }
+        for (int rep = 0; rep < reps; ++rep) launch_stream<kModeStats>(d, pa, p.ws.gt, grid, stream);
         if (timed) (void)hipEventRecord(g_prof_events[2 * g_prof_used++ + 1], stream);
         st = launch_status("partial kernel");
         if (st != HG_OK) return st;
@@ -278,6 +307,34 @@ hg_status run(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, i
     else
         hipLaunchKernelGGL(hg_segment_reduce_kernel<64>, rgrid, dim3(kReduceBlock), 0, stream, ra);
     return launch_status("segment reduce kernel");
+}
+
+// Workspace of hg_attn_concat: the streaming sections, then the group softmax partials and the
+// group table.
+void add_concat_sections(Plan &p, int32_t n_groups, int32_t n_q_heads)
+{
+    size_t off = p.total;
+    const size_t gs = (size_t)n_groups * (size_t)n_q_heads * kConcatSlices * sizeof(float);
+    p.off_gs_m = off;
+    off += align_up(gs);
+    p.off_gs_l = off;
+    off += align_up(gs);
+    p.off_groups = off;
+    if (n_groups > kInlineGroups) off += align_up(((size_t)n_groups + 1) * sizeof(int32_t));
+    p.total = off;
+}
+
+hg_status check_concat_groups(const hg_range *ranges, int32_t n_ranges, const int32_t *group_ptr, int32_t n_groups)
+{
+    if (n_groups < 0 || n_groups > 65535) return HG_ERR_SHAPE;
+    if (!group_ptr) return HG_ERR_NULL;
+    if (group_ptr[0] != 0 || group_ptr[n_groups] != n_ranges) return HG_ERR_RANGE;
+    for (int32_t i = 0; i < n_groups; ++i) {
+        if (group_ptr[i] > group_ptr[i + 1]) return HG_ERR_RANGE;
+        for (int32_t r = group_ptr[i] + 1; r < group_ptr[i + 1]; ++r)
+            if (ranges[r].seq != ranges[group_ptr[i]].seq) return HG_ERR_RANGE;  // one group, one sequence
+    }
+    return HG_OK;
 }
 
 hg_status full_ranges(const hg_attn_desc *d, std::vector<hg_range> &ranges)
@@ -428,6 +485,141 @@ hg_status hg_attn_full(const hg_attn_desc *desc, float *out, float *lse_out, voi
     return run(desc, ranges.data(), (int32_t)ranges.size(), 1, lse_out, nullptr, out, workspace, ws_bytes, stream);
 }
 
+// The logits call records nothing: its workspace only holds the range table when that does
+// not fit in the kernel arguments.
+size_t logits_ws_bytes(int32_t n_ranges)
+{
+    return n_ranges > kInlineRanges ? align_up(((size_t)n_ranges + 1) * sizeof(RangeEntry)) : 0;
+}
+
+hg_status hg_attn_logits_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, size_t *bytes)
+{
+    if (!bytes) return HG_ERR_NULL;
+    hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = check_ranges(desc, ranges, n_ranges);
+    if (st != HG_OK) return st;
+    *bytes = logits_ws_bytes(n_ranges);
+    return HG_OK;
+}
+
+hg_status hg_attn_logits(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, float *logits,
+                         void *workspace, size_t ws_bytes, void *stream_v)
+{
+    hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = check_ranges(desc, ranges, n_ranges);
+    if (st != HG_OK) return st;
+    Plan p;
+    st = make_plan(desc, ranges, n_ranges, p);
+    if (st != HG_OK) return st;
+    if (p.n_workgroups == 0) return HG_OK;
+    if (!logits) return HG_ERR_NULL;
+    st = check_workspace(workspace, ws_bytes, logits_ws_bytes(n_ranges));
+    if (st != HG_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    PartialArgs pa;
+    std::memset(&pa, 0, sizeof(pa));
+    p.off_tab = 0;  // the table is the only thing in this workspace
+    st = stage_table(p, n_ranges, static_cast<char *>(workspace), stream, pa.tab);
+    if (st != HG_OK) return st;
+    fill_stream_args(desc, p, nullptr, pa);
+    pa.qscale = desc->scale;  // logits leave in natural-log units
+    pa.logits = logits;
+    launch_stream<kModeLogits>(desc, pa, p.ws.gt, dim3((unsigned)p.n_workgroups), stream);
+    return launch_status("logits kernel");
+}
+
+hg_status hg_attn_concat_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges,
+                                        int32_t n_groups, size_t *bytes)
+{
+    if (!bytes) return HG_ERR_NULL;
+    if (n_groups < 0 || n_groups > 65535) return HG_ERR_SHAPE;
+    hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = check_ranges(desc, ranges, n_ranges);
+    if (st != HG_OK) return st;
+    Plan p;
+    st = make_plan(desc, ranges, n_ranges, p);
+    if (st != HG_OK) return st;
+    add_concat_sections(p, n_groups, desc->n_q_heads);
+    *bytes = p.total;
+    return HG_OK;
+}
+
+hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, const float *logits,
+                         const int32_t *group_ptr, int32_t n_groups, float *out, float *lse_out, void *workspace,
+                         size_t ws_bytes, void *stream_v)
+{
+    hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = check_ranges(desc, ranges, n_ranges);
+    if (st != HG_OK) return st;
+    st = check_concat_groups(ranges, n_ranges, group_ptr, n_groups);
+    if (st != HG_OK) return st;
+    if (n_groups == 0) return HG_OK;
+    if (!out) return HG_ERR_NULL;
+    Plan p;
+    st = make_plan(desc, ranges, n_ranges, p);
+    if (st != HG_OK) return st;
+    if (p.ws.total > 0 && !logits) return HG_ERR_NULL;
+    add_concat_sections(p, n_groups, desc->n_q_heads);
+    st = check_workspace(workspace, ws_bytes, p.total);
+    if (st != HG_OK) return st;
+    for (int32_t i = 0; i < n_groups; ++i)
+        for (int32_t r = group_ptr[i]; r < group_ptr[i + 1]; ++r) p.entries[r].grp = i;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char *ws = static_cast<char *>(workspace);
+
+    PartialArgs pa;
+    std::memset(&pa, 0, sizeof(pa));
+    st = stage_table(p, n_ranges, ws, stream, pa.tab);
+    if (st != HG_OK) return st;
+    fill_stream_args(desc, p, ws, pa);
+    pa.logits = const_cast<float *>(logits);
+    float *gs_m = reinterpret_cast<float *>(ws + p.off_gs_m), *gs_l = reinterpret_cast<float *>(ws + p.off_gs_l);
+    pa.gs_m = gs_m;
+    pa.gs_l = gs_l;
+
+    ConcatStatsArgs sa;
+    std::memset(&sa, 0, sizeof(sa));
+    st = stage_groups(group_ptr, n_groups, reinterpret_cast<int32_t *>(ws + p.off_groups), stream, sa.groups);
+    if (st != HG_OK) return st;
+    sa.logits = logits;
+    sa.gs_m = gs_m;
+    sa.gs_l = gs_l;
+    sa.ltok = p.ws.ltok;
+    sa.n_q_heads = desc->n_q_heads;
+    sa.tab = pa.tab;
+    hipLaunchKernelGGL(hg_concat_stats_kernel, dim3(kConcatSlices, (unsigned)desc->n_q_heads, (unsigned)n_groups), dim3(256),
+                       0, stream, sa);
+    st = launch_status("concat stats kernel");
+    if (st != HG_OK) return st;
+
+    if (p.n_workgroups > 0) {
+        launch_stream<kModeConcat>(desc, pa, p.ws.gt, dim3((unsigned)p.n_workgroups), stream);
+        st = launch_status("concat streaming kernel");
+        if (st != HG_OK) return st;
+    }
+
+    ConcatReduceArgs ra;
+    std::memset(&ra, 0, sizeof(ra));
+    ra.ws_o = pa.ws_o;
+    ra.gs_m = gs_m;
+    ra.gs_l = gs_l;
+    ra.out = out;
+    ra.lse = lse_out;
+    ra.ws = p.ws;
+    ra.groups = sa.groups;
+    ra.tab = pa.tab;
+    dim3 rgrid((unsigned)n_groups, (unsigned)desc->n_q_heads);
+    if (desc->head_dim == 128)
+        hipLaunchKernelGGL(hg_concat_reduce_kernel<128>, rgrid, dim3(kReduceBlock), 0, stream, ra);
+    else
+        hipLaunchKernelGGL(hg_concat_reduce_kernel<64>, rgrid, dim3(kReduceBlock), 0, stream, ra);
+    return launch_status("concat reduce kernel");
+}
+
 hg_status hg_attn_merge_workspace_size(int32_t n_groups, size_t *bytes)
 {
     if (!bytes) return HG_ERR_NULL;
@@ -461,22 +653,8 @@ hg_status hg_attn_merge(const float *m, const float *l, const float *o, const in
     a.out = out;
     a.lse = lse_out;
     a.n_q_heads = n_q_heads;
-    a.tab.n_groups = n_groups;
-    if (n_groups <= kInlineGroups) {
-        std::memcpy(a.tab.inl, group_ptr, ((size_t)n_groups + 1) * sizeof(int32_t));
-    } else {
-        int32_t *dst = static_cast<int32_t *>(workspace);
-        a.tab.ext = dst;
-        const size_t n = (size_t)n_groups + 1;
-        for (size_t i = 0; i < n; i += kUploadInts) {
-            IntChunk chunk;
-            const int cnt = (int)std::min<size_t>(kUploadInts, n - i);
-            std::memcpy(chunk.e, group_ptr + i, (size_t)cnt * sizeof(int32_t));
-            hipLaunchKernelGGL(hg_upload_ints_kernel, dim3(1), dim3(kUploadInts), 0, stream, dst + i, cnt, chunk);
-        }
-        st = launch_status("group table upload");
-        if (st != HG_OK) return st;
-    }
+    st = stage_groups(group_ptr, n_groups, static_cast<int32_t *>(workspace), stream, a.tab);
+    if (st != HG_OK) return st;
     dim3 grid((unsigned)n_groups, (unsigned)n_q_heads);
     if (head_dim == 128)
         hipLaunchKernelGGL(hg_merge_kernel<128>, grid, dim3(kReduceBlock), 0, stream, a);

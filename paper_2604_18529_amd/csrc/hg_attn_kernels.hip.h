@@ -64,10 +64,17 @@ constexpr float kLn2 = 0.6931471805599453f;
 // exp2(marker - marker) = 1 multiplies an all-zero state instead of producing NaN.
 constexpr float kNegBig = -3.0e38f;
 
-// pre = number of tokens in the ranges before this one (prefix sum of the range lengths).
+// pre = number of tokens in the ranges before this one (prefix sum of the range lengths);
+// grp = the concatenation group the range belongs to (used by the concat path only).
 struct RangeEntry {
-    int32_t seq, begin, end, pre;
+    int32_t seq, begin, end, pre, grp;
 };
+
+// What a streaming kernel instance does with the rows it reads.
+constexpr int kModeStats = 0;   // K and V -> (m, l, O) records                     (hg_attn_partial / hg_attn_full)
+constexpr int kModeLogits = 1;  // K only  -> raw scaled logits                     (hg_attn_logits)
+constexpr int kModeConcat = 2;  // V and given logits + group softmax stats -> sum p.v records  (hg_attn_concat)
+constexpr int kConcatSlices = 32;  // partial (max, sum) records per (group, head) of the concat path
 
 // The range table travels by value in the kernel arguments when it is small; otherwise `ext`
 // points at a device copy.  Entry n_ranges is a sentinel whose pre is ltok.
@@ -92,8 +99,10 @@ struct WorkSplit {
 struct PartialArgs {
     const void *q, *k, *v;
     int64_t stride_b, stride_h, stride_t;  // elements
-    float scale_log2;                      // scale * log2(e)
+    float qscale;                          // scale * log2(e); plain scale in logits mode
     float *ws_m, *ws_l, *ws_o;             // segment records [slot][gt], [slot][gt][D]; m in log2 units
+    float *logits;                         // [Hq][ltok]: written in logits mode, read in concat mode
+    const float *gs_m, *gs_l;              // concat mode: [n_groups][Hq][kConcatSlices] partial (max in log2 units, sum)
     WorkSplit ws;
     RangeTable tab;
 };
@@ -117,6 +126,23 @@ struct MergeArgs {
     float *out, *lse;
     int32_t n_q_heads;
     GroupTable tab;
+};
+
+struct ConcatStatsArgs {
+    const float *logits;  // [Hq][ltok], natural-log units
+    float *gs_m, *gs_l;   // [n_groups][Hq][kConcatSlices]
+    int32_t ltok, n_q_heads;
+    GroupTable groups;    // CSR over ranges
+    RangeTable tab;
+};
+
+struct ConcatReduceArgs {
+    const float *ws_o;        // segment records [slot][gt][D]: sums of p.v
+    const float *gs_m, *gs_l;
+    float *out, *lse;
+    WorkSplit ws;
+    GroupTable groups;
+    RangeTable tab;
 };
 
 struct RangeChunk {
@@ -166,8 +192,9 @@ __device__ __forceinline__ int find_range(const RangeTable &tab, int x)
     return lo;
 }
 
-// Walk the segments of this workgroup's span.  f(stream, seq, t0, t1, slot) is called by every
-// thread of the workgroup, in the same order (the control flow is uniform).
+// Walk the segments of this workgroup's span.  f(stream, range entry, t0, t1, col0, slot) is
+// called by every thread of the workgroup, in the same order (the control flow is uniform);
+// col0 is the position of token t0 in the concatenation of all ranges.
 template <typename F>
 __device__ __forceinline__ void for_each_segment(const WorkSplit &ws, const RangeTable &tab, F &&f)
 {
@@ -182,7 +209,7 @@ __device__ __forceinline__ void for_each_segment(const WorkSplit &ws, const Rang
         const int64_t left = p_end - p;
         const int len = left < (int64_t)(r_end - x) ? (int)left : r_end - x;
         const int t0 = e.begin + (x - e.pre);
-        f(s, e.seq, t0, t0 + len, (int64_t)blockIdx.x + (int64_t)s * tab.n_ranges + r);
+        f(s, e, t0, t0 + len, x, (int64_t)blockIdx.x + (int64_t)s * tab.n_ranges + r);
         p += len;
         x += len;
         if (x == r_end) {
@@ -279,7 +306,17 @@ __device__ __forceinline__ void merge_state(float &m, float &l, float *acc, floa
     for (int i = 0; i < N; ++i) acc[i] = acc[i] * wa + acc_b[i] * wb;
 }
 
-template <typename TR, int GT, int U>
+// Global softmax maximum (log2 units) of (concat group, query head) from the kConcatSlices
+// partial records.  Computed by one wave cooperatively.
+__device__ __forceinline__ float group_softmax_max(const float *gs_m, int64_t base, int lane)
+{
+    float m = lane < kConcatSlices ? gs_m[base + lane] : kNegBig;
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1) m = fmaxf(m, __shfl_xor(m, step, 64));
+    return m;
+}
+
+template <typename TR, int GT, int U, int MODE>
 __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArgs a)
 {
     constexpr int D = TR::D, EPL = TR::EPL, NV = TR::NV, EPV = TR::EPV, ES = TR::ES;
@@ -290,32 +327,48 @@ __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArg
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane & 15, grp = lane >> 4;
 
-    for_each_segment(a.ws, a.tab, [&](int stream, int seq, int t0, int t1, int64_t slot) __attribute__((always_inline)) {
+    for_each_segment(a.ws, a.tab, [&](int stream, const RangeEntry &e, int t0, int t1, int col0, int64_t slot) __attribute__((always_inline)) {
+    const int seq = e.seq;
     const int hk = stream / a.ws.n_chunks;
     const int chunk = stream - hk * a.ws.n_chunks;
     const int g0 = chunk * GT;                              // first head of this chunk inside its group
     const int nh = min(GT, a.ws.group - g0);                // valid heads in this chunk
     const int h0 = hk * a.ws.group + g0;                    // first query head
 
-    // q fragments, scaled into the log2 domain
+    // q fragments, scaled into the log2 domain (natural-log domain when exporting logits)
     float qf[GT][EPL];
+    if constexpr (MODE != kModeConcat) {
 #pragma unroll
-    for (int g = 0; g < GT; ++g) {
-        const int h = h0 + (g < nh ? g : 0);
-        const char *qrow = static_cast<const char *>(a.q) + ((int64_t)seq * a.ws.n_q_heads + h) * (int64_t)(D * ES);
+        for (int g = 0; g < GT; ++g) {
+            const int h = h0 + (g < nh ? g : 0);
+            const char *qrow = static_cast<const char *>(a.q) + ((int64_t)seq * a.ws.n_q_heads + h) * (int64_t)(D * ES);
 #pragma unroll
-        for (int j = 0; j < NV; ++j) {
-            typename TR::Raw raw = TR::template load<false>(qrow, sub, j);
-            TR::widen(raw, &qf[g][j * EPV]);
+            for (int j = 0; j < NV; ++j) {
+                typename TR::Raw raw = TR::template load<false>(qrow, sub, j);
+                TR::widen(raw, &qf[g][j * EPV]);
+            }
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) qf[g][i] *= a.qscale;
         }
+    }
+
+    // concat mode: the group's global softmax maximum per head (the division by the global sum
+    // happens once, in the reduce kernel), and the logits rows
+    float gmax[GT];
+    const float *lrow[GT];
+    if constexpr (MODE == kModeConcat) {
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) qf[g][i] *= a.scale_log2;
+        for (int g = 0; g < GT; ++g) {
+            const int h = h0 + (g < nh ? g : 0);
+            gmax[g] = group_softmax_max(a.gs_m, ((int64_t)e.grp * a.ws.n_q_heads + h) * kConcatSlices, lane);
+            lrow[g] = a.logits + (int64_t)h * a.ws.ltok + (col0 - t0);  // lrow[g][tok] is the logit of token tok
+        }
     }
 
     float m[GT], l[GT], acc[GT][EPL];
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
-        m[g] = kNegBig;
+        m[g] = MODE == kModeConcat ? 0.f : kNegBig;  // concat records are plain sums: equal maxima, weight 1
         l[g] = 0.f;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) acc[g][i] = 0.f;
@@ -329,52 +382,86 @@ __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArg
     for (int tb = t0 + wave * CH; tb < t1; tb += kValuWaves * CH) {
         typename TR::Raw kraw[U][NV], vraw[U][NV];
         bool valid[U];
+        int tokc[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int tok = tb + 4 * u + grp;
             valid[u] = tok < t1;
-            const int64_t off = (int64_t)(valid[u] ? tok : t1 - 1) * row_bytes;  // clamp: never read past the segment
+            tokc[u] = valid[u] ? tok : t1 - 1;  // clamp: never read past the segment
+            const int64_t off = (int64_t)tokc[u] * row_bytes;
+            if constexpr (MODE != kModeConcat) {
 #pragma unroll
-            for (int j = 0; j < NV; ++j) kraw[u][j] = TR::template load<true>(kbase + off, sub, j);
+                for (int j = 0; j < NV; ++j) kraw[u][j] = TR::template load<true>(kbase + off, sub, j);
+            }
+            if constexpr (MODE != kModeLogits) {
 #pragma unroll
-            for (int j = 0; j < NV; ++j) vraw[u][j] = TR::template load<true>(vbase + off, sub, j);
-        }
-
-        // logits (log2 domain) of the U tokens of this lane group, for every head of the chunk
-        float s[GT][U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float kf[EPL];
-#pragma unroll
-            for (int j = 0; j < NV; ++j) TR::widen(kraw[u][j], &kf[j * EPV]);
-#pragma unroll
-            for (int g = 0; g < GT; ++g) {
-                float d = 0.f;
-#pragma unroll
-                for (int i = 0; i < EPL; ++i) d = fmaf(qf[g][i], kf[i], d);
-                d = row16_sum(d);
-                s[g][u] = valid[u] ? d : -INFINITY;
+                for (int j = 0; j < NV; ++j) vraw[u][j] = TR::template load<true>(vbase + off, sub, j);
             }
         }
 
-        // online softmax update
-        float p[GT][U];
-#pragma unroll
-        for (int g = 0; g < GT; ++g) {
-            float mx = m[g];
-#pragma unroll
-            for (int u = 0; u < U; ++u) mx = fmaxf(mx, s[g][u]);
-            const float alpha = fast_exp2(m[g] - mx);
-            m[g] = mx;
-            float ls = 0.f;
+        // logits of the U tokens of this lane group, for every head of the chunk
+        float s[GT][U];
+        if constexpr (MODE != kModeConcat) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                p[g][u] = fast_exp2(s[g][u] - mx);
-                ls += p[g][u];
-            }
-            l[g] = l[g] * alpha + ls;
+                float kf[EPL];
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) acc[g][i] *= alpha;
+                for (int j = 0; j < NV; ++j) TR::widen(kraw[u][j], &kf[j * EPV]);
+#pragma unroll
+                for (int g = 0; g < GT; ++g) {
+                    float d = 0.f;
+#pragma unroll
+                    for (int i = 0; i < EPL; ++i) d = fmaf(qf[g][i], kf[i], d);
+                    d = row16_sum(d);
+                    s[g][u] = valid[u] ? d : -INFINITY;
+                }
+            }
+        }
+
+        if constexpr (MODE == kModeLogits) {
+            // lane `g` of each 16-lane group stores head g's logit of that group's token
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int g = 0; g < GT; ++g)
+                    if (sub == g && g < nh && valid[u])
+                        a.logits[(int64_t)(h0 + g) * a.ws.ltok + col0 + (tokc[u] - t0)] = s[g][u];
+            continue;
+        }
+
+        float p[GT][U];
+        if constexpr (MODE == kModeStats) {
+            // online softmax update
+#pragma unroll
+            for (int g = 0; g < GT; ++g) {
+                float mx = m[g];
+#pragma unroll
+                for (int u = 0; u < U; ++u) mx = fmaxf(mx, s[g][u]);
+                const float alpha = fast_exp2(m[g] - mx);
+                m[g] = mx;
+                float ls = 0.f;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    p[g][u] = fast_exp2(s[g][u] - mx);
+                    ls += p[g][u];
+                }
+                l[g] = l[g] * alpha + ls;
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) acc[g][i] *= alpha;
+            }
+        } else {
+            // numerators exp(s - M) of the ONE softmax over the concatenated logits of the group
+#pragma unroll
+            for (int g = 0; g < GT; ++g) {
+                float ls = 0.f;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const float sv = lrow[g][tokc[u]];
+                    p[g][u] = valid[u] ? fast_exp2(sv * kLog2e - gmax[g]) : 0.f;
+                    ls += p[g][u];
+                }
+                l[g] += ls;
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -387,6 +474,7 @@ __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArg
                 for (int i = 0; i < EPL; ++i) acc[g][i] = fmaf(p[g][u], vf[i], acc[g][i]);
         }
     }
+    if constexpr (MODE == kModeLogits) return;  // nothing to merge or record
 
     // merge the four lane groups of the wave (lanes xor 16, xor 32)
 #pragma unroll
@@ -413,7 +501,7 @@ __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArg
     }
     __syncthreads();
 
-    // merge the four waves; one thread per (head, channel)
+    // merge the waves; one thread per (head, channel)
     for (int idx = threadIdx.x; idx < GT * D; idx += kValuBlock) {
         const int g = idx / D, c = idx - g * D;
         if (g >= nh) continue;
@@ -490,6 +578,7 @@ __device__ __forceinline__ void wave_lds_handover()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+template <int MODE>
 __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_gqa_kernel(const PartialArgs a)
 {
     constexpr int D = 128;
@@ -503,7 +592,8 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     char *kls = smem + wave * kGqaWaveBytes;
     char *pls = kls + kGqaKBytes;
 
-    for_each_segment(a.ws, a.tab, [&](int stream, int seq, int t0, int t1, int64_t slot) __attribute__((always_inline)) {
+    for_each_segment(a.ws, a.tab, [&](int stream, const RangeEntry &e, int t0, int t1, int col0, int64_t slot) __attribute__((always_inline)) {
+    const int seq = e.seq;
     const int hk = stream / a.ws.n_chunks;
     const int chunk = stream - hk * a.ws.n_chunks;
     const int g0 = chunk * kGqaHeads;
@@ -512,7 +602,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 
     // Q as A operand: lane l holds head l%16, channels 8*(4kk + l/16)..+7 for kk = 0..3
     hg_h8 qa[4];
-    {
+    if constexpr (MODE != kModeConcat) {
         const _Float16 *qrow = static_cast<const _Float16 *>(a.q) + ((int64_t)seq * a.ws.n_q_heads + h0 + (n < nh ? n : 0)) * D;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
@@ -522,11 +612,23 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         }
     }
 
+    // concat mode: global softmax maximum (log2 units) of this lane's head n, and its logits
+    // row (lrow[tok] is the logit of token tok)
+    float gmax = 0.f;
+    const float *lrow = nullptr;
+    if constexpr (MODE == kModeConcat) {
+        const int h = h0 + (n < nh ? n : 0);
+        const int64_t base = ((int64_t)e.grp * a.ws.n_q_heads + h) * kConcatSlices;
+        gmax = kNegBig;
+        for (int z = 0; z < kConcatSlices; ++z) gmax = fmaxf(gmax, a.gs_m[base + z]);
+        lrow = a.logits + (int64_t)h * a.ws.ltok + (col0 - t0);
+    }
+
     float m[4], lsum[4];
     hg_f4 o[8];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        m[r] = kNegBig;
+        m[r] = MODE == kModeConcat ? 0.f : kNegBig;  // concat records are plain sums
         lsum[r] = 0.f;
     }
 #pragma unroll
@@ -549,7 +651,9 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     auto load_v = [&](int tb, hg_u32x4(&vreg)[8]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            int tok = tb + 16 * (j & 1) + 4 * (j >> 1) + rg;
+            // token j of lane group rg: interleaved so that S halves pair up (stats mode), or the
+            // 8 consecutive tokens whose logits this lane reads (concat mode)
+            int tok = MODE == kModeConcat ? tb + 8 * rg + j : tb + 16 * (j & 1) + 4 * (j >> 1) + rg;
             tok = tok < t1 ? tok : t1 - 1;
             vreg[j] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(vbase + (int64_t)tok * row_bytes));
         }
@@ -576,14 +680,27 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             }
         }
 
-        // online softmax on S (lane: token n of each half, heads 4rg..4rg+3)
         const bool ok0 = tb + n < t1, ok1 = tb + 16 + n < t1;
+        if constexpr (MODE == kModeLogits) {
+            // export: lane (n, rg) holds heads 4rg..4rg+3 of tokens tb + n and tb + 16 + n
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (4 * rg + r >= nh) continue;
+                float *row = a.logits + (int64_t)(h0 + 4 * rg + r) * a.ws.ltok + col0 + (tb - t0);
+                if (ok0) row[n] = s[0][r] * a.qscale;
+                if (ok1) row[16 + n] = s[1][r] * a.qscale;
+            }
+            wave_lds_handover();  // the next block overwrites the K staging area
+            return;
+        }
+
+        // online softmax on S (lane: token n of each half, heads 4rg..4rg+3)
         float alpha[4];
         uint32_t ph[4], pl[4];  // packed (half 0, half 1) weights: fp16 head and fp16 remainder
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const float s0 = ok0 ? s[0][r] * a.scale_log2 : -INFINITY;
-            const float s1 = ok1 ? s[1][r] * a.scale_log2 : -INFINITY;
+            const float s0 = ok0 ? s[0][r] * a.qscale : -INFINITY;
+            const float s1 = ok1 ? s[1][r] * a.qscale : -INFINITY;
             const float mx = fmaxf(m[r], row16_max(fmaxf(s0, s1)));
             alpha[r] = fast_exp2(m[r] - mx);
             m[r] = mx;
@@ -627,19 +744,60 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         wave_lds_handover();  // the next block overwrites the K and P staging areas
     };
 
+    // Concat mode block: the numerators exp(s - M) of the ONE softmax over the group's concatenated
+    // logits come straight from memory in A-operand order (lane: head n, tokens tb + 8rg .. + 7);
+    // they lie in (0, 1], so the fp16 head + remainder keeps them to ~22 bits.  The division by the
+    // global sum happens once, in the reduce kernel.
+    auto concat_block = [&](int tb, int tb_next, hg_u32x4(&vreg)[8]) __attribute__((always_inline)) {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        hg_u32x4 hi_raw, lo_raw;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            float pj[2];
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+                const int tok = tb + 8 * rg + 2 * jj + x;
+                const bool ok = tok < t1 && n < nh;
+                const float sv = lrow[tok < t1 ? tok : t1 - 1];
+                pj[x] = ok ? fast_exp2(sv * kLog2e - gmax) : 0.f;
+            }
+            const _Float16 h0f = (_Float16)pj[0], h1f = (_Float16)pj[1];
+            const _Float16 l0f = (_Float16)(pj[0] - (float)h0f), l1f = (_Float16)(pj[1] - (float)h1f);
+            hi_raw[jj] = __builtin_bit_cast(uint32_t, h2{h0f, h1f});
+            lo_raw[jj] = __builtin_bit_cast(uint32_t, h2{l0f, l1f});
+        }
+        const hg_h8 pa_hi = __builtin_bit_cast(hg_h8, hi_raw), pa_lo = __builtin_bit_cast(hg_h8, lo_raw);
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) {
+            const uint32_t sel = (nb & 1) ? 0x07060302u : 0x05040100u;
+            hg_u32x4 braw;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                braw[jj] = __builtin_amdgcn_perm(vreg[2 * jj + 1][nb >> 1], vreg[2 * jj][nb >> 1], sel);
+            const hg_h8 b = __builtin_bit_cast(hg_h8, braw);
+            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
+            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
+        }
+        if (tb_next < t1) load_v(tb_next, vreg);
+    };
+
     {
         constexpr int kStride = kGqaWaves * kGqaBlockTokens;
         hg_u32x4 kreg[8], vreg[8];
         int tb = t0 + wave * kGqaBlockTokens;
         if (tb < t1) {
-            load_k(tb, kreg);
-            load_v(tb, vreg);
+            if constexpr (MODE != kModeConcat) load_k(tb, kreg);
+            if constexpr (MODE != kModeLogits) load_v(tb, vreg);
         }
         while (tb < t1) {
-            compute_block(tb, tb + kStride, kreg, vreg);
+            if constexpr (MODE == kModeConcat)
+                concat_block(tb, tb + kStride, vreg);
+            else
+                compute_block(tb, tb + kStride, kreg, vreg);
             tb += kStride;
         }
     }
+    if constexpr (MODE == kModeLogits) return;  // nothing to merge or record
 
     // per-wave state -> LDS (staging areas are dead now), then merge the four waves
     __syncthreads();
@@ -794,6 +952,89 @@ __global__ __launch_bounds__(kReduceBlock) void hg_merge_kernel(const MergeArgs 
     const bool empty = !(lt > 0.f);
     a.out[gh * D + c] = empty ? 0.f : ot / lt;
     if (c == 0 && a.lse) a.lse[gh] = empty ? -INFINITY : mx * kLn2 + logf(lt);
+}
+
+// ---- concat path: one softmax over the concatenated logits of a group --------------------------
+
+__device__ __forceinline__ int group_entry(const GroupTable &g, int i) { return g.ext ? g.ext[i] : g.inl[i]; }
+
+// Partial (max, sum of exp) of one slice of a group's logits row.  The ranges of a group are
+// consecutive table entries, so their logits are one contiguous piece [c0, c1) of the row: the
+// concatenation the paper describes is already how the logits are stored.
+// Grid (kConcatSlices, n_q_heads, n_groups), 256 threads.
+__global__ __launch_bounds__(256) void hg_concat_stats_kernel(const ConcatStatsArgs a)
+{
+    __shared__ float s_red[4];
+    const int z = blockIdx.x, h = blockIdx.y, gi = blockIdx.z;
+    const int c0 = table_entry(a.tab, group_entry(a.groups, gi)).pre;
+    const int c1 = table_entry(a.tab, group_entry(a.groups, gi + 1)).pre;
+    const int per = (c1 - c0 + kConcatSlices - 1) / kConcatSlices;
+    const int b = c0 + z * per < c1 ? c0 + z * per : c1;
+    const int e = b + per < c1 ? b + per : c1;
+    const float *row = a.logits + (int64_t)h * a.ltok;
+
+    float mx = kNegBig;
+    for (int i = b + (int)threadIdx.x; i < e; i += 256) mx = fmaxf(mx, row[i] * kLog2e);
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1) mx = fmaxf(mx, __shfl_xor(mx, step, 64));
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+    __syncthreads();
+    float lt = 0.f;
+    for (int i = b + (int)threadIdx.x; i < e; i += 256) lt += fast_exp2(row[i] * kLog2e - mx);
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1) lt += __shfl_xor(lt, step, 64);
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = lt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int64_t idx = ((int64_t)gi * a.n_q_heads + h) * kConcatSlices + z;
+        a.gs_m[idx] = mx;
+        a.gs_l[idx] = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+    }
+}
+
+// out[group][head] = (sum of the exp(s - M).v records of all segments of the group's ranges) / L,
+// lse = M + log L, with (M, L) the group's global softmax statistics.  Grid (n_groups, n_q_heads).
+template <int D>
+__global__ __launch_bounds__(kReduceBlock) void hg_concat_reduce_kernel(const ConcatReduceArgs a)
+{
+    constexpr int S = kReduceBlock / D;
+    __shared__ float s_o[S][D];
+    const int gi = blockIdx.x, h = blockIdx.y;
+    const int c = threadIdx.x % D, sl = threadIdx.x / D;
+    const int hk = h / a.ws.group, gidx = h - hk * a.ws.group;
+    const int chunk = gidx / a.ws.gt, gl = gidx - chunk * a.ws.gt;
+    const int stream = hk * a.ws.n_chunks + chunk;
+    const int r0 = group_entry(a.groups, gi), r1 = group_entry(a.groups, gi + 1);
+
+    float ot = 0.f;
+    for (int r = r0; r < r1; ++r) {
+        const int pre0 = table_entry(a.tab, r).pre, pre1 = table_entry(a.tab, r + 1).pre;
+        if (pre1 == pre0) continue;
+        const int64_t p0 = (int64_t)stream * a.ws.ltok + pre0, p1 = (int64_t)stream * a.ws.ltok + pre1;
+        const int64_t w0 = p0 / a.ws.span;
+        const int n_rec = (int)((p1 - 1) / a.ws.span - w0) + 1;
+        const int64_t rec0 = (w0 + (int64_t)stream * a.tab.n_ranges + r) * a.ws.gt + gl;
+#pragma unroll 4
+        for (int i = sl; i < n_rec; i += S) ot += a.ws_o[(rec0 + (int64_t)i * a.ws.gt) * D + c];
+    }
+    s_o[sl][c] = ot;
+    __syncthreads();
+    if (sl != 0) return;
+    ot = 0.f;
+#pragma unroll
+    for (int i = 0; i < S; ++i) ot += s_o[i][c];
+    const int64_t gh = (int64_t)gi * a.ws.n_q_heads + h;
+    float mx = kNegBig, lt = 0.f;  // the group's global maximum and sum of exp
+    for (int z = 0; z < kConcatSlices; ++z) {
+        const float mi = a.gs_m[gh * kConcatSlices + z], li = a.gs_l[gh * kConcatSlices + z];
+        const float mn = fmaxf(mx, mi);
+        lt = lt * fast_exp2(mx - mn) + li * fast_exp2(mi - mn);
+        mx = mn;
+    }
+    a.out[gh * D + c] = lt > 0.f ? ot / lt : 0.f;
+    if (c == 0 && a.lse) a.lse[gh] = lt > 0.f ? mx * kLn2 + logf(lt) : -INFINITY;
 }
 
 // ---- table upload (host tables reach the device through kernel arguments only) ----------------

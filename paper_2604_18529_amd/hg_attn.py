@@ -72,6 +72,10 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_partial.argtypes = [D, R, i32, vp, vp, vp, vp, sz, vp]
     lib.hg_attn_merge_workspace_size.argtypes = [i32, ctypes.POINTER(sz)]
     lib.hg_attn_merge.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.hg_attn_logits_workspace_size.argtypes = [D, R, i32, ctypes.POINTER(sz)]
+    lib.hg_attn_logits.argtypes = [D, R, i32, vp, vp, sz, vp]
+    lib.hg_attn_concat_workspace_size.argtypes = [D, R, i32, i32, ctypes.POINTER(sz)]
+    lib.hg_attn_concat.argtypes = [D, R, i32, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.hg_attn_full_workspace_size.argtypes = [D, ctypes.POINTER(sz)]
     lib.hg_attn_full.argtypes = [D, vp, vp, vp, sz, vp]
     lib.hg_attn_plan.argtypes = [D, R, i32, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_int64)]
@@ -83,6 +87,7 @@ def load_library() -> ctypes.CDLL:
         "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_merge_workspace_size", "hg_attn_merge",
         "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_tile_tokens",
         "hg_attn_profile_start", "hg_attn_profile_stop", "hg_attn_calibration_copy",
+        "hg_attn_logits_workspace_size", "hg_attn_logits", "hg_attn_concat_workspace_size", "hg_attn_concat",
     ):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -296,5 +301,77 @@ def hg_attn_full(q, k, v, seq_lens, scale=None, *, out=None, lse=None, want_lse=
     with torch.cuda.device(dev):
         st = lib.hg_attn_full(ctypes.byref(desc), _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, _stream_handle(stream))
     _check(st, "hg_attn_full")
+    del keep
+    return out, lse
+
+
+def hg_attn_logits(q, k, v, seq_lens, ranges, scale=None, *, logits=None, workspace=None, stream=None, desc=None):
+    """Raw scaled logits of the listed ranges, concatenated in table order: fp32 [Hq, ltok]."""
+    lib = load_library()
+    if desc is None:
+        desc, keep = make_desc(q, k, v, seq_lens, scale)
+    else:
+        keep = None
+    packed = pack_ranges(ranges)
+    R = _n_ranges(packed)
+    ltok = sum(packed[i].end - packed[i].begin for i in range(R))
+    dev = q.device
+    if logits is None:
+        logits = torch.empty((q.shape[1], ltok), dtype=torch.float32, device=dev)
+    elif tuple(logits.shape) != (q.shape[1], ltok) or logits.dtype != torch.float32 or not logits.is_contiguous():
+        raise ValueError("logits must be contiguous fp32 [Hq, ltok]")
+    if workspace is None:
+        sz = ctypes.c_size_t()
+        _check(lib.hg_attn_logits_workspace_size(ctypes.byref(desc), packed, R, ctypes.byref(sz)), "hg_attn_logits_workspace_size")
+        workspace, ws_bytes = _workspace(sz.value, dev, None)
+    else:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        st = lib.hg_attn_logits(ctypes.byref(desc), packed, R, _ptr(logits), _ptr(workspace), ws_bytes, _stream_handle(stream))
+    _check(st, "hg_attn_logits")
+    del keep
+    return logits
+
+
+def hg_attn_concat_workspace_size(desc, packed, n_groups) -> int:
+    sz = ctypes.c_size_t()
+    _check(load_library().hg_attn_concat_workspace_size(ctypes.byref(desc), packed, _n_ranges(packed), int(n_groups),
+                                                        ctypes.byref(sz)), "hg_attn_concat_workspace_size")
+    return sz.value
+
+
+def hg_attn_concat(q, k, v, seq_lens, ranges, logits, group_ptr, scale=None, *, out=None, lse=None, want_lse=True,
+                   workspace=None, stream=None, desc=None):
+    """One softmax over the concatenated logits of each group, then P.V (the paper-literal merge).
+    Returns (out [n_groups,Hq,d], lse [n_groups,Hq] or None)."""
+    lib = load_library()
+    if desc is None:
+        desc, keep = make_desc(q, k, v, seq_lens, scale)
+    else:
+        keep = None
+    packed = pack_ranges(ranges)
+    R = _n_ranges(packed)
+    gp = np.ascontiguousarray(group_ptr, dtype=np.int32)
+    if gp.ndim != 1 or gp.size < 1:
+        raise ValueError("group_ptr must be CSR offsets [n_groups+1]")
+    n_groups = gp.size - 1
+    if logits.dtype != torch.float32 or not logits.is_contiguous() or logits.dim() != 2 or logits.shape[0] != q.shape[1]:
+        raise ValueError("logits must be contiguous fp32 [Hq, ltok]")
+    if logits.shape[1] != sum(packed[i].end - packed[i].begin for i in range(R)):
+        raise ValueError("logits do not match the range table")
+    dev = q.device
+    Hq, d = q.shape[1], q.shape[2]
+    if out is None:
+        out = torch.empty((n_groups, Hq, d), dtype=torch.float32, device=dev)
+    if lse is None and want_lse:
+        lse = torch.empty((n_groups, Hq), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace, ws_bytes = _workspace(hg_attn_concat_workspace_size(desc, packed, n_groups), dev, None)
+    else:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        st = lib.hg_attn_concat(ctypes.byref(desc), packed, R, _ptr(logits), gp.ctypes.data, n_groups, _ptr(out), _ptr(lse),
+                                _ptr(workspace), ws_bytes, _stream_handle(stream))
+    _check(st, "hg_attn_concat")
     del keep
     return out, lse
