@@ -101,6 +101,21 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
 
     full_ms, _ = _time_steps(full_step, max(steps // 2, 1), max(warmup // 2, 1), torch)
 
+    # the paper-literal route: export raw logits per range, then concatenate, one softmax, P.V
+    ltok = sum(e - b for (_, b, e) in w.ranges)
+    logits = torch.empty((Hq, ltok), dtype=torch.float32, device=dev)
+    cws = torch.empty(max(binding.hg_attn_concat_workspace_size(desc, packed, spec.batch), 256), dtype=torch.uint8, device=dev)
+
+    def logits_step():
+        hg.hg_attn_logits(w.q, w.k, w.v, w.seq_lens, packed, w.scale, logits=logits, desc=desc)
+
+    def concat_step():
+        hg.hg_attn_concat(w.q, w.k, w.v, w.seq_lens, packed, logits, w.group_ptr, w.scale, out=out, lse=lse,
+                          workspace=cws, desc=desc)
+
+    logits_ms, _ = _time_steps(logits_step, max(steps // 2, 1), max(warmup // 2, 1), torch)
+    concat_ms, _ = _time_steps(concat_step, max(steps // 2, 1), max(warmup // 2, 1), torch)
+
     kv_bytes = w.kv_bytes
     res = {
         "workload": spec.name,
@@ -122,6 +137,13 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
         "stream_kernel_us": kernel_ms * 1e3,
         "stream_kernel_gbps": kv_bytes / (kernel_ms * 1e-3) / 1e9,
         "host_wall_us_per_step": wall_ms * 1e3,
+        "concat_route": {
+            "logits_us": logits_ms * 1e3,
+            "concat_us": concat_ms * 1e3,
+            "us": (logits_ms + concat_ms) * 1e3,
+            "gbps": kv_bytes / ((logits_ms + concat_ms) * 1e-3) / 1e9,
+            "logits_bytes": int(Hq) * int(ltok) * 4,
+        },
     }
 
     cpu = None
@@ -231,6 +253,7 @@ def main():
         },
         "cpu_baseline": cpu,
         "full_path": {"us": head["full_path_us"], "gbps": head["full_path_gbps"]},
+        "concat_route": head["concat_route"],
         "other_workloads": others,
         "paper_context": PAPER_CONTEXT,
     }

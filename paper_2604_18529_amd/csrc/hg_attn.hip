@@ -188,14 +188,17 @@ hg_status stage_table(const Plan &p, int32_t n_ranges, char *ws, hipStream_t str
     return launch_status("range table upload");
 }
 
+// Rows in flight per 16-lane group.  The logits and concat modes read only K or only V, so they
+// keep twice as many rows in flight to have the same number of bytes outstanding.
 template <typename TR, int MODE>
 void launch_valu_gt(const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
 {
+    constexpr int F = MODE == kModeStats ? 1 : 2;
     switch (gt) {
-    case 1: hipLaunchKernelGGL((hg_partial_kernel<TR, 1, HG_VALU_U, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((hg_partial_kernel<TR, 2, HG_VALU_U, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
-    case 4: hipLaunchKernelGGL((hg_partial_kernel<TR, 4, 2, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
-    default: hipLaunchKernelGGL((hg_partial_kernel<TR, 8, 2, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
+    case 1: hipLaunchKernelGGL((hg_partial_kernel<TR, 1, F * HG_VALU_U, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
+    case 2: hipLaunchKernelGGL((hg_partial_kernel<TR, 2, F * HG_VALU_U, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
+    case 4: hipLaunchKernelGGL((hg_partial_kernel<TR, 4, F * 2, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
+    default: hipLaunchKernelGGL((hg_partial_kernel<TR, 8, F * 2, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
     }
 }
 

@@ -451,13 +451,19 @@ __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArg
             }
         } else {
             // numerators exp(s - M) of the ONE softmax over the concatenated logits of the group
+            // (the mask is applied as a product so that every logit load stays unconditional and
+            // all of them are issued together with the V loads)
+            float sv[GT][U];
+#pragma unroll
+            for (int g = 0; g < GT; ++g)
+#pragma unroll
+                for (int u = 0; u < U; ++u) sv[g][u] = lrow[g][tokc[u]];
 #pragma unroll
             for (int g = 0; g < GT; ++g) {
                 float ls = 0.f;
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const float sv = lrow[g][tokc[u]];
-                    p[g][u] = valid[u] ? fast_exp2(sv * kLog2e - gmax[g]) : 0.f;
+                    p[g][u] = fast_exp2(sv[g][u] * kLog2e - gmax[g]) * (valid[u] ? 1.f : 0.f);
                     ls += p[g][u];
                 }
                 l[g] += ls;
@@ -757,9 +763,8 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
                 const int tok = tb + 8 * rg + 2 * jj + x;
-                const bool ok = tok < t1 && n < nh;
-                const float sv = lrow[tok < t1 ? tok : t1 - 1];
-                pj[x] = ok ? fast_exp2(sv * kLog2e - gmax) : 0.f;
+                const float sv = lrow[tok < t1 ? tok : t1 - 1];  // unconditional load; masked by a product
+                pj[x] = fast_exp2(sv * kLog2e - gmax) * ((tok < t1 && n < nh) ? 1.f : 0.f);
             }
             const _Float16 h0f = (_Float16)pj[0], h1f = (_Float16)pj[1];
             const _Float16 l0f = (_Float16)(pj[0] - (float)h0f), l1f = (_Float16)(pj[1] - (float)h1f);
@@ -783,18 +788,42 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 
     {
         constexpr int kStride = kGqaWaves * kGqaBlockTokens;
-        hg_u32x4 kreg[8], vreg[8];
         int tb = t0 + wave * kGqaBlockTokens;
-        if (tb < t1) {
-            if constexpr (MODE != kModeConcat) load_k(tb, kreg);
-            if constexpr (MODE != kModeLogits) load_v(tb, vreg);
-        }
-        while (tb < t1) {
-            if constexpr (MODE == kModeConcat)
-                concat_block(tb, tb + kStride, vreg);
-            else
+        if constexpr (MODE == kModeStats) {
+            hg_u32x4 kreg[8], vreg[8];
+            if (tb < t1) {
+                load_k(tb, kreg);
+                load_v(tb, vreg);
+            }
+            while (tb < t1) {
                 compute_block(tb, tb + kStride, kreg, vreg);
-            tb += kStride;
+                tb += kStride;
+            }
+        } else {
+            // Only K (logits) or only V (concat) is read: two register buffers, so that two
+            // blocks (16 KiB per wave) are in flight as in the statistics mode.
+            hg_u32x4 ra[8], rb[8];
+            auto load_one = [&](int t, hg_u32x4(&reg)[8]) __attribute__((always_inline)) {
+                if constexpr (MODE == kModeLogits)
+                    load_k(t, reg);
+                else
+                    load_v(t, reg);
+            };
+            auto compute_one = [&](int t, hg_u32x4(&reg)[8]) __attribute__((always_inline)) {
+                if constexpr (MODE == kModeLogits)
+                    compute_block(t, t + 2 * kStride, reg, reg);
+                else
+                    concat_block(t, t + 2 * kStride, reg);
+            };
+            if (tb < t1) load_one(tb, ra);
+            if (tb + kStride < t1) load_one(tb + kStride, rb);
+            while (tb < t1) {
+                compute_one(tb, ra);
+                tb += kStride;
+                if (tb >= t1) break;
+                compute_one(tb, rb);
+                tb += kStride;
+            }
         }
     }
     if constexpr (MODE == kModeLogits) return;  // nothing to merge or record
@@ -973,24 +1002,39 @@ __global__ __launch_bounds__(256) void hg_concat_stats_kernel(const ConcatStatsA
     const int e = b + per < c1 ? b + per : c1;
     const float *row = a.logits + (int64_t)h * a.ltok;
 
-    float mx = kNegBig;
-    for (int i = b + (int)threadIdx.x; i < e; i += 256) mx = fmaxf(mx, row[i] * kLog2e);
+    // one pass: every thread folds groups of four logits into a running (max, sum) pair
+    float mx = kNegBig, lt = 0.f;
+    for (int i = b + 4 * (int)threadIdx.x; i < e; i += 4 * 256) {
+        float x[4];
 #pragma unroll
-    for (int step = 32; step >= 1; step >>= 1) mx = fmaxf(mx, __shfl_xor(mx, step, 64));
-    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = mx;
-    __syncthreads();
-    mx = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
-    __syncthreads();
-    float lt = 0.f;
-    for (int i = b + (int)threadIdx.x; i < e; i += 256) lt += fast_exp2(row[i] * kLog2e - mx);
+        for (int j = 0; j < 4; ++j) x[j] = row[i + j < e ? i + j : e - 1] * kLog2e * 1.f;
 #pragma unroll
-    for (int step = 32; step >= 1; step >>= 1) lt += __shfl_xor(lt, step, 64);
-    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = lt;
+        for (int j = 0; j < 4; ++j) x[j] = i + j < e ? x[j] : kNegBig;
+        const float mn = fmaxf(fmaxf(mx, fmaxf(x[0], x[1])), fmaxf(x[2], x[3]));
+        lt = lt * fast_exp2(mx - mn) + ((fast_exp2(x[0] - mn) + fast_exp2(x[1] - mn)) + (fast_exp2(x[2] - mn) + fast_exp2(x[3] - mn)));
+        mx = mn;
+    }
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1) {
+        const float mo = __shfl_xor(mx, step, 64), lo = __shfl_xor(lt, step, 64);
+        const float mn = fmaxf(mx, mo);
+        lt = lt * fast_exp2(mx - mn) + lo * fast_exp2(mo - mn);
+        mx = mn;
+    }
+    __shared__ float s_l[4];
+    if ((threadIdx.x & 63) == 0) {
+        s_red[threadIdx.x >> 6] = mx;
+        s_l[threadIdx.x >> 6] = lt;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
+        const float M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) L += s_l[w] * fast_exp2(s_red[w] - M);
         const int64_t idx = ((int64_t)gi * a.n_q_heads + h) * kConcatSlices + z;
-        a.gs_m[idx] = mx;
-        a.gs_l[idx] = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+        a.gs_m[idx] = M;
+        a.gs_l[idx] = L;
     }
 }
 
