@@ -224,3 +224,18 @@ def random_ranges(seq_lens: Sequence[int], n_ranges: int, seed: int, max_len: Op
             e = min(e, a + max_len)
         out.append((b, a, e))
     return out
+
+
+def proxy_query(q: torch.Tensor, cosine: float, seed: int) -> torch.Tensor:
+    """A stand-in for the paper's proxy query (the previous layer's input pushed through this
+    layer's weights, Section 4.2): q rotated towards seeded noise so that every head's cosine
+    similarity to the true query is `cosine`, same norm, rounded once to q's dtype."""
+    gen = torch.Generator(device=q.device)
+    gen.manual_seed(_stream_seed(seed, 23))
+    q32 = q.float()
+    noise = torch.randn(q32.shape, generator=gen, device=q.device, dtype=torch.float32)
+    qn = q32 / q32.norm(dim=-1, keepdim=True)
+    noise = noise - (noise * qn).sum(-1, keepdim=True) * qn  # orthogonal to q
+    noise = noise / noise.norm(dim=-1, keepdim=True)
+    mixed = cosine * qn + math.sqrt(max(0.0, 1.0 - cosine * cosine)) * noise
+    return (mixed * q32.norm(dim=-1, keepdim=True)).to(q.dtype)
