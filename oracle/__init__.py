@@ -9,6 +9,7 @@ from .oracle import (  # noqa: F401
     attn_logits,
     attn_merge,
     attn_partial,
+    attn_select,
     build,
     max_threads,
 )

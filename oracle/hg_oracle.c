@@ -23,6 +23,11 @@
  *
  *   hgo_attn_logits   the raw scaled logits of each range, the quantity an executor ships in the
  *                     paper's own wire format (Section 4.2.2, Logits Calculator).
+ *   hgo_attn_select   Post-QK^T selection (Section 4.3.1; Section 4.5): per (group, query head),
+ *                     keep the top_k highest logits of the group's ranges and fold them and their
+ *                     V rows into one (m, l, O).  The logits are an INPUT in fp32 (the decision
+ *                     which tokens are kept is taken on those fp32 values, as on the GPU); ties
+ *                     go to the lower column.
  *
  * All arithmetic is fp64, plain sequential sums in token order, libm exp/log.  Inputs are the
  * caller's fp16 / fp32 bit patterns widened exactly; nothing is re-rounded.  The only parallelism
@@ -238,6 +243,95 @@ int hgo_attn_logits(const hgo_problem *p, const hgo_range *ranges, int32_t n_ran
         for (int r = 0; r < n_ranges; ++r)
             for (int64_t t = ranges[r].begin; t < ranges[r].end; ++t) logits[(int64_t)h * ltok + col++] = logit(p, ranges[r].seq, h, t);
     }
+    return 0;
+}
+
+/* ---- 2c. Post-QK^T selection: top-k logits of a group, then (m, l, O) over the kept tokens ---- */
+
+typedef struct {
+    float val;
+    int32_t col;
+} hgo_cand;
+
+static int cmp_cand(const void *a, const void *b)
+{
+    const hgo_cand *x = (const hgo_cand *)a, *y = (const hgo_cand *)b;
+    if (x->val != y->val) return x->val > y->val ? -1 : 1; /* higher logit first */
+    return (x->col > y->col) - (x->col < y->col);          /* ties: lower column first */
+}
+
+static int cmp_int32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* logits: fp32 [Hq][ltok] laid out as hgo_attn_logits writes them for `ranges`.  group_ptr: CSR
+ * over the ranges (group_ptr[0] == 0, group_ptr[n_groups] == n_ranges, one sequence per group).
+ * sel: int32 [n_groups][Hq][top_k] kept TOKEN positions in ascending column order, -1 padded.
+ * m, l: [n_groups][Hq]; o: [n_groups][Hq][d]. */
+int hgo_attn_select(const hgo_problem *p, const hgo_range *ranges, int32_t n_ranges, const float *logits,
+                    const int32_t *group_ptr, int32_t n_groups, int32_t top_k, int32_t *sel, double *m, double *l,
+                    double *o)
+{
+    int rc = check_problem(p);
+    if (rc) return rc;
+    if (n_ranges < 0 || n_groups < 0 || top_k < 1) return -2;
+    if (n_groups && (!group_ptr || !sel || !m || !l || !o)) return -1;
+    if (n_groups && (group_ptr[0] != 0 || group_ptr[n_groups] != n_ranges)) return -4;
+    int64_t ltok = 0;
+    int64_t *pre = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n_ranges + 1));
+    if (!pre) return -7;
+    for (int r = 0; r < n_ranges; ++r) {
+        pre[r] = ltok;
+        ltok += ranges[r].end - ranges[r].begin;
+    }
+    pre[n_ranges] = ltok;
+    for (int g = 0; g < n_groups; ++g) {
+        int r0 = group_ptr[g], r1 = group_ptr[g + 1];
+        int64_t c0 = pre[r0], c1 = pre[r1], n = c1 - c0;
+        for (int h = 0; h < p->Hq; ++h) {
+            int64_t gh = (int64_t)g * p->Hq + h;
+            int32_t *out_sel = sel + gh * top_k;
+            double *dst = o + gh * p->d;
+            for (int i = 0; i < top_k; ++i) out_sel[i] = -1;
+            for (int c = 0; c < p->d; ++c) dst[c] = 0.0;
+            m[gh] = -INFINITY;
+            l[gh] = 0.0;
+            if (n == 0) continue;
+            hgo_cand *cand = (hgo_cand *)malloc(sizeof(hgo_cand) * (size_t)n);
+            if (!cand) {
+                free(pre);
+                return -7;
+            }
+            for (int64_t j = 0; j < n; ++j) {
+                cand[j].val = logits[(int64_t)h * ltok + c0 + j];
+                cand[j].col = (int32_t)(c0 + j);
+            }
+            qsort(cand, (size_t)n, sizeof(hgo_cand), cmp_cand);
+            int keep = n < top_k ? (int)n : top_k;
+            int32_t *cols = (int32_t *)malloc(sizeof(int32_t) * (size_t)keep);
+            for (int i = 0; i < keep; ++i) cols[i] = cand[i].col;
+            qsort(cols, (size_t)keep, sizeof(int32_t), cmp_int32); /* back to token order */
+            double mx = (double)cand[0].val;
+            double lt = 0.0;
+            for (int i = 0; i < keep; ++i) {
+                int r = r0;
+                while (!(cols[i] >= pre[r] && cols[i] < pre[r + 1])) ++r; /* the range holding this column */
+                int64_t tok = ranges[r].begin + (cols[i] - pre[r]);
+                out_sel[i] = (int32_t)tok;
+                double w = exp((double)logits[(int64_t)h * ltok + cols[i]] - mx);
+                lt += w;
+                int64_t voff = kv_row(p, ranges[r].seq, h, tok);
+                for (int c = 0; c < p->d; ++c) dst[c] += w * load_elem(p->v, voff + c, p->dtype);
+            }
+            m[gh] = mx;
+            l[gh] = lt;
+            free(cols);
+            free(cand);
+        }
+    }
+    free(pre);
     return 0;
 }
 

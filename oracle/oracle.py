@@ -68,6 +68,9 @@ def _load():
         lib.hgo_attn_merge.argtypes = [dp, dp, dp, dp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, dp, dp]
         lib.hgo_attn_concat.argtypes = [P, ctypes.POINTER(_Range), ctypes.c_int32, dp, ctypes.c_int]
         lib.hgo_attn_logits.argtypes = [P, ctypes.POINTER(_Range), ctypes.c_int32, dp, ctypes.c_int]
+        lib.hgo_attn_select.argtypes = [P, ctypes.POINTER(_Range), ctypes.c_int32, dp, dp, ctypes.c_int32, ctypes.c_int32,
+                                        dp, dp, dp, dp]
+        lib.hgo_attn_select.restype = ctypes.c_int
         for f in (lib.hgo_attn_full, lib.hgo_attn_partial, lib.hgo_attn_merge, lib.hgo_attn_concat, lib.hgo_attn_logits,
                   lib.hgo_max_threads):
             f.restype = ctypes.c_int
@@ -187,3 +190,25 @@ def attn_logits(q, k, v, seq_lens, scale, ranges, nthreads: int = 0):
     _check(_load().hgo_attn_logits(ctypes.byref(prob), arr, len(ranges), out.ctypes.data, nthreads), "attn_logits")
     del keep
     return out
+
+
+def attn_select(q, k, v, seq_lens, scale, ranges, logits, group_ptr, top_k):
+    """Post-QK^T selection on GIVEN fp32 logits [Hq, ltok]: per (group, head) keep the top_k
+    logits (ties to the lower column) and fold them with their V rows into (m, l, O).
+    Returns (sel int32 [G,Hq,top_k] token positions ascending, -1 padded; m, l [G,Hq]; o [G,Hq,d])."""
+    prob, keep = _problem(q, k, v, seq_lens, scale)
+    lg = np.ascontiguousarray(logits, dtype=np.float32)
+    gp = np.ascontiguousarray(group_ptr, dtype=np.int32)
+    ltok = sum(int(e) - int(b) for (_, b, e) in ranges)
+    if lg.shape != (prob.Hq, ltok):
+        raise ValueError("logits must be [Hq, ltok]")
+    G = gp.size - 1
+    sel = np.full((G, prob.Hq, top_k), -1, dtype=np.int32)
+    m = np.zeros((G, prob.Hq), dtype=np.float64)
+    l = np.zeros((G, prob.Hq), dtype=np.float64)
+    o = np.zeros((G, prob.Hq, prob.d), dtype=np.float64)
+    arr = _ranges(ranges)
+    _check(_load().hgo_attn_select(ctypes.byref(prob), arr, len(ranges), lg.ctypes.data, gp.ctypes.data, G, int(top_k),
+                                   sel.ctypes.data, m.ctypes.data, l.ctypes.data, o.ctypes.data), "attn_select")
+    del keep
+    return sel, m, l, o

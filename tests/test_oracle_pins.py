@@ -427,3 +427,58 @@ def test_logits_match_exact_dot_products_and_rebuild_the_attention():
         s1 = np.concatenate([lg[h, 17:19], lg[h, 0:5]])
         p1 = scipy.special.softmax(s1)
         assert np.allclose(p1 @ v64[1, h // G, :7], full[1, h], rtol=0, atol=1e-13)
+
+
+# ---- Post-QK^T selection -------------------------------------------------------------------------
+
+
+def test_select_matches_python_sort_and_definition():
+    """Top-k by Python's sort on (-value, column) -- an independent routine -- and the triple over
+    the kept tokens written out with fsum.  Catches: wrong tie-break, wrong column->token map
+    across ranges, selection over the wrong group, m not the kept maximum."""
+    B, Hq, Hkv, N, d = 2, 4, 2, 40, 4
+    q, k, v = _case(22, B, Hq, Hkv, N, d, np.float16)
+    seq_lens = [40, 25]
+    ranges = [(0, 5, 20), (0, 30, 40), (1, 0, 0), (1, 3, 25)]
+    gp = [0, 2, 4]
+    rng = RNG(23)
+    ltok = 15 + 10 + 0 + 22
+    lg = np.round(rng.standard_normal((Hq, ltok)) * 4).astype(np.float32) / 4  # many exact ties
+    G = Hq // Hkv
+    for top_k in (1, 3, 10, 100):
+        sel, m, l, o = oracle.attn_select(q, k, v, seq_lens, 0.5, ranges, lg, gp, top_k)
+        for g, (c0, c1, toks, b) in enumerate([(0, 25, list(range(5, 20)) + list(range(30, 40)), 0),
+                                               (25, 47, list(range(3, 25)), 1)]):
+            for h in range(Hq):
+                order = sorted(range(c0, c1), key=lambda c: (-float(lg[h, c]), c))[:top_k]
+                kept = sorted(order)
+                want_tok = [toks[c - c0] for c in kept]
+                got = [t for t in sel[g, h] if t >= 0]
+                assert got == want_tok
+                assert list(sel[g, h][len(got):]) == [-1] * (top_k - len(got))
+                mx = max(float(lg[h, c]) for c in kept)
+                w = [math.exp(float(lg[h, c]) - mx) for c in kept]
+                assert m[g, h] == mx and abs(l[g, h] - math.fsum(w)) < 1e-13
+                for cc in range(d):
+                    ref = math.fsum(wi * float(v[b, h // G, t, cc]) for wi, t in zip(w, want_tok))
+                    assert abs(o[g, h, cc] - ref) < 1e-13
+
+
+def test_select_everything_equals_partial_and_select_one_is_argmax():
+    """top_k >= group size keeps every token: with the oracle's own logits it reproduces the
+    partial statistics of the group's ranges merged; top_k = 1 returns the V row of the argmax."""
+    B, Hq, Hkv, N, d = 1, 2, 1, 30, 8
+    q, k, v = _case(24, B, Hq, Hkv, N, d)
+    ranges = [(0, 0, 12), (0, 12, 30)]
+    lg64 = oracle.attn_logits(q, k, v, [30], 0.3, ranges)
+    lg = lg64.astype(np.float32)
+    sel, m, l, o = oracle.attn_select(q, k, v, [30], 0.3, ranges, lg, [0, 2], 64)
+    full, lse = oracle.attn_full(q, k, v, [30], 0.3)
+    assert [list(sel[0, h][:30]) for h in range(Hq)] == [list(range(30))] * Hq
+    assert np.abs(o[0] / l[0][:, None] - full[0]).max() < 1e-6  # fp32 rounding of the logits
+    assert np.abs(m[0] + np.log(l[0]) - lse[0]).max() < 1e-6
+    sel1, m1, l1, o1 = oracle.attn_select(q, k, v, [30], 0.3, ranges, lg, [0, 2], 1)
+    for h in range(Hq):
+        j = int(np.argmax(lg[h]))
+        assert sel1[0, h, 0] == j and l1[0, h] == 1.0 and m1[0, h] == float(lg[h, j])
+        assert np.array_equal(o1[0, h], v[0, 0, j].astype(np.float64))
