@@ -176,6 +176,27 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
                          size_t ws_bytes, void *stream);
 
 /*
+ * hg_attn_select -- Post-QK^T token selection (Section 4.3.1; Section 4.5): the executor that
+ * holds the offloaded tokens has computed the logits of ALL of them; per (group, query head) only
+ * the top_k highest are kept, and those logits with their V rows are folded into one (m, l, O)
+ * triple that hg_attn_merge combines with the triples of the resident tokens.
+ *
+ *   ranges, logits, group_ptr   as for hg_attn_concat (a group = the offloaded ranges of one sequence).
+ *   top_k    1 .. 4096.  A group with fewer tokens keeps all of them.  The decision is taken on
+ *            the fp32 logits as given; ties at the threshold go to the lower column (earlier
+ *            range in the table, earlier token).
+ *   sel      DEVICE int32 [n_groups][n_q_heads][top_k] or NULL: the kept TOKEN positions of each
+ *            head in ascending column order, padded with -1.
+ *   m, l     DEVICE [n_groups][n_q_heads] fp32;  o  DEVICE [n_groups][n_q_heads][head_dim] fp32.
+ *            An empty group yields (-inf, 0, 0).
+ *   Reads the logits (about five passes) and the kept V rows only.
+ */
+hg_status hg_attn_select_workspace_size(int32_t n_ranges, int32_t n_groups, size_t *bytes);
+hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, const float *logits,
+                         const int32_t *group_ptr, int32_t n_groups, int32_t top_k, int32_t *sel, float *m, float *l,
+                         float *o, void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * Host-side planning, exposed for inspection and tests.  The tokens of all ranges, repeated for
  * every stream (KV head x chunk of query heads sharing it), form one linear work space that is
  * cut into equal spans, one workgroup each, so that every workgroup streams the same number of

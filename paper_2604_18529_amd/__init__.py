@@ -11,6 +11,7 @@ _API = (
     "hg_attn_full",
     "hg_attn_logits",
     "hg_attn_concat",
+    "hg_attn_select",
     "hg_attn_plan",
     "hg_attn_set_tile_tokens",
     "hg_attn_profile_start",

@@ -623,6 +623,79 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
     return launch_status("concat reduce kernel");
 }
 
+// The selection call records nothing: its workspace only holds the range and group tables when
+// they do not fit in the kernel arguments.
+size_t select_ws_bytes(int32_t n_ranges, int32_t n_groups)
+{
+    return logits_ws_bytes(n_ranges) + merge_ws_bytes(n_groups);
+}
+
+hg_status hg_attn_select_workspace_size(int32_t n_ranges, int32_t n_groups, size_t *bytes)
+{
+    if (!bytes) return HG_ERR_NULL;
+    if (n_ranges < 0 || n_groups < 0 || n_groups > 65535) return HG_ERR_SHAPE;
+    *bytes = select_ws_bytes(n_ranges, n_groups);
+    return HG_OK;
+}
+
+hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, const float *logits,
+                         const int32_t *group_ptr, int32_t n_groups, int32_t top_k, int32_t *sel, float *m, float *l,
+                         float *o, void *workspace, size_t ws_bytes, void *stream_v)
+{
+    hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = check_ranges(desc, ranges, n_ranges);
+    if (st != HG_OK) return st;
+    if (top_k < 1 || top_k > kMaxTopK) return HG_ERR_SHAPE;
+    st = check_concat_groups(ranges, n_ranges, group_ptr, n_groups);
+    if (st != HG_OK) return st;
+    if (n_groups == 0) return HG_OK;
+    if (!m || !l || !o) return HG_ERR_NULL;
+    Plan p;
+    st = make_plan(desc, ranges, n_ranges, p);
+    if (st != HG_OK) return st;
+    if (p.ws.ltok > 0 && !logits) return HG_ERR_NULL;
+    st = check_workspace(workspace, ws_bytes, select_ws_bytes(n_ranges, n_groups));
+    if (st != HG_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char *ws = static_cast<char *>(workspace);
+
+    SelectArgs sa;
+    std::memset(&sa, 0, sizeof(sa));
+    p.off_tab = 0;
+    st = stage_table(p, n_ranges, ws, stream, sa.tab);
+    if (st != HG_OK) return st;
+    st = stage_groups(group_ptr, n_groups, reinterpret_cast<int32_t *>(ws + logits_ws_bytes(n_ranges)), stream, sa.groups);
+    if (st != HG_OK) return st;
+    sa.logits = logits;
+    sa.v = desc->v;
+    sa.stride_b = desc->stride_b;
+    sa.stride_h = desc->stride_h;
+    sa.stride_t = desc->stride_t;
+    sa.ltok = p.ws.ltok;
+    sa.n_q_heads = desc->n_q_heads;
+    sa.group = desc->n_q_heads / desc->n_kv_heads;
+    sa.top_k = top_k;
+    sa.sel = sel;
+    sa.m = m;
+    sa.l = l;
+    sa.o = o;
+    dim3 grid((unsigned)n_groups, (unsigned)desc->n_q_heads);
+    const bool f16 = desc->dtype == HG_F16;
+    if (desc->head_dim == 128) {
+        if (f16)
+            hipLaunchKernelGGL((hg_select_kernel<Traits<128, true>>), grid, dim3(kSelectBlock), 0, stream, sa);
+        else
+            hipLaunchKernelGGL((hg_select_kernel<Traits<128, false>>), grid, dim3(kSelectBlock), 0, stream, sa);
+    } else {
+        if (f16)
+            hipLaunchKernelGGL((hg_select_kernel<Traits<64, true>>), grid, dim3(kSelectBlock), 0, stream, sa);
+        else
+            hipLaunchKernelGGL((hg_select_kernel<Traits<64, false>>), grid, dim3(kSelectBlock), 0, stream, sa);
+    }
+    return launch_status("selection kernel");
+}
+
 hg_status hg_attn_merge_workspace_size(int32_t n_groups, size_t *bytes)
 {
     if (!bytes) return HG_ERR_NULL;

@@ -145,6 +145,20 @@ struct ConcatReduceArgs {
     RangeTable tab;
 };
 
+constexpr int kSelectBlock = 1024;  // threads of the selection kernel (16 waves)
+constexpr int kMaxTopK = 4096;      // kept tokens per (group, head): their columns and logits sit in LDS
+
+struct SelectArgs {
+    const float *logits;  // [Hq][ltok], natural-log units
+    const void *v;
+    int64_t stride_b, stride_h, stride_t;  // elements
+    int32_t ltok, n_q_heads, group, top_k;
+    int32_t *sel;         // [n_groups][Hq][top_k] or NULL
+    float *m, *l, *o;     // [n_groups][Hq](..[D])
+    GroupTable groups;
+    RangeTable tab;
+};
+
 struct RangeChunk {
     RangeEntry e[kUploadRanges];
 };
@@ -1079,6 +1093,217 @@ __global__ __launch_bounds__(kReduceBlock) void hg_concat_reduce_kernel(const Co
     }
     a.out[gh * D + c] = lt > 0.f ? ot / lt : 0.f;
     if (c == 0 && a.lse) a.lse[gh] = lt > 0.f ? mx * kLn2 + logf(lt) : -INFINITY;
+}
+
+// ---- Post-QK^T selection: top-k logits of a group, folded with their V rows into (m, l, O) ------
+//
+// One workgroup of 16 waves per (group, query head).
+//   1. radix select on order-preserving integer keys of the fp32 logits: four 8-bit passes, each
+//      a histogram over the elements that still match the prefix, find the key T of the k-th
+//      largest logit and how many elements equal to T are to be kept (ties go to lower columns);
+//   2. one ordered sweep compacts the kept columns into LDS in ascending (token) order: a kept
+//      element's slot is (#greater before it) + min(#equal before it, k_eq), which a single
+//      packed block scan provides;
+//   3. the kept logits give m and the weights exp(s - m); the 16 waves gather the kept V rows
+//      (four rows per wave load, 16 lanes per row as in the streaming kernel) and sum p.v.
+
+__device__ __forceinline__ uint32_t order_key(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // larger float <=> larger key
+}
+
+// Exclusive scan of v over the 1024 threads of the workgroup; total receives the sum.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *s_wave, uint32_t &total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t t = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += t;
+    }
+    if (lane == 63) s_wave[wave] = inc;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kSelectBlock / 64; ++w) {
+        const uint32_t t = s_wave[w];
+        before += w < wave ? t : 0u;
+        all += t;
+    }
+    __syncthreads();  // s_wave is reused by the next call
+    total = all;
+    return before + inc - v;
+}
+
+template <typename TR>
+__global__ __launch_bounds__(kSelectBlock) void hg_select_kernel(const SelectArgs a)
+{
+    constexpr int D = TR::D, EPL = TR::EPL, NV = TR::NV, EPV = TR::EPV, ES = TR::ES;
+    constexpr int NW = kSelectBlock / 64;
+    __shared__ uint32_t s_hist[256];
+    __shared__ uint32_t s_wave[NW];
+    __shared__ uint32_t s_prefix, s_krem;
+    __shared__ int32_t s_cols[kMaxTopK];   // kept columns, later their token positions
+    __shared__ float s_vals[kMaxTopK];     // kept logits, later their weights
+    __shared__ float s_red[NW];
+    __shared__ float s_acc[NW][D];
+
+    const int gi = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r0 = group_entry(a.groups, gi), r1 = group_entry(a.groups, gi + 1);
+    const int c0 = table_entry(a.tab, r0).pre, c1 = table_entry(a.tab, r1).pre;
+    const int n = c1 - c0;
+    const int keep = n < a.top_k ? n : a.top_k;
+    const int64_t gh = (int64_t)gi * a.n_q_heads + h;
+    const float *row = a.logits + (int64_t)h * a.ltok + c0;
+
+    if (a.sel)
+        for (int j = tid + keep; j < a.top_k; j += kSelectBlock) a.sel[gh * a.top_k + j] = -1;
+    if (n == 0) {
+        if (tid < D) a.o[gh * D + tid] = 0.f;
+        if (tid == 0) {
+            a.m[gh] = -INFINITY;
+            a.l[gh] = 0.f;
+        }
+        return;
+    }
+
+    // 1. radix select
+    uint32_t prefix = 0, mask = 0, krem = (uint32_t)keep;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) s_hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < n; i += kSelectBlock) {
+            const uint32_t u = order_key(row[i]);
+            if ((u & mask) == prefix) atomicAdd(&s_hist[(u >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t cum = 0;
+            int dsel = 0;
+            for (int d = 255; d >= 0; --d) {
+                const uint32_t cnt = s_hist[d];
+                if (cum + cnt >= krem) {
+                    dsel = d;
+                    break;
+                }
+                cum += cnt;
+            }
+            s_prefix = prefix | ((uint32_t)dsel << shift);
+            s_krem = krem - cum;
+        }
+        __syncthreads();
+        prefix = s_prefix;
+        krem = s_krem;
+        mask |= 0xffu << shift;
+    }
+    const uint32_t T = prefix, k_eq = krem;  // keep every key > T and the first k_eq keys == T
+
+    // 2. ordered compaction of the kept columns
+    uint32_t run_gt = 0, run_eq = 0;
+    for (int base = 0; base < n; base += kSelectBlock) {
+        const int i = base + tid;
+        const float x = i < n ? row[i] : 0.f;
+        const uint32_t u = order_key(x);
+        const uint32_t gt = (i < n && u > T) ? 1u : 0u, eq = (i < n && u == T) ? 1u : 0u;
+        uint32_t total;
+        const uint32_t scan = block_exclusive_scan(gt | (eq << 16), s_wave, total);
+        const uint32_t gt_before = run_gt + (scan & 0xffffu), eq_before = run_eq + (scan >> 16);
+        if (gt || (eq && eq_before < k_eq)) {
+            const uint32_t pos = gt_before + (eq_before < k_eq ? eq_before : k_eq);
+            s_cols[pos] = c0 + i;
+            s_vals[pos] = x;
+        }
+        run_gt += total & 0xffffu;
+        run_eq += total >> 16;
+    }
+    __syncthreads();
+
+    // 3a. m = max kept logit; weights; l
+    float mx = -INFINITY;
+    for (int j = tid; j < keep; j += kSelectBlock) mx = fmaxf(mx, s_vals[j]);
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1) mx = fmaxf(mx, __shfl_xor(mx, step, 64));
+    if (lane == 0) s_red[wave] = mx;
+    __syncthreads();
+    mx = s_red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) mx = fmaxf(mx, s_red[w]);
+    __syncthreads();
+    float lt = 0.f;
+    const int seq = table_entry(a.tab, r0).seq;
+    for (int j = tid; j < keep; j += kSelectBlock) {
+        const float w = fast_exp2((s_vals[j] - mx) * kLog2e);
+        lt += w;
+        // column -> token position: the range of the group that holds the column
+        const int col = s_cols[j];
+        int lo = r0, hi = r1;  // pre[lo] <= col < pre[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (table_entry(a.tab, mid).pre <= col)
+                lo = mid;
+            else
+                hi = mid;
+        }
+        const RangeEntry e = table_entry(a.tab, lo);
+        const int tok = e.begin + (col - e.pre);
+        s_cols[j] = tok;
+        s_vals[j] = w;
+        if (a.sel) a.sel[gh * a.top_k + j] = tok;
+    }
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1) lt += __shfl_xor(lt, step, 64);
+    if (lane == 0) s_red[wave] = lt;
+    __syncthreads();
+    lt = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) lt += s_red[w];
+
+    // 3b. gather the kept V rows: lane group grp of wave `wave` takes kept entries
+    //     4*wave + grp, + 64, + 128, ...
+    const int sub = lane & 15, grp = lane >> 4;
+    const int hk = h / a.group;
+    const char *vbase = static_cast<const char *>(a.v) + ((int64_t)seq * a.stride_b + (int64_t)hk * a.stride_h) * ES;
+    const int64_t row_bytes = a.stride_t * ES;
+    float acc[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+    for (int j = 4 * wave + grp; j < keep; j += 4 * NW) {
+        const float w = s_vals[j];
+        const char *vrow = vbase + (int64_t)s_cols[j] * row_bytes;
+        float vf[EPL];
+#pragma unroll
+        for (int jj = 0; jj < NV; ++jj) {
+            typename TR::Raw raw = TR::template load<false>(vrow, sub, jj);
+            TR::widen(raw, &vf[jj * EPV]);
+        }
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[i] = fmaf(w, vf[i], acc[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+        acc[i] += __shfl_xor(acc[i], 16, 64);
+        acc[i] += __shfl_xor(acc[i], 32, 64);
+    }
+    if (grp == 0) {
+#pragma unroll
+        for (int jj = 0; jj < NV; ++jj)
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) s_acc[wave][TR::vec_offset(sub, jj) + i] = acc[jj * EPV + i];
+    }
+    __syncthreads();
+    if (tid < D) {
+        float ot = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) ot += s_acc[w][tid];
+        a.o[gh * D + tid] = ot;
+    }
+    if (tid == 0) {
+        a.m[gh] = mx;
+        a.l[gh] = lt;
+    }
 }
 
 // ---- table upload (host tables reach the device through kernel arguments only) ----------------

@@ -76,6 +76,8 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_logits.argtypes = [D, R, i32, vp, vp, sz, vp]
     lib.hg_attn_concat_workspace_size.argtypes = [D, R, i32, i32, ctypes.POINTER(sz)]
     lib.hg_attn_concat.argtypes = [D, R, i32, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.hg_attn_select_workspace_size.argtypes = [i32, i32, ctypes.POINTER(sz)]
+    lib.hg_attn_select.argtypes = [D, R, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.hg_attn_full_workspace_size.argtypes = [D, ctypes.POINTER(sz)]
     lib.hg_attn_full.argtypes = [D, vp, vp, vp, sz, vp]
     lib.hg_attn_plan.argtypes = [D, R, i32, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_int64)]
@@ -87,7 +89,7 @@ def load_library() -> ctypes.CDLL:
         "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_merge_workspace_size", "hg_attn_merge",
         "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_tile_tokens",
         "hg_attn_profile_start", "hg_attn_profile_stop", "hg_attn_calibration_copy",
-        "hg_attn_logits_workspace_size", "hg_attn_logits", "hg_attn_concat_workspace_size", "hg_attn_concat",
+        "hg_attn_logits_workspace_size", "hg_attn_logits", "hg_attn_select_workspace_size", "hg_attn_select", "hg_attn_concat_workspace_size", "hg_attn_concat",
     ):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -375,3 +377,42 @@ def hg_attn_concat(q, k, v, seq_lens, ranges, logits, group_ptr, scale=None, *, 
     _check(st, "hg_attn_concat")
     del keep
     return out, lse
+
+
+def hg_attn_select(q, k, v, seq_lens, ranges, logits, group_ptr, top_k, scale=None, *, want_sel=True, workspace=None,
+                   stream=None, desc=None):
+    """Post-QK^T selection: per (group, head) keep the top_k logits and fold them with their V rows.
+    Returns (sel int32 [G,Hq,top_k] or None, m [G,Hq], l [G,Hq], o [G,Hq,d])."""
+    lib = load_library()
+    if desc is None:
+        desc, keep = make_desc(q, k, v, seq_lens, scale)
+    else:
+        keep = None
+    packed = pack_ranges(ranges)
+    R = _n_ranges(packed)
+    gp = np.ascontiguousarray(group_ptr, dtype=np.int32)
+    if gp.ndim != 1 or gp.size < 1:
+        raise ValueError("group_ptr must be CSR offsets [n_groups+1]")
+    G = gp.size - 1
+    if logits.dtype != torch.float32 or not logits.is_contiguous() or logits.dim() != 2 or logits.shape[0] != q.shape[1]:
+        raise ValueError("logits must be contiguous fp32 [Hq, ltok]")
+    if logits.shape[1] != sum(packed[i].end - packed[i].begin for i in range(R)):
+        raise ValueError("logits do not match the range table")
+    dev = q.device
+    Hq, d = q.shape[1], q.shape[2]
+    sel = torch.empty((G, Hq, int(top_k)), dtype=torch.int32, device=dev) if want_sel else None
+    m = torch.empty((G, Hq), dtype=torch.float32, device=dev)
+    l = torch.empty((G, Hq), dtype=torch.float32, device=dev)
+    o = torch.empty((G, Hq, d), dtype=torch.float32, device=dev)
+    if workspace is None:
+        sz = ctypes.c_size_t()
+        _check(lib.hg_attn_select_workspace_size(R, G, ctypes.byref(sz)), "hg_attn_select_workspace_size")
+        workspace, ws_bytes = _workspace(sz.value, dev, None)
+    else:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        st = lib.hg_attn_select(ctypes.byref(desc), packed, R, _ptr(logits), gp.ctypes.data, G, int(top_k), _ptr(sel),
+                                _ptr(m), _ptr(l), _ptr(o), _ptr(workspace), ws_bytes, _stream_handle(stream))
+    _check(st, "hg_attn_select")
+    del keep
+    return sel, m, l, o

@@ -1,0 +1,158 @@
+"""GPU parity of Post-QK^T selection (hg_attn_select): which tokens are kept is integer work and
+must match the oracle bit for bit when both decide on the same fp32 logits; the folded triple
+matches to the floating-point bars."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_18529_amd as hg
+from paper_2604_18529_amd import workloads as W
+
+from parity_utils import check_out, check_triples, kv_np, to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _seeded_logits(hq, ltok, seed, ties):
+    """fp32 logits as an INPUT (seeded, not produced by either side).  `ties` quantises them so
+    that many values collide exactly and the tie-break is exercised."""
+    rng = np.random.RandomState(seed)
+    lg = (rng.standard_normal((hq, ltok)) * 3).astype(np.float32)
+    if ties:
+        lg = (np.round(lg * 8) / 8).astype(np.float32)
+    return lg
+
+
+def _check_select(w, ranges, gp, lg_np, top_k, what):
+    lg = torch.from_numpy(lg_np).to(DEV)
+    sel, m, l, o = hg.hg_attn_select(w.q, w.k, w.v, w.seq_lens, ranges, lg, gp, top_k, w.scale)
+    rsel, rm, rl, ro = oracle.attn_select(to_np(w.q), *kv_np(w), w.seq_lens, w.scale, ranges, lg_np, gp, top_k)
+    assert np.array_equal(to_np(sel), rsel), what + ": kept tokens differ"
+    m_g = to_np(m).astype(np.float64)
+    fin = np.isfinite(rm)
+    assert np.array_equal(m_g[fin], rm[fin]), what + ": m must be the kept maximum exactly"
+    check_triples(m, l, o, rm, rl, ro, what)
+    return sel, m, l, o
+
+
+@pytest.mark.parametrize("ties", [False, True])
+@pytest.mark.parametrize("top_k", [1, 7, 128, 1000, 4096])
+def test_selection_is_bit_exact_on_given_logits(top_k, ties):
+    spec = W.WorkloadSpec("sel", 3, 4, 2, 128, "f16", 100, 6000, "none", seed=51)
+    w = W.make_workload(spec, DEV)
+    w.seq_lens[:] = [6000, 100, 2500]
+    ranges = [(0, 0, 2500), (0, 2500, 2500), (0, 3000, 6000), (1, 0, 100), (2, 10, 2500)]
+    gp = [0, 3, 4, 5]
+    ltok = sum(e - s for _, s, e in ranges)
+    _check_select(w, ranges, gp, _seeded_logits(4, ltok, 52 + top_k, ties), top_k, "k=%d ties=%s" % (top_k, ties))
+
+
+@pytest.mark.parametrize("dtype,d,group", [("f16", 128, 8), ("f32", 64, 1), ("f16", 64, 2), ("f32", 128, 3)])
+def test_every_storage_type(dtype, d, group):
+    spec = W.WorkloadSpec("selinst", 2, 2 * group, 2, d, dtype, 300, 900, "ratios", 2, seed=53)
+    w = W.make_workload(spec, DEV)
+    ltok = sum(e - s for _, s, e in w.ranges)
+    _check_select(w, w.ranges, w.group_ptr, _seeded_logits(2 * group, ltok, 54, True), 50, "%s d=%d G=%d" % (dtype, d, group))
+
+
+def test_edge_groups():
+    """An empty group, a group of empty ranges, a one-token group, all-equal logits (the first
+    top_k columns win), and more ranges/groups than fit in kernel arguments."""
+    spec = W.WorkloadSpec("seledge", 3, 2, 2, 128, "f16", 0, 500, "none", seed=55)
+    w = W.make_workload(spec, DEV)
+    w.seq_lens[:] = [500, 0, 1]
+    ranges = [(0, 0, 0), (0, 7, 7), (2, 0, 1), (0, 0, 500)]
+    gp = [0, 2, 2, 3, 4]
+    lg = _seeded_logits(2, 501, 56, True)
+    lg[:, 1:] = 2.5  # group 3: every logit equal
+    sel, m, l, o = _check_select(w, ranges, gp, lg, 16, "edge")
+    assert to_np(sel[3, 0]).tolist() == list(range(16))
+    assert np.all(to_np(sel[0]) == -1) and np.all(to_np(sel[1]) == -1)
+    spec = W.WorkloadSpec("selmany", 2, 4, 4, 64, "f16", 3000, 3000, "none", seed=57)
+    w = W.make_workload(spec, DEV)
+    ranges, gp = [], [0]
+    for b in range(2):
+        for i in range(300):
+            ranges.append((b, 10 * i, 10 * i + 9))
+            gp.append(len(ranges))
+    _check_select(w, ranges, gp, _seeded_logits(4, 2 * 300 * 9, 58, False), 4, "many")
+
+
+def test_post_qk_selection_end_to_end():
+    """The whole Post-QK^T flow on the GPU: logits of the offloaded (old) tokens, top-k, triple,
+    merge with the resident (recent) tokens' triple.  The oracle runs the same flow on its own
+    logits; kept sets may differ only where logits are within rounding of the threshold, and the
+    merged outputs agree to the output bar.  With top_k >= the offloaded count the flow is exact
+    attention."""
+    spec = W.WorkloadSpec("postqk", 2, 8, 2, 128, "f16", 3000, 5000, "none", seed=59)
+    w = W.make_workload(spec, DEV)
+    old = [(b, 0, int(0.8 * n)) for b, n in enumerate(w.seq_lens)]
+    new = [(b, int(0.8 * n), int(n)) for b, n in enumerate(w.seq_lens)]
+    gp_old = np.arange(spec.batch + 1, dtype=np.int32)
+    qn = to_np(w.q)
+    kn, vn = kv_np(w)
+    lg_ref = oracle.attn_logits(qn, kn, vn, w.seq_lens, w.scale, old)
+    pm, pl, po = oracle.attn_partial(qn, kn, vn, w.seq_lens, w.scale, new)
+    m2, l2, o2 = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, new, w.scale)
+    lg = hg.hg_attn_logits(w.q, w.k, w.v, w.seq_lens, old, w.scale)
+    merge_gp = np.arange(0, 2 * spec.batch + 1, 2, dtype=np.int32)
+    idx = torch.arange(2 * spec.batch, device=DEV).reshape(2, spec.batch).t().reshape(-1)
+    idn = np.arange(2 * spec.batch).reshape(2, spec.batch).T.reshape(-1)
+    for top_k in (128, 4096):
+        sel, m1, l1, o1 = hg.hg_attn_select(w.q, w.k, w.v, w.seq_lens, old, lg, gp_old, top_k, w.scale)
+        out, lse = hg.hg_attn_merge(torch.cat([m1, m2])[idx].contiguous(), torch.cat([l1, l2])[idx].contiguous(),
+                                    torch.cat([o1, o2])[idx].contiguous(), merge_gp)
+        rsel, rm, rl, ro = oracle.attn_select(qn, kn, vn, w.seq_lens, w.scale, old, lg_ref.astype(np.float32), gp_old, top_k)
+        ref, rlse = oracle.attn_merge(np.concatenate([rm, pm])[idn], np.concatenate([rl, pl])[idn],
+                                      np.concatenate([ro, po])[idn], merge_gp)
+        check_out(out, lse, ref, rlse, "post-qk k=%d" % top_k)
+        # kept sets: identical except for tokens whose logit is within rounding of the threshold
+        sel_np = to_np(sel)
+        col0 = 0
+        for b in range(spec.batch):
+            n_old = old[b][2]
+            for h in range(spec.n_q_heads):
+                got, want = set(sel_np[b, h][sel_np[b, h] >= 0].tolist()), set(rsel[b, h][rsel[b, h] >= 0].tolist())
+                assert len(got) == len(want) == min(top_k, n_old)
+                row = lg_ref[h, col0:col0 + n_old]
+                thr = np.sort(row)[-min(top_k, n_old)]
+                for t in got ^ want:
+                    assert abs(row[t] - thr) <= 1e-4
+            col0 += n_old
+        if top_k >= max(r[2] for r in old):
+            exact, elsE = oracle.attn_full(qn, kn, vn, w.seq_lens, w.scale)
+            check_out(out, lse, exact, elsE, "post-qk keeps everything")
+
+
+def test_bad_arguments():
+    spec = W.WorkloadSpec("selerr", 1, 2, 2, 64, "f16", 100, 100, "none", seed=60)
+    w = W.make_workload(spec, DEV)
+    lg = torch.zeros((2, 100), dtype=torch.float32, device=DEV)
+    for k in (0, 4097):
+        with pytest.raises(hg.HgError) as ei:
+            hg.hg_attn_select(w.q, w.k, w.v, w.seq_lens, w.ranges, lg, [0, 1], k, w.scale)
+        assert ei.value.status == -2
+
+
+def test_full_size_million_token_group():
+    """Benchmark shape: 64 query heads over 8 KV heads, one group of 1,048,576 offloaded tokens,
+    top_k = 1024; sampled heads against the oracle on seeded logits."""
+    spec = W.WORKLOADS[4]
+    w = W.make_workload(spec, DEV)
+    n = int(w.seq_lens[0])
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(61)
+    lg = (torch.randn((spec.n_q_heads, n), generator=gen, device=DEV, dtype=torch.float32) * 2)
+    lg = (lg * 64).round() / 64  # exact ties
+    ranges, gp = [(0, 0, n)], [0, 1]
+    sel, m, l, o = hg.hg_attn_select(w.q, w.k, w.v, w.seq_lens, ranges, lg, gp, 1024, w.scale)
+    G = spec.n_q_heads // spec.n_kv_heads
+    for h in (0, 13, 63):
+        qs = to_np(w.q[:, h:h + 1])
+        ks = to_np(w.k[:, h // G:h // G + 1])
+        vs = to_np(w.v[:, h // G:h // G + 1])
+        rsel, rm, rl, ro = oracle.attn_select(qs, ks, vs, [n], w.scale, ranges, to_np(lg[h:h + 1]), gp, 1024)
+        assert np.array_equal(to_np(sel[0, h]), rsel[0, 0])
+        check_triples(m[:, h:h + 1], l[:, h:h + 1], o[:, h:h + 1], rm, rl, ro, "1M head %d" % h)
