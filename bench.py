@@ -116,6 +116,35 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
     logits_ms, _ = _time_steps(logits_step, max(steps // 2, 1), max(warmup // 2, 1), torch)
     concat_ms, _ = _time_steps(concat_step, max(steps // 2, 1), max(warmup // 2, 1), torch)
 
+    # Post-QK^T flow (the paper's default selection mode): logits of the offloaded 80 % of every
+    # cache, top-128 per (sequence, head), triple of the kept tokens; the resident 20 % streamed
+    # as usual; one merge
+    old = [(b, 0, int(0.8 * n)) for b, n in enumerate(w.seq_lens)]
+    new = [(b, int(0.8 * n), int(n)) for b, n in enumerate(w.seq_lens)]
+    p_old, p_new = hg.pack_ranges(old), hg.pack_ranges(new)
+    lg_old = torch.empty((Hq, sum(e - b for (_, b, e) in old)), dtype=torch.float32, device=dev)
+    gp_old = list(range(spec.batch + 1))
+    merge_gp = list(range(0, 2 * spec.batch + 1, 2))
+    order = torch.arange(2 * spec.batch, device=dev).reshape(2, spec.batch).t().reshape(-1)
+    nws = torch.empty(max(binding.hg_attn_partial_workspace_size(desc, p_new), 256), dtype=torch.uint8, device=dev)
+    top_k = 128
+
+    def postqk_logits():
+        hg.hg_attn_logits(w.q, w.k, w.v, w.seq_lens, p_old, w.scale, logits=lg_old, desc=desc)
+
+    def postqk_select():
+        return hg.hg_attn_select(w.q, w.k, w.v, w.seq_lens, p_old, lg_old, gp_old, top_k, w.scale, want_sel=False, desc=desc)
+
+    def postqk_rest():
+        _, m1, l1, o1 = postqk_select()
+        m2, l2, o2 = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, p_new, w.scale, workspace=nws, desc=desc)
+        hg.hg_attn_merge(torch.cat([m1, m2])[order].contiguous(), torch.cat([l1, l2])[order].contiguous(),
+                         torch.cat([o1, o2])[order].contiguous(), merge_gp, out=out, lse=lse)
+
+    pq_logits_ms, _ = _time_steps(postqk_logits, max(steps // 4, 1), max(warmup // 4, 1), torch)
+    pq_select_ms, _ = _time_steps(postqk_select, max(steps // 4, 1), max(warmup // 4, 1), torch)
+    pq_rest_ms, _ = _time_steps(postqk_rest, max(steps // 4, 1), max(warmup // 4, 1), torch)
+
     kv_bytes = w.kv_bytes
     res = {
         "workload": spec.name,
@@ -137,6 +166,14 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
         "stream_kernel_us": kernel_ms * 1e3,
         "stream_kernel_gbps": kv_bytes / (kernel_ms * 1e-3) / 1e9,
         "host_wall_us_per_step": wall_ms * 1e3,
+        "post_qk_route": {
+            "offloaded_fraction": 0.8,
+            "top_k": top_k,
+            "logits_us": pq_logits_ms * 1e3,
+            "select_us": pq_select_ms * 1e3,
+            "select_resident_merge_us": pq_rest_ms * 1e3,
+            "us": (pq_logits_ms + pq_rest_ms) * 1e3,
+        },
         "concat_route": {
             "logits_us": logits_ms * 1e3,
             "concat_us": concat_ms * 1e3,
@@ -254,6 +291,7 @@ def main():
         "cpu_baseline": cpu,
         "full_path": {"us": head["full_path_us"], "gbps": head["full_path_gbps"]},
         "concat_route": head["concat_route"],
+        "post_qk_route": head["post_qk_route"],
         "other_workloads": others,
         "paper_context": PAPER_CONTEXT,
     }

@@ -1175,24 +1175,29 @@ __global__ __launch_bounds__(kSelectBlock) void hg_select_kernel(const SelectArg
     for (int shift = 24; shift >= 0; shift -= 8) {
         if (tid < 256) s_hist[tid] = 0;
         __syncthreads();
-        for (int i = tid; i < n; i += kSelectBlock) {
-            const uint32_t u = order_key(row[i]);
-            if ((u & mask) == prefix) atomicAdd(&s_hist[(u >> shift) & 255u], 1u);
+        for (int i0 = 0; i0 < n; i0 += 8 * kSelectBlock) {  // eight loads in flight per thread
+            float x[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int i = i0 + j * kSelectBlock + tid;
+                x[j] = row[i < n ? i : n - 1];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t u = order_key(x[j]);
+                if (i0 + j * kSelectBlock + tid < n && (u & mask) == prefix) atomicAdd(&s_hist[(u >> shift) & 255u], 1u);
+            }
         }
         __syncthreads();
-        if (tid == 0) {
-            uint32_t cum = 0;
-            int dsel = 0;
-            for (int d = 255; d >= 0; --d) {
-                const uint32_t cnt = s_hist[d];
-                if (cum + cnt >= krem) {
-                    dsel = d;
-                    break;
-                }
-                cum += cnt;
+        // the digit d with  #(digits > d) < krem <= #(digits >= d):  scan the bins from the top
+        {
+            const uint32_t cnt = tid < 256 ? s_hist[255 - tid] : 0u;
+            uint32_t total;
+            const uint32_t above = block_exclusive_scan(cnt, s_wave, total);
+            if (tid < 256 && above < krem && above + cnt >= krem) {
+                s_prefix = prefix | ((uint32_t)(255 - tid) << shift);
+                s_krem = krem - above;
             }
-            s_prefix = prefix | ((uint32_t)dsel << shift);
-            s_krem = krem - cum;
         }
         __syncthreads();
         prefix = s_prefix;
@@ -1201,20 +1206,34 @@ __global__ __launch_bounds__(kSelectBlock) void hg_select_kernel(const SelectArg
     }
     const uint32_t T = prefix, k_eq = krem;  // keep every key > T and the first k_eq keys == T
 
-    // 2. ordered compaction of the kept columns
+    // 2. ordered compaction of the kept columns; every thread owns kRun consecutive columns of a
+    //    chunk, so one block scan serves kRun * 1024 elements
+    constexpr int kRun = 8;
     uint32_t run_gt = 0, run_eq = 0;
-    for (int base = 0; base < n; base += kSelectBlock) {
-        const int i = base + tid;
-        const float x = i < n ? row[i] : 0.f;
-        const uint32_t u = order_key(x);
-        const uint32_t gt = (i < n && u > T) ? 1u : 0u, eq = (i < n && u == T) ? 1u : 0u;
+    for (int base = 0; base < n; base += kRun * kSelectBlock) {
+        const int i0 = base + kRun * tid;
+        float x[kRun];
+        uint32_t cnt = 0;  // low half: keys > T, high half: keys == T
+#pragma unroll
+        for (int j = 0; j < kRun; ++j) {
+            x[j] = row[i0 + j < n ? i0 + j : n - 1];
+            const uint32_t u = order_key(x[j]);
+            if (i0 + j < n) cnt += (u > T ? 1u : 0u) + (u == T ? 0x10000u : 0u);
+        }
         uint32_t total;
-        const uint32_t scan = block_exclusive_scan(gt | (eq << 16), s_wave, total);
-        const uint32_t gt_before = run_gt + (scan & 0xffffu), eq_before = run_eq + (scan >> 16);
-        if (gt || (eq && eq_before < k_eq)) {
-            const uint32_t pos = gt_before + (eq_before < k_eq ? eq_before : k_eq);
-            s_cols[pos] = c0 + i;
-            s_vals[pos] = x;
+        const uint32_t scan = block_exclusive_scan(cnt, s_wave, total);
+        uint32_t gt_before = run_gt + (scan & 0xffffu), eq_before = run_eq + (scan >> 16);
+#pragma unroll
+        for (int j = 0; j < kRun; ++j) {
+            const uint32_t u = order_key(x[j]);
+            const bool in = i0 + j < n, gt = in && u > T, eq = in && u == T;
+            if (gt || (eq && eq_before < k_eq)) {
+                const uint32_t pos = gt_before + (eq_before < k_eq ? eq_before : k_eq);
+                s_cols[pos] = c0 + i0 + j;
+                s_vals[pos] = x[j];
+            }
+            gt_before += gt ? 1u : 0u;
+            eq_before += eq ? 1u : 0u;
         }
         run_gt += total & 0xffffu;
         run_eq += total >> 16;
