@@ -354,6 +354,75 @@ size_t merge_ws_bytes(int32_t n_groups)
     return n_groups > kInlineGroups ? align_up(((size_t)n_groups + 1) * sizeof(int32_t)) : 0;
 }
 
+// The logits call records nothing: its workspace only holds the range table when that does
+// not fit in the kernel arguments.
+size_t logits_ws_bytes(int32_t n_ranges)
+{
+    return n_ranges > kInlineRanges ? align_up(((size_t)n_ranges + 1) * sizeof(RangeEntry)) : 0;
+}
+
+// Long groups are selected in two stages (candidates per part, then among the candidates).
+constexpr int kSelectSplitTokens = 65536;  // groups up to this size are handled by one workgroup
+constexpr int kSelectPartTokens = 32768;
+constexpr int kSelectMaxParts = 32;
+
+int32_t select_parts(const hg_range *ranges, const int32_t *group_ptr, int32_t n_groups)
+{
+    int64_t longest = 0;
+    for (int32_t i = 0; i < n_groups; ++i) {
+        int64_t n = 0;
+        for (int32_t r = group_ptr[i]; r < group_ptr[i + 1]; ++r) n += ranges[r].end - ranges[r].begin;
+        longest = std::max(longest, n);
+    }
+    if (longest <= kSelectSplitTokens) return 1;
+    return (int32_t)std::min<int64_t>(kSelectMaxParts, (longest + kSelectPartTokens - 1) / kSelectPartTokens);
+}
+
+// Workspace of hg_attn_select: range table, group table (when they do not fit in kernel
+// arguments), then the candidate values and columns of the two-stage path.
+struct SelectPlan {
+    int32_t parts = 1;
+    size_t off_tab = 0, off_groups = 0, off_cand_val = 0, off_cand_col = 0, total = 0;
+};
+
+SelectPlan plan_select(const hg_range *ranges, int32_t n_ranges, const int32_t *group_ptr, int32_t n_groups,
+                       int32_t n_q_heads, int32_t top_k)
+{
+    SelectPlan sp;
+    sp.parts = select_parts(ranges, group_ptr, n_groups);
+    size_t off = 0;
+    sp.off_tab = off;
+    off += logits_ws_bytes(n_ranges);
+    sp.off_groups = off;
+    off += merge_ws_bytes(n_groups);
+    if (sp.parts > 1) {
+        const size_t cand = (size_t)n_groups * (size_t)n_q_heads * (size_t)sp.parts * (size_t)top_k * 4;
+        sp.off_cand_val = off;
+        off += align_up(cand);
+        sp.off_cand_col = off;
+        off += align_up(cand);
+    }
+    sp.total = off;
+    return sp;
+}
+
+template <int STAGE>
+void launch_select(const hg_attn_desc *desc, const SelectArgs &sa, dim3 grid, hipStream_t stream)
+{
+    const bool f16 = desc->dtype == HG_F16;
+    if (desc->head_dim == 128) {
+        if (f16)
+            hipLaunchKernelGGL((hg_select_kernel<Traits<128, true>, STAGE>), grid, dim3(kSelectBlock), 0, stream, sa);
+        else
+            hipLaunchKernelGGL((hg_select_kernel<Traits<128, false>, STAGE>), grid, dim3(kSelectBlock), 0, stream, sa);
+    } else {
+        if (f16)
+            hipLaunchKernelGGL((hg_select_kernel<Traits<64, true>, STAGE>), grid, dim3(kSelectBlock), 0, stream, sa);
+        else
+            hipLaunchKernelGGL((hg_select_kernel<Traits<64, false>, STAGE>), grid, dim3(kSelectBlock), 0, stream, sa);
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -488,13 +557,6 @@ hg_status hg_attn_full(const hg_attn_desc *desc, float *out, float *lse_out, voi
     return run(desc, ranges.data(), (int32_t)ranges.size(), 1, lse_out, nullptr, out, workspace, ws_bytes, stream);
 }
 
-// The logits call records nothing: its workspace only holds the range table when that does
-// not fit in the kernel arguments.
-size_t logits_ws_bytes(int32_t n_ranges)
-{
-    return n_ranges > kInlineRanges ? align_up(((size_t)n_ranges + 1) * sizeof(RangeEntry)) : 0;
-}
-
 hg_status hg_attn_logits_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, size_t *bytes)
 {
     if (!bytes) return HG_ERR_NULL;
@@ -623,18 +685,18 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
     return launch_status("concat reduce kernel");
 }
 
-// The selection call records nothing: its workspace only holds the range and group tables when
-// they do not fit in the kernel arguments.
-size_t select_ws_bytes(int32_t n_ranges, int32_t n_groups)
-{
-    return logits_ws_bytes(n_ranges) + merge_ws_bytes(n_groups);
-}
-
-hg_status hg_attn_select_workspace_size(int32_t n_ranges, int32_t n_groups, size_t *bytes)
+hg_status hg_attn_select_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges,
+                                        const int32_t *group_ptr, int32_t n_groups, int32_t top_k, size_t *bytes)
 {
     if (!bytes) return HG_ERR_NULL;
-    if (n_ranges < 0 || n_groups < 0 || n_groups > 65535) return HG_ERR_SHAPE;
-    *bytes = select_ws_bytes(n_ranges, n_groups);
+    hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = check_ranges(desc, ranges, n_ranges);
+    if (st != HG_OK) return st;
+    if (top_k < 1 || top_k > kMaxTopK) return HG_ERR_SHAPE;
+    st = check_concat_groups(ranges, n_ranges, group_ptr, n_groups);
+    if (st != HG_OK) return st;
+    *bytes = plan_select(ranges, n_ranges, group_ptr, n_groups, desc->n_q_heads, top_k).total;
     return HG_OK;
 }
 
@@ -655,17 +717,19 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
     st = make_plan(desc, ranges, n_ranges, p);
     if (st != HG_OK) return st;
     if (p.ws.ltok > 0 && !logits) return HG_ERR_NULL;
-    st = check_workspace(workspace, ws_bytes, select_ws_bytes(n_ranges, n_groups));
+    const SelectPlan sp = plan_select(ranges, n_ranges, group_ptr, n_groups, desc->n_q_heads, top_k);
+    if ((int64_t)n_groups * sp.parts > 0x7fffffff) return HG_ERR_SHAPE;
+    st = check_workspace(workspace, ws_bytes, sp.total);
     if (st != HG_OK) return st;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     char *ws = static_cast<char *>(workspace);
 
     SelectArgs sa;
     std::memset(&sa, 0, sizeof(sa));
-    p.off_tab = 0;
+    p.off_tab = sp.off_tab;
     st = stage_table(p, n_ranges, ws, stream, sa.tab);
     if (st != HG_OK) return st;
-    st = stage_groups(group_ptr, n_groups, reinterpret_cast<int32_t *>(ws + logits_ws_bytes(n_ranges)), stream, sa.groups);
+    st = stage_groups(group_ptr, n_groups, reinterpret_cast<int32_t *>(ws + sp.off_groups), stream, sa.groups);
     if (st != HG_OK) return st;
     sa.logits = logits;
     sa.v = desc->v;
@@ -680,20 +744,19 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
     sa.m = m;
     sa.l = l;
     sa.o = o;
+    sa.parts = sp.parts;
     dim3 grid((unsigned)n_groups, (unsigned)desc->n_q_heads);
-    const bool f16 = desc->dtype == HG_F16;
-    if (desc->head_dim == 128) {
-        if (f16)
-            hipLaunchKernelGGL((hg_select_kernel<Traits<128, true>>), grid, dim3(kSelectBlock), 0, stream, sa);
-        else
-            hipLaunchKernelGGL((hg_select_kernel<Traits<128, false>>), grid, dim3(kSelectBlock), 0, stream, sa);
-    } else {
-        if (f16)
-            hipLaunchKernelGGL((hg_select_kernel<Traits<64, true>>), grid, dim3(kSelectBlock), 0, stream, sa);
-        else
-            hipLaunchKernelGGL((hg_select_kernel<Traits<64, false>>), grid, dim3(kSelectBlock), 0, stream, sa);
+    if (sp.parts == 1) {
+        launch_select<kSelectDirect>(desc, sa, grid, stream);
+        return launch_status("selection kernel");
     }
-    return launch_status("selection kernel");
+    sa.cand_val = reinterpret_cast<float *>(ws + sp.off_cand_val);
+    sa.cand_col = reinterpret_cast<int32_t *>(ws + sp.off_cand_col);
+    launch_select<kSelectCandidates>(desc, sa, dim3((unsigned)(n_groups * sp.parts), (unsigned)desc->n_q_heads), stream);
+    st = launch_status("selection kernel (candidates)");
+    if (st != HG_OK) return st;
+    launch_select<kSelectFromCands>(desc, sa, grid, stream);
+    return launch_status("selection kernel (final)");
 }
 
 hg_status hg_attn_merge_workspace_size(int32_t n_groups, size_t *bytes)

@@ -155,9 +155,18 @@ struct SelectArgs {
     int32_t ltok, n_q_heads, group, top_k;
     int32_t *sel;         // [n_groups][Hq][top_k] or NULL
     float *m, *l, *o;     // [n_groups][Hq](..[D])
+    // two-stage selection of long groups: every group is cut into `parts` column intervals whose
+    // own top_k candidates (value, column; -inf padded) are the input of the second stage
+    int32_t parts;
+    float *cand_val;      // [n_groups][Hq][parts][top_k]
+    int32_t *cand_col;
     GroupTable groups;
     RangeTable tab;
 };
+
+constexpr int kSelectDirect = 0;      // one workgroup selects from the group's logits row
+constexpr int kSelectCandidates = 1;  // stage 1: per part, write its top_k candidates
+constexpr int kSelectFromCands = 2;   // stage 2: select among the parts' candidates
 
 struct RangeChunk {
     RangeEntry e[kUploadRanges];
@@ -1106,6 +1115,10 @@ __global__ __launch_bounds__(kReduceBlock) void hg_concat_reduce_kernel(const Co
 //      packed block scan provides;
 //   3. the kept logits give m and the weights exp(s - m); the 16 waves gather the kept V rows
 //      (four rows per wave load, 16 lanes per row as in the streaming kernel) and sum p.v.
+// A group of a million tokens would keep one compute unit busy for a millisecond, so long groups
+// are cut into parts: stage 1 runs steps 1-2 per part and writes the part's top_k candidates
+// (the global top_k is a subset of their union, and candidates stay in ascending column order),
+// stage 2 runs steps 1-3 over the candidates.
 
 __device__ __forceinline__ uint32_t order_key(float x)
 {
@@ -1137,7 +1150,7 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *s
     return before + inc - v;
 }
 
-template <typename TR>
+template <typename TR, int STAGE>
 __global__ __launch_bounds__(kSelectBlock) void hg_select_kernel(const SelectArgs a)
 {
     constexpr int D = TR::D, EPL = TR::EPL, NV = TR::NV, EPV = TR::EPV, ES = TR::ES;
@@ -1150,24 +1163,59 @@ __global__ __launch_bounds__(kSelectBlock) void hg_select_kernel(const SelectArg
     __shared__ float s_red[NW];
     __shared__ float s_acc[NW][D];
 
-    const int gi = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
+    const int tid = threadIdx.x, h = blockIdx.y;
+    const int gi = STAGE == kSelectCandidates ? blockIdx.x / a.parts : blockIdx.x;
+    const int part = STAGE == kSelectCandidates ? blockIdx.x - gi * a.parts : 0;
     const int lane = tid & 63, wave = tid >> 6;
     const int r0 = group_entry(a.groups, gi), r1 = group_entry(a.groups, gi + 1);
     const int c0 = table_entry(a.tab, r0).pre, c1 = table_entry(a.tab, r1).pre;
-    const int n = c1 - c0;
-    const int keep = n < a.top_k ? n : a.top_k;
     const int64_t gh = (int64_t)gi * a.n_q_heads + h;
-    const float *row = a.logits + (int64_t)h * a.ltok + c0;
 
-    if (a.sel)
-        for (int j = tid + keep; j < a.top_k; j += kSelectBlock) a.sel[gh * a.top_k + j] = -1;
-    if (n == 0) {
-        if (tid < D) a.o[gh * D + tid] = 0.f;
-        if (tid == 0) {
-            a.m[gh] = -INFINITY;
-            a.l[gh] = 0.f;
+    // the values this workgroup selects from: row[0..n), element i being logits column
+    // col_map ? col_map[i] : col_base + i
+    const float *row;
+    const int32_t *col_map = nullptr;
+    int n, col_base = 0, keep;
+    if constexpr (STAGE == kSelectDirect) {
+        row = a.logits + (int64_t)h * a.ltok + c0;
+        n = c1 - c0;
+        col_base = c0;
+        keep = n < a.top_k ? n : a.top_k;
+    } else if constexpr (STAGE == kSelectCandidates) {
+        const int per = (c1 - c0 + a.parts - 1) / a.parts;
+        const int b = c0 + part * per < c1 ? c0 + part * per : c1;
+        const int e = b + per < c1 ? b + per : c1;
+        row = a.logits + (int64_t)h * a.ltok + b;
+        n = e - b;
+        col_base = b;
+        keep = n < a.top_k ? n : a.top_k;
+    } else {
+        const int64_t base = gh * a.parts * (int64_t)a.top_k;
+        row = a.cand_val + base;
+        col_map = a.cand_col + base;
+        n = c1 > c0 ? a.parts * a.top_k : 0;  // padded with -inf entries, which sort below every logit
+        keep = c1 - c0 < a.top_k ? c1 - c0 : a.top_k;
+    }
+
+    if constexpr (STAGE == kSelectCandidates) {
+        // pad the part's candidate slots; the kept ones are overwritten below
+        const int64_t base = (gh * a.parts + part) * (int64_t)a.top_k;
+        for (int j = tid + keep; j < a.top_k; j += kSelectBlock) {
+            a.cand_val[base + j] = -INFINITY;
+            a.cand_col[base + j] = 0;
         }
-        return;
+        if (n == 0) return;
+    } else {
+        if (a.sel)
+            for (int j = tid + keep; j < a.top_k; j += kSelectBlock) a.sel[gh * a.top_k + j] = -1;
+        if (n == 0) {
+            if (tid < D) a.o[gh * D + tid] = 0.f;
+            if (tid == 0) {
+                a.m[gh] = -INFINITY;
+                a.l[gh] = 0.f;
+            }
+            return;
+        }
     }
 
     // 1. radix select
@@ -1229,7 +1277,7 @@ __global__ __launch_bounds__(kSelectBlock) void hg_select_kernel(const SelectArg
             const bool in = i0 + j < n, gt = in && u > T, eq = in && u == T;
             if (gt || (eq && eq_before < k_eq)) {
                 const uint32_t pos = gt_before + (eq_before < k_eq ? eq_before : k_eq);
-                s_cols[pos] = c0 + i0 + j;
+                s_cols[pos] = col_map ? col_map[i0 + j] : col_base + i0 + j;
                 s_vals[pos] = x[j];
             }
             gt_before += gt ? 1u : 0u;
@@ -1239,6 +1287,15 @@ __global__ __launch_bounds__(kSelectBlock) void hg_select_kernel(const SelectArg
         run_eq += total >> 16;
     }
     __syncthreads();
+
+    if constexpr (STAGE == kSelectCandidates) {
+        const int64_t base = (gh * a.parts + part) * (int64_t)a.top_k;
+        for (int j = tid; j < keep; j += kSelectBlock) {
+            a.cand_val[base + j] = s_vals[j];
+            a.cand_col[base + j] = s_cols[j];
+        }
+        return;
+    }
 
     // 3a. m = max kept logit; weights; l
     float mx = -INFINITY;

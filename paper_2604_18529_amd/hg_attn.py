@@ -76,7 +76,7 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_logits.argtypes = [D, R, i32, vp, vp, sz, vp]
     lib.hg_attn_concat_workspace_size.argtypes = [D, R, i32, i32, ctypes.POINTER(sz)]
     lib.hg_attn_concat.argtypes = [D, R, i32, vp, vp, i32, vp, vp, vp, sz, vp]
-    lib.hg_attn_select_workspace_size.argtypes = [i32, i32, ctypes.POINTER(sz)]
+    lib.hg_attn_select_workspace_size.argtypes = [D, R, i32, vp, i32, i32, ctypes.POINTER(sz)]
     lib.hg_attn_select.argtypes = [D, R, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.hg_attn_full_workspace_size.argtypes = [D, ctypes.POINTER(sz)]
     lib.hg_attn_full.argtypes = [D, vp, vp, vp, sz, vp]
@@ -406,7 +406,8 @@ def hg_attn_select(q, k, v, seq_lens, ranges, logits, group_ptr, top_k, scale=No
     o = torch.empty((G, Hq, d), dtype=torch.float32, device=dev)
     if workspace is None:
         sz = ctypes.c_size_t()
-        _check(lib.hg_attn_select_workspace_size(R, G, ctypes.byref(sz)), "hg_attn_select_workspace_size")
+        _check(lib.hg_attn_select_workspace_size(ctypes.byref(desc), packed, R, gp.ctypes.data, G, int(top_k), ctypes.byref(sz)),
+               "hg_attn_select_workspace_size")
         workspace, ws_bytes = _workspace(sz.value, dev, None)
     else:
         ws_bytes = workspace.numel() * workspace.element_size()

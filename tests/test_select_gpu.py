@@ -126,6 +126,23 @@ def test_post_qk_selection_end_to_end():
             check_out(out, lse, exact, elsE, "post-qk keeps everything")
 
 
+@pytest.mark.parametrize("top_k", [5, 4096])
+def test_long_groups_take_the_two_stage_path(top_k):
+    """Groups longer than 65536 tokens are cut into parts whose candidates are merged; the kept
+    set must still be the exact global top-k with the global tie-break (lower column)."""
+    spec = W.WorkloadSpec("sellong", 2, 2, 1, 128, "f16", 70000, 150000, "none", seed=62)
+    w = W.make_workload(spec, DEV)
+    w.seq_lens[:] = [150000, 70000]
+    ranges = [(0, 0, 90000), (0, 90000, 150000), (1, 100, 70000)]
+    gp = [0, 2, 3]
+    ltok = sum(e - s for _, s, e in ranges)
+    lg = _seeded_logits(2, ltok, 63, True)
+    lg[1, :] = 1.25  # one head with every logit equal: the first top_k columns of each group win
+    sel, _, _, _ = _check_select(w, ranges, gp, lg, top_k, "two-stage k=%d" % top_k)
+    assert to_np(sel[0, 1]).tolist() == list(range(top_k))
+    assert to_np(sel[1, 1]).tolist() == list(range(100, 100 + top_k))
+
+
 def test_bad_arguments():
     spec = W.WorkloadSpec("selerr", 1, 2, 2, 64, "f16", 100, 100, "none", seed=60)
     w = W.make_workload(spec, DEV)
