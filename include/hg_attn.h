@@ -199,6 +199,32 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
                          float *o, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * Feedback scheduler policy (Algorithm 1): host-only integer logic that sizes the offloaded
+ * executor's work from the measured stage latencies.  One call = one tick.
+ *
+ *   state->k         tokens the offloaded executor keeps per head (the K of hg_attn_select);
+ *                    hg_sched_init sets it to k_min with the Post-QK^T strategy.
+ *   t_gpu            latency of the GPU stage (attention + FFN of the current layer),
+ *   t_cpu, t_tx      latency of the offloaded logit stage and of its transfer, same unit.
+ *   k_min            offline accuracy threshold; k_max = tokens available to the executor;
+ *   k_step           how far one tick moves K (the paper leaves the step open).
+ *
+ * If t_cpu + t_tx <= t_gpu the offloaded stage is hidden behind the GPU stage and K grows by
+ * k_step (at most k_max); otherwise K shrinks by k_step but not below k_min; and if K is already
+ * k_min the strategy switches to Pre-QK^T (select before computing logits).  The strategy of a
+ * tick is Post-QK^T unless that last case applies.  A state whose k lies outside
+ * [k_min, k_max] is clamped first.
+ */
+typedef enum hg_select_strategy { HG_SELECT_POST_QK = 0, HG_SELECT_PRE_QK = 1 } hg_select_strategy;
+typedef struct hg_sched_state {
+    int32_t k;
+    int32_t strategy; /* hg_select_strategy */
+} hg_sched_state;
+hg_status hg_sched_init(hg_sched_state *state, int32_t k_min);
+hg_status hg_sched_step(hg_sched_state *state, float t_gpu, float t_cpu, float t_tx, int32_t k_min, int32_t k_max,
+                        int32_t k_step);
+
+/*
  * Host-side planning, exposed for inspection and tests.  The tokens of all ranges, repeated for
  * every stream (KV head x chunk of query heads sharing it), form one linear work space that is
  * cut into equal spans, one workgroup each, so that every workgroup streams the same number of

@@ -12,6 +12,9 @@ _API = (
     "hg_attn_logits",
     "hg_attn_concat",
     "hg_attn_select",
+    "hg_sched_init",
+    "hg_sched_step",
+    "HgSchedState",
     "hg_attn_plan",
     "hg_attn_set_tile_tokens",
     "hg_attn_profile_start",

@@ -448,6 +448,35 @@ hg_status hg_attn_set_tile_tokens(int32_t tile_tokens)
     return HG_OK;
 }
 
+hg_status hg_sched_init(hg_sched_state *state, int32_t k_min)
+{
+    if (!state) return HG_ERR_NULL;
+    if (k_min < 1) return HG_ERR_SHAPE;
+    state->k = k_min;
+    state->strategy = HG_SELECT_POST_QK;
+    return HG_OK;
+}
+
+hg_status hg_sched_step(hg_sched_state *state, float t_gpu, float t_cpu, float t_tx, int32_t k_min, int32_t k_max,
+                        int32_t k_step)
+{
+    if (!state) return HG_ERR_NULL;
+    if (k_min < 1 || k_max < k_min || k_step < 1) return HG_ERR_SHAPE;
+    if (!(t_gpu >= 0.f) || !(t_cpu >= 0.f) || !(t_tx >= 0.f) || !std::isfinite(t_gpu + t_cpu + t_tx)) return HG_ERR_SHAPE;
+    int64_t k = std::min<int64_t>(std::max<int64_t>(state->k, k_min), k_max);
+    int32_t strategy = HG_SELECT_POST_QK;
+    if (t_cpu + t_tx <= t_gpu) {
+        k = std::min<int64_t>(k + k_step, k_max);
+    } else if (k > k_min) {
+        k = std::max<int64_t>(k - k_step, k_min);
+    } else {
+        strategy = HG_SELECT_PRE_QK;
+    }
+    state->k = (int32_t)k;
+    state->strategy = strategy;
+    return HG_OK;
+}
+
 hg_status hg_attn_calibration_copy(void *dst, const void *src, size_t bytes, void *stream)
 {
     if (!dst || !src) return HG_ERR_NULL;

@@ -49,6 +49,12 @@ class _Desc(ctypes.Structure):
     ]
 
 
+class HgSchedState(ctypes.Structure):
+    """State of the feedback scheduler policy: k and strategy (0 = Post-QK^T, 1 = Pre-QK^T)."""
+
+    _fields_ = [("k", ctypes.c_int32), ("strategy", ctypes.c_int32)]
+
+
 class _Range(ctypes.Structure):
     _fields_ = [("seq", ctypes.c_int32), ("begin", ctypes.c_int32), ("end", ctypes.c_int32)]
 
@@ -78,6 +84,8 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_concat.argtypes = [D, R, i32, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.hg_attn_select_workspace_size.argtypes = [D, R, i32, vp, i32, i32, ctypes.POINTER(sz)]
     lib.hg_attn_select.argtypes = [D, R, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.hg_sched_init.argtypes = [ctypes.POINTER(HgSchedState), i32]
+    lib.hg_sched_step.argtypes = [ctypes.POINTER(HgSchedState), ctypes.c_float, ctypes.c_float, ctypes.c_float, i32, i32, i32]
     lib.hg_attn_full_workspace_size.argtypes = [D, ctypes.POINTER(sz)]
     lib.hg_attn_full.argtypes = [D, vp, vp, vp, sz, vp]
     lib.hg_attn_plan.argtypes = [D, R, i32, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_int64)]
@@ -89,7 +97,7 @@ def load_library() -> ctypes.CDLL:
         "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_merge_workspace_size", "hg_attn_merge",
         "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_tile_tokens",
         "hg_attn_profile_start", "hg_attn_profile_stop", "hg_attn_calibration_copy",
-        "hg_attn_logits_workspace_size", "hg_attn_logits", "hg_attn_select_workspace_size", "hg_attn_select", "hg_attn_concat_workspace_size", "hg_attn_concat",
+        "hg_sched_init", "hg_sched_step", "hg_attn_logits_workspace_size", "hg_attn_logits", "hg_attn_select_workspace_size", "hg_attn_select", "hg_attn_concat_workspace_size", "hg_attn_concat",
     ):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -417,3 +425,16 @@ def hg_attn_select(q, k, v, seq_lens, ranges, logits, group_ptr, top_k, scale=No
     _check(st, "hg_attn_select")
     del keep
     return sel, m, l, o
+
+
+def hg_sched_init(k_min: int) -> HgSchedState:
+    st = HgSchedState()
+    _check(load_library().hg_sched_init(ctypes.byref(st), int(k_min)), "hg_sched_init")
+    return st
+
+
+def hg_sched_step(state: HgSchedState, t_gpu: float, t_cpu: float, t_tx: float, k_min: int, k_max: int, k_step: int):
+    """One tick of the feedback scheduler policy; updates and returns (k, strategy)."""
+    _check(load_library().hg_sched_step(ctypes.byref(state), float(t_gpu), float(t_cpu), float(t_tx), int(k_min), int(k_max),
+                                        int(k_step)), "hg_sched_step")
+    return state.k, state.strategy
