@@ -71,6 +71,16 @@ typedef enum hg_dtype { HG_F16 = 0, HG_F32 = 1 } hg_dtype;
  *   seq_lens HOST [batch], 0 <= seq_lens[b].
  *   head_dim 64 or 128.  n_q_heads % n_kv_heads == 0.
  *   scale   multiplies q.k before the softmax (natural-log domain); callers pass 1/sqrt(head_dim).
+ *
+ * Paged cache (block_table != NULL; the KV manager of a paged serving stack, Section 4.8):
+ *   block_table DEVICE int32 [batch][max_blocks]: token t of sequence b lives in physical block
+ *               block_table[b][t / block_tokens], at row t % block_tokens of that block.
+ *   block_tokens power of two, 16 .. 65536;  max_blocks >= ceil(max seq_lens / block_tokens).
+ *   k, v        element (block p, head g, row r, c) is at base + p*stride_b + g*stride_h + r*stride_t + c:
+ *               stride_b is the distance between physical blocks.  Table entries are not checked
+ *               (they are device memory): every entry a valid token maps to must be a valid block.
+ *   Supported by hg_attn_partial and hg_attn_full; the other calls return HG_ERR_SHAPE for a
+ *   paged descriptor.
  */
 typedef struct hg_attn_desc {
     const void *q;
@@ -81,6 +91,8 @@ typedef struct hg_attn_desc {
     int32_t batch, n_q_heads, n_kv_heads, head_dim;
     int32_t dtype; /* hg_dtype */
     float scale;
+    const int32_t *block_table; /* NULL: contiguous cache */
+    int32_t block_tokens, max_blocks;
 } hg_attn_desc;
 
 /* Tokens [begin, end) of sequence `seq` (the Token Mapper's positional range, Section 4.2.3).

@@ -69,8 +69,18 @@ hg_status check_desc(const hg_attn_desc *d)
     if (!std::isfinite(d->scale)) return HG_ERR_SHAPE;
     for (int32_t b = 0; b < d->batch; ++b)
         if (d->seq_lens[b] < 0) return HG_ERR_RANGE;
+    if (d->block_table) {
+        const int32_t bt = d->block_tokens;
+        if (bt < 16 || bt > 65536 || (bt & (bt - 1))) return HG_ERR_SHAPE;
+        if (d->max_blocks < 1) return HG_ERR_SHAPE;
+        for (int32_t b = 0; b < d->batch; ++b)
+            if (((int64_t)d->seq_lens[b] + bt - 1) / bt > d->max_blocks) return HG_ERR_RANGE;
+    }
     return HG_OK;
 }
+
+// Entry points without paged-cache support.
+hg_status reject_paged(const hg_attn_desc *d) { return d && d->block_table ? HG_ERR_SHAPE : HG_OK; }
 
 hg_status check_ranges(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges)
 {
@@ -190,38 +200,51 @@ hg_status stage_table(const Plan &p, int32_t n_ranges, char *ws, hipStream_t str
 
 // Rows in flight per 16-lane group.  The logits and concat modes read only K or only V, so they
 // keep twice as many rows in flight to have the same number of bytes outstanding.
-template <typename TR, int MODE>
+template <typename TR, int MODE, bool PAGED>
 void launch_valu_gt(const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
 {
     constexpr int F = MODE == kModeStats ? 1 : 2;
     switch (gt) {
-    case 1: hipLaunchKernelGGL((hg_partial_kernel<TR, 1, F * HG_VALU_U, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((hg_partial_kernel<TR, 2, F * HG_VALU_U, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
-    case 4: hipLaunchKernelGGL((hg_partial_kernel<TR, 4, F * 2, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
-    default: hipLaunchKernelGGL((hg_partial_kernel<TR, 8, F * 2, MODE>), grid, dim3(kValuBlock), 0, stream, a); break;
+    case 1: hipLaunchKernelGGL((hg_partial_kernel<TR, 1, F * HG_VALU_U, MODE, PAGED>), grid, dim3(kValuBlock), 0, stream, a); break;
+    case 2: hipLaunchKernelGGL((hg_partial_kernel<TR, 2, F * HG_VALU_U, MODE, PAGED>), grid, dim3(kValuBlock), 0, stream, a); break;
+    case 4: hipLaunchKernelGGL((hg_partial_kernel<TR, 4, F * 2, MODE, PAGED>), grid, dim3(kValuBlock), 0, stream, a); break;
+    default: hipLaunchKernelGGL((hg_partial_kernel<TR, 8, F * 2, MODE, PAGED>), grid, dim3(kValuBlock), 0, stream, a); break;
     }
 }
 
-// One launch of the streaming kernel that fits the problem, in the given mode.
-template <int MODE>
-void launch_stream(const hg_attn_desc *d, const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
+template <int MODE, bool PAGED>
+void launch_stream_paged(const hg_attn_desc *d, const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
 {
     if (use_gqa_kernel(d)) {
-        hipLaunchKernelGGL(hg_partial_gqa_kernel<MODE>, grid, dim3(kGqaBlock), 0, stream, a);
+        hipLaunchKernelGGL((hg_partial_gqa_kernel<MODE, PAGED>), grid, dim3(kGqaBlock), 0, stream, a);
         return;
     }
     const bool f16 = d->dtype == HG_F16;
     if (d->head_dim == 128) {
         if (f16)
-            launch_valu_gt<Traits<128, true>, MODE>(a, gt, grid, stream);
+            launch_valu_gt<Traits<128, true>, MODE, PAGED>(a, gt, grid, stream);
         else
-            launch_valu_gt<Traits<128, false>, MODE>(a, gt, grid, stream);
+            launch_valu_gt<Traits<128, false>, MODE, PAGED>(a, gt, grid, stream);
     } else {
         if (f16)
-            launch_valu_gt<Traits<64, true>, MODE>(a, gt, grid, stream);
+            launch_valu_gt<Traits<64, true>, MODE, PAGED>(a, gt, grid, stream);
         else
-            launch_valu_gt<Traits<64, false>, MODE>(a, gt, grid, stream);
+            launch_valu_gt<Traits<64, false>, MODE, PAGED>(a, gt, grid, stream);
     }
+}
+
+// One launch of the streaming kernel that fits the problem, in the given mode.  Paged caches
+// exist for the statistics mode only (the other entry points reject them up front).
+template <int MODE>
+void launch_stream(const hg_attn_desc *d, const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
+{
+    if constexpr (MODE == kModeStats) {
+        if (d->block_table) {
+            launch_stream_paged<MODE, true>(d, a, gt, grid, stream);
+            return;
+        }
+    }
+    launch_stream_paged<MODE, false>(d, a, gt, grid, stream);
 }
 
 void fill_stream_args(const hg_attn_desc *d, const Plan &p, char *ws, PartialArgs &pa)
@@ -234,6 +257,13 @@ void fill_stream_args(const hg_attn_desc *d, const Plan &p, char *ws, PartialArg
     pa.stride_t = d->stride_t;
     pa.ws = p.ws;
     pa.qscale = d->scale * kLog2e;
+    if (d->block_table) {
+        pa.pages.table = d->block_table;
+        pa.pages.mask = d->block_tokens - 1;
+        pa.pages.shift = 0;
+        while ((1 << pa.pages.shift) < d->block_tokens) ++pa.pages.shift;
+        pa.pages.max_blocks = d->max_blocks;
+    }
     if (ws) {
         pa.ws_m = reinterpret_cast<float *>(ws + p.off_m);
         pa.ws_l = reinterpret_cast<float *>(ws + p.off_l);
@@ -591,6 +621,8 @@ hg_status hg_attn_logits_workspace_size(const hg_attn_desc *desc, const hg_range
     if (!bytes) return HG_ERR_NULL;
     hg_status st = check_desc(desc);
     if (st != HG_OK) return st;
+    st = reject_paged(desc);
+    if (st != HG_OK) return st;
     st = check_ranges(desc, ranges, n_ranges);
     if (st != HG_OK) return st;
     *bytes = logits_ws_bytes(n_ranges);
@@ -601,6 +633,8 @@ hg_status hg_attn_logits(const hg_attn_desc *desc, const hg_range *ranges, int32
                          void *workspace, size_t ws_bytes, void *stream_v)
 {
     hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = reject_paged(desc);
     if (st != HG_OK) return st;
     st = check_ranges(desc, ranges, n_ranges);
     if (st != HG_OK) return st;
@@ -631,6 +665,8 @@ hg_status hg_attn_concat_workspace_size(const hg_attn_desc *desc, const hg_range
     if (n_groups < 0 || n_groups > 65535) return HG_ERR_SHAPE;
     hg_status st = check_desc(desc);
     if (st != HG_OK) return st;
+    st = reject_paged(desc);
+    if (st != HG_OK) return st;
     st = check_ranges(desc, ranges, n_ranges);
     if (st != HG_OK) return st;
     Plan p;
@@ -646,6 +682,8 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
                          size_t ws_bytes, void *stream_v)
 {
     hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = reject_paged(desc);
     if (st != HG_OK) return st;
     st = check_ranges(desc, ranges, n_ranges);
     if (st != HG_OK) return st;
@@ -720,6 +758,8 @@ hg_status hg_attn_select_workspace_size(const hg_attn_desc *desc, const hg_range
     if (!bytes) return HG_ERR_NULL;
     hg_status st = check_desc(desc);
     if (st != HG_OK) return st;
+    st = reject_paged(desc);
+    if (st != HG_OK) return st;
     st = check_ranges(desc, ranges, n_ranges);
     if (st != HG_OK) return st;
     if (top_k < 1 || top_k > kMaxTopK) return HG_ERR_SHAPE;
@@ -734,6 +774,8 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
                          float *o, void *workspace, size_t ws_bytes, void *stream_v)
 {
     hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = reject_paged(desc);
     if (st != HG_OK) return st;
     st = check_ranges(desc, ranges, n_ranges);
     if (st != HG_OK) return st;

@@ -96,9 +96,18 @@ struct WorkSplit {
     int32_t n_q_heads;
 };
 
+// Paged cache: token t of sequence b lives in physical block table[b * max_blocks + (t >> shift)]
+// at row t & mask; stride_b is then the distance between physical blocks.  table == nullptr
+// means a contiguous cache.
+struct PageMap {
+    const int32_t *table;
+    int32_t shift, mask, max_blocks, pad;
+};
+
 struct PartialArgs {
     const void *q, *k, *v;
     int64_t stride_b, stride_h, stride_t;  // elements
+    PageMap pages;
     float qscale;                          // scale * log2(e); plain scale in logits mode
     float *ws_m, *ws_l, *ws_o;             // segment records [slot][gt], [slot][gt][D]; m in log2 units
     float *logits;                         // [Hq][ltok]: written in logits mode, read in concat mode
@@ -339,7 +348,7 @@ __device__ __forceinline__ float group_softmax_max(const float *gs_m, int64_t ba
     return m;
 }
 
-template <typename TR, int GT, int U, int MODE>
+template <typename TR, int GT, int U, int MODE, bool PAGED>
 __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArgs a)
 {
     constexpr int D = TR::D, EPL = TR::EPL, NV = TR::NV, EPV = TR::EPV, ES = TR::ES;
@@ -397,10 +406,28 @@ __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArg
         for (int i = 0; i < EPL; ++i) acc[g][i] = 0.f;
     }
 
-    const int64_t slab = (int64_t)seq * a.stride_b + (int64_t)hk * a.stride_h;
+    // contiguous cache: one slab per (sequence, KV head); paged cache: the head's offset inside a
+    // block, the block comes from the table
+    const int64_t slab = (PAGED ? 0 : (int64_t)seq * a.stride_b) + (int64_t)hk * a.stride_h;
     const char *kbase = static_cast<const char *>(a.k) + slab * ES;
     const char *vbase = static_cast<const char *>(a.v) + slab * ES;
     const int64_t row_bytes = a.stride_t * ES;
+    const int64_t block_bytes = a.stride_b * ES;
+    const int32_t *table = PAGED ? a.pages.table + (int64_t)seq * a.pages.max_blocks : nullptr;
+
+    // physical blocks of the U tokens this lane group takes in the iteration starting at tbb;
+    // they are looked up one iteration ahead so that the row loads never wait for the table
+    int pg[U], pg_next[U];
+    auto lookup = [&](int tbb, int(&out)[U]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int tok = tbb + 4 * u + grp;
+            out[u] = table[(tok < t1 ? tok : t1 - 1) >> a.pages.shift];
+        }
+    };
+    if constexpr (PAGED) {
+        if (t0 + wave * CH < t1) lookup(t0 + wave * CH, pg);
+    }
 
     for (int tb = t0 + wave * CH; tb < t1; tb += kValuWaves * CH) {
         typename TR::Raw kraw[U][NV], vraw[U][NV];
@@ -411,7 +438,8 @@ __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArg
             const int tok = tb + 4 * u + grp;
             valid[u] = tok < t1;
             tokc[u] = valid[u] ? tok : t1 - 1;  // clamp: never read past the segment
-            const int64_t off = (int64_t)tokc[u] * row_bytes;
+            const int64_t off = PAGED ? (int64_t)pg[u] * block_bytes + (int64_t)(tokc[u] & a.pages.mask) * row_bytes
+                                      : (int64_t)tokc[u] * row_bytes;
             if constexpr (MODE != kModeConcat) {
 #pragma unroll
                 for (int j = 0; j < NV; ++j) kraw[u][j] = TR::template load<true>(kbase + off, sub, j);
@@ -420,6 +448,10 @@ __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArg
 #pragma unroll
                 for (int j = 0; j < NV; ++j) vraw[u][j] = TR::template load<true>(vbase + off, sub, j);
             }
+        }
+
+        if constexpr (PAGED) {
+            if (tb + kValuWaves * CH < t1) lookup(tb + kValuWaves * CH, pg_next);
         }
 
         // logits of the U tokens of this lane group, for every head of the chunk
@@ -449,9 +481,9 @@ __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArg
                 for (int g = 0; g < GT; ++g)
                     if (sub == g && g < nh && valid[u])
                         a.logits[(int64_t)(h0 + g) * a.ws.ltok + col0 + (tokc[u] - t0)] = s[g][u];
-            continue;
         }
 
+        if constexpr (MODE != kModeLogits) {
         float p[GT][U];
         if constexpr (MODE == kModeStats) {
             // online softmax update
@@ -501,6 +533,11 @@ __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArg
             for (int g = 0; g < GT; ++g)
 #pragma unroll
                 for (int i = 0; i < EPL; ++i) acc[g][i] = fmaf(p[g][u], vf[i], acc[g][i]);
+        }
+        }  // MODE != kModeLogits
+        if constexpr (PAGED) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) pg[u] = pg_next[u];
         }
     }
     if constexpr (MODE == kModeLogits) return;  // nothing to merge or record
@@ -607,9 +644,10 @@ __device__ __forceinline__ void wave_lds_handover()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int MODE>
+template <int MODE, bool PAGED>
 __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_gqa_kernel(const PartialArgs a)
 {
+    static_assert(!PAGED || MODE == kModeStats, "paged caches are only wired into the statistics mode");
     constexpr int D = 128;
     constexpr int kMergeBytes = kGqaWaves * kGqaHeads * (D + 2) * 4;
     constexpr int kSmemBytes = kGqaWaves * kGqaWaveBytes > kMergeBytes ? kGqaWaves * kGqaWaveBytes : kMergeBytes;
@@ -663,30 +701,48 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 #pragma unroll
     for (int nb = 0; nb < 8; ++nb) o[nb] = hg_f4{0.f, 0.f, 0.f, 0.f};
 
-    const int64_t slab = (int64_t)seq * a.stride_b + (int64_t)hk * a.stride_h;
+    const int64_t slab = (PAGED ? 0 : (int64_t)seq * a.stride_b) + (int64_t)hk * a.stride_h;
     const char *kbase = static_cast<const char *>(a.k) + slab * 2 + n * 16;
     const char *vbase = static_cast<const char *>(a.v) + slab * 2 + n * 16;
     const int64_t row_bytes = a.stride_t * 2;
+    const int64_t block_bytes = a.stride_b * 2;
+    const int32_t *table = PAGED ? a.pages.table + (int64_t)seq * a.pages.max_blocks : nullptr;
+
+    // Paged cache: physical blocks of the 8 tokens tb + 4x + rg (x = 0..7) a lane touches in a
+    // block; K load i uses x = i, V load j uses x = 4*(j&1) + (j>>1), the same 8 tokens.
+    auto lookup = [&](int tb, int(&pg)[8]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int tok = tb + 4 * x + rg;
+            pg[x] = table[(tok < t1 ? tok : t1 - 1) >> a.pages.shift];
+        }
+    };
+    auto row_offset = [&](int tok, int page) __attribute__((always_inline)) -> int64_t {
+        return PAGED ? (int64_t)page * block_bytes + (int64_t)(tok & a.pages.mask) * row_bytes : (int64_t)tok * row_bytes;
+    };
 
     // The 8 K-row loads and the 8 V-row loads of one 32-token block (8 KiB each per wave).
-    auto load_k = [&](int tb, hg_u32x4(&kreg)[8]) __attribute__((always_inline)) {
+    auto load_k = [&](int tb, hg_u32x4(&kreg)[8], const int(&pg)[8]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             int tok = tb + 4 * i + rg;
             tok = tok < t1 ? tok : t1 - 1;  // clamp: never read past the segment
-            kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(kbase + (int64_t)tok * row_bytes));
+            kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(kbase + row_offset(tok, pg[i])));
         }
     };
-    auto load_v = [&](int tb, hg_u32x4(&vreg)[8]) __attribute__((always_inline)) {
+    auto load_v = [&](int tb, hg_u32x4(&vreg)[8], const int(&pg)[8]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             // token j of lane group rg: interleaved so that S halves pair up (stats mode), or the
             // 8 consecutive tokens whose logits this lane reads (concat mode)
             int tok = MODE == kModeConcat ? tb + 8 * rg + j : tb + 16 * (j & 1) + 4 * (j >> 1) + rg;
             tok = tok < t1 ? tok : t1 - 1;
-            vreg[j] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(vbase + (int64_t)tok * row_bytes));
+            vreg[j] = __builtin_nontemporal_load(
+                reinterpret_cast<const hg_u32x4 *>(vbase + row_offset(tok, pg[4 * (j & 1) + (j >> 1)])));
         }
     };
+    // pages of the next block (pg1) and of the one after (pg2, in flight); unused when not paged
+    int pg1[8] = {0, 0, 0, 0, 0, 0, 0, 0}, pg2[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 
     // One block.  Software pipeline with a single register buffer: the K rows of the next block
     // are requested as soon as this block's K sits in LDS, its V rows as soon as this block's V
@@ -697,7 +753,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         for (int i = 0; i < 8; ++i)
             *reinterpret_cast<hg_u32x4 *>(kls + (4 * i + rg) * kGqaKRow + n * 16) = kreg[i];
         wave_lds_handover();
-        if (tb_next < t1) load_k(tb_next, kreg);
+        if (tb_next < t1) load_k(tb_next, kreg, pg1);
         hg_f4 s[2];
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {
@@ -769,7 +825,19 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
         }
-        if (tb_next < t1) load_v(tb_next, vreg);
+        if (tb_next < t1) {
+            if constexpr (PAGED) {
+                // table look-up for the block after next goes out BEFORE the V loads: the K loads
+                // of that block then only wait for what was issued earlier (loads return in order)
+                const int tb_nn = tb_next + (tb_next - tb);
+                if (tb_nn < t1) lookup(tb_nn, pg2);
+            }
+            load_v(tb_next, vreg, pg1);
+            if constexpr (PAGED) {
+#pragma unroll
+                for (int x = 0; x < 8; ++x) pg1[x] = pg2[x];
+            }
+        }
         wave_lds_handover();  // the next block overwrites the K and P staging areas
     };
 
@@ -806,7 +874,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
         }
-        if (tb_next < t1) load_v(tb_next, vreg);
+        if (tb_next < t1) load_v(tb_next, vreg, pg1);
     };
 
     {
@@ -815,8 +883,12 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         if constexpr (MODE == kModeStats) {
             hg_u32x4 kreg[8], vreg[8];
             if (tb < t1) {
-                load_k(tb, kreg);
-                load_v(tb, vreg);
+                if constexpr (PAGED) {
+                    lookup(tb, pg2);
+                    if (tb + kStride < t1) lookup(tb + kStride, pg1);
+                }
+                load_k(tb, kreg, pg2);
+                load_v(tb, vreg, pg2);
             }
             while (tb < t1) {
                 compute_block(tb, tb + kStride, kreg, vreg);
@@ -828,9 +900,9 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             hg_u32x4 ra[8], rb[8];
             auto load_one = [&](int t, hg_u32x4(&reg)[8]) __attribute__((always_inline)) {
                 if constexpr (MODE == kModeLogits)
-                    load_k(t, reg);
+                    load_k(t, reg, pg1);
                 else
-                    load_v(t, reg);
+                    load_v(t, reg, pg1);
             };
             auto compute_one = [&](int t, hg_u32x4(&reg)[8]) __attribute__((always_inline)) {
                 if constexpr (MODE == kModeLogits)

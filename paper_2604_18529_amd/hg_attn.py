@@ -46,6 +46,9 @@ class _Desc(ctypes.Structure):
         ("head_dim", ctypes.c_int32),
         ("dtype", ctypes.c_int32),
         ("scale", ctypes.c_float),
+        ("block_table", ctypes.c_void_p),
+        ("block_tokens", ctypes.c_int32),
+        ("max_blocks", ctypes.c_int32),
     ]
 
 
@@ -140,16 +143,20 @@ def _stream_handle(stream) -> Optional[int]:
     return int(stream) or None
 
 
-def make_desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seq_lens, scale: Optional[float] = None):
-    """Describe a problem.  Returns (desc, keepalive); keepalive must outlive the calls using desc."""
+def make_desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seq_lens, scale: Optional[float] = None,
+              block_table: Optional[torch.Tensor] = None):
+    """Describe a problem.  Returns (desc, keepalive); keepalive must outlive the calls using desc.
+
+    Contiguous cache: k, v are [B, Hkv, N, d].  Paged cache (``block_table`` int32 [B, max_blocks]
+    on the device): k, v are the physical pools [n_blocks, Hkv, block_tokens, d]."""
     if q.dtype not in (torch.float16, torch.float32) or k.dtype != q.dtype or v.dtype != q.dtype:
         raise TypeError("q, k, v must share dtype float16 or float32")
     if q.dim() != 3 or k.dim() != 4 or v.dim() != 4 or k.shape != v.shape:
-        raise ValueError("q must be [B,Hq,d]; k and v [B,Hkv,N,d] of equal shape")
+        raise ValueError("q must be [B,Hq,d]; k and v [B,Hkv,N,d] (or [blocks,Hkv,block_tokens,d]) of equal shape")
     if not q.is_contiguous():
         raise ValueError("q must be contiguous")
     B, Hq, d = q.shape
-    if k.shape[0] != B or k.shape[3] != d:
+    if k.shape[3] != d or (block_table is None and k.shape[0] != B):
         raise ValueError("k/v do not match q")
     if k.stride() != v.stride() or (k.numel() and k.stride(3) != 1):
         raise ValueError("k and v must share strides and have a contiguous channel axis")
@@ -158,14 +165,21 @@ def make_desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seq_lens, scale
     seq = np.ascontiguousarray(seq_lens, dtype=np.int32)
     if seq.shape != (B,):
         raise ValueError("seq_lens must be [B]")
-    if B and int(seq.max()) > k.shape[2]:
-        raise ValueError("seq_lens exceeds the cache length")
+    bt_ptr, block_tokens, max_blocks = None, 0, 0
+    if block_table is None:
+        if B and int(seq.max()) > k.shape[2]:
+            raise ValueError("seq_lens exceeds the cache length")
+    else:
+        if block_table.dtype != torch.int32 or block_table.dim() != 2 or block_table.shape[0] != B or \
+                not block_table.is_contiguous() or block_table.device != q.device:
+            raise ValueError("block_table must be a contiguous int32 [B, max_blocks] tensor on q's device")
+        bt_ptr, block_tokens, max_blocks = block_table.data_ptr(), int(k.shape[2]), int(block_table.shape[1])
     desc = _Desc(
         q.data_ptr(), k.data_ptr(), v.data_ptr(), k.stride(0), k.stride(1), k.stride(2), seq.ctypes.data,
         B, Hq, k.shape[1], d, HG_F16 if q.dtype == torch.float16 else HG_F32,
-        float(scale if scale is not None else 1.0 / math.sqrt(d)),
+        float(scale if scale is not None else 1.0 / math.sqrt(d)), bt_ptr, block_tokens, max_blocks,
     )
-    return desc, (q, k, v, seq)
+    return desc, (q, k, v, seq, block_table)
 
 
 def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> Tuple[Optional[torch.Tensor], int]:
@@ -222,11 +236,11 @@ def hg_attn_partial_workspace_size(desc, packed) -> int:
 
 
 def hg_attn_partial(q, k, v, seq_lens, ranges, scale=None, *, m=None, l=None, o=None, workspace=None, stream=None,
-                    desc=None):
+                    desc=None, block_table=None):
     """Per-range statistics.  Returns (m [R,Hq], l [R,Hq], o [R,Hq,d]) fp32 device tensors."""
     lib = load_library()
     if desc is None:
-        desc, keep = make_desc(q, k, v, seq_lens, scale)
+        desc, keep = make_desc(q, k, v, seq_lens, scale, block_table)
     else:
         keep = None
     packed = pack_ranges(ranges)
@@ -291,11 +305,11 @@ def hg_attn_full_workspace_size(desc) -> int:
 
 
 def hg_attn_full(q, k, v, seq_lens, scale=None, *, out=None, lse=None, want_lse=True, workspace=None, stream=None,
-                 desc=None):
+                 desc=None, block_table=None):
     """Unsplit attention over the whole cache.  Returns (out [B,Hq,d], lse [B,Hq] or None)."""
     lib = load_library()
     if desc is None:
-        desc, keep = make_desc(q, k, v, seq_lens, scale)
+        desc, keep = make_desc(q, k, v, seq_lens, scale, block_table)
     else:
         keep = None
     dev = q.device

@@ -239,3 +239,32 @@ def proxy_query(q: torch.Tensor, cosine: float, seed: int) -> torch.Tensor:
     noise = noise / noise.norm(dim=-1, keepdim=True)
     mixed = cosine * qn + math.sqrt(max(0.0, 1.0 - cosine * cosine)) * noise
     return (mixed * q32.norm(dim=-1, keepdim=True)).to(q.dtype)
+
+
+def make_paged(w: Workload, block_tokens: int, seed: int = 0):
+    """The same cache as a paged pool: K, V pools [n_blocks, Hkv, block_tokens, d] whose physical
+    blocks are in a seeded random order, and the block table int32 [B, max_blocks] (unused
+    entries point at block 0, which holds real data of some other place, so that a reader which
+    consults them computes a wrong answer rather than touching unmapped memory)."""
+    B, Hkv, nmax, d = w.k.shape
+    bt = int(block_tokens)
+    per_seq = [(int(n) + bt - 1) // bt for n in w.seq_lens]
+    max_blocks = max(max(per_seq), 1)
+    n_blocks = max(sum(per_seq), 1)
+    rng = np.random.RandomState(_stream_seed(seed, 29))
+    perm = rng.permutation(n_blocks)
+    table = np.zeros((B, max_blocks), dtype=np.int32)
+    dev = w.k.device
+    k_pool = torch.zeros((n_blocks, Hkv, bt, d), dtype=w.k.dtype, device=dev)
+    v_pool = torch.zeros((n_blocks, Hkv, bt, d), dtype=w.v.dtype, device=dev)
+    nxt = 0
+    for b in range(B):
+        n = int(w.seq_lens[b])
+        for i in range(per_seq[b]):
+            p = int(perm[nxt])
+            nxt += 1
+            table[b, i] = p
+            rows = min(bt, n - i * bt)
+            k_pool[p, :, :rows] = w.k[b, :, i * bt:i * bt + rows]
+            v_pool[p, :, :rows] = w.v[b, :, i * bt:i * bt + rows]
+    return k_pool, v_pool, torch.from_numpy(table).to(dev)

@@ -33,7 +33,8 @@ def _desc(seq_lens, batch=None, hq=4, hkv=2, d=128, dtype=0, stride_t=None, q=FA
     batch = len(seq) if batch is None else batch
     stride_t = d if stride_t is None else stride_t
     nmax = max(int(seq.max()), 1) if len(seq) else 1
-    desc = B._Desc(q, k, v, hkv * nmax * stride_t, nmax * stride_t, stride_t, seq.ctypes.data, batch, hq, hkv, d, dtype, scale)
+    desc = B._Desc(q, k, v, hkv * nmax * stride_t, nmax * stride_t, stride_t, seq.ctypes.data, batch, hq, hkv, d, dtype, scale,
+                   None, 0, 0)
     desc._keep = seq
     return desc
 
