@@ -145,6 +145,21 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
     pq_select_ms, _ = _time_steps(postqk_select, max(steps // 4, 1), max(warmup // 4, 1), torch)
     pq_rest_ms, _ = _time_steps(postqk_rest, max(steps // 4, 1), max(warmup // 4, 1), torch)
 
+    # the same cache as a paged pool (16-token blocks in shuffled physical order), same step
+    paged = {}
+    for bt in (16, 256):
+        kp, vp, table = W.make_paged(w, bt, seed=1)
+        pdesc, pkeep = hg.make_desc(w.q, kp, vp, w.seq_lens, w.scale, table)
+
+        def paged_step():
+            hg.hg_attn_partial(w.q, kp, vp, w.seq_lens, packed, w.scale, m=m, l=l, o=o, workspace=ws, desc=pdesc)
+            hg.hg_attn_merge(m, l, o, w.group_ptr, out=out, lse=lse)
+
+        pms, _ = _time_steps(paged_step, max(steps // 4, 1), max(warmup // 4, 1), torch)
+        paged["block_%d" % bt] = {"us": pms * 1e3, "gbps": w.kv_bytes / (pms * 1e-3) / 1e9}
+        del kp, vp, table, pdesc, pkeep
+        torch.cuda.empty_cache()
+
     kv_bytes = w.kv_bytes
     res = {
         "workload": spec.name,
@@ -174,6 +189,7 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
             "select_resident_merge_us": pq_rest_ms * 1e3,
             "us": (pq_logits_ms + pq_rest_ms) * 1e3,
         },
+        "paged_cache": paged,
         "concat_route": {
             "logits_us": logits_ms * 1e3,
             "concat_us": concat_ms * 1e3,
@@ -292,6 +308,7 @@ def main():
         "full_path": {"us": head["full_path_us"], "gbps": head["full_path_gbps"]},
         "concat_route": head["concat_route"],
         "post_qk_route": head["post_qk_route"],
+        "paged_cache": head["paged_cache"],
         "other_workloads": others,
         "paper_context": PAPER_CONTEXT,
     }
