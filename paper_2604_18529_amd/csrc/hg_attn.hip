@@ -291,6 +291,25 @@ hg_status stage_groups(const int32_t *group_ptr, int32_t n_groups, int32_t *dst,
     return launch_status("group table upload");
 }
 
+// True when no (range, stream) pair is cut by a span boundary and no range is empty: every
+// segment is then a whole pair, the streaming kernel writes the results itself and the reduce
+// launch is skipped.  (Checked only for tables small enough for the check to be free.)
+bool plan_is_direct(const Plan &p, int32_t n_ranges, int64_t n_streams)
+{
+#ifdef HG_NO_DIRECT
+    return false;
+#endif
+    if (p.ws.total == 0 || n_streams * n_ranges > 65536) return false;
+    for (int64_t s = 0; s < n_streams; ++s)
+        for (int32_t r = 0; r < n_ranges; ++r) {
+            const int64_t len = p.entries[r + 1].pre - p.entries[r].pre;
+            if (len == 0) return false;
+            const int64_t p0 = s * p.ws.ltok + p.entries[r].pre;
+            if (p0 / p.ws.span != (p0 + len - 1) / p.ws.span) return false;
+        }
+    return true;
+}
+
 // Shared by hg_attn_partial (normalise = 0) and hg_attn_full (normalise = 1).
 hg_status run(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, int normalise, float *m, float *l,
               float *o, void *workspace, size_t ws_bytes, void *stream_v)
@@ -309,6 +328,11 @@ hg_status run(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, i
     st = stage_table(p, n_ranges, ws, stream, pa.tab);
     if (st != HG_OK) return st;
     fill_stream_args(d, p, ws, pa);
+    pa.direct = plan_is_direct(p, n_ranges, (int64_t)d->n_kv_heads * p.ws.n_chunks) ? 1 : 0;
+    pa.normalise = normalise;
+    pa.out_m = m;
+    pa.out_l = l;
+    pa.out_o = o;
     if (p.n_workgroups > 0) {
         dim3 grid((unsigned)p.n_workgroups);
         // In timing mode the kernel is launched g_prof_repeat times back to back between one pair
@@ -322,6 +346,7 @@ hg_status run(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, i
         st = launch_status("partial kernel");
         if (st != HG_OK) return st;
     }
+    if (pa.direct) return HG_OK;
 
     ReduceArgs ra;
     std::memset(&ra, 0, sizeof(ra));

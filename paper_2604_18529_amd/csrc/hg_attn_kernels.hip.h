@@ -110,6 +110,11 @@ struct PartialArgs {
     PageMap pages;
     float qscale;                          // scale * log2(e); plain scale in logits mode
     float *ws_m, *ws_l, *ws_o;             // segment records [slot][gt], [slot][gt][D]; m in log2 units
+    // direct mode (statistics only): no (range, stream) pair is cut by a span boundary, so every
+    // segment IS a whole pair and its result goes straight to the caller's arrays; the reduce
+    // kernel is not launched.  normalise as in ReduceArgs.
+    int32_t direct, normalise;
+    float *out_m, *out_l, *out_o;
     float *logits;                         // [Hq][ltok]: written in logits mode, read in concat mode
     const float *gs_m, *gs_l;              // concat mode: [n_groups][Hq][kConcatSlices] partial (max in log2 units, sum)
     WorkSplit ws;
@@ -224,7 +229,7 @@ __device__ __forceinline__ int find_range(const RangeTable &tab, int x)
     return lo;
 }
 
-// Walk the segments of this workgroup's span.  f(stream, range entry, t0, t1, col0, slot) is
+// Walk the segments of this workgroup's span.  f(stream, range index, range entry, t0, t1, col0, slot) is
 // called by every thread of the workgroup, in the same order (the control flow is uniform);
 // col0 is the position of token t0 in the concatenation of all ranges.
 template <typename F>
@@ -241,7 +246,7 @@ __device__ __forceinline__ void for_each_segment(const WorkSplit &ws, const Rang
         const int64_t left = p_end - p;
         const int len = left < (int64_t)(r_end - x) ? (int)left : r_end - x;
         const int t0 = e.begin + (x - e.pre);
-        f(s, e, t0, t0 + len, x, (int64_t)blockIdx.x + (int64_t)s * tab.n_ranges + r);
+        f(s, r, e, t0, t0 + len, x, (int64_t)blockIdx.x + (int64_t)s * tab.n_ranges + r);
         p += len;
         x += len;
         if (x == r_end) {
@@ -348,8 +353,37 @@ __device__ __forceinline__ float group_softmax_max(const float *gs_m, int64_t ba
     return m;
 }
 
+// Result of one segment for one (head, channel): a record for the reduce kernel, or, in direct
+// mode, the caller's triple / normalised output itself.  mx in log2 units.
+template <int D>
+__device__ __forceinline__ void write_segment_result(const PartialArgs &a, int64_t rec, int r_idx, int head, int c, float mx,
+                                                     float lt, float ot)
+{
+    if (!a.direct) {
+        a.ws_o[rec * D + c] = ot;
+        if (c == 0) {
+            a.ws_m[rec] = mx;
+            a.ws_l[rec] = lt;
+        }
+        return;
+    }
+    const int64_t rh = (int64_t)r_idx * a.ws.n_q_heads + head;
+    if (a.normalise) {
+        a.out_o[rh * D + c] = ot / lt;  // a segment is never empty
+        if (c == 0 && a.out_m) a.out_m[rh] = mx * kLn2 + logf(lt);
+    } else {
+        a.out_o[rh * D + c] = ot;
+        if (c == 0) {
+            a.out_m[rh] = mx * kLn2;
+            a.out_l[rh] = lt;
+        }
+    }
+}
+
+// (One workgroup per compute unit is launched on long inputs, so the register allocator is told
+// that two waves per SIMD is all the occupancy this kernel wants.)
 template <typename TR, int GT, int U, int MODE, bool PAGED>
-__global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArgs a)
+__global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2))) void hg_partial_kernel(const PartialArgs a)
 {
     constexpr int D = TR::D, EPL = TR::EPL, NV = TR::NV, EPV = TR::EPV, ES = TR::ES;
     constexpr int CH = 4 * U;  // tokens one wave takes per iteration
@@ -359,7 +393,7 @@ __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArg
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane & 15, grp = lane >> 4;
 
-    for_each_segment(a.ws, a.tab, [&](int stream, const RangeEntry &e, int t0, int t1, int col0, int64_t slot) __attribute__((always_inline)) {
+    for_each_segment(a.ws, a.tab, [&](int stream, int r_idx, const RangeEntry &e, int t0, int t1, int col0, int64_t slot) __attribute__((always_inline)) {
     const int seq = e.seq;
     const int hk = stream / a.ws.n_chunks;
     const int chunk = stream - hk * a.ws.n_chunks;
@@ -453,6 +487,10 @@ __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArg
         if constexpr (PAGED) {
             if (tb + kValuWaves * CH < t1) lookup(tb + kValuWaves * CH, pg_next);
         }
+        // Every load of this iteration is issued before any of its arithmetic: the bytes in
+        // flight per wave are what the kernel's bandwidth rests on, and without this fence the
+        // instruction scheduler is free to trade them for a lower register count.
+        __builtin_amdgcn_sched_barrier(0);
 
         // logits of the U tokens of this lane group, for every head of the chunk
         float s[GT][U];
@@ -581,12 +619,7 @@ __global__ __launch_bounds__(kValuBlock) void hg_partial_kernel(const PartialArg
             lt += wt * sm[w][g][D + 1];
             ot += wt * sm[w][g][c];
         }
-        const int64_t th = slot * GT + g;
-        a.ws_o[th * D + c] = ot;
-        if (c == 0) {
-            a.ws_m[th] = mx;
-            a.ws_l[th] = lt;
-        }
+        write_segment_result<D>(a, slot * GT + g, r_idx, h0 + g, c, mx, lt, ot);
     }
     __syncthreads();  // the next segment reuses sm
     });
@@ -659,7 +692,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     char *kls = smem + wave * kGqaWaveBytes;
     char *pls = kls + kGqaKBytes;
 
-    for_each_segment(a.ws, a.tab, [&](int stream, const RangeEntry &e, int t0, int t1, int col0, int64_t slot) __attribute__((always_inline)) {
+    for_each_segment(a.ws, a.tab, [&](int stream, int r_idx, const RangeEntry &e, int t0, int t1, int col0, int64_t slot) __attribute__((always_inline)) {
     const int seq = e.seq;
     const int hk = stream / a.ws.n_chunks;
     const int chunk = stream - hk * a.ws.n_chunks;
@@ -950,12 +983,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             lt += wt * sm[w][g][D + 1];
             ot += wt * sm[w][g][c];
         }
-        const int64_t th = slot * kGqaHeads + g;
-        a.ws_o[th * D + c] = ot;
-        if (c == 0) {
-            a.ws_m[th] = mx;
-            a.ws_l[th] = lt;
-        }
+        write_segment_result<D>(a, slot * kGqaHeads + g, r_idx, h0 + g, c, mx, lt, ot);
     }
     __syncthreads();  // the next segment reuses the staging areas
     });
