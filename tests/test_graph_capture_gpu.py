@@ -1,0 +1,76 @@
+"""The library enqueues kernels only (host tables travel in kernel arguments or through upload
+kernels; nothing is copied, set or allocated), so a call sequence can be recorded into a HIP
+graph.  The graph is replayed several times with new query values and eager work in between, and
+every replay is checked against the eager result and the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_18529_amd as hg
+from paper_2604_18529_amd import hg_attn as binding
+from paper_2604_18529_amd import workloads as W
+
+from parity_utils import check_out, kv_np, to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.mark.parametrize("many_ranges", [False, True])
+def test_partial_merge_and_full_replay_from_a_graph(many_ranges):
+    hg.hg_attn_set_tile_tokens(0)
+    spec = W.WorkloadSpec("graph", 2, 8, 2, 128, "f16", 2000, 3000, "dirichlet", 5, seed=80)
+    w = W.make_workload(spec, DEV)
+    ranges, gp = w.ranges, w.group_ptr
+    if many_ranges:  # more ranges and groups than fit in kernel arguments: upload kernels get recorded too
+        ranges, gp = [], [0]
+        for b, n in enumerate(w.seq_lens):
+            for i in range(150):
+                ranges.append((b, 10 * i, 10 * i + 10))
+            ranges.append((b, 1500, int(n)))
+            gp.append(len(ranges))
+    desc, keep = hg.make_desc(w.q, w.k, w.v, w.seq_lens, w.scale)
+    packed = hg.pack_ranges(ranges)
+    R, Hq, d = len(ranges), spec.n_q_heads, spec.head_dim
+    m = torch.empty((R, Hq), dtype=torch.float32, device=DEV)
+    l = torch.empty_like(m)
+    o = torch.empty((R, Hq, d), dtype=torch.float32, device=DEV)
+    out = torch.empty((spec.batch, Hq, d), dtype=torch.float32, device=DEV)
+    lse = torch.empty((spec.batch, Hq), dtype=torch.float32, device=DEV)
+    fout, flse = torch.empty_like(out), torch.empty_like(lse)
+    ws = torch.empty(max(binding.hg_attn_partial_workspace_size(desc, packed), 256), dtype=torch.uint8, device=DEV)
+    fws = torch.empty(max(binding.hg_attn_full_workspace_size(desc), 256), dtype=torch.uint8, device=DEV)
+    mws = torch.empty(4096, dtype=torch.uint8, device=DEV)
+
+    def step():
+        hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, packed, w.scale, m=m, l=l, o=o, workspace=ws, desc=desc)
+        hg.hg_attn_merge(m, l, o, gp, out=out, lse=lse, workspace=mws)
+        hg.hg_attn_full(w.q, w.k, w.v, w.seq_lens, w.scale, out=fout, lse=flse, workspace=fws, desc=desc)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(81)
+    for rep in range(4):
+        w.q.copy_(torch.randn(w.q.shape, generator=gen, device=DEV, dtype=torch.float32))  # new query, same buffers
+        out.zero_(); fout.zero_(); m.zero_()  # eager work between the replays
+        graph.replay()
+        torch.cuda.synchronize()
+        g_out, g_lse, g_fout = out.clone(), lse.clone(), fout.clone()
+        out.zero_(); fout.zero_()
+        step()  # eager, same inputs
+        torch.cuda.synchronize()
+        assert torch.equal(g_out, out) and torch.equal(g_lse, lse) and torch.equal(g_fout, fout), "replay %d" % rep
+        ref, rlse = oracle.attn_full(to_np(w.q), *kv_np(w), w.seq_lens, w.scale)
+        check_out(g_fout, flse, ref, rlse, "graph replay %d full" % rep)
+        if not many_ranges:
+            check_out(g_out, g_lse, ref, rlse, "graph replay %d merge" % rep)
+    del keep
