@@ -9,8 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libhg_attn.so")
 SOURCES = [os.path.join(CSRC, "hg_attn.hip")]
-HEADERS = [
-    os.path.join(CSRC, "hg_attn_kernels.hip.h"),
+HEADERS = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")) + [
     os.path.join(os.path.dirname(_HERE), "include", "hg_attn.h"),
 ]
 

@@ -3,7 +3,11 @@
 // GPU inside kernel arguments (small tables) or through chunked upload kernels (large tables),
 // so no memcpy semantics are relied upon and every call is safe to record into a HIP graph.
 
-#include "hg_attn_kernels.hip.h"
+#include "hg_combine.hip.h"
+#include "hg_common.hip.h"
+#include "hg_select.hip.h"
+#include "hg_stream_gqa.hip.h"
+#include "hg_stream_valu.hip.h"
 
 #include <cmath>
 #include <cstdio>

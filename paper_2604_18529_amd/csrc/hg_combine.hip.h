@@ -1,0 +1,245 @@
+// Small combining kernels: segment reduce, exact merge, the concat path's statistics and reduce,
+// table uploads and the calibration copy.
+#pragma once
+
+#include "hg_common.hip.h"
+
+namespace hg {
+
+// ---- segment records -> range triple (or normalised output) -----------------------------------
+
+constexpr int kReduceBlock = 512;
+
+// Shared tail of the two combining kernels.  Each of the S = kReduceBlock / D slices has folded
+// its share of the records into a running (mx, lt, ot) in ONE pass (independent loads, no
+// max pre-pass, so the kernel costs a single memory round trip); the slices are merged here.
+// Returns true in the threads of slice 0, which then hold the total (mx, lt, ot[c]).
+template <int D>
+__device__ __forceinline__ bool combine_slices(float &mx, float &lt, float &ot, int c, int sl)
+{
+    constexpr int S = kReduceBlock / D;
+    __shared__ float s_o[S][D];
+    __shared__ float s_m[S], s_l[S];
+    s_o[sl][c] = ot;
+    if (c == 0) {
+        s_m[sl] = mx;
+        s_l[sl] = lt;
+    }
+    __syncthreads();
+    if (sl != 0) return false;
+    float M = s_m[0];
+#pragma unroll
+    for (int i = 1; i < S; ++i) M = fmaxf(M, s_m[i]);
+    lt = 0.f;
+    ot = 0.f;
+#pragma unroll
+    for (int i = 0; i < S; ++i) {
+        const float wt = fast_exp2(s_m[i] - M);
+        lt += wt * s_l[i];
+        ot += wt * s_o[i][c];
+    }
+    mx = M;
+    return true;
+}
+
+// One workgroup per (range, query head).  The segment records of the range are dealt round-robin
+// to kReduceBlock / D slices of D threads (one thread per channel), so that a range cut into
+// hundreds of segments is not one long chain of dependent loads.
+template <int D>
+__global__ __launch_bounds__(kReduceBlock) void hg_segment_reduce_kernel(const ReduceArgs a)
+{
+    constexpr int S = kReduceBlock / D;
+    const int r = blockIdx.x, h = blockIdx.y;
+    const int c = threadIdx.x % D, sl = threadIdx.x / D;
+
+    // the records of (range r, stream of head h) sit in slots w + stream * n_ranges + r for the
+    // workgroups w whose span overlaps the pair's positions [p0, p1)
+    const int hk = h / a.ws.group, gi = h - hk * a.ws.group;
+    const int chunk = gi / a.ws.gt, gl = gi - chunk * a.ws.gt;
+    const int stream = hk * a.ws.n_chunks + chunk;
+    const int pre0 = table_entry(a.tab, r).pre, pre1 = table_entry(a.tab, r + 1).pre;
+    const int64_t p0 = (int64_t)stream * a.ws.ltok + pre0, p1 = (int64_t)stream * a.ws.ltok + pre1;
+    const int64_t w0 = pre1 > pre0 ? p0 / a.ws.span : 0;
+    const int n_rec = pre1 > pre0 ? (int)((p1 - 1) / a.ws.span - w0) + 1 : 0;
+    const int64_t rec0 = (w0 + (int64_t)stream * a.tab.n_ranges + r) * a.ws.gt + gl;  // record i at rec0 + i * gt
+
+    float mx = kNegBig, lt = 0.f, ot = 0.f;  // log2 units
+#pragma unroll 4
+    for (int i = sl; i < n_rec; i += S) {
+        const int64_t th = rec0 + (int64_t)i * a.ws.gt;
+        const float mi = a.ws_m[th], li = a.ws_l[th], oi = a.ws_o[th * D + c];
+        const float mn = fmaxf(mx, mi);
+        const float wa = fast_exp2(mx - mn), wb = fast_exp2(mi - mn);
+        lt = lt * wa + li * wb;
+        ot = ot * wa + oi * wb;
+        mx = mn;
+    }
+    if (!combine_slices<D>(mx, lt, ot, c, sl)) return;
+
+    const int64_t rh = (int64_t)r * a.ws.n_q_heads + h;
+    const bool empty = !(lt > 0.f);
+    if (a.normalise) {
+        a.o_out[rh * D + c] = empty ? 0.f : ot / lt;
+        if (c == 0 && a.m_out) a.m_out[rh] = empty ? -INFINITY : mx * kLn2 + logf(lt);
+    } else {
+        a.o_out[rh * D + c] = empty ? 0.f : ot;
+        if (c == 0) {
+            a.m_out[rh] = empty ? -INFINITY : mx * kLn2;
+            a.l_out[rh] = empty ? 0.f : lt;
+        }
+    }
+}
+
+// ---- exact merge of range triples ---------------------------------------------------------------
+
+// One workgroup per (group, query head); the group's triples are dealt to the slices as above.
+// Triples arrive in natural-log units and are folded in log2 units.
+template <int D>
+__global__ __launch_bounds__(kReduceBlock) void hg_merge_kernel(const MergeArgs a)
+{
+    constexpr int S = kReduceBlock / D;
+    const int gidx = blockIdx.x, h = blockIdx.y;
+    const int c = threadIdx.x % D, sl = threadIdx.x / D;
+    const int ts = a.tab.ext ? a.tab.ext[gidx] : a.tab.inl[gidx];
+    const int te = a.tab.ext ? a.tab.ext[gidx + 1] : a.tab.inl[gidx + 1];
+
+    float mx = kNegBig, lt = 0.f, ot = 0.f;
+#pragma unroll 4
+    for (int t = ts + sl; t < te; t += S) {
+        const int64_t th = (int64_t)t * a.n_q_heads + h;
+        const float li = a.l[th], oi = a.o[th * D + c];
+        const float mi = li != 0.f ? a.m[th] * kLog2e : kNegBig;  // identity element: ignored
+        const float mn = fmaxf(mx, mi);
+        const float wa = fast_exp2(mx - mn), wb = li != 0.f ? fast_exp2(mi - mn) : 0.f;
+        lt = lt * wa + li * wb;
+        ot = ot * wa + oi * wb;
+        mx = mn;
+    }
+    if (!combine_slices<D>(mx, lt, ot, c, sl)) return;
+
+    const int64_t gh = (int64_t)gidx * a.n_q_heads + h;
+    const bool empty = !(lt > 0.f);
+    a.out[gh * D + c] = empty ? 0.f : ot / lt;
+    if (c == 0 && a.lse) a.lse[gh] = empty ? -INFINITY : mx * kLn2 + logf(lt);
+}
+
+// ---- concat path: one softmax over the concatenated logits of a group --------------------------
+
+__device__ __forceinline__ int group_entry(const GroupTable &g, int i) { return g.ext ? g.ext[i] : g.inl[i]; }
+
+// Partial (max, sum of exp) of one slice of a group's logits row.  The ranges of a group are
+// consecutive table entries, so their logits are one contiguous piece [c0, c1) of the row: the
+// concatenation the paper describes is already how the logits are stored.
+// Grid (kConcatSlices, n_q_heads, n_groups), 256 threads.
+__global__ __launch_bounds__(256) void hg_concat_stats_kernel(const ConcatStatsArgs a)
+{
+    __shared__ float s_red[4];
+    const int z = blockIdx.x, h = blockIdx.y, gi = blockIdx.z;
+    const int c0 = table_entry(a.tab, group_entry(a.groups, gi)).pre;
+    const int c1 = table_entry(a.tab, group_entry(a.groups, gi + 1)).pre;
+    const int per = (c1 - c0 + kConcatSlices - 1) / kConcatSlices;
+    const int b = c0 + z * per < c1 ? c0 + z * per : c1;
+    const int e = b + per < c1 ? b + per : c1;
+    const float *row = a.logits + (int64_t)h * a.ltok;
+
+    // one pass: every thread folds groups of four logits into a running (max, sum) pair
+    float mx = kNegBig, lt = 0.f;
+    for (int i = b + 4 * (int)threadIdx.x; i < e; i += 4 * 256) {
+        float x[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[j] = row[i + j < e ? i + j : e - 1] * kLog2e * 1.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[j] = i + j < e ? x[j] : kNegBig;
+        const float mn = fmaxf(fmaxf(mx, fmaxf(x[0], x[1])), fmaxf(x[2], x[3]));
+        lt = lt * fast_exp2(mx - mn) + ((fast_exp2(x[0] - mn) + fast_exp2(x[1] - mn)) + (fast_exp2(x[2] - mn) + fast_exp2(x[3] - mn)));
+        mx = mn;
+    }
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1) {
+        const float mo = __shfl_xor(mx, step, 64), lo = __shfl_xor(lt, step, 64);
+        const float mn = fmaxf(mx, mo);
+        lt = lt * fast_exp2(mx - mn) + lo * fast_exp2(mo - mn);
+        mx = mn;
+    }
+    __shared__ float s_l[4];
+    if ((threadIdx.x & 63) == 0) {
+        s_red[threadIdx.x >> 6] = mx;
+        s_l[threadIdx.x >> 6] = lt;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) L += s_l[w] * fast_exp2(s_red[w] - M);
+        const int64_t idx = ((int64_t)gi * a.n_q_heads + h) * kConcatSlices + z;
+        a.gs_m[idx] = M;
+        a.gs_l[idx] = L;
+    }
+}
+
+// out[group][head] = (sum of the exp(s - M).v records of all segments of the group's ranges) / L,
+// lse = M + log L, with (M, L) the group's global softmax statistics.  Grid (n_groups, n_q_heads).
+template <int D>
+__global__ __launch_bounds__(kReduceBlock) void hg_concat_reduce_kernel(const ConcatReduceArgs a)
+{
+    constexpr int S = kReduceBlock / D;
+    __shared__ float s_o[S][D];
+    const int gi = blockIdx.x, h = blockIdx.y;
+    const int c = threadIdx.x % D, sl = threadIdx.x / D;
+    const int hk = h / a.ws.group, gidx = h - hk * a.ws.group;
+    const int chunk = gidx / a.ws.gt, gl = gidx - chunk * a.ws.gt;
+    const int stream = hk * a.ws.n_chunks + chunk;
+    const int r0 = group_entry(a.groups, gi), r1 = group_entry(a.groups, gi + 1);
+
+    float ot = 0.f;
+    for (int r = r0; r < r1; ++r) {
+        const int pre0 = table_entry(a.tab, r).pre, pre1 = table_entry(a.tab, r + 1).pre;
+        if (pre1 == pre0) continue;
+        const int64_t p0 = (int64_t)stream * a.ws.ltok + pre0, p1 = (int64_t)stream * a.ws.ltok + pre1;
+        const int64_t w0 = p0 / a.ws.span;
+        const int n_rec = (int)((p1 - 1) / a.ws.span - w0) + 1;
+        const int64_t rec0 = (w0 + (int64_t)stream * a.tab.n_ranges + r) * a.ws.gt + gl;
+#pragma unroll 4
+        for (int i = sl; i < n_rec; i += S) ot += a.ws_o[(rec0 + (int64_t)i * a.ws.gt) * D + c];
+    }
+    s_o[sl][c] = ot;
+    __syncthreads();
+    if (sl != 0) return;
+    ot = 0.f;
+#pragma unroll
+    for (int i = 0; i < S; ++i) ot += s_o[i][c];
+    const int64_t gh = (int64_t)gi * a.ws.n_q_heads + h;
+    float mx = kNegBig, lt = 0.f;  // the group's global maximum and sum of exp
+    for (int z = 0; z < kConcatSlices; ++z) {
+        const float mi = a.gs_m[gh * kConcatSlices + z], li = a.gs_l[gh * kConcatSlices + z];
+        const float mn = fmaxf(mx, mi);
+        lt = lt * fast_exp2(mx - mn) + li * fast_exp2(mi - mn);
+        mx = mn;
+    }
+    a.out[gh * D + c] = lt > 0.f ? ot / lt : 0.f;
+    if (c == 0 && a.lse) a.lse[gh] = lt > 0.f ? mx * kLn2 + logf(lt) : -INFINITY;
+}
+
+// ---- table upload (host tables reach the device through kernel arguments only) ----------------
+
+__global__ void hg_upload_ranges_kernel(RangeEntry *dst, int count, const RangeChunk chunk)
+{
+    const int i = threadIdx.x;
+    if (i < count) dst[i] = chunk.e[i];
+}
+
+__global__ void hg_upload_ints_kernel(int32_t *dst, int count, const IntChunk chunk)
+{
+    const int i = threadIdx.x;
+    if (i < count) dst[i] = chunk.e[i];
+}
+
+// Plain copy of known traffic (n bytes read, n bytes written): the yardstick that profiler byte
+// counters are scaled by.
+__global__ __launch_bounds__(256) void hg_calibration_copy_kernel(hg_u32x4 *dst, const hg_u32x4 *src, size_t n_vec)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+}  // namespace hg

@@ -1,0 +1,355 @@
+// Device code of the partitioned decode-attention library (gfx950, wave64): definitions shared by
+// all kernels -- argument structures, the work split, storage traits and small helpers.
+//
+//   hg_stream_valu.hip.h   hg_partial_kernel: streams the K and V rows of a span of tokens once and
+//                          folds them into softmax statistics (m, l, O) per query head (paper
+//                          Section 4.2: the per-token logit stage, run here per positional
+//                          range); also the logits-export and concat modes.
+//   hg_stream_gqa.hip.h    hg_partial_gqa_kernel: the same on the matrix cores for grouped-query
+//                          attention.
+//   hg_combine.hip.h       hg_segment_reduce_kernel (segment records -> range triple or, for the
+//                          unsplit path, normalised output), hg_merge_kernel (exact recombination
+//                          of range triples: Section 4.2.3, Token Concatenator, in statistics
+//                          form), the concat path's statistics and reduce kernels, table uploads.
+//   hg_select.hip.h        hg_select_kernel: Post-QK^T top-k selection.
+//
+// Work distribution.  The tokens of all ranges, repeated for every stream (KV head x chunk of
+// query heads), form one linear space of `total` positions: position p = s * ltok + x, where
+// x runs over the concatenated ranges.  Workgroup w owns positions [w * span, (w+1) * span), so
+// every workgroup streams the same number of bytes whatever the shape of the partition table,
+// and the launch is sized to the chip (one workgroup per compute unit for long inputs).  A
+// workgroup's span is cut into segments at range and stream boundaries; each segment yields one
+// (m, l, O) record in slot  w + s * n_ranges + r  (strictly increasing along the linear order,
+// hence unique), and the records of a (range, stream) pair occupy a contiguous run of slots.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hg {
+
+constexpr int kInlineRanges = 64;   // range-table entries carried inside the kernel arguments
+constexpr int kInlineGroups = 256;  // CSR offsets carried inside the merge kernel's arguments
+constexpr int kUploadRanges = 128;  // entries per table-upload launch
+constexpr int kUploadInts = 512;
+// Waves per streaming workgroup and workgroups per compute unit (tuning constants).
+#ifndef HG_VALU_WAVES
+#define HG_VALU_WAVES 4
+#endif
+#ifndef HG_GQA_WAVES
+#define HG_GQA_WAVES 4
+#endif
+#ifndef HG_VALU_U
+#define HG_VALU_U 4  // rows in flight per 16-lane group (kernels with 1 or 2 heads per stream)
+#endif
+#ifndef HG_VALU_WG_PER_CU
+#define HG_VALU_WG_PER_CU 1
+#endif
+#ifndef HG_GQA_WG_PER_CU
+#define HG_GQA_WG_PER_CU 1
+#endif
+constexpr int kValuWaves = HG_VALU_WAVES;
+constexpr int kGqaWaves = HG_GQA_WAVES;
+constexpr int kValuBlock = 64 * kValuWaves;
+constexpr int kGqaBlock = 64 * kGqaWaves;
+constexpr int kValuWorkgroupsPerCu = HG_VALU_WG_PER_CU;
+constexpr int kGqaWorkgroupsPerCu = HG_GQA_WG_PER_CU;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+// "no token seen yet" marker for running maxima (log2 domain).  Finite, so that
+// exp2(marker - marker) = 1 multiplies an all-zero state instead of producing NaN.
+constexpr float kNegBig = -3.0e38f;
+
+// pre = number of tokens in the ranges before this one (prefix sum of the range lengths);
+// grp = the concatenation group the range belongs to (used by the concat path only).
+struct RangeEntry {
+    int32_t seq, begin, end, pre, grp;
+};
+
+// What a streaming kernel instance does with the rows it reads.
+constexpr int kModeStats = 0;   // K and V -> (m, l, O) records                     (hg_attn_partial / hg_attn_full)
+constexpr int kModeLogits = 1;  // K only  -> raw scaled logits                     (hg_attn_logits)
+constexpr int kModeConcat = 2;  // V and given logits + group softmax stats -> sum p.v records  (hg_attn_concat)
+constexpr int kConcatSlices = 32;  // partial (max, sum) records per (group, head) of the concat path
+
+// The range table travels by value in the kernel arguments when it is small; otherwise `ext`
+// points at a device copy.  Entry n_ranges is a sentinel whose pre is ltok.
+struct RangeTable {
+    const RangeEntry *ext;
+    int32_t n_ranges;
+    int32_t pad;
+    RangeEntry inl[kInlineRanges + 1];
+};
+
+// How the linear work space is laid out and cut (shared by the streaming and reduce kernels).
+struct WorkSplit {
+    int64_t total;    // n_streams * ltok
+    int32_t ltok;     // tokens in all ranges together
+    int32_t span;     // positions per workgroup
+    int32_t group;    // query heads per KV head
+    int32_t gt;       // query heads per stream (chunk of a group)
+    int32_t n_chunks; // streams per KV head
+    int32_t n_q_heads;
+};
+
+// Paged cache: token t of sequence b lives in physical block table[b * max_blocks + (t >> shift)]
+// at row t & mask; stride_b is then the distance between physical blocks.  table == nullptr
+// means a contiguous cache.
+struct PageMap {
+    const int32_t *table;
+    int32_t shift, mask, max_blocks, pad;
+};
+
+struct PartialArgs {
+    const void *q, *k, *v;
+    int64_t stride_b, stride_h, stride_t;  // elements
+    PageMap pages;
+    float qscale;                          // scale * log2(e); plain scale in logits mode
+    float *ws_m, *ws_l, *ws_o;             // segment records [slot][gt], [slot][gt][D]; m in log2 units
+    // direct mode (statistics only): no (range, stream) pair is cut by a span boundary, so every
+    // segment IS a whole pair and its result goes straight to the caller's arrays; the reduce
+    // kernel is not launched.  normalise as in ReduceArgs.
+    int32_t direct, normalise;
+    float *out_m, *out_l, *out_o;
+    float *logits;                         // [Hq][ltok]: written in logits mode, read in concat mode
+    const float *gs_m, *gs_l;              // concat mode: [n_groups][Hq][kConcatSlices] partial (max in log2 units, sum)
+    WorkSplit ws;
+    RangeTable tab;
+};
+
+struct ReduceArgs {
+    const float *ws_m, *ws_l, *ws_o;
+    int32_t normalise;  // 0: write the range triple (m, l, o); 1: write out = O/L and lse
+    float *m_out, *l_out, *o_out;  // [n_ranges][Hq](..[D])  or  out/lse when normalise
+    WorkSplit ws;
+    RangeTable tab;
+};
+
+struct GroupTable {
+    const int32_t *ext;
+    int32_t n_groups;
+    int32_t inl[kInlineGroups + 1];
+};
+
+struct MergeArgs {
+    const float *m, *l, *o;
+    float *out, *lse;
+    int32_t n_q_heads;
+    GroupTable tab;
+};
+
+struct ConcatStatsArgs {
+    const float *logits;  // [Hq][ltok], natural-log units
+    float *gs_m, *gs_l;   // [n_groups][Hq][kConcatSlices]
+    int32_t ltok, n_q_heads;
+    GroupTable groups;    // CSR over ranges
+    RangeTable tab;
+};
+
+struct ConcatReduceArgs {
+    const float *ws_o;        // segment records [slot][gt][D]: sums of p.v
+    const float *gs_m, *gs_l;
+    float *out, *lse;
+    WorkSplit ws;
+    GroupTable groups;
+    RangeTable tab;
+};
+
+constexpr int kSelectBlock = 1024;  // threads of the selection kernel (16 waves)
+constexpr int kMaxTopK = 4096;      // kept tokens per (group, head): their columns and logits sit in LDS
+
+struct SelectArgs {
+    const float *logits;  // [Hq][ltok], natural-log units
+    const void *v;
+    int64_t stride_b, stride_h, stride_t;  // elements
+    int32_t ltok, n_q_heads, group, top_k;
+    int32_t *sel;         // [n_groups][Hq][top_k] or NULL
+    float *m, *l, *o;     // [n_groups][Hq](..[D])
+    // two-stage selection of long groups: every group is cut into `parts` column intervals whose
+    // own top_k candidates (value, column; -inf padded) are the input of the second stage
+    int32_t parts;
+    float *cand_val;      // [n_groups][Hq][parts][top_k]
+    int32_t *cand_col;
+    GroupTable groups;
+    RangeTable tab;
+};
+
+constexpr int kSelectDirect = 0;      // one workgroup selects from the group's logits row
+constexpr int kSelectCandidates = 1;  // stage 1: per part, write its top_k candidates
+constexpr int kSelectFromCands = 2;   // stage 2: select among the parts' candidates
+
+struct RangeChunk {
+    RangeEntry e[kUploadRanges];
+};
+struct IntChunk {
+    int32_t e[kUploadInts];
+};
+
+// ---- small device helpers ----------------------------------------------------------------------
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row ends with the total.
+__device__ __forceinline__ float row16_sum(float x)
+{
+    x += dpp_move<0xB1>(x);   // quad_perm [1,0,3,2]
+    x += dpp_move<0x4E>(x);   // quad_perm [2,3,0,1]
+    x += dpp_move<0x141>(x);  // row_half_mirror: quads 0<->1, 2<->3
+    x += dpp_move<0x140>(x);  // row_mirror: halves swap
+    return x;
+}
+
+__device__ __forceinline__ RangeEntry table_entry(const RangeTable &tab, int i)
+{
+    return tab.ext ? tab.ext[i] : tab.inl[i];
+}
+
+// Largest r with pre[r] <= x (0 <= x < ltok); it contains x because empty ranges share their
+// successor's prefix.
+__device__ __forceinline__ int find_range(const RangeTable &tab, int x)
+{
+    int lo = 0, hi = tab.n_ranges;  // invariant: pre[lo] <= x < pre[hi]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (table_entry(tab, mid).pre <= x)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    return lo;
+}
+
+// Walk the segments of this workgroup's span.  f(stream, range index, range entry, t0, t1, col0, slot) is
+// called by every thread of the workgroup, in the same order (the control flow is uniform);
+// col0 is the position of token t0 in the concatenation of all ranges.
+template <typename F>
+__device__ __forceinline__ void for_each_segment(const WorkSplit &ws, const RangeTable &tab, F &&f)
+{
+    int64_t p = (int64_t)blockIdx.x * ws.span;
+    const int64_t p_end = p + ws.span < ws.total ? p + ws.span : ws.total;
+    int s = (int)(p / ws.ltok);
+    int x = (int)(p - (int64_t)s * ws.ltok);
+    int r = find_range(tab, x);
+    while (p < p_end) {
+        const RangeEntry e = table_entry(tab, r);
+        const int r_end = table_entry(tab, r + 1).pre;
+        const int64_t left = p_end - p;
+        const int len = left < (int64_t)(r_end - x) ? (int)left : r_end - x;
+        const int t0 = e.begin + (x - e.pre);
+        f(s, r, e, t0, t0 + len, x, (int64_t)blockIdx.x + (int64_t)s * tab.n_ranges + r);
+        p += len;
+        x += len;
+        if (x == r_end) {
+            if (x == ws.ltok) {  // next stream, first non-empty range
+                ++s;
+                x = 0;
+                r = find_range(tab, 0);
+            } else {
+                r = find_range(tab, x);
+            }
+        }
+    }
+}
+
+// ---- storage traits ----------------------------------------------------------------------------
+
+// K and V are read exactly once, so their loads carry the non-temporal hint: measured on MI355X
+// a pure read stream reaches about 7.1 TB/s with it against about 6.3 TB/s without.
+#ifndef HG_NT_LOADS
+#define HG_NT_LOADS 1
+#endif
+
+typedef unsigned int hg_u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int hg_u32x2 __attribute__((ext_vector_type(2)));
+
+template <int VB>
+struct RawVec;
+template <>
+struct RawVec<16> {
+    hg_u32x4 d;
+};
+template <>
+struct RawVec<8> {
+    hg_u32x2 d;
+};
+
+template <int D_, bool F16_>
+struct Traits {
+    static constexpr int D = D_;
+    static constexpr bool F16 = F16_;
+    static constexpr int ES = F16_ ? 2 : 4;
+    static constexpr int LANE_BYTES = D_ * ES / 16;           // bytes of a row held by one lane
+    static constexpr int VB = LANE_BYTES >= 16 ? 16 : 8;      // bytes per load
+    static constexpr int NV = LANE_BYTES / VB;                // loads per row per lane
+    static constexpr int EPV = VB / ES;                       // elements per load
+    static constexpr int EPL = NV * EPV;                      // elements per lane
+    static constexpr int SEG = 16 * EPV;                      // elements covered by one wave-row load
+    using Raw = RawVec<VB>;
+
+    // element offset inside a row of lane `sub`'s vector j
+    __device__ static __forceinline__ int vec_offset(int sub, int j) { return j * SEG + sub * EPV; }
+
+    // STREAM = true for K and V (read once), false for q (re-read by every workgroup of the head)
+    template <bool STREAM>
+    __device__ static __forceinline__ Raw load(const char *row_ptr, int sub, int j)
+    {
+        Raw r;
+        const char *p = row_ptr + (size_t)vec_offset(sub, j) * ES;
+        using vec_t = decltype(r.d);
+        if constexpr (STREAM && HG_NT_LOADS)
+            r.d = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(p));
+        else
+            r.d = *reinterpret_cast<const vec_t *>(p);
+        return r;
+    }
+
+    __device__ static __forceinline__ void widen(const Raw &r, float *out)
+    {
+        if constexpr (F16_) {
+            typedef _Float16 hvec __attribute__((ext_vector_type(EPV)));
+            hvec h = __builtin_bit_cast(hvec, r.d);
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) out[i] = (float)h[i];
+        } else {
+            typedef float fvec __attribute__((ext_vector_type(EPV)));
+            fvec f = __builtin_bit_cast(fvec, r.d);
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) out[i] = f[i];
+        }
+    }
+};
+
+// Result of one segment for one (head, channel): a record for the reduce kernel, or, in direct
+// mode, the caller's triple / normalised output itself.  mx in log2 units.
+template <int D>
+__device__ __forceinline__ void write_segment_result(const PartialArgs &a, int64_t rec, int r_idx, int head, int c, float mx,
+                                                     float lt, float ot)
+{
+    if (!a.direct) {
+        a.ws_o[rec * D + c] = ot;
+        if (c == 0) {
+            a.ws_m[rec] = mx;
+            a.ws_l[rec] = lt;
+        }
+        return;
+    }
+    const int64_t rh = (int64_t)r_idx * a.ws.n_q_heads + head;
+    if (a.normalise) {
+        a.out_o[rh * D + c] = ot / lt;  // a segment is never empty
+        if (c == 0 && a.out_m) a.out_m[rh] = mx * kLn2 + logf(lt);
+    } else {
+        a.out_o[rh * D + c] = ot;
+        if (c == 0) {
+            a.out_m[rh] = mx * kLn2;
+            a.out_l[rh] = lt;
+        }
+    }
+}
+
+}  // namespace hg

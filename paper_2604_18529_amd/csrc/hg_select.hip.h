@@ -1,0 +1,287 @@
+// Post-QK^T selection kernel.
+#pragma once
+
+#include "hg_common.hip.h"
+#include "hg_combine.hip.h"
+
+namespace hg {
+
+// ---- Post-QK^T selection: top-k logits of a group, folded with their V rows into (m, l, O) ------
+//
+// One workgroup of 16 waves per (group, query head).
+//   1. radix select on order-preserving integer keys of the fp32 logits: four 8-bit passes, each
+//      a histogram over the elements that still match the prefix, find the key T of the k-th
+//      largest logit and how many elements equal to T are to be kept (ties go to lower columns);
+//   2. one ordered sweep compacts the kept columns into LDS in ascending (token) order: a kept
+//      element's slot is (#greater before it) + min(#equal before it, k_eq), which a single
+//      packed block scan provides;
+//   3. the kept logits give m and the weights exp(s - m); the 16 waves gather the kept V rows
+//      (four rows per wave load, 16 lanes per row as in the streaming kernel) and sum p.v.
+// A group of a million tokens would keep one compute unit busy for a millisecond, so long groups
+// are cut into parts: stage 1 runs steps 1-2 per part and writes the part's top_k candidates
+// (the global top_k is a subset of their union, and candidates stay in ascending column order),
+// stage 2 runs steps 1-3 over the candidates.
+
+__device__ __forceinline__ uint32_t order_key(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // larger float <=> larger key
+}
+
+// Exclusive scan of v over the 1024 threads of the workgroup; total receives the sum.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *s_wave, uint32_t &total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t t = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += t;
+    }
+    if (lane == 63) s_wave[wave] = inc;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kSelectBlock / 64; ++w) {
+        const uint32_t t = s_wave[w];
+        before += w < wave ? t : 0u;
+        all += t;
+    }
+    __syncthreads();  // s_wave is reused by the next call
+    total = all;
+    return before + inc - v;
+}
+
+template <typename TR, int STAGE>
+__global__ __launch_bounds__(kSelectBlock) void hg_select_kernel(const SelectArgs a)
+{
+    constexpr int D = TR::D, EPL = TR::EPL, NV = TR::NV, EPV = TR::EPV, ES = TR::ES;
+    constexpr int NW = kSelectBlock / 64;
+    __shared__ uint32_t s_hist[256];
+    __shared__ uint32_t s_wave[NW];
+    __shared__ uint32_t s_prefix, s_krem;
+    __shared__ int32_t s_cols[kMaxTopK];   // kept columns, later their token positions
+    __shared__ float s_vals[kMaxTopK];     // kept logits, later their weights
+    __shared__ float s_red[NW];
+    __shared__ float s_acc[NW][D];
+
+    const int tid = threadIdx.x, h = blockIdx.y;
+    const int gi = STAGE == kSelectCandidates ? blockIdx.x / a.parts : blockIdx.x;
+    const int part = STAGE == kSelectCandidates ? blockIdx.x - gi * a.parts : 0;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r0 = group_entry(a.groups, gi), r1 = group_entry(a.groups, gi + 1);
+    const int c0 = table_entry(a.tab, r0).pre, c1 = table_entry(a.tab, r1).pre;
+    const int64_t gh = (int64_t)gi * a.n_q_heads + h;
+
+    // the values this workgroup selects from: row[0..n), element i being logits column
+    // col_map ? col_map[i] : col_base + i
+    const float *row;
+    const int32_t *col_map = nullptr;
+    int n, col_base = 0, keep;
+    if constexpr (STAGE == kSelectDirect) {
+        row = a.logits + (int64_t)h * a.ltok + c0;
+        n = c1 - c0;
+        col_base = c0;
+        keep = n < a.top_k ? n : a.top_k;
+    } else if constexpr (STAGE == kSelectCandidates) {
+        const int per = (c1 - c0 + a.parts - 1) / a.parts;
+        const int b = c0 + part * per < c1 ? c0 + part * per : c1;
+        const int e = b + per < c1 ? b + per : c1;
+        row = a.logits + (int64_t)h * a.ltok + b;
+        n = e - b;
+        col_base = b;
+        keep = n < a.top_k ? n : a.top_k;
+    } else {
+        const int64_t base = gh * a.parts * (int64_t)a.top_k;
+        row = a.cand_val + base;
+        col_map = a.cand_col + base;
+        n = c1 > c0 ? a.parts * a.top_k : 0;  // padded with -inf entries, which sort below every logit
+        keep = c1 - c0 < a.top_k ? c1 - c0 : a.top_k;
+    }
+
+    if constexpr (STAGE == kSelectCandidates) {
+        // pad the part's candidate slots; the kept ones are overwritten below
+        const int64_t base = (gh * a.parts + part) * (int64_t)a.top_k;
+        for (int j = tid + keep; j < a.top_k; j += kSelectBlock) {
+            a.cand_val[base + j] = -INFINITY;
+            a.cand_col[base + j] = 0;
+        }
+        if (n == 0) return;
+    } else {
+        if (a.sel)
+            for (int j = tid + keep; j < a.top_k; j += kSelectBlock) a.sel[gh * a.top_k + j] = -1;
+        if (n == 0) {
+            if (tid < D) a.o[gh * D + tid] = 0.f;
+            if (tid == 0) {
+                a.m[gh] = -INFINITY;
+                a.l[gh] = 0.f;
+            }
+            return;
+        }
+    }
+
+    // 1. radix select
+    uint32_t prefix = 0, mask = 0, krem = (uint32_t)keep;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) s_hist[tid] = 0;
+        __syncthreads();
+        for (int i0 = 0; i0 < n; i0 += 8 * kSelectBlock) {  // eight loads in flight per thread
+            float x[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int i = i0 + j * kSelectBlock + tid;
+                x[j] = row[i < n ? i : n - 1];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t u = order_key(x[j]);
+                if (i0 + j * kSelectBlock + tid < n && (u & mask) == prefix) atomicAdd(&s_hist[(u >> shift) & 255u], 1u);
+            }
+        }
+        __syncthreads();
+        // the digit d with  #(digits > d) < krem <= #(digits >= d):  scan the bins from the top
+        {
+            const uint32_t cnt = tid < 256 ? s_hist[255 - tid] : 0u;
+            uint32_t total;
+            const uint32_t above = block_exclusive_scan(cnt, s_wave, total);
+            if (tid < 256 && above < krem && above + cnt >= krem) {
+                s_prefix = prefix | ((uint32_t)(255 - tid) << shift);
+                s_krem = krem - above;
+            }
+        }
+        __syncthreads();
+        prefix = s_prefix;
+        krem = s_krem;
+        mask |= 0xffu << shift;
+    }
+    const uint32_t T = prefix, k_eq = krem;  // keep every key > T and the first k_eq keys == T
+
+    // 2. ordered compaction of the kept columns; every thread owns kRun consecutive columns of a
+    //    chunk, so one block scan serves kRun * 1024 elements
+    constexpr int kRun = 8;
+    uint32_t run_gt = 0, run_eq = 0;
+    for (int base = 0; base < n; base += kRun * kSelectBlock) {
+        const int i0 = base + kRun * tid;
+        float x[kRun];
+        uint32_t cnt = 0;  // low half: keys > T, high half: keys == T
+#pragma unroll
+        for (int j = 0; j < kRun; ++j) {
+            x[j] = row[i0 + j < n ? i0 + j : n - 1];
+            const uint32_t u = order_key(x[j]);
+            if (i0 + j < n) cnt += (u > T ? 1u : 0u) + (u == T ? 0x10000u : 0u);
+        }
+        uint32_t total;
+        const uint32_t scan = block_exclusive_scan(cnt, s_wave, total);
+        uint32_t gt_before = run_gt + (scan & 0xffffu), eq_before = run_eq + (scan >> 16);
+#pragma unroll
+        for (int j = 0; j < kRun; ++j) {
+            const uint32_t u = order_key(x[j]);
+            const bool in = i0 + j < n, gt = in && u > T, eq = in && u == T;
+            if (gt || (eq && eq_before < k_eq)) {
+                const uint32_t pos = gt_before + (eq_before < k_eq ? eq_before : k_eq);
+                s_cols[pos] = col_map ? col_map[i0 + j] : col_base + i0 + j;
+                s_vals[pos] = x[j];
+            }
+            gt_before += gt ? 1u : 0u;
+            eq_before += eq ? 1u : 0u;
+        }
+        run_gt += total & 0xffffu;
+        run_eq += total >> 16;
+    }
+    __syncthreads();
+
+    if constexpr (STAGE == kSelectCandidates) {
+        const int64_t base = (gh * a.parts + part) * (int64_t)a.top_k;
+        for (int j = tid; j < keep; j += kSelectBlock) {
+            a.cand_val[base + j] = s_vals[j];
+            a.cand_col[base + j] = s_cols[j];
+        }
+        return;
+    }
+
+    // 3a. m = max kept logit; weights; l
+    float mx = -INFINITY;
+    for (int j = tid; j < keep; j += kSelectBlock) mx = fmaxf(mx, s_vals[j]);
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1) mx = fmaxf(mx, __shfl_xor(mx, step, 64));
+    if (lane == 0) s_red[wave] = mx;
+    __syncthreads();
+    mx = s_red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) mx = fmaxf(mx, s_red[w]);
+    __syncthreads();
+    float lt = 0.f;
+    const int seq = table_entry(a.tab, r0).seq;
+    for (int j = tid; j < keep; j += kSelectBlock) {
+        const float w = fast_exp2((s_vals[j] - mx) * kLog2e);
+        lt += w;
+        // column -> token position: the range of the group that holds the column
+        const int col = s_cols[j];
+        int lo = r0, hi = r1;  // pre[lo] <= col < pre[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (table_entry(a.tab, mid).pre <= col)
+                lo = mid;
+            else
+                hi = mid;
+        }
+        const RangeEntry e = table_entry(a.tab, lo);
+        const int tok = e.begin + (col - e.pre);
+        s_cols[j] = tok;
+        s_vals[j] = w;
+        if (a.sel) a.sel[gh * a.top_k + j] = tok;
+    }
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1) lt += __shfl_xor(lt, step, 64);
+    if (lane == 0) s_red[wave] = lt;
+    __syncthreads();
+    lt = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) lt += s_red[w];
+
+    // 3b. gather the kept V rows: lane group grp of wave `wave` takes kept entries
+    //     4*wave + grp, + 64, + 128, ...
+    const int sub = lane & 15, grp = lane >> 4;
+    const int hk = h / a.group;
+    const char *vbase = static_cast<const char *>(a.v) + ((int64_t)seq * a.stride_b + (int64_t)hk * a.stride_h) * ES;
+    const int64_t row_bytes = a.stride_t * ES;
+    float acc[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+    for (int j = 4 * wave + grp; j < keep; j += 4 * NW) {
+        const float w = s_vals[j];
+        const char *vrow = vbase + (int64_t)s_cols[j] * row_bytes;
+        float vf[EPL];
+#pragma unroll
+        for (int jj = 0; jj < NV; ++jj) {
+            typename TR::Raw raw = TR::template load<false>(vrow, sub, jj);
+            TR::widen(raw, &vf[jj * EPV]);
+        }
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[i] = fmaf(w, vf[i], acc[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+        acc[i] += __shfl_xor(acc[i], 16, 64);
+        acc[i] += __shfl_xor(acc[i], 32, 64);
+    }
+    if (grp == 0) {
+#pragma unroll
+        for (int jj = 0; jj < NV; ++jj)
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) s_acc[wave][TR::vec_offset(sub, jj) + i] = acc[jj * EPV + i];
+    }
+    __syncthreads();
+    if (tid < D) {
+        float ot = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) ot += s_acc[w][tid];
+        a.o[gh * D + tid] = ot;
+    }
+    if (tid == 0) {
+        a.m[gh] = mx;
+        a.l[gh] = lt;
+    }
+}
+
+}  // namespace hg

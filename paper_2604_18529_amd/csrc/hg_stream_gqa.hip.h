@@ -1,0 +1,372 @@
+// Streaming kernel for grouped-query attention on the matrix cores (fp16, head_dim 128).
+#pragma once
+
+#include "hg_common.hip.h"
+
+namespace hg {
+
+// ---- streaming kernel for grouped-query attention (fp16, head_dim 128) on the matrix cores -----
+//
+// With G query heads sharing one KV head, every K and V byte feeds G dot products; on the
+// vector ALU that makes the scan arithmetic-bound from G = 4 upwards.  Here up to 16 query heads
+// of a KV head form the M dimension of v_mfma_f32_16x16x32_f16, so the arithmetic is a few
+// percent of the matrix cores and the kernel is bandwidth-bound again.
+//
+// Per wave and per block of 32 tokens:
+//   K   8 coalesced 16-byte loads per lane (4 whole rows per instruction) -> wave-private LDS
+//       (rows padded to 272 bytes) -> read back "token per lane": lane l gets token l%16,
+//       channels 8*(4kk + l/16)..+7, which IS the B operand of MFMA kk (the contraction runs
+//       over channels, and Q is laid out with the same channel grouping as A operand).
+//       S = Q.K^T lands as: lane (n = l%16, rg = l/16) holds heads 4rg..4rg+3 of token n.
+//   softmax  row max over the 16 token lanes by DPP, running (m, l) per head, P = exp2(S - m).
+//       P is split into an fp16 head and an fp16 remainder (p = ph + pl to ~22 bits), so the
+//       fp16 MFMA does not cost precision in the weights.
+//   P   goes through 2 KiB of LDS to become the A operand (lane l: head l%16, tokens of group l/16).
+//   V   8 coalesced 16-byte loads per lane; the contraction now runs over tokens, which sit in a
+//       lane's own registers (8 tokens x 8 channels), so an in-lane 8x8 transpose of halves
+//       (32 v_perm_b32) yields the B operands: no LDS, no cross-lane traffic.  Token j of lane
+//       group g is block token 16*(j%2) + 4*(j/2) + g, so that each load instruction still
+//       fetches 4 adjacent rows and the two halves of a P word come from one lane.
+//       O[nb] (nb = 0..7) holds out[head 4rg + r][channel 8n + nb].
+
+constexpr int kGqaHeads = 16;            // query heads per workgroup (M of the MFMA)
+constexpr int kGqaBlockTokens = 32;      // tokens per wave iteration (K of the P.V MFMA)
+constexpr int kGqaKRow = 272;            // padded LDS row: 256 bytes + 16 so that 16 rows spread over all banks
+constexpr int kGqaKBytes = kGqaBlockTokens * kGqaKRow;
+constexpr int kGqaPBytes = kGqaHeads * kGqaBlockTokens * 2;
+constexpr int kGqaWaveBytes = kGqaKBytes + 2 * kGqaPBytes;
+
+typedef _Float16 hg_h8 __attribute__((ext_vector_type(8)));
+typedef float hg_f4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float row16_max(float x)
+{
+    x = fmaxf(x, dpp_move<0xB1>(x));
+    x = fmaxf(x, dpp_move<0x4E>(x));
+    x = fmaxf(x, dpp_move<0x141>(x));
+    x = fmaxf(x, dpp_move<0x140>(x));
+    return x;
+}
+
+// LDS traffic between the lanes of ONE wave: the hardware keeps a wave's LDS operations in
+// order; this only stops the compiler from moving accesses across the hand-over point.
+__device__ __forceinline__ void wave_lds_handover()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int MODE, bool PAGED>
+__global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_gqa_kernel(const PartialArgs a)
+{
+    static_assert(!PAGED || MODE == kModeStats, "paged caches are only wired into the statistics mode");
+    constexpr int D = 128;
+    constexpr int kMergeBytes = kGqaWaves * kGqaHeads * (D + 2) * 4;
+    constexpr int kSmemBytes = kGqaWaves * kGqaWaveBytes > kMergeBytes ? kGqaWaves * kGqaWaveBytes : kMergeBytes;
+    __shared__ __align__(16) char smem[kSmemBytes];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, rg = lane >> 4;
+
+    char *kls = smem + wave * kGqaWaveBytes;
+    char *pls = kls + kGqaKBytes;
+
+    for_each_segment(a.ws, a.tab, [&](int stream, int r_idx, const RangeEntry &e, int t0, int t1, int col0, int64_t slot) __attribute__((always_inline)) {
+    const int seq = e.seq;
+    const int hk = stream / a.ws.n_chunks;
+    const int chunk = stream - hk * a.ws.n_chunks;
+    const int g0 = chunk * kGqaHeads;
+    const int nh = min(kGqaHeads, a.ws.group - g0);
+    const int h0 = hk * a.ws.group + g0;
+
+    // Q as A operand: lane l holds head l%16, channels 8*(4kk + l/16)..+7 for kk = 0..3
+    hg_h8 qa[4];
+    if constexpr (MODE != kModeConcat) {
+        const _Float16 *qrow = static_cast<const _Float16 *>(a.q) + ((int64_t)seq * a.ws.n_q_heads + h0 + (n < nh ? n : 0)) * D;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            hg_u32x4 raw = *reinterpret_cast<const hg_u32x4 *>(qrow + 8 * (4 * kk + rg));
+            if (n >= nh) raw = hg_u32x4{0u, 0u, 0u, 0u};
+            qa[kk] = __builtin_bit_cast(hg_h8, raw);
+        }
+    }
+
+    // concat mode: global softmax maximum (log2 units) of this lane's head n, and its logits
+    // row (lrow[tok] is the logit of token tok)
+    float gmax = 0.f;
+    const float *lrow = nullptr;
+    if constexpr (MODE == kModeConcat) {
+        const int h = h0 + (n < nh ? n : 0);
+        const int64_t base = ((int64_t)e.grp * a.ws.n_q_heads + h) * kConcatSlices;
+        gmax = kNegBig;
+        for (int z = 0; z < kConcatSlices; ++z) gmax = fmaxf(gmax, a.gs_m[base + z]);
+        lrow = a.logits + (int64_t)h * a.ws.ltok + (col0 - t0);
+    }
+
+    float m[4], lsum[4];
+    hg_f4 o[8];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        m[r] = MODE == kModeConcat ? 0.f : kNegBig;  // concat records are plain sums
+        lsum[r] = 0.f;
+    }
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) o[nb] = hg_f4{0.f, 0.f, 0.f, 0.f};
+
+    const int64_t slab = (PAGED ? 0 : (int64_t)seq * a.stride_b) + (int64_t)hk * a.stride_h;
+    const char *kbase = static_cast<const char *>(a.k) + slab * 2 + n * 16;
+    const char *vbase = static_cast<const char *>(a.v) + slab * 2 + n * 16;
+    const int64_t row_bytes = a.stride_t * 2;
+    const int64_t block_bytes = a.stride_b * 2;
+    const int32_t *table = PAGED ? a.pages.table + (int64_t)seq * a.pages.max_blocks : nullptr;
+
+    // Paged cache: physical blocks of the 8 tokens tb + 4x + rg (x = 0..7) a lane touches in a
+    // block; K load i uses x = i, V load j uses x = 4*(j&1) + (j>>1), the same 8 tokens.
+    auto lookup = [&](int tb, int(&pg)[8]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int tok = tb + 4 * x + rg;
+            pg[x] = table[(tok < t1 ? tok : t1 - 1) >> a.pages.shift];
+        }
+    };
+    auto row_offset = [&](int tok, int page) __attribute__((always_inline)) -> int64_t {
+        return PAGED ? (int64_t)page * block_bytes + (int64_t)(tok & a.pages.mask) * row_bytes : (int64_t)tok * row_bytes;
+    };
+
+    // The 8 K-row loads and the 8 V-row loads of one 32-token block (8 KiB each per wave).
+    auto load_k = [&](int tb, hg_u32x4(&kreg)[8], const int(&pg)[8]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int tok = tb + 4 * i + rg;
+            tok = tok < t1 ? tok : t1 - 1;  // clamp: never read past the segment
+            kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(kbase + row_offset(tok, pg[i])));
+        }
+    };
+    auto load_v = [&](int tb, hg_u32x4(&vreg)[8], const int(&pg)[8]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            // token j of lane group rg: interleaved so that S halves pair up (stats mode), or the
+            // 8 consecutive tokens whose logits this lane reads (concat mode)
+            int tok = MODE == kModeConcat ? tb + 8 * rg + j : tb + 16 * (j & 1) + 4 * (j >> 1) + rg;
+            tok = tok < t1 ? tok : t1 - 1;
+            vreg[j] = __builtin_nontemporal_load(
+                reinterpret_cast<const hg_u32x4 *>(vbase + row_offset(tok, pg[4 * (j & 1) + (j >> 1)])));
+        }
+    };
+    // pages of the next block (pg1) and of the one after (pg2, in flight); unused when not paged
+    int pg1[8] = {0, 0, 0, 0, 0, 0, 0, 0}, pg2[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+
+    // One block.  Software pipeline with a single register buffer: the K rows of the next block
+    // are requested as soon as this block's K sits in LDS, its V rows as soon as this block's V
+    // has been consumed, so a wave always has 8-16 KiB in flight while it computes.
+    auto compute_block = [&](int tb, int tb_next, hg_u32x4(&kreg)[8], hg_u32x4(&vreg)[8]) __attribute__((always_inline)) {
+        // K: registers -> LDS (row per token) -> B operands (token per lane)
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            *reinterpret_cast<hg_u32x4 *>(kls + (4 * i + rg) * kGqaKRow + n * 16) = kreg[i];
+        wave_lds_handover();
+        if (tb_next < t1) load_k(tb_next, kreg, pg1);
+        hg_f4 s[2];
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+            s[hf] = hg_f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                hg_u32x4 raw = *reinterpret_cast<const hg_u32x4 *>(kls + (16 * hf + n) * kGqaKRow + (4 * kk + rg) * 16);
+                s[hf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[kk], __builtin_bit_cast(hg_h8, raw), s[hf], 0, 0, 0);
+            }
+        }
+
+        const bool ok0 = tb + n < t1, ok1 = tb + 16 + n < t1;
+        if constexpr (MODE == kModeLogits) {
+            // export: lane (n, rg) holds heads 4rg..4rg+3 of tokens tb + n and tb + 16 + n
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (4 * rg + r >= nh) continue;
+                float *row = a.logits + (int64_t)(h0 + 4 * rg + r) * a.ws.ltok + col0 + (tb - t0);
+                if (ok0) row[n] = s[0][r] * a.qscale;
+                if (ok1) row[16 + n] = s[1][r] * a.qscale;
+            }
+            wave_lds_handover();  // the next block overwrites the K staging area
+            return;
+        }
+
+        // online softmax on S (lane: token n of each half, heads 4rg..4rg+3)
+        float alpha[4];
+        uint32_t ph[4], pl[4];  // packed (half 0, half 1) weights: fp16 head and fp16 remainder
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float s0 = ok0 ? s[0][r] * a.qscale : -INFINITY;
+            const float s1 = ok1 ? s[1][r] * a.qscale : -INFINITY;
+            const float mx = fmaxf(m[r], row16_max(fmaxf(s0, s1)));
+            alpha[r] = fast_exp2(m[r] - mx);
+            m[r] = mx;
+            const float p0 = fast_exp2(s0 - mx), p1 = fast_exp2(s1 - mx);
+            lsum[r] = lsum[r] * alpha[r] + (p0 + p1);
+            const _Float16 h0f = (_Float16)p0, h1f = (_Float16)p1;
+            const _Float16 l0f = (_Float16)(p0 - (float)h0f), l1f = (_Float16)(p1 - (float)h1f);
+            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+            ph[r] = __builtin_bit_cast(uint32_t, h2{h0f, h1f});
+            pl[r] = __builtin_bit_cast(uint32_t, h2{l0f, l1f});
+        }
+        // P -> LDS as [head][group g = n%4][j = 2*(n/4) + half], then read as A operand
+        {
+            const int col = (n & 3) * 16 + (n >> 2) * 4;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                *reinterpret_cast<uint32_t *>(pls + (4 * rg + r) * 64 + col) = ph[r];
+                *reinterpret_cast<uint32_t *>(pls + kGqaPBytes + (4 * rg + r) * 64 + col) = pl[r];
+            }
+        }
+        wave_lds_handover();
+        const hg_h8 pa_hi = __builtin_bit_cast(hg_h8, *reinterpret_cast<const hg_u32x4 *>(pls + n * 64 + rg * 16));
+        const hg_h8 pa_lo =
+            __builtin_bit_cast(hg_h8, *reinterpret_cast<const hg_u32x4 *>(pls + kGqaPBytes + n * 64 + rg * 16));
+
+        // V: in-lane transpose of halves, then O[nb] = alpha * O[nb] + P . V[:, channel 8n + nb]
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) {
+            const uint32_t sel = (nb & 1) ? 0x07060302u : 0x05040100u;
+            hg_u32x4 braw;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                braw[jj] = __builtin_amdgcn_perm(vreg[2 * jj + 1][nb >> 1], vreg[2 * jj][nb >> 1], sel);
+            const hg_h8 b = __builtin_bit_cast(hg_h8, braw);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[nb][r] *= alpha[r];
+            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
+            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
+        }
+        if (tb_next < t1) {
+            if constexpr (PAGED) {
+                // table look-up for the block after next goes out BEFORE the V loads: the K loads
+                // of that block then only wait for what was issued earlier (loads return in order)
+                const int tb_nn = tb_next + (tb_next - tb);
+                if (tb_nn < t1) lookup(tb_nn, pg2);
+            }
+            load_v(tb_next, vreg, pg1);
+            if constexpr (PAGED) {
+#pragma unroll
+                for (int x = 0; x < 8; ++x) pg1[x] = pg2[x];
+            }
+        }
+        wave_lds_handover();  // the next block overwrites the K and P staging areas
+    };
+
+    // Concat mode block: the numerators exp(s - M) of the ONE softmax over the group's concatenated
+    // logits come straight from memory in A-operand order (lane: head n, tokens tb + 8rg .. + 7);
+    // they lie in (0, 1], so the fp16 head + remainder keeps them to ~22 bits.  The division by the
+    // global sum happens once, in the reduce kernel.
+    auto concat_block = [&](int tb, int tb_next, hg_u32x4(&vreg)[8]) __attribute__((always_inline)) {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        hg_u32x4 hi_raw, lo_raw;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            float pj[2];
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+                const int tok = tb + 8 * rg + 2 * jj + x;
+                const float sv = lrow[tok < t1 ? tok : t1 - 1];  // unconditional load; masked by a product
+                pj[x] = fast_exp2(sv * kLog2e - gmax) * ((tok < t1 && n < nh) ? 1.f : 0.f);
+            }
+            const _Float16 h0f = (_Float16)pj[0], h1f = (_Float16)pj[1];
+            const _Float16 l0f = (_Float16)(pj[0] - (float)h0f), l1f = (_Float16)(pj[1] - (float)h1f);
+            hi_raw[jj] = __builtin_bit_cast(uint32_t, h2{h0f, h1f});
+            lo_raw[jj] = __builtin_bit_cast(uint32_t, h2{l0f, l1f});
+        }
+        const hg_h8 pa_hi = __builtin_bit_cast(hg_h8, hi_raw), pa_lo = __builtin_bit_cast(hg_h8, lo_raw);
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) {
+            const uint32_t sel = (nb & 1) ? 0x07060302u : 0x05040100u;
+            hg_u32x4 braw;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                braw[jj] = __builtin_amdgcn_perm(vreg[2 * jj + 1][nb >> 1], vreg[2 * jj][nb >> 1], sel);
+            const hg_h8 b = __builtin_bit_cast(hg_h8, braw);
+            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
+            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
+        }
+        if (tb_next < t1) load_v(tb_next, vreg, pg1);
+    };
+
+    {
+        constexpr int kStride = kGqaWaves * kGqaBlockTokens;
+        int tb = t0 + wave * kGqaBlockTokens;
+        if constexpr (MODE == kModeStats) {
+            hg_u32x4 kreg[8], vreg[8];
+            if (tb < t1) {
+                if constexpr (PAGED) {
+                    lookup(tb, pg2);
+                    if (tb + kStride < t1) lookup(tb + kStride, pg1);
+                }
+                load_k(tb, kreg, pg2);
+                load_v(tb, vreg, pg2);
+            }
+            while (tb < t1) {
+                compute_block(tb, tb + kStride, kreg, vreg);
+                tb += kStride;
+            }
+        } else {
+            // Only K (logits) or only V (concat) is read: two register buffers, so that two
+            // blocks (16 KiB per wave) are in flight as in the statistics mode.
+            hg_u32x4 ra[8], rb[8];
+            auto load_one = [&](int t, hg_u32x4(&reg)[8]) __attribute__((always_inline)) {
+                if constexpr (MODE == kModeLogits)
+                    load_k(t, reg, pg1);
+                else
+                    load_v(t, reg, pg1);
+            };
+            auto compute_one = [&](int t, hg_u32x4(&reg)[8]) __attribute__((always_inline)) {
+                if constexpr (MODE == kModeLogits)
+                    compute_block(t, t + 2 * kStride, reg, reg);
+                else
+                    concat_block(t, t + 2 * kStride, reg);
+            };
+            if (tb < t1) load_one(tb, ra);
+            if (tb + kStride < t1) load_one(tb + kStride, rb);
+            while (tb < t1) {
+                compute_one(tb, ra);
+                tb += kStride;
+                if (tb >= t1) break;
+                compute_one(tb, rb);
+                tb += kStride;
+            }
+        }
+    }
+    if constexpr (MODE == kModeLogits) return;  // nothing to merge or record
+
+    // per-wave state -> LDS (staging areas are dead now), then merge the four waves
+    __syncthreads();
+    float(*sm)[kGqaHeads][D + 2] = reinterpret_cast<float(*)[kGqaHeads][D + 2]>(smem);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float lrow = row16_sum(lsum[r]);
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) sm[wave][4 * rg + r][8 * n + nb] = o[nb][r];
+        if (n == 0) {
+            sm[wave][4 * rg + r][D] = m[r];
+            sm[wave][4 * rg + r][D + 1] = lrow;
+        }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < kGqaHeads * D; idx += kGqaBlock) {
+        const int g = idx / D, c = idx - g * D;
+        if (g >= nh) continue;
+        float mx = kNegBig;
+#pragma unroll
+        for (int w = 0; w < kGqaWaves; ++w) mx = fmaxf(mx, sm[w][g][D]);
+        float lt = 0.f, ot = 0.f;
+#pragma unroll
+        for (int w = 0; w < kGqaWaves; ++w) {
+            const float wt = fast_exp2(sm[w][g][D] - mx);
+            lt += wt * sm[w][g][D + 1];
+            ot += wt * sm[w][g][c];
+        }
+        write_segment_result<D>(a, slot * kGqaHeads + g, r_idx, h0 + g, c, mx, lt, ot);
+    }
+    __syncthreads();  // the next segment reuses the staging areas
+    });
+}
+
+}  // namespace hg
