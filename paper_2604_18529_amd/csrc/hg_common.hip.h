@@ -205,6 +205,17 @@ __device__ __forceinline__ float row16_sum(float x)
     return x;
 }
 
+// Sum over a lane group of LPR = 16 or 8 lanes (8: the two halves of a DPP row are separate groups).
+template <int LPR>
+__device__ __forceinline__ float lane_group_sum(float x)
+{
+    x += dpp_move<0xB1>(x);
+    x += dpp_move<0x4E>(x);
+    x += dpp_move<0x141>(x);
+    if constexpr (LPR == 16) x += dpp_move<0x140>(x);
+    return x;
+}
+
 __device__ __forceinline__ RangeEntry table_entry(const RangeTable &tab, int i)
 {
     return tab.ext ? tab.ext[i] : tab.inl[i];
@@ -284,12 +295,14 @@ struct Traits {
     static constexpr int D = D_;
     static constexpr bool F16 = F16_;
     static constexpr int ES = F16_ ? 2 : 4;
-    static constexpr int LANE_BYTES = D_ * ES / 16;           // bytes of a row held by one lane
-    static constexpr int VB = LANE_BYTES >= 16 ? 16 : 8;      // bytes per load
+    static constexpr int LPR = D_ * ES >= 256 ? 16 : 8;       // lanes per row: a lane always loads 16 bytes
+    static constexpr int RPW = 64 / LPR;                      // rows per wave load instruction (4 or 8)
+    static constexpr int LANE_BYTES = D_ * ES / LPR;          // bytes of a row held by one lane
+    static constexpr int VB = 16;                             // bytes per load
     static constexpr int NV = LANE_BYTES / VB;                // loads per row per lane
     static constexpr int EPV = VB / ES;                       // elements per load
     static constexpr int EPL = NV * EPV;                      // elements per lane
-    static constexpr int SEG = 16 * EPV;                      // elements covered by one wave-row load
+    static constexpr int SEG = LPR * EPV;                     // elements covered by one row load of the lane group
     using Raw = RawVec<VB>;
 
     // element offset inside a row of lane `sub`'s vector j

@@ -241,14 +241,15 @@ __global__ __launch_bounds__(kSelectBlock) void hg_select_kernel(const SelectArg
 
     // 3b. gather the kept V rows: lane group grp of wave `wave` takes kept entries
     //     4*wave + grp, + 64, + 128, ...
-    const int sub = lane & 15, grp = lane >> 4;
+    constexpr int LPR = TR::LPR, RPW = TR::RPW;
+    const int sub = lane % LPR, grp = lane / LPR;
     const int hk = h / a.group;
     const char *vbase = static_cast<const char *>(a.v) + ((int64_t)seq * a.stride_b + (int64_t)hk * a.stride_h) * ES;
     const int64_t row_bytes = a.stride_t * ES;
     float acc[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
-    for (int j = 4 * wave + grp; j < keep; j += 4 * NW) {
+    for (int j = RPW * wave + grp; j < keep; j += RPW * NW) {
         const float w = s_vals[j];
         const char *vrow = vbase + (int64_t)s_cols[j] * row_bytes;
         float vf[EPL];
@@ -262,8 +263,8 @@ __global__ __launch_bounds__(kSelectBlock) void hg_select_kernel(const SelectArg
     }
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
-        acc[i] += __shfl_xor(acc[i], 16, 64);
-        acc[i] += __shfl_xor(acc[i], 32, 64);
+#pragma unroll
+        for (int step = LPR; step <= 32; step <<= 1) acc[i] += __shfl_xor(acc[i], step, 64);
     }
     if (grp == 0) {
 #pragma unroll

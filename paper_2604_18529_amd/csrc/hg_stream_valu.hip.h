@@ -43,12 +43,13 @@ template <typename TR, int GT, int U, int MODE, bool PAGED>
 __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2))) void hg_partial_kernel(const PartialArgs a)
 {
     constexpr int D = TR::D, EPL = TR::EPL, NV = TR::NV, EPV = TR::EPV, ES = TR::ES;
-    constexpr int CH = 4 * U;  // tokens one wave takes per iteration
+    constexpr int LPR = TR::LPR, RPW = TR::RPW;
+    constexpr int CH = RPW * U;  // tokens one wave takes per iteration
 
     __shared__ float sm[kValuWaves][GT][D + 2];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int sub = lane & 15, grp = lane >> 4;
+    const int sub = lane % LPR, grp = lane / LPR;
 
     for_each_segment(a.ws, a.tab, [&](int stream, int r_idx, const RangeEntry &e, int t0, int t1, int col0, int64_t slot) __attribute__((always_inline)) {
     const int seq = e.seq;
@@ -112,7 +113,7 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
     auto lookup = [&](int tbb, int(&out)[U]) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int tok = tbb + 4 * u + grp;
+            const int tok = tbb + RPW * u + grp;
             out[u] = table[(tok < t1 ? tok : t1 - 1) >> a.pages.shift];
         }
     };
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
         int tokc[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int tok = tb + 4 * u + grp;
+            const int tok = tb + RPW * u + grp;
             valid[u] = tok < t1;
             tokc[u] = valid[u] ? tok : t1 - 1;  // clamp: never read past the segment
             const int64_t off = PAGED ? (int64_t)pg[u] * block_bytes + (int64_t)(tokc[u] & a.pages.mask) * row_bytes
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
                     float d = 0.f;
 #pragma unroll
                     for (int i = 0; i < EPL; ++i) d = fmaf(qf[g][i], kf[i], d);
-                    d = row16_sum(d);
+                    d = lane_group_sum<LPR>(d);
                     s[g][u] = valid[u] ? d : -INFINITY;
                 }
             }
@@ -237,11 +238,11 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
     }
     if constexpr (MODE == kModeLogits) return;  // nothing to merge or record
 
-    // merge the four lane groups of the wave (lanes xor 16, xor 32)
+    // merge the lane groups of the wave (lanes xor 16, xor 32; xor 8 too when a group is 8 lanes)
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
 #pragma unroll
-        for (int step = 16; step <= 32; step <<= 1) {
+        for (int step = LPR; step <= 32; step <<= 1) {
             float m_b = __shfl_xor(m[g], step, 64);
             float l_b = __shfl_xor(l[g], step, 64);
             float acc_b[EPL];
