@@ -3,7 +3,7 @@
 
 A "step" is one pass of the whole hot path over one batch of synthetic input that is already
 resident in HBM:  hg_attn_partial over every range of every sequence (streams K and V once,
-tile statistics, tile reduce)  ->  hg_attn_merge over each sequence's triples.  The headline
+segment records, segment reduce)  ->  hg_attn_merge over each sequence's triples.  The headline
 workload is the OPT-6.7B-shaped decode layer (batch 8, 32 heads, head_dim 128, 8192 cached
 tokens per sequence, fp16 K/V, two partitions per sequence); the longer workloads are timed the
 same way and reported under "other_workloads".
@@ -77,7 +77,7 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
     from paper_2604_18529_amd import hg_attn as binding
 
     ws = torch.empty(max(binding.hg_attn_partial_workspace_size(desc, packed), 256), dtype=torch.uint8, device=dev)
-    tile_tokens, n_tiles = hg.hg_attn_plan(w.q, w.k, w.v, w.seq_lens, packed, w.scale)
+    span_tokens, n_workgroups = hg.hg_attn_plan(w.q, w.k, w.v, w.seq_lens, packed, w.scale)
 
     def step():
         hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, packed, w.scale, m=m, l=l, o=o, workspace=ws, desc=desc)
@@ -183,8 +183,8 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
         "kv_dtype": spec.dtype,
         "tokens_total": int(w.seq_lens.sum()),
         "partitions": R,
-        "span_tokens": tile_tokens,
-        "workgroups": n_tiles,
+        "span_tokens": span_tokens,
+        "workgroups": n_workgroups,
         "kv_bytes": kv_bytes,
         "us_per_layer": ms * 1e3,
         "gbps": kv_bytes / (ms * 1e-3) / 1e9,
@@ -256,7 +256,7 @@ def main():
     ap.add_argument("--workload", type=int, default=1, help="index into the standard workloads (headline: 1)")
     ap.add_argument("--others", type=str, default="0,2,3,4", help="comma list of further workloads to time ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--tile-tokens", type=int, default=0)
+    ap.add_argument("--span-tokens", type=int, default=0, help="force the span length (tuning)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run the library's plain 1 GiB device copy three times (known traffic: the "
                          "yardstick profiler byte counters are scaled by)")
@@ -273,7 +273,7 @@ def main():
     from paper_2604_18529_amd import workloads as W
 
     hg.load_library()
-    hg.hg_attn_set_tile_tokens(args.tile_tokens)
+    hg.hg_attn_set_span_tokens(args.span_tokens)
 
     if args.calibration_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0")

@@ -249,7 +249,7 @@ hg_status hg_attn_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t
 /* Tuning knob: force the span length in tokens (multiple of 64, 64..2^24); 0 restores the
  * built-in choice (one workgroup per compute unit on long inputs).  Process-wide; not
  * thread-safe against concurrent calls. */
-hg_status hg_attn_set_tile_tokens(int32_t tile_tokens);
+hg_status hg_attn_set_span_tokens(int32_t span_tokens);
 
 /*
  * Measurement aid: time the streaming kernel (the one that reads K and V) by itself.  After

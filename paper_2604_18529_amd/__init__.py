@@ -16,7 +16,7 @@ _API = (
     "hg_sched_step",
     "HgSchedState",
     "hg_attn_plan",
-    "hg_attn_set_tile_tokens",
+    "hg_attn_set_span_tokens",
     "hg_attn_profile_start",
     "hg_attn_profile_stop",
     "hg_attn_calibration_copy",

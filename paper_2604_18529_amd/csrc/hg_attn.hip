@@ -1,4 +1,4 @@
-// Host side of the C ABI declared in include/hg_attn.h: validation, tile planning, launches.
+// Host side of the C ABI declared in include/hg_attn.h: validation, work-split planning, launches.
 // Nothing here allocates device memory or synchronises with the device; host tables reach the
 // GPU inside kernel arguments (small tables) or through chunked upload kernels (large tables),
 // so no memcpy semantics are relied upon and every call is safe to record into a HIP graph.
@@ -20,7 +20,7 @@ namespace {
 
 using namespace hg;
 
-int g_forced_tile_tokens = 0;
+int g_forced_span_tokens = 0;
 
 // Optional timing of the streaming kernel alone: event pairs recorded on the caller's stream
 // right around its launch (hg_attn_profile_start / hg_attn_profile_stop).
@@ -120,7 +120,7 @@ int32_t pick_group_tile(const hg_attn_desc *d)
 // over the chip.
 int32_t pick_span(int64_t total, bool gqa)
 {
-    if (g_forced_tile_tokens) return g_forced_tile_tokens;
+    if (g_forced_span_tokens) return g_forced_span_tokens;
     const int64_t target = (int64_t)(gqa ? kGqaWorkgroupsPerCu : kValuWorkgroupsPerCu) * compute_units();
     int64_t t = (total + target - 1) / target;
     t = (t + 63) / 64 * 64;
@@ -300,9 +300,6 @@ hg_status stage_groups(const int32_t *group_ptr, int32_t n_groups, int32_t *dst,
 // launch is skipped.  (Checked only for tables small enough for the check to be free.)
 bool plan_is_direct(const Plan &p, int32_t n_ranges, int64_t n_streams)
 {
-#ifdef HG_NO_DIRECT
-    return false;
-#endif
     if (p.ws.total == 0 || n_streams * n_ranges > 65536) return false;
     for (int64_t s = 0; s < n_streams; ++s)
         for (int32_t r = 0; r < n_ranges; ++r) {
@@ -500,10 +497,10 @@ const char *hg_strerror(hg_status status)
     return "unknown status";
 }
 
-hg_status hg_attn_set_tile_tokens(int32_t tile_tokens)
+hg_status hg_attn_set_span_tokens(int32_t span_tokens)
 {
-    if (tile_tokens != 0 && (tile_tokens < 64 || tile_tokens > (1 << 24) || tile_tokens % 64)) return HG_ERR_SHAPE;
-    g_forced_tile_tokens = tile_tokens;
+    if (span_tokens != 0 && (span_tokens < 64 || span_tokens > (1 << 24) || span_tokens % 64)) return HG_ERR_SHAPE;
+    g_forced_span_tokens = span_tokens;
     return HG_OK;
 }
 

@@ -277,17 +277,12 @@ __device__ __forceinline__ void for_each_segment(const WorkSplit &ws, const Rang
 #endif
 
 typedef unsigned int hg_u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int hg_u32x2 __attribute__((ext_vector_type(2)));
 
 template <int VB>
 struct RawVec;
 template <>
 struct RawVec<16> {
     hg_u32x4 d;
-};
-template <>
-struct RawVec<8> {
-    hg_u32x2 d;
 };
 
 template <int D_, bool F16_>

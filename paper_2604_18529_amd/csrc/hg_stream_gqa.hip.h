@@ -178,21 +178,40 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             }
         }
 
-        const bool ok0 = tb + n < t1, ok1 = tb + 16 + n < t1;
         if constexpr (MODE == kModeLogits) {
-            // export: lane (n, rg) holds heads 4rg..4rg+3 of tokens tb + n and tb + 16 + n
+            // export: lane (n, rg) holds heads 4rg..4rg+3 of tokens tb + n and tb + 16 + n.  The
+            // tile goes through the (idle) P staging area as [head][32 tokens] so that a lane can
+            // store four consecutive tokens of one head: a wave store instruction then writes
+            // 8 heads x 128 bytes instead of 64-byte pieces.
+            float *stile = reinterpret_cast<float *>(pls);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                if (4 * rg + r >= nh) continue;
-                float *row = a.logits + (int64_t)(h0 + 4 * rg + r) * a.ws.ltok + col0 + (tb - t0);
-                if (ok0) row[n] = s[0][r] * a.qscale;
-                if (ok1) row[16 + n] = s[1][r] * a.qscale;
+                stile[(4 * rg + r) * 32 + n] = s[0][r] * a.qscale;
+                stile[(4 * rg + r) * 32 + 16 + n] = s[1][r] * a.qscale;
             }
-            wave_lds_handover();  // the next block overwrites the K staging area
+            wave_lds_handover();
+            typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int head = 8 * half + (lane >> 3), tq = 4 * (lane & 7);  // 8 lanes per head
+                if (head < nh && tb + tq < t1) {
+                    const hg_f4 vals = *reinterpret_cast<const hg_f4 *>(stile + head * 32 + tq);
+                    float *dst = a.logits + (int64_t)(h0 + head) * a.ws.ltok + col0 + (tb - t0) + tq;
+                    if (tb + tq + 4 <= t1) {
+                        *reinterpret_cast<f4u *>(dst) = vals;
+                    } else {
+#pragma unroll
+                        for (int x = 0; x < 4; ++x)
+                            if (tb + tq + x < t1) dst[x] = vals[x];
+                    }
+                }
+            }
+            wave_lds_handover();  // the next block overwrites the staging areas
             return;
         }
 
         // online softmax on S (lane: token n of each half, heads 4rg..4rg+3)
+        const bool ok0 = tb + n < t1, ok1 = tb + 16 + n < t1;
         float alpha[4];
         uint32_t ph[4], pl[4];  // packed (half 0, half 1) weights: fp16 head and fp16 remainder
 #pragma unroll

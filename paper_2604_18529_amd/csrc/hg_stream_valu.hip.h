@@ -145,6 +145,14 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
         if constexpr (PAGED) {
             if (tb + kValuWaves * CH < t1) lookup(tb + kValuWaves * CH, pg_next);
         }
+        // concat mode: the given logits of these tokens (unconditional loads, issued with the V loads)
+        float sv[GT][U];
+        if constexpr (MODE == kModeConcat) {
+#pragma unroll
+            for (int g = 0; g < GT; ++g)
+#pragma unroll
+                for (int u = 0; u < U; ++u) sv[g][u] = lrow[g][tokc[u]];
+        }
         // Every load of this iteration is issued before any of its arithmetic: the bytes in
         // flight per wave are what the kernel's bandwidth rests on, and without this fence the
         // instruction scheduler is free to trade them for a lower register count.
@@ -170,13 +178,28 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
         }
 
         if constexpr (MODE == kModeLogits) {
-            // lane `g` of each 16-lane group stores head g's logit of that group's token
+            // Every lane of a group holds all GT*U logits of the group's U tokens.  Lane `sub`
+            // stores entry (g, u) = (idx / U, idx % U), idx = pass * LPR + sub, so one store
+            // instruction of the wave writes U * RPW consecutive tokens (128 bytes or more) of
+            // each head instead of one token per group.
+            constexpr int kPasses = (GT * U + LPR - 1) / LPR;
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+            for (int pass = 0; pass < kPasses; ++pass) {
+                const int idx = pass * LPR + sub;
+                float val = 0.f;
+                bool ok = false;
+                int tok = t0;
 #pragma unroll
                 for (int g = 0; g < GT; ++g)
-                    if (sub == g && g < nh && valid[u])
-                        a.logits[(int64_t)(h0 + g) * a.ws.ltok + col0 + (tokc[u] - t0)] = s[g][u];
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        if (g * U + u >= pass * LPR && g * U + u < (pass + 1) * LPR && idx == g * U + u) {
+                            val = s[g][u];
+                            ok = valid[u] && g < nh;
+                            tok = tokc[u];
+                        }
+                if (ok) a.logits[(int64_t)(h0 + idx / U) * a.ws.ltok + col0 + (tok - t0)] = val;
+            }
         }
 
         if constexpr (MODE != kModeLogits) {
@@ -202,13 +225,7 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
             }
         } else {
             // numerators exp(s - M) of the ONE softmax over the concatenated logits of the group
-            // (the mask is applied as a product so that every logit load stays unconditional and
-            // all of them are issued together with the V loads)
-            float sv[GT][U];
-#pragma unroll
-            for (int g = 0; g < GT; ++g)
-#pragma unroll
-                for (int u = 0; u < U; ++u) sv[g][u] = lrow[g][tokc[u]];
+            // (the mask is applied as a product so that every logit load stays unconditional)
 #pragma unroll
             for (int g = 0; g < GT; ++g) {
                 float ls = 0.f;

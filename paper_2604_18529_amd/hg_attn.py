@@ -92,13 +92,13 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_full_workspace_size.argtypes = [D, ctypes.POINTER(sz)]
     lib.hg_attn_full.argtypes = [D, vp, vp, vp, sz, vp]
     lib.hg_attn_plan.argtypes = [D, R, i32, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_int64)]
-    lib.hg_attn_set_tile_tokens.argtypes = [i32]
+    lib.hg_attn_set_span_tokens.argtypes = [i32]
     lib.hg_attn_profile_start.argtypes = [i32, i32]
     lib.hg_attn_calibration_copy.argtypes = [vp, vp, sz, vp]
     lib.hg_attn_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
     for name in (
         "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_merge_workspace_size", "hg_attn_merge",
-        "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_tile_tokens",
+        "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_span_tokens",
         "hg_attn_profile_start", "hg_attn_profile_stop", "hg_attn_calibration_copy",
         "hg_sched_init", "hg_sched_step", "hg_attn_logits_workspace_size", "hg_attn_logits", "hg_attn_select_workspace_size", "hg_attn_select", "hg_attn_concat_workspace_size", "hg_attn_concat",
     ):
@@ -192,19 +192,19 @@ def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> Tuple[
 
 
 def hg_attn_plan(q, k, v, seq_lens, ranges, scale=None) -> Tuple[int, int]:
-    """(tile_tokens, n_tiles) the library would use; host only."""
+    """(span_tokens, n_workgroups) the library would use; host only."""
     lib = load_library()
     desc, keep = make_desc(q, k, v, seq_lens, scale)
     packed = pack_ranges(ranges)
-    tile = ctypes.c_int32()
+    span = ctypes.c_int32()
     n = ctypes.c_int64()
-    _check(lib.hg_attn_plan(ctypes.byref(desc), packed, _n_ranges(packed), ctypes.byref(tile), ctypes.byref(n)), "hg_attn_plan")
+    _check(lib.hg_attn_plan(ctypes.byref(desc), packed, _n_ranges(packed), ctypes.byref(span), ctypes.byref(n)), "hg_attn_plan")
     del keep
-    return tile.value, n.value
+    return span.value, n.value
 
 
-def hg_attn_set_tile_tokens(tile_tokens: int) -> None:
-    _check(load_library().hg_attn_set_tile_tokens(int(tile_tokens)), "hg_attn_set_tile_tokens")
+def hg_attn_set_span_tokens(span_tokens: int) -> None:
+    _check(load_library().hg_attn_set_span_tokens(int(span_tokens)), "hg_attn_set_span_tokens")
 
 
 def hg_attn_profile_start(max_calls: int, repeat: int = 1) -> None:

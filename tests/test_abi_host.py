@@ -117,7 +117,7 @@ def test_span_plan_covers_the_work(lib):
         ltok = sum(e - b for _, b, e in ranges)
         streams = 2  # hkv = 2, both query heads of a KV head travel together
         for forced in (0, 64, 128, 1024, 4096, 1 << 20):
-            assert lib.hg_attn_set_tile_tokens(forced) == 0
+            assert lib.hg_attn_set_span_tokens(forced) == 0
             span, n = _plan(lib, _desc(seq), ranges)
             assert span % 64 == 0 and 64 <= span
             if forced:
@@ -126,9 +126,9 @@ def test_span_plan_covers_the_work(lib):
                 assert n <= 256  # one workgroup per compute unit (256 assumed without a GPU)
             assert n == (streams * ltok + span - 1) // span
         for bad in (63, 100, -64, (1 << 24) + 64):
-            assert lib.hg_attn_set_tile_tokens(bad) == -2
+            assert lib.hg_attn_set_span_tokens(bad) == -2
         # workspace holds one record of (d + 2) floats per head for every possible segment
-        lib.hg_attn_set_tile_tokens(64)
+        lib.hg_attn_set_span_tokens(64)
         d = _desc(seq)
         sz = ctypes.c_size_t()
         packed = B.pack_ranges(ranges)
@@ -139,7 +139,7 @@ def test_span_plan_covers_the_work(lib):
         span, n = _plan(lib, _desc(seq), [(0, 5, 5), (2, 0, 0)])
         assert n == 0
     finally:
-        lib.hg_attn_set_tile_tokens(0)
+        lib.hg_attn_set_span_tokens(0)
 
 
 def test_large_range_tables_need_table_space(lib):

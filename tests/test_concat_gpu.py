@@ -18,9 +18,9 @@ LOGIT_TOL = 1e-3
 
 @pytest.fixture(autouse=True)
 def _default_spans():
-    hg.hg_attn_set_tile_tokens(0)
+    hg.hg_attn_set_span_tokens(0)
     yield
-    hg.hg_attn_set_tile_tokens(0)
+    hg.hg_attn_set_span_tokens(0)
 
 
 def _oracle_concat(w, ranges, group_ptr):
@@ -79,7 +79,7 @@ REDUCED = [
 @pytest.mark.parametrize("spec", REDUCED, ids=lambda s: s.name)
 @pytest.mark.parametrize("span", [0, 64, 1024])
 def test_reduced_configs(spec, span):
-    hg.hg_attn_set_tile_tokens(span)
+    hg.hg_attn_set_span_tokens(span)
     w = W.make_workload(spec, DEV)
     _run(w, what="%s span=%d" % (spec.name, span))
 
@@ -132,7 +132,7 @@ def test_logits_from_another_executor():
 def test_edge_tables():
     """Empty ranges, an empty group, a group of only empty ranges, one-token ranges, unordered
     ranges inside a group, more ranges and groups than fit in kernel arguments."""
-    hg.hg_attn_set_tile_tokens(64)
+    hg.hg_attn_set_span_tokens(64)
     spec = W.WorkloadSpec("edge", 3, 4, 2, 128, "f16", 0, 1000, "none", seed=33)
     w = W.make_workload(spec, DEV)
     w.seq_lens[:] = [1000, 0, 257]

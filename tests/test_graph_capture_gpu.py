@@ -19,7 +19,7 @@ DEV = "cuda:0"
 
 @pytest.mark.parametrize("many_ranges", [False, True])
 def test_partial_merge_and_full_replay_from_a_graph(many_ranges):
-    hg.hg_attn_set_tile_tokens(0)
+    hg.hg_attn_set_span_tokens(0)
     spec = W.WorkloadSpec("graph", 2, 8, 2, 128, "f16", 2000, 3000, "dirichlet", 5, seed=80)
     w = W.make_workload(spec, DEV)
     ranges, gp = w.ranges, w.group_ptr

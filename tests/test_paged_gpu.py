@@ -17,9 +17,9 @@ DEV = "cuda:0"
 
 @pytest.fixture(autouse=True)
 def _default_spans():
-    hg.hg_attn_set_tile_tokens(0)
+    hg.hg_attn_set_span_tokens(0)
     yield
-    hg.hg_attn_set_tile_tokens(0)
+    hg.hg_attn_set_span_tokens(0)
 
 
 def _run_paged(w, block_tokens, what, ranges=None, gp=None):
@@ -51,7 +51,7 @@ def test_paged_matches_contiguous(dtype, d, group, block_tokens):
 
 @pytest.mark.parametrize("span", [64, 256])
 def test_paged_small_spans_and_edge_ranges(span):
-    hg.hg_attn_set_tile_tokens(span)
+    hg.hg_attn_set_span_tokens(span)
     spec = W.WorkloadSpec("pagededge", 3, 8, 1, 128, "f16", 0, 1000, "none", seed=71)
     w = W.make_workload(spec, DEV)
     w.seq_lens[:] = [1000, 0, 17]
@@ -62,7 +62,7 @@ def test_paged_small_spans_and_edge_ranges(span):
 def test_zero_query_bitplanes_are_exact_through_the_block_table():
     """q = 0 and bit-plane values: l and O are exact integers, which pins that every token was
     fetched from the right physical block and row."""
-    hg.hg_attn_set_tile_tokens(128)
+    hg.hg_attn_set_span_tokens(128)
     N, d = 5000, 128
     spec = W.WorkloadSpec("pagedbits", 1, 8, 1, d, "f16", N, N, "none", seed=72)
     w = W.make_workload(spec, DEV)

@@ -27,7 +27,7 @@ def _sample_pairs(spec, n, seed):
 
 @pytest.mark.parametrize("index", [1, 2, 3, 4])
 def test_full_size_sampled_against_oracle(index):
-    hg.hg_attn_set_tile_tokens(0)
+    hg.hg_attn_set_span_tokens(0)
     spec = W.WORKLOADS[index]
     w = W.make_workload(spec, DEV)
     m, l, o = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, w.ranges, w.scale)
@@ -73,7 +73,7 @@ def _bit_count(n, c):
 def test_full_size_range_membership_is_bit_exact(index):
     """Zero queries + bit-plane values at full context length (131072 and 1048576 tokens):
     l is the exact range length and O the exact per-bit token count of every range."""
-    hg.hg_attn_set_tile_tokens(0)
+    hg.hg_attn_set_span_tokens(0)
     spec = W.WORKLOADS[index].scaled(batch=1, n_q_heads=W.WORKLOADS[index].n_q_heads // W.WORKLOADS[index].n_kv_heads * 2,
                                      n_kv_heads=2)
     w = W.make_workload(spec, DEV)

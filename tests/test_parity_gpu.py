@@ -17,9 +17,9 @@ DEV = "cuda:0"
 
 @pytest.fixture(autouse=True)
 def _default_tiles():
-    hg.hg_attn_set_tile_tokens(0)
+    hg.hg_attn_set_span_tokens(0)
     yield
-    hg.hg_attn_set_tile_tokens(0)
+    hg.hg_attn_set_span_tokens(0)
 
 
 def test_config0_tiny_mha_exact_shape():
@@ -41,7 +41,7 @@ REDUCED = [
 @pytest.mark.parametrize("spec", REDUCED, ids=lambda s: s.name)
 @pytest.mark.parametrize("tile", [0, 64, 1024])
 def test_reduced_configs(spec, tile):
-    hg.hg_attn_set_tile_tokens(tile)
+    hg.hg_attn_set_span_tokens(tile)
     w = W.make_workload(spec, DEV)
     run_all_and_check(w, what="%s tile=%d" % (spec.name, tile))
 
@@ -59,7 +59,7 @@ def test_every_kernel_instance(dtype, d, group):
 @pytest.mark.parametrize("tile", [64, 128])
 def test_edge_ranges(tile):
     """Empty, one-token, tile-edge, unsorted and overlapping ranges; a zero-length sequence."""
-    hg.hg_attn_set_tile_tokens(tile)
+    hg.hg_attn_set_span_tokens(tile)
     spec = W.WorkloadSpec("edge", 3, 4, 2, 128, "f16", 0, 1000, "none", seed=5)
     w = W.make_workload(spec, DEV)
     w.seq_lens[:] = [1000, 0, 257]
@@ -88,7 +88,7 @@ def test_edge_ranges(tile):
 def test_zero_query_counts_tokens_bit_exact():
     """q = 0: m = 0 and l = range length exactly; with bit-plane values O is an exact integer
     count per channel, which pins the membership of every range and tile."""
-    hg.hg_attn_set_tile_tokens(128)
+    hg.hg_attn_set_span_tokens(128)
     N, d = 5000, 128
     spec = W.WorkloadSpec("bits", 1, 2, 1, d, "f16", N, N, "none", seed=9)
     w = W.make_workload(spec, DEV)
