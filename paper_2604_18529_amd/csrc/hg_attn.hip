@@ -7,6 +7,7 @@
 #include "hg_common.hip.h"
 #include "hg_select.hip.h"
 #include "hg_stream_gqa.hip.h"
+#include "hg_stream_gqa64.hip.h"
 #include "hg_stream_valu.hip.h"
 
 #include <cmath>
@@ -98,11 +99,8 @@ hg_status check_ranges(const hg_attn_desc *d, const hg_range *ranges, int32_t n_
     return HG_OK;
 }
 
-// The matrix-core kernel takes fp16, head_dim 128 and at least 4 query heads per KV head.
-bool use_gqa_kernel(const hg_attn_desc *d)
-{
-    return d->dtype == HG_F16 && d->head_dim == 128 && d->n_q_heads / d->n_kv_heads >= 4;
-}
+// The matrix-core kernels take fp16 and at least 4 query heads per KV head.
+bool use_gqa_kernel(const hg_attn_desc *d) { return d->dtype == HG_F16 && d->n_q_heads / d->n_kv_heads >= 4; }
 
 int32_t pick_group_tile(const hg_attn_desc *d)
 {
@@ -148,6 +146,15 @@ hg_status make_plan(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ran
     p.ws.ltok = (int32_t)ltok;
     p.ws.total = n_streams * ltok;
     p.ws.span = pick_span(p.ws.total, use_gqa_kernel(d));
+    {
+        // the streaming kernels address rows inside a workgroup's span with 32-bit byte offsets
+        const int64_t row_bytes = d->stride_t * (d->dtype == HG_F16 ? 2 : 4);
+        if (row_bytes > 0) {
+            const int64_t cap = (0xffffffffll - 65536) / row_bytes / 64 * 64;
+            if (cap < 64) return HG_ERR_SHAPE;
+            if (p.ws.span > cap) p.ws.span = (int32_t)cap;
+        }
+    }
     p.n_workgroups = (p.ws.total + p.ws.span - 1) / p.ws.span;
     if (p.n_workgroups > 0x7fffffff) return HG_ERR_SHAPE;
     p.n_slots = p.ws.total ? p.n_workgroups + n_streams * n_ranges : 0;
@@ -220,7 +227,10 @@ template <int MODE, bool PAGED>
 void launch_stream_paged(const hg_attn_desc *d, const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
 {
     if (use_gqa_kernel(d)) {
-        hipLaunchKernelGGL((hg_partial_gqa_kernel<MODE, PAGED>), grid, dim3(kGqaBlock), 0, stream, a);
+        if (d->head_dim == 128)
+            hipLaunchKernelGGL((hg_partial_gqa_kernel<MODE, PAGED>), grid, dim3(kGqaBlock), 0, stream, a);
+        else
+            hipLaunchKernelGGL((hg_partial_gqa64_kernel<MODE, PAGED>), grid, dim3(kGqaBlock), 0, stream, a);
         return;
     }
     const bool f16 = d->dtype == HG_F16;

@@ -66,7 +66,8 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     constexpr int kSmemBytes = kGqaWaves * kGqaWaveBytes > kMergeBytes ? kGqaWaves * kGqaWaveBytes : kMergeBytes;
     __shared__ __align__(16) char smem[kSmemBytes];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: block loop control stays scalar
     const int n = lane & 15, rg = lane >> 4;
 
     char *kls = smem + wave * kGqaWaveBytes;
@@ -114,11 +115,20 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 #pragma unroll
     for (int nb = 0; nb < 8; ++nb) o[nb] = hg_f4{0.f, 0.f, 0.f, 0.f};
 
-    const int64_t slab = (PAGED ? 0 : (int64_t)seq * a.stride_b) + (int64_t)hk * a.stride_h;
-    const char *kbase = static_cast<const char *>(a.k) + slab * 2 + n * 16;
-    const char *vbase = static_cast<const char *>(a.v) + slab * 2 + n * 16;
+    // Contiguous cache: the address of a row is a uniform 64-bit base (start of the segment) plus a
+    // 32-bit byte offset, (token - t0) * row_bytes + 16 * chunk.  The host keeps a workgroup's span
+    // times the row stride below 4 GiB.  Only the lane part of the offset is a vector quantity, so a
+    // load costs one add and one min (the clamp to the last row, taken in offset space).
+    // Paged cache: per-lane 64-bit addresses from the block table.
+    const int64_t slab = PAGED ? (int64_t)hk * a.stride_h : (int64_t)seq * a.stride_b + (int64_t)hk * a.stride_h + (int64_t)t0 * a.stride_t;
+    const char *kbase = static_cast<const char *>(a.k) + slab * 2 + (PAGED ? n * 16 : 0);
+    const char *vbase = static_cast<const char *>(a.v) + slab * 2 + (PAGED ? n * 16 : 0);
     const int64_t row_bytes = a.stride_t * 2;
     const int64_t block_bytes = a.stride_b * 2;
+    const uint32_t row_b32 = (uint32_t)row_bytes;
+    const uint32_t lane_off = (uint32_t)rg * row_b32 + (uint32_t)n * 16u;  // row rg of a load
+    const uint32_t lane_off_cc = (uint32_t)(8 * rg) * row_b32 + (uint32_t)n * 16u;  // concat mode: rows 8rg + j
+    const uint32_t last_off = (uint32_t)(t1 - 1 - t0) * row_b32 + (uint32_t)n * 16u;
     const int32_t *table = PAGED ? a.pages.table + (int64_t)seq * a.pages.max_blocks : nullptr;
 
     // Paged cache: physical blocks of the 8 tokens tb + 4x + rg (x = 0..7) a lane touches in a
@@ -130,17 +140,22 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             pg[x] = table[(tok < t1 ? tok : t1 - 1) >> a.pages.shift];
         }
     };
-    auto row_offset = [&](int tok, int page) __attribute__((always_inline)) -> int64_t {
-        return PAGED ? (int64_t)page * block_bytes + (int64_t)(tok & a.pages.mask) * row_bytes : (int64_t)tok * row_bytes;
+    auto paged_offset = [&](int tok, int page) __attribute__((always_inline)) -> int64_t {
+        tok = tok < t1 ? tok : t1 - 1;  // clamp: never read past the segment
+        return (int64_t)page * block_bytes + (int64_t)(tok & a.pages.mask) * row_bytes;
+    };
+    // row = token of the load relative to the lane's first row of the block (uniform)
+    auto flat_offset = [&](int tb, int row, uint32_t lane_part) __attribute__((always_inline)) -> uint32_t {
+        const uint32_t off = (uint32_t)(tb - t0 + row) * row_b32 + lane_part;
+        return off < last_off ? off : last_off;  // clamp: never read past the segment
     };
 
     // The 8 K-row loads and the 8 V-row loads of one 32-token block (8 KiB each per wave).
     auto load_k = [&](int tb, hg_u32x4(&kreg)[8], const int(&pg)[8]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            int tok = tb + 4 * i + rg;
-            tok = tok < t1 ? tok : t1 - 1;  // clamp: never read past the segment
-            kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(kbase + row_offset(tok, pg[i])));
+            const char *src = PAGED ? kbase + paged_offset(tb + 4 * i + rg, pg[i]) : kbase + flat_offset(tb, 4 * i, lane_off);
+            kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(src));
         }
     };
     auto load_v = [&](int tb, hg_u32x4(&vreg)[8], const int(&pg)[8]) __attribute__((always_inline)) {
@@ -148,10 +163,11 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         for (int j = 0; j < 8; ++j) {
             // token j of lane group rg: interleaved so that S halves pair up (stats mode), or the
             // 8 consecutive tokens whose logits this lane reads (concat mode)
-            int tok = MODE == kModeConcat ? tb + 8 * rg + j : tb + 16 * (j & 1) + 4 * (j >> 1) + rg;
-            tok = tok < t1 ? tok : t1 - 1;
-            vreg[j] = __builtin_nontemporal_load(
-                reinterpret_cast<const hg_u32x4 *>(vbase + row_offset(tok, pg[4 * (j & 1) + (j >> 1)])));
+            const int row = 16 * (j & 1) + 4 * (j >> 1);
+            const char *src = PAGED                 ? vbase + paged_offset(tb + row + rg, pg[4 * (j & 1) + (j >> 1)])
+                              : MODE == kModeConcat ? vbase + flat_offset(tb, j, lane_off_cc)
+                                                    : vbase + flat_offset(tb, row, lane_off);
+            vreg[j] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(src));
         }
     };
     // pages of the next block (pg1) and of the one after (pg2, in flight); unused when not paged
@@ -212,17 +228,38 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 
         // online softmax on S (lane: token n of each half, heads 4rg..4rg+3)
         const bool ok0 = tb + n < t1, ok1 = tb + 16 + n < t1;
-        float alpha[4];
+        // e = s - m against the running maximum.  Once a few blocks have been seen a new maximum is
+        // rare, so the row-maximum reduction and the rescaling of the accumulators sit behind a
+        // wave-uniform branch that is taken only when some logit of the block exceeds its m.
+        float e0[4], e1[4];
+        float top = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            e0[r] = ok0 ? fmaf(s[0][r], a.qscale, -m[r]) : -INFINITY;
+            e1[r] = ok1 ? fmaf(s[1][r], a.qscale, -m[r]) : -INFINITY;
+            top = fmaxf(fmaxf(e0[r], e1[r]), top);
+        }
+        const bool grow = __builtin_amdgcn_ballot_w64(top > 0.f) != 0;
+        if (grow) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float s0 = ok0 ? s[0][r] * a.qscale : -INFINITY;
+                const float s1 = ok1 ? s[1][r] * a.qscale : -INFINITY;
+                const float mx = fmaxf(m[r], row16_max(fmaxf(s0, s1)));
+                const float alpha = fast_exp2(m[r] - mx);
+                m[r] = mx;
+                e0[r] = s0 - mx;
+                e1[r] = s1 - mx;
+                lsum[r] *= alpha;
+#pragma unroll
+                for (int nb = 0; nb < 8; ++nb) o[nb][r] *= alpha;
+            }
+        }
         uint32_t ph[4], pl[4];  // packed (half 0, half 1) weights: fp16 head and fp16 remainder
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const float s0 = ok0 ? s[0][r] * a.qscale : -INFINITY;
-            const float s1 = ok1 ? s[1][r] * a.qscale : -INFINITY;
-            const float mx = fmaxf(m[r], row16_max(fmaxf(s0, s1)));
-            alpha[r] = fast_exp2(m[r] - mx);
-            m[r] = mx;
-            const float p0 = fast_exp2(s0 - mx), p1 = fast_exp2(s1 - mx);
-            lsum[r] = lsum[r] * alpha[r] + (p0 + p1);
+            const float p0 = fast_exp2(e0[r]), p1 = fast_exp2(e1[r]);
+            lsum[r] += p0 + p1;
             const _Float16 h0f = (_Float16)p0, h1f = (_Float16)p1;
             const _Float16 l0f = (_Float16)(p0 - (float)h0f), l1f = (_Float16)(p1 - (float)h1f);
             typedef _Float16 h2 __attribute__((ext_vector_type(2)));
@@ -252,8 +289,6 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             for (int jj = 0; jj < 4; ++jj)
                 braw[jj] = __builtin_amdgcn_perm(vreg[2 * jj + 1][nb >> 1], vreg[2 * jj][nb >> 1], sel);
             const hg_h8 b = __builtin_bit_cast(hg_h8, braw);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) o[nb][r] *= alpha[r];
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
         }
