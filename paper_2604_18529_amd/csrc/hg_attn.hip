@@ -428,11 +428,19 @@ size_t logits_ws_bytes(int32_t n_ranges)
 }
 
 // Long groups are selected in two stages (candidates per part, then among the candidates).
-constexpr int kSelectSplitTokens = 65536;  // groups up to this size are handled by one workgroup
-constexpr int kSelectPartTokens = 32768;
-constexpr int kSelectMaxParts = 32;
+// The fast path of the selection kernel holds kSelectRegTokens elements per workgroup, which is also the part size.
+constexpr int kSelectMaxParts = 64;
 
-int32_t select_parts(const hg_range *ranges, const int32_t *group_ptr, int32_t n_groups)
+// Workspace of hg_attn_select: range table, group table (when they do not fit in kernel
+// arguments), then the candidate values and columns of the two-stage path.
+struct SelectPlan {
+    int32_t parts = 1;
+    bool fast_first = true;  // fast path possible in the direct / candidates launch: top_k and elements per workgroup fit
+    bool fast_final = true;  // the same for the launch that selects among the candidates
+    size_t off_tab = 0, off_groups = 0, off_cand_val = 0, off_cand_col = 0, total = 0;
+};
+
+void select_parts(const hg_range *ranges, const int32_t *group_ptr, int32_t n_groups, int32_t top_k, SelectPlan &sp)
 {
     int64_t longest = 0;
     for (int32_t i = 0; i < n_groups; ++i) {
@@ -440,22 +448,16 @@ int32_t select_parts(const hg_range *ranges, const int32_t *group_ptr, int32_t n
         for (int32_t r = group_ptr[i]; r < group_ptr[i + 1]; ++r) n += ranges[r].end - ranges[r].begin;
         longest = std::max(longest, n);
     }
-    if (longest <= kSelectSplitTokens) return 1;
-    return (int32_t)std::min<int64_t>(kSelectMaxParts, (longest + kSelectPartTokens - 1) / kSelectPartTokens);
+    sp.parts = (int32_t)std::min<int64_t>(kSelectMaxParts, std::max<int64_t>(1, (longest + kSelectRegTokens - 1) / kSelectRegTokens));
+    sp.fast_first = top_k <= kSelectFastKeep && (longest + sp.parts - 1) / sp.parts <= kSelectRegTokens;
+    sp.fast_final = top_k <= kSelectFastKeep && (int64_t)sp.parts * top_k <= kSelectRegTokens;
 }
-
-// Workspace of hg_attn_select: range table, group table (when they do not fit in kernel
-// arguments), then the candidate values and columns of the two-stage path.
-struct SelectPlan {
-    int32_t parts = 1;
-    size_t off_tab = 0, off_groups = 0, off_cand_val = 0, off_cand_col = 0, total = 0;
-};
 
 SelectPlan plan_select(const hg_range *ranges, int32_t n_ranges, const int32_t *group_ptr, int32_t n_groups,
                        int32_t n_q_heads, int32_t top_k)
 {
     SelectPlan sp;
-    sp.parts = select_parts(ranges, group_ptr, n_groups);
+    select_parts(ranges, group_ptr, n_groups, top_k, sp);
     size_t off = 0;
     sp.off_tab = off;
     off += logits_ws_bytes(n_ranges);
@@ -472,21 +474,30 @@ SelectPlan plan_select(const hg_range *ranges, int32_t n_ranges, const int32_t *
     return sp;
 }
 
-template <int STAGE>
-void launch_select(const hg_attn_desc *desc, const SelectArgs &sa, dim3 grid, hipStream_t stream)
+template <int STAGE, bool FAST>
+void launch_select_variant(const hg_attn_desc *desc, const SelectArgs &sa, dim3 grid, hipStream_t stream)
 {
     const bool f16 = desc->dtype == HG_F16;
     if (desc->head_dim == 128) {
         if (f16)
-            hipLaunchKernelGGL((hg_select_kernel<Traits<128, true>, STAGE>), grid, dim3(kSelectBlock), 0, stream, sa);
+            hipLaunchKernelGGL((hg_select_kernel<Traits<128, true>, STAGE, FAST>), grid, dim3(FAST ? kSelectFastBlock : kSelectBlock), 0, stream, sa);
         else
-            hipLaunchKernelGGL((hg_select_kernel<Traits<128, false>, STAGE>), grid, dim3(kSelectBlock), 0, stream, sa);
+            hipLaunchKernelGGL((hg_select_kernel<Traits<128, false>, STAGE, FAST>), grid, dim3(FAST ? kSelectFastBlock : kSelectBlock), 0, stream, sa);
     } else {
         if (f16)
-            hipLaunchKernelGGL((hg_select_kernel<Traits<64, true>, STAGE>), grid, dim3(kSelectBlock), 0, stream, sa);
+            hipLaunchKernelGGL((hg_select_kernel<Traits<64, true>, STAGE, FAST>), grid, dim3(FAST ? kSelectFastBlock : kSelectBlock), 0, stream, sa);
         else
-            hipLaunchKernelGGL((hg_select_kernel<Traits<64, false>, STAGE>), grid, dim3(kSelectBlock), 0, stream, sa);
+            hipLaunchKernelGGL((hg_select_kernel<Traits<64, false>, STAGE, FAST>), grid, dim3(FAST ? kSelectFastBlock : kSelectBlock), 0, stream, sa);
     }
+}
+
+template <int STAGE>
+void launch_select(const hg_attn_desc *desc, const SelectArgs &sa, dim3 grid, bool fast, hipStream_t stream)
+{
+    if (fast)
+        launch_select_variant<STAGE, true>(desc, sa, grid, stream);
+    else
+        launch_select_variant<STAGE, false>(desc, sa, grid, stream);
 }
 
 }  // namespace
@@ -854,15 +865,15 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
     sa.parts = sp.parts;
     dim3 grid((unsigned)n_groups, (unsigned)desc->n_q_heads);
     if (sp.parts == 1) {
-        launch_select<kSelectDirect>(desc, sa, grid, stream);
+        launch_select<kSelectDirect>(desc, sa, grid, sp.fast_first, stream);
         return launch_status("selection kernel");
     }
     sa.cand_val = reinterpret_cast<float *>(ws + sp.off_cand_val);
     sa.cand_col = reinterpret_cast<int32_t *>(ws + sp.off_cand_col);
-    launch_select<kSelectCandidates>(desc, sa, dim3((unsigned)(n_groups * sp.parts), (unsigned)desc->n_q_heads), stream);
+    launch_select<kSelectCandidates>(desc, sa, dim3((unsigned)(n_groups * sp.parts), (unsigned)desc->n_q_heads), sp.fast_first, stream);
     st = launch_status("selection kernel (candidates)");
     if (st != HG_OK) return st;
-    launch_select<kSelectFromCands>(desc, sa, grid, stream);
+    launch_select<kSelectFromCands>(desc, sa, grid, sp.fast_final, stream);
     return launch_status("selection kernel (final)");
 }
 

@@ -128,7 +128,7 @@ def test_post_qk_selection_end_to_end():
 
 @pytest.mark.parametrize("top_k", [5, 4096])
 def test_long_groups_take_the_two_stage_path(top_k):
-    """Groups longer than 65536 tokens are cut into parts whose candidates are merged; the kept
+    """Groups longer than 16384 tokens are cut into parts whose candidates are merged; the kept
     set must still be the exact global top-k with the global tie-break (lower column)."""
     spec = W.WorkloadSpec("sellong", 2, 2, 1, 128, "f16", 70000, 150000, "none", seed=62)
     w = W.make_workload(spec, DEV)
@@ -143,6 +143,43 @@ def test_long_groups_take_the_two_stage_path(top_k):
     assert to_np(sel[1, 1]).tolist() == list(range(100, 100 + top_k))
 
 
+@pytest.mark.parametrize("order", ["ascending", "descending", "sawtooth", "two_values"])
+@pytest.mark.parametrize("n", [1000, 16384, 40000])
+def test_adversarial_orders(order, n):
+    """Orders that defeat the lower bound taken from per-thread maxima (every large logit in the
+    same few threads, or in the last columns), and logits with two distinct values only."""
+    spec = W.WorkloadSpec("seladv", 1, 2, 1, 64, "f16", n, n, "none", seed=64)
+    w = W.make_workload(spec, DEV)
+    ranges, gp = [(0, 0, n)], [0, 1]
+    base = np.arange(n, dtype=np.float32) / 64
+    if order == "ascending":
+        rows = [base, base * 0.5]
+    elif order == "descending":
+        rows = [base[::-1], -base]
+    elif order == "sawtooth":
+        rows = [(np.arange(n) % 1024).astype(np.float32), (np.arange(n) % 1024 == 3).astype(np.float32) * 5]
+    else:
+        rng = np.random.default_rng(65)
+        rows = [(rng.random(n) < 0.01).astype(np.float32), (rng.random(n) < 0.9).astype(np.float32) - 2]
+    lg = np.ascontiguousarray(np.stack(rows).astype(np.float32))
+    for top_k in (3, 128, 256, 2000):
+        _check_select(w, ranges, gp, lg, top_k, "%s n=%d k=%d" % (order, n, top_k))
+
+
+def test_groups_beyond_the_part_limit():
+    """A group of more than 64 x 16384 tokens leaves parts that do not fit in registers: the
+    streaming variant of the candidates stage runs.  Sorted logits put every kept token in the last part."""
+    n = 1_200_000
+    spec = W.WorkloadSpec("selhuge", 1, 1, 1, 64, "f16", n, n, "none", seed=66)
+    w = W.make_workload(spec, DEV)
+    ranges, gp = [(0, 0, 500_000), (0, 500_000, n)], [0, 2]
+    rng = np.random.default_rng(67)
+    lg = np.sort(rng.standard_normal(n).astype(np.float32))[None, :]
+    lg = np.ascontiguousarray(np.round(lg * 256) / 256)
+    sel, _, _, _ = _check_select(w, ranges, gp, lg, 500, "huge group")
+    assert int(to_np(sel[0, 0]).min()) > n - 40000
+
+
 def test_bad_arguments():
     spec = W.WorkloadSpec("selerr", 1, 2, 2, 64, "f16", 100, 100, "none", seed=60)
     w = W.make_workload(spec, DEV)
@@ -153,9 +190,11 @@ def test_bad_arguments():
         assert ei.value.status == -2
 
 
-def test_full_size_million_token_group():
-    """Benchmark shape: 64 query heads over 8 KV heads, one group of 1,048,576 offloaded tokens,
-    top_k = 1024; sampled heads against the oracle on seeded logits."""
+@pytest.mark.parametrize("top_k", [1024, 2048])
+def test_full_size_million_token_group(top_k):
+    """Benchmark shape: 64 query heads over 8 KV heads, one group of 1,048,576 offloaded tokens;
+    sampled heads against the oracle on seeded logits (top_k beyond the fast path: the radix
+    passes run in both stages, the final one over 64 x top_k candidates)."""
     spec = W.WORKLOADS[4]
     w = W.make_workload(spec, DEV)
     n = int(w.seq_lens[0])
@@ -164,12 +203,12 @@ def test_full_size_million_token_group():
     lg = (torch.randn((spec.n_q_heads, n), generator=gen, device=DEV, dtype=torch.float32) * 2)
     lg = (lg * 64).round() / 64  # exact ties
     ranges, gp = [(0, 0, n)], [0, 1]
-    sel, m, l, o = hg.hg_attn_select(w.q, w.k, w.v, w.seq_lens, ranges, lg, gp, 1024, w.scale)
+    sel, m, l, o = hg.hg_attn_select(w.q, w.k, w.v, w.seq_lens, ranges, lg, gp, top_k, w.scale)
     G = spec.n_q_heads // spec.n_kv_heads
     for h in (0, 13, 63):
         qs = to_np(w.q[:, h:h + 1])
         ks = to_np(w.k[:, h // G:h // G + 1])
         vs = to_np(w.v[:, h // G:h // G + 1])
-        rsel, rm, rl, ro = oracle.attn_select(qs, ks, vs, [n], w.scale, ranges, to_np(lg[h:h + 1]), gp, 1024)
+        rsel, rm, rl, ro = oracle.attn_select(qs, ks, vs, [n], w.scale, ranges, to_np(lg[h:h + 1]), gp, top_k)
         assert np.array_equal(to_np(sel[0, h]), rsel[0, 0])
         check_triples(m[:, h:h + 1], l[:, h:h + 1], o[:, h:h + 1], rm, rl, ro, "1M head %d" % h)
