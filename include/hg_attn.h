@@ -201,8 +201,10 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
  *            head in ascending column order, padded with -1.
  *   m, l     DEVICE [n_groups][n_q_heads] fp32;  o  DEVICE [n_groups][n_q_heads][head_dim] fp32.
  *            An empty group yields (-inf, 0, 0).
- *   Reads the logits (about five passes) and the kept V rows only.  Groups longer than 65536
- *   tokens are selected in two stages (candidates per 32768-token part, then among those).
+ *   Reads the logits and the kept V rows only: one pass over the logits for top_k <= 256, about
+ *   five for larger top_k or when the quick bound fails (sorted or masked rows).  Groups longer
+ *   than 16384 tokens are selected in two stages (candidates per part, then among those).
+ *   Logits must not contain NaN; -inf (masked tokens) is fine.
  */
 hg_status hg_attn_select_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges,
                                         const int32_t *group_ptr, int32_t n_groups, int32_t top_k, size_t *bytes);
