@@ -68,6 +68,8 @@ typedef enum hg_dtype { HG_F16 = 0, HG_F32 = 1 } hg_dtype;
  *               strides counted in ELEMENTS; the channel stride is 1.  Bases are 16-byte aligned
  *               and every stride is a multiple of 16 bytes, so each row is 16-byte aligned.
  *               K and V use the same strides.  Rows at t >= seq_lens[b] are never read.
+ *               A row stride of 64 MiB or more is refused (HG_ERR_SHAPE): the kernels address
+ *               the rows of one workgroup's share with 32-bit byte offsets.
  *   seq_lens HOST [batch], 0 <= seq_lens[b].
  *   head_dim 64 or 128.  n_q_heads % n_kv_heads == 0.
  *   scale   multiplies q.k before the softmax (natural-log domain); callers pass 1/sqrt(head_dim).
@@ -79,8 +81,7 @@ typedef enum hg_dtype { HG_F16 = 0, HG_F32 = 1 } hg_dtype;
  *   k, v        element (block p, head g, row r, c) is at base + p*stride_b + g*stride_h + r*stride_t + c:
  *               stride_b is the distance between physical blocks.  Table entries are not checked
  *               (they are device memory): every entry a valid token maps to must be a valid block.
- *   Supported by hg_attn_partial and hg_attn_full; the other calls return HG_ERR_SHAPE for a
- *   paged descriptor.
+ *   Every call that takes a descriptor accepts a paged one.
  */
 typedef struct hg_attn_desc {
     const void *q;

@@ -84,9 +84,6 @@ hg_status check_desc(const hg_attn_desc *d)
     return HG_OK;
 }
 
-// Entry points without paged-cache support.
-hg_status reject_paged(const hg_attn_desc *d) { return d && d->block_table ? HG_ERR_SHAPE : HG_OK; }
-
 hg_status check_ranges(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges)
 {
     if (n_ranges < 0) return HG_ERR_SHAPE;
@@ -247,18 +244,25 @@ void launch_stream_paged(const hg_attn_desc *d, const PartialArgs &a, int gt, di
     }
 }
 
-// One launch of the streaming kernel that fits the problem, in the given mode.  Paged caches
-// exist for the statistics mode only (the other entry points reject them up front).
+// One launch of the streaming kernel that fits the problem (storage type, head_dim, query group,
+// contiguous or paged cache), in the given mode.
 template <int MODE>
 void launch_stream(const hg_attn_desc *d, const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
 {
-    if constexpr (MODE == kModeStats) {
-        if (d->block_table) {
-            launch_stream_paged<MODE, true>(d, a, gt, grid, stream);
-            return;
-        }
-    }
-    launch_stream_paged<MODE, false>(d, a, gt, grid, stream);
+    if (d->block_table)
+        launch_stream_paged<MODE, true>(d, a, gt, grid, stream);
+    else
+        launch_stream_paged<MODE, false>(d, a, gt, grid, stream);
+}
+
+void fill_pages(const hg_attn_desc *d, PageMap &pages)
+{
+    if (!d->block_table) return;  // the caller zeroed the structure: table == nullptr means contiguous
+    pages.table = d->block_table;
+    pages.mask = d->block_tokens - 1;
+    pages.shift = 0;
+    while ((1 << pages.shift) < d->block_tokens) ++pages.shift;
+    pages.max_blocks = d->max_blocks;
 }
 
 void fill_stream_args(const hg_attn_desc *d, const Plan &p, char *ws, PartialArgs &pa)
@@ -271,13 +275,7 @@ void fill_stream_args(const hg_attn_desc *d, const Plan &p, char *ws, PartialArg
     pa.stride_t = d->stride_t;
     pa.ws = p.ws;
     pa.qscale = d->scale * kLog2e;
-    if (d->block_table) {
-        pa.pages.table = d->block_table;
-        pa.pages.mask = d->block_tokens - 1;
-        pa.pages.shift = 0;
-        while ((1 << pa.pages.shift) < d->block_tokens) ++pa.pages.shift;
-        pa.pages.max_blocks = d->max_blocks;
-    }
+    fill_pages(d, pa.pages);
     if (ws) {
         pa.ws_m = reinterpret_cast<float *>(ws + p.off_m);
         pa.ws_l = reinterpret_cast<float *>(ws + p.off_l);
@@ -668,8 +666,6 @@ hg_status hg_attn_logits_workspace_size(const hg_attn_desc *desc, const hg_range
     if (!bytes) return HG_ERR_NULL;
     hg_status st = check_desc(desc);
     if (st != HG_OK) return st;
-    st = reject_paged(desc);
-    if (st != HG_OK) return st;
     st = check_ranges(desc, ranges, n_ranges);
     if (st != HG_OK) return st;
     *bytes = logits_ws_bytes(n_ranges);
@@ -680,8 +676,6 @@ hg_status hg_attn_logits(const hg_attn_desc *desc, const hg_range *ranges, int32
                          void *workspace, size_t ws_bytes, void *stream_v)
 {
     hg_status st = check_desc(desc);
-    if (st != HG_OK) return st;
-    st = reject_paged(desc);
     if (st != HG_OK) return st;
     st = check_ranges(desc, ranges, n_ranges);
     if (st != HG_OK) return st;
@@ -712,8 +706,6 @@ hg_status hg_attn_concat_workspace_size(const hg_attn_desc *desc, const hg_range
     if (n_groups < 0 || n_groups > 65535) return HG_ERR_SHAPE;
     hg_status st = check_desc(desc);
     if (st != HG_OK) return st;
-    st = reject_paged(desc);
-    if (st != HG_OK) return st;
     st = check_ranges(desc, ranges, n_ranges);
     if (st != HG_OK) return st;
     Plan p;
@@ -729,8 +721,6 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
                          size_t ws_bytes, void *stream_v)
 {
     hg_status st = check_desc(desc);
-    if (st != HG_OK) return st;
-    st = reject_paged(desc);
     if (st != HG_OK) return st;
     st = check_ranges(desc, ranges, n_ranges);
     if (st != HG_OK) return st;
@@ -805,8 +795,6 @@ hg_status hg_attn_select_workspace_size(const hg_attn_desc *desc, const hg_range
     if (!bytes) return HG_ERR_NULL;
     hg_status st = check_desc(desc);
     if (st != HG_OK) return st;
-    st = reject_paged(desc);
-    if (st != HG_OK) return st;
     st = check_ranges(desc, ranges, n_ranges);
     if (st != HG_OK) return st;
     if (top_k < 1 || top_k > kMaxTopK) return HG_ERR_SHAPE;
@@ -821,8 +809,6 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
                          float *o, void *workspace, size_t ws_bytes, void *stream_v)
 {
     hg_status st = check_desc(desc);
-    if (st != HG_OK) return st;
-    st = reject_paged(desc);
     if (st != HG_OK) return st;
     st = check_ranges(desc, ranges, n_ranges);
     if (st != HG_OK) return st;
@@ -851,6 +837,7 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
     if (st != HG_OK) return st;
     sa.logits = logits;
     sa.v = desc->v;
+    fill_pages(desc, sa.pages);
     sa.stride_b = desc->stride_b;
     sa.stride_h = desc->stride_h;
     sa.stride_t = desc->stride_t;

@@ -170,6 +170,7 @@ struct SelectArgs {
     int32_t parts;
     float *cand_val;      // [n_groups][Hq][parts][top_k]
     int32_t *cand_col;
+    PageMap pages;        // table == nullptr: contiguous cache
     GroupTable groups;
     RangeTable tab;
 };

@@ -415,14 +415,19 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
     constexpr int LPR = TR::LPR, RPW = TR::RPW;
     const int sub = lane % LPR, grp = lane / LPR;
     const int hk = h / a.group;
-    const char *vbase = static_cast<const char *>(a.v) + ((int64_t)seq * a.stride_b + (int64_t)hk * a.stride_h) * ES;
+    // contiguous cache: the (sequence, KV head) slab; paged cache: the head's offset inside a block
+    const bool paged = a.pages.table != nullptr;
+    const char *vbase = static_cast<const char *>(a.v) + ((paged ? 0 : (int64_t)seq * a.stride_b) + (int64_t)hk * a.stride_h) * ES;
     const int64_t row_bytes = a.stride_t * ES;
+    const int32_t *table = paged ? a.pages.table + (int64_t)seq * a.pages.max_blocks : nullptr;
     float acc[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
     for (int j = RPW * wave + grp; j < keep; j += RPW * NW) {
         const float w = s_vals[j];
-        const char *vrow = vbase + (int64_t)s_cols[j] * row_bytes;
+        const int tok = s_cols[j];
+        const char *vrow = paged ? vbase + ((int64_t)table[tok >> a.pages.shift] * a.stride_b + (int64_t)(tok & a.pages.mask) * a.stride_t) * ES
+                                 : vbase + (int64_t)tok * row_bytes;
         float vf[EPL];
 #pragma unroll
         for (int jj = 0; jj < NV; ++jj) {

@@ -60,7 +60,6 @@ __device__ __forceinline__ void wave_lds_handover()
 template <int MODE, bool PAGED>
 __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_gqa_kernel(const PartialArgs a)
 {
-    static_assert(!PAGED || MODE == kModeStats, "paged caches are only wired into the statistics mode");
     constexpr int D = 128;
     constexpr int kMergeBytes = kGqaWaves * kGqaHeads * (D + 2) * 4;
     constexpr int kSmemBytes = kGqaWaves * kGqaWaveBytes > kMergeBytes ? kGqaWaves * kGqaWaveBytes : kMergeBytes;
@@ -132,11 +131,12 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     const int32_t *table = PAGED ? a.pages.table + (int64_t)seq * a.pages.max_blocks : nullptr;
 
     // Paged cache: physical blocks of the 8 tokens tb + 4x + rg (x = 0..7) a lane touches in a
-    // block; K load i uses x = i, V load j uses x = 4*(j&1) + (j>>1), the same 8 tokens.
+    // block; K load i uses x = i, V load j uses x = 4*(j&1) + (j>>1), the same 8 tokens.  In
+    // concat mode a lane's V tokens are tb + 8rg + x instead.
     auto lookup = [&](int tb, int(&pg)[8]) __attribute__((always_inline)) {
 #pragma unroll
         for (int x = 0; x < 8; ++x) {
-            const int tok = tb + 4 * x + rg;
+            const int tok = MODE == kModeConcat ? tb + 8 * rg + x : tb + 4 * x + rg;
             pg[x] = table[(tok < t1 ? tok : t1 - 1) >> a.pages.shift];
         }
     };
@@ -164,9 +164,11 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             // token j of lane group rg: interleaved so that S halves pair up (stats mode), or the
             // 8 consecutive tokens whose logits this lane reads (concat mode)
             const int row = 16 * (j & 1) + 4 * (j >> 1);
-            const char *src = PAGED                 ? vbase + paged_offset(tb + row + rg, pg[4 * (j & 1) + (j >> 1)])
-                              : MODE == kModeConcat ? vbase + flat_offset(tb, j, lane_off_cc)
-                                                    : vbase + flat_offset(tb, row, lane_off);
+            const char *src;
+            if constexpr (MODE == kModeConcat)
+                src = PAGED ? vbase + paged_offset(tb + 8 * rg + j, pg[j]) : vbase + flat_offset(tb, j, lane_off_cc);
+            else
+                src = PAGED ? vbase + paged_offset(tb + row + rg, pg[4 * (j & 1) + (j >> 1)]) : vbase + flat_offset(tb, row, lane_off);
             vreg[j] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(src));
         }
     };
@@ -182,7 +184,12 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         for (int i = 0; i < 8; ++i)
             *reinterpret_cast<hg_u32x4 *>(kls + (4 * i + rg) * kGqaKRow + n * 16) = kreg[i];
         wave_lds_handover();
-        if (tb_next < t1) load_k(tb_next, kreg, pg1);
+        if (tb_next < t1) {
+            load_k(tb_next, kreg, pg1);
+            if constexpr (PAGED && MODE == kModeLogits) {  // blocks are loaded in order: pages of the one after
+                if (tb_next + kGqaWaves * kGqaBlockTokens < t1) lookup(tb_next + kGqaWaves * kGqaBlockTokens, pg1);
+            }
+        }
         hg_f4 s[2];
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {
@@ -341,7 +348,12 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
         }
-        if (tb_next < t1) load_v(tb_next, vreg, pg1);
+        if (tb_next < t1) {
+            load_v(tb_next, vreg, pg1);
+            if constexpr (PAGED) {
+                if (tb_next + kGqaWaves * kGqaBlockTokens < t1) lookup(tb_next + kGqaWaves * kGqaBlockTokens, pg1);
+            }
+        }
     };
 
     {
@@ -364,13 +376,21 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         } else {
             // Only K (logits) or only V (concat) is read: two register buffers, so that two
             // blocks (16 KiB per wave) are in flight as in the statistics mode.
+            // Paged: pg1 always holds the pages of the next block to be loaded; the look-up for the
+            // block after it goes out right behind the loads and has one block of compute to land.
             hg_u32x4 ra[8], rb[8];
             auto load_one = [&](int t, hg_u32x4(&reg)[8]) __attribute__((always_inline)) {
                 if constexpr (MODE == kModeLogits)
                     load_k(t, reg, pg1);
                 else
                     load_v(t, reg, pg1);
+                if constexpr (PAGED) {
+                    if (t + kStride < t1) lookup(t + kStride, pg1);
+                }
             };
+            if constexpr (PAGED) {
+                if (tb < t1) lookup(tb, pg1);
+            }
             auto compute_one = [&](int t, hg_u32x4(&reg)[8]) __attribute__((always_inline)) {
                 if constexpr (MODE == kModeLogits)
                     compute_block(t, t + 2 * kStride, reg, reg);

@@ -28,7 +28,6 @@ constexpr int kGqa64WaveBytes = kGqa64KBytes + 2 * kGqaPBytes;
 template <int MODE, bool PAGED>
 __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_gqa64_kernel(const PartialArgs a)
 {
-    static_assert(!PAGED || MODE == kModeStats, "paged caches are only wired into the statistics mode");
     constexpr int D = 64;
     constexpr int kMergeBytes = kGqaWaves * kGqaHeads * (D + 2) * 4;
     constexpr int kSmemBytes = kGqaWaves * kGqa64WaveBytes > kMergeBytes ? kGqaWaves * kGqa64WaveBytes : kMergeBytes;
@@ -99,11 +98,12 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     const uint32_t last_off = (uint32_t)(t1 - 1 - t0) * row_b32 + (uint32_t)c8 * 16u;
     const int32_t *table = PAGED ? a.pages.table + (int64_t)seq * a.pages.max_blocks : nullptr;
 
-    // the 4 tokens tb + 8i + rl (i = 0..3) a lane touches in a block, for K and for V alike
+    // the 4 tokens a lane touches in a block, for K and for V alike: tb + 8i + rl (i = 0..3), or
+    // tb + 4rl + (slot of load i) in concat mode
     auto lookup = [&](int tb, int(&pg)[4]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int tok = tb + 8 * i + rl;
+            const int tok = MODE == kModeConcat ? tb + 4 * rl + 2 * (i & 1) + (i >> 1) : tb + 8 * i + rl;
             pg[i] = table[(tok < t1 ? tok : t1 - 1) >> a.pages.shift];
         }
     };
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if constexpr (PAGED) {
-                int tok = tb + 8 * i + rl;
+                int tok = MODE == kModeConcat ? tb + 4 * rl + 2 * (i & 1) + (i >> 1) : tb + 8 * i + rl;
                 tok = tok < t1 ? tok : t1 - 1;  // clamp: never read past the segment
                 const int64_t off = (int64_t)pg[i] * block_bytes + (int64_t)(tok & a.pages.mask) * row_bytes;
                 reg[i] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(base + off));
@@ -148,7 +148,12 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         for (int i = 0; i < 4; ++i)
             *reinterpret_cast<hg_u32x4 *>(kls + (8 * i + rl) * kGqa64KRow + c8 * 16) = kreg[i];
         wave_lds_handover();
-        if (tb_next < t1) load_rows(kbase, tb_next, kreg, pg1);
+        if (tb_next < t1) {
+            load_rows(kbase, tb_next, kreg, pg1);
+            if constexpr (PAGED && MODE == kModeLogits) {  // blocks are loaded in order: pages of the one after
+                if (tb_next + kGqaWaves * kGqaBlockTokens < t1) lookup(tb_next + kGqaWaves * kGqaBlockTokens, pg1);
+            }
+        }
         hg_f4 s[2];
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {
@@ -291,7 +296,12 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
         }
-        if (tb_next < t1) load_rows(vbase, tb_next, vreg, pg1);
+        if (tb_next < t1) {
+            load_rows(vbase, tb_next, vreg, pg1);
+            if constexpr (PAGED) {
+                if (tb_next + kGqaWaves * kGqaBlockTokens < t1) lookup(tb_next + kGqaWaves * kGqaBlockTokens, pg1);
+            }
+        }
     };
 
     {
@@ -313,18 +323,29 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             }
         } else {
             // K only (logits) or V only (concat): four register buffers keep 16 KiB per wave in flight
+            // Paged: pg1 always holds the pages of the next block to be loaded; the look-up for the
+            // block after it goes out right behind the loads.
             hg_u32x4 r0[4], r1[4], r2[4], r3[4];
             const char *base = MODE == kModeLogits ? kbase : vbase;
+            auto load_one = [&](int t, hg_u32x4(&reg)[4]) __attribute__((always_inline)) {
+                load_rows(base, t, reg, pg1);
+                if constexpr (PAGED) {
+                    if (t + kStride < t1) lookup(t + kStride, pg1);
+                }
+            };
+            if constexpr (PAGED) {
+                if (tb < t1) lookup(tb, pg1);
+            }
             auto compute_one = [&](int t, hg_u32x4(&reg)[4]) __attribute__((always_inline)) {
                 if constexpr (MODE == kModeLogits)
                     compute_block(t, t + 4 * kStride, reg, reg);
                 else
                     concat_block(t, t + 4 * kStride, reg);
             };
-            if (tb < t1) load_rows(base, tb, r0, pg1);
-            if (tb + kStride < t1) load_rows(base, tb + kStride, r1, pg1);
-            if (tb + 2 * kStride < t1) load_rows(base, tb + 2 * kStride, r2, pg1);
-            if (tb + 3 * kStride < t1) load_rows(base, tb + 3 * kStride, r3, pg1);
+            if (tb < t1) load_one(tb, r0);
+            if (tb + kStride < t1) load_one(tb + kStride, r1);
+            if (tb + 2 * kStride < t1) load_one(tb + 2 * kStride, r2);
+            if (tb + 3 * kStride < t1) load_one(tb + 3 * kStride, r3);
             while (tb < t1) {
                 compute_one(tb, r0);
                 tb += kStride;

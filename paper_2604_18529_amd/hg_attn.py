@@ -329,11 +329,12 @@ def hg_attn_full(q, k, v, seq_lens, scale=None, *, out=None, lse=None, want_lse=
     return out, lse
 
 
-def hg_attn_logits(q, k, v, seq_lens, ranges, scale=None, *, logits=None, workspace=None, stream=None, desc=None):
+def hg_attn_logits(q, k, v, seq_lens, ranges, scale=None, *, logits=None, workspace=None, stream=None, desc=None,
+                   block_table=None):
     """Raw scaled logits of the listed ranges, concatenated in table order: fp32 [Hq, ltok]."""
     lib = load_library()
     if desc is None:
-        desc, keep = make_desc(q, k, v, seq_lens, scale)
+        desc, keep = make_desc(q, k, v, seq_lens, scale, block_table)
     else:
         keep = None
     packed = pack_ranges(ranges)
@@ -365,12 +366,12 @@ def hg_attn_concat_workspace_size(desc, packed, n_groups) -> int:
 
 
 def hg_attn_concat(q, k, v, seq_lens, ranges, logits, group_ptr, scale=None, *, out=None, lse=None, want_lse=True,
-                   workspace=None, stream=None, desc=None):
+                   workspace=None, stream=None, desc=None, block_table=None):
     """One softmax over the concatenated logits of each group, then P.V (the paper-literal merge).
     Returns (out [n_groups,Hq,d], lse [n_groups,Hq] or None)."""
     lib = load_library()
     if desc is None:
-        desc, keep = make_desc(q, k, v, seq_lens, scale)
+        desc, keep = make_desc(q, k, v, seq_lens, scale, block_table)
     else:
         keep = None
     packed = pack_ranges(ranges)
@@ -402,12 +403,12 @@ def hg_attn_concat(q, k, v, seq_lens, ranges, logits, group_ptr, scale=None, *, 
 
 
 def hg_attn_select(q, k, v, seq_lens, ranges, logits, group_ptr, top_k, scale=None, *, want_sel=True, workspace=None,
-                   stream=None, desc=None):
+                   stream=None, desc=None, block_table=None):
     """Post-QK^T selection: per (group, head) keep the top_k logits and fold them with their V rows.
     Returns (sel int32 [G,Hq,top_k] or None, m [G,Hq], l [G,Hq], o [G,Hq,d])."""
     lib = load_library()
     if desc is None:
-        desc, keep = make_desc(q, k, v, seq_lens, scale)
+        desc, keep = make_desc(q, k, v, seq_lens, scale, block_table)
     else:
         keep = None
     packed = pack_ranges(ranges)

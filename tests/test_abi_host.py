@@ -68,6 +68,7 @@ def test_partial_rejects_bad_arguments_before_any_launch(lib):
     assert _partial(lib, _desc([10], k=FAKE + 8), good) == -2  # misaligned base
     assert _partial(lib, _desc([10], stride_t=64), good) == -2  # rows overlap
     assert _partial(lib, _desc([10], stride_t=132), good) == -2  # rows not 16-byte aligned
+    assert _partial(lib, _desc([10], stride_t=1 << 26), good) == -2  # rows 128 MiB apart: beyond 32-bit offsets
     assert _partial(lib, _desc([10], scale=float("nan")), good) == -2
     assert _partial(lib, _desc([-1]), good) == -4
     for bad in [(0, 5, 4), (0, 0, 11), (1, 0, 1), (-1, 0, 1), (0, -1, 3)]:

@@ -166,6 +166,21 @@ def test_adversarial_orders(order, n):
         _check_select(w, ranges, gp, lg, top_k, "%s n=%d k=%d" % (order, n, top_k))
 
 
+@pytest.mark.parametrize("n,finite", [(20000, 14000), (1000, 50), (40000, 100)])
+def test_masked_logits(n, finite):
+    """Logits of masked tokens are -inf.  With fewer finite logits than top_k the kept set is the
+    finite ones plus the first masked columns, whose weights are exactly zero."""
+    spec = W.WorkloadSpec("selmask", 1, 2, 1, 64, "f16", n, n, "none", seed=68)
+    w = W.make_workload(spec, DEV)
+    ranges, gp = [(0, 0, n)], [0, 1]
+    rng = np.random.default_rng(69)
+    lg = np.full((2, n), -np.inf, dtype=np.float32)
+    for h in range(2):
+        cols = rng.choice(n, size=finite, replace=False)
+        lg[h, cols] = rng.standard_normal(finite).astype(np.float32)
+    _check_select(w, ranges, gp, lg, 128, "masked n=%d finite=%d" % (n, finite))
+
+
 def test_groups_beyond_the_part_limit():
     """A group of more than 64 x 16384 tokens leaves parts that do not fit in registers: the
     streaming variant of the candidates stage runs.  Sorted logits put every kept token in the last part."""
