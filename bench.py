@@ -61,8 +61,8 @@ def _time_steps(step, steps, warmup, torch):
     return e0.elapsed_time(e1) / steps, wall_ms / steps
 
 
-def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
-    spec = W.WORKLOADS[index]
+def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W, routes=True):
+    spec = W.ALL_WORKLOADS[index]
     w = W.make_workload(spec, "cuda:0")
     desc, keep = hg.make_desc(w.q, w.k, w.v, w.seq_lens, w.scale)
     packed = hg.pack_ranges(w.ranges)
@@ -114,66 +114,86 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
 
     full_ms, _ = _time_steps(full_step, max(steps // 2, 1), max(warmup // 2, 1), torch)
 
-    # the paper-literal route: export raw logits per range, then concatenate, one softmax, P.V
-    ltok = sum(e - b for (_, b, e) in w.ranges)
-    logits = torch.empty((Hq, ltok), dtype=torch.float32, device=dev)
-    cws = torch.empty(max(binding.hg_attn_concat_workspace_size(desc, packed, spec.batch), 256), dtype=torch.uint8, device=dev)
-
-    def logits_step():
-        hg.hg_attn_logits(w.q, w.k, w.v, w.seq_lens, packed, w.scale, logits=logits, desc=desc)
-
-    def concat_step():
-        hg.hg_attn_concat(w.q, w.k, w.v, w.seq_lens, packed, logits, w.group_ptr, w.scale, out=out, lse=lse,
-                          workspace=cws, desc=desc)
-
-    logits_ms, _ = _time_steps(logits_step, max(steps // 2, 1), max(warmup // 2, 1), torch)
-    concat_ms, _ = _time_steps(concat_step, max(steps // 2, 1), max(warmup // 2, 1), torch)
-
-    # Post-QK^T flow (the paper's default selection mode): logits of the offloaded 80 % of every
-    # cache, top-128 per (sequence, head), triple of the kept tokens; the resident 20 % streamed
-    # as usual; one merge
-    old = [(b, 0, int(0.8 * n)) for b, n in enumerate(w.seq_lens)]
-    new = [(b, int(0.8 * n), int(n)) for b, n in enumerate(w.seq_lens)]
-    p_old, p_new = hg.pack_ranges(old), hg.pack_ranges(new)
-    lg_old = torch.empty((Hq, sum(e - b for (_, b, e) in old)), dtype=torch.float32, device=dev)
-    gp_old = list(range(spec.batch + 1))
-    merge_gp = list(range(0, 2 * spec.batch + 1, 2))
-    order = torch.arange(2 * spec.batch, device=dev).reshape(2, spec.batch).t().reshape(-1)
-    nws = torch.empty(max(binding.hg_attn_partial_workspace_size(desc, p_new), 256), dtype=torch.uint8, device=dev)
-    top_k = 128
-
-    def postqk_logits():
-        hg.hg_attn_logits(w.q, w.k, w.v, w.seq_lens, p_old, w.scale, logits=lg_old, desc=desc)
-
-    def postqk_select():
-        return hg.hg_attn_select(w.q, w.k, w.v, w.seq_lens, p_old, lg_old, gp_old, top_k, w.scale, want_sel=False, desc=desc)
-
-    def postqk_rest():
-        _, m1, l1, o1 = postqk_select()
-        m2, l2, o2 = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, p_new, w.scale, workspace=nws, desc=desc)
-        hg.hg_attn_merge(torch.cat([m1, m2])[order].contiguous(), torch.cat([l1, l2])[order].contiguous(),
-                         torch.cat([o1, o2])[order].contiguous(), merge_gp, out=out, lse=lse)
-
-    pq_logits_ms, _ = _time_steps(postqk_logits, max(steps // 4, 1), max(warmup // 4, 1), torch)
-    pq_select_ms, _ = _time_steps(postqk_select, max(steps // 4, 1), max(warmup // 4, 1), torch)
-    pq_rest_ms, _ = _time_steps(postqk_rest, max(steps // 4, 1), max(warmup // 4, 1), torch)
-
-    # the same cache as a paged pool (16-token blocks in shuffled physical order), same step
-    paged = {}
-    for bt in (16, 256):
-        kp, vp, table = W.make_paged(w, bt, seed=1)
-        pdesc, pkeep = hg.make_desc(w.q, kp, vp, w.seq_lens, w.scale, table)
-
-        def paged_step():
-            hg.hg_attn_partial(w.q, kp, vp, w.seq_lens, packed, w.scale, m=m, l=l, o=o, workspace=ws, desc=pdesc)
-            hg.hg_attn_merge(m, l, o, w.group_ptr, out=out, lse=lse)
-
-        pms, _ = _time_steps(paged_step, max(steps // 4, 1), max(warmup // 4, 1), torch)
-        paged["block_%d" % bt] = {"us": pms * 1e3, "gbps": w.kv_bytes / (pms * 1e-3) / 1e9}
-        del kp, vp, table, pdesc, pkeep
-        torch.cuda.empty_cache()
-
     kv_bytes = w.kv_bytes
+    route_results = {}
+    if routes:
+        # the paper-literal route: export raw logits per range, then concatenate, one softmax, P.V
+        ltok = sum(e - b for (_, b, e) in w.ranges)
+        logits = torch.empty((Hq, ltok), dtype=torch.float32, device=dev)
+        cws = torch.empty(max(binding.hg_attn_concat_workspace_size(desc, packed, spec.batch), 256), dtype=torch.uint8, device=dev)
+
+        def logits_step():
+            hg.hg_attn_logits(w.q, w.k, w.v, w.seq_lens, packed, w.scale, logits=logits, desc=desc)
+
+        def concat_step():
+            hg.hg_attn_concat(w.q, w.k, w.v, w.seq_lens, packed, logits, w.group_ptr, w.scale, out=out, lse=lse,
+                              workspace=cws, desc=desc)
+
+        logits_ms, _ = _time_steps(logits_step, max(steps // 2, 1), max(warmup // 2, 1), torch)
+        concat_ms, _ = _time_steps(concat_step, max(steps // 2, 1), max(warmup // 2, 1), torch)
+
+        # Post-QK^T flow (the paper's default selection mode): logits of the offloaded 80 % of every
+        # cache, top-128 per (sequence, head), triple of the kept tokens; the resident 20 % streamed
+        # as usual; one merge
+        old = [(b, 0, int(0.8 * n)) for b, n in enumerate(w.seq_lens)]
+        new = [(b, int(0.8 * n), int(n)) for b, n in enumerate(w.seq_lens)]
+        p_old, p_new = hg.pack_ranges(old), hg.pack_ranges(new)
+        lg_old = torch.empty((Hq, sum(e - b for (_, b, e) in old)), dtype=torch.float32, device=dev)
+        gp_old = list(range(spec.batch + 1))
+        merge_gp = list(range(0, 2 * spec.batch + 1, 2))
+        order = torch.arange(2 * spec.batch, device=dev).reshape(2, spec.batch).t().reshape(-1)
+        nws = torch.empty(max(binding.hg_attn_partial_workspace_size(desc, p_new), 256), dtype=torch.uint8, device=dev)
+        top_k = 128
+
+        def postqk_logits():
+            hg.hg_attn_logits(w.q, w.k, w.v, w.seq_lens, p_old, w.scale, logits=lg_old, desc=desc)
+
+        def postqk_select():
+            return hg.hg_attn_select(w.q, w.k, w.v, w.seq_lens, p_old, lg_old, gp_old, top_k, w.scale, want_sel=False, desc=desc)
+
+        def postqk_rest():
+            _, m1, l1, o1 = postqk_select()
+            m2, l2, o2 = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, p_new, w.scale, workspace=nws, desc=desc)
+            hg.hg_attn_merge(torch.cat([m1, m2])[order].contiguous(), torch.cat([l1, l2])[order].contiguous(),
+                             torch.cat([o1, o2])[order].contiguous(), merge_gp, out=out, lse=lse)
+
+        pq_logits_ms, _ = _time_steps(postqk_logits, max(steps // 4, 1), max(warmup // 4, 1), torch)
+        pq_select_ms, _ = _time_steps(postqk_select, max(steps // 4, 1), max(warmup // 4, 1), torch)
+        pq_rest_ms, _ = _time_steps(postqk_rest, max(steps // 4, 1), max(warmup // 4, 1), torch)
+
+        # the same cache as a paged pool (16-token blocks in shuffled physical order), same step
+        paged = {}
+        for bt in (16, 256):
+            kp, vp, table = W.make_paged(w, bt, seed=1)
+            pdesc, pkeep = hg.make_desc(w.q, kp, vp, w.seq_lens, w.scale, table)
+
+            def paged_step():
+                hg.hg_attn_partial(w.q, kp, vp, w.seq_lens, packed, w.scale, m=m, l=l, o=o, workspace=ws, desc=pdesc)
+                hg.hg_attn_merge(m, l, o, w.group_ptr, out=out, lse=lse)
+
+            pms, _ = _time_steps(paged_step, max(steps // 4, 1), max(warmup // 4, 1), torch)
+            paged["block_%d" % bt] = {"us": pms * 1e3, "gbps": w.kv_bytes / (pms * 1e-3) / 1e9}
+            del kp, vp, table, pdesc, pkeep
+            torch.cuda.empty_cache()
+
+        route_results = {
+            "post_qk_route": {
+                "offloaded_fraction": 0.8,
+                "top_k": top_k,
+                "logits_us": pq_logits_ms * 1e3,
+                "select_us": pq_select_ms * 1e3,
+                "select_resident_merge_us": pq_rest_ms * 1e3,
+                "us": (pq_logits_ms + pq_rest_ms) * 1e3,
+            },
+            "paged_cache": paged,
+            "concat_route": {
+                "logits_us": logits_ms * 1e3,
+                "concat_us": concat_ms * 1e3,
+                "us": (logits_ms + concat_ms) * 1e3,
+                "gbps": kv_bytes / ((logits_ms + concat_ms) * 1e-3) / 1e9,
+                "logits_bytes": int(Hq) * int(ltok) * 4,
+            },
+        }
     res = {
         "workload": spec.name,
         "batch": spec.batch,
@@ -195,23 +215,8 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W):
         "stream_kernel_gbps": kv_bytes / (kernel_ms * 1e-3) / 1e9,
         "host_wall_us_per_step": wall_ms * 1e3,
         "graph_replay_us": graph_ms * 1e3,
-        "post_qk_route": {
-            "offloaded_fraction": 0.8,
-            "top_k": top_k,
-            "logits_us": pq_logits_ms * 1e3,
-            "select_us": pq_select_ms * 1e3,
-            "select_resident_merge_us": pq_rest_ms * 1e3,
-            "us": (pq_logits_ms + pq_rest_ms) * 1e3,
-        },
-        "paged_cache": paged,
-        "concat_route": {
-            "logits_us": logits_ms * 1e3,
-            "concat_us": concat_ms * 1e3,
-            "us": (logits_ms + concat_ms) * 1e3,
-            "gbps": kv_bytes / ((logits_ms + concat_ms) * 1e-3) / 1e9,
-            "logits_bytes": int(Hq) * int(ltok) * 4,
-        },
     }
+    res.update(route_results)
 
     cpu = None
     if with_cpu_baseline:
@@ -253,9 +258,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", type=int, default=1, help="index into the standard workloads (headline: 1)")
+    ap.add_argument("--workload", type=int, default=1, help="index into workloads.ALL_WORKLOADS (headline: 1; 0-4 are the benchmark configurations, 5+ further shapes)")
     ap.add_argument("--others", type=str, default="0,2,3,4", help="comma list of further workloads to time ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-routes", action="store_true",
+                    help="time the step and the unsplit path only (skips the concat, Post-QK^T and paged-cache timings)")
     ap.add_argument("--span-tokens", type=int, default=0, help="force the span length (tuning)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run the library's plain 1 GiB device copy three times (known traffic: the "
@@ -283,7 +290,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    head, cpu = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, torch, hg, W)
+    head, cpu = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, torch, hg, W, not args.no_routes)
     others = []
     for tok in [t for t in args.others.split(",") if t.strip()]:
         i = int(tok)
@@ -291,12 +298,14 @@ def main():
             continue
         torch.cuda.empty_cache()
         k = max(args.steps // 10, 5)
-        r, _ = run_workload(i, k, max(args.warmup // 10, 2), False, torch, hg, W)
+        r, _ = run_workload(i, k, max(args.warmup // 10, 2), False, torch, hg, W, not args.no_routes)
         r["steps"] = k
         others.append(r)
 
-    kernel_name = "hg_partial_gqa_kernel" if (head["kv_dtype"] == "f16" and head["head_dim"] == 128
-                                               and head["n_q_heads"] // head["n_kv_heads"] >= 4) else "hg_partial_kernel"
+    if head["kv_dtype"] == "f16" and head["n_q_heads"] // head["n_kv_heads"] >= 4:  # the library's own dispatch rule
+        kernel_name = "hg_partial_gqa_kernel" if head["head_dim"] == 128 else "hg_partial_gqa64_kernel"
+    else:
+        kernel_name = "hg_partial_kernel"
     traffic, traffic_src = _profiled_traffic(kernel_name, head["workload"])
     line = {
         "metric": "decode attention effective KV GB/s (% of HBM peak) and us/layer at 1 GPU",
@@ -330,9 +339,9 @@ def main():
         },
         "cpu_baseline": cpu,
         "full_path": {"us": head["full_path_us"], "gbps": head["full_path_gbps"]},
-        "concat_route": head["concat_route"],
-        "post_qk_route": head["post_qk_route"],
-        "paged_cache": head["paged_cache"],
+        "concat_route": head.get("concat_route"),
+        "post_qk_route": head.get("post_qk_route"),
+        "paged_cache": head.get("paged_cache"),
         "other_workloads": others,
         "paper_context": PAPER_CONTEXT,
     }

@@ -60,6 +60,15 @@ WORKLOADS: List[WorkloadSpec] = [
     WorkloadSpec("gqa70b-b1-1m", 1, 64, 8, 128, "f16", 1048576, 1048576, "dirichlet", 16, outlier_k=True),
 ]
 
+# Further shapes, measured and parity-tested like the benchmark configurations but not part of
+# them: they exercise kernel variants that no benchmark configuration reaches.  Indices continue
+# after WORKLOADS (ALL_WORKLOADS[5] is the first).
+EXTRA_WORKLOADS: List[WorkloadSpec] = [
+    # fp16, head_dim 64, 4 query heads per KV head: the matrix-core kernel for 128-byte rows
+    WorkloadSpec("gqa4-d64-b8-64k", 8, 32, 8, 64, "f16", 65536, 65536, "dirichlet", 4, seed=5),
+]
+ALL_WORKLOADS: List[WorkloadSpec] = WORKLOADS + EXTRA_WORKLOADS
+
 
 @dataclasses.dataclass
 class Workload:

@@ -25,10 +25,10 @@ def _sample_pairs(spec, n, seed):
     return sorted(pairs)
 
 
-@pytest.mark.parametrize("index", [1, 2, 3, 4])
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5])
 def test_full_size_sampled_against_oracle(index):
     hg.hg_attn_set_span_tokens(0)
-    spec = W.WORKLOADS[index]
+    spec = W.ALL_WORKLOADS[index]
     w = W.make_workload(spec, DEV)
     m, l, o = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, w.ranges, w.scale)
     out, lse = hg.hg_attn_merge(m, l, o, w.group_ptr)
