@@ -144,8 +144,20 @@ hg_status make_plan(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ran
     p.ws.total = n_streams * ltok;
     p.ws.span = pick_span(p.ws.total, use_gqa_kernel(d));
     {
-        // the streaming kernels address rows inside a workgroup's span with 32-bit byte offsets
         const int64_t row_bytes = d->stride_t * (d->dtype == HG_F16 ? 2 : 4);
+        // Long spans whose byte length is a multiple of 1 MiB put every workgroup of the vector
+        // kernel at the same phase of the memory interleave, and the workgroups then advance in
+        // step.  Measured on three MI355X machines this costs 4-6 % of the bandwidth (84-87 %
+        // instead of 90-91 % of the peak) for spans from 8 to 32 MiB, while starts shifted by
+        // 32 KiB from one workgroup to the next held 90-91 % on all of them.  Short spans (one
+        // workgroup per (sequence, head) slab, a few MiB) and the matrix-core kernels showed no
+        // gain or a small loss, so they keep their aligned spans.
+        if (!g_forced_span_tokens && !use_gqa_kernel(d) && row_bytes > 0 && p.ws.span >= 32768 &&
+            ((int64_t)p.ws.span * row_bytes) % (1 << 20) == 0) {
+            const int64_t skew = std::max<int64_t>(64, ((32768 / row_bytes) + 63) / 64 * 64);
+            p.ws.span += (int32_t)skew;
+        }
+        // the streaming kernels address rows inside a workgroup's span with 32-bit byte offsets
         if (row_bytes > 0) {
             const int64_t cap = (0xffffffffll - 65536) / row_bytes / 64 * 64;
             if (cap < 64) return HG_ERR_SHAPE;
