@@ -96,8 +96,11 @@ hg_status check_ranges(const hg_attn_desc *d, const hg_range *ranges, int32_t n_
     return HG_OK;
 }
 
-// The matrix-core kernels take fp16 and at least 4 query heads per KV head.
-bool use_gqa_kernel(const hg_attn_desc *d) { return d->dtype == HG_F16 && d->n_q_heads / d->n_kv_heads >= 4; }
+// The matrix-core kernels take fp16 and at least HG_GQA_MIN_GROUP query heads per KV head.
+#ifndef HG_GQA_MIN_GROUP
+#define HG_GQA_MIN_GROUP 2
+#endif
+bool use_gqa_kernel(const hg_attn_desc *d) { return d->dtype == HG_F16 && d->n_q_heads / d->n_kv_heads >= HG_GQA_MIN_GROUP; }
 
 int32_t pick_group_tile(const hg_attn_desc *d)
 {
