@@ -196,8 +196,8 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
  *
  *   ranges, logits, group_ptr   as for hg_attn_concat (a group = the offloaded ranges of one sequence).
  *   top_k    1 .. 4096.  A group with fewer tokens keeps all of them.  The decision is taken on
- *            the fp32 logits as given; ties at the threshold go to the lower column (earlier
- *            range in the table, earlier token).
+ *            the fp32 logits as given; ties at the threshold (equal values; -0.0 equals +0.0) go
+ *            to the lower column (earlier range in the table, earlier token).
  *   sel      DEVICE int32 [n_groups][n_q_heads][top_k] or NULL: the kept TOKEN positions of each
  *            head in ascending column order, padded with -1.
  *   m, l     DEVICE [n_groups][n_q_heads] fp32;  o  DEVICE [n_groups][n_q_heads][head_dim] fp32.

@@ -41,7 +41,8 @@ namespace hg {
 
 __device__ __forceinline__ uint32_t order_key(float x)
 {
-    const uint32_t u = __float_as_uint(x);
+    uint32_t u = __float_as_uint(x);
+    u = u == 0x80000000u ? 0u : u;                      // -0.0 and +0.0 are one value: they tie
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // larger float <=> larger key
 }
 
@@ -112,11 +113,15 @@ __device__ __forceinline__ bool select_fast(const float *__restrict__ row, int n
     }
     if (tid < 2) f.cand[kSelectCandCap + tid] = 0ull;
     if (tid == 0) f.count = 0u;
-    // Slots past the end repeat the last element (the clamp above): the copies change neither the
-    // maxima nor the bound, and they are dropped when the candidates are written.
+    // Slots past the end must not count as elements: they become -inf, which no bound admits (a
+    // bound at or below -inf sends the workgroup to the radix passes).  Without this the copies of
+    // the last element made by the clamp above would pose as per-thread maxima of their own.
     float tm = -INFINITY;
 #pragma unroll
-    for (int e = 0; e < kSelectRegs; ++e) tm = fmaxf(tm, x[e]);
+    for (int e = 0; e < kSelectRegs; ++e) {
+        if (e * kSelectFastBlock + tid >= n) x[e] = -INFINITY;
+        tm = fmaxf(tm, x[e]);
+    }
     // a. bound
     const uint32_t tmax = order_key(tm);
     const int need = (keep + NW - 1) / NW;
@@ -148,17 +153,16 @@ __device__ __forceinline__ bool select_fast(const float *__restrict__ row, int n
             const uint64_t bc = __builtin_amdgcn_ballot_w64(c);
             if (bc) {
                 const uint32_t pos = at + (uint32_t)__builtin_popcountll(bc & below);
-                if (c && e * kSelectFastBlock + tid < n && pos < (uint32_t)kSelectCandCap)
+                if (c && pos < (uint32_t)kSelectCandCap)
                     f.cand[pos] = ((unsigned long long)order_key(x[e]) << 32) | (uint32_t)~(uint32_t)(e * kSelectFastBlock + tid);
                 at += (uint32_t)__builtin_popcountll(bc);
             }
         }
     }
     __syncthreads();
-    // nc counts the copies too; their slots stay zero words, which rank below every candidate.  At
-    // least `keep` real candidates exist (the maxima that reach the bound are distinct elements).
+    // At least `keep` candidates exist: the maxima that reach the bound are distinct elements.
     const int nc = (int)f.count;
-    if (nc > kSelectCandCap) return false;
+    if (nc > kSelectCandCap || nc < keep) return false;  // (nc < keep: only with NaN logits)
 
     // c. ranks.  Few candidates: candidate c = tid % ncr is counted by split tid / ncr over its
     //    share of the list (partial counts meet in f.rank); many: one thread per candidate or two.

@@ -1,0 +1,106 @@
+"""Seeded random sweep over storage type, head size, query group, layout, paging, span length and
+range tables: every entry point against the oracle.  The fixed cases of the other files pin the
+known edges; this one looks for the combinations nobody thought of."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_18529_amd as hg
+from paper_2604_18529_amd import workloads as W
+
+from parity_utils import check_out, check_triples, kv_np, to_np
+from test_concat_gpu import LOGIT_TOL, _oracle_concat
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(autouse=True)
+def _default_spans():
+    hg.hg_attn_set_span_tokens(0)
+    yield
+    hg.hg_attn_set_span_tokens(0)
+
+
+def _grouped_ranges(rng, seq_lens, max_per_seq):
+    """Ranges grouped by sequence (ascending, possibly overlapping, possibly empty) and their CSR."""
+    ranges, gp = [], [0]
+    for b, n in enumerate(seq_lens):
+        k = int(rng.integers(0, max_per_seq + 1))
+        rs = []
+        for _ in range(k):
+            a, c = sorted(int(x) for x in rng.integers(0, n + 1, size=2))
+            if rng.random() < 0.15:
+                c = a  # empty
+            if rng.random() < 0.15:
+                a, c = 0, int(n)  # the whole sequence
+            rs.append((b, a, c))
+        rs.sort(key=lambda r: (r[1], r[2]))
+        ranges += rs
+        gp.append(len(ranges))
+    return ranges, gp
+
+
+@pytest.mark.parametrize("case", range(96))
+def test_random_case(case):
+    rng = np.random.default_rng(1000 + case)
+    dtype = ["f16", "f32"][int(rng.integers(2))]
+    d = [64, 128][int(rng.integers(2))]
+    group = int(rng.choice([1, 1, 2, 3, 4, 6, 8, 16, 17]))
+    hkv = int(rng.integers(1, 4))
+    batch = int(rng.integers(1, 5))
+    n_max = int(rng.choice([40, 300, 1500, 4000]))
+    layout = ["bhtd", "bthd"][int(rng.integers(2))]
+    paged = rng.random() < 0.4
+    block_tokens = int(rng.choice([16, 32, 128]))
+    span = int(rng.choice([0, 0, 64, 192, 1024]))
+    top_k = int(rng.choice([1, 5, 64, 200, 300, 1500]))
+    what = "case %d: %s d=%d G=%d Hkv=%d B=%d n<=%d %s paged=%s/%d span=%d k=%d" % (
+        case, dtype, d, group, hkv, batch, n_max, layout, paged, block_tokens, span, top_k)
+    print(what, flush=True)
+
+    spec = W.WorkloadSpec("rnd", batch, group * hkv, hkv, d, dtype, 0, n_max, "none", seed=2000 + case)
+    w = W.make_workload(spec, DEV, layout=layout)
+    if rng.random() < 0.3:
+        w.seq_lens[int(rng.integers(batch))] = 0
+    ranges, gp = _grouped_ranges(rng, w.seq_lens, 5)
+    hg.hg_attn_set_span_tokens(span)
+    qn = to_np(w.q)
+    kn, vn = kv_np(w)
+    if paged:
+        k_dev, v_dev, table = W.make_paged(w, block_tokens, seed=case)
+    else:
+        k_dev, v_dev, table = w.k, w.v, None
+
+    m, l, o = hg.hg_attn_partial(w.q, k_dev, v_dev, w.seq_lens, ranges, w.scale, block_table=table)
+    mo, lo, oo = oracle.attn_partial(qn, kn, vn, w.seq_lens, w.scale, ranges)
+    check_triples(m, l, o, mo, lo, oo, what + " partial")
+    out, lse = hg.hg_attn_merge(m, l, o, gp)
+    ref, rlse = oracle.attn_merge(mo, lo, oo, gp)
+    check_out(out, lse, ref, rlse, what + " merge")
+    fout, flse = hg.hg_attn_full(w.q, k_dev, v_dev, w.seq_lens, w.scale, block_table=table)
+    fref, frlse = oracle.attn_full(qn, kn, vn, w.seq_lens, w.scale)
+    check_out(fout, flse, fref, frlse, what + " full")
+
+    lg = hg.hg_attn_logits(w.q, k_dev, v_dev, w.seq_lens, ranges, w.scale, block_table=table)
+    lg_ref = oracle.attn_logits(qn, kn, vn, w.seq_lens, w.scale, ranges)
+    assert lg.shape == lg_ref.shape
+    if lg_ref.size:
+        assert np.abs(to_np(lg).astype(np.float64) - lg_ref).max() <= LOGIT_TOL, what + " logits"
+    cout, clse = hg.hg_attn_concat(w.q, k_dev, v_dev, w.seq_lens, ranges, lg, gp, w.scale, block_table=table)
+    cref, crlse = _oracle_concat(w, ranges, gp)
+    check_out(cout, clse, cref, crlse, what + " concat")
+
+    # selection decides on the logits as given: quantise a copy so that ties occur
+    lg_q = (torch.round(lg * 4) / 4).contiguous()
+    sel, sm, sl, so = hg.hg_attn_select(w.q, k_dev, v_dev, w.seq_lens, ranges, lg_q, gp, top_k, w.scale, block_table=table)
+    rsel, rm, rl, ro = oracle.attn_select(qn, kn, vn, w.seq_lens, w.scale, ranges, to_np(lg_q), gp, top_k)
+    got = to_np(sel)
+    if not np.array_equal(got, rsel):
+        g, h = [int(x[0]) for x in np.nonzero((got != rsel).any(axis=2))]
+        pre = np.cumsum([0] + [e - s for _, s, e in ranges])
+        row = to_np(lg_q)[h, pre[gp[g]]:pre[gp[g + 1]]]
+        raise AssertionError("%s select: kept tokens differ in group %d head %d\n got  %s\n want %s\n logits %s" % (
+            what, g, h, got[g, h].tolist(), rsel[g, h].tolist(), row.tolist()))
+    check_triples(sm, sl, so, rm, rl, ro, what + " select")

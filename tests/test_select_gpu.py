@@ -181,6 +181,24 @@ def test_masked_logits(n, finite):
     _check_select(w, ranges, gp, lg, 128, "masked n=%d finite=%d" % (n, finite))
 
 
+def test_signed_zeros_tie():
+    """-0.0 and +0.0 are the same logit: at a threshold of zero the lower column wins whatever the
+    sign bits say."""
+    n = 600
+    spec = W.WorkloadSpec("selzero", 1, 2, 1, 64, "f16", n, n, "none", seed=74)
+    w = W.make_workload(spec, DEV)
+    rng = np.random.default_rng(75)
+    lg = np.where(rng.random((2, n)) < 0.5, np.float32(-0.0), np.float32(0.0)).astype(np.float32)
+    lg[0, rng.choice(n, 20, replace=False)] = 1.0
+    lg[1, rng.choice(n, 300, replace=False)] = -1.0
+    for top_k in (50, 200, 1000):
+        sel, _, _, _ = _check_select(w, [(0, 0, n)], [0, 1], lg, top_k, "signed zeros k=%d" % top_k)
+    sel, _, _, _ = _check_select(w, [(0, 0, n)], [0, 1], lg, 50, "signed zeros")
+    ones = np.flatnonzero(lg[0] == 1.0)
+    zeros = np.flatnonzero(lg[0] == 0.0)[:30]
+    assert to_np(sel[0, 0]).tolist() == sorted(ones.tolist() + zeros.tolist())
+
+
 def test_groups_beyond_the_part_limit():
     """A group of more than 64 x 16384 tokens leaves parts that do not fit in registers: the
     streaming variant of the candidates stage runs.  Sorted logits put every kept token in the last part."""
