@@ -42,20 +42,23 @@ def _grouped_ranges(rng, seq_lens, max_per_seq):
     return ranges, gp
 
 
-@pytest.mark.parametrize("case", range(96))
+@pytest.mark.parametrize("case", list(range(96)) + list(range(500, 516)))
 def test_random_case(case):
+    """Cases below 500 are short (every code path of a workgroup, many combinations); cases from
+    500 are long enough for several spans per stream and for the two-stage selection."""
     rng = np.random.default_rng(1000 + case)
+    big = case >= 500
     dtype = ["f16", "f32"][int(rng.integers(2))]
     d = [64, 128][int(rng.integers(2))]
-    group = int(rng.choice([1, 1, 2, 3, 4, 6, 8, 16, 17]))
-    hkv = int(rng.integers(1, 4))
-    batch = int(rng.integers(1, 5))
-    n_max = int(rng.choice([40, 300, 1500, 4000]))
+    group = int(rng.choice([1, 4, 8, 3] if big else [1, 1, 2, 3, 4, 6, 8, 16, 17]))
+    hkv = int(rng.integers(1, 3 if big else 4))
+    batch = int(rng.integers(1, 3 if big else 5))
+    n_max = int(rng.choice([20000, 70000] if big else [40, 300, 1500, 4000]))
     layout = ["bhtd", "bthd"][int(rng.integers(2))]
     paged = rng.random() < 0.4
     block_tokens = int(rng.choice([16, 32, 128]))
-    span = int(rng.choice([0, 0, 64, 192, 1024]))
-    top_k = int(rng.choice([1, 5, 64, 200, 300, 1500]))
+    span = int(rng.choice([0, 0, 0, 4096] if big else [0, 0, 64, 192, 1024]))
+    top_k = int(rng.choice([64, 256, 700] if big else [1, 5, 64, 200, 300, 1500]))
     what = "case %d: %s d=%d G=%d Hkv=%d B=%d n<=%d %s paged=%s/%d span=%d k=%d" % (
         case, dtype, d, group, hkv, batch, n_max, layout, paged, block_tokens, span, top_k)
     print(what, flush=True)
