@@ -202,7 +202,7 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
  *            head in ascending column order, padded with -1.
  *   m, l     DEVICE [n_groups][n_q_heads] fp32;  o  DEVICE [n_groups][n_q_heads][head_dim] fp32.
  *            An empty group yields (-inf, 0, 0).
- *   Reads the logits and the kept V rows only: one pass over the logits for top_k <= 256, about
+ *   Reads the logits and the kept V rows only: one pass over the logits for top_k <= 1024, about
  *   five for larger top_k or when the quick bound fails (sorted or masked rows).  Groups longer
  *   than 16384 tokens are selected in two stages (candidates per part, then among those).
  *   Logits must not contain NaN; -inf (masked tokens) is fine.

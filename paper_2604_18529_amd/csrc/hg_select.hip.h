@@ -22,22 +22,24 @@ namespace hg {
 // (the global top_k is a subset of their union, and candidates stay in ascending column order),
 // stage 2 runs steps 1-3 over the candidates.
 //
-// Fast path (FAST variants: workgroups of 8 waves, at most 32 x 512 elements each, top_k <= 256)
-// replacing steps 1-2.
-// The radix passes above pay for LDS atomics that nearly all land in the few bins of the common
-// exponents, and read the row five times.  Here the elements are read once into registers
-// (element e of thread t is column e*512 + t) and a cheap lower bound discards nearly all of them:
-//   a. every thread takes the maximum of its elements.  With j = ceil(keep / 8), each wave finds
-//      by bisection on the key bits (ballots only) the largest Tw that j of its 64 maxima reach;
-//      the smallest Tw of the 8 waves is reached by 8*j >= keep maxima, i.e. by at least `keep`
-//      distinct elements, so it is a lower bound of the keep-th largest element;
-//   b. the elements at or above the bound (a few hundred for unordered data) are written to LDS as
-//      64-bit words (key, ~index), whose order is "larger logit first, lower column first";
-//   c. the rank of a candidate is the number of candidates above it, counted by comparison, the
-//      list being split over as many threads per candidate as the workgroup has; ranks below
-//      `keep` are the kept set, which a second count puts in ascending column order.
+// Fast path (FAST variants: workgroups of 8 waves, at most 32 x 512 elements each, top_k <= 1024)
+// replacing steps 1-2.  The radix passes above pay for LDS atomics that nearly all land in the few
+// bins of the common exponents, and read the row five times.  Here the elements are read once into
+// registers (element e of thread t is column e*512 + t) and a cheap lower bound discards nearly
+// all of them:
+//   a. every thread takes 8 maxima, each over 4 of its elements.  With j = ceil(keep / 8), each
+//      wave finds by bisection on the key bits (ballots only) the largest Tw that j of its 512
+//      maxima reach; the smallest Tw of the 8 waves is reached by 8*j >= keep maxima, i.e. by at
+//      least `keep` distinct elements, so it is a lower bound of the keep-th largest element;
+//   b. the keys of the elements at or above the bound (about keep..2*keep for unordered data) go
+//      to LDS, in any order;
+//   c. radix select among those few keys, and only over the digits below the common prefix of
+//      the bound and the largest key: T and the number of ties to keep;
+//   d. the ordered compaction works on wave ballots straight from the registers: one count per
+//      (e, wave), one block scan over those 256 counts, and a kept element's slot follows from the
+//      counts before its wave row plus the kept lanes below it.
 // Inputs that defeat the bound (sorted rows, masked rows full of -inf, too many candidates) fall
-// back to the radix passes; the result is the same either way.
+// back to the radix passes over the row; the result is the same either way.
 
 __device__ __forceinline__ uint32_t order_key(float x)
 {
@@ -54,8 +56,9 @@ __device__ __forceinline__ float key_to_float(uint32_t k)
 constexpr int kSelectFastBlock = 512;                             // threads of the FAST variants (8 waves)
 constexpr int kSelectRegs = 32;                                   // elements per thread of the fast path
 constexpr int kSelectRegTokens = kSelectRegs * kSelectFastBlock;  // 16384
-constexpr int kSelectFastKeep = 256;                              // largest top_k of the fast path
-constexpr int kSelectCandCap = 1024;                              // most candidates the fast path ranks
+constexpr int kSelectSubMax = 8;                                  // maxima per thread that feed the lower bound
+constexpr int kSelectFastKeep = 1024;                             // largest top_k of the fast path
+constexpr int kSelectCandCap = 4096;                              // most candidates the fast path takes
 
 // Exclusive scan of v over the BLOCK threads of the workgroup; total receives the sum.
 template <int BLOCK>
@@ -82,136 +85,224 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *s
     return before + inc - v;
 }
 
+// Exclusive scan of v over the 64 lanes of a wave (no LDS, no barrier).
+__device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t v)
+{
+    const int lane = threadIdx.x & 63;
+    uint32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t t = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += t;
+    }
+    return inc - v;
+}
+
 // Fast path of steps 1-2 (see the top of the file).  row[0..n) with n <= kSelectRegTokens and
 // keep <= kSelectFastKeep.  On success the kept columns (ascending) and logits are in s_cols /
 // s_vals and the function returns true; otherwise nothing has been decided and the caller runs
-// the radix passes.  The return value is uniform; every thread of the workgroup must call it.
+// the radix passes over the row.  The return value is uniform; every thread of the workgroup
+// must call it.
 struct SelectFastLds {
-    unsigned long long cand[kSelectCandCap + 2];  // (key << 32) | ~index; zero words never outrank anything
-    unsigned long long kept[kSelectFastKeep + 2];  // the kept words by rank; read in pairs
-    uint32_t rank[kSelectCandCap];
-    uint32_t bound[kSelectFastBlock / 64];
+    uint32_t cand[kSelectCandCap];                           // keys of the elements at or above the bound
+    uint32_t cnt[kSelectRegs * (kSelectFastBlock / 64)];     // kept elements per (e, wave), then their scan
+    uint32_t hist[2][256];                                   // alternating between radix passes
+    uint32_t wave[kSelectFastBlock / 64];
+    uint32_t bcast[2];
     uint32_t count;
 };
 
 __device__ __forceinline__ bool select_fast(const float *__restrict__ row, int n, int keep, const int32_t *col_map,
                                             int col_base, SelectFastLds &f, int32_t *s_cols, float *s_vals)
 {
-    constexpr int NW = kSelectFastBlock / 64;
+    constexpr int BLOCK = kSelectFastBlock, NW = BLOCK / 64, R = kSelectRegs, G = kSelectSubMax;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    float x[kSelectRegs];
+    float x[R];
 #pragma unroll
-    for (int e = 0; e < kSelectRegs; ++e) {
-        const int i = e * kSelectFastBlock + tid;
+    for (int e = 0; e < R; ++e) {
+        const int i = e * BLOCK + tid;
         x[e] = row[i < n ? i : n - 1];
     }
-    // LDS set-up while the loads are in flight
-#pragma unroll
-    for (int c = tid; c < kSelectCandCap; c += kSelectFastBlock) {
-        f.cand[c] = 0ull;
-        f.rank[c] = 0u;
-    }
-    if (tid < 2) f.cand[kSelectCandCap + tid] = 0ull;
     if (tid == 0) f.count = 0u;
+    if (tid < 256) f.hist[0][tid] = 0u;
+    if (tid < R * NW) f.cnt[tid] = 0u;  // most (e, wave) rows will hold nothing at or above T
     // Slots past the end must not count as elements: they become -inf, which no bound admits (a
-    // bound at or below -inf sends the workgroup to the radix passes).  Without this the copies of
-    // the last element made by the clamp above would pose as per-thread maxima of their own.
-    float tm = -INFINITY;
+    // bound at or below -inf sends the workgroup to the radix passes over the row).
+    // G maxima per thread, each over the R / G elements e = g, g + G, ...
+    float tm[G];
 #pragma unroll
-    for (int e = 0; e < kSelectRegs; ++e) {
-        if (e * kSelectFastBlock + tid >= n) x[e] = -INFINITY;
-        tm = fmaxf(tm, x[e]);
+    for (int g = 0; g < G; ++g) tm[g] = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < R; ++e) {
+        if (e * BLOCK + tid >= n) x[e] = -INFINITY;
+        tm[e % G] = fmaxf(tm[e % G], x[e]);
     }
-    // a. bound
-    const uint32_t tmax = order_key(tm);
+    // a. bound: per wave, the largest Tw (upper 20 key bits) that `need` of its 64 * G maxima reach
+    uint32_t tk[G], top = 0u;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        tk[g] = order_key(tm[g]);
+        top = tk[g] > top ? tk[g] : top;
+    }
+    // (small keep: fewer, coarser maxima do -- 512 * g_use >= 4 * keep keeps the bound within the
+    // upper quarter of the maxima -- and the bisection below costs g_use ballots per step)
+    const int g_use = keep <= 128 ? 1 : keep <= 256 ? 2 : keep <= 512 ? 4 : 8;
+    static_assert(G == 8, "the folding below is written for 8 maxima per thread");
+    if (g_use <= 4) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) tk[g] = tk[g] > tk[g + 4] ? tk[g] : tk[g + 4];
+    }
+    if (g_use <= 2) {
+#pragma unroll
+        for (int g = 0; g < 2; ++g) tk[g] = tk[g] > tk[g + 2] ? tk[g] : tk[g + 2];
+    }
+    if (g_use <= 1) tk[0] = tk[0] > tk[1] ? tk[0] : tk[1];
     const int need = (keep + NW - 1) / NW;
     uint32_t tw = 0u;
     for (int b = 31; b >= 12; --b) {
         const uint32_t c = tw | (1u << b);
-        if (__builtin_popcountll(__builtin_amdgcn_ballot_w64(tmax >= c)) >= need) tw = c;
-    }
-    if (lane == 0) f.bound[wave] = tw;
-    __syncthreads();
-    uint32_t lower = f.bound[0];
+        int reach = 0;
 #pragma unroll
-    for (int w = 1; w < NW; ++w) lower = f.bound[w] < lower ? f.bound[w] : lower;
+        for (int g = 0; g < G; ++g)
+            if (g < g_use) reach += __builtin_popcountll(__builtin_amdgcn_ballot_w64(tk[g] >= c));
+        if (reach >= need) tw = c;
+    }
+    // the largest key of the workgroup bounds the digits the radix passes have to look at
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)top, step, 64);
+        top = o > top ? o : top;
+    }
+    if (lane == 0) {
+        f.wave[wave] = tw;
+        f.hist[1][wave] = top;  // (the second histogram is free until the second pass)
+    }
+    __syncthreads();
+    uint32_t lower = f.wave[0], hi = f.hist[1][0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+        lower = f.wave[w] < lower ? f.wave[w] : lower;
+        hi = f.hist[1][w] > hi ? f.hist[1][w] : hi;
+    }
     if (lower <= order_key(-INFINITY)) return false;  // masked or nearly empty rows: no useful bound
     const float lower_f = key_to_float(lower);
 
-    // b. candidates -> LDS, any order: count, one counter bump per wave, write
+    // b. keys of the candidates -> LDS, any order: count, one counter bump per wave, write
     uint32_t mine = 0;
 #pragma unroll
-    for (int e = 0; e < kSelectRegs; ++e) mine += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(x[e] >= lower_f));
+    for (int e = 0; e < R; ++e) mine += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(x[e] >= lower_f));
     uint32_t at = 0;
     if (lane == 0 && mine) at = atomicAdd(&f.count, mine);
     at = __builtin_amdgcn_readfirstlane(at);
+    const uint64_t below = ((uint64_t)1 << lane) - 1;
     if (mine) {
-        const uint64_t below = ((uint64_t)1 << lane) - 1;
 #pragma unroll
-        for (int e = 0; e < kSelectRegs; ++e) {
+        for (int e = 0; e < R; ++e) {
             const bool c = x[e] >= lower_f;
             const uint64_t bc = __builtin_amdgcn_ballot_w64(c);
             if (bc) {
                 const uint32_t pos = at + (uint32_t)__builtin_popcountll(bc & below);
-                if (c && pos < (uint32_t)kSelectCandCap)
-                    f.cand[pos] = ((unsigned long long)order_key(x[e]) << 32) | (uint32_t)~(uint32_t)(e * kSelectFastBlock + tid);
+                if (c && pos < (uint32_t)kSelectCandCap) f.cand[pos] = order_key(x[e]);
                 at += (uint32_t)__builtin_popcountll(bc);
             }
         }
     }
-    __syncthreads();
+    __syncthreads();  // (also: every thread has read f.hist[1][0..NW) before a pass clears it)
     // At least `keep` candidates exist: the maxima that reach the bound are distinct elements.
     const int nc = (int)f.count;
     if (nc > kSelectCandCap || nc < keep) return false;  // (nc < keep: only with NaN logits)
 
-    // c. ranks.  Few candidates: candidate c = tid % ncr is counted by split tid / ncr over its
-    //    share of the list (partial counts meet in f.rank); many: one thread per candidate or two.
-    {
-        const int ncr = (nc + 63) & ~63;  // whole waves per split: the list reads broadcast
-        if (ncr <= kSelectFastBlock) {
-            const int splits = kSelectFastBlock / ncr;
-            const int len = ((nc + splits - 1) / splits + 1) & ~1;  // even: two words per LDS read
-            const int sp = tid / ncr, c = tid - sp * ncr;
-            if (sp < splits && c < nc) {
-                const unsigned long long me = f.cand[c];
-                const int j0 = sp * len, j1 = j0 + len < nc ? j0 + len : nc;  // reads past nc see zero words
-                uint32_t r = 0;
-                for (int j = j0; j < j1; j += 2) {
-                    const unsigned long long a0 = f.cand[j], a1 = f.cand[j + 1];
-                    r += (a0 > me ? 1u : 0u) + (a1 > me ? 1u : 0u);
-                }
-                atomicAdd(&f.rank[c], r);
+    // c. radix select among the candidates: T = key of the keep-th largest, k_eq = how many keys
+    //    equal to T are kept.  Every candidate lies in [lower, hi]: the bits above the highest bit
+    //    in which those two differ are common to all and need no pass.
+    uint32_t T = hi, k_eq = (uint32_t)keep;
+    if (hi != lower) {
+        const int top_bit = 31 - __builtin_clz(hi ^ lower);
+        int shift = top_bit & ~7;
+        uint32_t mask = shift == 24 ? 0u : ~0u << (shift + 8);
+        uint32_t prefix = hi & mask, krem = (uint32_t)keep;
+        // One pass = two barriers: all add to the current histogram | wave 0 scans its 256 bins from
+        // the top (4 per lane) and publishes the digit while the other waves clear the histogram
+        // of the next pass | all read the digit.
+        for (int cur = 0; shift >= 0; shift -= 8, cur ^= 1) {
+            for (int c = tid; c < nc; c += BLOCK) {
+                const uint32_t u = f.cand[c];
+                if ((u & mask) == prefix) atomicAdd(&f.hist[cur][(u >> shift) & 255u], 1u);
             }
-        } else {
-            for (int c = tid; c < nc; c += kSelectFastBlock) {
-                const unsigned long long me = f.cand[c];
-                uint32_t r = 0;
-                for (int j = 0; j < nc; j += 2) {
-                    const unsigned long long a0 = f.cand[j], a1 = f.cand[j + 1];
-                    r += (a0 > me ? 1u : 0u) + (a1 > me ? 1u : 0u);
+            __syncthreads();
+            if (wave == 0) {
+                uint32_t c4[4], mine4 = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    c4[j] = f.hist[cur][255 - (4 * lane + j)];
+                    mine4 += c4[j];
                 }
-                f.rank[c] = r;
+                uint32_t above = wave_exclusive_scan(mine4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (above < krem && above + c4[j] >= krem) {
+                        f.bcast[0] = prefix | ((uint32_t)(255 - (4 * lane + j)) << shift);
+                        f.bcast[1] = krem - above;
+                    }
+                    above += c4[j];
+                }
+            } else if (tid - 64 < 256) {
+                f.hist[cur ^ 1][tid - 64] = 0u;
             }
+            __syncthreads();
+            prefix = f.bcast[0];
+            krem = f.bcast[1];
+            mask |= 0xffu << shift;
+        }
+        T = prefix;
+        k_eq = krem;
+    }
+
+    // d. ordered compaction from the registers: kept elements per (e, wave), one scan over those
+    //    counts, then a kept element's slot = kept before its wave row + kept lanes below it.
+    //    Keep every x > T and the first k_eq (in column order) x == T.
+    const float T_f = key_to_float(T);
+#pragma unroll
+    for (int e = 0; e < R; ++e) {
+        if (__builtin_amdgcn_ballot_w64(x[e] >= T_f)) {
+            const uint64_t bg = __builtin_amdgcn_ballot_w64(x[e] > T_f);
+            const uint64_t be = __builtin_amdgcn_ballot_w64(x[e] == T_f);
+            if (lane == 0) f.cnt[e * NW + wave] = (uint32_t)__builtin_popcountll(bg) | ((uint32_t)__builtin_popcountll(be) << 16);
         }
     }
     __syncthreads();
-    for (int c = tid; c < nc; c += kSelectFastBlock) {
-        const uint32_t r = f.rank[c];
-        if (r < (uint32_t)keep) f.kept[r] = f.cand[c];
+    if (wave == 0) {  // exclusive scan of the R * NW = 256 counts, 4 per lane
+        static_assert(R * NW == 256, "four counts per lane of one wave");
+        uint32_t c4[4], mine4 = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            c4[j] = f.cnt[4 * lane + j];
+            mine4 += c4[j];
+        }
+        uint32_t before = wave_exclusive_scan(mine4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            f.cnt[4 * lane + j] = before;
+            before += c4[j];
+        }
     }
     __syncthreads();
-    // kept set in ascending column order: position = number of kept entries with a lower index
-    if (tid < keep) {
-        const unsigned long long me = f.kept[tid];
-        const uint32_t inv = (uint32_t)me;  // ~index: a lower index is a larger value
-        uint32_t pos = 0;
-        for (int j = 0; j < keep; j += 2) {
-            const uint32_t i0 = (uint32_t)f.kept[j], i1 = (uint32_t)f.kept[j + 1];
-            pos += (i0 > inv ? 1u : 0u) + ((j + 1 < keep && i1 > inv) ? 1u : 0u);
+#pragma unroll
+    for (int e = 0; e < R; ++e) {
+        if (__builtin_amdgcn_ballot_w64(x[e] >= T_f)) {
+            const bool gt = x[e] > T_f, eq = x[e] == T_f;
+            const uint64_t bg = __builtin_amdgcn_ballot_w64(gt);
+            const uint64_t be = __builtin_amdgcn_ballot_w64(eq);
+            const uint32_t base = f.cnt[e * NW + wave];
+            const uint32_t gt_before = (base & 0xffffu) + (uint32_t)__builtin_popcountll(bg & below);
+            const uint32_t eq_before = (base >> 16) + (uint32_t)__builtin_popcountll(be & below);
+            if (gt || (eq && eq_before < k_eq)) {
+                const uint32_t pos = gt_before + (eq_before < k_eq ? eq_before : k_eq);
+                const int i = e * BLOCK + tid;
+                s_cols[pos] = col_map ? col_map[i] : col_base + i;
+                s_vals[pos] = x[e];
+            }
         }
-        const int i = (int)~inv;
-        s_cols[pos] = col_map ? col_map[i] : col_base + i;
-        s_vals[pos] = key_to_float((uint32_t)(me >> 32));
     }
     __syncthreads();
     return true;

@@ -162,7 +162,7 @@ def test_adversarial_orders(order, n):
         rng = np.random.default_rng(65)
         rows = [(rng.random(n) < 0.01).astype(np.float32), (rng.random(n) < 0.9).astype(np.float32) - 2]
     lg = np.ascontiguousarray(np.stack(rows).astype(np.float32))
-    for top_k in (3, 128, 256, 2000):
+    for top_k in (3, 128, 256, 1000, 2000):
         _check_select(w, ranges, gp, lg, top_k, "%s n=%d k=%d" % (order, n, top_k))
 
 
@@ -223,11 +223,11 @@ def test_bad_arguments():
         assert ei.value.status == -2
 
 
-@pytest.mark.parametrize("top_k", [1024, 2048])
+@pytest.mark.parametrize("top_k", [128, 1024, 2048])
 def test_full_size_million_token_group(top_k):
     """Benchmark shape: 64 query heads over 8 KV heads, one group of 1,048,576 offloaded tokens;
-    sampled heads against the oracle on seeded logits (top_k beyond the fast path: the radix
-    passes run in both stages, the final one over 64 x top_k candidates)."""
+    sampled heads against the oracle on seeded logits.  top_k = 128: fast path in both stages;
+    1024: fast first stage, radix passes over the 64 x 1024 candidates; 2048: radix passes in both."""
     spec = W.WORKLOADS[4]
     w = W.make_workload(spec, DEV)
     n = int(w.seq_lens[0])
