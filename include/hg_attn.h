@@ -204,7 +204,7 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
  *            An empty group yields (-inf, 0, 0).
  *   Reads the logits and the kept V rows only: one pass over the logits for top_k <= 1024, about
  *   five for larger top_k or when the quick bound fails (sorted or masked rows).  Groups longer
- *   than 16384 tokens are selected in two stages (candidates per part, then among those).
+ *   than 16384 tokens are selected in two or three stages (candidates per part, then among those).
  *   Logits must not contain NaN; -inf (masked tokens) is fine.
  */
 hg_status hg_attn_select_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges,

@@ -448,9 +448,10 @@ constexpr int kSelectMaxParts = 64;
 // arguments), then the candidate values and columns of the two-stage path.
 struct SelectPlan {
     int32_t parts = 1;
+    int32_t parts2 = 0;      // > 0: a middle stage reduces parts * top_k candidates to parts2 * top_k
     bool fast_first = true;  // fast path possible in the direct / candidates launch: top_k and elements per workgroup fit
     bool fast_final = true;  // the same for the launch that selects among the candidates
-    size_t off_tab = 0, off_groups = 0, off_cand_val = 0, off_cand_col = 0, total = 0;
+    size_t off_tab = 0, off_groups = 0, off_cand_val = 0, off_cand_col = 0, off_cand2_val = 0, off_cand2_col = 0, total = 0;
 };
 
 void select_parts(const hg_range *ranges, const int32_t *group_ptr, int32_t n_groups, int32_t top_k, SelectPlan &sp)
@@ -463,7 +464,13 @@ void select_parts(const hg_range *ranges, const int32_t *group_ptr, int32_t n_gr
     }
     sp.parts = (int32_t)std::min<int64_t>(kSelectMaxParts, std::max<int64_t>(1, (longest + kSelectRegTokens - 1) / kSelectRegTokens));
     sp.fast_first = top_k <= kSelectFastKeep && (longest + sp.parts - 1) / sp.parts <= kSelectRegTokens;
-    sp.fast_final = top_k <= kSelectFastKeep && (int64_t)sp.parts * top_k <= kSelectRegTokens;
+    // More candidates than one workgroup of the fast path holds: a middle stage brings them down to
+    // parts2 * top_k (at most 4 * 1024), so that no stage has to run the slow passes over them.
+    const int64_t cands = (int64_t)sp.parts * top_k;
+    sp.parts2 = 0;
+    if (sp.parts > 1 && top_k <= kSelectFastKeep && cands > kSelectRegTokens)
+        sp.parts2 = (int32_t)((cands + kSelectRegTokens - 1) / kSelectRegTokens);
+    sp.fast_final = top_k <= kSelectFastKeep && (sp.parts2 ? (int64_t)sp.parts2 * top_k : cands) <= kSelectRegTokens;
 }
 
 SelectPlan plan_select(const hg_range *ranges, int32_t n_ranges, const int32_t *group_ptr, int32_t n_groups,
@@ -482,6 +489,13 @@ SelectPlan plan_select(const hg_range *ranges, int32_t n_ranges, const int32_t *
         off += align_up(cand);
         sp.off_cand_col = off;
         off += align_up(cand);
+        if (sp.parts2) {
+            const size_t cand2 = (size_t)n_groups * (size_t)n_q_heads * (size_t)sp.parts2 * (size_t)top_k * 4;
+            sp.off_cand2_val = off;
+            off += align_up(cand2);
+            sp.off_cand2_col = off;
+            off += align_up(cand2);
+        }
     }
     sp.total = off;
     return sp;
@@ -875,6 +889,14 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
     launch_select<kSelectCandidates>(desc, sa, dim3((unsigned)(n_groups * sp.parts), (unsigned)desc->n_q_heads), sp.fast_first, stream);
     st = launch_status("selection kernel (candidates)");
     if (st != HG_OK) return st;
+    if (sp.parts2) {
+        sa.parts2 = sp.parts2;
+        sa.cand2_val = reinterpret_cast<float *>(ws + sp.off_cand2_val);
+        sa.cand2_col = reinterpret_cast<int32_t *>(ws + sp.off_cand2_col);
+        launch_select<kSelectMidCands>(desc, sa, dim3((unsigned)(n_groups * sp.parts2), (unsigned)desc->n_q_heads), true, stream);
+        st = launch_status("selection kernel (middle stage)");
+        if (st != HG_OK) return st;
+    }
     launch_select<kSelectFromCands>(desc, sa, grid, sp.fast_final, stream);
     return launch_status("selection kernel (final)");
 }

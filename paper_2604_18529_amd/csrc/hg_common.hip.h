@@ -170,6 +170,11 @@ struct SelectArgs {
     int32_t parts;
     float *cand_val;      // [n_groups][Hq][parts][top_k]
     int32_t *cand_col;
+    // when parts * top_k is more than one workgroup selects from quickly, a middle stage reduces
+    // the candidates of each (group, head) to parts2 * top_k (0: no middle stage)
+    int32_t parts2, pad2;
+    float *cand2_val;     // [n_groups][Hq][parts2][top_k]
+    int32_t *cand2_col;
     PageMap pages;        // table == nullptr: contiguous cache
     GroupTable groups;
     RangeTable tab;
@@ -177,7 +182,8 @@ struct SelectArgs {
 
 constexpr int kSelectDirect = 0;      // one workgroup selects from the group's logits row
 constexpr int kSelectCandidates = 1;  // stage 1: per part, write its top_k candidates
-constexpr int kSelectFromCands = 2;   // stage 2: select among the parts' candidates
+constexpr int kSelectFromCands = 2;   // last stage: select among the candidates
+constexpr int kSelectMidCands = 3;    // middle stage: candidates of a chunk of the candidates
 
 struct RangeChunk {
     RangeEntry e[kUploadRanges];

@@ -325,8 +325,10 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
     __shared__ __align__(16) unsigned char s_fast_raw[FAST ? sizeof(SelectFastLds) : 16];
 
     const int tid = threadIdx.x, h = blockIdx.y;
-    const int gi = STAGE == kSelectCandidates ? blockIdx.x / a.parts : blockIdx.x;
-    const int part = STAGE == kSelectCandidates ? blockIdx.x - gi * a.parts : 0;
+    constexpr bool kEmits = STAGE == kSelectCandidates || STAGE == kSelectMidCands;  // writes candidates, no triple
+    const int n_parts = STAGE == kSelectCandidates ? a.parts : STAGE == kSelectMidCands ? a.parts2 : 1;
+    const int gi = blockIdx.x / n_parts;
+    const int part = blockIdx.x - gi * n_parts;
     const int lane = tid & 63, wave = tid >> 6;
     const int r0 = group_entry(a.groups, gi), r1 = group_entry(a.groups, gi + 1);
     const int c0 = table_entry(a.tab, r0).pre, c1 = table_entry(a.tab, r1).pre;
@@ -350,20 +352,39 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
         n = e - b;
         col_base = b;
         keep = n < a.top_k ? n : a.top_k;
-    } else {
-        const int64_t base = gh * a.parts * (int64_t)a.top_k;
+    } else if constexpr (STAGE == kSelectMidCands) {
+        // chunk `part` of the group's parts * top_k candidates (pad entries included: they sort
+        // below everything and are never kept ahead of a real entry)
+        const int total = c1 > c0 ? a.parts * a.top_k : 0;
+        const int per = (total + a.parts2 - 1) / a.parts2;
+        const int b = part * per < total ? part * per : total;
+        const int e = b + per < total ? b + per : total;
+        const int64_t base = gh * a.parts * (int64_t)a.top_k + b;
         row = a.cand_val + base;
         col_map = a.cand_col + base;
-        n = c1 > c0 ? a.parts * a.top_k : 0;  // padded with -inf entries, which sort below every logit
+        n = e - b;
+        keep = n < a.top_k ? n : a.top_k;
+    } else {
+        const bool mid = a.parts2 > 0;
+        const int np = mid ? a.parts2 : a.parts;
+        const int64_t base = gh * np * (int64_t)a.top_k;
+        row = (mid ? a.cand2_val : a.cand_val) + base;
+        col_map = (mid ? a.cand2_col : a.cand_col) + base;
+        n = c1 > c0 ? np * a.top_k : 0;  // padded with entries that sort below every logit
         keep = c1 - c0 < a.top_k ? c1 - c0 : a.top_k;
     }
 
-    if constexpr (STAGE == kSelectCandidates) {
-        // pad the part's candidate slots; the kept ones are overwritten below
-        const int64_t base = (gh * a.parts + part) * (int64_t)a.top_k;
+    // where a candidates stage writes
+    float *const out_val = STAGE == kSelectMidCands ? a.cand2_val : a.cand_val;
+    int32_t *const out_col = STAGE == kSelectMidCands ? a.cand2_col : a.cand_col;
+    if constexpr (kEmits) {
+        // pad the part's candidate slots; the kept ones are overwritten below.  A pad is the NaN
+        // with every bit set: its key is 0, below -inf, and it fails every float comparison, so no
+        // stage ever prefers it to a real logit, masked (-inf) ones included.
+        const int64_t base = (gh * n_parts + part) * (int64_t)a.top_k;
         for (int j = tid + keep; j < a.top_k; j += BLOCK) {
-            a.cand_val[base + j] = -INFINITY;
-            a.cand_col[base + j] = 0;
+            out_val[base + j] = __uint_as_float(0xffffffffu);
+            out_col[base + j] = 0;
         }
         if (n == 0) return;
     } else {
@@ -456,11 +477,11 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
         __syncthreads();
     }
 
-    if constexpr (STAGE == kSelectCandidates) {
-        const int64_t base = (gh * a.parts + part) * (int64_t)a.top_k;
+    if constexpr (kEmits) {
+        const int64_t base = (gh * n_parts + part) * (int64_t)a.top_k;
         for (int j = tid; j < keep; j += BLOCK) {
-            a.cand_val[base + j] = s_vals[j];
-            a.cand_col[base + j] = s_cols[j];
+            out_val[base + j] = s_vals[j];
+            out_col[base + j] = s_cols[j];
         }
         return;
     }

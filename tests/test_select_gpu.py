@@ -181,6 +181,24 @@ def test_masked_logits(n, finite):
     _check_select(w, ranges, gp, lg, 128, "masked n=%d finite=%d" % (n, finite))
 
 
+def test_middle_stage_and_pads_below_masked_logits():
+    """19 parts x top_k 1000 candidates are more than one workgroup takes at once: a middle stage
+    reduces them first.  The second group is tiny and mostly masked: all its tokens are kept, the
+    -inf ones included, although its parts are nearly all padding."""
+    n0, n1 = 300_000, 50
+    spec = W.WorkloadSpec("selmid", 2, 2, 1, 64, "f16", n1, n0, "none", seed=76)
+    w = W.make_workload(spec, DEV)
+    w.seq_lens[:] = [n0, n1]
+    ranges, gp = [(0, 0, 200_000), (0, 200_000, n0), (1, 0, n1)], [0, 2, 3]
+    rng = np.random.default_rng(77)
+    lg = (np.round(rng.standard_normal((2, n0 + n1)) * 16) / 16).astype(np.float32)
+    lg[:, n0:] = -np.inf
+    lg[:, n0 + rng.choice(n1, 10, replace=False)] = 0.5
+    lg[1, :n0] = np.sort(lg[1, :n0])  # sorted row: every kept token in the last parts
+    sel, _, _, _ = _check_select(w, ranges, gp, lg, 1000, "middle stage")
+    assert to_np(sel[1, 0][:n1]).tolist() == list(range(n1))
+
+
 def test_signed_zeros_tie():
     """-0.0 and +0.0 are the same logit: at a threshold of zero the lower column wins whatever the
     sign bits say."""
