@@ -319,7 +319,29 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     // logits come straight from memory in A-operand order (lane: head n, tokens tb + 8rg .. + 7);
     // they lie in (0, 1], so the fp16 head + remainder keeps them to ~22 bits.  The division by the
     // global sum happens once, in the reduce kernel.
-    auto concat_block = [&](int tb, int tb_next, hg_u32x4(&vreg)[8]) __attribute__((always_inline)) {
+    // The 8 logits a lane needs for block tb are requested with the V rows of that block: two
+    // 16-byte loads when the block is full (they need 4-byte alignment only), clamped single loads
+    // in the last block of a segment.  The branch is wave-uniform, so neither side has to wait for
+    // its loads before the join.
+    typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+    auto load_logits = [&](int tb, float(&sv)[8]) __attribute__((always_inline)) {
+        if (tb + kGqaBlockTokens <= t1) {
+            const f4u lo4 = *reinterpret_cast<const f4u *>(lrow + tb + 8 * rg);
+            const f4u hi4 = *reinterpret_cast<const f4u *>(lrow + tb + 8 * rg + 4);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                sv[x] = lo4[x];
+                sv[4 + x] = hi4[x];
+            }
+        } else {
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                const int tok = tb + 8 * rg + x;
+                sv[x] = lrow[tok < t1 ? tok : t1 - 1];
+            }
+        }
+    };
+    auto concat_block = [&](int tb, int tb_next, hg_u32x4(&vreg)[8], float(&sv)[8]) __attribute__((always_inline)) {
         typedef _Float16 h2 __attribute__((ext_vector_type(2)));
         hg_u32x4 hi_raw, lo_raw;
 #pragma unroll
@@ -328,8 +350,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
                 const int tok = tb + 8 * rg + 2 * jj + x;
-                const float sv = lrow[tok < t1 ? tok : t1 - 1];  // unconditional load; masked by a product
-                pj[x] = fast_exp2(sv * kLog2e - gmax) * ((tok < t1 && n < nh) ? 1.f : 0.f);
+                pj[x] = fast_exp2(sv[2 * jj + x] * kLog2e - gmax) * ((tok < t1 && n < nh) ? 1.f : 0.f);
             }
             const _Float16 h0f = (_Float16)pj[0], h1f = (_Float16)pj[1];
             const _Float16 l0f = (_Float16)(pj[0] - (float)h0f), l1f = (_Float16)(pj[1] - (float)h1f);
@@ -350,6 +371,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         }
         if (tb_next < t1) {
             load_v(tb_next, vreg, pg1);
+            load_logits(tb_next, sv);
             if constexpr (PAGED) {
                 if (tb_next + kGqaWaves * kGqaBlockTokens < t1) lookup(tb_next + kGqaWaves * kGqaBlockTokens, pg1);
             }
@@ -379,11 +401,14 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             // Paged: pg1 always holds the pages of the next block to be loaded; the look-up for the
             // block after it goes out right behind the loads and has one block of compute to land.
             hg_u32x4 ra[8], rb[8];
-            auto load_one = [&](int t, hg_u32x4(&reg)[8]) __attribute__((always_inline)) {
-                if constexpr (MODE == kModeLogits)
+            float sa[8], sb[8];  // concat mode: the logits that go with ra, rb
+            auto load_one = [&](int t, hg_u32x4(&reg)[8], float(&sv)[8]) __attribute__((always_inline)) {
+                if constexpr (MODE == kModeLogits) {
                     load_k(t, reg, pg1);
-                else
+                } else {
                     load_v(t, reg, pg1);
+                    load_logits(t, sv);
+                }
                 if constexpr (PAGED) {
                     if (t + kStride < t1) lookup(t + kStride, pg1);
                 }
@@ -391,19 +416,19 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             if constexpr (PAGED) {
                 if (tb < t1) lookup(tb, pg1);
             }
-            auto compute_one = [&](int t, hg_u32x4(&reg)[8]) __attribute__((always_inline)) {
+            auto compute_one = [&](int t, hg_u32x4(&reg)[8], float(&sv)[8]) __attribute__((always_inline)) {
                 if constexpr (MODE == kModeLogits)
                     compute_block(t, t + 2 * kStride, reg, reg);
                 else
-                    concat_block(t, t + 2 * kStride, reg);
+                    concat_block(t, t + 2 * kStride, reg, sv);
             };
-            if (tb < t1) load_one(tb, ra);
-            if (tb + kStride < t1) load_one(tb + kStride, rb);
+            if (tb < t1) load_one(tb, ra, sa);
+            if (tb + kStride < t1) load_one(tb + kStride, rb, sb);
             while (tb < t1) {
-                compute_one(tb, ra);
+                compute_one(tb, ra, sa);
                 tb += kStride;
                 if (tb >= t1) break;
-                compute_one(tb, rb);
+                compute_one(tb, rb, sb);
                 tb += kStride;
             }
         }

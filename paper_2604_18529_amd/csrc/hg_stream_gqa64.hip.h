@@ -272,7 +272,29 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 
     // Concat mode block: numerators exp(s - M) of the one softmax over the concatenated logits,
     // read in A-operand order (lane: head n, tokens tb + 8rg .. + 7) as in the head_dim 128 kernel.
-    auto concat_block = [&](int tb, int tb_next, hg_u32x4(&vreg)[4]) __attribute__((always_inline)) {
+    // The 8 logits a lane needs for block tb (head n, tokens tb + 8rg .. + 7) are requested with the
+    // V rows of that block, two 16-byte loads when the block is full (they need 4-byte alignment
+    // only), clamped single loads in the last block of a segment.  The branch is wave-uniform, so
+    // neither side has to wait for its loads before the join.
+    typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+    auto load_logits = [&](int tb, float(&sv)[8]) __attribute__((always_inline)) {
+        if (tb + kGqaBlockTokens <= t1) {
+            const f4u lo4 = *reinterpret_cast<const f4u *>(lrow + tb + 8 * rg);
+            const f4u hi4 = *reinterpret_cast<const f4u *>(lrow + tb + 8 * rg + 4);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                sv[x] = lo4[x];
+                sv[4 + x] = hi4[x];
+            }
+        } else {
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                const int tok = tb + 8 * rg + x;
+                sv[x] = lrow[tok < t1 ? tok : t1 - 1];
+            }
+        }
+    };
+    auto concat_block = [&](int tb, int tb_next, hg_u32x4(&vreg)[4], float(&sv)[8]) __attribute__((always_inline)) {
         typedef _Float16 h2 __attribute__((ext_vector_type(2)));
         hg_u32x4 hi_raw, lo_raw;
 #pragma unroll
@@ -281,8 +303,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
                 const int tok = tb + 8 * rg + 2 * jj + x;
-                const float sv = lrow[tok < t1 ? tok : t1 - 1];  // unconditional load; masked by a product
-                pj[x] = fast_exp2(sv * kLog2e - gmax) * ((tok < t1 && n < nh) ? 1.f : 0.f);
+                pj[x] = fast_exp2(sv[2 * jj + x] * kLog2e - gmax) * ((tok < t1 && n < nh) ? 1.f : 0.f);
             }
             const _Float16 h0f = (_Float16)pj[0], h1f = (_Float16)pj[1];
             const _Float16 l0f = (_Float16)(pj[0] - (float)h0f), l1f = (_Float16)(pj[1] - (float)h1f);
@@ -298,6 +319,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         }
         if (tb_next < t1) {
             load_rows(vbase, tb_next, vreg, pg1);
+            load_logits(tb_next, sv);
             if constexpr (PAGED) {
                 if (tb_next + kGqaWaves * kGqaBlockTokens < t1) lookup(tb_next + kGqaWaves * kGqaBlockTokens, pg1);
             }
@@ -327,8 +349,10 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             // block after it goes out right behind the loads.
             hg_u32x4 r0[4], r1[4], r2[4], r3[4];
             const char *base = MODE == kModeLogits ? kbase : vbase;
-            auto load_one = [&](int t, hg_u32x4(&reg)[4]) __attribute__((always_inline)) {
+            float s0[8], s1[8], s2[8], s3[8];  // concat mode: the logits that go with r0..r3
+            auto load_one = [&](int t, hg_u32x4(&reg)[4], float(&sv)[8]) __attribute__((always_inline)) {
                 load_rows(base, t, reg, pg1);
+                if constexpr (MODE == kModeConcat) load_logits(t, sv);
                 if constexpr (PAGED) {
                     if (t + kStride < t1) lookup(t + kStride, pg1);
                 }
@@ -336,27 +360,27 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             if constexpr (PAGED) {
                 if (tb < t1) lookup(tb, pg1);
             }
-            auto compute_one = [&](int t, hg_u32x4(&reg)[4]) __attribute__((always_inline)) {
+            auto compute_one = [&](int t, hg_u32x4(&reg)[4], float(&sv)[8]) __attribute__((always_inline)) {
                 if constexpr (MODE == kModeLogits)
                     compute_block(t, t + 4 * kStride, reg, reg);
                 else
-                    concat_block(t, t + 4 * kStride, reg);
+                    concat_block(t, t + 4 * kStride, reg, sv);
             };
-            if (tb < t1) load_one(tb, r0);
-            if (tb + kStride < t1) load_one(tb + kStride, r1);
-            if (tb + 2 * kStride < t1) load_one(tb + 2 * kStride, r2);
-            if (tb + 3 * kStride < t1) load_one(tb + 3 * kStride, r3);
+            if (tb < t1) load_one(tb, r0, s0);
+            if (tb + kStride < t1) load_one(tb + kStride, r1, s1);
+            if (tb + 2 * kStride < t1) load_one(tb + 2 * kStride, r2, s2);
+            if (tb + 3 * kStride < t1) load_one(tb + 3 * kStride, r3, s3);
             while (tb < t1) {
-                compute_one(tb, r0);
+                compute_one(tb, r0, s0);
                 tb += kStride;
                 if (tb >= t1) break;
-                compute_one(tb, r1);
+                compute_one(tb, r1, s1);
                 tb += kStride;
                 if (tb >= t1) break;
-                compute_one(tb, r2);
+                compute_one(tb, r2, s2);
                 tb += kStride;
                 if (tb >= t1) break;
-                compute_one(tb, r3);
+                compute_one(tb, r3, s3);
                 tb += kStride;
             }
         }
