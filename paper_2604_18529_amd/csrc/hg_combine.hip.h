@@ -142,9 +142,33 @@ __global__ __launch_bounds__(256) void hg_concat_stats_kernel(const ConcatStatsA
     const int e = b + per < c1 ? b + per : c1;
     const float *row = a.logits + (int64_t)h * a.ltok;
 
-    // one pass: every thread folds groups of four logits into a running (max, sum) pair
+    // One pass: every thread folds its logits into a running (max, sum) pair.  Whole chunks of
+    // 4096 logits go four 16-byte loads per thread at a time (each load instruction of a wave is
+    // one contiguous KiB; the loads need 4-byte alignment only), sixteen values per rescale; the
+    // rest of the slice goes in groups of four with clamped single loads.
+    typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
     float mx = kNegBig, lt = 0.f;
-    for (int i = b + 4 * (int)threadIdx.x; i < e; i += 4 * 256) {
+    int i0 = b;
+    for (; i0 + 4096 <= e; i0 += 4096) {
+        f4u x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x[u] = *reinterpret_cast<const f4u *>(row + i0 + 4 * ((int)threadIdx.x + 256 * u));
+        float mn = mx;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                x[u][j] *= kLog2e;
+                mn = fmaxf(mn, x[u][j]);
+            }
+        }
+        float sum = 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) sum += (fast_exp2(x[u][0] - mn) + fast_exp2(x[u][1] - mn)) + (fast_exp2(x[u][2] - mn) + fast_exp2(x[u][3] - mn));
+        lt = lt * fast_exp2(mx - mn) + sum;
+        mx = mn;
+    }
+    for (int i = i0 + 4 * (int)threadIdx.x; i < e; i += 4 * 256) {
         float x[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) x[j] = row[i + j < e ? i + j : e - 1] * kLog2e * 1.f;
