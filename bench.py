@@ -168,9 +168,10 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W, routes=T
         for bt in (16, 256):
             kp, vp, table = W.make_paged(w, bt, seed=1)
             pdesc, pkeep = hg.make_desc(w.q, kp, vp, w.seq_lens, w.scale, table)
+            pws = torch.empty(max(binding.hg_attn_partial_workspace_size(pdesc, packed), 256), dtype=torch.uint8, device=dev)
 
             def paged_step():
-                hg.hg_attn_partial(w.q, kp, vp, w.seq_lens, packed, w.scale, m=m, l=l, o=o, workspace=ws, desc=pdesc)
+                hg.hg_attn_partial(w.q, kp, vp, w.seq_lens, packed, w.scale, m=m, l=l, o=o, workspace=pws, desc=pdesc)
                 hg.hg_attn_merge(m, l, o, w.group_ptr, out=out, lse=lse)
 
             pms, _ = _time_steps(paged_step, max(steps // 4, 1), max(warmup // 4, 1), torch)

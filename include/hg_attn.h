@@ -81,6 +81,7 @@ typedef enum hg_dtype { HG_F16 = 0, HG_F32 = 1 } hg_dtype;
  *   k, v        element (block p, head g, row r, c) is at base + p*stride_b + g*stride_h + r*stride_t + c:
  *               stride_b is the distance between physical blocks.  Table entries are not checked
  *               (they are device memory): every entry a valid token maps to must be a valid block.
+ *               Limits of a paged descriptor: block stride below 4 GiB, row stride below 16 MiB.
  *   Every call that takes a descriptor accepts a paged one.
  */
 typedef struct hg_attn_desc {

@@ -78,6 +78,8 @@ hg_status check_desc(const hg_attn_desc *d)
         const int32_t bt = d->block_tokens;
         if (bt < 16 || bt > 65536 || (bt & (bt - 1))) return HG_ERR_SHAPE;
         if (d->max_blocks < 1) return HG_ERR_SHAPE;
+        // the kernels form paged addresses with a 32-bit block stride and a 24-bit row stride
+        if (d->stride_b * es >= (int64_t)1 << 32 || d->stride_t * es >= (int64_t)1 << 24) return HG_ERR_SHAPE;
         for (int32_t b = 0; b < d->batch; ++b)
             if (((int64_t)d->seq_lens[b] + bt - 1) / bt > d->max_blocks) return HG_ERR_RANGE;
     }
@@ -116,10 +118,10 @@ int32_t pick_group_tile(const hg_attn_desc *d)
 // from as few waves as possible gives the highest HBM read rate (more resident waves lose 4-5 %),
 // and the launch ends without a tail.  Short inputs get 64-token spans so that they still spread
 // over the chip.
-int32_t pick_span(int64_t total, bool gqa)
+int32_t pick_span(int64_t total, bool gqa, int per_cu_factor)
 {
     if (g_forced_span_tokens) return g_forced_span_tokens;
-    const int64_t target = (int64_t)(gqa ? kGqaWorkgroupsPerCu : kValuWorkgroupsPerCu) * compute_units();
+    const int64_t target = (int64_t)(gqa ? kGqaWorkgroupsPerCu : kValuWorkgroupsPerCu) * per_cu_factor * compute_units();
     int64_t t = (total + target - 1) / target;
     t = (t + 63) / 64 * 64;
     if (t < 64) t = 64;
@@ -145,7 +147,13 @@ hg_status make_plan(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ran
     p.entries[n_ranges] = RangeEntry{0, 0, 0, (int32_t)ltok, 0};
     p.ws.ltok = (int32_t)ltok;
     p.ws.total = n_streams * ltok;
-    p.ws.span = pick_span(p.ws.total, use_gqa_kernel(d));
+    // The matrix-core kernel for 128-byte rows is the one kernel close to its instruction-issue
+    // limit (one wave per SIMD has to issue a block's instructions in the time its 8 KiB arrive);
+    // the table look-ups and 64-bit addresses of a paged cache push it over, and a second
+    // workgroup per compute unit fills the gaps: 218 -> 185 us on the d=64 grouped-query shape,
+    // where the contiguous cache and the other kernels measured no gain or a small loss.
+    const int per_cu_factor = use_gqa_kernel(d) && d->head_dim == 64 && d->block_table ? 2 : 1;
+    p.ws.span = pick_span(p.ws.total, use_gqa_kernel(d), per_cu_factor);
     {
         const int64_t row_bytes = d->stride_t * (d->dtype == HG_F16 ? 2 : 4);
         // Long spans whose byte length is a multiple of 1 MiB put every workgroup of the vector

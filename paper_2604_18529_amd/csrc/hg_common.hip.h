@@ -100,6 +100,15 @@ struct PageMap {
     int32_t shift, mask, max_blocks, pad;
 };
 
+// Byte offset of row `tok` of a paged cache whose table entry is `page`.  The host admits paged
+// descriptors only with a block stride below 4 GiB and a row stride below 16 MiB, so one
+// 32x32->64 multiply-add and one 24-bit multiply (full rate) do; a generic 64-bit product would
+// cost two quarter-rate multiplies per row.
+__device__ __forceinline__ int64_t paged_row_offset(int page, int tok, int mask, uint32_t block_b32, uint32_t row_b32)
+{
+    return (int64_t)((uint64_t)(uint32_t)page * block_b32 + __umul24((uint32_t)(tok & mask), row_b32));
+}
+
 struct PartialArgs {
     const void *q, *k, *v;
     int64_t stride_b, stride_h, stride_t;  // elements

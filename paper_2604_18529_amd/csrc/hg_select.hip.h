@@ -542,7 +542,7 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
     for (int j = RPW * wave + grp; j < keep; j += RPW * NW) {
         const float w = s_vals[j];
         const int tok = s_cols[j];
-        const char *vrow = paged ? vbase + ((int64_t)table[tok >> a.pages.shift] * a.stride_b + (int64_t)(tok & a.pages.mask) * a.stride_t) * ES
+        const char *vrow = paged ? vbase + paged_row_offset(table[tok >> a.pages.shift], tok, a.pages.mask, (uint32_t)(a.stride_b * ES), (uint32_t)row_bytes)
                                  : vbase + (int64_t)tok * row_bytes;
         float vf[EPL];
 #pragma unroll

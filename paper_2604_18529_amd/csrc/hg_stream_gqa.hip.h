@@ -142,7 +142,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     };
     auto paged_offset = [&](int tok, int page) __attribute__((always_inline)) -> int64_t {
         tok = tok < t1 ? tok : t1 - 1;  // clamp: never read past the segment
-        return (int64_t)page * block_bytes + (int64_t)(tok & a.pages.mask) * row_bytes;
+        return paged_row_offset(page, tok, a.pages.mask, (uint32_t)block_bytes, row_b32);
     };
     // row = token of the load relative to the lane's first row of the block (uniform)
     auto flat_offset = [&](int tb, int row, uint32_t lane_part) __attribute__((always_inline)) -> uint32_t {
@@ -172,8 +172,9 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             vreg[j] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(src));
         }
     };
-    // pages of the next block (pg1) and of the one after (pg2, in flight); unused when not paged
-    int pg1[8] = {0, 0, 0, 0, 0, 0, 0, 0}, pg2[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    // pages of the next block (pg1), the one after (pg2) and the one after that (pg3, in flight);
+    // unused when not paged
+    int pg1[8] = {0, 0, 0, 0, 0, 0, 0, 0}, pg2[8] = {0, 0, 0, 0, 0, 0, 0, 0}, pg3[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 
     // One block.  Software pipeline with a single register buffer: the K rows of the next block
     // are requested as soon as this block's K sits in LDS, its V rows as soon as this block's V
@@ -184,6 +185,14 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         for (int i = 0; i < 8; ++i)
             *reinterpret_cast<hg_u32x4 *>(kls + (4 * i + rg) * kGqaKRow + n * 16) = kreg[i];
         wave_lds_handover();
+        if constexpr (PAGED && MODE == kModeStats) {
+            // Pages three blocks ahead, requested before this block's loads: the registers are not
+            // touched again until the rotation at the end of the block, a whole block later, so the
+            // wave never stands waiting for a table entry (with a shorter look-ahead it did, once
+            // per block, for a full memory latency).
+            const int tb_3 = tb + 3 * (tb_next - tb);
+            if (tb_3 < t1) lookup(tb_3, pg3);
+        }
         if (tb_next < t1) {
             load_k(tb_next, kreg, pg1);
             if constexpr (PAGED && MODE == kModeLogits) {  // blocks are loaded in order: pages of the one after
@@ -300,16 +309,13 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
         }
         if (tb_next < t1) {
-            if constexpr (PAGED) {
-                // table look-up for the block after next goes out BEFORE the V loads: the K loads
-                // of that block then only wait for what was issued earlier (loads return in order)
-                const int tb_nn = tb_next + (tb_next - tb);
-                if (tb_nn < t1) lookup(tb_nn, pg2);
-            }
             load_v(tb_next, vreg, pg1);
             if constexpr (PAGED) {
 #pragma unroll
-                for (int x = 0; x < 8; ++x) pg1[x] = pg2[x];
+                for (int x = 0; x < 8; ++x) {
+                    pg1[x] = pg2[x];
+                    pg2[x] = pg3[x];
+                }
             }
         }
         wave_lds_handover();  // the next block overwrites the K and P staging areas
@@ -385,11 +391,12 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             hg_u32x4 kreg[8], vreg[8];
             if (tb < t1) {
                 if constexpr (PAGED) {
-                    lookup(tb, pg2);
+                    lookup(tb, pg3);
                     if (tb + kStride < t1) lookup(tb + kStride, pg1);
+                    if (tb + 2 * kStride < t1) lookup(tb + 2 * kStride, pg2);
                 }
-                load_k(tb, kreg, pg2);
-                load_v(tb, vreg, pg2);
+                load_k(tb, kreg, pg3);
+                load_v(tb, vreg, pg3);
             }
             while (tb < t1) {
                 compute_block(tb, tb + kStride, kreg, vreg);

@@ -115,7 +115,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             if constexpr (PAGED) {
                 int tok = MODE == kModeConcat ? tb + 4 * rl + 2 * (i & 1) + (i >> 1) : tb + 8 * i + rl;
                 tok = tok < t1 ? tok : t1 - 1;  // clamp: never read past the segment
-                const int64_t off = (int64_t)pg[i] * block_bytes + (int64_t)(tok & a.pages.mask) * row_bytes;
+                const int64_t off = paged_row_offset(pg[i], tok, a.pages.mask, (uint32_t)block_bytes, row_b32);
                 reg[i] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(base + off));
             } else {
                 const int row = MODE == kModeConcat ? 2 * (i & 1) + (i >> 1) : 8 * i;
@@ -125,7 +125,8 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             }
         }
     };
-    int pg1[4] = {0, 0, 0, 0}, pg2[4] = {0, 0, 0, 0};  // pages of the next block / the one after (paged only)
+    // pages of the next block, the one after and the one after that (paged only)
+    int pg1[4] = {0, 0, 0, 0}, pg2[4] = {0, 0, 0, 0}, pg3[4] = {0, 0, 0, 0};
 
     // B operand nb of the P.V product: the halves of channel 8*(n%8) + nb of the lane's 4 tokens go
     // to the slots of its parity, the other 4 slots are zero.  A byte selector of 0x0c makes
@@ -148,6 +149,11 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         for (int i = 0; i < 4; ++i)
             *reinterpret_cast<hg_u32x4 *>(kls + (8 * i + rl) * kGqa64KRow + c8 * 16) = kreg[i];
         wave_lds_handover();
+        if constexpr (PAGED && MODE == kModeStats) {
+            // pages three blocks ahead, requested before this block's loads: see hg_partial_gqa_kernel
+            const int tb_3 = tb + 3 * (tb_next - tb);
+            if (tb_3 < t1) lookup(tb_3, pg3);
+        }
         if (tb_next < t1) {
             load_rows(kbase, tb_next, kreg, pg1);
             if constexpr (PAGED && MODE == kModeLogits) {  // blocks are loaded in order: pages of the one after
@@ -257,14 +263,13 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
         }
         if (tb_next < t1) {
-            if constexpr (PAGED) {
-                const int tb_nn = tb_next + (tb_next - tb);
-                if (tb_nn < t1) lookup(tb_nn, pg2);  // before the V loads: see hg_partial_gqa_kernel
-            }
             load_rows(vbase, tb_next, vreg, pg1);
             if constexpr (PAGED) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) pg1[i] = pg2[i];
+                for (int i = 0; i < 4; ++i) {
+                    pg1[i] = pg2[i];
+                    pg2[i] = pg3[i];
+                }
             }
         }
         wave_lds_handover();  // the next block overwrites the K and P staging areas
@@ -333,11 +338,12 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             hg_u32x4 kreg[4], vreg[4];
             if (tb < t1) {
                 if constexpr (PAGED) {
-                    lookup(tb, pg2);
+                    lookup(tb, pg3);
                     if (tb + kStride < t1) lookup(tb + kStride, pg1);
+                    if (tb + 2 * kStride < t1) lookup(tb + 2 * kStride, pg2);
                 }
-                load_rows(kbase, tb, kreg, pg2);
-                load_rows(vbase, tb, vreg, pg2);
+                load_rows(kbase, tb, kreg, pg3);
+                load_rows(vbase, tb, vreg, pg3);
             }
             while (tb < t1) {
                 compute_block(tb, tb + kStride, kreg, vreg);

@@ -130,7 +130,7 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
             const int tok = tb + RPW * u + grp;
             valid[u] = tok < t1;
             tokc[u] = valid[u] ? tok : t1 - 1;  // clamp: never read past the segment
-            const int64_t off = PAGED ? (int64_t)pg[u] * block_bytes + (int64_t)(tokc[u] & a.pages.mask) * row_bytes
+            const int64_t off = PAGED ? paged_row_offset(pg[u], tokc[u], a.pages.mask, (uint32_t)block_bytes, (uint32_t)row_bytes)
                                       : (int64_t)tokc[u] * row_bytes;
             if constexpr (MODE != kModeConcat) {
 #pragma unroll
