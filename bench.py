@@ -142,8 +142,7 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W, routes=T
         p_old, p_new = hg.pack_ranges(old), hg.pack_ranges(new)
         lg_old = torch.empty((Hq, sum(e - b for (_, b, e) in old)), dtype=torch.float32, device=dev)
         gp_old = list(range(spec.batch + 1))
-        merge_gp = list(range(0, 2 * spec.batch + 1, 2))
-        order = torch.arange(2 * spec.batch, device=dev).reshape(2, spec.batch).t().reshape(-1)
+        one_each = list(range(spec.batch + 1))  # per sequence: one triple from the selection, one from the resident part
         nws = torch.empty(max(binding.hg_attn_partial_workspace_size(desc, p_new), 256), dtype=torch.uint8, device=dev)
         top_k = 128
 
@@ -156,8 +155,7 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W, routes=T
         def postqk_rest():
             _, m1, l1, o1 = postqk_select()
             m2, l2, o2 = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, p_new, w.scale, workspace=nws, desc=desc)
-            hg.hg_attn_merge(torch.cat([m1, m2])[order].contiguous(), torch.cat([l1, l2])[order].contiguous(),
-                             torch.cat([o1, o2])[order].contiguous(), merge_gp, out=out, lse=lse)
+            hg.hg_attn_merge2(m1, l1, o1, one_each, m2, l2, o2, one_each, out=out, lse=lse)
 
         pq_logits_ms, _ = _time_steps(postqk_logits, max(steps // 4, 1), max(warmup // 4, 1), torch)
         pq_select_ms, _ = _time_steps(postqk_select, max(steps // 4, 1), max(warmup // 4, 1), torch)

@@ -142,6 +142,19 @@ hg_status hg_attn_merge(const float *m, const float *l, const float *o, const in
                         size_t ws_bytes, void *stream);
 
 /*
+ * hg_attn_merge2 -- the same recombination over the triples of TWO producers, each with its own
+ * arrays and CSR (Section 4.2.3; Section 4.6 step 5: the concatenator joins what the executor of
+ * the offloaded tokens returns with what the executor of the resident tokens computed): group i
+ * merges triples group_ptr_a[i] .. group_ptr_a[i+1]-1 of set A with triples group_ptr_b[i] ..
+ * group_ptr_b[i+1]-1 of set B.  Either set may be empty for a group.  Saves the caller the
+ * gather of both results into one array.  Arguments as for hg_attn_merge.
+ */
+hg_status hg_attn_merge2_workspace_size(int32_t n_groups, size_t *bytes);
+hg_status hg_attn_merge2(const float *m_a, const float *l_a, const float *o_a, const int32_t *group_ptr_a, const float *m_b,
+                         const float *l_b, const float *o_b, const int32_t *group_ptr_b, int32_t n_groups, int32_t n_q_heads,
+                         int32_t head_dim, float *out, float *lse_out, void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * hg_attn_full -- the unsplit reference path ("monolithic execution", Section 4.2.3): softmax
  * attention of every sequence over its whole cache [0, seq_lens[b]).
  *

@@ -8,6 +8,7 @@ the package (for example to reach ``workloads``) does not require the built libr
 _API = (
     "hg_attn_partial",
     "hg_attn_merge",
+    "hg_attn_merge2",
     "hg_attn_full",
     "hg_attn_logits",
     "hg_attn_concat",

@@ -535,6 +535,64 @@ void launch_select(const hg_attn_desc *desc, const SelectArgs &sa, dim3 grid, bo
         launch_select_variant<STAGE, false>(desc, sa, grid, stream);
 }
 
+// hg_attn_merge (one producer: csr_b == nullptr) and hg_attn_merge2 (two producers).
+hg_status check_csr(const int32_t *csr, int32_t n_groups, const float *m, const float *l, const float *o)
+{
+    if (!csr) return HG_ERR_NULL;
+    if (csr[0] < 0) return HG_ERR_RANGE;
+    for (int32_t i = 0; i < n_groups; ++i)
+        if (csr[i] > csr[i + 1]) return HG_ERR_RANGE;
+    if (csr[n_groups] > csr[0] && (!m || !l || !o)) return HG_ERR_NULL;
+    return HG_OK;
+}
+
+hg_status merge_sets(const float *m, const float *l, const float *o, const int32_t *csr, const float *m_b, const float *l_b,
+                     const float *o_b, const int32_t *csr_b, int32_t n_groups, int32_t n_q_heads, int32_t head_dim, float *out,
+                     float *lse_out, void *workspace, size_t ws_bytes, void *stream_v)
+{
+    if (n_groups < 0 || n_q_heads <= 0 || n_q_heads > 65535) return HG_ERR_SHAPE;
+    if (head_dim != 64 && head_dim != 128) return HG_ERR_SHAPE;
+    if (n_groups == 0) return HG_OK;
+    if (!out) return HG_ERR_NULL;
+    hg_status st = check_csr(csr, n_groups, m, l, o);
+    if (st != HG_OK) return st;
+    // the second set takes part only if it holds a triple at all
+    const bool two = csr_b != nullptr;
+    if (two) {
+        st = check_csr(csr_b, n_groups, m_b, l_b, o_b);
+        if (st != HG_OK) return st;
+    }
+    const bool use_b = two && csr_b[n_groups] > csr_b[0];
+    const size_t one = merge_ws_bytes(n_groups);
+    st = check_workspace(workspace, ws_bytes, (two ? 2 : 1) * one);
+    if (st != HG_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+
+    MergeArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.m = m;
+    a.l = l;
+    a.o = o;
+    a.out = out;
+    a.lse = lse_out;
+    a.n_q_heads = n_q_heads;
+    st = stage_groups(csr, n_groups, static_cast<int32_t *>(workspace), stream, a.tab);
+    if (st != HG_OK) return st;
+    if (use_b) {
+        a.m_b = m_b;
+        a.l_b = l_b;
+        a.o_b = o_b;
+        st = stage_groups(csr_b, n_groups, reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + one), stream, a.tab_b);
+        if (st != HG_OK) return st;
+    }
+    dim3 grid((unsigned)n_groups, (unsigned)n_q_heads);
+    if (head_dim == 128)
+        hipLaunchKernelGGL(hg_merge_kernel<128>, grid, dim3(kReduceBlock), 0, stream, a);
+    else
+        hipLaunchKernelGGL(hg_merge_kernel<64>, grid, dim3(kReduceBlock), 0, stream, a);
+    return launch_status("merge kernel");
+}
+
 }  // namespace
 
 extern "C" {
@@ -921,35 +979,25 @@ hg_status hg_attn_merge(const float *m, const float *l, const float *o, const in
                         int32_t n_q_heads, int32_t head_dim, float *out, float *lse_out, void *workspace,
                         size_t ws_bytes, void *stream_v)
 {
-    if (n_groups < 0 || n_q_heads <= 0 || n_q_heads > 65535) return HG_ERR_SHAPE;
-    if (head_dim != 64 && head_dim != 128) return HG_ERR_SHAPE;
-    if (n_groups == 0) return HG_OK;
-    if (!group_ptr || !out) return HG_ERR_NULL;
-    if (group_ptr[0] < 0) return HG_ERR_RANGE;
-    for (int32_t i = 0; i < n_groups; ++i)
-        if (group_ptr[i] > group_ptr[i + 1]) return HG_ERR_RANGE;
-    if (group_ptr[n_groups] > group_ptr[0] && (!m || !l || !o)) return HG_ERR_NULL;
-    const size_t need = merge_ws_bytes(n_groups);
-    hg_status st = check_workspace(workspace, ws_bytes, need);
-    if (st != HG_OK) return st;
-    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    return merge_sets(m, l, o, group_ptr, nullptr, nullptr, nullptr, nullptr, n_groups, n_q_heads, head_dim, out, lse_out,
+                      workspace, ws_bytes, stream_v);
+}
 
-    MergeArgs a;
-    std::memset(&a, 0, sizeof(a));
-    a.m = m;
-    a.l = l;
-    a.o = o;
-    a.out = out;
-    a.lse = lse_out;
-    a.n_q_heads = n_q_heads;
-    st = stage_groups(group_ptr, n_groups, static_cast<int32_t *>(workspace), stream, a.tab);
-    if (st != HG_OK) return st;
-    dim3 grid((unsigned)n_groups, (unsigned)n_q_heads);
-    if (head_dim == 128)
-        hipLaunchKernelGGL(hg_merge_kernel<128>, grid, dim3(kReduceBlock), 0, stream, a);
-    else
-        hipLaunchKernelGGL(hg_merge_kernel<64>, grid, dim3(kReduceBlock), 0, stream, a);
-    return launch_status("merge kernel");
+hg_status hg_attn_merge2_workspace_size(int32_t n_groups, size_t *bytes)
+{
+    if (!bytes) return HG_ERR_NULL;
+    if (n_groups < 0) return HG_ERR_SHAPE;
+    *bytes = 2 * merge_ws_bytes(n_groups);
+    return HG_OK;
+}
+
+hg_status hg_attn_merge2(const float *m_a, const float *l_a, const float *o_a, const int32_t *group_ptr_a, const float *m_b,
+                         const float *l_b, const float *o_b, const int32_t *group_ptr_b, int32_t n_groups, int32_t n_q_heads,
+                         int32_t head_dim, float *out, float *lse_out, void *workspace, size_t ws_bytes, void *stream_v)
+{
+    if (n_groups > 0 && !group_ptr_b) return HG_ERR_NULL;
+    return merge_sets(m_a, l_a, o_a, group_ptr_a, m_b, l_b, o_b, group_ptr_b, n_groups, n_q_heads, head_dim, out, lse_out,
+                      workspace, ws_bytes, stream_v);
 }
 
 }  // extern "C"

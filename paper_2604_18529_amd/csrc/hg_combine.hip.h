@@ -104,16 +104,24 @@ __global__ __launch_bounds__(kReduceBlock) void hg_merge_kernel(const MergeArgs 
     const int te = a.tab.ext ? a.tab.ext[gidx + 1] : a.tab.inl[gidx + 1];
 
     float mx = kNegBig, lt = 0.f, ot = 0.f;
+    auto fold = [&](const float *pm, const float *pl, const float *po, int t0, int t1) __attribute__((always_inline)) {
 #pragma unroll 4
-    for (int t = ts + sl; t < te; t += S) {
-        const int64_t th = (int64_t)t * a.n_q_heads + h;
-        const float li = a.l[th], oi = a.o[th * D + c];
-        const float mi = li != 0.f ? a.m[th] * kLog2e : kNegBig;  // identity element: ignored
-        const float mn = fmaxf(mx, mi);
-        const float wa = fast_exp2(mx - mn), wb = li != 0.f ? fast_exp2(mi - mn) : 0.f;
-        lt = lt * wa + li * wb;
-        ot = ot * wa + oi * wb;
-        mx = mn;
+        for (int t = t0 + sl; t < t1; t += S) {
+            const int64_t th = (int64_t)t * a.n_q_heads + h;
+            const float li = pl[th], oi = po[th * D + c];
+            const float mi = li != 0.f ? pm[th] * kLog2e : kNegBig;  // identity element: ignored
+            const float mn = fmaxf(mx, mi);
+            const float wa = fast_exp2(mx - mn), wb = li != 0.f ? fast_exp2(mi - mn) : 0.f;
+            lt = lt * wa + li * wb;
+            ot = ot * wa + oi * wb;
+            mx = mn;
+        }
+    };
+    fold(a.m, a.l, a.o, ts, te);
+    if (a.l_b) {
+        const int bs = a.tab_b.ext ? a.tab_b.ext[gidx] : a.tab_b.inl[gidx];
+        const int be = a.tab_b.ext ? a.tab_b.ext[gidx + 1] : a.tab_b.inl[gidx + 1];
+        fold(a.m_b, a.l_b, a.o_b, bs, be);
     }
     if (!combine_slices<D>(mx, lt, ot, c, sl)) return;
 

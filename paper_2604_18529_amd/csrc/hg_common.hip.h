@@ -145,6 +145,9 @@ struct MergeArgs {
     float *out, *lse;
     int32_t n_q_heads;
     GroupTable tab;
+    // second producer (hg_attn_merge2): its own triple arrays and CSR; m_b == nullptr: none
+    const float *m_b, *l_b, *o_b;
+    GroupTable tab_b;
 };
 
 struct ConcatStatsArgs {

@@ -81,6 +81,8 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_partial.argtypes = [D, R, i32, vp, vp, vp, vp, sz, vp]
     lib.hg_attn_merge_workspace_size.argtypes = [i32, ctypes.POINTER(sz)]
     lib.hg_attn_merge.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.hg_attn_merge2_workspace_size.argtypes = [i32, ctypes.POINTER(sz)]
+    lib.hg_attn_merge2.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.hg_attn_logits_workspace_size.argtypes = [D, R, i32, ctypes.POINTER(sz)]
     lib.hg_attn_logits.argtypes = [D, R, i32, vp, vp, sz, vp]
     lib.hg_attn_concat_workspace_size.argtypes = [D, R, i32, i32, ctypes.POINTER(sz)]
@@ -98,6 +100,7 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
     for name in (
         "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_merge_workspace_size", "hg_attn_merge",
+        "hg_attn_merge2_workspace_size", "hg_attn_merge2",
         "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_span_tokens",
         "hg_attn_profile_start", "hg_attn_profile_stop", "hg_attn_calibration_copy",
         "hg_sched_init", "hg_sched_step", "hg_attn_logits_workspace_size", "hg_attn_logits", "hg_attn_select_workspace_size", "hg_attn_select", "hg_attn_concat_workspace_size", "hg_attn_concat",
@@ -295,6 +298,50 @@ def hg_attn_merge(m, l, o, group_ptr, *, out=None, lse=None, want_lse=True, work
         st = lib.hg_attn_merge(_ptr(m), _ptr(l), _ptr(o), gp.ctypes.data, n_groups, Hq, d, _ptr(out), _ptr(lse),
                                _ptr(workspace), ws_bytes, _stream_handle(stream))
     _check(st, "hg_attn_merge")
+    return out, lse
+
+
+def _check_triples(m, l, o, gp, what):
+    if o.dim() != 3 or tuple(m.shape) != tuple(o.shape[:2]) or m.shape != l.shape:
+        raise ValueError("%s: m, l must be [T,Hq] and o [T,Hq,d]" % what)
+    for t in (m, l, o):
+        if t.dtype != torch.float32 or not t.is_contiguous():
+            raise ValueError("%s: triples must be contiguous fp32" % what)
+    if gp.ndim != 1 or gp.size < 1:
+        raise ValueError("%s: group_ptr must be CSR offsets [n_groups+1]" % what)
+    if gp[-1] > m.shape[0]:
+        raise ValueError("%s: group_ptr runs past the triples" % what)
+
+
+def hg_attn_merge2(m_a, l_a, o_a, group_ptr_a, m_b, l_b, o_b, group_ptr_b, *, out=None, lse=None, want_lse=True,
+                   workspace=None, stream=None):
+    """Exact merge of the triples of two producers (each with its own arrays and CSR) per group.
+    Returns (out [n_groups,Hq,d], lse [n_groups,Hq] or None)."""
+    lib = load_library()
+    gpa = np.ascontiguousarray(group_ptr_a, dtype=np.int32)
+    gpb = np.ascontiguousarray(group_ptr_b, dtype=np.int32)
+    _check_triples(m_a, l_a, o_a, gpa, "set A")
+    _check_triples(m_b, l_b, o_b, gpb, "set B")
+    if gpa.size != gpb.size or o_a.shape[1:] != o_b.shape[1:]:
+        raise ValueError("the two sets must agree in groups, heads and head_dim")
+    n_groups = gpa.size - 1
+    _, Hq, d = o_a.shape
+    dev = o_a.device
+    if out is None:
+        out = torch.empty((n_groups, Hq, d), dtype=torch.float32, device=dev)
+    if lse is None and want_lse:
+        lse = torch.empty((n_groups, Hq), dtype=torch.float32, device=dev)
+    if workspace is None:
+        sz = ctypes.c_size_t()
+        _check(lib.hg_attn_merge2_workspace_size(n_groups, ctypes.byref(sz)), "hg_attn_merge2_workspace_size")
+        workspace, ws_bytes = _workspace(sz.value, dev, None)
+    else:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        st = lib.hg_attn_merge2(_ptr(m_a), _ptr(l_a), _ptr(o_a), gpa.ctypes.data, _ptr(m_b), _ptr(l_b), _ptr(o_b),
+                                gpb.ctypes.data, n_groups, Hq, d, _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes,
+                                _stream_handle(stream))
+    _check(st, "hg_attn_merge2")
     return out, lse
 
 

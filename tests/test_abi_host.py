@@ -96,6 +96,11 @@ def test_full_and_merge_reject_bad_arguments(lib):
     assert lib.hg_attn_merge(None, FAKE, FAKE, gp.ctypes.data, 1, 4, 128, FAKE, None, None, 0, None) == -1
     assert lib.hg_attn_merge(FAKE, FAKE, FAKE, None, 1, 4, 128, FAKE, None, None, 0, None) == -1
     assert lib.hg_attn_merge(None, None, None, None, 0, 4, 128, None, None, None, 0, None) == 0
+    one = np.array([0, 1], dtype=np.int32)
+    assert lib.hg_attn_merge2(FAKE, FAKE, FAKE, one.ctypes.data, FAKE, FAKE, FAKE, None, 1, 4, 128, FAKE, None, None, 0, None) == -1
+    assert lib.hg_attn_merge2(FAKE, FAKE, FAKE, one.ctypes.data, None, FAKE, FAKE, one.ctypes.data, 1, 4, 128, FAKE, None, None, 0, None) == -1
+    bad = np.array([1, 0], dtype=np.int32)
+    assert lib.hg_attn_merge2(FAKE, FAKE, FAKE, one.ctypes.data, FAKE, FAKE, FAKE, bad.ctypes.data, 1, 4, 128, FAKE, None, None, 0, None) == -4
     big = np.arange(1000, dtype=np.int32)  # more groups than fit in kernel arguments: needs workspace
     sz = ctypes.c_size_t()
     assert lib.hg_attn_merge_workspace_size(999, ctypes.byref(sz)) == 0 and sz.value >= 4000

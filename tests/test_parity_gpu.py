@@ -120,6 +120,40 @@ def test_many_ranges_take_the_table_upload_path():
     check_out(out, lse, ref, rlse, "many groups")
 
 
+@pytest.mark.parametrize("n_groups", [3, 400])
+def test_merge_of_two_producers(n_groups):
+    """hg_attn_merge2: every group takes triples from two separate arrays (uneven counts, empty
+    on either side or on both); the reference is the oracle's merge over the two sets stacked."""
+    rng = np.random.default_rng(80 + n_groups)
+    spec = W.WorkloadSpec("two", 2, 6, 3, 128, "f16", 1500, 1500, "none", seed=13)
+    w = W.make_workload(spec, DEV)
+    ca = np.concatenate([[0], np.cumsum(rng.integers(0, 4, n_groups))]).astype(np.int32)
+    cb = np.concatenate([[0], np.cumsum(rng.integers(0, 3, n_groups))]).astype(np.int32)
+    ca[1], cb[1] = ca[0], cb[0]  # group 0: nothing from either producer
+    ra = W.random_ranges(w.seq_lens, int(ca[-1]), seed=5, max_len=400)
+    rb = W.random_ranges(w.seq_lens, int(cb[-1]), seed=6, max_len=400)
+    ma, la, oa = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, ra, w.scale)
+    mb, lb, ob = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, rb, w.scale)
+    out, lse = hg.hg_attn_merge2(ma, la, oa, ca, mb, lb, ob, cb)
+    qn = to_np(w.q)
+    kn, vn = kv_np(w)
+    # oracle: group i = A-ranges of i followed by B-ranges of i, one stacked table
+    stacked, gp = [], [0]
+    for i in range(n_groups):
+        stacked += ra[ca[i]:ca[i + 1]] + rb[cb[i]:cb[i + 1]]
+        gp.append(len(stacked))
+    mo, lo, oo = oracle.attn_partial(qn, kn, vn, w.seq_lens, w.scale, stacked)
+    ref, rlse = oracle.attn_merge(mo, lo, oo, gp)
+    check_out(out, lse, ref, rlse, "two producers, %d groups" % n_groups)
+    # and it agrees with the one-producer call on the gathered triples (the triples are dealt to
+    # the folding slices in another order, so only to rounding)
+    idx = torch.tensor([j for i in range(n_groups) for j in list(range(ca[i], ca[i + 1])) +
+                        [int(ca[-1]) + x for x in range(cb[i], cb[i + 1])]], dtype=torch.long, device=DEV)
+    m1, l1, o1 = (torch.cat([a, b])[idx].contiguous() for a, b in ((ma, mb), (la, lb), (oa, ob)))
+    out1, lse1 = hg.hg_attn_merge(m1, l1, o1, gp)
+    assert (out - out1).abs().max().item() <= 1e-5 and torch.equal(torch.isinf(lse), torch.isinf(lse1))
+
+
 def test_batch_larger_than_inline_table():
     spec = W.WorkloadSpec("b100", 100, 2, 2, 64, "f32", 1, 90, "half", 2, seed=12)
     w = W.make_workload(spec, DEV)
