@@ -269,8 +269,8 @@ def main():
                          "yardstick profiler byte counters are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build measures one GPU only (the path shards by (sequence, KV head) or by "
-                 "token range across GPUs, see DESIGN.md); run with --gpus 1")
+        sys.exit("bench.py: this build measures one GPU only (across GPUs the path shards by (sequence, KV head), "
+                 "or by token range with one exchange of the (m, l, O) triples); run with --gpus 1")
 
     import torch
 
