@@ -30,7 +30,7 @@
  *                     go to the lower column.
  *
  * All arithmetic is fp64, plain sequential sums in token order, libm exp/log.  Inputs are the
- * caller's fp16 / fp32 bit patterns widened exactly; nothing is re-rounded.  The only parallelism
+ * caller's fp16 / bf16 / fp32 bit patterns widened exactly; nothing is re-rounded.  The only parallelism
  * is an OpenMP loop over independent (sequence, query head) pairs; there is no blocking, fusion
  * or reordering.
  *
@@ -51,7 +51,8 @@ typedef struct {
 } hgo_range;
 
 /* Problem description shared by the routines that read the KV cache.
- * dtype: 0 = IEEE binary16 bit patterns (uint16_t), 1 = binary32 (float).
+ * dtype: 0 = IEEE binary16 bit patterns (uint16_t), 1 = binary32 (float), 2 = bfloat16 bit patterns
+ * (uint16_t: the upper half of a binary32).
  * q is [B][Hq][d] contiguous.  Element (b, g, t, c) of K or V sits at
  * base + b*stride_b + g*stride_h + t*stride_t + c   (strides counted in elements). */
 typedef struct {
@@ -81,9 +82,28 @@ static double half_bits_to_double(uint16_t h)
     return sign ? -val : val;
 }
 
+/* bfloat16 = sign, 8 exponent bits, 7 fraction bits: the value of the binary32 whose upper 16
+ * bits are these and whose lower 16 bits are zero. */
+static double bf16_bits_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int ex = (h >> 7) & 0xff;
+    int man = h & 0x7f;
+    double val;
+    if (ex == 0) {
+        val = ldexp((double)man, -133); /* zero or subnormal: man * 2^-7 * 2^-126 */
+    } else if (ex == 255) {
+        val = man ? NAN : INFINITY;
+    } else {
+        val = ldexp((double)(man + 128), ex - 134); /* (1 + man/128) * 2^(ex-127) */
+    }
+    return sign ? -val : val;
+}
+
 static double load_elem(const void *base, int64_t idx, int dtype)
 {
     if (dtype == 0) return half_bits_to_double(((const uint16_t *)base)[idx]);
+    if (dtype == 2) return bf16_bits_to_double(((const uint16_t *)base)[idx]);
     return (double)((const float *)base)[idx];
 }
 
@@ -110,7 +130,7 @@ static int check_problem(const hgo_problem *p)
     if (!p || !p->q || !p->k || !p->v || !p->seq_lens) return -1;
     if (p->B < 0 || p->Hq <= 0 || p->Hkv <= 0 || p->d <= 0) return -2;
     if (p->Hq % p->Hkv) return -2;
-    if (p->dtype != 0 && p->dtype != 1) return -3;
+    if (p->dtype != 0 && p->dtype != 1 && p->dtype != 2) return -3;
     return 0;
 }
 

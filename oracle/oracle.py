@@ -2,7 +2,7 @@
 
 Argument marshalling only: numpy arrays in, numpy float64 arrays out.  q is ``[B, Hq, d]``;
 K and V are ``[B, Hkv, Nmax, d]`` arrays (any strides over the first three axes, channel axis
-contiguous) of dtype float16 or float32; ``seq_lens[b]`` tokens of sequence ``b`` are valid.
+contiguous) of dtype float16, float32, or uint16 holding bfloat16 bit patterns; ``seq_lens[b]`` tokens of sequence ``b`` are valid.
 The routines and the passages of the paper they follow are described in ``hg_oracle.c``.
 """
 from __future__ import annotations
@@ -89,8 +89,8 @@ def _check(rc: int, what: str) -> None:
 
 def _problem(q, k, v, seq_lens, scale):
     q = np.ascontiguousarray(q)
-    if q.dtype not in (np.float16, np.float32) or k.dtype != q.dtype or v.dtype != q.dtype:
-        raise TypeError("q, k, v must share dtype float16 or float32")
+    if q.dtype not in (np.float16, np.float32, np.uint16) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise TypeError("q, k, v must share dtype float16, float32 or uint16 (bfloat16 bit patterns)")
     if q.ndim != 3 or k.ndim != 4 or v.ndim != 4 or k.shape != v.shape:
         raise ValueError("q must be [B,Hq,d]; k and v [B,Hkv,N,d] of equal shape")
     B, Hq, d = q.shape
@@ -107,7 +107,7 @@ def _problem(q, k, v, seq_lens, scale):
     prob = _Problem(
         q.ctypes.data, k.ctypes.data, v.ctypes.data,
         k.strides[0] // es, k.strides[1] // es, k.strides[2] // es,
-        seq.ctypes.data, B, Hq, k.shape[1], d, 0 if q.dtype == np.float16 else 1, float(scale),
+        seq.ctypes.data, B, Hq, k.shape[1], d, {np.dtype(np.float16): 0, np.dtype(np.float32): 1, np.dtype(np.uint16): 2}[q.dtype], float(scale),
     )
     return prob, (q, k, v, seq)  # second item keeps the buffers alive
 

@@ -53,6 +53,49 @@ def test_fp16_bit_patterns_widen_exactly():
     assert np.all(l == 1.0)
 
 
+def test_bf16_bit_patterns_widen_exactly():
+    """The same for every finite bfloat16 pattern; the expected values come from numpy's own
+    binary32 reading of the pattern shifted into the upper half (an independent decoder)."""
+    bits = np.arange(65536, dtype=np.uint32)
+    vals = (bits << 16).astype(np.uint32).view(np.float32)
+    keep = np.isfinite(vals)
+    bits16, vals = bits[keep].astype(np.uint16), vals[keep]
+    n = vals.size
+    one = np.array([0x3F80], dtype=np.uint16).reshape(1, 1, 1)  # 1.0
+    k = bits16.reshape(1, 1, n, 1).copy()
+    v = bits16[::-1].reshape(1, 1, n, 1).copy()
+    ranges = [(0, j, j + 1) for j in range(n)]
+    m, l, o = oracle.attn_partial(one, k, v, [n], 1.0, ranges)
+    assert np.array_equal(m[:, 0], vals.astype(np.float64))
+    assert np.array_equal(o[:, 0, 0], vals[::-1].astype(np.float64))
+    assert np.all(l == 1.0)
+    # and the torch library conversion agrees on the same patterns
+    import torch
+    t = torch.from_numpy(bits16.view(np.int16).copy()).view(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(t, vals)
+
+
+def test_bf16_matches_the_same_values_stored_as_fp32():
+    """bfloat16 inputs are exactly representable in binary32, so the oracle must give bit-identical
+    results for the bf16 patterns and for their fp32 widening (catches any bf16-specific path)."""
+    rng = RNG(91)
+    B, Hq, Hkv, N, d = 2, 4, 2, 37, 8
+    def mk(shape):
+        f = rng.standard_normal(shape).astype(np.float32)
+        bits = (f.view(np.uint32) >> 16).astype(np.uint16)  # truncation is fine: any bf16 pattern will do
+        return bits, (bits.astype(np.uint32) << 16).view(np.float32)
+    qb, qf = mk((B, Hq, d))
+    kb, kf = mk((B, Hkv, N, d))
+    vb, vf = mk((B, Hkv, N, d))
+    seq_lens = [37, 20]
+    ranges = [(0, 0, 10), (0, 10, 37), (1, 0, 20), (1, 5, 5)]
+    for a, b in zip(oracle.attn_partial(qb, kb, vb, seq_lens, 0.4, ranges), oracle.attn_partial(qf, kf, vf, seq_lens, 0.4, ranges)):
+        assert np.array_equal(a, b)
+    for a, b in zip(oracle.attn_full(qb, kb, vb, seq_lens, 0.4), oracle.attn_full(qf, kf, vf, seq_lens, 0.4)):
+        assert np.array_equal(a, b)
+    assert np.array_equal(oracle.attn_logits(qb, kb, vb, seq_lens, 0.4, ranges), oracle.attn_logits(qf, kf, vf, seq_lens, 0.4, ranges))
+
+
 # ---- P1 brute force in rational arithmetic -----------------------------------------------------
 
 
