@@ -305,7 +305,7 @@ def main():
         r["steps"] = k
         others.append(r)
 
-    if head["kv_dtype"] == "f16" and head["n_q_heads"] // head["n_kv_heads"] >= 2:  # the library's own dispatch rule
+    if head["kv_dtype"] != "f32" and head["n_q_heads"] // head["n_kv_heads"] >= 2:  # the library's own dispatch rule
         kernel_name = "hg_partial_gqa_kernel" if head["head_dim"] == 128 else "hg_partial_gqa64_kernel"
     else:
         kernel_name = "hg_partial_kernel"

@@ -53,13 +53,13 @@ typedef enum hg_status {
     HG_OK = 0,
     HG_ERR_NULL = -1,      /* a required pointer is NULL                                        */
     HG_ERR_SHAPE = -2,     /* batch/heads/head_dim/strides/alignment/counts not supported       */
-    HG_ERR_DTYPE = -3,     /* dtype is not HG_F16 or HG_F32                                     */
+    HG_ERR_DTYPE = -3,     /* dtype is not HG_F16, HG_F32 or HG_BF16                            */
     HG_ERR_RANGE = -4,     /* a range or CSR offset is malformed or exceeds its sequence        */
     HG_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or smaller than required               */
     HG_ERR_LAUNCH = -6     /* the HIP runtime refused a copy or a launch (details on stderr)    */
 } hg_status;
 
-typedef enum hg_dtype { HG_F16 = 0, HG_F32 = 1 } hg_dtype;
+typedef enum hg_dtype { HG_F16 = 0, HG_F32 = 1, HG_BF16 = 2 } hg_dtype; /* storage of q, K and V */
 
 /*
  * One decode-attention problem: a batch of sequences, one query token each.

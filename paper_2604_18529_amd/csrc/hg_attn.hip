@@ -61,13 +61,13 @@ int compute_units()
 hg_status check_desc(const hg_attn_desc *d)
 {
     if (!d) return HG_ERR_NULL;
-    if (d->dtype != HG_F16 && d->dtype != HG_F32) return HG_ERR_DTYPE;
+    if (d->dtype != HG_F16 && d->dtype != HG_F32 && d->dtype != HG_BF16) return HG_ERR_DTYPE;
     if (d->batch < 0 || d->n_q_heads <= 0 || d->n_q_heads > 65535 || d->n_kv_heads <= 0) return HG_ERR_SHAPE;
     if (d->n_q_heads % d->n_kv_heads) return HG_ERR_SHAPE;
     if (d->head_dim != 64 && d->head_dim != 128) return HG_ERR_SHAPE;
     if (d->batch == 0) return HG_OK;
     if (!d->q || !d->k || !d->v || !d->seq_lens) return HG_ERR_NULL;
-    const int64_t es = d->dtype == HG_F16 ? 2 : 4;
+    const int64_t es = d->dtype == HG_F32 ? 4 : 2;
     if (d->stride_t < d->head_dim || d->stride_b < 0 || d->stride_h < 0) return HG_ERR_SHAPE;
     if ((d->stride_t * es) % 16 || (d->stride_b * es) % 16 || (d->stride_h * es) % 16) return HG_ERR_SHAPE;
     if (((uintptr_t)d->q | (uintptr_t)d->k | (uintptr_t)d->v) % 16) return HG_ERR_SHAPE;
@@ -98,11 +98,11 @@ hg_status check_ranges(const hg_attn_desc *d, const hg_range *ranges, int32_t n_
     return HG_OK;
 }
 
-// The matrix-core kernels take fp16 and at least HG_GQA_MIN_GROUP query heads per KV head.
+// The matrix-core kernels take fp16 or bf16 and at least HG_GQA_MIN_GROUP query heads per KV head.
 #ifndef HG_GQA_MIN_GROUP
 #define HG_GQA_MIN_GROUP 2
 #endif
-bool use_gqa_kernel(const hg_attn_desc *d) { return d->dtype == HG_F16 && d->n_q_heads / d->n_kv_heads >= HG_GQA_MIN_GROUP; }
+bool use_gqa_kernel(const hg_attn_desc *d) { return d->dtype != HG_F32 && d->n_q_heads / d->n_kv_heads >= HG_GQA_MIN_GROUP; }
 
 int32_t pick_group_tile(const hg_attn_desc *d)
 {
@@ -155,7 +155,7 @@ hg_status make_plan(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ran
     const int per_cu_factor = use_gqa_kernel(d) && d->head_dim == 64 && d->block_table ? 2 : 1;
     p.ws.span = pick_span(p.ws.total, use_gqa_kernel(d), per_cu_factor);
     {
-        const int64_t row_bytes = d->stride_t * (d->dtype == HG_F16 ? 2 : 4);
+        const int64_t row_bytes = d->stride_t * (d->dtype == HG_F32 ? 4 : 2);
         // Long spans whose byte length is a multiple of 1 MiB put every workgroup of the vector
         // kernel at the same phase of the memory interleave, and the workgroups then advance in
         // step.  Measured on three MI355X machines this costs 4-6 % of the bandwidth (84-87 %
@@ -235,6 +235,11 @@ template <typename TR, int MODE, bool PAGED>
 void launch_valu_gt(const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
 {
     constexpr int F = MODE == kModeStats ? 1 : 2;
+    if constexpr (TR::DT != kDtF32) {
+        // 16-bit storage with a query group goes to the matrix-core kernels: only one head per lane group here
+        hipLaunchKernelGGL((hg_partial_kernel<TR, 1, F * HG_VALU_U, MODE, PAGED>), grid, dim3(kValuBlock), 0, stream, a);
+        return;
+    }
     switch (gt) {
     case 1: hipLaunchKernelGGL((hg_partial_kernel<TR, 1, F * HG_VALU_U, MODE, PAGED>), grid, dim3(kValuBlock), 0, stream, a); break;
     case 2: hipLaunchKernelGGL((hg_partial_kernel<TR, 2, F * HG_VALU_U, MODE, PAGED>), grid, dim3(kValuBlock), 0, stream, a); break;
@@ -246,24 +251,35 @@ void launch_valu_gt(const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
 template <int MODE, bool PAGED>
 void launch_stream_paged(const hg_attn_desc *d, const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
 {
+    const bool bf16 = d->dtype == HG_BF16;
     if (use_gqa_kernel(d)) {
-        if (d->head_dim == 128)
-            hipLaunchKernelGGL((hg_partial_gqa_kernel<MODE, PAGED>), grid, dim3(kGqaBlock), 0, stream, a);
-        else
-            hipLaunchKernelGGL((hg_partial_gqa64_kernel<MODE, PAGED>), grid, dim3(kGqaBlock), 0, stream, a);
+        if (d->head_dim == 128) {
+            if (bf16)
+                hipLaunchKernelGGL((hg_partial_gqa_kernel<MODE, PAGED, true>), grid, dim3(kGqaBlock), 0, stream, a);
+            else
+                hipLaunchKernelGGL((hg_partial_gqa_kernel<MODE, PAGED, false>), grid, dim3(kGqaBlock), 0, stream, a);
+        } else {
+            if (bf16)
+                hipLaunchKernelGGL((hg_partial_gqa64_kernel<MODE, PAGED, true>), grid, dim3(kGqaBlock), 0, stream, a);
+            else
+                hipLaunchKernelGGL((hg_partial_gqa64_kernel<MODE, PAGED, false>), grid, dim3(kGqaBlock), 0, stream, a);
+        }
         return;
     }
-    const bool f16 = d->dtype == HG_F16;
     if (d->head_dim == 128) {
-        if (f16)
-            launch_valu_gt<Traits<128, true>, MODE, PAGED>(a, gt, grid, stream);
+        if (d->dtype == HG_F16)
+            launch_valu_gt<Traits<128, kDtF16>, MODE, PAGED>(a, gt, grid, stream);
+        else if (bf16)
+            launch_valu_gt<Traits<128, kDtBf16>, MODE, PAGED>(a, gt, grid, stream);
         else
-            launch_valu_gt<Traits<128, false>, MODE, PAGED>(a, gt, grid, stream);
+            launch_valu_gt<Traits<128, kDtF32>, MODE, PAGED>(a, gt, grid, stream);
     } else {
-        if (f16)
-            launch_valu_gt<Traits<64, true>, MODE, PAGED>(a, gt, grid, stream);
+        if (d->dtype == HG_F16)
+            launch_valu_gt<Traits<64, kDtF16>, MODE, PAGED>(a, gt, grid, stream);
+        else if (bf16)
+            launch_valu_gt<Traits<64, kDtBf16>, MODE, PAGED>(a, gt, grid, stream);
         else
-            launch_valu_gt<Traits<64, false>, MODE, PAGED>(a, gt, grid, stream);
+            launch_valu_gt<Traits<64, kDtF32>, MODE, PAGED>(a, gt, grid, stream);
     }
 }
 
@@ -512,17 +528,21 @@ SelectPlan plan_select(const hg_range *ranges, int32_t n_ranges, const int32_t *
 template <int STAGE, bool FAST>
 void launch_select_variant(const hg_attn_desc *desc, const SelectArgs &sa, dim3 grid, hipStream_t stream)
 {
-    const bool f16 = desc->dtype == HG_F16;
+    const dim3 block(FAST ? kSelectFastBlock : kSelectBlock);
     if (desc->head_dim == 128) {
-        if (f16)
-            hipLaunchKernelGGL((hg_select_kernel<Traits<128, true>, STAGE, FAST>), grid, dim3(FAST ? kSelectFastBlock : kSelectBlock), 0, stream, sa);
+        if (desc->dtype == HG_F16)
+            hipLaunchKernelGGL((hg_select_kernel<Traits<128, kDtF16>, STAGE, FAST>), grid, block, 0, stream, sa);
+        else if (desc->dtype == HG_BF16)
+            hipLaunchKernelGGL((hg_select_kernel<Traits<128, kDtBf16>, STAGE, FAST>), grid, block, 0, stream, sa);
         else
-            hipLaunchKernelGGL((hg_select_kernel<Traits<128, false>, STAGE, FAST>), grid, dim3(FAST ? kSelectFastBlock : kSelectBlock), 0, stream, sa);
+            hipLaunchKernelGGL((hg_select_kernel<Traits<128, kDtF32>, STAGE, FAST>), grid, block, 0, stream, sa);
     } else {
-        if (f16)
-            hipLaunchKernelGGL((hg_select_kernel<Traits<64, true>, STAGE, FAST>), grid, dim3(FAST ? kSelectFastBlock : kSelectBlock), 0, stream, sa);
+        if (desc->dtype == HG_F16)
+            hipLaunchKernelGGL((hg_select_kernel<Traits<64, kDtF16>, STAGE, FAST>), grid, block, 0, stream, sa);
+        else if (desc->dtype == HG_BF16)
+            hipLaunchKernelGGL((hg_select_kernel<Traits<64, kDtBf16>, STAGE, FAST>), grid, block, 0, stream, sa);
         else
-            hipLaunchKernelGGL((hg_select_kernel<Traits<64, false>, STAGE, FAST>), grid, dim3(FAST ? kSelectFastBlock : kSelectBlock), 0, stream, sa);
+            hipLaunchKernelGGL((hg_select_kernel<Traits<64, kDtF32>, STAGE, FAST>), grid, block, 0, stream, sa);
     }
 }
 

@@ -304,11 +304,14 @@ struct RawVec<16> {
     hg_u32x4 d;
 };
 
-template <int D_, bool F16_>
+// storage types of q, K and V (the values of hg_dtype)
+constexpr int kDtF16 = 0, kDtF32 = 1, kDtBf16 = 2;
+
+template <int D_, int DT_>
 struct Traits {
     static constexpr int D = D_;
-    static constexpr bool F16 = F16_;
-    static constexpr int ES = F16_ ? 2 : 4;
+    static constexpr int DT = DT_;
+    static constexpr int ES = DT_ == kDtF32 ? 4 : 2;
     static constexpr int LPR = D_ * ES >= 256 ? 16 : 8;       // lanes per row: a lane always loads 16 bytes
     static constexpr int RPW = 64 / LPR;                      // rows per wave load instruction (4 or 8)
     static constexpr int LANE_BYTES = D_ * ES / LPR;          // bytes of a row held by one lane
@@ -338,11 +341,20 @@ struct Traits {
 
     __device__ static __forceinline__ void widen(const Raw &r, float *out)
     {
-        if constexpr (F16_) {
+        if constexpr (DT_ == kDtF16) {
             typedef _Float16 hvec __attribute__((ext_vector_type(EPV)));
             hvec h = __builtin_bit_cast(hvec, r.d);
 #pragma unroll
             for (int i = 0; i < EPV; ++i) out[i] = (float)h[i];
+        } else if constexpr (DT_ == kDtBf16) {
+            // a bfloat16 is the upper half of the binary32 of the same value
+            typedef uint32_t uvec __attribute__((ext_vector_type(EPV / 2)));
+            uvec u = __builtin_bit_cast(uvec, r.d);
+#pragma unroll
+            for (int i = 0; i < EPV / 2; ++i) {
+                out[2 * i] = __uint_as_float(u[i] << 16);
+                out[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+            }
         } else {
             typedef float fvec __attribute__((ext_vector_type(EPV)));
             fvec f = __builtin_bit_cast(fvec, r.d);

@@ -37,7 +37,40 @@ constexpr int kGqaPBytes = kGqaHeads * kGqaBlockTokens * 2;
 constexpr int kGqaWaveBytes = kGqaKBytes + 2 * kGqaPBytes;
 
 typedef _Float16 hg_h8 __attribute__((ext_vector_type(8)));
+typedef __bf16 hg_b8 __attribute__((ext_vector_type(8)));
 typedef float hg_f4 __attribute__((ext_vector_type(4)));
+
+// D += A . B on the 16x16x32 matrix-core shape; the operands are eight 16-bit values per lane,
+// fp16 or bf16 (same layout, same rate).
+template <bool BF16>
+__device__ __forceinline__ hg_f4 mfma_16x16x32(hg_u32x4 a, hg_u32x4 b, hg_f4 c)
+{
+    if constexpr (BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(hg_b8, a), __builtin_bit_cast(hg_b8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(hg_h8, a), __builtin_bit_cast(hg_h8, b), c, 0, 0, 0);
+}
+
+// Two softmax weights in [0, 1] as a packed pair of 16-bit heads (hi) and a packed pair of 16-bit
+// remainders (lo), p = hi + lo to about 22 bits (fp16) or 16 bits (bf16): two matrix-core passes
+// then carry the weights at far better than the precision of the 16-bit V they multiply.
+template <bool BF16>
+__device__ __forceinline__ void split_weights(float p0, float p1, uint32_t &hi, uint32_t &lo)
+{
+    if constexpr (BF16) {
+        typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+        const __bf16 h0 = (__bf16)p0, h1 = (__bf16)p1;
+        const __bf16 l0 = (__bf16)(p0 - (float)h0), l1 = (__bf16)(p1 - (float)h1);
+        hi = __builtin_bit_cast(uint32_t, b2{h0, h1});
+        lo = __builtin_bit_cast(uint32_t, b2{l0, l1});
+    } else {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        const _Float16 h0 = (_Float16)p0, h1 = (_Float16)p1;
+        const _Float16 l0 = (_Float16)(p0 - (float)h0), l1 = (_Float16)(p1 - (float)h1);
+        hi = __builtin_bit_cast(uint32_t, h2{h0, h1});
+        lo = __builtin_bit_cast(uint32_t, h2{l0, l1});
+    }
+}
 
 __device__ __forceinline__ float row16_max(float x)
 {
@@ -57,7 +90,7 @@ __device__ __forceinline__ void wave_lds_handover()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int MODE, bool PAGED>
+template <int MODE, bool PAGED, bool BF16>
 __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_gqa_kernel(const PartialArgs a)
 {
     constexpr int D = 128;
@@ -81,14 +114,14 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     const int h0 = hk * a.ws.group + g0;
 
     // Q as A operand: lane l holds head l%16, channels 8*(4kk + l/16)..+7 for kk = 0..3
-    hg_h8 qa[4];
+    hg_u32x4 qa[4];
     if constexpr (MODE != kModeConcat) {
-        const _Float16 *qrow = static_cast<const _Float16 *>(a.q) + ((int64_t)seq * a.ws.n_q_heads + h0 + (n < nh ? n : 0)) * D;
+        const uint16_t *qrow = static_cast<const uint16_t *>(a.q) + ((int64_t)seq * a.ws.n_q_heads + h0 + (n < nh ? n : 0)) * D;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             hg_u32x4 raw = *reinterpret_cast<const hg_u32x4 *>(qrow + 8 * (4 * kk + rg));
             if (n >= nh) raw = hg_u32x4{0u, 0u, 0u, 0u};
-            qa[kk] = __builtin_bit_cast(hg_h8, raw);
+            qa[kk] = raw;
         }
     }
 
@@ -206,7 +239,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
                 hg_u32x4 raw = *reinterpret_cast<const hg_u32x4 *>(kls + (16 * hf + n) * kGqaKRow + (4 * kk + rg) * 16);
-                s[hf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[kk], __builtin_bit_cast(hg_h8, raw), s[hf], 0, 0, 0);
+                s[hf] = mfma_16x16x32<BF16>(qa[kk], raw, s[hf]);
             }
         }
 
@@ -276,11 +309,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         for (int r = 0; r < 4; ++r) {
             const float p0 = fast_exp2(e0[r]), p1 = fast_exp2(e1[r]);
             lsum[r] += p0 + p1;
-            const _Float16 h0f = (_Float16)p0, h1f = (_Float16)p1;
-            const _Float16 l0f = (_Float16)(p0 - (float)h0f), l1f = (_Float16)(p1 - (float)h1f);
-            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-            ph[r] = __builtin_bit_cast(uint32_t, h2{h0f, h1f});
-            pl[r] = __builtin_bit_cast(uint32_t, h2{l0f, l1f});
+            split_weights<BF16>(p0, p1, ph[r], pl[r]);
         }
         // P -> LDS as [head][group g = n%4][j = 2*(n/4) + half], then read as A operand
         {
@@ -292,9 +321,8 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             }
         }
         wave_lds_handover();
-        const hg_h8 pa_hi = __builtin_bit_cast(hg_h8, *reinterpret_cast<const hg_u32x4 *>(pls + n * 64 + rg * 16));
-        const hg_h8 pa_lo =
-            __builtin_bit_cast(hg_h8, *reinterpret_cast<const hg_u32x4 *>(pls + kGqaPBytes + n * 64 + rg * 16));
+        const hg_u32x4 pa_hi = *reinterpret_cast<const hg_u32x4 *>(pls + n * 64 + rg * 16);
+        const hg_u32x4 pa_lo = *reinterpret_cast<const hg_u32x4 *>(pls + kGqaPBytes + n * 64 + rg * 16);
 
         // V: in-lane transpose of halves, then O[nb] = alpha * O[nb] + P . V[:, channel 8n + nb]
 #pragma unroll
@@ -304,9 +332,9 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj)
                 braw[jj] = __builtin_amdgcn_perm(vreg[2 * jj + 1][nb >> 1], vreg[2 * jj][nb >> 1], sel);
-            const hg_h8 b = __builtin_bit_cast(hg_h8, braw);
-            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
-            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
+            const hg_u32x4 b = braw;
+            o[nb] = mfma_16x16x32<BF16>(pa_hi, b, o[nb]);
+            o[nb] = mfma_16x16x32<BF16>(pa_lo, b, o[nb]);
         }
         if (tb_next < t1) {
             load_v(tb_next, vreg, pg1);
@@ -348,7 +376,6 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         }
     };
     auto concat_block = [&](int tb, int tb_next, hg_u32x4(&vreg)[8], float(&sv)[8]) __attribute__((always_inline)) {
-        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
         hg_u32x4 hi_raw, lo_raw;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
@@ -358,12 +385,12 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
                 const int tok = tb + 8 * rg + 2 * jj + x;
                 pj[x] = fast_exp2(sv[2 * jj + x] * kLog2e - gmax) * ((tok < t1 && n < nh) ? 1.f : 0.f);
             }
-            const _Float16 h0f = (_Float16)pj[0], h1f = (_Float16)pj[1];
-            const _Float16 l0f = (_Float16)(pj[0] - (float)h0f), l1f = (_Float16)(pj[1] - (float)h1f);
-            hi_raw[jj] = __builtin_bit_cast(uint32_t, h2{h0f, h1f});
-            lo_raw[jj] = __builtin_bit_cast(uint32_t, h2{l0f, l1f});
+            uint32_t hi_w, lo_w;
+            split_weights<BF16>(pj[0], pj[1], hi_w, lo_w);
+            hi_raw[jj] = hi_w;
+            lo_raw[jj] = lo_w;
         }
-        const hg_h8 pa_hi = __builtin_bit_cast(hg_h8, hi_raw), pa_lo = __builtin_bit_cast(hg_h8, lo_raw);
+        const hg_u32x4 pa_hi = hi_raw, pa_lo = lo_raw;
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb) {
             const uint32_t sel = (nb & 1) ? 0x07060302u : 0x05040100u;
@@ -371,9 +398,9 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj)
                 braw[jj] = __builtin_amdgcn_perm(vreg[2 * jj + 1][nb >> 1], vreg[2 * jj][nb >> 1], sel);
-            const hg_h8 b = __builtin_bit_cast(hg_h8, braw);
-            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
-            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
+            const hg_u32x4 b = braw;
+            o[nb] = mfma_16x16x32<BF16>(pa_hi, b, o[nb]);
+            o[nb] = mfma_16x16x32<BF16>(pa_lo, b, o[nb]);
         }
         if (tb_next < t1) {
             load_v(tb_next, vreg, pg1);

@@ -25,7 +25,7 @@ constexpr int kGqa64KRow = 144;  // 128 bytes + 16: 16 rows land in 16 distinct 
 constexpr int kGqa64KBytes = kGqaBlockTokens * kGqa64KRow;
 constexpr int kGqa64WaveBytes = kGqa64KBytes + 2 * kGqaPBytes;
 
-template <int MODE, bool PAGED>
+template <int MODE, bool PAGED, bool BF16>
 __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_gqa64_kernel(const PartialArgs a)
 {
     constexpr int D = 64;
@@ -51,14 +51,14 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     const int h0 = hk * a.ws.group + g0;
 
     // Q as A operand: lane l holds head l%16, channels 8*(4kk + l/16)..+7 for kk = 0, 1
-    hg_h8 qa[2];
+    hg_u32x4 qa[2];
     if constexpr (MODE != kModeConcat) {
-        const _Float16 *qrow = static_cast<const _Float16 *>(a.q) + ((int64_t)seq * a.ws.n_q_heads + h0 + (n < nh ? n : 0)) * D;
+        const uint16_t *qrow = static_cast<const uint16_t *>(a.q) + ((int64_t)seq * a.ws.n_q_heads + h0 + (n < nh ? n : 0)) * D;
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
             hg_u32x4 raw = *reinterpret_cast<const hg_u32x4 *>(qrow + 8 * (4 * kk + rg));
             if (n >= nh) raw = hg_u32x4{0u, 0u, 0u, 0u};
-            qa[kk] = __builtin_bit_cast(hg_h8, raw);
+            qa[kk] = raw;
         }
     }
 
@@ -133,14 +133,14 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     // v_perm_b32 emit a zero byte, so the masking costs nothing beyond the transpose itself.
     const uint32_t sel_even_lo = odd ? 0x0c0c0c0cu : 0x05040100u, sel_even_hi = odd ? 0x05040100u : 0x0c0c0c0cu;
     const uint32_t sel_odd_lo = odd ? 0x0c0c0c0cu : 0x07060302u, sel_odd_hi = odd ? 0x07060302u : 0x0c0c0c0cu;
-    auto v_operand = [&](const hg_u32x4(&vreg)[4], int nb) __attribute__((always_inline)) -> hg_h8 {
+    auto v_operand = [&](const hg_u32x4(&vreg)[4], int nb) __attribute__((always_inline)) -> hg_u32x4 {
         const uint32_t s_lo = (nb & 1) ? sel_odd_lo : sel_even_lo, s_hi = (nb & 1) ? sel_odd_hi : sel_even_hi;
         hg_u32x4 braw;
         braw[0] = __builtin_amdgcn_perm(vreg[2][nb >> 1], vreg[0][nb >> 1], s_lo);
         braw[1] = __builtin_amdgcn_perm(vreg[3][nb >> 1], vreg[1][nb >> 1], s_lo);
         braw[2] = __builtin_amdgcn_perm(vreg[2][nb >> 1], vreg[0][nb >> 1], s_hi);
         braw[3] = __builtin_amdgcn_perm(vreg[3][nb >> 1], vreg[1][nb >> 1], s_hi);
-        return __builtin_bit_cast(hg_h8, braw);
+        return braw;
     };
 
     auto compute_block = [&](int tb, int tb_next, hg_u32x4(&kreg)[4], hg_u32x4(&vreg)[4]) __attribute__((always_inline)) {
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
                 hg_u32x4 raw = *reinterpret_cast<const hg_u32x4 *>(kls + (16 * hf + n) * kGqa64KRow + (4 * kk + rg) * 16);
-                s[hf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[kk], __builtin_bit_cast(hg_h8, raw), s[hf], 0, 0, 0);
+                s[hf] = mfma_16x16x32<BF16>(qa[kk], raw, s[hf]);
             }
         }
 
@@ -234,11 +234,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         for (int r = 0; r < 4; ++r) {
             const float p0 = fast_exp2(e0[r]), p1 = fast_exp2(e1[r]);
             lsum[r] += p0 + p1;
-            const _Float16 h0f = (_Float16)p0, h1f = (_Float16)p1;
-            const _Float16 l0f = (_Float16)(p0 - (float)h0f), l1f = (_Float16)(p1 - (float)h1f);
-            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-            ph[r] = __builtin_bit_cast(uint32_t, h2{h0f, h1f});
-            pl[r] = __builtin_bit_cast(uint32_t, h2{l0f, l1f});
+            split_weights<BF16>(p0, p1, ph[r], pl[r]);
         }
         // P -> LDS as [head][k-group g][slot j]: token t = 16*half + n belongs to k-group (n%8)/2,
         // parity n%2, load 2*half + n/8, i.e. slot 4*(n%2) + 2*(n/8) + half: the two halves are one word
@@ -251,16 +247,15 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             }
         }
         wave_lds_handover();
-        const hg_h8 pa_hi = __builtin_bit_cast(hg_h8, *reinterpret_cast<const hg_u32x4 *>(pls + n * 64 + rg * 16));
-        const hg_h8 pa_lo =
-            __builtin_bit_cast(hg_h8, *reinterpret_cast<const hg_u32x4 *>(pls + kGqaPBytes + n * 64 + rg * 16));
+        const hg_u32x4 pa_hi = *reinterpret_cast<const hg_u32x4 *>(pls + n * 64 + rg * 16);
+        const hg_u32x4 pa_lo = *reinterpret_cast<const hg_u32x4 *>(pls + kGqaPBytes + n * 64 + rg * 16);
 
         // V: this lane's 4 tokens fill the slots of its parity in the order load 0, 2, 1, 3
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb) {
-            const hg_h8 b = v_operand(vreg, nb);
-            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
-            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
+            const hg_u32x4 b = v_operand(vreg, nb);
+            o[nb] = mfma_16x16x32<BF16>(pa_hi, b, o[nb]);
+            o[nb] = mfma_16x16x32<BF16>(pa_lo, b, o[nb]);
         }
         if (tb_next < t1) {
             load_rows(vbase, tb_next, vreg, pg1);
@@ -300,7 +295,6 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         }
     };
     auto concat_block = [&](int tb, int tb_next, hg_u32x4(&vreg)[4], float(&sv)[8]) __attribute__((always_inline)) {
-        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
         hg_u32x4 hi_raw, lo_raw;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
@@ -310,17 +304,17 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
                 const int tok = tb + 8 * rg + 2 * jj + x;
                 pj[x] = fast_exp2(sv[2 * jj + x] * kLog2e - gmax) * ((tok < t1 && n < nh) ? 1.f : 0.f);
             }
-            const _Float16 h0f = (_Float16)pj[0], h1f = (_Float16)pj[1];
-            const _Float16 l0f = (_Float16)(pj[0] - (float)h0f), l1f = (_Float16)(pj[1] - (float)h1f);
-            hi_raw[jj] = __builtin_bit_cast(uint32_t, h2{h0f, h1f});
-            lo_raw[jj] = __builtin_bit_cast(uint32_t, h2{l0f, l1f});
+            uint32_t hi_w, lo_w;
+            split_weights<BF16>(pj[0], pj[1], hi_w, lo_w);
+            hi_raw[jj] = hi_w;
+            lo_raw[jj] = lo_w;
         }
-        const hg_h8 pa_hi = __builtin_bit_cast(hg_h8, hi_raw), pa_lo = __builtin_bit_cast(hg_h8, lo_raw);
+        const hg_u32x4 pa_hi = hi_raw, pa_lo = lo_raw;
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb) {
-            const hg_h8 b = v_operand(vreg, nb);
-            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_hi, b, o[nb], 0, 0, 0);
-            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa_lo, b, o[nb], 0, 0, 0);
+            const hg_u32x4 b = v_operand(vreg, nb);
+            o[nb] = mfma_16x16x32<BF16>(pa_hi, b, o[nb]);
+            o[nb] = mfma_16x16x32<BF16>(pa_lo, b, o[nb]);
         }
         if (tb_next < t1) {
             load_rows(vbase, tb_next, vreg, pg1);

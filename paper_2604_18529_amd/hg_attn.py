@@ -22,7 +22,7 @@ import torch
 from . import _build
 
 HG_OK = 0
-HG_F16, HG_F32 = 0, 1
+HG_F16, HG_F32, HG_BF16 = 0, 1, 2
 
 
 class HgError(RuntimeError):
@@ -152,8 +152,8 @@ def make_desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seq_lens, scale
 
     Contiguous cache: k, v are [B, Hkv, N, d].  Paged cache (``block_table`` int32 [B, max_blocks]
     on the device): k, v are the physical pools [n_blocks, Hkv, block_tokens, d]."""
-    if q.dtype not in (torch.float16, torch.float32) or k.dtype != q.dtype or v.dtype != q.dtype:
-        raise TypeError("q, k, v must share dtype float16 or float32")
+    if q.dtype not in (torch.float16, torch.float32, torch.bfloat16) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise TypeError("q, k, v must share dtype float16, bfloat16 or float32")
     if q.dim() != 3 or k.dim() != 4 or v.dim() != 4 or k.shape != v.shape:
         raise ValueError("q must be [B,Hq,d]; k and v [B,Hkv,N,d] (or [blocks,Hkv,block_tokens,d]) of equal shape")
     if not q.is_contiguous():
@@ -179,7 +179,7 @@ def make_desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seq_lens, scale
         bt_ptr, block_tokens, max_blocks = block_table.data_ptr(), int(k.shape[2]), int(block_table.shape[1])
     desc = _Desc(
         q.data_ptr(), k.data_ptr(), v.data_ptr(), k.stride(0), k.stride(1), k.stride(2), seq.ctypes.data,
-        B, Hq, k.shape[1], d, HG_F16 if q.dtype == torch.float16 else HG_F32,
+        B, Hq, k.shape[1], d, {torch.float16: HG_F16, torch.float32: HG_F32, torch.bfloat16: HG_BF16}[q.dtype],
         float(scale if scale is not None else 1.0 / math.sqrt(d)), bt_ptr, block_tokens, max_blocks,
     )
     return desc, (q, k, v, seq, block_table)

@@ -37,7 +37,7 @@ class WorkloadSpec:
     n_q_heads: int
     n_kv_heads: int
     head_dim: int
-    dtype: str  # "f16" | "f32"
+    dtype: str  # "f16" | "f32" | "bf16"
     n_min: int  # context length is uniform in [n_min, n_max]
     n_max: int
     partition: str  # "at" | "half" | "ratios" | "dirichlet" | "none"
@@ -66,6 +66,8 @@ WORKLOADS: List[WorkloadSpec] = [
 EXTRA_WORKLOADS: List[WorkloadSpec] = [
     # fp16, head_dim 64, 4 query heads per KV head: the matrix-core kernel for 128-byte rows
     WorkloadSpec("gqa4-d64-b8-64k", 8, 32, 8, 64, "f16", 65536, 65536, "dirichlet", 4, seed=5),
+    # bf16, head_dim 128, 4 query heads per KV head (the head structure of an 8B Llama-class model)
+    WorkloadSpec("gqa4-d128-bf16-b8-32k", 8, 32, 8, 128, "bf16", 32768, 32768, "dirichlet", 4, seed=6),
 ]
 ALL_WORKLOADS: List[WorkloadSpec] = WORKLOADS + EXTRA_WORKLOADS
 
@@ -89,7 +91,7 @@ class Workload:
 
 
 def _torch_dtype(name: str) -> torch.dtype:
-    return {"f16": torch.float16, "f32": torch.float32}[name]
+    return {"f16": torch.float16, "f32": torch.float32, "bf16": torch.bfloat16}[name]
 
 
 def _stream_seed(seed: int, *keys: int) -> int:

@@ -20,7 +20,12 @@ LSE_TOL = 1e-3
 
 
 def to_np(t: torch.Tensor) -> np.ndarray:
-    return t.detach().cpu().numpy()
+    """Host copy as numpy; bfloat16 tensors come back as their uint16 bit patterns, which is how
+    the oracle takes that storage type."""
+    t = t.detach().cpu()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
 
 
 def kv_np(w):

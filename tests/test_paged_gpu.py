@@ -58,7 +58,7 @@ def _run_paged(w, block_tokens, what, ranges=None, gp=None, routes=True):
 
 @pytest.mark.parametrize("block_tokens", [16, 64, 1024])
 @pytest.mark.parametrize("dtype,d,group", [("f16", 128, 1), ("f16", 128, 8), ("f32", 64, 1), ("f16", 64, 2), ("f32", 128, 4),
-                                            ("f16", 128, 16), ("f16", 128, 5), ("f16", 64, 4), ("f16", 64, 9)])
+                                            ("f16", 128, 16), ("f16", 128, 5), ("f16", 64, 4), ("f16", 64, 9), ("bf16", 128, 4), ("bf16", 64, 1), ("bf16", 64, 6)])
 def test_paged_matches_contiguous(dtype, d, group, block_tokens):
     spec = W.WorkloadSpec("paged", 3, 2 * group, 2, d, dtype, 1, 3000, "ratios", 3, seed=70 + group)
     w = W.make_workload(spec, DEV)

@@ -25,7 +25,7 @@ def _sample_pairs(spec, n, seed):
     return sorted(pairs)
 
 
-@pytest.mark.parametrize("index", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5, 6])
 def test_full_size_sampled_against_oracle(index):
     hg.hg_attn_set_span_tokens(0)
     spec = W.ALL_WORKLOADS[index]

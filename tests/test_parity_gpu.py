@@ -46,7 +46,7 @@ def test_reduced_configs(spec, tile):
     run_all_and_check(w, what="%s tile=%d" % (spec.name, tile))
 
 
-@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("dtype", ["f16", "f32", "bf16"])
 @pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("group", [1, 2, 3, 4, 5, 8, 16])
 def test_every_kernel_instance(dtype, d, group):

@@ -42,13 +42,13 @@ def _grouped_ranges(rng, seq_lens, max_per_seq):
     return ranges, gp
 
 
-@pytest.mark.parametrize("case", list(range(96)) + list(range(500, 516)))
+@pytest.mark.parametrize("case", list(range(96)) + list(range(100, 148)) + list(range(500, 516)))
 def test_random_case(case):
-    """Cases below 500 are short (every code path of a workgroup, many combinations); cases from
-    500 are long enough for several spans per stream and for the two-stage selection."""
+    """Cases below 500 are short (every code path of a workgroup, many combinations; bf16 joins
+    from case 100 on); cases from 500 are long enough for several spans per stream and for the two-stage selection."""
     rng = np.random.default_rng(1000 + case)
     big = case >= 500
-    dtype = ["f16", "f32"][int(rng.integers(2))]
+    dtype = ["f16", "f32", "bf16"][int(rng.integers(2)) if case < 96 else case % 3]  # (the first 96 keep their draws)
     d = [64, 128][int(rng.integers(2))]
     group = int(rng.choice([1, 4, 8, 3] if big else [1, 1, 2, 3, 4, 6, 8, 16, 17]))
     hkv = int(rng.integers(1, 3 if big else 4))
