@@ -6,6 +6,7 @@ The product path (the HIP library and its binding) never does.
 from .oracle import (  # noqa: F401
     attn_concat,
     attn_full,
+    attn_gather,
     attn_logits,
     attn_merge,
     attn_partial,

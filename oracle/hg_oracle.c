@@ -28,6 +28,9 @@
  *                     V rows into one (m, l, O).  The logits are an INPUT in fp32 (the decision
  *                     which tokens are kept is taken on those fp32 values, as on the GPU); ties
  *                     go to the lower column.
+ *   hgo_attn_gather   statistics over a LISTED token set per (group, query head): what an
+ *                     executor computes once a selector has named the tokens (Pre-QK^T selection,
+ *                     Section 4.3.2; Section 4.6 step 1).
  *
  * All arithmetic is fp64, plain sequential sums in token order, libm exp/log.  Inputs are the
  * caller's fp16 / bf16 / fp32 bit patterns widened exactly; nothing is re-rounded.  The only parallelism
@@ -352,6 +355,60 @@ int hgo_attn_select(const hgo_problem *p, const hgo_range *ranges, int32_t n_ran
         }
     }
     free(pre);
+    return 0;
+}
+
+/* ---- 2d. statistics over a LISTED token set ------------------------------------------------- */
+
+/* The executor's side of a selection decided elsewhere: under Pre-QK^T selection the token
+ * selector names the tokens before any logit exists and the executor computes logits and value
+ * sums for exactly those (Section 4.3.2; Section 4.6 step 1); the same holds for a Post-QK^T
+ * list taken with a proxy query (Section 4.2.1) and evaluated with the true one.
+ *
+ * group_seq: [n_groups] sequence of each group.  index: int32 [n_groups][Hq][max_k] token
+ * positions of that sequence in any order; negative entries are padding; a token listed twice
+ * counts twice.  Per (group, head): m = max over the listed tokens of s_t, l = sum exp(s_t - m),
+ * O = sum exp(s_t - m) v_t, all with this problem's q; (-inf, 0, 0) for a list without tokens.
+ * Returns -4 when an entry is not below the sequence's length. */
+int hgo_attn_gather(const hgo_problem *p, const int32_t *group_seq, int32_t n_groups, const int32_t *index,
+                    int32_t max_k, double *m, double *l, double *o)
+{
+    int rc = check_problem(p);
+    if (rc) return rc;
+    if (n_groups < 0 || max_k < 1) return -2;
+    if (n_groups && (!group_seq || !index || !m || !l || !o)) return -1;
+    for (int g = 0; g < n_groups; ++g) {
+        if (group_seq[g] < 0 || group_seq[g] >= p->B) return -4;
+        for (int64_t i = 0; i < (int64_t)p->Hq * max_k; ++i)
+            if (index[(int64_t)g * p->Hq * max_k + i] >= p->seq_lens[group_seq[g]]) return -4;
+    }
+    double *s = (double *)malloc(sizeof(double) * (size_t)max_k);
+    if (!s) return -7;
+    for (int g = 0; g < n_groups; ++g) {
+        int b = group_seq[g];
+        for (int h = 0; h < p->Hq; ++h) {
+            int64_t gh = (int64_t)g * p->Hq + h;
+            const int32_t *idx = index + gh * max_k;
+            double *dst = o + gh * p->d;
+            for (int c = 0; c < p->d; ++c) dst[c] = 0.0;
+            double mx = -INFINITY, lt = 0.0;
+            for (int i = 0; i < max_k; ++i)
+                if (idx[i] >= 0) {
+                    s[i] = logit(p, b, h, idx[i]);
+                    if (s[i] > mx) mx = s[i];
+                }
+            for (int i = 0; i < max_k; ++i)
+                if (idx[i] >= 0) {
+                    double w = exp(s[i] - mx);
+                    int64_t voff = kv_row(p, b, h, idx[i]);
+                    lt += w;
+                    for (int c = 0; c < p->d; ++c) dst[c] += w * load_elem(p->v, voff + c, p->dtype);
+                }
+            m[gh] = mx;
+            l[gh] = lt;
+        }
+    }
+    free(s);
     return 0;
 }
 

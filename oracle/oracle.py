@@ -71,6 +71,8 @@ def _load():
         lib.hgo_attn_select.argtypes = [P, ctypes.POINTER(_Range), ctypes.c_int32, dp, dp, ctypes.c_int32, ctypes.c_int32,
                                         dp, dp, dp, dp]
         lib.hgo_attn_select.restype = ctypes.c_int
+        lib.hgo_attn_gather.argtypes = [P, dp, ctypes.c_int32, dp, ctypes.c_int32, dp, dp, dp]
+        lib.hgo_attn_gather.restype = ctypes.c_int
         for f in (lib.hgo_attn_full, lib.hgo_attn_partial, lib.hgo_attn_merge, lib.hgo_attn_concat, lib.hgo_attn_logits,
                   lib.hgo_max_threads):
             f.restype = ctypes.c_int
@@ -212,3 +214,22 @@ def attn_select(q, k, v, seq_lens, scale, ranges, logits, group_ptr, top_k):
                                    sel.ctypes.data, m.ctypes.data, l.ctypes.data, o.ctypes.data), "attn_select")
     del keep
     return sel, m, l, o
+
+
+def attn_gather(q, k, v, seq_lens, scale, group_seq, index):
+    """Statistics over listed tokens: index int32 [G,Hq,max_k] positions of sequence group_seq[g]
+    (negative = padding, duplicates count as often as listed).
+    Returns (m [G,Hq], l [G,Hq], o [G,Hq,d]) in float64."""
+    prob, keep = _problem(q, k, v, seq_lens, scale)
+    gs = np.ascontiguousarray(group_seq, dtype=np.int32)
+    idx = np.ascontiguousarray(index, dtype=np.int32)
+    G = gs.size
+    if idx.ndim != 3 or idx.shape[:2] != (G, prob.Hq) or idx.shape[2] < 1:
+        raise ValueError("index must be [n_groups, Hq, max_k]")
+    m = np.zeros((G, prob.Hq), dtype=np.float64)
+    l = np.zeros((G, prob.Hq), dtype=np.float64)
+    o = np.zeros((G, prob.Hq, prob.d), dtype=np.float64)
+    _check(_load().hgo_attn_gather(ctypes.byref(prob), gs.ctypes.data, G, idx.ctypes.data, int(idx.shape[2]),
+                                   m.ctypes.data, l.ctypes.data, o.ctypes.data), "attn_gather")
+    del keep
+    return m, l, o

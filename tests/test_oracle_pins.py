@@ -525,3 +525,118 @@ def test_select_everything_equals_partial_and_select_one_is_argmax():
         j = int(np.argmax(lg[h]))
         assert sel1[0, h, 0] == j and l1[0, h] == 1.0 and m1[0, h] == float(lg[h, j])
         assert np.array_equal(o1[0, h], v[0, 0, j].astype(np.float64))
+
+
+# ---- statistics over a listed token set --------------------------------------------------------
+
+
+def _lists(rng, G, Hq, max_k, seq_len_of_group, pad_frac=0.3, dup=True):
+    idx = np.full((G, Hq, max_k), -1, dtype=np.int32)
+    for g in range(G):
+        for h in range(Hq):
+            n = seq_len_of_group[g]
+            row = rng.randint(0, n, size=max_k) if dup else rng.permutation(n)[:max_k]
+            row = np.asarray(row, dtype=np.int32)
+            if row.size < max_k:
+                row = np.concatenate([row, np.full(max_k - row.size, -1, np.int32)])
+            row[rng.random_sample(max_k) < pad_frac] = -1 - rng.randint(0, 5)  # any negative value pads
+            idx[g, h] = row
+    return idx
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_gather_brute_force_with_duplicates_padding_and_gqa(dtype):
+    """Listed-token statistics against the definition in rational arithmetic.  Catches: a list
+    read for the wrong (group, head), the wrong sequence or KV head behind a group, padding that
+    is counted, a duplicate that is dropped, m taken over the wrong set."""
+    B, Hq, Hkv, N, d = 3, 4, 2, 9, 4
+    q, k, v = _case(31, B, Hq, Hkv, N, d, dtype)
+    seq_lens = [9, 4, 7]
+    group_seq = [2, 0, 0, 1]
+    rng = RNG(32)
+    idx = _lists(rng, 4, Hq, 6, [seq_lens[b] for b in group_seq])
+    idx[1, 2] = -1  # a list without tokens
+    m, l, o = oracle.attn_gather(q, k, v, seq_lens, 0.5, group_seq, idx)
+    G = Hq // Hkv
+    for g, b in enumerate(group_seq):
+        for h in range(Hq):
+            toks = [int(t) for t in idx[g, h] if t >= 0]
+            if not toks:
+                assert m[g, h] == -np.inf and l[g, h] == 0 and not o[g, h].any()
+                continue
+            ref, mx, den, _ = _brute(q[b, h], k[b, h // G], v[b, h // G], 0.5, toks)
+            assert abs(m[g, h] - mx) < 1e-14
+            assert abs(l[g, h] - den) < 1e-13
+            assert np.allclose(o[g, h] / l[g, h], ref, rtol=0, atol=1e-13)
+
+
+def test_gather_zero_query_counts_listings_and_bitplanes_exactly():
+    """q = 0: l is the number of listings (duplicates included) and, with V[t][c] = bit c of t,
+    O[c] is the number of listed tokens whose bit c is set -- exact integers that pin which rows
+    were read."""
+    B, Hq, Hkv, N, d = 2, 2, 1, 300, 16
+    q = np.zeros((B, Hq, d), np.float16)
+    k = _rand(RNG(33), (B, Hkv, N, d), np.float16)
+    t = np.arange(N)
+    v = ((t[:, None] >> np.arange(d)[None, :]) & 1).astype(np.float16)
+    v = np.broadcast_to(v, (B, Hkv, N, d)).copy()
+    idx = _lists(RNG(34), 2, Hq, 50, [300, 200])
+    m, l, o = oracle.attn_gather(q, k, v, [300, 200], 0.25, [0, 1], idx)
+    for g in range(2):
+        for h in range(Hq):
+            toks = idx[g, h][idx[g, h] >= 0]
+            assert m[g, h] == 0.0 and l[g, h] == toks.size
+            want = ((toks[:, None] >> np.arange(d)[None, :]) & 1).sum(axis=0)
+            assert np.array_equal(o[g, h], want.astype(np.float64))
+
+
+def test_gather_of_a_whole_range_equals_partial_and_order_is_free():
+    """The list [begin, end) in any order gives the range's statistics; one listed token gives
+    (s, 1, V); listing every token twice doubles l and O and leaves m and O/l alone."""
+    B, Hq, Hkv, N, d = 1, 4, 2, 64, 8
+    q, k, v = _case(35, B, Hq, Hkv, N, d, np.float16)
+    pm, pl, po = oracle.attn_partial(q, k, v, [64], 0.3, [(0, 10, 50)])
+    rng = RNG(36)
+    idx = np.stack([rng.permutation(np.arange(10, 50)) for _ in range(Hq)]).astype(np.int32)[None]
+    m, l, o = oracle.attn_gather(q, k, v, [64], 0.3, [0], idx)
+    assert np.array_equal(m, pm)
+    assert np.abs(l - pl).max() < 1e-12 and np.abs(o - po).max() < 1e-12
+    m2, l2, o2 = oracle.attn_gather(q, k, v, [64], 0.3, [0], np.concatenate([idx, idx[:, :, ::-1]], axis=2))
+    assert np.array_equal(m2, pm)
+    assert np.abs(l2 - 2 * pl).max() < 1e-12 and np.abs(o2 - 2 * po).max() < 1e-12
+    one = np.full((1, Hq, 3), -1, np.int32)
+    one[0, :, 1] = [7, 0, 63, 7]
+    m1, l1, o1 = oracle.attn_gather(q, k, v, [64], 0.3, [0], one)
+    lg = oracle.attn_logits(q, k, v, [64], 0.3, [(0, 0, 64)])
+    for h in range(Hq):
+        tkn = one[0, h, 1]
+        assert m1[0, h] == lg[h, tkn] and l1[0, h] == 1.0
+        assert np.array_equal(o1[0, h], v[0, h // 2, tkn].astype(np.float64))
+
+
+def test_gather_over_a_selection_reproduces_the_selection_triple():
+    """The kept-token list that the Post-QK^T selection writes, evaluated by the listed-token
+    routine with the same query, gives the selection's own triple (up to the fp32 rounding of the
+    logits the selection was handed)."""
+    B, Hq, Hkv, N, d = 2, 4, 4, 80, 8
+    q, k, v = _case(37, B, Hq, Hkv, N, d, np.float16)
+    seq_lens = [80, 60]
+    ranges = [(0, 0, 30), (0, 40, 80), (1, 5, 60)]
+    gp = [0, 2, 3]
+    lg = oracle.attn_logits(q, k, v, seq_lens, 0.35, ranges).astype(np.float32)
+    sel, sm, sl, so = oracle.attn_select(q, k, v, seq_lens, 0.35, ranges, lg, gp, 12)
+    m, l, o = oracle.attn_gather(q, k, v, seq_lens, 0.35, [0, 1], sel)
+    assert np.abs(m - sm).max() < 1e-6
+    assert np.abs(o / l[..., None] - so / sl[..., None]).max() < 1e-6
+    assert np.abs(m + np.log(l) - sm - np.log(sl)).max() < 1e-6
+
+
+def test_gather_rejects_tokens_past_the_sequence_end():
+    q, k, v = _case(38, 2, 2, 2, 10, 4)
+    idx = np.zeros((1, 2, 3), np.int32)
+    idx[0, 1, 2] = 6
+    with pytest.raises(ValueError):
+        oracle.attn_gather(q, k, v, [10, 6], 1.0, [1], idx)
+    oracle.attn_gather(q, k, v, [10, 6], 1.0, [0], idx)
+    with pytest.raises(ValueError):
+        oracle.attn_gather(q, k, v, [10, 6], 1.0, [2], idx)
