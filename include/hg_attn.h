@@ -228,6 +228,28 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
                          float *o, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * hg_attn_gather -- attention statistics over a LISTED set of tokens per (group, query head): the
+ * executor's side of a selection that was decided elsewhere.  Under Pre-QK^T selection (Section
+ * 4.3.2; Section 4.6 step 1) the token selector names the tokens before the logits exist and the
+ * executor computes logits and value sums for exactly those; the same call serves a Post-QK^T
+ * selection taken with another query (the list hg_attn_select wrote for a proxy query, Section
+ * 4.2.1, evaluated here with the true query).
+ *
+ *   group_seq  HOST   [n_groups]: the sequence each group's tokens belong to.
+ *   index      DEVICE int32 [n_groups][n_q_heads][max_k]: token positions of sequence
+ *              group_seq[g], in any order; negative entries are padding (the layout and padding
+ *              of hg_attn_select's `sel`).  Entries are not checked (device memory): every
+ *              non-negative one must be below seq_lens[group_seq[g]].  A token listed twice
+ *              counts twice.
+ *   max_k      1 .. 1048576.
+ *   m, l, o    as hg_attn_partial writes them, one triple per (group, head); a list without
+ *              tokens yields (-inf, 0, 0).
+ */
+hg_status hg_attn_gather_workspace_size(int32_t n_groups, size_t *bytes);
+hg_status hg_attn_gather(const hg_attn_desc *desc, const int32_t *group_seq, int32_t n_groups, const int32_t *index,
+                         int32_t max_k, float *m, float *l, float *o, void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * Feedback scheduler policy (Algorithm 1): host-only integer logic that sizes the offloaded
  * executor's work from the measured stage latencies.  One call = one tick.
  *

@@ -5,6 +5,7 @@
 
 #include "hg_combine.hip.h"
 #include "hg_common.hip.h"
+#include "hg_gather.hip.h"
 #include "hg_select.hip.h"
 #include "hg_stream_gqa.hip.h"
 #include "hg_stream_gqa64.hip.h"
@@ -985,6 +986,70 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
     }
     launch_select<kSelectFromCands>(desc, sa, grid, sp.fast_final, stream);
     return launch_status("selection kernel (final)");
+}
+
+hg_status hg_attn_gather_workspace_size(int32_t n_groups, size_t *bytes)
+{
+    if (!bytes) return HG_ERR_NULL;
+    if (n_groups < 0) return HG_ERR_SHAPE;
+    *bytes = merge_ws_bytes(n_groups);
+    return HG_OK;
+}
+
+hg_status hg_attn_gather(const hg_attn_desc *desc, const int32_t *group_seq, int32_t n_groups, const int32_t *index,
+                         int32_t max_k, float *m, float *l, float *o, void *workspace, size_t ws_bytes, void *stream_v)
+{
+    hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    if (n_groups < 0 || n_groups > 65535 || max_k < 1 || max_k > (1 << 20)) return HG_ERR_SHAPE;
+    if (n_groups == 0) return HG_OK;
+    if (!group_seq || !index || !m || !l || !o) return HG_ERR_NULL;
+    for (int32_t i = 0; i < n_groups; ++i)
+        if (group_seq[i] < 0 || group_seq[i] >= desc->batch) return HG_ERR_RANGE;
+    st = check_workspace(workspace, ws_bytes, merge_ws_bytes(n_groups));
+    if (st != HG_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+
+    GatherArgs ga;
+    std::memset(&ga, 0, sizeof(ga));
+    ga.q = desc->q;
+    ga.k = desc->k;
+    ga.v = desc->v;
+    ga.stride_b = desc->stride_b;
+    ga.stride_h = desc->stride_h;
+    ga.stride_t = desc->stride_t;
+    fill_pages(desc, ga.pages);
+    ga.index = index;
+    ga.m = m;
+    ga.l = l;
+    ga.o = o;
+    ga.max_k = max_k;
+    ga.n_q_heads = desc->n_q_heads;
+    ga.group = desc->n_q_heads / desc->n_kv_heads;
+    ga.qscale = desc->scale * kLog2e;
+    // the sequences travel like a group CSR (n_groups + 1 entries; the last one is unused)
+    std::vector<int32_t> seqs(group_seq, group_seq + n_groups);
+    seqs.push_back(0);
+    st = stage_groups(seqs.data(), n_groups, static_cast<int32_t *>(workspace), stream, ga.seqs);
+    if (st != HG_OK) return st;
+    dim3 grid((unsigned)n_groups, (unsigned)desc->n_q_heads);
+    const dim3 block(256);
+    if (desc->head_dim == 128) {
+        if (desc->dtype == HG_F16)
+            hipLaunchKernelGGL((hg_gather_kernel<Traits<128, kDtF16>>), grid, block, 0, stream, ga);
+        else if (desc->dtype == HG_BF16)
+            hipLaunchKernelGGL((hg_gather_kernel<Traits<128, kDtBf16>>), grid, block, 0, stream, ga);
+        else
+            hipLaunchKernelGGL((hg_gather_kernel<Traits<128, kDtF32>>), grid, block, 0, stream, ga);
+    } else {
+        if (desc->dtype == HG_F16)
+            hipLaunchKernelGGL((hg_gather_kernel<Traits<64, kDtF16>>), grid, block, 0, stream, ga);
+        else if (desc->dtype == HG_BF16)
+            hipLaunchKernelGGL((hg_gather_kernel<Traits<64, kDtBf16>>), grid, block, 0, stream, ga);
+        else
+            hipLaunchKernelGGL((hg_gather_kernel<Traits<64, kDtF32>>), grid, block, 0, stream, ga);
+    }
+    return launch_status("gather kernel");
 }
 
 hg_status hg_attn_merge_workspace_size(int32_t n_groups, size_t *bytes)

@@ -81,6 +81,8 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_partial.argtypes = [D, R, i32, vp, vp, vp, vp, sz, vp]
     lib.hg_attn_merge_workspace_size.argtypes = [i32, ctypes.POINTER(sz)]
     lib.hg_attn_merge.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.hg_attn_gather_workspace_size.argtypes = [i32, ctypes.POINTER(sz)]
+    lib.hg_attn_gather.argtypes = [ctypes.POINTER(_Desc), vp, i32, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.hg_attn_merge2_workspace_size.argtypes = [i32, ctypes.POINTER(sz)]
     lib.hg_attn_merge2.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.hg_attn_logits_workspace_size.argtypes = [D, R, i32, ctypes.POINTER(sz)]
@@ -100,7 +102,7 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
     for name in (
         "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_merge_workspace_size", "hg_attn_merge",
-        "hg_attn_merge2_workspace_size", "hg_attn_merge2",
+        "hg_attn_merge2_workspace_size", "hg_attn_merge2", "hg_attn_gather_workspace_size", "hg_attn_gather",
         "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_span_tokens",
         "hg_attn_profile_start", "hg_attn_profile_stop", "hg_attn_calibration_copy",
         "hg_sched_init", "hg_sched_step", "hg_attn_logits_workspace_size", "hg_attn_logits", "hg_attn_select_workspace_size", "hg_attn_select", "hg_attn_concat_workspace_size", "hg_attn_concat",
@@ -487,6 +489,38 @@ def hg_attn_select(q, k, v, seq_lens, ranges, logits, group_ptr, top_k, scale=No
     _check(st, "hg_attn_select")
     del keep
     return sel, m, l, o
+
+
+def hg_attn_gather(q, k, v, seq_lens, group_seq, index, scale=None, *, workspace=None, stream=None, desc=None,
+                   block_table=None):
+    """Statistics over listed tokens: index int32 [G,Hq,max_k] (negative = padding) of sequence
+    group_seq[g].  Returns (m [G,Hq], l [G,Hq], o [G,Hq,d])."""
+    lib = load_library()
+    if desc is None:
+        desc, keep = make_desc(q, k, v, seq_lens, scale, block_table)
+    else:
+        keep = None
+    gs = np.ascontiguousarray(group_seq, dtype=np.int32)
+    G = gs.size
+    Hq, d = q.shape[1], q.shape[2]
+    if index.dtype != torch.int32 or not index.is_contiguous() or index.dim() != 3 or tuple(index.shape[:2]) != (G, Hq):
+        raise ValueError("index must be contiguous int32 [n_groups, Hq, max_k]")
+    dev = q.device
+    m = torch.empty((G, Hq), dtype=torch.float32, device=dev)
+    l = torch.empty((G, Hq), dtype=torch.float32, device=dev)
+    o = torch.empty((G, Hq, d), dtype=torch.float32, device=dev)
+    if workspace is None:
+        sz = ctypes.c_size_t()
+        _check(lib.hg_attn_gather_workspace_size(G, ctypes.byref(sz)), "hg_attn_gather_workspace_size")
+        workspace, ws_bytes = _workspace(sz.value, dev, None)
+    else:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        st = lib.hg_attn_gather(ctypes.byref(desc), gs.ctypes.data, G, _ptr(index), int(index.shape[2]), _ptr(m), _ptr(l),
+                                _ptr(o), _ptr(workspace), ws_bytes, _stream_handle(stream))
+    _check(st, "hg_attn_gather")
+    del keep
+    return m, l, o
 
 
 def hg_sched_init(k_min: int) -> HgSchedState:

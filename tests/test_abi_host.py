@@ -107,6 +107,30 @@ def test_full_and_merge_reject_bad_arguments(lib):
     assert lib.hg_attn_merge(FAKE, FAKE, FAKE, big.ctypes.data, 999, 4, 128, FAKE, None, None, 0, None) == -5
 
 
+def test_gather_rejects_bad_arguments_before_any_launch(lib):
+    d = _desc([10, 20])
+    seqs = np.array([0, 1, 1], dtype=np.int32)
+
+    def call(desc=d, gs=seqs.ctypes.data, n=3, index=FAKE, max_k=8, m=FAKE, l=FAKE, o=FAKE, ws=None, ws_bytes=0):
+        return lib.hg_attn_gather(ctypes.byref(desc), gs, n, index, max_k, m, l, o, ws, ws_bytes, None)
+
+    assert call(desc=_desc([10, 20], dtype=9)) == -3
+    assert call(desc=_desc([10, 20], d=80)) == -2
+    assert call(max_k=0) == -2 and call(max_k=(1 << 20) + 1) == -2 and call(n=-1) == -2 and call(n=70000) == -2
+    assert call(index=None) == -1 and call(gs=None) == -1 and call(m=None) == -1 and call(o=None) == -1
+    for bad in ([0, 2, 1], [-1, 0, 0]):
+        b = np.array(bad, dtype=np.int32)
+        assert call(gs=b.ctypes.data) == -4
+    assert call(n=0, index=None, gs=None, m=None, l=None, o=None) == 0  # nothing to do
+    many = np.zeros(1000, dtype=np.int32)
+    sz = ctypes.c_size_t()
+    assert lib.hg_attn_gather_workspace_size(1000, ctypes.byref(sz)) == 0 and sz.value >= 4000
+    assert lib.hg_attn_gather_workspace_size(3, ctypes.byref(sz)) == 0 and sz.value == 0
+    assert call(gs=many.ctypes.data, n=1000) == -5
+    assert lib.hg_attn_gather_workspace_size(-1, ctypes.byref(sz)) == -2
+    assert lib.hg_attn_gather_workspace_size(3, None) == -1
+
+
 def _plan(lib, desc, ranges):
     packed = B.pack_ranges(ranges)
     tile, n = ctypes.c_int32(), ctypes.c_int64()
