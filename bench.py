@@ -161,6 +161,28 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W, routes=T
         pq_select_ms, _ = _time_steps(postqk_select, max(steps // 4, 1), max(warmup // 4, 1), torch)
         pq_rest_ms, _ = _time_steps(postqk_rest, max(steps // 4, 1), max(warmup // 4, 1), torch)
 
+        # Pre-QK^T flow: the tokens of the offloaded 80 % are named up front (a seeded stand-in for
+        # the selector: 128 distinct positions per (sequence, head)); the executor evaluates exactly
+        # those with hg_attn_gather; resident 20 % and merge as above
+        lists = torch.from_numpy(W.listed_tokens([e for (_, _, e) in old], Hq, top_k, seed=11)).to(dev)
+        seq_of_group = list(range(spec.batch))
+
+        gm = torch.empty((spec.batch, Hq), dtype=torch.float32, device=dev)
+        gl = torch.empty((spec.batch, Hq), dtype=torch.float32, device=dev)
+        go = torch.empty((spec.batch, Hq, d), dtype=torch.float32, device=dev)
+
+        def preqk_gather():
+            return hg.hg_attn_gather(w.q, w.k, w.v, w.seq_lens, seq_of_group, lists, w.scale, m=gm, l=gl, o=go,
+                                     workspace=ws, desc=desc)
+
+        def preqk_step():
+            m1, l1, o1 = preqk_gather()
+            m2, l2, o2 = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, p_new, w.scale, workspace=nws, desc=desc)
+            hg.hg_attn_merge2(m1, l1, o1, one_each, m2, l2, o2, one_each, out=out, lse=lse)
+
+        pre_gather_ms, _ = _time_steps(preqk_gather, max(steps // 4, 1), max(warmup // 4, 1), torch)
+        pre_step_ms, _ = _time_steps(preqk_step, max(steps // 4, 1), max(warmup // 4, 1), torch)
+
         # the same cache as a paged pool (16-token blocks in shuffled physical order), same step
         paged = {}
         for bt in (16, 256):
@@ -184,6 +206,12 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W, routes=T
                 "select_us": pq_select_ms * 1e3,
                 "select_resident_merge_us": pq_rest_ms * 1e3,
                 "us": (pq_logits_ms + pq_rest_ms) * 1e3,
+            },
+            "pre_qk_route": {
+                "offloaded_fraction": 0.8,
+                "listed_tokens": top_k,
+                "gather_us": pre_gather_ms * 1e3,
+                "us": pre_step_ms * 1e3,
             },
             "paged_cache": paged,
             "concat_route": {
@@ -262,7 +290,7 @@ def main():
     ap.add_argument("--others", type=str, default="0,2,3,4", help="comma list of further workloads to time ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-routes", action="store_true",
-                    help="time the step and the unsplit path only (skips the concat, Post-QK^T and paged-cache timings)")
+                    help="time the step and the unsplit path only (skips the concat, Post-QK^T, Pre-QK^T and paged-cache timings)")
     ap.add_argument("--span-tokens", type=int, default=0, help="force the span length (tuning)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run the library's plain 1 GiB device copy three times (known traffic: the "
@@ -344,6 +372,7 @@ def main():
         "full_path": {"us": head["full_path_us"], "gbps": head["full_path_gbps"]},
         "concat_route": head.get("concat_route"),
         "post_qk_route": head.get("post_qk_route"),
+        "pre_qk_route": head.get("pre_qk_route"),
         "paged_cache": head.get("paged_cache"),
         "other_workloads": others,
         "paper_context": PAPER_CONTEXT,

@@ -491,8 +491,8 @@ def hg_attn_select(q, k, v, seq_lens, ranges, logits, group_ptr, top_k, scale=No
     return sel, m, l, o
 
 
-def hg_attn_gather(q, k, v, seq_lens, group_seq, index, scale=None, *, workspace=None, stream=None, desc=None,
-                   block_table=None):
+def hg_attn_gather(q, k, v, seq_lens, group_seq, index, scale=None, *, m=None, l=None, o=None, workspace=None,
+                   stream=None, desc=None, block_table=None):
     """Statistics over listed tokens: index int32 [G,Hq,max_k] (negative = padding) of sequence
     group_seq[g].  Returns (m [G,Hq], l [G,Hq], o [G,Hq,d])."""
     lib = load_library()
@@ -506,9 +506,12 @@ def hg_attn_gather(q, k, v, seq_lens, group_seq, index, scale=None, *, workspace
     if index.dtype != torch.int32 or not index.is_contiguous() or index.dim() != 3 or tuple(index.shape[:2]) != (G, Hq):
         raise ValueError("index must be contiguous int32 [n_groups, Hq, max_k]")
     dev = q.device
-    m = torch.empty((G, Hq), dtype=torch.float32, device=dev)
-    l = torch.empty((G, Hq), dtype=torch.float32, device=dev)
-    o = torch.empty((G, Hq, d), dtype=torch.float32, device=dev)
+    if m is None:
+        m = torch.empty((G, Hq), dtype=torch.float32, device=dev)
+    if l is None:
+        l = torch.empty((G, Hq), dtype=torch.float32, device=dev)
+    if o is None:
+        o = torch.empty((G, Hq, d), dtype=torch.float32, device=dev)
     if workspace is None:
         sz = ctypes.c_size_t()
         _check(lib.hg_attn_gather_workspace_size(G, ctypes.byref(sz)), "hg_attn_gather_workspace_size")

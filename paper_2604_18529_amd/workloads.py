@@ -252,6 +252,29 @@ def proxy_query(q: torch.Tensor, cosine: float, seed: int) -> torch.Tensor:
     return (mixed * q32.norm(dim=-1, keepdim=True)).to(q.dtype)
 
 
+def listed_tokens(limits: Sequence[int], n_q_heads: int, max_k: int, seed: int) -> np.ndarray:
+    """A stand-in for a Pre-QK^T token selector (Section 4.3.2; Section 4.5): per (sequence,
+    query head) up to `max_k` distinct token positions below limits[b], seeded, in ascending
+    order, -1 padded.  Returns int32 [B, Hq, max_k].  The paper's selectors are third-party
+    predictors that need trained models; what the executor receives from any of them is such a
+    list, and its cost depends only on the list's length and scatter."""
+    rng = np.random.RandomState(_stream_seed(seed, 29) % (2 ** 31))
+    B = len(limits)
+    idx = np.full((B, n_q_heads, max_k), -1, dtype=np.int32)
+    for b in range(B):
+        n = int(limits[b])
+        kk = min(max_k, n)
+        for h in range(n_q_heads):
+            if n <= 4 * max_k:
+                row = rng.permutation(n)[:kk]
+            else:  # long caches: draw with replacement, de-duplicate, top up
+                row = np.unique(rng.randint(0, n, size=2 * kk))
+                rng.shuffle(row)
+                row = row[:kk]
+            idx[b, h, :row.size] = np.sort(row)
+    return idx
+
+
 def make_paged(w: Workload, block_tokens: int, seed: int = 0):
     """The same cache as a paged pool: K, V pools [n_blocks, Hkv, block_tokens, d] whose physical
     blocks are in a seeded random order, and the block table int32 [B, max_blocks] (unused

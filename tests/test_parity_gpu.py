@@ -214,3 +214,24 @@ def test_runs_on_a_side_stream():
     s.synchronize()
     ref, rlse = oracle.attn_full(to_np(w.q), *kv_np(w), w.seq_lens, w.scale)
     check_out(out, lse, ref, rlse, "side stream")
+
+
+def test_position_based_selection_is_a_range_table():
+    """Position-based token selection (Section 4.5; the evaluation's attention-sink baseline keeps
+    the first 4 tokens and the last 1024): such a set is two positional ranges per sequence, so
+    hg_attn_partial + hg_attn_merge evaluate it directly.  The reference is the oracle's
+    listed-token routine over the same positions, an independent path."""
+    spec = W.WorkloadSpec("sinkwin", 3, 8, 2, 128, "f16", 900, 5000, "none", seed=17)
+    w = W.make_workload(spec, DEV)
+    ranges, gp, lists = [], [0], []
+    for b, n in enumerate(int(x) for x in w.seq_lens):
+        lo = max(n - 1024, 4)
+        ranges += [(b, 0, min(4, n)), (b, lo, n)]
+        gp.append(len(ranges))
+        toks = list(range(min(4, n))) + list(range(lo, n))
+        lists.append(toks + [-1] * (1028 - len(toks)))
+    m, l, o = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, ranges, w.scale)
+    out, lse = hg.hg_attn_merge(m, l, o, gp)
+    idx = np.repeat(np.asarray(lists, dtype=np.int32)[:, None, :], 8, axis=1)
+    rm, rl, ro = oracle.attn_gather(to_np(w.q), *kv_np(w), w.seq_lens, w.scale, [0, 1, 2], idx)
+    check_out(out, lse, ro / rl[..., None], rm + np.log(rl), "sinks + window")

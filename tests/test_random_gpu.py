@@ -107,3 +107,20 @@ def test_random_case(case):
         raise AssertionError("%s select: kept tokens differ in group %d head %d\n got  %s\n want %s\n logits %s" % (
             what, g, h, got[g, h].tolist(), rsel[g, h].tolist(), row.tolist()))
     check_triples(sm, sl, so, rm, rl, ro, what + " select")
+
+    # the kept lists evaluated again as listed tokens (true query), plus a list with padding and
+    # duplicates at seeded positions; groups are the sequences that have a group of ranges
+    group_seq = [b for b in range(batch)]
+    rm2, rl2, ro2 = oracle.attn_gather(qn, kn, vn, w.seq_lens, w.scale, group_seq, rsel)
+    gm, gl, go = hg.hg_attn_gather(w.q, k_dev, v_dev, w.seq_lens, group_seq, sel, w.scale, block_table=table)
+    check_triples(gm, gl, go, rm2, rl2, ro2, what + " gather(sel)")
+    max_k = int(rng.choice([1, 9, 70, 333]))
+    idx = np.full((batch, group * hkv, max_k), -1, dtype=np.int32)
+    for b in range(batch):
+        n = int(w.seq_lens[b])
+        if n:
+            idx[b] = rng.integers(-n // 3 - 1, n, size=(group * hkv, max_k))  # about a quarter negative: padding
+    rm3, rl3, ro3 = oracle.attn_gather(qn, kn, vn, w.seq_lens, w.scale, group_seq, idx)
+    gm, gl, go = hg.hg_attn_gather(w.q, k_dev, v_dev, w.seq_lens, group_seq, torch.from_numpy(idx).to(DEV), w.scale,
+                                   block_table=table)
+    check_triples(gm, gl, go, rm3, rl3, ro3, what + " gather(random list)")
