@@ -11,6 +11,7 @@ from .oracle import (  # noqa: F401
     attn_merge,
     attn_partial,
     attn_select,
+    attn_topk,
     build,
     max_threads,
 )

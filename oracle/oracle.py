@@ -233,3 +233,13 @@ def attn_gather(q, k, v, seq_lens, scale, group_seq, index):
                                    m.ctypes.data, l.ctypes.data, o.ctypes.data), "attn_gather")
     del keep
     return m, l, o
+
+
+def attn_topk(q, k, v, seq_lens, scale, ranges, group_ptr, top_k):
+    """The Post-QK^T executor stage as one operation (Section 4.3.1; Section 4.6 step 1): the
+    logits of the ranges with this query (attn_logits), rounded once to fp32 -- the precision in
+    which the selection is decided -- then attn_select on them.  A composition of the two routines
+    above, nothing else.  Returns (sel, m, l, o, logits_fp32)."""
+    lg = attn_logits(q, k, v, seq_lens, scale, ranges).astype(np.float32)
+    sel, m, l, o = attn_select(q, k, v, seq_lens, scale, ranges, lg, group_ptr, top_k)
+    return sel, m, l, o, lg

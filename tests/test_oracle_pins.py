@@ -640,3 +640,31 @@ def test_gather_rejects_tokens_past_the_sequence_end():
     oracle.attn_gather(q, k, v, [10, 6], 1.0, [0], idx)
     with pytest.raises(ValueError):
         oracle.attn_gather(q, k, v, [10, 6], 1.0, [2], idx)
+
+
+def test_topk_is_the_definition_on_exactly_representable_logits():
+    """Dyadic inputs and a power-of-two scale make every logit exact in fp32 and in fp64 alike,
+    so the composed routine must keep exactly the k largest q.k (ties to the earlier token) found
+    by integer arithmetic, and its triple is the listed-token routine over that set."""
+    B, Hq, Hkv, N, d = 2, 4, 2, 50, 8
+    rng = RNG(41)
+    q = (rng.randint(-8, 9, size=(B, Hq, d)) / 4).astype(np.float16)
+    k = (rng.randint(-8, 9, size=(B, Hkv, N, d)) / 4).astype(np.float16)
+    v = _rand(rng, (B, Hkv, N, d), np.float16)
+    seq_lens = [50, 30]
+    ranges = [(0, 0, 20), (0, 25, 50), (1, 2, 30)]
+    gp = [0, 2, 3]
+    toks = [list(range(0, 20)) + list(range(25, 50)), list(range(2, 30))]
+    for top_k in (1, 6, 40, 64):
+        sel, m, l, o, lg = oracle.attn_topk(q, k, v, seq_lens, 0.25, ranges, gp, top_k)
+        gm, gl, go = oracle.attn_gather(q, k, v, seq_lens, 0.25, [0, 1], sel)
+        assert np.array_equal(m, gm) and np.abs(l - gl).max() < 1e-12 and np.abs(o - go).max() < 1e-12
+        for g in range(2):
+            for h in range(Hq):
+                # integer dot products: 16 q.k, exact
+                dots = [(int(np.round(16 * float(np.dot(q[g, h].astype(np.float64), k[g, h // 2, t].astype(np.float64))))), i)
+                        for i, t in enumerate(toks[g])]
+                best = sorted(dots, key=lambda x: (-x[0], x[1]))[:top_k]
+                want = sorted(toks[g][i] for _, i in best)
+                assert [t for t in sel[g, h] if t >= 0] == want
+                assert m[g, h] == best[0][0] / 64.0  # scale 1/4 of (16 q.k)/16
