@@ -228,6 +228,29 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
                          float *o, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * hg_attn_topk -- the whole Post-QK^T executor stage in one call (Section 4.3.1; Section 4.6 step
+ * 1): logits of every token of the listed ranges with THIS descriptor's query, top_k per (group,
+ * query head), kept logits and V rows folded into one (m, l, O) triple.  The result is what
+ * hg_attn_logits followed by hg_attn_select gives, bit for bit (the same fp32 logits decide, ties
+ * go to the lower column), but the logits never travel through memory: the scan keeps a running
+ * lower bound of each head's top_k-th largest logit and writes out only the logits that reach it
+ * (a few per cent of them on unordered data; all of them if the logits arrive in ascending
+ * order, which costs time, never correctness).
+ *
+ *   ranges, group_ptr, top_k, sel, m, l, o   as for hg_attn_select.
+ *   workspace   DEVICE, 256-byte aligned, hg_attn_topk_workspace_size bytes: room for the worst
+ *               case of the scan (4 x 4 bytes per (query head, token of the ranges)).
+ *   The fused scan serves top_k <= 256 on contiguous caches with 16-bit storage, head_dim 128 and
+ *   two or more query heads per KV head; other cases run the two-call sequence inside, with the
+ *   logits in the workspace.
+ */
+hg_status hg_attn_topk_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges,
+                                      const int32_t *group_ptr, int32_t n_groups, int32_t top_k, size_t *bytes);
+hg_status hg_attn_topk(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, const int32_t *group_ptr,
+                       int32_t n_groups, int32_t top_k, int32_t *sel, float *m, float *l, float *o, void *workspace,
+                       size_t ws_bytes, void *stream);
+
+/*
  * hg_attn_gather -- attention statistics over a LISTED set of tokens per (group, query head): the
  * executor's side of a selection that was decided elsewhere.  Under Pre-QK^T selection (Section
  * 4.3.2; Section 4.6 step 1) the token selector names the tokens before the logits exist and the

@@ -14,6 +14,7 @@ _API = (
     "hg_attn_concat",
     "hg_attn_select",
     "hg_attn_gather",
+    "hg_attn_topk",
     "hg_sched_init",
     "hg_sched_step",
     "HgSchedState",

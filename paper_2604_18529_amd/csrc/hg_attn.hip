@@ -556,6 +556,118 @@ void launch_select(const hg_attn_desc *desc, const SelectArgs &sa, dim3 grid, bo
         launch_select_variant<STAGE, false>(desc, sa, grid, stream);
 }
 
+// The launches of a selection whose tables (sa.tab, sa.groups) and input (sa.logits, or the dense
+// survivor lists sa.dense_*) are in place: one kernel for short groups, else candidates per part,
+// an optional middle stage, and the final selection among the candidates.
+hg_status select_stages(const hg_attn_desc *desc, const Plan &p, const SelectPlan &sp, SelectArgs &sa, int32_t n_groups,
+                        int32_t top_k, int32_t *sel, float *m, float *l, float *o, char *ws, hipStream_t stream)
+{
+    sa.v = desc->v;
+    fill_pages(desc, sa.pages);
+    sa.stride_b = desc->stride_b;
+    sa.stride_h = desc->stride_h;
+    sa.stride_t = desc->stride_t;
+    sa.ltok = p.ws.ltok;
+    sa.n_q_heads = desc->n_q_heads;
+    sa.group = desc->n_q_heads / desc->n_kv_heads;
+    sa.top_k = top_k;
+    sa.sel = sel;
+    sa.m = m;
+    sa.l = l;
+    sa.o = o;
+    sa.parts = sp.parts;
+    dim3 grid((unsigned)n_groups, (unsigned)desc->n_q_heads);
+    if (sp.parts == 1) {
+        launch_select<kSelectDirect>(desc, sa, grid, sp.fast_first, stream);
+        return launch_status("selection kernel");
+    }
+    sa.cand_val = reinterpret_cast<float *>(ws + sp.off_cand_val);
+    sa.cand_col = reinterpret_cast<int32_t *>(ws + sp.off_cand_col);
+    launch_select<kSelectCandidates>(desc, sa, dim3((unsigned)(n_groups * sp.parts), (unsigned)desc->n_q_heads), sp.fast_first, stream);
+    hg_status st = launch_status("selection kernel (candidates)");
+    if (st != HG_OK) return st;
+    if (sp.parts2) {
+        sa.parts2 = sp.parts2;
+        sa.cand2_val = reinterpret_cast<float *>(ws + sp.off_cand2_val);
+        sa.cand2_col = reinterpret_cast<int32_t *>(ws + sp.off_cand2_col);
+        launch_select<kSelectMidCands>(desc, sa, dim3((unsigned)(n_groups * sp.parts2), (unsigned)desc->n_q_heads), true, stream);
+        st = launch_status("selection kernel (middle stage)");
+        if (st != HG_OK) return st;
+    }
+    launch_select<kSelectFromCands>(desc, sa, grid, sp.fast_final, stream);
+    return launch_status("selection kernel (final)");
+}
+
+// hg_attn_topk: the scan that keeps only logits which can still be among a group's top_k (filter
+// mode of the streaming kernels) exists for the matrix-core kernel of 256-byte rows and for the
+// vector kernel with one query head per KV head, contiguous caches, top_k <= kFilterMaxTopK;
+// everything else exports all logits to the workspace and selects from them.
+constexpr int kFilterMaxTopK = 256;
+
+bool filter_supported(const hg_attn_desc *d, int32_t top_k)
+{
+    if (top_k > kFilterMaxTopK || d->block_table) return false;
+    if (use_gqa_kernel(d)) return d->head_dim == 128;
+    return false;
+}
+
+int filter_sub_spans(const hg_attn_desc *d) { return use_gqa_kernel(d) ? kGqaWaves : kValuWaves; }
+
+struct TopkPlan {
+    bool fused = false;
+    int32_t n_sub = 0, chunks = 1;
+    size_t off_logits = 0;  // unfused: all logits [Hq][ltok]
+    size_t off_surv_val = 0, off_surv_col = 0, off_surv_cnt = 0, off_dense_val = 0, off_dense_col = 0, off_dense_cnt = 0;
+    size_t total = 0;
+};
+
+TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, int32_t n_groups, int32_t top_k)
+{
+    TopkPlan tp;
+    tp.fused = filter_supported(d, top_k);
+    size_t off = align_up(sp.total);
+    const size_t rows = align_up((size_t)d->n_q_heads * (size_t)p.ws.ltok * 4);
+    if (!tp.fused) {
+        tp.off_logits = off;
+        off += rows;
+    } else {
+        tp.n_sub = filter_sub_spans(d);
+        const int64_t pairs = std::max<int64_t>(1, (int64_t)n_groups * d->n_q_heads);
+        tp.chunks = (int32_t)std::min<int64_t>(16, std::max<int64_t>(1, 512 / pairs));
+        tp.off_surv_val = off;
+        off += rows;
+        tp.off_surv_col = off;
+        off += rows;
+        tp.off_dense_val = off;
+        off += rows;
+        tp.off_dense_col = off;
+        off += rows;
+        tp.off_surv_cnt = off;
+        off += align_up((size_t)p.n_slots * (size_t)tp.n_sub * (size_t)p.ws.gt * 4);
+        tp.off_dense_cnt = off;
+        off += align_up((size_t)std::max<int32_t>(n_groups, 1) * (size_t)d->n_q_heads * 4);
+    }
+    tp.total = off;
+    return tp;
+}
+
+void launch_filter(const hg_attn_desc *d, const PartialArgs &a, dim3 grid, hipStream_t stream)
+{
+    // (filter_supported() admits exactly the variants instantiated here)
+    const bool wide = a.filter_rank >= 2;  // four kept logits per lane instead of two
+    if (d->dtype == HG_BF16) {
+        if (wide)
+            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, false, true, 4>), grid, dim3(kGqaBlock), 0, stream, a);
+        else
+            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, false, true, 2>), grid, dim3(kGqaBlock), 0, stream, a);
+    } else {
+        if (wide)
+            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, false, false, 4>), grid, dim3(kGqaBlock), 0, stream, a);
+        else
+            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, false, false, 2>), grid, dim3(kGqaBlock), 0, stream, a);
+    }
+}
+
 // hg_attn_merge (one producer: csr_b == nullptr) and hg_attn_merge2 (two producers).
 hg_status check_csr(const int32_t *csr, int32_t n_groups, const float *m, const float *l, const float *o)
 {
@@ -952,40 +1064,111 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
     st = stage_groups(group_ptr, n_groups, reinterpret_cast<int32_t *>(ws + sp.off_groups), stream, sa.groups);
     if (st != HG_OK) return st;
     sa.logits = logits;
-    sa.v = desc->v;
-    fill_pages(desc, sa.pages);
-    sa.stride_b = desc->stride_b;
-    sa.stride_h = desc->stride_h;
-    sa.stride_t = desc->stride_t;
-    sa.ltok = p.ws.ltok;
-    sa.n_q_heads = desc->n_q_heads;
-    sa.group = desc->n_q_heads / desc->n_kv_heads;
-    sa.top_k = top_k;
-    sa.sel = sel;
-    sa.m = m;
-    sa.l = l;
-    sa.o = o;
-    sa.parts = sp.parts;
-    dim3 grid((unsigned)n_groups, (unsigned)desc->n_q_heads);
-    if (sp.parts == 1) {
-        launch_select<kSelectDirect>(desc, sa, grid, sp.fast_first, stream);
-        return launch_status("selection kernel");
-    }
-    sa.cand_val = reinterpret_cast<float *>(ws + sp.off_cand_val);
-    sa.cand_col = reinterpret_cast<int32_t *>(ws + sp.off_cand_col);
-    launch_select<kSelectCandidates>(desc, sa, dim3((unsigned)(n_groups * sp.parts), (unsigned)desc->n_q_heads), sp.fast_first, stream);
-    st = launch_status("selection kernel (candidates)");
+    return select_stages(desc, p, sp, sa, n_groups, top_k, sel, m, l, o, ws, stream);
+}
+
+hg_status hg_attn_topk_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges,
+                                      const int32_t *group_ptr, int32_t n_groups, int32_t top_k, size_t *bytes)
+{
+    if (!bytes) return HG_ERR_NULL;
+    hg_status st = check_desc(desc);
     if (st != HG_OK) return st;
-    if (sp.parts2) {
-        sa.parts2 = sp.parts2;
-        sa.cand2_val = reinterpret_cast<float *>(ws + sp.off_cand2_val);
-        sa.cand2_col = reinterpret_cast<int32_t *>(ws + sp.off_cand2_col);
-        launch_select<kSelectMidCands>(desc, sa, dim3((unsigned)(n_groups * sp.parts2), (unsigned)desc->n_q_heads), true, stream);
-        st = launch_status("selection kernel (middle stage)");
+    st = check_ranges(desc, ranges, n_ranges);
+    if (st != HG_OK) return st;
+    if (top_k < 1 || top_k > kMaxTopK) return HG_ERR_SHAPE;
+    st = check_concat_groups(ranges, n_ranges, group_ptr, n_groups);
+    if (st != HG_OK) return st;
+    Plan p;
+    st = make_plan(desc, ranges, n_ranges, p);
+    if (st != HG_OK) return st;
+    const SelectPlan sp = plan_select(ranges, n_ranges, group_ptr, n_groups, desc->n_q_heads, top_k);
+    *bytes = plan_topk(desc, p, sp, n_groups, top_k).total;
+    return HG_OK;
+}
+
+hg_status hg_attn_topk(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, const int32_t *group_ptr,
+                       int32_t n_groups, int32_t top_k, int32_t *sel, float *m, float *l, float *o, void *workspace,
+                       size_t ws_bytes, void *stream_v)
+{
+    hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = check_ranges(desc, ranges, n_ranges);
+    if (st != HG_OK) return st;
+    if (top_k < 1 || top_k > kMaxTopK) return HG_ERR_SHAPE;
+    st = check_concat_groups(ranges, n_ranges, group_ptr, n_groups);
+    if (st != HG_OK) return st;
+    if (n_groups == 0) return HG_OK;
+    if (!m || !l || !o) return HG_ERR_NULL;
+    Plan p;
+    st = make_plan(desc, ranges, n_ranges, p);
+    if (st != HG_OK) return st;
+    const SelectPlan sp = plan_select(ranges, n_ranges, group_ptr, n_groups, desc->n_q_heads, top_k);
+    if ((int64_t)n_groups * sp.parts > 0x7fffffff) return HG_ERR_SHAPE;
+    const TopkPlan tp = plan_topk(desc, p, sp, n_groups, top_k);
+    st = check_workspace(workspace, ws_bytes, tp.total);
+    if (st != HG_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char *ws = static_cast<char *>(workspace);
+
+    SelectArgs sa;
+    std::memset(&sa, 0, sizeof(sa));
+    p.off_tab = sp.off_tab;  // one uploaded table serves the scan, the compaction and the selection
+    st = stage_table(p, n_ranges, ws, stream, sa.tab);
+    if (st != HG_OK) return st;
+    st = stage_groups(group_ptr, n_groups, reinterpret_cast<int32_t *>(ws + sp.off_groups), stream, sa.groups);
+    if (st != HG_OK) return st;
+
+    PartialArgs pa;
+    std::memset(&pa, 0, sizeof(pa));
+    pa.tab = sa.tab;
+    fill_stream_args(desc, p, nullptr, pa);
+    pa.qscale = desc->scale;  // logits in natural-log units, exactly as hg_attn_logits writes them
+    const dim3 sgrid((unsigned)p.n_workgroups);
+    if (!tp.fused) {
+        float *logits = reinterpret_cast<float *>(ws + tp.off_logits);
+        if (p.n_workgroups > 0) {
+            pa.logits = logits;
+            launch_stream<kModeLogits>(desc, pa, p.ws.gt, sgrid, stream);
+            st = launch_status("logits kernel");
+            if (st != HG_OK) return st;
+        }
+        sa.logits = logits;
+        return select_stages(desc, p, sp, sa, n_groups, top_k, sel, m, l, o, ws, stream);
+    }
+
+    float *dense_val = reinterpret_cast<float *>(ws + tp.off_dense_val);
+    int32_t *dense_col = reinterpret_cast<int32_t *>(ws + tp.off_dense_col);
+    int32_t *dense_cnt = reinterpret_cast<int32_t *>(ws + tp.off_dense_cnt);
+    pa.surv_val = reinterpret_cast<float *>(ws + tp.off_surv_val);
+    pa.surv_col = reinterpret_cast<int32_t *>(ws + tp.off_surv_col);
+    pa.surv_cnt = reinterpret_cast<int32_t *>(ws + tp.off_surv_cnt);
+    pa.filter_rank = (top_k + 63) / 64 - 1;  // 64 lanes-and-waves per head keep rank + 1 logits each
+    if (p.n_workgroups > 0) {
+        launch_filter(desc, pa, sgrid, stream);
+        st = launch_status("filter kernel");
         if (st != HG_OK) return st;
     }
-    launch_select<kSelectFromCands>(desc, sa, grid, sp.fast_final, stream);
-    return launch_status("selection kernel (final)");
+    CompactArgs ca;
+    std::memset(&ca, 0, sizeof(ca));
+    ca.surv_val = pa.surv_val;
+    ca.surv_col = pa.surv_col;
+    ca.surv_cnt = pa.surv_cnt;
+    ca.dense_val = dense_val;
+    ca.dense_col = dense_col;
+    ca.dense_cnt = dense_cnt;
+    ca.n_sub = tp.n_sub;
+    ca.chunks = tp.chunks;
+    ca.ws = p.ws;
+    ca.groups = sa.groups;
+    ca.tab = sa.tab;
+    hipLaunchKernelGGL(hg_survivor_compact_kernel, dim3((unsigned)n_groups, (unsigned)desc->n_q_heads, (unsigned)tp.chunks),
+                       dim3(256), 0, stream, ca);
+    st = launch_status("survivor compaction kernel");
+    if (st != HG_OK) return st;
+    sa.dense_val = dense_val;
+    sa.dense_col = dense_col;
+    sa.dense_cnt = dense_cnt;
+    return select_stages(desc, p, sp, sa, n_groups, top_k, sel, m, l, o, ws, stream);
 }
 
 hg_status hg_attn_gather_workspace_size(int32_t n_groups, size_t *bytes)

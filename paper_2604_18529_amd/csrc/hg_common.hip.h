@@ -70,6 +70,7 @@ struct RangeEntry {
 constexpr int kModeStats = 0;   // K and V -> (m, l, O) records                     (hg_attn_partial / hg_attn_full)
 constexpr int kModeLogits = 1;  // K only  -> raw scaled logits                     (hg_attn_logits)
 constexpr int kModeConcat = 2;  // V and given logits + group softmax stats -> sum p.v records  (hg_attn_concat)
+constexpr int kModeFilter = 3;  // K only  -> logits at or above a running lower bound of the k-th largest, densely (hg_attn_topk)
 constexpr int kConcatSlices = 32;  // partial (max, sum) records per (group, head) of the concat path
 
 // The range table travels by value in the kernel arguments when it is small; otherwise `ext`
@@ -122,9 +123,23 @@ struct PartialArgs {
     float *out_m, *out_l, *out_o;
     float *logits;                         // [Hq][ltok]: written in logits mode, read in concat mode
     const float *gs_m, *gs_l;              // concat mode: [n_groups][Hq][kConcatSlices] partial (max in log2 units, sum)
+    // filter mode: every segment is cut into n_sub consecutive sub-spans (one per wave); the
+    // survivors of sub-span j of head h -- logit and column, in ascending column order -- are
+    // written to surv_val / surv_col [Hq][ltok] starting at the sub-span's own first column, and
+    // their number to surv_cnt[(slot * n_sub + j) * gt + head in stream]
+    float *surv_val;
+    int32_t *surv_col, *surv_cnt;
+    int32_t filter_rank, pad_f;            // bound = filter_rank-th (0-based) largest of every lane's own elements
     WorkSplit ws;
     RangeTable tab;
 };
+
+// Tokens per sub-span of a segment of `len` tokens in filter mode (a multiple of every streaming
+// kernel's tokens per wave iteration).
+__host__ __device__ __forceinline__ int filter_sub_len(int len, int n_sub)
+{
+    return (len + n_sub * 64 - 1) / (n_sub * 64) * 64;
+}
 
 struct ReduceArgs {
     const float *ws_m, *ws_l, *ws_o;
@@ -188,6 +203,25 @@ struct SelectArgs {
     float *cand2_val;     // [n_groups][Hq][parts2][top_k]
     int32_t *cand2_col;
     PageMap pages;        // table == nullptr: contiguous cache
+    // hg_attn_topk: instead of the full logits rows, the first stage selects among the survivors
+    // of the filter pass: dense_cnt[group][head] entries (logit, column; ascending columns) that
+    // start at the group's first column of row `head` of dense_val / dense_col [Hq][ltok].
+    // dense_cnt == nullptr: select from `logits`.
+    const float *dense_val;
+    const int32_t *dense_col, *dense_cnt;
+    GroupTable groups;
+    RangeTable tab;
+};
+
+// Gathers the survivors that the filter pass left per (segment, sub-span, head) into one dense,
+// column-ordered list per (group, head).
+struct CompactArgs {
+    const float *surv_val;
+    const int32_t *surv_col, *surv_cnt;
+    float *dense_val;
+    int32_t *dense_col, *dense_cnt;
+    int32_t n_sub, chunks;  // sub-spans per segment; workgroups that share the copying of one (group, head)
+    WorkSplit ws;
     GroupTable groups;
     RangeTable tab;
 };

@@ -339,18 +339,19 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
     const float *row;
     const int32_t *col_map = nullptr;
     int n, col_base = 0, keep;
-    if constexpr (STAGE == kSelectDirect) {
-        row = a.logits + (int64_t)h * a.ltok + c0;
-        n = c1 - c0;
-        col_base = c0;
-        keep = n < a.top_k ? n : a.top_k;
-    } else if constexpr (STAGE == kSelectCandidates) {
-        const int per = (c1 - c0 + a.parts - 1) / a.parts;
-        const int b = c0 + part * per < c1 ? c0 + part * per : c1;
-        const int e = b + per < c1 ? b + per : c1;
-        row = a.logits + (int64_t)h * a.ltok + b;
+    if constexpr (STAGE == kSelectDirect || STAGE == kSelectCandidates) {
+        // the group's logits row -- or, after a filter pass, the dense list of its survivors (a
+        // superset of the group's top_k, in ascending column order)
+        const bool dense = a.dense_cnt != nullptr;
+        const int total = dense ? a.dense_cnt[gh] : c1 - c0;
+        const int n_cut = STAGE == kSelectCandidates ? a.parts : 1;
+        const int per = (total + n_cut - 1) / n_cut;
+        const int b = part * per < total ? part * per : total;
+        const int e = b + per < total ? b + per : total;
+        row = (dense ? a.dense_val : a.logits) + (int64_t)h * a.ltok + c0 + b;
+        if (dense) col_map = a.dense_col + (int64_t)h * a.ltok + c0 + b;
         n = e - b;
-        col_base = b;
+        col_base = c0 + b;
         keep = n < a.top_k ? n : a.top_k;
     } else if constexpr (STAGE == kSelectMidCands) {
         // chunk `part` of the group's parts * top_k candidates (pad entries included: they sort
@@ -575,6 +576,71 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
         a.m[gh] = mx;
         a.l[gh] = lt;
     }
+}
+
+// ---- hg_survivor_compact_kernel ------------------------------------------------------------------
+//
+// Grid (group, query head, chunk).  The segments of the group's ranges in this head's stream, and
+// the sub-spans inside each, are visited in column order; an exclusive scan of their survivor
+// counts gives every sub-span's place in the dense list; the copying of the entries is shared by
+// the `chunks` workgroups of the (group, head) pair (every one of them repeats the cheap scan).
+__global__ __launch_bounds__(256) void hg_survivor_compact_kernel(const CompactArgs a)
+{
+    __shared__ uint32_t s_wave[4];
+    __shared__ int32_t s_src[256], s_dst[256], s_cnt[256];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int gi = blockIdx.x, h = blockIdx.y, z = blockIdx.z;
+    const int r0 = group_entry(a.groups, gi), r1 = group_entry(a.groups, gi + 1);
+    const int c0 = table_entry(a.tab, r0).pre;
+    const int hk = h / a.ws.group, gl = h - hk * a.ws.group;
+    const int chunk = gl / a.ws.gt, g = gl - chunk * a.ws.gt;
+    const int64_t s = (int64_t)hk * a.ws.n_chunks + chunk;  // this head's stream
+    const int64_t row = (int64_t)h * a.ws.ltok;
+    uint32_t running = 0;  // survivors of the group before the current batch of sub-spans
+    for (int r = r0; r < r1; ++r) {
+        const int pre = table_entry(a.tab, r).pre, pre_next = table_entry(a.tab, r + 1).pre;
+        if (pre_next == pre) continue;
+        const int64_t p_first = s * a.ws.ltok + pre, p_last = s * a.ws.ltok + pre_next - 1;
+        const int64_t w_first = p_first / a.ws.span, w_last = p_last / a.ws.span;
+        const int64_t n_items = (w_last - w_first + 1) * a.n_sub;
+        for (int64_t base = 0; base < n_items; base += 256) {
+            const int64_t i = base + tid;
+            uint32_t c = 0;
+            int src = 0;
+            if (i < n_items) {
+                const int64_t w = w_first + i / a.n_sub;
+                const int j = (int)(i % a.n_sub);
+                // the segment of workgroup w inside range r, in columns of the concatenated ranges
+                const int64_t lo = w * a.ws.span - s * a.ws.ltok, hi = lo + a.ws.span;
+                const int x0 = lo > pre ? (int)lo : pre, x1 = hi < pre_next ? (int)hi : pre_next;
+                const int sub_len = filter_sub_len(x1 - x0, a.n_sub);
+                src = x0 + (j * sub_len < x1 - x0 ? j * sub_len : x1 - x0);
+                const int64_t slot = w + s * a.tab.n_ranges + r;
+                c = (uint32_t)a.surv_cnt[(slot * a.n_sub + j) * a.ws.gt + g];
+            }
+            uint32_t total;
+            const uint32_t before = block_exclusive_scan<256>(c, s_wave, total);
+            s_src[tid] = src;
+            s_dst[tid] = (int32_t)(running + before);
+            s_cnt[tid] = (i % a.chunks == z) ? (int32_t)c : 0;  // another workgroup copies the rest
+            __syncthreads();
+            const int n_here = n_items - base < 256 ? (int)(n_items - base) : 256;
+            for (int it = wave; it < n_here; it += 4) {
+                const int cnt = s_cnt[it];
+                const float *sv = a.surv_val + row + s_src[it];
+                const int32_t *sc = a.surv_col + row + s_src[it];
+                float *dv = a.dense_val + row + c0 + s_dst[it];
+                int32_t *dc = a.dense_col + row + c0 + s_dst[it];
+                for (int x = lane; x < cnt; x += 64) {
+                    dv[x] = sv[x];
+                    dc[x] = sc[x];
+                }
+            }
+            __syncthreads();
+            running += total;
+        }
+    }
+    if (z == 0 && tid == 0) a.dense_cnt[(int64_t)gi * a.ws.n_q_heads + h] = (int32_t)running;
 }
 
 }  // namespace hg

@@ -72,6 +72,27 @@ __device__ __forceinline__ void split_weights(float p0, float p1, uint32_t &hi, 
     }
 }
 
+__device__ __forceinline__ float row16_min(float x)
+{
+    x = fminf(x, dpp_move<0xB1>(x));
+    x = fminf(x, dpp_move<0x4E>(x));
+    x = fminf(x, dpp_move<0x141>(x));
+    x = fminf(x, dpp_move<0x140>(x));
+    return x;
+}
+
+// Insert x into the descending list t[0] >= t[1] >= ... >= t[J-1] of the J largest values seen.
+template <int J>
+__device__ __forceinline__ void track_largest(float (&t)[J], float x)
+{
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const float hi = fmaxf(t[j], x);
+        x = fminf(t[j], x);
+        t[j] = hi;
+    }
+}
+
 __device__ __forceinline__ float row16_max(float x)
 {
     x = fmaxf(x, dpp_move<0xB1>(x));
@@ -90,13 +111,16 @@ __device__ __forceinline__ void wave_lds_handover()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int MODE, bool PAGED, bool BF16>
-__global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_gqa_kernel(const PartialArgs a)
+// FJ (filter mode only): logits each lane keeps for the bound, 2 (top_k <= 128) or 4 (top_k <= 256)
+template <int MODE, bool PAGED, bool BF16, int FJ = 2>
+__global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 2 : 1) void hg_partial_gqa_kernel(const PartialArgs a)
 {
     constexpr int D = 128;
     constexpr int kMergeBytes = kGqaWaves * kGqaHeads * (D + 2) * 4;
     constexpr int kSmemBytes = kGqaWaves * kGqaWaveBytes > kMergeBytes ? kGqaWaves * kGqaWaveBytes : kMergeBytes;
     __shared__ __align__(16) char smem[kSmemBytes];
+    // filter mode: per wave and head, the smallest of the 16 lanes' rank-th largest logits
+    __shared__ float wmin_raw[MODE == kModeFilter ? kGqaWaves * kGqaHeads : 1];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: block loop control stays scalar
@@ -105,7 +129,18 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     char *kls = smem + wave * kGqaWaveBytes;
     char *pls = kls + kGqaKBytes;
 
-    for_each_segment(a.ws, a.tab, [&](int stream, int r_idx, const RangeEntry &e, int t0, int t1, int col0, int64_t slot) __attribute__((always_inline)) {
+    for_each_segment(a.ws, a.tab, [&](int stream, int r_idx, const RangeEntry &e, int seg_t0, int seg_t1, int seg_col0, int64_t slot) __attribute__((always_inline)) {
+    // Tokens [t0, t1) this wave works on and the column of t0: the whole segment, whose 32-token
+    // blocks the waves take in turn -- or, in filter mode, the wave's own consecutive sub-span, so
+    // that the survivors a wave appends are in ascending column order.
+    int t0 = seg_t0, t1 = seg_t1, col0 = seg_col0;
+    constexpr int kStride = MODE == kModeFilter ? kGqaBlockTokens : kGqaWaves * kGqaBlockTokens;
+    if constexpr (MODE == kModeFilter) {
+        const int sub_len = filter_sub_len(seg_t1 - seg_t0, kGqaWaves);
+        t0 = min(seg_t0 + wave * sub_len, seg_t1);
+        t1 = min(t0 + sub_len, seg_t1);
+        col0 = seg_col0 + (t0 - seg_t0);
+    }
     const int seq = e.seq;
     const int hk = stream / a.ws.n_chunks;
     const int chunk = stream - hk * a.ws.n_chunks;
@@ -209,6 +244,27 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     // unused when not paged
     int pg1[8] = {0, 0, 0, 0, 0, 0, 0, 0}, pg2[8] = {0, 0, 0, 0, 0, 0, 0, 0}, pg3[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 
+    // Filter mode.  Every lane keeps the largest logits of its own tokens (per head: tokens n and
+    // 16 + n of every block of this wave), tj[r][0] >= tj[r][1] >= ...  The smallest, over the 16
+    // lanes of a head and the waves of the workgroup, of the lanes' (rank+1)-th largest is reached
+    // by 64 * (rank + 1) >= top_k distinct logits of this segment, so it is a lower bound of the
+    // segment's (hence the group's) top_k-th largest logit: nothing below it can be among the
+    // kept tokens.  tau[r] holds the bound as of the last refresh (older = lower = still valid).
+    float tj[4][FJ], tau[4];
+    uint32_t cnt[4] = {0u, 0u, 0u, 0u};
+    int blk = 0;
+    volatile float *wmin = wmin_raw;
+    if constexpr (MODE == kModeFilter) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            tau[r] = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < FJ; ++j) tj[r][j] = -INFINITY;
+        }
+        if (lane < kGqaHeads) wmin[wave * kGqaHeads + lane] = -INFINITY;
+        __syncthreads();
+    }
+
     // One block.  Software pipeline with a single register buffer: the K rows of the next block
     // are requested as soon as this block's K sits in LDS, its V rows as soon as this block's V
     // has been consumed, so a wave always has 8-16 KiB in flight while it computes.
@@ -228,8 +284,8 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         }
         if (tb_next < t1) {
             load_k(tb_next, kreg, pg1);
-            if constexpr (PAGED && MODE == kModeLogits) {  // blocks are loaded in order: pages of the one after
-                if (tb_next + kGqaWaves * kGqaBlockTokens < t1) lookup(tb_next + kGqaWaves * kGqaBlockTokens, pg1);
+            if constexpr (PAGED && (MODE == kModeLogits || MODE == kModeFilter)) {  // blocks are loaded in order: pages of the one after
+                if (tb_next + kStride < t1) lookup(tb_next + kStride, pg1);
             }
         }
         hg_f4 s[2];
@@ -272,6 +328,73 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
                 }
             }
             wave_lds_handover();  // the next block overwrites the staging areas
+            return;
+        }
+        if constexpr (MODE == kModeFilter) {
+            // lane (n, rg): logits of heads 4rg..4rg+3 for tokens tb + n and tb + 16 + n, the same
+            // values the logits mode exports
+            const bool ok0 = tb + n < t1, ok1 = tb + 16 + n < t1;
+            float v0[4], v1[4];
+            bool c0[4], c1[4], any = false;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bool head_ok = 4 * rg + r < nh;
+                v0[r] = ok0 && head_ok ? s[0][r] * a.qscale : -INFINITY;
+                v1[r] = ok1 && head_ok ? s[1][r] * a.qscale : -INFINITY;
+                c0[r] = ok0 && head_ok && v0[r] >= tau[r];
+                c1[r] = ok1 && head_ok && v1[r] >= tau[r];
+                any = any || c0[r] || c1[r];
+            }
+            if (__builtin_amdgcn_ballot_w64(any)) {
+                // append in column order: tokens tb + 0..15, then tb + 16..31; the 16 lanes of row
+                // group rg are the tokens of heads 4rg..4rg+3
+                const uint32_t below = (1u << n) - 1u;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t m0 = (uint32_t)(__builtin_amdgcn_ballot_w64(c0[r]) >> (16 * rg)) & 0xffffu;
+                    const uint32_t m1 = (uint32_t)(__builtin_amdgcn_ballot_w64(c1[r]) >> (16 * rg)) & 0xffffu;
+                    const uint32_t n0 = (uint32_t)__builtin_popcount(m0);
+                    const int64_t row = (int64_t)(h0 + 4 * rg + r) * a.ws.ltok + col0;
+                    if (c0[r]) {
+                        const int64_t at = row + cnt[r] + (uint32_t)__builtin_popcount(m0 & below);
+                        a.surv_val[at] = v0[r];
+                        a.surv_col[at] = col0 + (tb - t0) + n;
+                    }
+                    if (c1[r]) {
+                        const int64_t at = row + cnt[r] + n0 + (uint32_t)__builtin_popcount(m1 & below);
+                        a.surv_val[at] = v1[r];
+                        a.surv_col[at] = col0 + (tb - t0) + 16 + n;
+                    }
+                    cnt[r] += n0 + (uint32_t)__builtin_popcount(m1);
+                }
+            }
+            const int rank = a.filter_rank;  // uniform, < FJ
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                track_largest<FJ>(tj[r], v0[r]);
+                track_largest<FJ>(tj[r], v1[r]);
+            }
+            if ((blk & 7) == 7) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float mine = tj[r][0];
+#pragma unroll
+                    for (int j = 1; j < FJ; ++j) mine = rank == j ? tj[r][j] : mine;
+                    const float low = row16_min(mine);
+                    if (n == 0) wmin[wave * kGqaHeads + 4 * rg + r] = low;
+                }
+                // (a wave's own LDS operations complete in order; what the other waves have
+                // published so far may be older, i.e. lower, which is still a valid bound)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float t = wmin[4 * rg + r];
+#pragma unroll
+                    for (int w = 1; w < kGqaWaves; ++w) t = fminf(t, wmin[w * kGqaHeads + 4 * rg + r]);
+                    tau[r] = t;
+                }
+            }
+            ++blk;
+            wave_lds_handover();  // the next block overwrites the K staging area
             return;
         }
 
@@ -406,14 +529,13 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             load_v(tb_next, vreg, pg1);
             load_logits(tb_next, sv);
             if constexpr (PAGED) {
-                if (tb_next + kGqaWaves * kGqaBlockTokens < t1) lookup(tb_next + kGqaWaves * kGqaBlockTokens, pg1);
+                if (tb_next + kStride < t1) lookup(tb_next + kStride, pg1);
             }
         }
     };
 
     {
-        constexpr int kStride = kGqaWaves * kGqaBlockTokens;
-        int tb = t0 + wave * kGqaBlockTokens;
+        int tb = MODE == kModeFilter ? t0 : t0 + wave * kGqaBlockTokens;
         if constexpr (MODE == kModeStats) {
             hg_u32x4 kreg[8], vreg[8];
             if (tb < t1) {
@@ -437,7 +559,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
             hg_u32x4 ra[8], rb[8];
             float sa[8], sb[8];  // concat mode: the logits that go with ra, rb
             auto load_one = [&](int t, hg_u32x4(&reg)[8], float(&sv)[8]) __attribute__((always_inline)) {
-                if constexpr (MODE == kModeLogits) {
+                if constexpr (MODE != kModeConcat) {
                     load_k(t, reg, pg1);
                 } else {
                     load_v(t, reg, pg1);
@@ -451,7 +573,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
                 if (tb < t1) lookup(tb, pg1);
             }
             auto compute_one = [&](int t, hg_u32x4(&reg)[8], float(&sv)[8]) __attribute__((always_inline)) {
-                if constexpr (MODE == kModeLogits)
+                if constexpr (MODE != kModeConcat)
                     compute_block(t, t + 2 * kStride, reg, reg);
                 else
                     concat_block(t, t + 2 * kStride, reg, sv);
@@ -468,6 +590,14 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         }
     }
     if constexpr (MODE == kModeLogits) return;  // nothing to merge or record
+    if constexpr (MODE == kModeFilter) {
+        if (n == 0) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) a.surv_cnt[(slot * kGqaWaves + wave) * kGqaHeads + 4 * rg + r] = (int32_t)cnt[r];
+        }
+        __syncthreads();  // the next segment resets the published bounds
+        return;
+    }
 
     // per-wave state -> LDS (staging areas are dead now), then merge the four waves
     __syncthreads();

@@ -81,6 +81,8 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_partial.argtypes = [D, R, i32, vp, vp, vp, vp, sz, vp]
     lib.hg_attn_merge_workspace_size.argtypes = [i32, ctypes.POINTER(sz)]
     lib.hg_attn_merge.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.hg_attn_topk_workspace_size.argtypes = [D, R, i32, vp, i32, i32, ctypes.POINTER(sz)]
+    lib.hg_attn_topk.argtypes = [D, R, i32, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.hg_attn_gather_workspace_size.argtypes = [i32, ctypes.POINTER(sz)]
     lib.hg_attn_gather.argtypes = [ctypes.POINTER(_Desc), vp, i32, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.hg_attn_merge2_workspace_size.argtypes = [i32, ctypes.POINTER(sz)]
@@ -103,6 +105,7 @@ def load_library() -> ctypes.CDLL:
     for name in (
         "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_merge_workspace_size", "hg_attn_merge",
         "hg_attn_merge2_workspace_size", "hg_attn_merge2", "hg_attn_gather_workspace_size", "hg_attn_gather",
+        "hg_attn_topk_workspace_size", "hg_attn_topk",
         "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_span_tokens",
         "hg_attn_profile_start", "hg_attn_profile_stop", "hg_attn_calibration_copy",
         "hg_sched_init", "hg_sched_step", "hg_attn_logits_workspace_size", "hg_attn_logits", "hg_attn_select_workspace_size", "hg_attn_select", "hg_attn_concat_workspace_size", "hg_attn_concat",
@@ -487,6 +490,47 @@ def hg_attn_select(q, k, v, seq_lens, ranges, logits, group_ptr, top_k, scale=No
         st = lib.hg_attn_select(ctypes.byref(desc), packed, R, _ptr(logits), gp.ctypes.data, G, int(top_k), _ptr(sel),
                                 _ptr(m), _ptr(l), _ptr(o), _ptr(workspace), ws_bytes, _stream_handle(stream))
     _check(st, "hg_attn_select")
+    del keep
+    return sel, m, l, o
+
+
+def hg_attn_topk_workspace_size(desc, packed, group_ptr, top_k) -> int:
+    gp = np.ascontiguousarray(group_ptr, dtype=np.int32)
+    sz = ctypes.c_size_t()
+    _check(load_library().hg_attn_topk_workspace_size(ctypes.byref(desc), packed, _n_ranges(packed), gp.ctypes.data, gp.size - 1,
+                                                      int(top_k), ctypes.byref(sz)), "hg_attn_topk_workspace_size")
+    return sz.value
+
+
+def hg_attn_topk(q, k, v, seq_lens, ranges, group_ptr, top_k, scale=None, *, want_sel=True, workspace=None, stream=None,
+                 desc=None, block_table=None):
+    """Post-QK^T executor stage in one call: logits of the ranges, top_k per (group, head), kept
+    tokens folded with their V rows.  Returns (sel int32 [G,Hq,top_k] or None, m, l [G,Hq], o [G,Hq,d])."""
+    lib = load_library()
+    if desc is None:
+        desc, keep = make_desc(q, k, v, seq_lens, scale, block_table)
+    else:
+        keep = None
+    packed = pack_ranges(ranges)
+    R = _n_ranges(packed)
+    gp = np.ascontiguousarray(group_ptr, dtype=np.int32)
+    if gp.ndim != 1 or gp.size < 1:
+        raise ValueError("group_ptr must be CSR offsets [n_groups+1]")
+    G = gp.size - 1
+    dev = q.device
+    Hq, d = q.shape[1], q.shape[2]
+    sel = torch.empty((G, Hq, int(top_k)), dtype=torch.int32, device=dev) if want_sel else None
+    m = torch.empty((G, Hq), dtype=torch.float32, device=dev)
+    l = torch.empty((G, Hq), dtype=torch.float32, device=dev)
+    o = torch.empty((G, Hq, d), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace, ws_bytes = _workspace(hg_attn_topk_workspace_size(desc, packed, gp, top_k), dev, None)
+    else:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        st = lib.hg_attn_topk(ctypes.byref(desc), packed, R, gp.ctypes.data, G, int(top_k), _ptr(sel), _ptr(m), _ptr(l),
+                              _ptr(o), _ptr(workspace), ws_bytes, _stream_handle(stream))
+    _check(st, "hg_attn_topk")
     del keep
     return sel, m, l, o
 

@@ -252,6 +252,18 @@ def proxy_query(q: torch.Tensor, cosine: float, seed: int) -> torch.Tensor:
     return (mixed * q32.norm(dim=-1, keepdim=True)).to(q.dtype)
 
 
+def make_dyadic_(w: "Workload", seed: int) -> None:
+    """Overwrite q and K of a workload, in place, with seeded multiples of 1/4 in [-2, 2].  With a
+    power-of-two scale every logit is then exact in fp32 (and in any summation order), so a
+    selection decided on fp32 logits and one decided on exactly computed logits must agree bit
+    for bit, ties included -- of which such coarse values produce many."""
+    gen = torch.Generator(device=w.q.device)
+    gen.manual_seed(_stream_seed(seed, 31))
+    for t in (w.q, w.k):
+        vals = torch.randint(-8, 9, t.shape, generator=gen, device=t.device, dtype=torch.int32)
+        t.copy_((vals.float() / 4).to(t.dtype))
+
+
 def listed_tokens(limits: Sequence[int], n_q_heads: int, max_k: int, seed: int) -> np.ndarray:
     """A stand-in for a Pre-QK^T token selector (Section 4.3.2; Section 4.5): per (sequence,
     query head) up to `max_k` distinct token positions below limits[b], seeded, in ascending
