@@ -157,6 +157,18 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W, routes=T
             m2, l2, o2 = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, p_new, w.scale, workspace=nws, desc=desc)
             hg.hg_attn_merge2(m1, l1, o1, one_each, m2, l2, o2, one_each, out=out, lse=lse)
 
+        tws = torch.empty(max(binding.hg_attn_topk_workspace_size(desc, p_old, gp_old, top_k), 256), dtype=torch.uint8, device=dev)
+
+        def postqk_topk():
+            return hg.hg_attn_topk(w.q, w.k, w.v, w.seq_lens, p_old, gp_old, top_k, w.scale, want_sel=False, workspace=tws, desc=desc)
+
+        def postqk_fused_step():
+            _, m1, l1, o1 = postqk_topk()
+            m2, l2, o2 = hg.hg_attn_partial(w.q, w.k, w.v, w.seq_lens, p_new, w.scale, workspace=nws, desc=desc)
+            hg.hg_attn_merge2(m1, l1, o1, one_each, m2, l2, o2, one_each, out=out, lse=lse)
+
+        pq_topk_ms, _ = _time_steps(postqk_topk, max(steps // 4, 1), max(warmup // 4, 1), torch)
+        pq_fused_ms, _ = _time_steps(postqk_fused_step, max(steps // 4, 1), max(warmup // 4, 1), torch)
         pq_logits_ms, _ = _time_steps(postqk_logits, max(steps // 4, 1), max(warmup // 4, 1), torch)
         pq_select_ms, _ = _time_steps(postqk_select, max(steps // 4, 1), max(warmup // 4, 1), torch)
         pq_rest_ms, _ = _time_steps(postqk_rest, max(steps // 4, 1), max(warmup // 4, 1), torch)
@@ -206,6 +218,8 @@ def run_workload(index, steps, warmup, with_cpu_baseline, torch, hg, W, routes=T
                 "select_us": pq_select_ms * 1e3,
                 "select_resident_merge_us": pq_rest_ms * 1e3,
                 "us": (pq_logits_ms + pq_rest_ms) * 1e3,
+                "topk_us": pq_topk_ms * 1e3,  # hg_attn_topk: logits + selection in one call
+                "one_call_us": pq_fused_ms * 1e3,  # hg_attn_topk + resident partial + merge
             },
             "pre_qk_route": {
                 "offloaded_fraction": 0.8,

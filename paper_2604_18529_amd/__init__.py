@@ -20,6 +20,7 @@ _API = (
     "HgSchedState",
     "hg_attn_plan",
     "hg_attn_set_span_tokens",
+    "hg_attn_set_topk_mode",
     "hg_attn_profile_start",
     "hg_attn_profile_stop",
     "hg_attn_calibration_copy",

@@ -23,6 +23,7 @@ namespace {
 using namespace hg;
 
 int g_forced_span_tokens = 0;
+int g_topk_mode = 0;  // hg_attn_set_topk_mode: 0 = choose, 1 = filter scan wherever it exists, 2 = never
 
 // Optional timing of the streaming kernel alone: event pairs recorded on the caller's stream
 // right around its launch (hg_attn_profile_start / hg_attn_profile_stop).
@@ -130,7 +131,7 @@ int32_t pick_span(int64_t total, bool gqa, int per_cu_factor)
     return (int32_t)t;
 }
 
-hg_status make_plan(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, Plan &p)
+hg_status make_plan(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, Plan &p, int workgroups_per_cu = 1)
 {
     const int32_t group = d->n_q_heads / d->n_kv_heads;
     p.ws.group = group;
@@ -153,7 +154,7 @@ hg_status make_plan(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ran
     // the table look-ups and 64-bit addresses of a paged cache push it over, and a second
     // workgroup per compute unit fills the gaps: 218 -> 185 us on the d=64 grouped-query shape,
     // where the contiguous cache and the other kernels measured no gain or a small loss.
-    const int per_cu_factor = use_gqa_kernel(d) && d->head_dim == 64 && d->block_table ? 2 : 1;
+    const int per_cu_factor = (use_gqa_kernel(d) && d->head_dim == 64 && d->block_table ? 2 : 1) * workgroups_per_cu;
     p.ws.span = pick_span(p.ws.total, use_gqa_kernel(d), per_cu_factor);
     {
         const int64_t row_bytes = d->stride_t * (d->dtype == HG_F32 ? 4 : 2);
@@ -606,25 +607,46 @@ constexpr int kFilterMaxTopK = 256;
 
 bool filter_supported(const hg_attn_desc *d, int32_t top_k)
 {
-    if (top_k > kFilterMaxTopK || d->block_table) return false;
+    if (g_topk_mode == 2 || top_k > kFilterMaxTopK || d->block_table) return false;
     if (use_gqa_kernel(d)) return d->head_dim == 128;
     return false;
 }
 
+// The filter scan pays off when the groups are long against top_k: the bounds rise like the
+// logarithm of the tokens seen, so a short group lets a large share of its logits through (a third
+// at 26k tokens and top_k 128, against 4 % at 840k) and the two-call sequence is faster then.
+constexpr int64_t kFilterMinTokensPerKept = 2048;
+
+bool filter_chosen(const hg_attn_desc *d, int32_t top_k, int64_t ltok, int32_t n_groups)
+{
+    if (!filter_supported(d, top_k)) return false;
+    if (g_topk_mode == 1) return true;
+    return ltok >= kFilterMinTokensPerKept * top_k * std::max<int32_t>(n_groups, 1);
+}
+
 int filter_sub_spans(const hg_attn_desc *d) { return use_gqa_kernel(d) ? kGqaWaves : kValuWaves; }
+
+// Workgroups per compute unit of the filter pass (a tuning constant; every further segment a group
+// is cut into lets more logits through before the bounds have risen).
+#ifndef HG_FILTER_WG_PER_CU
+#define HG_FILTER_WG_PER_CU 1
+#endif
+int topk_workgroups_per_cu(const hg_attn_desc *d, int32_t top_k) { return filter_supported(d, top_k) ? HG_FILTER_WG_PER_CU : 1; }
+static_assert(HG_FILTER_WG_PER_CU == 1, "with another value the plan of the two-call sequence inside hg_attn_topk would differ from hg_attn_logits'");
 
 struct TopkPlan {
     bool fused = false;
     int32_t n_sub = 0, chunks = 1;
     size_t off_logits = 0;  // unfused: all logits [Hq][ltok]
     size_t off_surv_val = 0, off_surv_col = 0, off_surv_cnt = 0, off_dense_val = 0, off_dense_col = 0, off_dense_cnt = 0;
+    size_t off_gbound = 0, n_bounds = 0;  // shared bounds: one float per (slot, sub-span, head of the stream)
     size_t total = 0;
 };
 
 TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, int32_t n_groups, int32_t top_k)
 {
     TopkPlan tp;
-    tp.fused = filter_supported(d, top_k);
+    tp.fused = filter_chosen(d, top_k, p.ws.ltok, n_groups);
     size_t off = align_up(sp.total);
     const size_t rows = align_up((size_t)d->n_q_heads * (size_t)p.ws.ltok * 4);
     if (!tp.fused) {
@@ -633,7 +655,7 @@ TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, i
     } else {
         tp.n_sub = filter_sub_spans(d);
         const int64_t pairs = std::max<int64_t>(1, (int64_t)n_groups * d->n_q_heads);
-        tp.chunks = (int32_t)std::min<int64_t>(16, std::max<int64_t>(1, 512 / pairs));
+        tp.chunks = (int32_t)std::min<int64_t>(64, std::max<int64_t>(1, 4096 / pairs));
         tp.off_surv_val = off;
         off += rows;
         tp.off_surv_col = off;
@@ -642,8 +664,11 @@ TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, i
         off += rows;
         tp.off_dense_col = off;
         off += rows;
+        tp.n_bounds = (size_t)p.n_slots * (size_t)tp.n_sub * (size_t)p.ws.gt;
         tp.off_surv_cnt = off;
-        off += align_up((size_t)p.n_slots * (size_t)tp.n_sub * (size_t)p.ws.gt * 4);
+        off += align_up(tp.n_bounds * 4);
+        tp.off_gbound = off;
+        off += align_up(tp.n_bounds * 4);
         tp.off_dense_cnt = off;
         off += align_up((size_t)std::max<int32_t>(n_groups, 1) * (size_t)d->n_q_heads * 4);
     }
@@ -748,6 +773,13 @@ hg_status hg_attn_set_span_tokens(int32_t span_tokens)
 {
     if (span_tokens != 0 && (span_tokens < 64 || span_tokens > (1 << 24) || span_tokens % 64)) return HG_ERR_SHAPE;
     g_forced_span_tokens = span_tokens;
+    return HG_OK;
+}
+
+hg_status hg_attn_set_topk_mode(int32_t mode)
+{
+    if (mode < 0 || mode > 2) return HG_ERR_SHAPE;
+    g_topk_mode = mode;
     return HG_OK;
 }
 
@@ -1079,7 +1111,7 @@ hg_status hg_attn_topk_workspace_size(const hg_attn_desc *desc, const hg_range *
     st = check_concat_groups(ranges, n_ranges, group_ptr, n_groups);
     if (st != HG_OK) return st;
     Plan p;
-    st = make_plan(desc, ranges, n_ranges, p);
+    st = make_plan(desc, ranges, n_ranges, p, topk_workgroups_per_cu(desc, top_k));
     if (st != HG_OK) return st;
     const SelectPlan sp = plan_select(ranges, n_ranges, group_ptr, n_groups, desc->n_q_heads, top_k);
     *bytes = plan_topk(desc, p, sp, n_groups, top_k).total;
@@ -1100,7 +1132,7 @@ hg_status hg_attn_topk(const hg_attn_desc *desc, const hg_range *ranges, int32_t
     if (n_groups == 0) return HG_OK;
     if (!m || !l || !o) return HG_ERR_NULL;
     Plan p;
-    st = make_plan(desc, ranges, n_ranges, p);
+    st = make_plan(desc, ranges, n_ranges, p, topk_workgroups_per_cu(desc, top_k));
     if (st != HG_OK) return st;
     const SelectPlan sp = plan_select(ranges, n_ranges, group_ptr, n_groups, desc->n_q_heads, top_k);
     if ((int64_t)n_groups * sp.parts > 0x7fffffff) return HG_ERR_SHAPE;
@@ -1143,7 +1175,11 @@ hg_status hg_attn_topk(const hg_attn_desc *desc, const hg_range *ranges, int32_t
     pa.surv_col = reinterpret_cast<int32_t *>(ws + tp.off_surv_col);
     pa.surv_cnt = reinterpret_cast<int32_t *>(ws + tp.off_surv_cnt);
     pa.filter_rank = (top_k + 63) / 64 - 1;  // 64 lanes-and-waves per head keep rank + 1 logits each
+    pa.filter_k = top_k;
+    pa.gbound = reinterpret_cast<float *>(ws + tp.off_gbound);
     if (p.n_workgroups > 0) {
+        const unsigned fill_blocks = (unsigned)std::min<size_t>(1024, (tp.n_bounds + 255) / 256);
+        hipLaunchKernelGGL(hg_fill_kernel, dim3(fill_blocks), dim3(256), 0, stream, pa.gbound, (int64_t)tp.n_bounds, -INFINITY);
         launch_filter(desc, pa, sgrid, stream);
         st = launch_status("filter kernel");
         if (st != HG_OK) return st;

@@ -129,7 +129,11 @@ struct PartialArgs {
     // their number to surv_cnt[(slot * n_sub + j) * gt + head in stream]
     float *surv_val;
     int32_t *surv_col, *surv_cnt;
-    int32_t filter_rank, pad_f;            // bound = filter_rank-th (0-based) largest of every lane's own elements
+    int32_t filter_rank, filter_k;         // bound = filter_rank-th (0-based) largest of every lane's own elements; top_k
+    // Bounds shared between the workgroups that scan the same (range, stream) pair:
+    // gbound[slot * gt + head in stream], -inf before the launch.  An entry is what its workgroup
+    // has published so far (see the filter mode).
+    float *gbound;
     WorkSplit ws;
     RangeTable tab;
 };
@@ -139,6 +143,16 @@ struct PartialArgs {
 __host__ __device__ __forceinline__ int filter_sub_len(int len, int n_sub)
 {
     return (len + n_sub * 64 - 1) / (n_sub * 64) * 64;
+}
+
+// Sub-spans of a segment of `len` tokens that hold at least 16 tokens (every one of the 16 lanes
+// of a head then owns a logit after the wave's first block): the waves that take part in the
+// shared bound.
+__host__ __device__ __forceinline__ int filter_valid_waves(int len, int n_sub)
+{
+    if (len < 16) return 0;
+    const int v = (len - 16) / filter_sub_len(len, n_sub) + 1;
+    return v < n_sub ? v : n_sub;
 }
 
 struct ReduceArgs {

@@ -345,8 +345,11 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
         const bool dense = a.dense_cnt != nullptr;
         const int total = dense ? a.dense_cnt[gh] : c1 - c0;
         const int n_cut = STAGE == kSelectCandidates ? a.parts : 1;
-        const int per = (total + n_cut - 1) / n_cut;
-        const int b = part * per < total ? part * per : total;
+        // (dense lists are usually far shorter than the rows the parts were sized for: fill the
+        // parts of a fast-path launch to their capacity, the others find nothing and leave)
+        const int even = (total + n_cut - 1) / n_cut;
+        const int per = dense && FAST && even < kSelectRegTokens ? kSelectRegTokens : even;
+        const int b = (int64_t)part * per < total ? part * per : total;
         const int e = b + per < total ? b + per : total;
         row = (dense ? a.dense_val : a.logits) + (int64_t)h * a.ltok + c0 + b;
         if (dense) col_map = a.dense_col + (int64_t)h * a.ltok + c0 + b;
@@ -588,7 +591,7 @@ __global__ __launch_bounds__(256) void hg_survivor_compact_kernel(const CompactA
 {
     __shared__ uint32_t s_wave[4];
     __shared__ int32_t s_src[256], s_dst[256], s_cnt[256];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     const int gi = blockIdx.x, h = blockIdx.y, z = blockIdx.z;
     const int r0 = group_entry(a.groups, gi), r1 = group_entry(a.groups, gi + 1);
     const int c0 = table_entry(a.tab, r0).pre;
@@ -622,16 +625,17 @@ __global__ __launch_bounds__(256) void hg_survivor_compact_kernel(const CompactA
             const uint32_t before = block_exclusive_scan<256>(c, s_wave, total);
             s_src[tid] = src;
             s_dst[tid] = (int32_t)(running + before);
-            s_cnt[tid] = (i % a.chunks == z) ? (int32_t)c : 0;  // another workgroup copies the rest
+            s_cnt[tid] = (int32_t)c;
             __syncthreads();
+            // this workgroup copies the sub-spans z, z + chunks, ... of the batch, all threads on one
             const int n_here = n_items - base < 256 ? (int)(n_items - base) : 256;
-            for (int it = wave; it < n_here; it += 4) {
+            for (int it = z; it < n_here; it += a.chunks) {
                 const int cnt = s_cnt[it];
                 const float *sv = a.surv_val + row + s_src[it];
                 const int32_t *sc = a.surv_col + row + s_src[it];
                 float *dv = a.dense_val + row + c0 + s_dst[it];
                 int32_t *dc = a.dense_col + row + c0 + s_dst[it];
-                for (int x = lane; x < cnt; x += 64) {
+                for (int x = tid; x < cnt; x += 256) {
                     dv[x] = sv[x];
                     dc[x] = sc[x];
                 }

@@ -35,6 +35,7 @@ constexpr int kGqaKRow = 272;            // padded LDS row: 256 bytes + 16 so th
 constexpr int kGqaKBytes = kGqaBlockTokens * kGqaKRow;
 constexpr int kGqaPBytes = kGqaHeads * kGqaBlockTokens * 2;
 constexpr int kGqaWaveBytes = kGqaKBytes + 2 * kGqaPBytes;
+constexpr int kGqaStage = 64;            // filter mode: survivors staged in LDS per (wave, head) between write-outs
 
 typedef _Float16 hg_h8 __attribute__((ext_vector_type(8)));
 typedef __bf16 hg_b8 __attribute__((ext_vector_type(8)));
@@ -81,15 +82,22 @@ __device__ __forceinline__ float row16_min(float x)
     return x;
 }
 
-// Insert x into the descending list t[0] >= t[1] >= ... >= t[J-1] of the J largest values seen.
+// Insert x into the descending list a >= b (>= c >= d) of the J = 2 or 4 largest values seen.
+// (Separate scalars: an array indexed through a reference stayed in scratch memory.)
 template <int J>
-__device__ __forceinline__ void track_largest(float (&t)[J], float x)
+__device__ __forceinline__ void track_largest(float &a, float &b, float &c, float &d, float x)
 {
-#pragma unroll
-    for (int j = 0; j < J; ++j) {
-        const float hi = fmaxf(t[j], x);
-        x = fminf(t[j], x);
-        t[j] = hi;
+    float hi = fmaxf(a, x);
+    x = fminf(a, x);
+    a = hi;
+    hi = fmaxf(b, x);
+    x = fminf(b, x);
+    b = hi;
+    if constexpr (J > 2) {
+        hi = fmaxf(c, x);
+        x = fminf(c, x);
+        c = hi;
+        d = fmaxf(d, x);
     }
 }
 
@@ -111,7 +119,11 @@ __device__ __forceinline__ void wave_lds_handover()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// FJ (filter mode only): logits each lane keeps for the bound, 2 (top_k <= 128) or 4 (top_k <= 256)
+// FJ (filter mode only): logits each lane keeps for the bound, 2 (top_k <= 128) or 4 (top_k <= 256).
+// The filter mode keeps more state per lane than 256 registers hold; it is compiled for one wave
+// per SIMD (which is how the kernel is launched anyway), so that the rest lives in the accumulation
+// registers instead of scratch memory: a scratch access inside the loop would make every wait for
+// K rows a wait for all memory operations in flight.
 template <int MODE, bool PAGED, bool BF16, int FJ = 2>
 __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 2 : 1) void hg_partial_gqa_kernel(const PartialArgs a)
 {
@@ -120,7 +132,11 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     constexpr int kSmemBytes = kGqaWaves * kGqaWaveBytes > kMergeBytes ? kGqaWaves * kGqaWaveBytes : kMergeBytes;
     __shared__ __align__(16) char smem[kSmemBytes];
     // filter mode: per wave and head, the smallest of the 16 lanes' rank-th largest logits
-    __shared__ float wmin_raw[MODE == kModeFilter ? kGqaWaves * kGqaHeads : 1];
+    __shared__ volatile float wmin[MODE == kModeFilter ? kGqaWaves * kGqaHeads : 1];  // own bound: [wave][head]
+    __shared__ volatile float wpub[MODE == kModeFilter ? kGqaWaves * kGqaHeads : 1];  // shared bound: each wave's part
+    // filter mode: survivors wait here, per wave and head, until a run of them is written out
+    __shared__ float stage_val[MODE == kModeFilter ? kGqaWaves * kGqaHeads * kGqaStage : 1];
+    __shared__ int32_t stage_col[MODE == kModeFilter ? kGqaWaves * kGqaHeads * kGqaStage : 1];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: block loop control stays scalar
@@ -245,25 +261,85 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     int pg1[8] = {0, 0, 0, 0, 0, 0, 0, 0}, pg2[8] = {0, 0, 0, 0, 0, 0, 0, 0}, pg3[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 
     // Filter mode.  Every lane keeps the largest logits of its own tokens (per head: tokens n and
-    // 16 + n of every block of this wave), tj[r][0] >= tj[r][1] >= ...  The smallest, over the 16
-    // lanes of a head and the waves of the workgroup, of the lanes' (rank+1)-th largest is reached
-    // by 64 * (rank + 1) >= top_k distinct logits of this segment, so it is a lower bound of the
-    // segment's (hence the group's) top_k-th largest logit: nothing below it can be among the
-    // kept tokens.  tau[r] holds the bound as of the last refresh (older = lower = still valid).
-    float tj[4][FJ], tau[4];
+    // 16 + n of every block of this wave), tj0[r] >= tj1[r] >= ...
+    //
+    // Own bound.  The smallest, over the 16 lanes of a head and the waves of the workgroup, of the
+    // lanes' (rank+1)-th largest is reached by 64 * (rank + 1) >= top_k distinct logits of this
+    // segment, so it is a lower bound of the segment's (hence the group's) top_k-th largest logit:
+    // nothing below it can be among the kept tokens.
+    //
+    // Shared bound.  When many workgroups scan the same (range, stream) pair -- a long sequence with
+    // few KV heads -- each sees a slice of the group only and its own bound stays far below the
+    // group's.  Then every workgroup whose whole span lies inside the pair publishes, in global
+    // memory, a value that 4 * 2^level distinct logits of its span reach: the 16 lanes of a head
+    // form 2^level sets per wave, and the value is the smallest of the sets' maxima over the
+    // four waves.  With P such workgroups and 4 * P * 2^level >= top_k, the smallest published
+    // value is a lower bound of the pair's top_k-th largest logit, and it closes in on the true
+    // value as the workgroups advance together.  Only spans that are a whole interior segment take
+    // part: they are under way from the start of the launch, whereas the first segment of a pair
+    // is reached only after its workgroup has finished the end of the previous pair.  Nothing ever
+    // waits: an entry not published yet reads -inf (the host clears the array before the launch),
+    // a stale one reads lower than the current one, and either only makes the bound weaker.  What a
+    // refresh reads is used one block later, so the scan does not stand still for the round trip.
+    //
+    // tau[r] is the bound in use: the largest seen so far of both kinds.
+    constexpr int kMaxPeers = 32;  // entries read per refresh: two per lane of a head's 16
+    float tj0[4], tj1[4], tj2[4], tj3[4], tau[4], pend[2][4];  // tj0[r] >= tj1[r] >= ...: largest logits of head 4rg + r
+    bool have_pend = false;
     uint32_t cnt[4] = {0u, 0u, 0u, 0u};
-    int blk = 0;
-    volatile float *wmin = wmin_raw;
+    int blk = 0, next_refresh = 1;
+    uint32_t staged[4] = {0u, 0u, 0u, 0u};  // survivors of heads 4rg..4rg+3 waiting in LDS (cnt: already written out)
+    int level = -1, n_peers = 0;  // shared bound: sets per wave = 2^level (none if < 0), workgroups that take part
+    bool takes_part = false;      // this workgroup is one of them
+    int64_t gb_first = 0;         // entry of the first of them, head 0 of this stream
     if constexpr (MODE == kModeFilter) {
+        const int pre_r = e.pre, pre_n = table_entry(a.tab, r_idx + 1).pre;
+        const int64_t p_first = (int64_t)stream * a.ws.ltok + pre_r, p_last = (int64_t)stream * a.ws.ltok + pre_n - 1;
+        const int64_t w_first = p_first / a.ws.span, w_last = p_last / a.ws.span;
+        const int64_t n_inner = w_last - w_first - 1;
+        if (n_inner > 0 && filter_valid_waves(a.ws.span, kGqaWaves) == kGqaWaves) {
+            n_peers = n_inner < kMaxPeers ? (int)n_inner : kMaxPeers;
+#pragma unroll
+            for (int L = 4; L >= 0; --L)
+                if (((n_peers * kGqaWaves) << L) >= a.filter_k) level = L;
+            gb_first = (w_first + 1 + (int64_t)stream * a.tab.n_ranges + r_idx) * kGqaHeads;
+        }
+        takes_part = level >= 0 && (int64_t)blockIdx.x > w_first && (int64_t)blockIdx.x <= w_first + n_peers;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            tau[r] = -INFINITY;
-#pragma unroll
-            for (int j = 0; j < FJ; ++j) tj[r][j] = -INFINITY;
+            tau[r] = 4 * rg + r < nh ? -INFINITY : INFINITY;  // rows of the tile beyond the group's heads pass nothing
+            tj0[r] = tj1[r] = tj2[r] = tj3[r] = -INFINITY;
         }
-        if (lane < kGqaHeads) wmin[wave * kGqaHeads + lane] = -INFINITY;
+        if (lane < kGqaHeads) {
+            wmin[wave * kGqaHeads + lane] = -INFINITY;
+            wpub[wave * kGqaHeads + lane] = -INFINITY;
+        }
         __syncthreads();
     }
+
+    // Write the staged survivors of every head of this wave behind those already written out.
+    auto flush_staged = [&]() __attribute__((always_inline)) {
+        wave_lds_handover();
+#pragma unroll
+        for (int hh = 0; hh < kGqaHeads; ++hh) {
+            // head hh is held by row group hh / 4 as its entry hh % 4; lane 16 * (hh / 4) speaks for the group
+            const int c = __builtin_amdgcn_readlane((int)staged[hh & 3], 16 * (hh >> 2));
+            if (c == 0) continue;
+            const int done = __builtin_amdgcn_readlane((int)cnt[hh & 3], 16 * (hh >> 2));
+            const int64_t dst = (int64_t)(h0 + hh) * a.ws.ltok + col0 + done;
+            const int src = (wave * kGqaHeads + hh) * kGqaStage;
+            if (lane < c) {
+                a.surv_val[dst + lane] = stage_val[src + lane];
+                a.surv_col[dst + lane] = stage_col[src + lane];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            cnt[r] += staged[r];
+            staged[r] = 0u;
+        }
+        wave_lds_handover();
+    };
 
     // One block.  Software pipeline with a single register buffer: the K rows of the next block
     // are requested as soon as this block's K sits in LDS, its V rows as soon as this block's V
@@ -333,64 +409,139 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
         if constexpr (MODE == kModeFilter) {
             // lane (n, rg): logits of heads 4rg..4rg+3 for tokens tb + n and tb + 16 + n, the same
             // values the logits mode exports
+            // Common case first, on the vector ALU alone: a full block in which no logit reaches its
+            // head's bound (heads beyond the group carry a bound of +inf).  Only then are the exact
+            // per-token conditions formed.
             const bool ok0 = tb + n < t1, ok1 = tb + 16 + n < t1;
-            float v0[4], v1[4];
-            bool c0[4], c1[4], any = false;
+            float v0[4], v1[4], excess = -INFINITY;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const bool head_ok = 4 * rg + r < nh;
-                v0[r] = ok0 && head_ok ? s[0][r] * a.qscale : -INFINITY;
-                v1[r] = ok1 && head_ok ? s[1][r] * a.qscale : -INFINITY;
-                c0[r] = ok0 && head_ok && v0[r] >= tau[r];
-                c1[r] = ok1 && head_ok && v1[r] >= tau[r];
-                any = any || c0[r] || c1[r];
+                v0[r] = s[0][r] * a.qscale;
+                v1[r] = s[1][r] * a.qscale;
             }
+            if (tb + kGqaBlockTokens > t1) {  // last block of the sub-span: tokens past its end count for nothing
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    v0[r] = ok0 ? v0[r] : -INFINITY;
+                    v1[r] = ok1 ? v1[r] : -INFINITY;
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) excess = fmaxf(excess, fmaxf(v0[r] - tau[r], v1[r] - tau[r]));  // (fmaxf drops a NaN from -inf - -inf)
+            const bool any = excess >= 0.f;
+            bool c0[4], c1[4];
+            // Survivors go to LDS first, in column order (tokens tb + 0..15, then tb + 16..31; the 16
+            // lanes of row group rg are the tokens of heads 4rg..4rg+3), and reach global memory in
+            // runs.  A conditional global store in every block would leave the number of memory
+            // operations in flight unknown at compile time, and the wait for the next block's K rows
+            // would then also wait for the rows requested for the block after it.
             if (__builtin_amdgcn_ballot_w64(any)) {
-                // append in column order: tokens tb + 0..15, then tb + 16..31; the 16 lanes of row
-                // group rg are the tokens of heads 4rg..4rg+3
                 const uint32_t below = (1u << n) - 1u;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const uint32_t m0 = (uint32_t)(__builtin_amdgcn_ballot_w64(c0[r]) >> (16 * rg)) & 0xffffu;
-                    const uint32_t m1 = (uint32_t)(__builtin_amdgcn_ballot_w64(c1[r]) >> (16 * rg)) & 0xffffu;
+                    const bool head_ok = 4 * rg + r < nh;
+                    c0[r] = ok0 && head_ok && v0[r] >= tau[r];
+                    c1[r] = ok1 && head_ok && v1[r] >= tau[r];
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint64_t b0 = __builtin_amdgcn_ballot_w64(c0[r]), b1 = __builtin_amdgcn_ballot_w64(c1[r]);
+                    if ((b0 | b1) == 0) continue;  // uniform: usually only a few of the 16 heads have a survivor
+                    const uint32_t m0 = (uint32_t)(b0 >> (16 * rg)) & 0xffffu;
+                    const uint32_t m1 = (uint32_t)(b1 >> (16 * rg)) & 0xffffu;
                     const uint32_t n0 = (uint32_t)__builtin_popcount(m0);
-                    const int64_t row = (int64_t)(h0 + 4 * rg + r) * a.ws.ltok + col0;
+                    const int base = (wave * kGqaHeads + 4 * rg + r) * kGqaStage;
                     if (c0[r]) {
-                        const int64_t at = row + cnt[r] + (uint32_t)__builtin_popcount(m0 & below);
-                        a.surv_val[at] = v0[r];
-                        a.surv_col[at] = col0 + (tb - t0) + n;
+                        const int at = base + (int)(staged[r] + (uint32_t)__builtin_popcount(m0 & below));
+                        stage_val[at] = v0[r];
+                        stage_col[at] = col0 + (tb - t0) + n;
                     }
                     if (c1[r]) {
-                        const int64_t at = row + cnt[r] + n0 + (uint32_t)__builtin_popcount(m1 & below);
-                        a.surv_val[at] = v1[r];
-                        a.surv_col[at] = col0 + (tb - t0) + 16 + n;
+                        const int at = base + (int)(staged[r] + n0 + (uint32_t)__builtin_popcount(m1 & below));
+                        stage_val[at] = v1[r];
+                        stage_col[at] = col0 + (tb - t0) + 16 + n;
                     }
-                    cnt[r] += n0 + (uint32_t)__builtin_popcount(m1);
+                    staged[r] += n0 + (uint32_t)__builtin_popcount(m1);
                 }
+                // a block adds at most 32 per head: write out once a head could overflow next time
+                bool full = false;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) full = full || staged[r] > (uint32_t)(kGqaStage - kGqaBlockTokens);
+                if (__builtin_amdgcn_ballot_w64(full)) flush_staged();
             }
             const int rank = a.filter_rank;  // uniform, < FJ
+            if (level >= 0) {  // the shared bound needs every lane's largest logit only
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                track_largest<FJ>(tj[r], v0[r]);
-                track_largest<FJ>(tj[r], v1[r]);
-            }
-            if ((blk & 7) == 7) {
+                for (int r = 0; r < 4; ++r) tj0[r] = fmaxf(tj0[r], fmaxf(v0[r], v1[r]));
+            } else {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    float mine = tj[r][0];
-#pragma unroll
-                    for (int j = 1; j < FJ; ++j) mine = rank == j ? tj[r][j] : mine;
-                    const float low = row16_min(mine);
-                    if (n == 0) wmin[wave * kGqaHeads + 4 * rg + r] = low;
+                    track_largest<FJ>(tj0[r], tj1[r], tj2[r], tj3[r], v0[r]);
+                    track_largest<FJ>(tj0[r], tj1[r], tj2[r], tj3[r], v1[r]);
                 }
-                // (a wave's own LDS operations complete in order; what the other waves have
-                // published so far may be older, i.e. lower, which is still a valid bound)
+            }
+            // refresh the bound after blocks 2, 4, 9, 22, 54, ... (everything passes until a bound
+            // exists, and it settles like the logarithm of the tokens seen)
+            if (have_pend) {  // what the refresh of the previous block read has had a block's time to arrive
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float t = wmin[4 * rg + r];
+                for (int r = 0; r < 4; ++r) tau[r] = fmaxf(tau[r], row16_min(fminf(pend[0][r], pend[1][r])));
+                have_pend = false;
+            }
+            if (blk == next_refresh) {
+                next_refresh = next_refresh * 5 / 2 + 1;
+                if (level >= 0) {
+                    if (takes_part) {
 #pragma unroll
-                    for (int w = 1; w < kGqaWaves; ++w) t = fminf(t, wmin[w * kGqaHeads + 4 * rg + r]);
-                    tau[r] = t;
+                        for (int r = 0; r < 4; ++r) {
+                            // largest within sets of 16 >> level lanes, then smallest over the sets
+                            float x = tj0[r], y;
+                            y = dpp_move<0xB1>(x);
+                            x = level < 4 ? fmaxf(x, y) : fminf(x, y);
+                            y = dpp_move<0x4E>(x);
+                            x = level < 3 ? fmaxf(x, y) : fminf(x, y);
+                            y = dpp_move<0x141>(x);
+                            x = level < 2 ? fmaxf(x, y) : fminf(x, y);
+                            y = dpp_move<0x140>(x);
+                            x = level < 1 ? fmaxf(x, y) : fminf(x, y);
+                            if (n == 0) wpub[wave * kGqaHeads + 4 * rg + r] = x;
+                        }
+                        // (a wave's own LDS operations complete in order; the other waves' entries
+                        // may be older, i.e. lower)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            float t = wpub[4 * rg + r];
+#pragma unroll
+                            for (int w = 1; w < kGqaWaves; ++w) t = fminf(t, wpub[w * kGqaHeads + 4 * rg + r]);
+                            if (n == 0 && t > -INFINITY)
+                                __hip_atomic_store(a.gbound + slot * kGqaHeads + 4 * rg + r, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                    }
+                    // read the peers' entries: lane n takes peers n and n + 16 (clamped: reading an
+                    // entry twice does not change a minimum)
+#pragma unroll
+                    for (int it = 0; it < 2; ++it) {
+                        const int peer = min(n + 16 * it, n_peers - 1);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            pend[it][r] = __hip_atomic_load(a.gbound + gb_first + (int64_t)peer * kGqaHeads + 4 * rg + r, __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    have_pend = true;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float mine = rank == 0 ? tj0[r] : tj1[r];
+                        if constexpr (FJ > 2) mine = rank == 2 ? tj2[r] : rank == 3 ? tj3[r] : mine;
+                        const float low = row16_min(mine);
+                        if (n == 0) wmin[wave * kGqaHeads + 4 * rg + r] = low;
+                    }
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float t = wmin[4 * rg + r];
+#pragma unroll
+                        for (int w = 1; w < kGqaWaves; ++w) t = fminf(t, wmin[w * kGqaHeads + 4 * rg + r]);
+                        tau[r] = fmaxf(tau[r], t);
+                    }
                 }
             }
             ++blk;
@@ -591,6 +742,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     }
     if constexpr (MODE == kModeLogits) return;  // nothing to merge or record
     if constexpr (MODE == kModeFilter) {
+        flush_staged();
         if (n == 0) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) a.surv_cnt[(slot * kGqaWaves + wave) * kGqaHeads + 4 * rg + r] = (int32_t)cnt[r];

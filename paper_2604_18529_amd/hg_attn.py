@@ -99,6 +99,7 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_full.argtypes = [D, vp, vp, vp, sz, vp]
     lib.hg_attn_plan.argtypes = [D, R, i32, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_int64)]
     lib.hg_attn_set_span_tokens.argtypes = [i32]
+    lib.hg_attn_set_topk_mode.argtypes = [i32]
     lib.hg_attn_profile_start.argtypes = [i32, i32]
     lib.hg_attn_calibration_copy.argtypes = [vp, vp, sz, vp]
     lib.hg_attn_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
@@ -106,7 +107,7 @@ def load_library() -> ctypes.CDLL:
         "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_merge_workspace_size", "hg_attn_merge",
         "hg_attn_merge2_workspace_size", "hg_attn_merge2", "hg_attn_gather_workspace_size", "hg_attn_gather",
         "hg_attn_topk_workspace_size", "hg_attn_topk",
-        "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_span_tokens",
+        "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_span_tokens", "hg_attn_set_topk_mode",
         "hg_attn_profile_start", "hg_attn_profile_stop", "hg_attn_calibration_copy",
         "hg_sched_init", "hg_sched_step", "hg_attn_logits_workspace_size", "hg_attn_logits", "hg_attn_select_workspace_size", "hg_attn_select", "hg_attn_concat_workspace_size", "hg_attn_concat",
     ):
@@ -213,6 +214,11 @@ def hg_attn_plan(q, k, v, seq_lens, ranges, scale=None) -> Tuple[int, int]:
 
 def hg_attn_set_span_tokens(span_tokens: int) -> None:
     _check(load_library().hg_attn_set_span_tokens(int(span_tokens)), "hg_attn_set_span_tokens")
+
+
+def hg_attn_set_topk_mode(mode: int) -> None:
+    """0: the library chooses; 1: filtering scan wherever it exists; 2: always logits -> select."""
+    _check(load_library().hg_attn_set_topk_mode(int(mode)), "hg_attn_set_topk_mode")
 
 
 def hg_attn_profile_start(max_calls: int, repeat: int = 1) -> None:

@@ -107,6 +107,37 @@ def test_full_and_merge_reject_bad_arguments(lib):
     assert lib.hg_attn_merge(FAKE, FAKE, FAKE, big.ctypes.data, 999, 4, 128, FAKE, None, None, 0, None) == -5
 
 
+def test_topk_rejects_bad_arguments_before_any_launch(lib):
+    d = _desc([1000, 20])
+    packed = B.pack_ranges([(0, 0, 900), (1, 0, 20)])
+    gp = np.array([0, 1, 2], dtype=np.int32)
+
+    def call(desc=d, ranges=packed, n=2, groups=gp.ctypes.data, g=2, k=16, sel=FAKE, m=FAKE, l=FAKE, o=FAKE, ws=FAKE * 16,
+             ws_bytes=1 << 40):
+        return lib.hg_attn_topk(ctypes.byref(desc), ranges, n, groups, g, k, sel, m, l, o, ws, ws_bytes, None)
+
+    assert call(k=0) == -2 and call(k=5000) == -2
+    assert call(m=None) == -1 and call(groups=None) == -1
+    assert call(ws=None, ws_bytes=0) == -5 and call(ws_bytes=64) == -5
+    bad = np.array([0, 2, 1], dtype=np.int32)
+    assert call(groups=bad.ctypes.data) == -4
+    mixed = np.array([0, 2, 2], dtype=np.int32)  # a group may not span two sequences
+    assert call(groups=mixed.ctypes.data) == -4
+    assert call(ranges=B.pack_ranges([(0, 0, 1001), (1, 0, 20)])) == -4
+    sz, sz2 = ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.hg_attn_topk_workspace_size(ctypes.byref(d), packed, 2, gp.ctypes.data, 2, 16, ctypes.byref(sz)) == 0
+    # room for every logit of every head at least (the two-call sequence inside keeps them there)
+    assert sz.value >= 4 * 920 * 4
+    try:
+        assert lib.hg_attn_set_topk_mode(1) == 0
+        assert lib.hg_attn_topk_workspace_size(ctypes.byref(d), packed, 2, gp.ctypes.data, 2, 16, ctypes.byref(sz2)) == 0
+        assert sz2.value >= 4 * sz.value - 4096  # the scan's worst case: four such arrays
+        assert lib.hg_attn_set_topk_mode(3) == -2 and lib.hg_attn_set_topk_mode(-1) == -2
+    finally:
+        lib.hg_attn_set_topk_mode(0)
+    assert call(n=0, g=0, ranges=None, groups=gp.ctypes.data) == 0  # nothing to do
+
+
 def test_gather_rejects_bad_arguments_before_any_launch(lib):
     d = _desc([10, 20])
     seqs = np.array([0, 1, 1], dtype=np.int32)

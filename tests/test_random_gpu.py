@@ -108,6 +108,19 @@ def test_random_case(case):
             what, g, h, got[g, h].tolist(), rsel[g, h].tolist(), row.tolist()))
     check_triples(sm, sl, so, rm, rl, ro, what + " select")
 
+    # the one-call executor stage: the same kept tokens as logits -> select on the logits the library
+    # itself computes (filtering scan forced on even cases, where it exists), and the triple of the
+    # oracle's listed-token routine over that list
+    hg.hg_attn_set_topk_mode(1 if case % 2 == 0 else 0)
+    try:
+        tsel, tm, tl, to = hg.hg_attn_topk(w.q, k_dev, v_dev, w.seq_lens, ranges, gp, top_k, w.scale, block_table=table)
+    finally:
+        hg.hg_attn_set_topk_mode(0)
+    usel, um, ul, uo = hg.hg_attn_select(w.q, k_dev, v_dev, w.seq_lens, ranges, lg, gp, top_k, w.scale, block_table=table)
+    assert torch.equal(tsel, usel), what + " topk: kept tokens differ from logits -> select"
+    tm3, tl3, to3 = oracle.attn_gather(qn, kn, vn, w.seq_lens, w.scale, list(range(batch)), to_np(tsel))
+    check_triples(tm, tl, to, tm3, tl3, to3, what + " topk")
+
     # the kept lists evaluated again as listed tokens (true query), plus a list with padding and
     # duplicates at seeded positions; groups are the sequences that have a group of ranges
     group_seq = [b for b in range(batch)]

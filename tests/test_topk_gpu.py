@@ -25,11 +25,15 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.fixture(autouse=True)
-def _default_spans():
+@pytest.fixture(autouse=True, params=["scan", "auto"])
+def _modes(request):
+    """Every test runs with the filtering scan forced wherever it exists (the inputs here are far
+    shorter than what the library would choose it for) and with the library's own choice."""
     hg.hg_attn_set_span_tokens(0)
+    hg.hg_attn_set_topk_mode(1 if request.param == "scan" else 0)
     yield
     hg.hg_attn_set_span_tokens(0)
+    hg.hg_attn_set_topk_mode(0)
 
 
 def _groups_per_sequence(w, rng, max_ranges=3, frac=0.8):
@@ -92,11 +96,30 @@ def test_many_segments_and_edge_ranges(span, top_k):
     _check_exact(w, ranges, gp, top_k, "span=%d k=%d" % (span, top_k))
 
 
+@pytest.mark.parametrize("span", [256, 1024, 4096])
+@pytest.mark.parametrize("dtype,group,top_k", [("f16", 8, 128), ("bf16", 4, 256), ("f16", 16, 7), ("f16", 2, 200)])
+def test_many_workgroups_per_group_share_their_bounds(dtype, group, top_k, span):
+    """Long groups cut into many spans: the workgroups of a (range, stream) pair exchange bounds
+    through memory while they run.  Whatever each of them happens to read, the kept set is the
+    oracle's, bit for bit (run twice: the timing differs, the result must not)."""
+    hg.hg_attn_set_span_tokens(span)
+    spec = W.WorkloadSpec("topkshare", 2, 2 * group, 2, 128, dtype, 30000, 60000, "none", seed=119)
+    w = W.make_workload(spec, DEV)
+    W.make_dyadic_(w, seed=120)
+    w.scale = 0.125
+    n0, n1 = (int(x) for x in w.seq_lens)
+    ranges = [(0, 0, n0 - 500), (1, 100, 9000), (1, 9000, n1)]
+    for _ in range(2):
+        _check_exact(w, ranges, [0, 1, 3], top_k, "%s G=%d k=%d span=%d" % (dtype, group, top_k, span))
+
+
+@pytest.mark.parametrize("span", [0, 2048])
 @pytest.mark.parametrize("order", ["ascending", "descending", "equal"])
-def test_orders_that_defeat_the_bound(order):
+def test_orders_that_defeat_the_bound(order, span):
     """Logits that rise with the token index pass every running bound (the scan writes all of
     them out), falling ones pass none after the start, equal ones all tie: the result is the same
     selection, with ties going to the earlier token."""
+    hg.hg_attn_set_span_tokens(span)
     N, d, group = 20000, 128, 8
     spec = W.WorkloadSpec("topkorder", 1, group, 1, d, "f16", N, N, "none", seed=115)
     w = W.make_workload(spec, DEV)
@@ -148,6 +171,22 @@ def test_equals_logits_then_select_and_is_valid_against_the_oracle(dtype, d, gro
                 assert max(of_tok[t] for t in missing.tolist()) <= kth + 2 * LOGIT_TOL, "a clearly larger logit was dropped"
     gm, gl, go = oracle.attn_gather(qn, kn, vn, w.seq_lens, w.scale, list(range(len(gp) - 1)), got)
     check_triples(m, l, o, gm, gl, go, "triple over the kept list")
+
+
+def test_long_group_takes_the_scan_by_itself_and_matches_the_two_call_sequence():
+    """One 600k-token group, top_k 128: long enough for the library to choose the filtering scan;
+    forced to the two-call sequence it must keep the same tokens."""
+    spec = W.WorkloadSpec("topklong", 1, 8, 1, 128, "f16", 600000, 600000, "none", outlier_k=True, seed=121)
+    w = W.make_workload(spec, DEV)
+    ranges, gp = [(0, 0, 300000), (0, 300000, 590000)], [0, 2]
+    hg.hg_attn_set_topk_mode(0)
+    sel, m, l, o = hg.hg_attn_topk(w.q, w.k, w.v, w.seq_lens, ranges, gp, 128, w.scale)
+    hg.hg_attn_set_topk_mode(2)
+    sel2, m2, l2, o2 = hg.hg_attn_topk(w.q, w.k, w.v, w.seq_lens, ranges, gp, 128, w.scale)
+    assert torch.equal(sel, sel2) and torch.equal(m, m2)
+    assert (o - o2).abs().max().item() <= 1e-3
+    gm, gl, go = oracle.attn_gather(to_np(w.q), *kv_np(w), w.seq_lens, w.scale, [0], to_np(sel))
+    check_triples(m, l, o, gm, gl, go, "long group")
 
 
 def test_full_cover_reproduces_unsplit_attention():
