@@ -240,10 +240,10 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
  *   ranges, group_ptr, top_k, sel, m, l, o   as for hg_attn_select.
  *   workspace   DEVICE, 256-byte aligned, hg_attn_topk_workspace_size bytes: room for the worst
  *               case of the scan (4 x 4 bytes per (query head, token of the ranges)).
- *   The filtering scan exists for top_k <= 256 on contiguous caches with 16-bit storage, head_dim
- *   128 and two or more query heads per KV head, and is chosen when the groups are long (see
- *   hg_attn_set_topk_mode); other cases run the two-call sequence inside, with the logits in the
- *   workspace.
+ *   The filtering scan exists for top_k <= 256 on contiguous caches, for one query head per KV
+ *   head (any storage type) and for 16-bit storage with head_dim 128 and two or more query heads
+ *   per KV head; it is chosen when the groups are long (see hg_attn_set_topk_mode).  Other cases
+ *   run the two-call sequence inside, with the logits in the workspace.
  */
 hg_status hg_attn_topk_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges,
                                       const int32_t *group_ptr, int32_t n_groups, int32_t top_k, size_t *bytes);
@@ -315,7 +315,8 @@ hg_status hg_attn_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t
 hg_status hg_attn_set_span_tokens(int32_t span_tokens);
 
 /* Tuning knob for hg_attn_topk: 0 = the library chooses between the filtering scan and the
- * two-call sequence (the scan needs long groups: at least 2048 tokens per kept token on average),
+ * two-call sequence (the scan needs long groups: on average at least 256 tokens per kept token with
+ * one query head per KV head, 2048 with grouped queries),
  * 1 = the filtering scan wherever it exists, 2 = never.  The results are the same.  Process-wide;
  * not thread-safe against concurrent calls. */
 hg_status hg_attn_set_topk_mode(int32_t mode);

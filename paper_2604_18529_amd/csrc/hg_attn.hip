@@ -601,27 +601,37 @@ hg_status select_stages(const hg_attn_desc *desc, const Plan &p, const SelectPla
 
 // hg_attn_topk: the scan that keeps only logits which can still be among a group's top_k (filter
 // mode of the streaming kernels) exists for the matrix-core kernel of 256-byte rows and for the
-// vector kernel with one query head per KV head, contiguous caches, top_k <= kFilterMaxTopK;
-// everything else exports all logits to the workspace and selects from them.
+// vector kernel with one query head per KV head (any storage type), contiguous caches,
+// top_k <= kFilterMaxTopK; everything else exports all logits to the workspace and selects from them.
 constexpr int kFilterMaxTopK = 256;
 
 bool filter_supported(const hg_attn_desc *d, int32_t top_k)
 {
     if (g_topk_mode == 2 || top_k > kFilterMaxTopK || d->block_table) return false;
     if (use_gqa_kernel(d)) return d->head_dim == 128;
-    return false;
+    return d->n_q_heads == d->n_kv_heads;  // vector kernel: one query head per KV head
 }
 
+// Distinct logits per workgroup that the own bound of the matrix-core filter scan rests on when
+// every lane keeps one of them: 4 waves x 16 lanes of a head.  (The vector kernel counts among
+// the four logits each of its >= 32 row lanes per wave keeps: 128 per wave, of which it needs
+// top_k / 4 <= 64.)
+int filter_sets(const hg_attn_desc *) { return kGqaWaves * 16; }
+
 // The filter scan pays off when the groups are long against top_k: the bounds rise like the
-// logarithm of the tokens seen, so a short group lets a large share of its logits through (a third
-// at 26k tokens and top_k 128, against 4 % at 840k) and the two-call sequence is faster then.
-constexpr int64_t kFilterMinTokensPerKept = 2048;
+// logarithm of the tokens seen, so a short group lets a large share of its logits through and
+// the two-call sequence is faster then.  Measured at top_k 128: the vector kernel's scan loses at
+// 6.5k tokens per group (a third survives), is level at 20k and wins by a fifth at 105k (5 %
+// survive); the matrix-core kernel's scan, which has less time to spare per block, loses at 26k
+// and wins by a sixth at 840k (4 %).
+constexpr int64_t kFilterMinTokensPerKeptValu = 256, kFilterMinTokensPerKeptGqa = 2048;
 
 bool filter_chosen(const hg_attn_desc *d, int32_t top_k, int64_t ltok, int32_t n_groups)
 {
     if (!filter_supported(d, top_k)) return false;
     if (g_topk_mode == 1) return true;
-    return ltok >= kFilterMinTokensPerKept * top_k * std::max<int32_t>(n_groups, 1);
+    const int64_t per_kept = use_gqa_kernel(d) ? kFilterMinTokensPerKeptGqa : kFilterMinTokensPerKeptValu;
+    return ltok >= per_kept * top_k * std::max<int32_t>(n_groups, 1);
 }
 
 int filter_sub_spans(const hg_attn_desc *d) { return use_gqa_kernel(d) ? kGqaWaves : kValuWaves; }
@@ -676,9 +686,24 @@ TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, i
     return tp;
 }
 
+template <typename TR>
+void launch_valu_filter(const PartialArgs &a, dim3 grid, hipStream_t stream)
+{
+    hipLaunchKernelGGL((hg_partial_kernel<TR, 1, 2 * HG_VALU_U, kModeFilter, false>), grid, dim3(kValuBlock), 0, stream, a);
+}
+
 void launch_filter(const hg_attn_desc *d, const PartialArgs &a, dim3 grid, hipStream_t stream)
 {
     // (filter_supported() admits exactly the variants instantiated here)
+    if (!use_gqa_kernel(d)) {
+        const bool wide = d->head_dim == 128;
+        switch (d->dtype) {
+        case HG_F16: wide ? launch_valu_filter<Traits<128, kDtF16>>(a, grid, stream) : launch_valu_filter<Traits<64, kDtF16>>(a, grid, stream); break;
+        case HG_BF16: wide ? launch_valu_filter<Traits<128, kDtBf16>>(a, grid, stream) : launch_valu_filter<Traits<64, kDtBf16>>(a, grid, stream); break;
+        default: wide ? launch_valu_filter<Traits<128, kDtF32>>(a, grid, stream) : launch_valu_filter<Traits<64, kDtF32>>(a, grid, stream); break;
+        }
+        return;
+    }
     const bool wide = a.filter_rank >= 2;  // four kept logits per lane instead of two
     if (d->dtype == HG_BF16) {
         if (wide)
@@ -1174,7 +1199,7 @@ hg_status hg_attn_topk(const hg_attn_desc *desc, const hg_range *ranges, int32_t
     pa.surv_val = reinterpret_cast<float *>(ws + tp.off_surv_val);
     pa.surv_col = reinterpret_cast<int32_t *>(ws + tp.off_surv_col);
     pa.surv_cnt = reinterpret_cast<int32_t *>(ws + tp.off_surv_cnt);
-    pa.filter_rank = (top_k + 63) / 64 - 1;  // 64 lanes-and-waves per head keep rank + 1 logits each
+    pa.filter_rank = (top_k + filter_sets(desc) - 1) / filter_sets(desc) - 1;  // every set keeps rank + 1 logits
     pa.filter_k = top_k;
     pa.gbound = reinterpret_cast<float *>(ws + tp.off_gbound);
     if (p.n_workgroups > 0) {

@@ -283,6 +283,19 @@ __device__ __forceinline__ float lane_group_sum(float x)
     return x;
 }
 
+// Order-preserving integer keys of fp32 values: larger float <=> larger key.
+__device__ __forceinline__ uint32_t order_key(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    u = u == 0x80000000u ? 0u : u;                      // -0.0 and +0.0 are one value: they tie
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // larger float <=> larger key
+}
+
+__device__ __forceinline__ float key_to_float(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
+}
+
 __device__ __forceinline__ RangeEntry table_entry(const RangeTable &tab, int i)
 {
     return tab.ext ? tab.ext[i] : tab.inl[i];

@@ -41,18 +41,6 @@ namespace hg {
 // Inputs that defeat the bound (sorted rows, masked rows full of -inf, too many candidates) fall
 // back to the radix passes over the row; the result is the same either way.
 
-__device__ __forceinline__ uint32_t order_key(float x)
-{
-    uint32_t u = __float_as_uint(x);
-    u = u == 0x80000000u ? 0u : u;                      // -0.0 and +0.0 are one value: they tie
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // larger float <=> larger key
-}
-
-__device__ __forceinline__ float key_to_float(uint32_t k)
-{
-    return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
-}
-
 constexpr int kSelectFastBlock = 512;                             // threads of the FAST variants (8 waves)
 constexpr int kSelectRegs = 32;                                   // elements per thread of the fast path
 constexpr int kSelectRegTokens = kSelectRegs * kSelectFastBlock;  // 16384

@@ -47,11 +47,28 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
     constexpr int CH = RPW * U;  // tokens one wave takes per iteration
 
     __shared__ float sm[kValuWaves][GT][D + 2];
+    // filter mode (one head per stream): each wave's bound, and the survivors waiting to be written out
+    constexpr int kStage = 2 * CH;
+    __shared__ volatile float wmin[MODE == kModeFilter ? kValuWaves : 1];
+    __shared__ float stage_val[MODE == kModeFilter ? kValuWaves * kStage : 1];
+    __shared__ int32_t stage_col[MODE == kModeFilter ? kValuWaves * kStage : 1];
+    static_assert(MODE != kModeFilter || (GT == 1 && U <= LPR && CH <= 64), "filter mode: one head, one lane per row of an iteration");
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane % LPR, grp = lane / LPR;
 
-    for_each_segment(a.ws, a.tab, [&](int stream, int r_idx, const RangeEntry &e, int t0, int t1, int col0, int64_t slot) __attribute__((always_inline)) {
+    for_each_segment(a.ws, a.tab, [&](int stream, int r_idx, const RangeEntry &e, int seg_t0, int seg_t1, int seg_col0, int64_t slot) __attribute__((always_inline)) {
+    // Tokens [t0, t1) the waves share iteration by iteration and the column of t0 -- or, in filter
+    // mode, this wave's own consecutive sub-span, so that what it appends is in column order.
+    int t0 = seg_t0, t1 = seg_t1, col0 = seg_col0;
+    const int first = MODE == kModeFilter ? 0 : wave * CH;            // this wave's first iteration, relative to t0
+    constexpr int kStep = MODE == kModeFilter ? CH : kValuWaves * CH;  // from one of its iterations to the next
+    if constexpr (MODE == kModeFilter) {
+        const int sub_len = filter_sub_len(seg_t1 - seg_t0, kValuWaves);
+        t0 = min(seg_t0 + wave * sub_len, seg_t1);
+        t1 = min(t0 + sub_len, seg_t1);
+        col0 = seg_col0 + (t0 - seg_t0);
+    }
     const int seq = e.seq;
     const int hk = stream / a.ws.n_chunks;
     const int chunk = stream - hk * a.ws.n_chunks;
@@ -118,10 +135,48 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
         }
     };
     if constexpr (PAGED) {
-        if (t0 + wave * CH < t1) lookup(t0 + wave * CH, pg);
+        if (t0 + first < t1) lookup(t0 + first, pg);
     }
 
-    for (int tb = t0 + wave * CH; tb < t1; tb += kValuWaves * CH) {
+    // Filter mode.  Lane `sub` of a lane group speaks for row `sub` of the group's U rows of an
+    // iteration (sub < U) and keeps the four largest logits it has seen.  At a refresh every wave
+    // finds, by bisection on the key bits with ballots, a value that ceil(top_k / waves) of the
+    // logits its lanes keep reach; the smallest of the waves' values is then reached by top_k
+    // distinct logits of this segment: a lower bound of the group's top_k-th largest logit, below
+    // which nothing can be among the kept tokens.  (Counting among all kept logits follows the
+    // true value far more closely than the smallest of the lanes' maxima would: that one sits at
+    // the level of about the 700th largest logit for 128 lanes, this one near the 180th.)
+    // Survivors are staged in LDS in column order and
+    // written out in runs (a conditional global store in every iteration would leave the number of
+    // memory operations in flight unknown at compile time and stall the row loads).
+    const bool owner = sub < U;
+    float top_a = -INFINITY, top_b = -INFINITY, top_c = -INFINITY, top_d = -INFINITY, tau = -INFINITY;
+    uint32_t staged = 0, written = 0;
+    int iter = 0, next_refresh = 1;
+    auto flush_staged = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int64_t dst = (int64_t)h0 * a.ws.ltok + col0 + written;
+#pragma unroll
+        for (int x = 0; x < kStage; x += 64) {
+            if (x + lane < (int)staged) {
+                a.surv_val[dst + x + lane] = stage_val[wave * kStage + x + lane];
+                a.surv_col[dst + x + lane] = stage_col[wave * kStage + x + lane];
+            }
+        }
+        written += staged;
+        staged = 0;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    if constexpr (MODE == kModeFilter) {
+        if (lane == 0) wmin[wave] = -INFINITY;
+        __syncthreads();
+    }
+
+    for (int tb = t0 + first; tb < t1; tb += kStep) {
         typename TR::Raw kraw[U][NV], vraw[U][NV];
         bool valid[U];
         int tokc[U];
@@ -136,14 +191,14 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
 #pragma unroll
                 for (int j = 0; j < NV; ++j) kraw[u][j] = TR::template load<true>(kbase + off, sub, j);
             }
-            if constexpr (MODE != kModeLogits) {
+            if constexpr (MODE != kModeLogits && MODE != kModeFilter) {
 #pragma unroll
                 for (int j = 0; j < NV; ++j) vraw[u][j] = TR::template load<true>(vbase + off, sub, j);
             }
         }
 
         if constexpr (PAGED) {
-            if (tb + kValuWaves * CH < t1) lookup(tb + kValuWaves * CH, pg_next);
+            if (tb + kStep < t1) lookup(tb + kStep, pg_next);
         }
         // concat mode: the given logits of these tokens (unconditional loads, issued with the V loads)
         float sv[GT][U];
@@ -202,7 +257,70 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
             }
         }
 
-        if constexpr (MODE != kModeLogits) {
+        if constexpr (MODE == kModeFilter) {
+            // this lane's row of the iteration: logit, validity, token
+            float val = -INFINITY;
+            int tok = t0;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (sub == u) {
+                    val = s[0][u];  // (-inf past the end of the sub-span)
+                    tok = tokc[u];
+                }
+            if (!owner) val = -INFINITY;
+            const uint64_t pass = __builtin_amdgcn_ballot_w64(val >= tau && val > -INFINITY);
+            if (pass) {
+                // rows of an iteration in token order: row u of group g is token RPW * u + g
+                constexpr uint64_t kEvery = LPR == 16 ? 0x0001000100010001ull : 0x0101010101010101ull;  // one lane per group
+                const uint64_t rows_before = kEvery * ((1ull << sub) - 1ull);                   // rows u' < u of every group
+                const uint64_t same_row = (kEvery << sub) & ((1ull << (grp * LPR)) - 1ull);      // row u of the groups before
+                if (val >= tau && val > -INFINITY) {
+                    const int at = wave * kStage + (int)staged + __builtin_popcountll(pass & rows_before) + __builtin_popcountll(pass & same_row);
+                    stage_val[at] = val;
+                    stage_col[at] = col0 + (tok - t0);
+                }
+                staged += (uint32_t)__builtin_popcountll(pass);
+                if (staged > (uint32_t)(kStage - CH)) flush_staged();  // uniform
+            }
+            {   // the four largest of this lane's rows
+                float x = val, hi;
+                hi = fmaxf(top_a, x);
+                x = fminf(top_a, x);
+                top_a = hi;
+                hi = fmaxf(top_b, x);
+                x = fminf(top_b, x);
+                top_b = hi;
+                hi = fmaxf(top_c, x);
+                x = fminf(top_c, x);
+                top_c = hi;
+                top_d = fmaxf(top_d, x);
+            }
+            if (iter == next_refresh) {
+                next_refresh = next_refresh * 5 / 2 + 1;
+                // largest key (upper 20 bits) that `need` of the wave's kept logits reach; lanes that
+                // speak for no row hold -inf four times, which no useful bound admits
+                const uint32_t ka = order_key(top_a), kb = order_key(top_b), kc = order_key(top_c), kd = order_key(top_d);
+                const int need = (a.filter_k + kValuWaves - 1) / kValuWaves;
+                uint32_t tw = 0u;
+                for (int b = 31; b >= 12; --b) {
+                    const uint32_t c = tw | (1u << b);
+                    const int reach = __builtin_popcountll(__builtin_amdgcn_ballot_w64(ka >= c)) + __builtin_popcountll(__builtin_amdgcn_ballot_w64(kb >= c)) +
+                                      __builtin_popcountll(__builtin_amdgcn_ballot_w64(kc >= c)) + __builtin_popcountll(__builtin_amdgcn_ballot_w64(kd >= c));
+                    if (reach >= need) tw = c;
+                }
+                const float low = tw > order_key(-INFINITY) ? key_to_float(tw) : -INFINITY;
+                if (lane == 0) wmin[wave] = low;
+                // (a wave's own LDS operations complete in order; the other waves' entries may be
+                // older, i.e. lower, which is still a valid bound)
+                float t = wmin[0];
+#pragma unroll
+                for (int w = 1; w < kValuWaves; ++w) t = fminf(t, wmin[w]);
+                tau = fmaxf(tau, t);
+            }
+            ++iter;
+        }
+
+        if constexpr (MODE != kModeLogits && MODE != kModeFilter) {
         float p[GT][U];
         if constexpr (MODE == kModeStats) {
             // online softmax update
@@ -247,13 +365,19 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
 #pragma unroll
                 for (int i = 0; i < EPL; ++i) acc[g][i] = fmaf(p[g][u], vf[i], acc[g][i]);
         }
-        }  // MODE != kModeLogits
+        }  // modes that read V
         if constexpr (PAGED) {
 #pragma unroll
             for (int u = 0; u < U; ++u) pg[u] = pg_next[u];
         }
     }
     if constexpr (MODE == kModeLogits) return;  // nothing to merge or record
+    if constexpr (MODE == kModeFilter) {
+        flush_staged();
+        if (lane == 0) a.surv_cnt[(slot * kValuWaves + wave) * GT] = (int32_t)written;
+        __syncthreads();  // the next segment resets the waves' bounds
+        return;
+    }
 
     // merge the lane groups of the wave (lanes xor 16, xor 32; xor 8 too when a group is 8 lanes)
 #pragma unroll
