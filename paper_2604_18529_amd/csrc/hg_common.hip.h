@@ -296,6 +296,12 @@ __device__ __forceinline__ float key_to_float(uint32_t k)
     return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
 }
 
+// Hand-over of a float between the waves of a workgroup through LDS, without a barrier: relaxed
+// atomics keep the accesses real LDS instructions at the place they are written (a volatile
+// access compiled to a FLAT instruction, which ties up the vector-memory counters as well).
+__device__ __forceinline__ void lds_publish(float *p, float x) { __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+__device__ __forceinline__ float lds_peek(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+
 __device__ __forceinline__ RangeEntry table_entry(const RangeTable &tab, int i)
 {
     return tab.ext ? tab.ext[i] : tab.inl[i];

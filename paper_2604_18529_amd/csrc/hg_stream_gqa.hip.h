@@ -35,6 +35,7 @@ constexpr int kGqaKRow = 272;            // padded LDS row: 256 bytes + 16 so th
 constexpr int kGqaKBytes = kGqaBlockTokens * kGqaKRow;
 constexpr int kGqaPBytes = kGqaHeads * kGqaBlockTokens * 2;
 constexpr int kGqaWaveBytes = kGqaKBytes + 2 * kGqaPBytes;
+constexpr int kWaitVmcnt0 = 0x0F70;      // s_waitcnt vmcnt(0) alone (expcnt and lgkmcnt fields at their maxima)
 constexpr int kGqaStage = 64;            // filter mode: survivors staged in LDS per (wave, head) between write-outs
 
 typedef _Float16 hg_h8 __attribute__((ext_vector_type(8)));
@@ -132,8 +133,8 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     constexpr int kSmemBytes = kGqaWaves * kGqaWaveBytes > kMergeBytes ? kGqaWaves * kGqaWaveBytes : kMergeBytes;
     __shared__ __align__(16) char smem[kSmemBytes];
     // filter mode: per wave and head, the smallest of the 16 lanes' rank-th largest logits
-    __shared__ volatile float wmin[MODE == kModeFilter ? kGqaWaves * kGqaHeads : 1];  // own bound: [wave][head]
-    __shared__ volatile float wpub[MODE == kModeFilter ? kGqaWaves * kGqaHeads : 1];  // shared bound: each wave's part
+    __shared__ float wmin[MODE == kModeFilter ? kGqaWaves * kGqaHeads : 1];  // own bound: [wave][head]
+    __shared__ float wpub[MODE == kModeFilter ? kGqaWaves * kGqaHeads : 1];  // shared bound: each wave's part
     // filter mode: survivors wait here, per wave and head, until a run of them is written out
     __shared__ float stage_val[MODE == kModeFilter ? kGqaWaves * kGqaHeads * kGqaStage : 1];
     __shared__ int32_t stage_col[MODE == kModeFilter ? kGqaWaves * kGqaHeads * kGqaStage : 1];
@@ -311,8 +312,8 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
             tj0[r] = tj1[r] = tj2[r] = tj3[r] = -INFINITY;
         }
         if (lane < kGqaHeads) {
-            wmin[wave * kGqaHeads + lane] = -INFINITY;
-            wpub[wave * kGqaHeads + lane] = -INFINITY;
+            lds_publish(&wmin[wave * kGqaHeads + lane], -INFINITY);
+            lds_publish(&wpub[wave * kGqaHeads + lane], -INFINITY);
         }
         __syncthreads();
     }
@@ -320,13 +321,14 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     // Write the staged survivors of every head of this wave behind those already written out.
     auto flush_staged = [&]() __attribute__((always_inline)) {
         wave_lds_handover();
+        const int64_t ltok_here = a.ws.ltok;
 #pragma unroll
         for (int hh = 0; hh < kGqaHeads; ++hh) {
             // head hh is held by row group hh / 4 as its entry hh % 4; lane 16 * (hh / 4) speaks for the group
             const int c = __builtin_amdgcn_readlane((int)staged[hh & 3], 16 * (hh >> 2));
             if (c == 0) continue;
             const int done = __builtin_amdgcn_readlane((int)cnt[hh & 3], 16 * (hh >> 2));
-            const int64_t dst = (int64_t)(h0 + hh) * a.ws.ltok + col0 + done;
+            const int64_t dst = (int64_t)(h0 + hh) * ltok_here + col0 + done;
             const int src = (wave * kGqaHeads + hh) * kGqaStage;
             if (lane < c) {
                 a.surv_val[dst + lane] = stage_val[src + lane];
@@ -338,6 +340,10 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
             cnt[r] += staged[r];
             staged[r] = 0u;
         }
+        // Let the stores retire here, on the rare path.  While a store may be in flight the
+        // compiler has to treat the loads' completion order as unknown and waits for ALL of them
+        // before it touches a K row, which would undo the two register buffers.
+        __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
         wave_lds_handover();
     };
 
@@ -358,20 +364,45 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
             const int tb_3 = tb + 3 * (tb_next - tb);
             if (tb_3 < t1) lookup(tb_3, pg3);
         }
-        if (tb_next < t1) {
+        // K-only modes on a contiguous cache request the rows of the block after next
+        // unconditionally (past the end the clamped offsets re-read the segment's last row, at
+        // most two blocks' worth per segment): with a conditional request the number of loads in
+        // flight is unknown at compile time, the wait for this block's rows becomes a wait for all
+        // loads, and the second register buffer buys nothing.
+        constexpr bool kAlwaysAhead = !PAGED && (MODE == kModeLogits || MODE == kModeFilter);
+        if (kAlwaysAhead || tb_next < t1) {
             load_k(tb_next, kreg, pg1);
             if constexpr (PAGED && (MODE == kModeLogits || MODE == kModeFilter)) {  // blocks are loaded in order: pages of the one after
                 if (tb_next + kStride < t1) lookup(tb_next + kStride, pg1);
             }
         }
         hg_f4 s[2];
+        if constexpr (MODE == kModeFilter) {
+            // all eight LDS reads first, then the products: with every register in use the compiler
+            // otherwise sends each read and its product through one register quad, eight LDS round
+            // trips in a row
+            hg_u32x4 kf[2][4];
 #pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-            s[hf] = hg_f4{0.f, 0.f, 0.f, 0.f};
+            for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                hg_u32x4 raw = *reinterpret_cast<const hg_u32x4 *>(kls + (16 * hf + n) * kGqaKRow + (4 * kk + rg) * 16);
-                s[hf] = mfma_16x16x32<BF16>(qa[kk], raw, s[hf]);
+                for (int kk = 0; kk < 4; ++kk)
+                    kf[hf][kk] = *reinterpret_cast<const hg_u32x4 *>(kls + (16 * hf + n) * kGqaKRow + (4 * kk + rg) * 16);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                s[hf] = hg_f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) s[hf] = mfma_16x16x32<BF16>(qa[kk], kf[hf][kk], s[hf]);
+            }
+        } else {
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                s[hf] = hg_f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    hg_u32x4 raw = *reinterpret_cast<const hg_u32x4 *>(kls + (16 * hf + n) * kGqaKRow + (4 * kk + rg) * 16);
+                    s[hf] = mfma_16x16x32<BF16>(qa[kk], raw, s[hf]);
+                }
             }
         }
 
@@ -490,6 +521,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
             if (blk == next_refresh) {
                 next_refresh = next_refresh * 5 / 2 + 1;
                 if (level >= 0) {
+                    float *gb = a.gbound;
                     if (takes_part) {
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
@@ -503,18 +535,19 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
                             x = level < 2 ? fmaxf(x, y) : fminf(x, y);
                             y = dpp_move<0x140>(x);
                             x = level < 1 ? fmaxf(x, y) : fminf(x, y);
-                            if (n == 0) wpub[wave * kGqaHeads + 4 * rg + r] = x;
+                            if (n == 0) lds_publish(&wpub[wave * kGqaHeads + 4 * rg + r], x);
                         }
                         // (a wave's own LDS operations complete in order; the other waves' entries
                         // may be older, i.e. lower)
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            float t = wpub[4 * rg + r];
+                            float t = lds_peek(&wpub[4 * rg + r]);
 #pragma unroll
-                            for (int w = 1; w < kGqaWaves; ++w) t = fminf(t, wpub[w * kGqaHeads + 4 * rg + r]);
+                            for (int w = 1; w < kGqaWaves; ++w) t = fminf(t, lds_peek(&wpub[w * kGqaHeads + 4 * rg + r]));
                             if (n == 0 && t > -INFINITY)
-                                __hip_atomic_store(a.gbound + slot * kGqaHeads + 4 * rg + r, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                __hip_atomic_store(gb + slot * kGqaHeads + 4 * rg + r, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
+                        __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // (stores: see flush_staged)
                     }
                     // read the peers' entries: lane n takes peers n and n + 16 (clamped: reading an
                     // entry twice does not change a minimum)
@@ -523,7 +556,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
                         const int peer = min(n + 16 * it, n_peers - 1);
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
-                            pend[it][r] = __hip_atomic_load(a.gbound + gb_first + (int64_t)peer * kGqaHeads + 4 * rg + r, __ATOMIC_RELAXED,
+                            pend[it][r] = __hip_atomic_load(gb + gb_first + (int64_t)peer * kGqaHeads + 4 * rg + r, __ATOMIC_RELAXED,
                                                             __HIP_MEMORY_SCOPE_AGENT);
                     }
                     have_pend = true;
@@ -533,13 +566,13 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
                         float mine = rank == 0 ? tj0[r] : tj1[r];
                         if constexpr (FJ > 2) mine = rank == 2 ? tj2[r] : rank == 3 ? tj3[r] : mine;
                         const float low = row16_min(mine);
-                        if (n == 0) wmin[wave * kGqaHeads + 4 * rg + r] = low;
+                        if (n == 0) lds_publish(&wmin[wave * kGqaHeads + 4 * rg + r], low);
                     }
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        float t = wmin[4 * rg + r];
+                        float t = lds_peek(&wmin[4 * rg + r]);
 #pragma unroll
-                        for (int w = 1; w < kGqaWaves; ++w) t = fminf(t, wmin[w * kGqaHeads + 4 * rg + r]);
+                        for (int w = 1; w < kGqaWaves; ++w) t = fminf(t, lds_peek(&wmin[w * kGqaHeads + 4 * rg + r]));
                         tau[r] = fmaxf(tau[r], t);
                     }
                 }
@@ -729,12 +762,19 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
                 else
                     concat_block(t, t + 2 * kStride, reg, sv);
             };
-            if (tb < t1) load_one(tb, ra, sa);
-            if (tb + kStride < t1) load_one(tb + kStride, rb, sb);
+            constexpr bool kAlwaysAhead = !PAGED && (MODE == kModeLogits || MODE == kModeFilter);
+            if (tb < t1) {
+                load_one(tb, ra, sa);
+                if (kAlwaysAhead || tb + kStride < t1) load_one(tb + kStride, rb, sb);
+            }
             while (tb < t1) {
                 compute_one(tb, ra, sa);
                 tb += kStride;
-                if (tb >= t1) break;
+                // (the filter mode runs the second block of the pair even past the end -- all its
+                // tokens are then masked -- so that the loop body is one straight line: with the
+                // exit in the middle the compiler no longer knew how many loads are in flight at
+                // the top of the loop and waited there for all of them)
+                if (MODE != kModeFilter && tb >= t1) break;
                 compute_one(tb, rb, sb);
                 tb += kStride;
             }

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
     __shared__ float sm[kValuWaves][GT][D + 2];
     // filter mode (one head per stream): each wave's bound, and the survivors waiting to be written out
     constexpr int kStage = 2 * CH;
-    __shared__ volatile float wmin[MODE == kModeFilter ? kValuWaves : 1];
+    __shared__ float wmin[MODE == kModeFilter ? kValuWaves : 1];
     __shared__ float stage_val[MODE == kModeFilter ? kValuWaves * kStage : 1];
     __shared__ int32_t stage_col[MODE == kModeFilter ? kValuWaves * kStage : 1];
     static_assert(MODE != kModeFilter || (GT == 1 && U <= LPR && CH <= 64), "filter mode: one head, one lane per row of an iteration");
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
     if constexpr (MODE == kModeFilter) {
-        if (lane == 0) wmin[wave] = -INFINITY;
+        if (lane == 0) lds_publish(&wmin[wave], -INFINITY);
         __syncthreads();
     }
 
@@ -309,12 +309,12 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
                     if (reach >= need) tw = c;
                 }
                 const float low = tw > order_key(-INFINITY) ? key_to_float(tw) : -INFINITY;
-                if (lane == 0) wmin[wave] = low;
+                if (lane == 0) lds_publish(&wmin[wave], low);
                 // (a wave's own LDS operations complete in order; the other waves' entries may be
                 // older, i.e. lower, which is still a valid bound)
-                float t = wmin[0];
+                float t = lds_peek(&wmin[0]);
 #pragma unroll
-                for (int w = 1; w < kValuWaves; ++w) t = fminf(t, wmin[w]);
+                for (int w = 1; w < kValuWaves; ++w) t = fminf(t, lds_peek(&wmin[w]));
                 tau = fmaxf(tau, t);
             }
             ++iter;
