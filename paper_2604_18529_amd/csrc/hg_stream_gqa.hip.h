@@ -770,11 +770,11 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
             while (tb < t1) {
                 compute_one(tb, ra, sa);
                 tb += kStride;
-                // (the filter mode runs the second block of the pair even past the end -- all its
-                // tokens are then masked -- so that the loop body is one straight line: with the
+                // (the K-only modes on a contiguous cache run the second block of the pair even past
+                // the end -- all its tokens are then masked -- so that the loop body is one straight line: with the
                 // exit in the middle the compiler no longer knew how many loads are in flight at
                 // the top of the loop and waited there for all of them)
-                if (MODE != kModeFilter && tb >= t1) break;
+                if (!kAlwaysAhead && tb >= t1) break;
                 compute_one(tb, rb, sb);
                 tb += kStride;
             }
