@@ -92,3 +92,49 @@ def test_full_size_range_membership_is_bit_exact(index):
         assert np.all(l[r] == float(e - s)) and np.all(m[r] == 0.0)
         want = np.array([_bit_count(e, c) - _bit_count(s, c) if c < 24 else 0 for c in range(d)], dtype=np.float64)
         assert np.array_equal(o[r].astype(np.float64), np.broadcast_to(want, o[r].shape)), "range %d" % r
+
+
+@pytest.mark.parametrize("index", [3, 4])
+def test_full_size_topk_scan_against_two_call_sequence_and_oracle(index):
+    """hg_attn_topk at the benchmark sizes, as bench.py calls it (80 % of every cache offloaded,
+    top-128, the library's own choice, which is the filtering scan here): the same kept tokens as
+    the two-call sequence, and for sampled (sequence, head) pairs the oracle's exact logits
+    confirm the kept set up to rounding, and its listed-token routine the triple."""
+    from test_concat_gpu import LOGIT_TOL
+
+    hg.hg_attn_set_span_tokens(0)
+    spec = W.WORKLOADS[index]
+    w = W.make_workload(spec, DEV)
+    off = [(b, 0, int(0.8 * n)) for b, n in enumerate(w.seq_lens)]
+    gp = list(range(spec.batch + 1))
+    top_k = 128
+    try:
+        hg.hg_attn_set_topk_mode(0)
+        sel, m, l, o = hg.hg_attn_topk(w.q, w.k, w.v, w.seq_lens, off, gp, top_k, w.scale)
+        hg.hg_attn_set_topk_mode(2)
+        sel2, m2, l2, o2 = hg.hg_attn_topk(w.q, w.k, w.v, w.seq_lens, off, gp, top_k, w.scale)
+    finally:
+        hg.hg_attn_set_topk_mode(0)
+    torch.cuda.synchronize()
+    assert torch.equal(sel, sel2) and torch.equal(m, m2)
+    assert (o - o2).abs().max().item() <= 1e-3 and (l - l2).abs().max().item() <= 1e-3 * l2.abs().max().item()
+    G = spec.n_q_heads // spec.n_kv_heads
+    got = to_np(sel)
+    for b, h in _sample_pairs(spec, 3, seed=10 + index):
+        n_off = off[b][2]
+        qs = to_np(w.q[b : b + 1, h : h + 1])
+        ks = to_np(w.k[b : b + 1, h // G : h // G + 1, :n_off])
+        vs = to_np(w.v[b : b + 1, h // G : h // G + 1, :n_off])
+        exact = oracle.attn_logits(qs, ks, vs, [n_off], w.scale, [(0, 0, n_off)])[0]
+        kept = got[b, h]
+        assert kept.min() >= 0 and np.all(np.diff(kept) > 0) and kept.max() < n_off
+        kth = np.sort(exact)[-top_k]
+        assert exact[kept].min() >= kth - 2 * LOGIT_TOL
+        rest = np.ones(n_off, dtype=bool)
+        rest[kept] = False
+        assert exact[rest].max() <= kth + 2 * LOGIT_TOL
+        gm, gl, go = oracle.attn_gather(qs, ks, vs, [n_off], w.scale, [0], kept.reshape(1, 1, -1))
+        what = "%s (b=%d,h=%d)" % (spec.name, b, h)
+        assert abs(float(m[b, h]) - gm[0, 0]) <= M_TOL, what
+        assert abs(float(m[b, h]) + np.log(float(l[b, h])) - gm[0, 0] - np.log(gl[0, 0])) <= LSE_TOL, what
+        assert np.abs(to_np(o[b, h]).astype(np.float64) / float(l[b, h]) - go[0, 0] / gl[0, 0]).max() <= OUT_TOL, what
