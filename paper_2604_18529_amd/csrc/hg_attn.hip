@@ -601,13 +601,13 @@ hg_status select_stages(const hg_attn_desc *desc, const Plan &p, const SelectPla
 
 // hg_attn_topk: the scan that keeps only logits which can still be among a group's top_k (filter
 // mode of the streaming kernels) exists for the matrix-core kernel of 256-byte rows and for the
-// vector kernel with one query head per KV head (any storage type), contiguous caches,
+// vector kernel with one query head per KV head (any storage type), contiguous or paged caches,
 // top_k <= kFilterMaxTopK; everything else exports all logits to the workspace and selects from them.
 constexpr int kFilterMaxTopK = 256;
 
 bool filter_supported(const hg_attn_desc *d, int32_t top_k)
 {
-    if (g_topk_mode == 2 || top_k > kFilterMaxTopK || d->block_table) return false;
+    if (g_topk_mode == 2 || top_k > kFilterMaxTopK) return false;
     if (use_gqa_kernel(d)) return d->head_dim == 128;
     return d->n_q_heads == d->n_kv_heads;  // vector kernel: one query head per KV head
 }
@@ -687,35 +687,48 @@ TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, i
 }
 
 template <typename TR>
-void launch_valu_filter(const PartialArgs &a, dim3 grid, hipStream_t stream)
+void launch_valu_filter(const PartialArgs &a, bool paged, dim3 grid, hipStream_t stream)
 {
-    hipLaunchKernelGGL((hg_partial_kernel<TR, 1, 2 * HG_VALU_U, kModeFilter, false>), grid, dim3(kValuBlock), 0, stream, a);
+    if (paged)
+        hipLaunchKernelGGL((hg_partial_kernel<TR, 1, 2 * HG_VALU_U, kModeFilter, true>), grid, dim3(kValuBlock), 0, stream, a);
+    else
+        hipLaunchKernelGGL((hg_partial_kernel<TR, 1, 2 * HG_VALU_U, kModeFilter, false>), grid, dim3(kValuBlock), 0, stream, a);
+}
+
+template <bool PAGED>
+void launch_gqa_filter(const hg_attn_desc *d, const PartialArgs &a, dim3 grid, hipStream_t stream)
+{
+    const bool wide = a.filter_rank >= 2;  // four kept logits per lane instead of two
+    if (d->dtype == HG_BF16) {
+        if (wide)
+            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, PAGED, true, 4>), grid, dim3(kGqaBlock), 0, stream, a);
+        else
+            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, PAGED, true, 2>), grid, dim3(kGqaBlock), 0, stream, a);
+    } else {
+        if (wide)
+            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, PAGED, false, 4>), grid, dim3(kGqaBlock), 0, stream, a);
+        else
+            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, PAGED, false, 2>), grid, dim3(kGqaBlock), 0, stream, a);
+    }
 }
 
 void launch_filter(const hg_attn_desc *d, const PartialArgs &a, dim3 grid, hipStream_t stream)
 {
     // (filter_supported() admits exactly the variants instantiated here)
+    const bool paged = d->block_table != nullptr;
     if (!use_gqa_kernel(d)) {
         const bool wide = d->head_dim == 128;
         switch (d->dtype) {
-        case HG_F16: wide ? launch_valu_filter<Traits<128, kDtF16>>(a, grid, stream) : launch_valu_filter<Traits<64, kDtF16>>(a, grid, stream); break;
-        case HG_BF16: wide ? launch_valu_filter<Traits<128, kDtBf16>>(a, grid, stream) : launch_valu_filter<Traits<64, kDtBf16>>(a, grid, stream); break;
-        default: wide ? launch_valu_filter<Traits<128, kDtF32>>(a, grid, stream) : launch_valu_filter<Traits<64, kDtF32>>(a, grid, stream); break;
+        case HG_F16: wide ? launch_valu_filter<Traits<128, kDtF16>>(a, paged, grid, stream) : launch_valu_filter<Traits<64, kDtF16>>(a, paged, grid, stream); break;
+        case HG_BF16: wide ? launch_valu_filter<Traits<128, kDtBf16>>(a, paged, grid, stream) : launch_valu_filter<Traits<64, kDtBf16>>(a, paged, grid, stream); break;
+        default: wide ? launch_valu_filter<Traits<128, kDtF32>>(a, paged, grid, stream) : launch_valu_filter<Traits<64, kDtF32>>(a, paged, grid, stream); break;
         }
         return;
     }
-    const bool wide = a.filter_rank >= 2;  // four kept logits per lane instead of two
-    if (d->dtype == HG_BF16) {
-        if (wide)
-            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, false, true, 4>), grid, dim3(kGqaBlock), 0, stream, a);
-        else
-            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, false, true, 2>), grid, dim3(kGqaBlock), 0, stream, a);
-    } else {
-        if (wide)
-            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, false, false, 4>), grid, dim3(kGqaBlock), 0, stream, a);
-        else
-            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, false, false, 2>), grid, dim3(kGqaBlock), 0, stream, a);
-    }
+    if (paged)
+        launch_gqa_filter<true>(d, a, grid, stream);
+    else
+        launch_gqa_filter<false>(d, a, grid, stream);
 }
 
 // hg_attn_merge (one producer: csr_b == nullptr) and hg_attn_merge2 (two producers).

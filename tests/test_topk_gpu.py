@@ -80,6 +80,26 @@ def test_bit_exact_on_exactly_representable_logits(dtype, d, group, top_k):
     _check_exact(w, ranges, gp, top_k, "%s d=%d G=%d k=%d" % (dtype, d, group, top_k))
 
 
+@pytest.mark.parametrize("block_tokens", [16, 256])
+@pytest.mark.parametrize("span", [0, 512])
+@pytest.mark.parametrize("dtype,d,group", [("f16", 128, 8), ("bf16", 128, 2), ("f16", 128, 1), ("f32", 64, 1), ("bf16", 64, 1), ("f16", 64, 4)])
+def test_paged_cache(dtype, d, group, span, block_tokens):
+    """The same through a block table with physical blocks in shuffled order."""
+    hg.hg_attn_set_span_tokens(span)
+    spec = W.WorkloadSpec("topkpaged", 3, 2 * group, 2, d, dtype, 100, 6000, "none", seed=122 + group)
+    w = W.make_workload(spec, DEV)
+    W.make_dyadic_(w, seed=123)
+    w.scale = 0.125
+    kp, vp, table = W.make_paged(w, block_tokens, seed=9)
+    rng = np.random.default_rng(124)
+    ranges, gp = _groups_per_sequence(w, rng)
+    for top_k in (40, 200):
+        sel, m, l, o = hg.hg_attn_topk(w.q, kp, vp, w.seq_lens, ranges, gp, top_k, w.scale, block_table=table)
+        rsel, rm, rl, ro, _ = oracle.attn_topk(to_np(w.q), *kv_np(w), w.seq_lens, w.scale, ranges, gp, top_k)
+        assert np.array_equal(to_np(sel), rsel), "paged %s d=%d G=%d k=%d: kept tokens differ" % (dtype, d, group, top_k)
+        check_triples(m, l, o, rm, rl, ro, "paged topk")
+
+
 @pytest.mark.parametrize("span", [64, 192, 1024, 0])
 @pytest.mark.parametrize("top_k", [3, 128, 200])
 def test_many_segments_and_edge_ranges(span, top_k):
