@@ -621,10 +621,10 @@ int filter_sets(const hg_attn_desc *) { return kGqaWaves * 16; }
 // The filter scan pays off when the groups are long against top_k: the bounds rise like the
 // logarithm of the tokens seen, so a short group lets a large share of its logits through and
 // the two-call sequence is faster then.  Measured at top_k 128: the vector kernel's scan loses at
-// 6.5k tokens per group (a third survives), is level at 20k and wins by a fifth at 105k (5 %
+// 6.5k tokens per group (a third survives), wins by 6-8 % at 20k-26k and by a fifth at 105k (5 %
 // survive); the matrix-core kernel's scan, which has less time to spare per block, loses at 26k
-// and wins by a sixth at 840k (4 %).
-constexpr int64_t kFilterMinTokensPerKeptValu = 256, kFilterMinTokensPerKeptGqa = 2048;
+// and 52k, wins by 5 % from 105k to 420k and by a sixth at 840k (4 %).
+constexpr int64_t kFilterMinTokensPerKeptValu = 128, kFilterMinTokensPerKeptGqa = 768;
 
 bool filter_chosen(const hg_attn_desc *d, int32_t top_k, int64_t ltok, int32_t n_groups)
 {
