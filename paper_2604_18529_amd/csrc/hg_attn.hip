@@ -649,7 +649,8 @@ struct TopkPlan {
     int32_t n_sub = 0, chunks = 1;
     size_t off_logits = 0;  // unfused: all logits [Hq][ltok]
     size_t off_surv_val = 0, off_surv_col = 0, off_surv_cnt = 0, off_dense_val = 0, off_dense_col = 0, off_dense_cnt = 0;
-    size_t off_gbound = 0, n_bounds = 0;  // shared bounds: one float per (slot, sub-span, head of the stream)
+    size_t n_counts = 0;                  // survivor counts: one per (slot, sub-span, head of the stream)
+    size_t off_gbound = 0, n_bounds = 0;  // shared bounds: 16 floats per (slot, head of the stream)
     size_t total = 0;
 };
 
@@ -674,9 +675,10 @@ TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, i
         off += rows;
         tp.off_dense_col = off;
         off += rows;
-        tp.n_bounds = (size_t)p.n_slots * (size_t)tp.n_sub * (size_t)p.ws.gt;
+        tp.n_counts = (size_t)p.n_slots * (size_t)tp.n_sub * (size_t)p.ws.gt;
+        tp.n_bounds = (size_t)p.n_slots * (size_t)p.ws.gt * 16;
         tp.off_surv_cnt = off;
-        off += align_up(tp.n_bounds * 4);
+        off += align_up(tp.n_counts * 4);
         tp.off_gbound = off;
         off += align_up(tp.n_bounds * 4);
         tp.off_dense_cnt = off;
@@ -1214,10 +1216,10 @@ hg_status hg_attn_topk(const hg_attn_desc *desc, const hg_range *ranges, int32_t
     pa.surv_cnt = reinterpret_cast<int32_t *>(ws + tp.off_surv_cnt);
     pa.filter_rank = (top_k + filter_sets(desc) - 1) / filter_sets(desc) - 1;  // every set keeps rank + 1 logits
     pa.filter_k = top_k;
-    pa.gbound = reinterpret_cast<float *>(ws + tp.off_gbound);
+    pa.gbound = reinterpret_cast<uint32_t *>(ws + tp.off_gbound);
     if (p.n_workgroups > 0) {
         const unsigned fill_blocks = (unsigned)std::min<size_t>(1024, (tp.n_bounds + 255) / 256);
-        hipLaunchKernelGGL(hg_fill_kernel, dim3(fill_blocks), dim3(256), 0, stream, pa.gbound, (int64_t)tp.n_bounds, -INFINITY);
+        hipLaunchKernelGGL(hg_fill_kernel, dim3(fill_blocks), dim3(256), 0, stream, pa.gbound, (int64_t)tp.n_bounds, 0u);
         launch_filter(desc, pa, sgrid, stream);
         st = launch_status("filter kernel");
         if (st != HG_OK) return st;

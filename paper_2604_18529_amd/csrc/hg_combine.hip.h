@@ -255,9 +255,9 @@ __global__ __launch_bounds__(kReduceBlock) void hg_concat_reduce_kernel(const Co
 
 // ---- table upload (host tables reach the device through kernel arguments only) ----------------
 
-// Sets n floats to one value (the shared bounds of the filter pass start at -inf; a kernel rather
+// Sets n words to one value (the shared bounds of the filter pass start at 0; a kernel rather
 // than a memset so that the call can be recorded into a graph).
-__global__ __launch_bounds__(256) void hg_fill_kernel(float *dst, int64_t n, float value)
+__global__ __launch_bounds__(256) void hg_fill_kernel(uint32_t *dst, int64_t n, uint32_t value)
 {
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) dst[i] = value;
 }

@@ -36,6 +36,12 @@ constexpr int kGqaKBytes = kGqaBlockTokens * kGqaKRow;
 constexpr int kGqaPBytes = kGqaHeads * kGqaBlockTokens * 2;
 constexpr int kGqaWaveBytes = kGqaKBytes + 2 * kGqaPBytes;
 constexpr int kWaitVmcnt0 = 0x0F70;      // s_waitcnt vmcnt(0) alone (expcnt and lgkmcnt fields at their maxima)
+constexpr int kRawBufferFlags = 0x00020000;  // buffer descriptor, last word: raw buffer of 32-bit data
+constexpr int kCacheSc1 = 1 << 4;            // buffer load: device-scope coherence (bypass the compute unit's cache)
+constexpr int kGqaPublishLead = 2;  // filter mode: blocks between publishing and evaluating the shared bound
+constexpr int kGqaSeedBlocks = 2;   // filter mode: blocks of the seed pass (even: the loop runs them in pairs)
+constexpr int kGqaAfterSeed = 3;    // filter mode: first evaluation of the shared bound after a seed pass (block index)
+constexpr int kGqaMaxPeers = 32;         // filter mode: workgroups whose published values a shared bound is taken from
 constexpr int kGqaStage = 64;            // filter mode: survivors staged in LDS per (wave, head) between write-outs
 
 typedef _Float16 hg_h8 __attribute__((ext_vector_type(8)));
@@ -102,6 +108,16 @@ __device__ __forceinline__ void track_largest(float &a, float &b, float &c, floa
     }
 }
 
+// Sum over the 16 lanes of a DPP row; every lane of the row ends with the total.
+__device__ __forceinline__ uint32_t row16_sum_u32(uint32_t x)
+{
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xf, 0xf, true);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xf, 0xf, true);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xf, 0xf, true);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x140, 0xf, 0xf, true);
+    return x;
+}
+
 __device__ __forceinline__ float row16_max(float x)
 {
     x = fmaxf(x, dpp_move<0xB1>(x));
@@ -134,7 +150,10 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     __shared__ __align__(16) char smem[kSmemBytes];
     // filter mode: per wave and head, the smallest of the 16 lanes' rank-th largest logits
     __shared__ float wmin[MODE == kModeFilter ? kGqaWaves * kGqaHeads : 1];  // own bound: [wave][head]
-    __shared__ float wpub[MODE == kModeFilter ? kGqaWaves * kGqaHeads : 1];  // shared bound: each wave's part
+    // shared bound: every lane's largest logit [wave][head][lane n]; the bounds found [head]
+    __shared__ float wpub[MODE == kModeFilter ? kGqaWaves * kGqaHeads * 16 : 1];
+    __shared__ float wtau[MODE == kModeFilter ? kGqaHeads : 1];
+    static_assert(MODE != kModeFilter || kGqaWaves == 4, "filter mode: wave w evaluates the shared bound of heads 4w .. 4w + 3");
     // filter mode: survivors wait here, per wave and head, until a run of them is written out
     __shared__ float stage_val[MODE == kModeFilter ? kGqaWaves * kGqaHeads * kGqaStage : 1];
     __shared__ int32_t stage_col[MODE == kModeFilter ? kGqaWaves * kGqaHeads * kGqaStage : 1];
@@ -272,40 +291,43 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     // Shared bound.  When many workgroups scan the same (range, stream) pair -- a long sequence with
     // few KV heads -- each sees a slice of the group only and its own bound stays far below the
     // group's.  Then every workgroup whose whole span lies inside the pair publishes, in global
-    // memory, a value that 4 * 2^level distinct logits of its span reach: the 16 lanes of a head
-    // form 2^level sets per wave, and the value is the smallest of the sets' maxima over the
-    // four waves.  With P such workgroups and 4 * P * 2^level >= top_k, the smallest published
-    // value is a lower bound of the pair's top_k-th largest logit, and it closes in on the true
-    // value as the workgroups advance together.  Only spans that are a whole interior segment take
-    // part: they are under way from the start of the launch, whereas the first segment of a pair
-    // is reached only after its workgroup has finished the end of the previous pair.  Nothing ever
-    // waits: an entry not published yet reads -inf (the host clears the array before the launch),
-    // a stale one reads lower than the current one, and either only makes the bound weaker.  What a
-    // refresh reads is used one block later, so the scan does not stand still for the round trip.
+    // memory, sixteen values per head: for every lane position n the largest logit that lane n of
+    // any of its waves has seen -- the maxima of sixteen disjoint sets of its tokens.  Among the
+    // 16 * P values of P such workgroups the top_k-th largest is reached by top_k distinct logits
+    // of the pair, so it is a lower bound of the pair's top_k-th largest logit; it follows the true
+    // value closely (the smallest of the values would sit far lower) and closes in on it as the
+    // workgroups advance together.  Only spans that are a whole interior segment take part: they
+    // are under way from the start of the launch, whereas the first segment of a pair is reached
+    // only after its workgroup has finished the end of the previous pair.  Nothing ever waits: a
+    // value not published yet reads as the lowest key (the host clears the array before the launch), a stale
+    // one reads lower than the current one, and either only makes the bound weaker.  Wave w
+    // evaluates heads 4w .. 4w + 3 (its 16-lane rows take one head each, every lane the
+    // values of its own position n from all peers; the count in the bisection runs over the row)
+    // and hands the bounds to the other waves through LDS.
     //
     // tau[r] is the bound in use: the largest seen so far of both kinds.
-    constexpr int kMaxPeers = 32;  // entries read per refresh: two per lane of a head's 16
-    float tj0[4], tj1[4], tj2[4], tj3[4], tau[4], pend[2][4];  // tj0[r] >= tj1[r] >= ...: largest logits of head 4rg + r
-    bool have_pend = false;
+    float tj0[4], tj1[4], tj2[4], tj3[4], tau[4];  // tj0[r] >= tj1[r] >= ...: largest logits of head 4rg + r
     uint32_t cnt[4] = {0u, 0u, 0u, 0u};
     int blk = 0, next_refresh = 1;
+    bool published = false;
+    bool seeded = false;
+    bool seed = false;            // seed pass: nothing is appended
+    int pickup = 0;
     uint32_t staged[4] = {0u, 0u, 0u, 0u};  // survivors of heads 4rg..4rg+3 waiting in LDS (cnt: already written out)
-    int level = -1, n_peers = 0;  // shared bound: sets per wave = 2^level (none if < 0), workgroups that take part
+    int n_peers = 0;              // shared bound: workgroups that take part (0: none, own bound only)
     bool takes_part = false;      // this workgroup is one of them
-    int64_t gb_first = 0;         // entry of the first of them, head 0 of this stream
+    int64_t gb_first = 0;         // slot of the first of them
     if constexpr (MODE == kModeFilter) {
         const int pre_r = e.pre, pre_n = table_entry(a.tab, r_idx + 1).pre;
         const int64_t p_first = (int64_t)stream * a.ws.ltok + pre_r, p_last = (int64_t)stream * a.ws.ltok + pre_n - 1;
         const int64_t w_first = p_first / a.ws.span, w_last = p_last / a.ws.span;
         const int64_t n_inner = w_last - w_first - 1;
         if (n_inner > 0 && filter_valid_waves(a.ws.span, kGqaWaves) == kGqaWaves) {
-            n_peers = n_inner < kMaxPeers ? (int)n_inner : kMaxPeers;
-#pragma unroll
-            for (int L = 4; L >= 0; --L)
-                if (((n_peers * kGqaWaves) << L) >= a.filter_k) level = L;
-            gb_first = (w_first + 1 + (int64_t)stream * a.tab.n_ranges + r_idx) * kGqaHeads;
+            const int p = n_inner < kGqaMaxPeers ? (int)n_inner : kGqaMaxPeers;
+            if (p * 16 >= a.filter_k) n_peers = p;
+            gb_first = w_first + 1 + (int64_t)stream * a.tab.n_ranges + r_idx;
         }
-        takes_part = level >= 0 && (int64_t)blockIdx.x > w_first && (int64_t)blockIdx.x <= w_first + n_peers;
+        takes_part = n_peers > 0 && (int64_t)blockIdx.x > w_first && (int64_t)blockIdx.x <= w_first + n_peers;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             tau[r] = 4 * rg + r < nh ? -INFINITY : INFINITY;  // rows of the tile beyond the group's heads pass nothing
@@ -313,8 +335,10 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
         }
         if (lane < kGqaHeads) {
             lds_publish(&wmin[wave * kGqaHeads + lane], -INFINITY);
-            lds_publish(&wpub[wave * kGqaHeads + lane], -INFINITY);
+            if (wave == 0) lds_publish(&wtau[lane], -INFINITY);
         }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) lds_publish(&wpub[(wave * kGqaHeads + 4 * rg + r) * 16 + n], -INFINITY);
         __syncthreads();
     }
 
@@ -466,7 +490,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
             // runs.  A conditional global store in every block would leave the number of memory
             // operations in flight unknown at compile time, and the wait for the next block's K rows
             // would then also wait for the rows requested for the block after it.
-            if (__builtin_amdgcn_ballot_w64(any)) {
+            if (__builtin_amdgcn_ballot_w64(any) && !seed) {
                 const uint32_t below = (1u << n) - 1u;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -501,7 +525,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
                 if (__builtin_amdgcn_ballot_w64(full)) flush_staged();
             }
             const int rank = a.filter_rank;  // uniform, < FJ
-            if (level >= 0) {  // the shared bound needs every lane's largest logit only
+            if (n_peers > 0) {  // the shared bound needs every lane's largest logit only
 #pragma unroll
                 for (int r = 0; r < 4; ++r) tj0[r] = fmaxf(tj0[r], fmaxf(v0[r], v1[r]));
             } else {
@@ -511,55 +535,73 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
                     track_largest<FJ>(tj0[r], tj1[r], tj2[r], tj3[r], v1[r]);
                 }
             }
-            // refresh the bound after blocks 2, 4, 9, 22, 54, ... (everything passes until a bound
-            // exists, and it settles like the logarithm of the tokens seen)
-            if (have_pend) {  // what the refresh of the previous block read has had a block's time to arrive
+            // The bound is refreshed after blocks 2, 4, 9, 22, 54, ... (own bound) or, behind a seed
+            // pass, 4, 11, 32, 95, ... (shared bound): it settles like the logarithm of the tokens
+            // seen, and a refresh of the shared bound costs a round trip to memory plus the search --
+            // about as much as four blocks.
+            // Shared bound: a workgroup publishes kGqaPublishLead blocks before it evaluates, so
+            // that what it reads from peers that run a little behind it is of this round too.
+            if (n_peers > 0 && blk + (seed ? 1 : kGqaPublishLead) >= next_refresh && !published) {
+                published = true;
+                uint32_t *gb = a.gbound;
+                // this lane's largest logits -> LDS; then this row's head: lane n, all waves
 #pragma unroll
-                for (int r = 0; r < 4; ++r) tau[r] = fmaxf(tau[r], row16_min(fminf(pend[0][r], pend[1][r])));
-                have_pend = false;
+                for (int r = 0; r < 4; ++r) lds_publish(&wpub[(wave * kGqaHeads + 4 * rg + r) * 16 + n], tj0[r]);
+                const int hh = 4 * wave + rg;  // the head this 16-lane row evaluates
+                // (a wave's own LDS operations complete in order; what the other waves have
+                // written may be older, i.e. lower)
+                float mine = lds_peek(&wpub[hh * 16 + n]);
+#pragma unroll
+                for (int w = 1; w < kGqaWaves; ++w) mine = fmaxf(mine, lds_peek(&wpub[(w * kGqaHeads + hh) * 16 + n]));
+                // published as order-preserving keys: 0, the cleared state, is below every logit
+                if (takes_part && hh < nh && mine > -INFINITY) {
+                    __hip_atomic_store(gb + (slot * kGqaHeads + hh) * 16 + n, order_key(mine), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            // (the waves evaluate at about the same time: what the others have found for their
+            // heads is picked up during the blocks that follow)
+            if (pickup > 0) {
+                --pickup;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) tau[r] = fmaxf(tau[r], lds_peek(&wtau[4 * rg + r]));
             }
             if (blk == next_refresh) {
-                next_refresh = next_refresh * 5 / 2 + 1;
-                if (level >= 0) {
-                    float *gb = a.gbound;
-                    if (takes_part) {
+                next_refresh = seeded ? next_refresh * 3 + 1 : next_refresh * 5 / 2 + 1;
+                published = false;
+                if (n_peers > 0) {
+                    pickup = 2;
+                    uint32_t *gb = a.gbound;
+                    const int hh = 4 * wave + rg;  // the head this 16-lane row evaluates
+                    // the peers' values of this head and lane position (upper halves of the keys).
+                    // Buffer loads that go to the device-wide cache (sc1), not atomic loads: those
+                    // complete one by one, these are all in flight together.  The buffer is the
+                    // peers' part of the array; beyond it a load returns 0.
+                    const uint64_t peers_at = reinterpret_cast<uint64_t>(gb + gb_first * (kGqaHeads * 16));
+                    const uint64_t peers_uni = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(peers_at >> 32)) << 32) |
+                                               (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)peers_at);
+                    const __amdgpu_buffer_rsrc_t peers = __builtin_amdgcn_make_buffer_rsrc(
+                        reinterpret_cast<void *>(peers_uni), 0, __builtin_amdgcn_readfirstlane(n_peers) * (kGqaHeads * 16 * 4), kRawBufferFlags);
+                    uint32_t key[kGqaMaxPeers];
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            // largest within sets of 16 >> level lanes, then smallest over the sets
-                            float x = tj0[r], y;
-                            y = dpp_move<0xB1>(x);
-                            x = level < 4 ? fmaxf(x, y) : fminf(x, y);
-                            y = dpp_move<0x4E>(x);
-                            x = level < 3 ? fmaxf(x, y) : fminf(x, y);
-                            y = dpp_move<0x141>(x);
-                            x = level < 2 ? fmaxf(x, y) : fminf(x, y);
-                            y = dpp_move<0x140>(x);
-                            x = level < 1 ? fmaxf(x, y) : fminf(x, y);
-                            if (n == 0) lds_publish(&wpub[wave * kGqaHeads + 4 * rg + r], x);
-                        }
-                        // (a wave's own LDS operations complete in order; the other waves' entries
-                        // may be older, i.e. lower)
+                    for (int p = 0; p < kGqaMaxPeers; ++p)
+                        key[p] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(peers, ((p * kGqaHeads + hh) * 16 + n) * 4, 0, kCacheSc1) >> 16;
+                    // largest 16-bit key that top_k of the row's 16 * n_peers values reach
+                    uint32_t tw = 0u;
+#pragma unroll 1
+                    for (int b = 15; b >= 0; --b) {
+                        const uint32_t c = tw | (1u << b);
+                        uint32_t reach = 0;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            float t = lds_peek(&wpub[4 * rg + r]);
-#pragma unroll
-                            for (int w = 1; w < kGqaWaves; ++w) t = fminf(t, lds_peek(&wpub[w * kGqaHeads + 4 * rg + r]));
-                            if (n == 0 && t > -INFINITY)
-                                __hip_atomic_store(gb + slot * kGqaHeads + 4 * rg + r, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        }
-                        __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // (stores: see flush_staged)
+                        for (int p = 0; p < kGqaMaxPeers; ++p) reach += key[p] >= c ? 1u : 0u;
+                        reach = row16_sum_u32(reach);
+                        if (reach >= (uint32_t)a.filter_k) tw = c;
                     }
-                    // read the peers' entries: lane n takes peers n and n + 16 (clamped: reading an
-                    // entry twice does not change a minimum)
+                    tw <<= 16;
+                    if (n == 0 && hh < nh) lds_publish(&wtau[hh], tw > order_key(-INFINITY) ? key_to_float(tw) : -INFINITY);
+                    // bounds of this lane's own heads: this wave's are current, the others' as of
+                    // their last refresh
 #pragma unroll
-                    for (int it = 0; it < 2; ++it) {
-                        const int peer = min(n + 16 * it, n_peers - 1);
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            pend[it][r] = __hip_atomic_load(gb + gb_first + (int64_t)peer * kGqaHeads + 4 * rg + r, __ATOMIC_RELAXED,
-                                                            __HIP_MEMORY_SCOPE_AGENT);
-                    }
-                    have_pend = true;
+                    for (int r = 0; r < 4; ++r) tau[r] = fmaxf(tau[r], lds_peek(&wtau[4 * rg + r]));
                 } else {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
@@ -753,30 +795,60 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
                     if (t + kStride < t1) lookup(t + kStride, pg1);
                 }
             };
-            if constexpr (PAGED) {
-                if (tb < t1) lookup(tb, pg1);
-            }
+            int seed_tok = 0;  // filter mode, seed pass on a contiguous cache: the tokens it walks over
             auto compute_one = [&](int t, hg_u32x4(&reg)[8], float(&sv)[8]) __attribute__((always_inline)) {
-                if constexpr (MODE != kModeConcat)
-                    compute_block(t, t + 2 * kStride, reg, reg);
-                else
+                if constexpr (MODE != kModeConcat) {
+                    // (the seed pass ends by requesting its first two blocks again, for the scan proper)
+                    int ahead = t + 2 * kStride;
+                    if (MODE == kModeFilter && !PAGED && ahead >= t0 + seed_tok) ahead -= seed_tok;
+                    compute_block(t, ahead, reg, reg);
+                } else {
                     concat_block(t, t + 2 * kStride, reg, sv);
+                }
             };
             constexpr bool kAlwaysAhead = !PAGED && (MODE == kModeLogits || MODE == kModeFilter);
-            if (tb < t1) {
-                load_one(tb, ra, sa);
-                if (kAlwaysAhead || tb + kStride < t1) load_one(tb + kStride, rb, sb);
+            // Filter mode with a shared bound: the first blocks are scanned twice.  Until a bound
+            // exists everything would pass, and two blocks of every wave are already one percent
+            // of a long sequence -- several times what passes afterwards.  So the seed pass only
+            // looks (largest logits, published and evaluated as usual) and the scan proper then
+            // starts again at the first block with the bound that the workgroups have found by then.
+            if constexpr (MODE == kModeFilter) {
+                seed = n_peers > 0 && kGqaSeedBlocks > 0;
+                if (seed) next_refresh = kGqaSeedBlocks - 1;
             }
-            while (tb < t1) {
-                compute_one(tb, ra, sa);
-                tb += kStride;
-                // (the K-only modes on a contiguous cache run the second block of the pair even past
-                // the end -- all its tokens are then masked -- so that the loop body is one straight line: with the
-                // exit in the middle the compiler no longer knew how many loads are in flight at
-                // the top of the loop and waited there for all of them)
-                if (!kAlwaysAhead && tb >= t1) break;
-                compute_one(tb, rb, sb);
-                tb += kStride;
+            bool primed = false;
+            for (;;) {
+                const int t_end = seed ? min(t1, t0 + kGqaSeedBlocks * kStride) : t1;
+                // (the loop runs whole pairs of blocks)
+                seed_tok = seed && t_end > t0 ? (t_end - t0 + 2 * kStride - 1) / (2 * kStride) * (2 * kStride) : 0;
+                if (!primed) {
+                    if constexpr (PAGED) {
+                        if (tb < t1) lookup(tb, pg1);
+                    }
+                    if (tb < t1) {
+                        load_one(tb, ra, sa);
+                        if (kAlwaysAhead || tb + kStride < t1) load_one(tb + kStride, rb, sb);
+                    }
+                }
+                while (tb < t_end) {
+                    compute_one(tb, ra, sa);
+                    tb += kStride;
+                    // (the K-only modes on a contiguous cache run the second block of the pair even past
+                    // the end -- all its tokens are then masked -- so that the loop body is one straight line: with the
+                    // exit in the middle the compiler no longer knew how many loads are in flight at
+                    // the top of the loop and waited there for all of them)
+                    if (!kAlwaysAhead && tb >= t_end) break;
+                    compute_one(tb, rb, sb);
+                    tb += kStride;
+                }
+                if (!seed) break;
+                seed = false;
+                primed = !PAGED;
+                tb = t0;
+                blk = 0;
+                next_refresh = kGqaAfterSeed;
+                seeded = true;
+                published = false;
             }
         }
     }
