@@ -618,20 +618,32 @@ bool filter_supported(const hg_attn_desc *d, int32_t top_k)
 // top_k / 4 <= 64.)
 int filter_sets(const hg_attn_desc *) { return kGqaWaves * 16; }
 
-// The filter scan pays off when the groups are long against top_k: the bounds rise like the
-// logarithm of the tokens seen, so a short group lets a large share of its logits through and
-// the two-call sequence is faster then.  Measured at top_k 128: the vector kernel's scan loses at
-// 6.5k tokens per group (a third survives), wins by 6-8 % at 20k-26k and by a fifth at 105k (5 %
-// survive); the matrix-core kernel's scan, which has less time to spare per block, loses at 26k
-// and 52k, wins by 5 % from 105k to 420k and by a sixth at 840k (4 %).
-constexpr int64_t kFilterMinTokensPerKeptValu = 128, kFilterMinTokensPerKeptGqa = 768;
+// The filter scan pays off when the bounds rise quickly against the length of the scan; otherwise
+// a large share of the logits gets through and the two-call sequence is faster.
+//
+// Vector kernel (own bounds only): the bound rises like the logarithm of the tokens a workgroup has
+// seen, so the groups must be long against top_k.  Measured at top_k 128: the scan loses at 6.5k
+// tokens per group (a third survives), wins by 6-8 % at 20k-26k and by a fifth at 105k.
+//
+// Matrix-core kernel: it has less time to spare per block, and its scan wins where the workgroups
+// that share a (range, stream) pair can combine what they have seen (shared bound: at least six
+// of them per pair on average) and where the logits not written and read back are a sizeable part
+// of the traffic (8 bytes per query head and token against 256 per K row: eight or more query
+// heads per KV head).  Measured over 8 KV heads, 420k tokens in all, top_k 64 / 128 / 256: with 8
+// or 16 workgroups per pair the scan takes 0.89-0.94 of the two-call time at 8 query heads per KV
+// head and 0.78-0.81 at 16 (0.97-1.06 at 4); with 4 or fewer per pair it takes 1.0-1.45.
+constexpr int64_t kFilterMinTokensPerKeptValu = 128;
+constexpr int64_t kFilterMinWorkgroupsPerPairGqa = 6;
+constexpr int32_t kFilterMinQueryGroupGqa = 8;
 
-bool filter_chosen(const hg_attn_desc *d, int32_t top_k, int64_t ltok, int32_t n_groups)
+bool filter_chosen(const hg_attn_desc *d, int32_t top_k, const Plan &p, int32_t n_groups)
 {
     if (!filter_supported(d, top_k)) return false;
     if (g_topk_mode == 1) return true;
-    const int64_t per_kept = use_gqa_kernel(d) ? kFilterMinTokensPerKeptGqa : kFilterMinTokensPerKeptValu;
-    return ltok >= per_kept * top_k * std::max<int32_t>(n_groups, 1);
+    const int64_t ltok = p.ws.ltok;
+    if (!use_gqa_kernel(d)) return ltok >= kFilterMinTokensPerKeptValu * top_k * std::max<int32_t>(n_groups, 1);
+    const int64_t n_ranges = std::max<int64_t>((int64_t)p.entries.size() - 1, 1);
+    return d->n_q_heads >= kFilterMinQueryGroupGqa * d->n_kv_heads && ltok >= kFilterMinWorkgroupsPerPairGqa * p.ws.span * n_ranges;
 }
 
 int filter_sub_spans(const hg_attn_desc *d) { return use_gqa_kernel(d) ? kGqaWaves : kValuWaves; }
@@ -650,14 +662,14 @@ struct TopkPlan {
     size_t off_logits = 0;  // unfused: all logits [Hq][ltok]
     size_t off_surv_val = 0, off_surv_col = 0, off_surv_cnt = 0, off_dense_val = 0, off_dense_col = 0, off_dense_cnt = 0;
     size_t n_counts = 0;                  // survivor counts: one per (slot, sub-span, head of the stream)
-    size_t off_gbound = 0, n_bounds = 0;  // shared bounds: 16 floats per (slot, head of the stream)
+    size_t off_gbound = 0, n_bounds = 0;  // shared bounds: 64 words per (slot, head of the stream)
     size_t total = 0;
 };
 
 TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, int32_t n_groups, int32_t top_k)
 {
     TopkPlan tp;
-    tp.fused = filter_chosen(d, top_k, p.ws.ltok, n_groups);
+    tp.fused = filter_chosen(d, top_k, p, n_groups);
     size_t off = align_up(sp.total);
     const size_t rows = align_up((size_t)d->n_q_heads * (size_t)p.ws.ltok * 4);
     if (!tp.fused) {
@@ -676,7 +688,7 @@ TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, i
         tp.off_dense_col = off;
         off += rows;
         tp.n_counts = (size_t)p.n_slots * (size_t)tp.n_sub * (size_t)p.ws.gt;
-        tp.n_bounds = (size_t)p.n_slots * (size_t)p.ws.gt * 16;
+        tp.n_bounds = (size_t)p.n_slots * (size_t)p.ws.gt * 64;
         tp.off_surv_cnt = off;
         off += align_up(tp.n_counts * 4);
         tp.off_gbound = off;

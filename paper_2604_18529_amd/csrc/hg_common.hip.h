@@ -131,7 +131,7 @@ struct PartialArgs {
     int32_t *surv_col, *surv_cnt;
     int32_t filter_rank, filter_k;         // bound = filter_rank-th (0-based) largest of every lane's own elements; top_k
     // Bounds shared between the workgroups that scan the same (range, stream) pair:
-    // gbound[(slot * gt + head in stream) * 16 + lane position], order-preserving keys of logits,
+    // gbound[(slot * gt + head in stream) * 64 + 16 * wave + lane position], order-preserving keys of logits,
     // 0 (below every key) before the launch.  An entry is what its workgroup has published so far
     // (see the filter mode).
     uint32_t *gbound;

@@ -41,6 +41,7 @@ constexpr int kCacheSc1 = 1 << 4;            // buffer load: device-scope cohere
 constexpr int kGqaPublishLead = 2;  // filter mode: blocks between publishing and evaluating the shared bound
 constexpr int kGqaSeedBlocks = 2;   // filter mode: blocks of the seed pass (even: the loop runs them in pairs)
 constexpr int kGqaAfterSeed = 3;    // filter mode: first evaluation of the shared bound after a seed pass (block index)
+constexpr int kGqaSetsPerHead = 64;  // filter mode: values a workgroup may publish per head (one per lane position and wave)
 constexpr int kGqaMaxPeers = 32;         // filter mode: workgroups whose published values a shared bound is taken from
 constexpr int kGqaStage = 64;            // filter mode: survivors staged in LDS per (wave, head) between write-outs
 
@@ -288,22 +289,25 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     // segment, so it is a lower bound of the segment's (hence the group's) top_k-th largest logit:
     // nothing below it can be among the kept tokens.
     //
-    // Shared bound.  When many workgroups scan the same (range, stream) pair -- a long sequence with
-    // few KV heads -- each sees a slice of the group only and its own bound stays far below the
-    // group's.  Then every workgroup whose whole span lies inside the pair publishes, in global
+    // Shared bound.  When several workgroups scan the same (range, stream) pair -- a long sequence
+    // with few KV heads -- each sees a slice of the group only and its own bound stays far below
+    // the group's.  Then every workgroup whose span begins inside the pair publishes, in global
     // memory, sixteen values per head: for every lane position n the largest logit that lane n of
     // any of its waves has seen -- the maxima of sixteen disjoint sets of its tokens.  Among the
     // 16 * P values of P such workgroups the top_k-th largest is reached by top_k distinct logits
     // of the pair, so it is a lower bound of the pair's top_k-th largest logit; it follows the true
     // value closely (the smallest of the values would sit far lower) and closes in on it as the
-    // workgroups advance together.  Only spans that are a whole interior segment take part: they
-    // are under way from the start of the launch, whereas the first segment of a pair is reached
-    // only after its workgroup has finished the end of the previous pair.  Nothing ever waits: a
-    // value not published yet reads as the lowest key (the host clears the array before the launch), a stale
-    // one reads lower than the current one, and either only makes the bound weaker.  Wave w
-    // evaluates heads 4w .. 4w + 3 (its 16-lane rows take one head each, every lane the
-    // values of its own position n from all peers; the count in the bisection runs over the row)
-    // and hands the bounds to the other waves through LDS.
+    // workgroups advance together.  With few such workgroups (up to eight, or fewer than
+    // top_k / 16) they publish the waves' values separately -- 64 disjoint sets per head -- and up
+    // to eight of them are read.  Only workgroups whose span begins inside the pair take part:
+    // the pair is the first thing they scan, so they are under way from the start of the launch,
+    // whereas the workgroup that holds the beginning of the pair reaches it only after it has
+    // finished the end of the previous pair.  Nothing ever waits: a value not published yet reads
+    // as the lowest key (the host clears the array before the launch), a stale one reads lower
+    // than the current one, and either only makes the bound weaker.  Wave w evaluates heads
+    // 4w .. 4w + 3 (its 16-lane rows take one head each, every lane the values of its own position
+    // n; the count in the bisection runs over the row) and hands the bounds to the other waves
+    // through LDS.
     //
     // tau[r] is the bound in use: the largest seen so far of both kinds.
     float tj0[4], tj1[4], tj2[4], tj3[4], tau[4];  // tj0[r] >= tj1[r] >= ...: largest logits of head 4rg + r
@@ -315,19 +319,29 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     int pickup = 0;
     uint32_t staged[4] = {0u, 0u, 0u, 0u};  // survivors of heads 4rg..4rg+3 waiting in LDS (cnt: already written out)
     int n_peers = 0;              // shared bound: workgroups that take part (0: none, own bound only)
+    bool per_wave = false;        // they publish 64 values per head (every wave's lanes) rather than 16
     bool takes_part = false;      // this workgroup is one of them
     int64_t gb_first = 0;         // slot of the first of them
     if constexpr (MODE == kModeFilter) {
         const int pre_r = e.pre, pre_n = table_entry(a.tab, r_idx + 1).pre;
         const int64_t p_first = (int64_t)stream * a.ws.ltok + pre_r, p_last = (int64_t)stream * a.ws.ltok + pre_n - 1;
-        const int64_t w_first = p_first / a.ws.span, w_last = p_last / a.ws.span;
-        const int64_t n_inner = w_last - w_first - 1;
+        // the workgroups whose span begins inside the pair: this pair is the first thing they scan
+        const int64_t w_first = (p_first + a.ws.span - 1) / a.ws.span, w_last = p_last / a.ws.span;
+        const int64_t n_inner = w_last - w_first + 1;
         if (n_inner > 0 && filter_valid_waves(a.ws.span, kGqaWaves) == kGqaWaves) {
-            const int p = n_inner < kGqaMaxPeers ? (int)n_inner : kGqaMaxPeers;
-            if (p * 16 >= a.filter_k) n_peers = p;
-            gb_first = w_first + 1 + (int64_t)stream * a.tab.n_ranges + r_idx;
+            const int many = n_inner < kGqaMaxPeers ? (int)n_inner : kGqaMaxPeers;
+            const int few = n_inner < kGqaMaxPeers / kGqaWaves ? (int)n_inner : kGqaMaxPeers / kGqaWaves;
+            // (the top_k-th largest of S set maxima is about the -S ln(1 - top_k / S)-th largest
+            // logit of the tokens they cover: S = top_k would give the smallest maximum)
+            if (many > few && many * 16 >= 2 * a.filter_k) {
+                n_peers = many;
+            } else if (few * 16 * kGqaWaves * 3 >= 4 * a.filter_k) {
+                n_peers = few;
+                per_wave = true;
+            }
+            gb_first = w_first + (int64_t)stream * a.tab.n_ranges + r_idx;
         }
-        takes_part = n_peers > 0 && (int64_t)blockIdx.x > w_first && (int64_t)blockIdx.x <= w_first + n_peers;
+        takes_part = n_peers > 0 && (int64_t)blockIdx.x >= w_first && (int64_t)blockIdx.x < w_first + n_peers;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             tau[r] = 4 * rg + r < nh ? -INFINITY : INFINITY;  // rows of the tile beyond the group's heads pass nothing
@@ -554,8 +568,17 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
 #pragma unroll
                 for (int w = 1; w < kGqaWaves; ++w) mine = fmaxf(mine, lds_peek(&wpub[(w * kGqaHeads + hh) * 16 + n]));
                 // published as order-preserving keys: 0, the cleared state, is below every logit
-                if (takes_part && hh < nh && mine > -INFINITY) {
-                    __hip_atomic_store(gb + (slot * kGqaHeads + hh) * 16 + n, order_key(mine), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (takes_part && !per_wave && hh < nh && mine > -INFINITY) {
+                    __hip_atomic_store(gb + (slot * kGqaHeads + hh) * kGqaSetsPerHead + n, order_key(mine), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (takes_part && per_wave) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if (4 * rg + r < nh && tj0[r] > -INFINITY)
+                            __hip_atomic_store(gb + (slot * kGqaHeads + 4 * rg + r) * kGqaSetsPerHead + wave * 16 + n, order_key(tj0[r]),
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
                 }
             }
             // (the waves evaluate at about the same time: what the others have found for their
@@ -576,16 +599,20 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
                     // Buffer loads that go to the device-wide cache (sc1), not atomic loads: those
                     // complete one by one, these are all in flight together.  The buffer is the
                     // peers' part of the array; beyond it a load returns 0.
-                    const uint64_t peers_at = reinterpret_cast<uint64_t>(gb + gb_first * (kGqaHeads * 16));
+                    const uint64_t peers_at = reinterpret_cast<uint64_t>(gb + gb_first * (kGqaHeads * kGqaSetsPerHead));
                     const uint64_t peers_uni = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(peers_at >> 32)) << 32) |
                                                (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)peers_at);
                     const __amdgpu_buffer_rsrc_t peers = __builtin_amdgcn_make_buffer_rsrc(
-                        reinterpret_cast<void *>(peers_uni), 0, __builtin_amdgcn_readfirstlane(n_peers) * (kGqaHeads * 16 * 4), kRawBufferFlags);
+                        reinterpret_cast<void *>(peers_uni), 0, __builtin_amdgcn_readfirstlane(n_peers) * (kGqaHeads * kGqaSetsPerHead * 4), kRawBufferFlags);
                     uint32_t key[kGqaMaxPeers];
 #pragma unroll
-                    for (int p = 0; p < kGqaMaxPeers; ++p)
-                        key[p] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(peers, ((p * kGqaHeads + hh) * 16 + n) * 4, 0, kCacheSc1) >> 16;
-                    // largest 16-bit key that top_k of the row's 16 * n_peers values reach
+                    for (int j = 0; j < kGqaMaxPeers; ++j) {
+                        // one value of each of up to 32 peers, or four (the waves') of each of up to 8
+                        const int one = (j * kGqaHeads + hh) * kGqaSetsPerHead + n;
+                        const int four = ((j / kGqaWaves) * kGqaHeads + hh) * kGqaSetsPerHead + (j % kGqaWaves) * 16 + n;
+                        key[j] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(peers, (per_wave ? four : one) * 4, 0, kCacheSc1) >> 16;
+                    }
+                    // largest 16-bit key that top_k of the row's values reach
                     uint32_t tw = 0u;
 #pragma unroll 1
                     for (int b = 15; b >= 0; --b) {
