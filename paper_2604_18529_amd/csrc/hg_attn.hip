@@ -630,7 +630,7 @@ int filter_sets(const hg_attn_desc *) { return kGqaWaves * 16; }
 // of them per pair on average) and where the logits not written and read back are a sizeable part
 // of the traffic (8 bytes per query head and token against 256 per K row: eight or more query
 // heads per KV head).  Measured over 8 KV heads, 420k tokens in all, top_k 64 / 128 / 256: with 8
-// or 16 workgroups per pair the scan takes 0.89-0.94 of the two-call time at 8 query heads per KV
+// or 16 workgroups per pair the scan takes 0.88-0.94 of the two-call time at 8 query heads per KV
 // head and 0.78-0.81 at 16 (0.97-1.06 at 4); with 4 or fewer per pair it takes 1.0-1.45.
 constexpr int64_t kFilterMinTokensPerKeptValu = 128;
 constexpr int64_t kFilterMinWorkgroupsPerPairGqa = 6;
