@@ -316,8 +316,9 @@ hg_status hg_attn_set_span_tokens(int32_t span_tokens);
 
 /* Tuning knob for hg_attn_topk: 0 = the library chooses between the filtering scan and the
  * two-call sequence (with one query head per KV head the scan needs long groups, on average at
- * least 128 tokens per kept token; with grouped queries it needs eight or more query heads per
- * KV head and ranges long enough for six workgroups to share each (range, KV head) pair),
+ * least 128 tokens per kept token; with grouped queries it needs four or more query heads per
+ * KV head and ranges long enough for several workgroups -- two for top_k <= 96, three for <= 144,
+ * six for 256 -- to share each (range, KV head) pair),
  * 1 = the filtering scan wherever it exists, 2 = never.  The results are the same.  Process-wide;
  * not thread-safe against concurrent calls. */
 hg_status hg_attn_set_topk_mode(int32_t mode);

@@ -584,6 +584,16 @@ hg_status select_stages(const hg_attn_desc *desc, const Plan &p, const SelectPla
     }
     sa.cand_val = reinterpret_cast<float *>(ws + sp.off_cand_val);
     sa.cand_col = reinterpret_cast<int32_t *>(ws + sp.off_cand_col);
+    if (sa.dense_cnt && top_k <= kSelectFastKeep) {
+        // Survivor lists are sized for the worst case but are usually a fraction of a per cent of
+        // the group: whichever (group, head) has at most one fast-path workgroup's worth is selected
+        // by a single workgroup, and the staged kernels below leave it alone (they decide by the
+        // same count, on the device: the host never learns the counts).
+        sa.direct_limit = kSelectRegTokens;
+        launch_select<kSelectDirect>(desc, sa, grid, true, stream);
+        const hg_status st0 = launch_status("selection kernel (short lists)");
+        if (st0 != HG_OK) return st0;
+    }
     launch_select<kSelectCandidates>(desc, sa, dim3((unsigned)(n_groups * sp.parts), (unsigned)desc->n_q_heads), sp.fast_first, stream);
     hg_status st = launch_status("selection kernel (candidates)");
     if (st != HG_OK) return st;
@@ -626,15 +636,16 @@ int filter_sets(const hg_attn_desc *) { return kGqaWaves * 16; }
 // tokens per group (a third survives), wins by 6-8 % at 20k-26k and by a fifth at 105k.
 //
 // Matrix-core kernel: it has less time to spare per block, and its scan wins where the workgroups
-// that share a (range, stream) pair can combine what they have seen (shared bound: at least six
-// of them per pair on average) and where the logits not written and read back are a sizeable part
-// of the traffic (8 bytes per query head and token against 256 per K row: eight or more query
-// heads per KV head).  Measured over 8 KV heads, 420k tokens in all, top_k 64 / 128 / 256: with 8
-// or 16 workgroups per pair the scan takes 0.88-0.94 of the two-call time at 8 query heads per KV
-// head and 0.78-0.81 at 16 (0.97-1.06 at 4); with 4 or fewer per pair it takes 1.0-1.45.
+// that share a (range, stream) pair can combine what they have seen -- a shared bound with some
+// slack exists, by the kernel's own rule: 3 * 64 * min(workgroups per pair, 8) >= 4 * top_k, and
+// at least two of them -- and where the logits not written and read back are a sizeable part of
+// the traffic (8 bytes per query head and token against 256 per K row: four or more query heads
+// per KV head).  Measured over 8 KV heads, 420k tokens in all, top_k 64 / 128 / 256, where the
+// rule holds: the scan takes 0.91-0.99 of the two-call time at 4 query heads per KV head,
+// 0.83-0.91 at 8 and 0.71-0.80 at 16; where it does not hold, 0.96-1.5 (and 0.99-1.24 at 2 query
+// heads per KV head everywhere).
 constexpr int64_t kFilterMinTokensPerKeptValu = 128;
-constexpr int64_t kFilterMinWorkgroupsPerPairGqa = 6;
-constexpr int32_t kFilterMinQueryGroupGqa = 8;
+constexpr int32_t kFilterMinQueryGroupGqa = 4;
 
 bool filter_chosen(const hg_attn_desc *d, int32_t top_k, const Plan &p, int32_t n_groups)
 {
@@ -643,7 +654,9 @@ bool filter_chosen(const hg_attn_desc *d, int32_t top_k, const Plan &p, int32_t 
     const int64_t ltok = p.ws.ltok;
     if (!use_gqa_kernel(d)) return ltok >= kFilterMinTokensPerKeptValu * top_k * std::max<int32_t>(n_groups, 1);
     const int64_t n_ranges = std::max<int64_t>((int64_t)p.entries.size() - 1, 1);
-    return d->n_q_heads >= kFilterMinQueryGroupGqa * d->n_kv_heads && ltok >= kFilterMinWorkgroupsPerPairGqa * p.ws.span * n_ranges;
+    const int64_t per_pair = ltok / std::max<int64_t>((int64_t)p.ws.span * n_ranges, 1);  // workgroups per (range, stream) pair, on average
+    return d->n_q_heads >= kFilterMinQueryGroupGqa * d->n_kv_heads && per_pair >= 2 &&
+           3 * 64 * std::min<int64_t>(per_pair, 8) >= 4 * (int64_t)top_k;
 }
 
 int filter_sub_spans(const hg_attn_desc *d) { return use_gqa_kernel(d) ? kGqaWaves : kValuWaves; }
@@ -1230,8 +1243,10 @@ hg_status hg_attn_topk(const hg_attn_desc *desc, const hg_range *ranges, int32_t
     pa.filter_k = top_k;
     pa.gbound = reinterpret_cast<uint32_t *>(ws + tp.off_gbound);
     if (p.n_workgroups > 0) {
-        const unsigned fill_blocks = (unsigned)std::min<size_t>(1024, (tp.n_bounds + 255) / 256);
-        hipLaunchKernelGGL(hg_fill_kernel, dim3(fill_blocks), dim3(256), 0, stream, pa.gbound, (int64_t)tp.n_bounds, 0u);
+        if (use_gqa_kernel(desc)) {  // (the vector kernel shares no bounds)
+            const unsigned fill_blocks = (unsigned)std::min<size_t>(1024, (tp.n_bounds + 255) / 256);
+            hipLaunchKernelGGL(hg_fill_kernel, dim3(fill_blocks), dim3(256), 0, stream, pa.gbound, (int64_t)tp.n_bounds, 0u);
+        }
         launch_filter(desc, pa, sgrid, stream);
         st = launch_status("filter kernel");
         if (st != HG_OK) return st;

@@ -224,6 +224,10 @@ struct SelectArgs {
     // dense_cnt == nullptr: select from `logits`.
     const float *dense_val;
     const int32_t *dense_col, *dense_cnt;
+    // dense lists only, staged selection: a (group, head) whose list has at most direct_limit
+    // entries is selected by the one-workgroup stage (launched first) and skipped by the staged
+    // kernels; a longer list the other way round.  0: no such split.
+    int32_t direct_limit, pad3;
     GroupTable groups;
     RangeTable tab;
 };

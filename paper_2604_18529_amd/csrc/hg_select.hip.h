@@ -332,6 +332,7 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
         // superset of the group's top_k, in ascending column order)
         const bool dense = a.dense_cnt != nullptr;
         const int total = dense ? a.dense_cnt[gh] : c1 - c0;
+        if (dense && a.direct_limit > 0 && (STAGE == kSelectDirect) != (total <= a.direct_limit)) return;  // the other launch's
         const int n_cut = STAGE == kSelectCandidates ? a.parts : 1;
         // (dense lists are usually far shorter than the rows the parts were sized for: fill the
         // parts of a fast-path launch to their capacity, the others find nothing and leave)
@@ -345,6 +346,7 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
         col_base = c0 + b;
         keep = n < a.top_k ? n : a.top_k;
     } else if constexpr (STAGE == kSelectMidCands) {
+        if (a.dense_cnt && a.direct_limit > 0 && a.dense_cnt[gh] <= a.direct_limit) return;
         // chunk `part` of the group's parts * top_k candidates (pad entries included: they sort
         // below everything and are never kept ahead of a real entry)
         const int total = c1 > c0 ? a.parts * a.top_k : 0;
@@ -357,6 +359,7 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
         n = e - b;
         keep = n < a.top_k ? n : a.top_k;
     } else {
+        if (a.dense_cnt && a.direct_limit > 0 && a.dense_cnt[gh] <= a.direct_limit) return;
         const bool mid = a.parts2 > 0;
         const int np = mid ? a.parts2 : a.parts;
         const int64_t base = gh * np * (int64_t)a.top_k;
