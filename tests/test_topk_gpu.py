@@ -154,6 +154,24 @@ def test_orders_that_defeat_the_bound(order, span):
         _check_exact(w, [(0, 0, 7000), (0, 7000, N)], [0, 2], top_k, "%s k=%d" % (order, top_k))
 
 
+@pytest.mark.parametrize("group", [8, 1])
+def test_long_and_short_survivor_lists_in_one_call(group):
+    """One sequence whose logits rise with the token index (every logit passes the scan: a list
+    too long for the one-workgroup selection) beside one with random logits (a short list): the
+    selection behind the scan takes each (group, head) by the length of its own list."""
+    N = 30000
+    spec = W.WorkloadSpec("topkmixed", 2, group, 1, 128, "f16", N, N, "none", seed=131)
+    w = W.make_workload(spec, DEV)
+    W.make_dyadic_(w, seed=132)
+    w.scale = 0.125
+    w.q[0].zero_()
+    w.q[0, :, 0] = 1.0
+    w.k[0].zero_()
+    w.k[0, 0, :, 0] = (torch.arange(N, device=DEV) // 16).to(torch.float16)  # exact in fp16 up to 2048
+    for top_k in (50, 256):
+        _check_exact(w, [(0, 0, N), (1, 0, 11000), (1, 11000, N)], [0, 1, 3], top_k, "G=%d k=%d" % (group, top_k))
+
+
 @pytest.mark.parametrize("dtype,d,group", [("f16", 128, 8), ("bf16", 128, 4), ("f16", 128, 3), ("f16", 128, 1), ("f16", 64, 4)])
 @pytest.mark.parametrize("top_k", [100, 256])
 def test_equals_logits_then_select_and_is_valid_against_the_oracle(dtype, d, group, top_k):
