@@ -691,7 +691,9 @@ TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, i
     } else {
         tp.n_sub = filter_sub_spans(d);
         const int64_t pairs = std::max<int64_t>(1, (int64_t)n_groups * d->n_q_heads);
-        tp.chunks = (int32_t)std::min<int64_t>(64, std::max<int64_t>(1, 4096 / pairs));
+        // (every workgroup of a pair repeats the scan of the counts: up to 8 per pair, 512 in all,
+        // measured against 1-64 per pair)
+        tp.chunks = (int32_t)std::min<int64_t>(8, std::max<int64_t>(1, 512 / pairs));
         tp.off_surv_val = off;
         off += rows;
         tp.off_surv_col = off;

@@ -618,15 +618,16 @@ __global__ __launch_bounds__(256) void hg_survivor_compact_kernel(const CompactA
             s_dst[tid] = (int32_t)(running + before);
             s_cnt[tid] = (int32_t)c;
             __syncthreads();
-            // this workgroup copies the sub-spans z, z + chunks, ... of the batch, all threads on one
+            // this workgroup copies the sub-spans z, z + chunks, ... of the batch, eight at a time
+            // (32 threads each: a sub-span usually holds a few dozen survivors)
             const int n_here = n_items - base < 256 ? (int)(n_items - base) : 256;
-            for (int it = z; it < n_here; it += a.chunks) {
+            for (int it = z + (tid >> 5) * a.chunks; it < n_here; it += 8 * a.chunks) {
                 const int cnt = s_cnt[it];
                 const float *sv = a.surv_val + row + s_src[it];
                 const int32_t *sc = a.surv_col + row + s_src[it];
                 float *dv = a.dense_val + row + c0 + s_dst[it];
                 int32_t *dc = a.dense_col + row + c0 + s_dst[it];
-                for (int x = tid; x < cnt; x += 256) {
+                for (int x = tid & 31; x < cnt; x += 32) {
                     dv[x] = sv[x];
                     dc[x] = sc[x];
                 }
