@@ -298,8 +298,8 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     // of the pair, so it is a lower bound of the pair's top_k-th largest logit; it follows the true
     // value closely (the smallest of the values would sit far lower) and closes in on it as the
     // workgroups advance together.  With few such workgroups (up to eight, or fewer than
-    // top_k / 16) they publish the waves' values separately -- 64 disjoint sets per head -- and up
-    // to eight of them are read.  Only workgroups whose span begins inside the pair take part:
+    // top_k / 8: the sets should be twice top_k) they publish the waves' values separately -- 64
+    // disjoint sets per head -- and up to eight of them are read.  Only workgroups whose span begins inside the pair take part:
     // the pair is the first thing they scan, so they are under way from the start of the launch,
     // whereas the workgroup that holds the beginning of the pair reaches it only after it has
     // finished the end of the previous pair.  Nothing ever waits: a value not published yet reads
@@ -313,10 +313,10 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     float tj0[4], tj1[4], tj2[4], tj3[4], tau[4];  // tj0[r] >= tj1[r] >= ...: largest logits of head 4rg + r
     uint32_t cnt[4] = {0u, 0u, 0u, 0u};
     int blk = 0, next_refresh = 1;
-    bool published = false;
-    bool seeded = false;
+    bool published = false;       // shared bound: this round's values are out
+    bool seeded = false;          // a seed pass has run: sparser schedule
     bool seed = false;            // seed pass: nothing is appended
-    int pickup = 0;
+    int pickup = 0;               // blocks during which the other waves' new bounds are still picked up
     uint32_t staged[4] = {0u, 0u, 0u, 0u};  // survivors of heads 4rg..4rg+3 waiting in LDS (cnt: already written out)
     int n_peers = 0;              // shared bound: workgroups that take part (0: none, own bound only)
     bool per_wave = false;        // they publish 64 values per head (every wave's lanes) rather than 16
