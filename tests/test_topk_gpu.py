@@ -117,7 +117,7 @@ def test_many_segments_and_edge_ranges(span, top_k):
 
 
 @pytest.mark.parametrize("span", [256, 1024, 4096])
-@pytest.mark.parametrize("dtype,group,top_k", [("f16", 8, 128), ("bf16", 4, 256), ("f16", 16, 7), ("f16", 2, 200)])
+@pytest.mark.parametrize("dtype,group,top_k", [("f16", 8, 128), ("bf16", 4, 256), ("f16", 16, 7), ("f16", 2, 200), ("f16", 20, 100), ("bf16", 5, 64)])
 def test_many_workgroups_per_group_share_their_bounds(dtype, group, top_k, span):
     """Long groups cut into many spans: the workgroups of a (range, stream) pair exchange bounds
     through memory while they run.  Whatever each of them happens to read, the kept set is the
