@@ -42,7 +42,7 @@ def _grouped_ranges(rng, seq_lens, max_per_seq):
     return ranges, gp
 
 
-@pytest.mark.parametrize("case", list(range(96)) + list(range(100, 148)) + list(range(500, 516)))
+@pytest.mark.parametrize("case", list(range(96)) + list(range(100, 148)) + list(range(500, 532)))
 def test_random_case(case):
     """Cases below 500 are short (every code path of a workgroup, many combinations; bf16 joins
     from case 100 on); cases from 500 are long enough for several spans per stream and for the two-stage selection."""
