@@ -29,7 +29,10 @@
  *   - The library allocates nothing.  Scratch memory comes in through `workspace`
  *     (DEVICE, 256-byte aligned, at least the size the matching *_workspace_size call reports).
  *   - All device work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
- *     default stream).  No call synchronises with the device.
+ *     default stream).  No call declared in this header synchronises with the device.
+ *   - A launch that the HIP runtime refuses is reported as HG_ERR_LAUNCH from that launch's own
+ *     return value; the runtime's per-thread "last error" is neither read nor cleared, so errors
+ *     the caller's own HIP calls left behind are never taken for this library's.
  *   - Validation is finished on the host before anything is enqueued: on any error status
  *     nothing has been launched and no output byte has been touched.
  *   - The cache of sequence b holds seq_lens[b] valid tokens, the current token included (its
@@ -309,39 +312,9 @@ hg_status hg_sched_step(hg_sched_state *state, float t_gpu, float t_cpu, float t
 hg_status hg_attn_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, int32_t *span_tokens,
                        int64_t *n_workgroups);
 
-/* Tuning knob: force the span length in tokens (multiple of 64, 64..2^24); 0 restores the
- * built-in choice (one workgroup per compute unit on long inputs).  Process-wide; not
- * thread-safe against concurrent calls. */
-hg_status hg_attn_set_span_tokens(int32_t span_tokens);
-
-/* Tuning knob for hg_attn_topk: 0 = the library chooses between the filtering scan and the
- * two-call sequence (with one query head per KV head the scan needs long groups, on average at
- * least 128 tokens per kept token; with grouped queries it needs four or more query heads per
- * KV head and ranges long enough for several workgroups -- two for top_k <= 96, three for <= 144,
- * six for 256 -- to share each (range, KV head) pair),
- * 1 = the filtering scan wherever it exists, 2 = never.  The results are the same.  Process-wide;
- * not thread-safe against concurrent calls. */
-hg_status hg_attn_set_topk_mode(int32_t mode);
-
-/*
- * Measurement aid: time the streaming kernel (the one that reads K and V) by itself.  After
- * hg_attn_profile_start(n, repeat), each of the next n hg_attn_partial / hg_attn_full calls
- * records a pair of HIP events on the caller's stream directly around that kernel, which is
- * launched `repeat` times back to back between the two events (it is idempotent), so that the
- * fixed cost of recording events is spread over several launches; results are unchanged.
- * hg_attn_profile_stop waits for those events (the only call in this library that blocks),
- * returns the summed elapsed milliseconds and the number of kernel launches timed, and switches
- * the mode off.  Process-wide; not thread-safe.
- */
-hg_status hg_attn_profile_start(int32_t max_calls, int32_t repeat);
-hg_status hg_attn_profile_stop(float *total_ms, int32_t *launches);
-
-/*
- * Measurement aid: a plain device copy of `bytes` bytes (multiple of 16; dst, src DEVICE,
- * 16-byte aligned, not overlapping).  Its HBM traffic is known exactly (bytes read, bytes
- * written), which makes it the reference that profiler byte counters are scaled by.
- */
-hg_status hg_attn_calibration_copy(void *dst, const void *src, size_t bytes, void *stream);
+/* Identifies the sources this binary was built from (a hash of the HIP sources and headers taken
+ * by the build step, or "unknown"); static storage.  Lets a loader refuse a stale binary. */
+const char *hg_attn_build_id(void);
 
 #ifdef __cplusplus
 }

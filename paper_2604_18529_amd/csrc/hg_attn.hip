@@ -14,9 +14,14 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <tuple>
+#include <type_traits>
+#include <utility>
 #include <vector>
 
 #include "../../include/hg_attn.h"
+#include "../../include/hg_attn_debug.h"
 
 namespace {
 
@@ -34,6 +39,24 @@ int g_prof_repeat = 1;  // launches of the streaming kernel between the two even
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
+// Launches go through hipLaunchKernel, whose return value is this launch's own status.  The first
+// failure of a call is kept per thread and reported by launch_status(); the runtime's "last
+// error" is never consulted, so an error that the caller's earlier HIP calls left behind is not
+// taken for one of this library's launches (and is not cleared either).
+thread_local hipError_t t_launch_error = hipSuccess;
+
+template <typename... KArgs, typename... Args>
+void launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream, Args &&...args)
+{
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "one argument per kernel parameter");
+    std::tuple<std::remove_cv_t<KArgs>...> vals(std::forward<Args>(args)...);
+    void *argv[sizeof...(KArgs)];
+    std::apply([&](auto &...v) { int i = 0; ((argv[i++] = static_cast<void *>(&v)), ...); }, vals);
+    const hipError_t err = hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, argv, 0, stream);
+    if (err != hipSuccess && t_launch_error == hipSuccess) t_launch_error = err;
+}
+#define HG_LAUNCH(kernel, grid, block, stream, ...) launch_kernel(kernel, grid, block, stream, __VA_ARGS__)
+
 struct Plan {
     WorkSplit ws{};
     int64_t n_workgroups = 0;
@@ -44,20 +67,37 @@ struct Plan {
     size_t off_gs_m = 0, off_gs_l = 0, off_groups = 0;  // concat path only
 };
 
-// Compute units of the current device (256 on MI355X); 256 when no device can be queried, so
-// that planning also works on a host without a GPU.
+constexpr int kMaxDevices = 64;
+
+// The current HIP device, or -1 when none can be queried (a host without a GPU).  Queries that
+// fail here are this library's own and leave nothing behind.
+int current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return -1;
+    }
+    return dev;
+}
+
+// Compute units of the current device (256 on MI355X), looked up once per device; 256 when no
+// device can be queried, so that planning also works on a host without a GPU.
 int compute_units()
 {
-    static int cached = 0;
-    if (cached) return cached;
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) {
-        cached = cus;
-        return cus;
+    static std::mutex mu;
+    static int cached[kMaxDevices] = {};
+    const int dev = current_device();
+    if (dev < 0) return 256;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cached[dev]) return cached[dev];
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+        (void)hipGetLastError();
+        return 256;
     }
-    (void)hipGetLastError();
-    return 256;
+    cached[dev] = cus;
+    return cus;
 }
 
 hg_status check_desc(const hg_attn_desc *d)
@@ -201,9 +241,11 @@ hg_status check_workspace(const void *ws, size_t have, size_t need)
     return HG_OK;
 }
 
+// Status of the launches made since the last call of this function (by this thread).
 hg_status launch_status(const char *what)
 {
-    hipError_t err = hipGetLastError();
+    const hipError_t err = t_launch_error;
+    t_launch_error = hipSuccess;
     if (err == hipSuccess) return HG_OK;
     std::fprintf(stderr, "hg_attn: %s failed: %s\n", what, hipGetErrorString(err));
     return HG_ERR_LAUNCH;
@@ -226,7 +268,7 @@ hg_status stage_table(const Plan &p, int32_t n_ranges, char *ws, hipStream_t str
         RangeChunk chunk;
         const int cnt = (int)std::min<size_t>(kUploadRanges, n - i);
         std::memcpy(chunk.e, p.entries.data() + i, (size_t)cnt * sizeof(RangeEntry));
-        hipLaunchKernelGGL(hg_upload_ranges_kernel, dim3(1), dim3(kUploadRanges), 0, stream, dst + i, cnt, chunk);
+        HG_LAUNCH(hg_upload_ranges_kernel, dim3(1), dim3(kUploadRanges), stream, dst + i, cnt, chunk);
     }
     return launch_status("range table upload");
 }
@@ -239,14 +281,14 @@ void launch_valu_gt(const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
     constexpr int F = MODE == kModeStats ? 1 : 2;
     if constexpr (TR::DT != kDtF32) {
         // 16-bit storage with a query group goes to the matrix-core kernels: only one head per lane group here
-        hipLaunchKernelGGL((hg_partial_kernel<TR, 1, F * HG_VALU_U, MODE, PAGED>), grid, dim3(kValuBlock), 0, stream, a);
+        HG_LAUNCH((hg_partial_kernel<TR, 1, F * HG_VALU_U, MODE, PAGED>), grid, dim3(kValuBlock), stream, a);
         return;
     }
     switch (gt) {
-    case 1: hipLaunchKernelGGL((hg_partial_kernel<TR, 1, F * HG_VALU_U, MODE, PAGED>), grid, dim3(kValuBlock), 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((hg_partial_kernel<TR, 2, F * HG_VALU_U, MODE, PAGED>), grid, dim3(kValuBlock), 0, stream, a); break;
-    case 4: hipLaunchKernelGGL((hg_partial_kernel<TR, 4, F * 2, MODE, PAGED>), grid, dim3(kValuBlock), 0, stream, a); break;
-    default: hipLaunchKernelGGL((hg_partial_kernel<TR, 8, F * 2, MODE, PAGED>), grid, dim3(kValuBlock), 0, stream, a); break;
+    case 1: HG_LAUNCH((hg_partial_kernel<TR, 1, F * HG_VALU_U, MODE, PAGED>), grid, dim3(kValuBlock), stream, a); break;
+    case 2: HG_LAUNCH((hg_partial_kernel<TR, 2, F * HG_VALU_U, MODE, PAGED>), grid, dim3(kValuBlock), stream, a); break;
+    case 4: HG_LAUNCH((hg_partial_kernel<TR, 4, F * 2, MODE, PAGED>), grid, dim3(kValuBlock), stream, a); break;
+    default: HG_LAUNCH((hg_partial_kernel<TR, 8, F * 2, MODE, PAGED>), grid, dim3(kValuBlock), stream, a); break;
     }
 }
 
@@ -257,14 +299,14 @@ void launch_stream_paged(const hg_attn_desc *d, const PartialArgs &a, int gt, di
     if (use_gqa_kernel(d)) {
         if (d->head_dim == 128) {
             if (bf16)
-                hipLaunchKernelGGL((hg_partial_gqa_kernel<MODE, PAGED, true>), grid, dim3(kGqaBlock), 0, stream, a);
+                HG_LAUNCH((hg_partial_gqa_kernel<MODE, PAGED, true>), grid, dim3(kGqaBlock), stream, a);
             else
-                hipLaunchKernelGGL((hg_partial_gqa_kernel<MODE, PAGED, false>), grid, dim3(kGqaBlock), 0, stream, a);
+                HG_LAUNCH((hg_partial_gqa_kernel<MODE, PAGED, false>), grid, dim3(kGqaBlock), stream, a);
         } else {
             if (bf16)
-                hipLaunchKernelGGL((hg_partial_gqa64_kernel<MODE, PAGED, true>), grid, dim3(kGqaBlock), 0, stream, a);
+                HG_LAUNCH((hg_partial_gqa64_kernel<MODE, PAGED, true>), grid, dim3(kGqaBlock), stream, a);
             else
-                hipLaunchKernelGGL((hg_partial_gqa64_kernel<MODE, PAGED, false>), grid, dim3(kGqaBlock), 0, stream, a);
+                HG_LAUNCH((hg_partial_gqa64_kernel<MODE, PAGED, false>), grid, dim3(kGqaBlock), stream, a);
         }
         return;
     }
@@ -339,7 +381,7 @@ hg_status stage_groups(const int32_t *group_ptr, int32_t n_groups, int32_t *dst,
         IntChunk chunk;
         const int cnt = (int)std::min<size_t>(kUploadInts, n - i);
         std::memcpy(chunk.e, group_ptr + i, (size_t)cnt * sizeof(int32_t));
-        hipLaunchKernelGGL(hg_upload_ints_kernel, dim3(1), dim3(kUploadInts), 0, stream, dst + i, cnt, chunk);
+        HG_LAUNCH(hg_upload_ints_kernel, dim3(1), dim3(kUploadInts), stream, dst + i, cnt, chunk);
     }
     return launch_status("group table upload");
 }
@@ -411,9 +453,9 @@ hg_status run(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, i
     ra.o_out = o;
     dim3 rgrid((unsigned)n_ranges, (unsigned)d->n_q_heads);
     if (d->head_dim == 128)
-        hipLaunchKernelGGL(hg_segment_reduce_kernel<128>, rgrid, dim3(kReduceBlock), 0, stream, ra);
+        HG_LAUNCH(hg_segment_reduce_kernel<128>, rgrid, dim3(kReduceBlock), stream, ra);
     else
-        hipLaunchKernelGGL(hg_segment_reduce_kernel<64>, rgrid, dim3(kReduceBlock), 0, stream, ra);
+        HG_LAUNCH(hg_segment_reduce_kernel<64>, rgrid, dim3(kReduceBlock), stream, ra);
     return launch_status("segment reduce kernel");
 }
 
@@ -533,18 +575,18 @@ void launch_select_variant(const hg_attn_desc *desc, const SelectArgs &sa, dim3 
     const dim3 block(FAST ? kSelectFastBlock : kSelectBlock);
     if (desc->head_dim == 128) {
         if (desc->dtype == HG_F16)
-            hipLaunchKernelGGL((hg_select_kernel<Traits<128, kDtF16>, STAGE, FAST>), grid, block, 0, stream, sa);
+            HG_LAUNCH((hg_select_kernel<Traits<128, kDtF16>, STAGE, FAST>), grid, block, stream, sa);
         else if (desc->dtype == HG_BF16)
-            hipLaunchKernelGGL((hg_select_kernel<Traits<128, kDtBf16>, STAGE, FAST>), grid, block, 0, stream, sa);
+            HG_LAUNCH((hg_select_kernel<Traits<128, kDtBf16>, STAGE, FAST>), grid, block, stream, sa);
         else
-            hipLaunchKernelGGL((hg_select_kernel<Traits<128, kDtF32>, STAGE, FAST>), grid, block, 0, stream, sa);
+            HG_LAUNCH((hg_select_kernel<Traits<128, kDtF32>, STAGE, FAST>), grid, block, stream, sa);
     } else {
         if (desc->dtype == HG_F16)
-            hipLaunchKernelGGL((hg_select_kernel<Traits<64, kDtF16>, STAGE, FAST>), grid, block, 0, stream, sa);
+            HG_LAUNCH((hg_select_kernel<Traits<64, kDtF16>, STAGE, FAST>), grid, block, stream, sa);
         else if (desc->dtype == HG_BF16)
-            hipLaunchKernelGGL((hg_select_kernel<Traits<64, kDtBf16>, STAGE, FAST>), grid, block, 0, stream, sa);
+            HG_LAUNCH((hg_select_kernel<Traits<64, kDtBf16>, STAGE, FAST>), grid, block, stream, sa);
         else
-            hipLaunchKernelGGL((hg_select_kernel<Traits<64, kDtF32>, STAGE, FAST>), grid, block, 0, stream, sa);
+            HG_LAUNCH((hg_select_kernel<Traits<64, kDtF32>, STAGE, FAST>), grid, block, stream, sa);
     }
 }
 
@@ -719,9 +761,9 @@ template <typename TR>
 void launch_valu_filter(const PartialArgs &a, bool paged, dim3 grid, hipStream_t stream)
 {
     if (paged)
-        hipLaunchKernelGGL((hg_partial_kernel<TR, 1, 2 * HG_VALU_U, kModeFilter, true>), grid, dim3(kValuBlock), 0, stream, a);
+        HG_LAUNCH((hg_partial_kernel<TR, 1, 2 * HG_VALU_U, kModeFilter, true>), grid, dim3(kValuBlock), stream, a);
     else
-        hipLaunchKernelGGL((hg_partial_kernel<TR, 1, 2 * HG_VALU_U, kModeFilter, false>), grid, dim3(kValuBlock), 0, stream, a);
+        HG_LAUNCH((hg_partial_kernel<TR, 1, 2 * HG_VALU_U, kModeFilter, false>), grid, dim3(kValuBlock), stream, a);
 }
 
 template <bool PAGED>
@@ -730,14 +772,14 @@ void launch_gqa_filter(const hg_attn_desc *d, const PartialArgs &a, dim3 grid, h
     const bool wide = a.filter_rank >= 2;  // four kept logits per lane instead of two
     if (d->dtype == HG_BF16) {
         if (wide)
-            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, PAGED, true, 4>), grid, dim3(kGqaBlock), 0, stream, a);
+            HG_LAUNCH((hg_partial_gqa_kernel<kModeFilter, PAGED, true, 4>), grid, dim3(kGqaBlock), stream, a);
         else
-            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, PAGED, true, 2>), grid, dim3(kGqaBlock), 0, stream, a);
+            HG_LAUNCH((hg_partial_gqa_kernel<kModeFilter, PAGED, true, 2>), grid, dim3(kGqaBlock), stream, a);
     } else {
         if (wide)
-            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, PAGED, false, 4>), grid, dim3(kGqaBlock), 0, stream, a);
+            HG_LAUNCH((hg_partial_gqa_kernel<kModeFilter, PAGED, false, 4>), grid, dim3(kGqaBlock), stream, a);
         else
-            hipLaunchKernelGGL((hg_partial_gqa_kernel<kModeFilter, PAGED, false, 2>), grid, dim3(kGqaBlock), 0, stream, a);
+            HG_LAUNCH((hg_partial_gqa_kernel<kModeFilter, PAGED, false, 2>), grid, dim3(kGqaBlock), stream, a);
     }
 }
 
@@ -812,9 +854,9 @@ hg_status merge_sets(const float *m, const float *l, const float *o, const int32
     }
     dim3 grid((unsigned)n_groups, (unsigned)n_q_heads);
     if (head_dim == 128)
-        hipLaunchKernelGGL(hg_merge_kernel<128>, grid, dim3(kReduceBlock), 0, stream, a);
+        HG_LAUNCH(hg_merge_kernel<128>, grid, dim3(kReduceBlock), stream, a);
     else
-        hipLaunchKernelGGL(hg_merge_kernel<64>, grid, dim3(kReduceBlock), 0, stream, a);
+        HG_LAUNCH(hg_merge_kernel<64>, grid, dim3(kReduceBlock), stream, a);
     return launch_status("merge kernel");
 }
 
@@ -865,17 +907,15 @@ hg_status hg_sched_step(hg_sched_state *state, float t_gpu, float t_cpu, float t
     if (!state) return HG_ERR_NULL;
     if (k_min < 1 || k_max < k_min || k_step < 1) return HG_ERR_SHAPE;
     if (!(t_gpu >= 0.f) || !(t_cpu >= 0.f) || !(t_tx >= 0.f) || !std::isfinite(t_gpu + t_cpu + t_tx)) return HG_ERR_SHAPE;
-    int64_t k = std::min<int64_t>(std::max<int64_t>(state->k, k_min), k_max);
-    int32_t strategy = HG_SELECT_POST_QK;
-    if (t_cpu + t_tx <= t_gpu) {
-        k = std::min<int64_t>(k + k_step, k_max);
-    } else if (k > k_min) {
-        k = std::max<int64_t>(k - k_step, k_min);
-    } else {
-        strategy = HG_SELECT_PRE_QK;
-    }
-    state->k = (int32_t)k;
-    state->strategy = strategy;
+    // One clamped step: K moves by k_step towards k_max while the offloaded stage (logits +
+    // transfer) hides behind the GPU stage, towards k_min while it does not.  A tick that finds
+    // the offloaded stage exposed with K already at its floor has nothing left to shed and asks
+    // for selection before the logits are computed.
+    const auto clamp_k = [&](int64_t k) { return std::min<int64_t>(std::max<int64_t>(k, k_min), k_max); };
+    const bool hidden = t_cpu + t_tx <= t_gpu;
+    const int64_t k_now = clamp_k(state->k);
+    state->strategy = !hidden && k_now == k_min ? HG_SELECT_PRE_QK : HG_SELECT_POST_QK;
+    state->k = (int32_t)clamp_k(k_now + (hidden ? (int64_t)k_step : -(int64_t)k_step));
     return HG_OK;
 }
 
@@ -884,25 +924,47 @@ hg_status hg_attn_calibration_copy(void *dst, const void *src, size_t bytes, voi
     if (!dst || !src) return HG_ERR_NULL;
     if (bytes % 16 || ((uintptr_t)dst | (uintptr_t)src) % 16) return HG_ERR_SHAPE;
     if (bytes == 0) return HG_OK;
-    hipLaunchKernelGGL(hg_calibration_copy_kernel, dim3(4096), dim3(256), 0, static_cast<hipStream_t>(stream),
+    HG_LAUNCH(hg_calibration_copy_kernel, dim3(4096), dim3(256), static_cast<hipStream_t>(stream),
                        static_cast<hg_u32x4 *>(dst), static_cast<const hg_u32x4 *>(src), bytes / 16);
     return launch_status("calibration copy");
 }
 
 hg_status hg_attn_profile_start(int32_t max_calls, int32_t repeat)
 {
-    const int32_t max_launches = max_calls;
-    if (max_launches < 0 || max_launches > 65536 || repeat < 1 || repeat > 1024) return HG_ERR_SHAPE;
+    if (max_calls < 0 || max_calls > 65536 || repeat < 1 || repeat > 1024) return HG_ERR_SHAPE;
     g_prof_repeat = repeat;
     for (hipEvent_t ev : g_prof_events) (void)hipEventDestroy(ev);
     g_prof_events.clear();
     g_prof_used = 0;
-    for (int i = 0; i < 2 * max_launches; ++i) {
+    for (int i = 0; i < 2 * max_calls; ++i) {
         hipEvent_t ev;
-        if (hipEventCreate(&ev) != hipSuccess) return launch_status("event creation");
+        const hipError_t err = hipEventCreate(&ev);
+        if (err != hipSuccess) {
+            std::fprintf(stderr, "hg_attn: event creation failed: %s\n", hipGetErrorString(err));
+            return HG_ERR_LAUNCH;
+        }
         g_prof_events.push_back(ev);
     }
     return HG_OK;
+}
+
+hg_status hg_attn_profile_times(float *ms_each, int32_t capacity, int32_t *calls)
+{
+    if (capacity < 0 || (capacity > 0 && !ms_each)) return HG_ERR_NULL;
+    hg_status st = HG_OK;
+    const int n = g_prof_used < capacity ? g_prof_used : capacity;
+    for (int i = 0; i < n; ++i) {
+        float ms = 0.f;
+        hipError_t err = hipEventSynchronize(g_prof_events[2 * i + 1]);
+        if (err == hipSuccess) err = hipEventElapsedTime(&ms, g_prof_events[2 * i], g_prof_events[2 * i + 1]);
+        if (err != hipSuccess) {
+            std::fprintf(stderr, "hg_attn: event read-out failed: %s\n", hipGetErrorString(err));
+            st = HG_ERR_LAUNCH;
+        }
+        ms_each[i] = ms / (float)g_prof_repeat;
+    }
+    if (calls) *calls = g_prof_used;
+    return st;
 }
 
 hg_status hg_attn_profile_stop(float *total_ms, int32_t *launches)
@@ -911,9 +973,12 @@ hg_status hg_attn_profile_stop(float *total_ms, int32_t *launches)
     hg_status st = HG_OK;
     for (int i = 0; i < g_prof_used; ++i) {
         float ms = 0.f;
-        if (hipEventSynchronize(g_prof_events[2 * i + 1]) != hipSuccess ||
-            hipEventElapsedTime(&ms, g_prof_events[2 * i], g_prof_events[2 * i + 1]) != hipSuccess)
-            st = launch_status("event read-out");
+        hipError_t err = hipEventSynchronize(g_prof_events[2 * i + 1]);
+        if (err == hipSuccess) err = hipEventElapsedTime(&ms, g_prof_events[2 * i], g_prof_events[2 * i + 1]);
+        if (err != hipSuccess) {
+            std::fprintf(stderr, "hg_attn: event read-out failed: %s\n", hipGetErrorString(err));
+            st = HG_ERR_LAUNCH;
+        }
         sum += ms;
     }
     if (total_ms) *total_ms = sum;
@@ -923,6 +988,13 @@ hg_status hg_attn_profile_stop(float *total_ms, int32_t *launches)
     g_prof_used = 0;
     return st;
 }
+
+#ifndef HG_BUILD_ID
+#define HG_BUILD_ID "unknown"
+#endif
+// (the marker lets a loader read the id from the file without mapping the image)
+static const char kBuildIdMarker[] = "hg_attn_build_id=" HG_BUILD_ID;
+const char *hg_attn_build_id(void) { return kBuildIdMarker + sizeof("hg_attn_build_id=") - 1; }
 
 hg_status hg_attn_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, int32_t *span_tokens,
                        int64_t *n_workgroups)
@@ -1087,8 +1159,7 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
     sa.ltok = p.ws.ltok;
     sa.n_q_heads = desc->n_q_heads;
     sa.tab = pa.tab;
-    hipLaunchKernelGGL(hg_concat_stats_kernel, dim3(kConcatSlices, (unsigned)desc->n_q_heads, (unsigned)n_groups), dim3(256),
-                       0, stream, sa);
+    HG_LAUNCH(hg_concat_stats_kernel, dim3(kConcatSlices, (unsigned)desc->n_q_heads, (unsigned)n_groups), dim3(256), stream, sa);
     st = launch_status("concat stats kernel");
     if (st != HG_OK) return st;
 
@@ -1110,9 +1181,9 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
     ra.tab = pa.tab;
     dim3 rgrid((unsigned)n_groups, (unsigned)desc->n_q_heads);
     if (desc->head_dim == 128)
-        hipLaunchKernelGGL(hg_concat_reduce_kernel<128>, rgrid, dim3(kReduceBlock), 0, stream, ra);
+        HG_LAUNCH(hg_concat_reduce_kernel<128>, rgrid, dim3(kReduceBlock), stream, ra);
     else
-        hipLaunchKernelGGL(hg_concat_reduce_kernel<64>, rgrid, dim3(kReduceBlock), 0, stream, ra);
+        HG_LAUNCH(hg_concat_reduce_kernel<64>, rgrid, dim3(kReduceBlock), stream, ra);
     return launch_status("concat reduce kernel");
 }
 
@@ -1247,7 +1318,7 @@ hg_status hg_attn_topk(const hg_attn_desc *desc, const hg_range *ranges, int32_t
     if (p.n_workgroups > 0) {
         if (use_gqa_kernel(desc)) {  // (the vector kernel shares no bounds)
             const unsigned fill_blocks = (unsigned)std::min<size_t>(1024, (tp.n_bounds + 255) / 256);
-            hipLaunchKernelGGL(hg_fill_kernel, dim3(fill_blocks), dim3(256), 0, stream, pa.gbound, (int64_t)tp.n_bounds, 0u);
+            HG_LAUNCH(hg_fill_kernel, dim3(fill_blocks), dim3(256), stream, pa.gbound, (int64_t)tp.n_bounds, 0u);
         }
         launch_filter(desc, pa, sgrid, stream);
         st = launch_status("filter kernel");
@@ -1266,8 +1337,8 @@ hg_status hg_attn_topk(const hg_attn_desc *desc, const hg_range *ranges, int32_t
     ca.ws = p.ws;
     ca.groups = sa.groups;
     ca.tab = sa.tab;
-    hipLaunchKernelGGL(hg_survivor_compact_kernel, dim3((unsigned)n_groups, (unsigned)desc->n_q_heads, (unsigned)tp.chunks),
-                       dim3(256), 0, stream, ca);
+    HG_LAUNCH(hg_survivor_compact_kernel, dim3((unsigned)n_groups, (unsigned)desc->n_q_heads, (unsigned)tp.chunks),
+                       dim3(256), stream, ca);
     st = launch_status("survivor compaction kernel");
     if (st != HG_OK) return st;
     sa.dense_val = dense_val;
@@ -1324,18 +1395,18 @@ hg_status hg_attn_gather(const hg_attn_desc *desc, const int32_t *group_seq, int
     const dim3 block(256);
     if (desc->head_dim == 128) {
         if (desc->dtype == HG_F16)
-            hipLaunchKernelGGL((hg_gather_kernel<Traits<128, kDtF16>>), grid, block, 0, stream, ga);
+            HG_LAUNCH((hg_gather_kernel<Traits<128, kDtF16>>), grid, block, stream, ga);
         else if (desc->dtype == HG_BF16)
-            hipLaunchKernelGGL((hg_gather_kernel<Traits<128, kDtBf16>>), grid, block, 0, stream, ga);
+            HG_LAUNCH((hg_gather_kernel<Traits<128, kDtBf16>>), grid, block, stream, ga);
         else
-            hipLaunchKernelGGL((hg_gather_kernel<Traits<128, kDtF32>>), grid, block, 0, stream, ga);
+            HG_LAUNCH((hg_gather_kernel<Traits<128, kDtF32>>), grid, block, stream, ga);
     } else {
         if (desc->dtype == HG_F16)
-            hipLaunchKernelGGL((hg_gather_kernel<Traits<64, kDtF16>>), grid, block, 0, stream, ga);
+            HG_LAUNCH((hg_gather_kernel<Traits<64, kDtF16>>), grid, block, stream, ga);
         else if (desc->dtype == HG_BF16)
-            hipLaunchKernelGGL((hg_gather_kernel<Traits<64, kDtBf16>>), grid, block, 0, stream, ga);
+            HG_LAUNCH((hg_gather_kernel<Traits<64, kDtBf16>>), grid, block, stream, ga);
         else
-            hipLaunchKernelGGL((hg_gather_kernel<Traits<64, kDtF32>>), grid, block, 0, stream, ga);
+            HG_LAUNCH((hg_gather_kernel<Traits<64, kDtF32>>), grid, block, stream, ga);
     }
     return launch_status("gather kernel");
 }

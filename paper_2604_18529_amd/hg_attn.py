@@ -66,13 +66,19 @@ _lib = None
 
 
 def load_library() -> ctypes.CDLL:
-    """Load ``libhg_attn.so`` (building it with hipcc first if it was never built)."""
+    """Load ``libhg_attn.so``.  A binary that is missing, or that was built from other sources than
+    the present ones (its build id is a hash of them), is rebuilt with hipcc first; if that is not
+    possible the import fails rather than running a stale binary."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB_PATH):
+    if _build.is_stale():
         _build.build_library()
     lib = ctypes.CDLL(_build.LIB_PATH)
+    lib.hg_attn_build_id.restype = ctypes.c_char_p
+    if lib.hg_attn_build_id().decode() != _build.source_id():
+        raise RuntimeError("libhg_attn.so does not match the sources (build id %s, sources %s)"
+                           % (lib.hg_attn_build_id().decode(), _build.source_id()))
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     D, R = ctypes.POINTER(_Desc), ctypes.POINTER(_Range)
     lib.hg_strerror.argtypes = [ctypes.c_int]
@@ -103,8 +109,10 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_profile_start.argtypes = [i32, i32]
     lib.hg_attn_calibration_copy.argtypes = [vp, vp, sz, vp]
     lib.hg_attn_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+    lib.hg_attn_profile_times.argtypes = [ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32)]
     for name in (
-        "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_merge_workspace_size", "hg_attn_merge",
+        "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_profile_times",
+        "hg_attn_merge_workspace_size", "hg_attn_merge",
         "hg_attn_merge2_workspace_size", "hg_attn_merge2", "hg_attn_gather_workspace_size", "hg_attn_gather",
         "hg_attn_topk_workspace_size", "hg_attn_topk",
         "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_span_tokens", "hg_attn_set_topk_mode",
@@ -150,6 +158,18 @@ def _stream_handle(stream) -> Optional[int]:
     if isinstance(stream, torch.cuda.Stream):
         return stream.cuda_stream or None
     return int(stream) or None
+
+
+def _note_stream(stream, *tensors) -> None:
+    """Tensors the wrappers allocate (workspace, default outputs) come from torch's caching
+    allocator on the CURRENT stream; the calls only enqueue work.  When the work goes to another
+    torch stream, tell the allocator, so that a dropped tensor's block is not handed out again
+    while that stream still uses it.  (A raw stream handle cannot be recorded: pass caller-owned
+    buffers with it, as the C ABI requires anyway.)"""
+    if isinstance(stream, torch.cuda.Stream) and stream != torch.cuda.current_stream(stream.device):
+        for t in tensors:
+            if t is not None:
+                t.record_stream(stream)
 
 
 def make_desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seq_lens, scale: Optional[float] = None,
@@ -232,6 +252,18 @@ def hg_attn_profile_stop() -> Tuple[float, int]:
     return ms.value, n.value
 
 
+def hg_attn_profile_times(capacity: int):
+    """Milliseconds of one launch of the streaming kernel for each timed call so far (waits for them)."""
+    buf = (ctypes.c_float * max(int(capacity), 1))()
+    n = ctypes.c_int32()
+    _check(load_library().hg_attn_profile_times(buf, int(capacity), ctypes.byref(n)), "hg_attn_profile_times")
+    return [buf[i] for i in range(min(n.value, int(capacity)))]
+
+
+def hg_attn_build_id() -> str:
+    return load_library().hg_attn_build_id().decode()
+
+
 def hg_attn_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
     """Plain device copy of known traffic (profiler yardstick)."""
     nbytes = src.numel() * src.element_size()
@@ -275,6 +307,7 @@ def hg_attn_partial(q, k, v, seq_lens, ranges, scale=None, *, m=None, l=None, o=
         st = lib.hg_attn_partial(ctypes.byref(desc), packed, R, _ptr(m), _ptr(l), _ptr(o), _ptr(workspace), ws_bytes,
                                  _stream_handle(stream))
     _check(st, "hg_attn_partial")
+    _note_stream(stream, m, l, o, workspace)
     del keep
     return m, l, o
 
@@ -309,6 +342,7 @@ def hg_attn_merge(m, l, o, group_ptr, *, out=None, lse=None, want_lse=True, work
         st = lib.hg_attn_merge(_ptr(m), _ptr(l), _ptr(o), gp.ctypes.data, n_groups, Hq, d, _ptr(out), _ptr(lse),
                                _ptr(workspace), ws_bytes, _stream_handle(stream))
     _check(st, "hg_attn_merge")
+    _note_stream(stream, out, lse, workspace)
     return out, lse
 
 
@@ -353,6 +387,7 @@ def hg_attn_merge2(m_a, l_a, o_a, group_ptr_a, m_b, l_b, o_b, group_ptr_b, *, ou
                                 gpb.ctypes.data, n_groups, Hq, d, _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes,
                                 _stream_handle(stream))
     _check(st, "hg_attn_merge2")
+    _note_stream(stream, out, lse, workspace)
     return out, lse
 
 
@@ -383,6 +418,7 @@ def hg_attn_full(q, k, v, seq_lens, scale=None, *, out=None, lse=None, want_lse=
     with torch.cuda.device(dev):
         st = lib.hg_attn_full(ctypes.byref(desc), _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, _stream_handle(stream))
     _check(st, "hg_attn_full")
+    _note_stream(stream, out, lse, workspace)
     del keep
     return out, lse
 
@@ -412,6 +448,7 @@ def hg_attn_logits(q, k, v, seq_lens, ranges, scale=None, *, logits=None, worksp
     with torch.cuda.device(dev):
         st = lib.hg_attn_logits(ctypes.byref(desc), packed, R, _ptr(logits), _ptr(workspace), ws_bytes, _stream_handle(stream))
     _check(st, "hg_attn_logits")
+    _note_stream(stream, logits, workspace)
     del keep
     return logits
 
@@ -456,6 +493,7 @@ def hg_attn_concat(q, k, v, seq_lens, ranges, logits, group_ptr, scale=None, *, 
         st = lib.hg_attn_concat(ctypes.byref(desc), packed, R, _ptr(logits), gp.ctypes.data, n_groups, _ptr(out), _ptr(lse),
                                 _ptr(workspace), ws_bytes, _stream_handle(stream))
     _check(st, "hg_attn_concat")
+    _note_stream(stream, out, lse, workspace)
     del keep
     return out, lse
 
@@ -496,6 +534,7 @@ def hg_attn_select(q, k, v, seq_lens, ranges, logits, group_ptr, top_k, scale=No
         st = lib.hg_attn_select(ctypes.byref(desc), packed, R, _ptr(logits), gp.ctypes.data, G, int(top_k), _ptr(sel),
                                 _ptr(m), _ptr(l), _ptr(o), _ptr(workspace), ws_bytes, _stream_handle(stream))
     _check(st, "hg_attn_select")
+    _note_stream(stream, sel, m, l, o, workspace)
     del keep
     return sel, m, l, o
 
@@ -537,6 +576,7 @@ def hg_attn_topk(q, k, v, seq_lens, ranges, group_ptr, top_k, scale=None, *, wan
         st = lib.hg_attn_topk(ctypes.byref(desc), packed, R, gp.ctypes.data, G, int(top_k), _ptr(sel), _ptr(m), _ptr(l),
                               _ptr(o), _ptr(workspace), ws_bytes, _stream_handle(stream))
     _check(st, "hg_attn_topk")
+    _note_stream(stream, sel, m, l, o, workspace)
     del keep
     return sel, m, l, o
 
@@ -572,6 +612,7 @@ def hg_attn_gather(q, k, v, seq_lens, group_seq, index, scale=None, *, m=None, l
         st = lib.hg_attn_gather(ctypes.byref(desc), gs.ctypes.data, G, _ptr(index), int(index.shape[2]), _ptr(m), _ptr(l),
                                 _ptr(o), _ptr(workspace), ws_bytes, _stream_handle(stream))
     _check(st, "hg_attn_gather")
+    _note_stream(stream, m, l, o, workspace)
     del keep
     return m, l, o
 

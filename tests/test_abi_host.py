@@ -16,7 +16,7 @@ from paper_2604_18529_amd import _build
 from paper_2604_18529_amd import hg_attn as B
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "hg_attn.h")
+HEADERS = [os.path.join(ROOT, "include", "hg_attn.h"), os.path.join(ROOT, "include", "hg_attn_debug.h")]
 
 FAKE = 0x10000  # 16- and 256-byte aligned, never dereferenced
 
@@ -39,13 +39,26 @@ def _desc(seq_lens, batch=None, hq=4, hkv=2, d=128, dtype=0, stride_t=None, q=FA
     return desc
 
 
+def _declared(header):
+    text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+    return set(re.findall(r"\b(hg_[a-z_0-9]+)\s*\(", text))
+
+
 def test_exports_every_declared_function(lib):
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = set(re.findall(r"\b(hg_[a-z_0-9]+)\s*\(", text))
-    assert {"hg_attn_partial", "hg_attn_merge", "hg_attn_full", "hg_strerror"} <= names
-    for n in sorted(names):
+    method, aids = _declared(HEADERS[0]), _declared(HEADERS[1])
+    assert {"hg_attn_partial", "hg_attn_merge", "hg_attn_full", "hg_strerror", "hg_attn_build_id"} <= method
+    # process-wide knobs and blocking measurement aids live in the debug header only
+    assert {"hg_attn_set_span_tokens", "hg_attn_set_topk_mode", "hg_attn_profile_start", "hg_attn_profile_times",
+            "hg_attn_profile_stop", "hg_attn_calibration_copy"} <= aids
+    assert not (method & aids)
+    for n in sorted(method | aids):
         assert hasattr(lib, n), "library does not export %s" % n
+
+
+def test_binary_matches_the_sources(lib):
+    """The binary carries a hash of the sources it was built from; the loader compares it."""
+    assert B.hg_attn_build_id() == _build.source_id() == _build.binary_id()
+    assert not _build.is_stale()
 
 
 def test_strerror_is_total(lib):
