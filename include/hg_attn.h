@@ -316,6 +316,27 @@ hg_status hg_attn_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t
  * by the build step, or "unknown"); static storage.  Lets a loader refuse a stale binary. */
 const char *hg_attn_build_id(void);
 
+/*
+ * hg_attn_partial_static -- hg_attn_partial for callers that cannot allocate device memory and
+ * have no workspace to pass: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments and results as hg_attn_partial, but the segment records go to
+ * a buffer of HG_ATTN_STATIC_SCRATCH_BYTES bytes that is part of the library's device image (every
+ * GPU the library runs on holds its own copy until the process ends).  The call allocates
+ * nothing on the device.
+ *
+ *   HG_ERR_WORKSPACE  the problem needs more scratch than the static buffer holds (what
+ *                     hg_attn_partial_workspace_size reports for it); nothing has been enqueued.
+ *                     A message with both sizes goes to stderr.
+ *   All calls on one GPU share that GPU's buffer: two calls whose device work may overlap (other
+ *   streams, other threads) race on it.  Calls on one stream are ordered and safe.  Nothing in
+ *   the buffer has to start at zero: every record a call reads it has written itself.
+ *   The first call on a device looks the buffer's address up (and, like any first launch, loads
+ *   the device code); make that call outside a graph capture.
+ */
+#define HG_ATTN_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+hg_status hg_attn_partial_static(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, float *m, float *l,
+                                 float *o, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

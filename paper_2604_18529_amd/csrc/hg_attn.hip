@@ -23,6 +23,11 @@
 #include "../../include/hg_attn.h"
 #include "../../include/hg_attn_debug.h"
 
+// Scratch of hg_attn_partial_static: part of the device image, so every GPU the library runs on
+// holds its own copy at its own address.  Host code never uses this name as an address: it looks
+// the address up once per device (static_scratch below) and passes that pointer on.
+static __device__ __align__(256) unsigned char scratch[HG_ATTN_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace hg;
@@ -98,6 +103,30 @@ int compute_units()
     }
     cached[dev] = cus;
     return cus;
+}
+
+// Device address of `scratch` on the current device, looked up on the first call per device.
+hg_status static_scratch(void **ptr)
+{
+    static std::mutex mu;
+    static void *per_device[kMaxDevices] = {};
+    const int dev = current_device();
+    if (dev < 0) {
+        std::fprintf(stderr, "hg_attn: no current HIP device\n");
+        return HG_ERR_LAUNCH;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_device[dev]) {
+        void *p = nullptr;
+        const hipError_t err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || !p) {
+            std::fprintf(stderr, "hg_attn: address of the static scratch buffer on device %d: %s\n", dev, hipGetErrorString(err));
+            return HG_ERR_LAUNCH;
+        }
+        per_device[dev] = p;
+    }
+    *ptr = per_device[dev];
+    return HG_OK;
 }
 
 hg_status check_desc(const hg_attn_desc *d)
@@ -1035,6 +1064,29 @@ hg_status hg_attn_partial(const hg_attn_desc *desc, const hg_range *ranges, int3
     if (st != HG_OK) return st;
     if (n_ranges && (!m || !l || !o)) return HG_ERR_NULL;
     return run(desc, ranges, n_ranges, 0, m, l, o, workspace, ws_bytes, stream);
+}
+
+hg_status hg_attn_partial_static(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, float *m, float *l,
+                                 float *o, void *stream)
+{
+    hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = check_ranges(desc, ranges, n_ranges);
+    if (st != HG_OK) return st;
+    if (n_ranges && (!m || !l || !o)) return HG_ERR_NULL;
+    Plan p;
+    st = make_plan(desc, ranges, n_ranges, p);
+    if (st != HG_OK) return st;
+    if (p.total > HG_ATTN_STATIC_SCRATCH_BYTES) {
+        std::fprintf(stderr, "hg_attn_partial_static: this problem needs %zu bytes of scratch, the static buffer holds %zu; "
+                             "use hg_attn_partial with a workspace\n", p.total, (size_t)HG_ATTN_STATIC_SCRATCH_BYTES);
+        return HG_ERR_WORKSPACE;
+    }
+    if (n_ranges == 0 || p.total == 0) return run(desc, ranges, n_ranges, 0, m, l, o, nullptr, 0, stream);
+    void *buf = nullptr;
+    st = static_scratch(&buf);
+    if (st != HG_OK) return st;
+    return run(desc, ranges, n_ranges, 0, m, l, o, buf, HG_ATTN_STATIC_SCRATCH_BYTES, stream);
 }
 
 hg_status hg_attn_full_workspace_size(const hg_attn_desc *desc, size_t *bytes)

@@ -85,6 +85,7 @@ def load_library() -> ctypes.CDLL:
     lib.hg_strerror.restype = ctypes.c_char_p
     lib.hg_attn_partial_workspace_size.argtypes = [D, R, i32, ctypes.POINTER(sz)]
     lib.hg_attn_partial.argtypes = [D, R, i32, vp, vp, vp, vp, sz, vp]
+    lib.hg_attn_partial_static.argtypes = [D, R, i32, vp, vp, vp, vp]
     lib.hg_attn_merge_workspace_size.argtypes = [i32, ctypes.POINTER(sz)]
     lib.hg_attn_merge.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.hg_attn_topk_workspace_size.argtypes = [D, R, i32, vp, i32, i32, ctypes.POINTER(sz)]
@@ -111,7 +112,7 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
     lib.hg_attn_profile_times.argtypes = [ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32)]
     for name in (
-        "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_profile_times",
+        "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_partial_static", "hg_attn_profile_times",
         "hg_attn_merge_workspace_size", "hg_attn_merge",
         "hg_attn_merge2_workspace_size", "hg_attn_merge2", "hg_attn_gather_workspace_size", "hg_attn_gather",
         "hg_attn_topk_workspace_size", "hg_attn_topk",
@@ -308,6 +309,33 @@ def hg_attn_partial(q, k, v, seq_lens, ranges, scale=None, *, m=None, l=None, o=
                                  _stream_handle(stream))
     _check(st, "hg_attn_partial")
     _note_stream(stream, m, l, o, workspace)
+    del keep
+    return m, l, o
+
+
+def hg_attn_partial_static(q, k, v, seq_lens, ranges, scale=None, *, m=None, l=None, o=None, stream=None, desc=None,
+                           block_table=None):
+    """hg_attn_partial with the library's static scratch buffer instead of a workspace (the C
+    call allocates nothing; problems that need more scratch than it holds are refused)."""
+    lib = load_library()
+    if desc is None:
+        desc, keep = make_desc(q, k, v, seq_lens, scale, block_table)
+    else:
+        keep = None
+    packed = pack_ranges(ranges)
+    R = _n_ranges(packed)
+    dev = q.device
+    Hq, d = q.shape[1], q.shape[2]
+    if m is None:
+        m = torch.empty((R, Hq), dtype=torch.float32, device=dev)
+    if l is None:
+        l = torch.empty((R, Hq), dtype=torch.float32, device=dev)
+    if o is None:
+        o = torch.empty((R, Hq, d), dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        st = lib.hg_attn_partial_static(ctypes.byref(desc), packed, R, _ptr(m), _ptr(l), _ptr(o), _stream_handle(stream))
+    _check(st, "hg_attn_partial_static")
+    _note_stream(stream, m, l, o)
     del keep
     return m, l, o
 

@@ -46,7 +46,8 @@ def _declared(header):
 
 def test_exports_every_declared_function(lib):
     method, aids = _declared(HEADERS[0]), _declared(HEADERS[1])
-    assert {"hg_attn_partial", "hg_attn_merge", "hg_attn_full", "hg_strerror", "hg_attn_build_id"} <= method
+    assert {"hg_attn_partial", "hg_attn_merge", "hg_attn_full", "hg_strerror", "hg_attn_partial_static",
+            "hg_attn_build_id"} <= method
     # process-wide knobs and blocking measurement aids live in the debug header only
     assert {"hg_attn_set_span_tokens", "hg_attn_set_topk_mode", "hg_attn_profile_start", "hg_attn_profile_times",
             "hg_attn_profile_stop", "hg_attn_calibration_copy"} <= aids
@@ -59,6 +60,30 @@ def test_binary_matches_the_sources(lib):
     """The binary carries a hash of the sources it was built from; the loader compares it."""
     assert B.hg_attn_build_id() == _build.source_id() == _build.binary_id()
     assert not _build.is_stale()
+
+
+def test_static_scratch_entry_point_validates_like_partial(lib):
+    """hg_attn_partial_static: the same validation as hg_attn_partial, and problems whose segment
+    records do not fit the static buffer are refused before anything is enqueued."""
+    good = B.pack_ranges([(0, 0, 10)])
+
+    def call(desc, packed=good, n=1, m=FAKE, l=FAKE, o=FAKE):
+        return lib.hg_attn_partial_static(ctypes.byref(desc), packed, n, m, l, o, None)
+
+    assert call(_desc([10], dtype=7)) == -3
+    assert call(_desc([10], d=96)) == -2
+    assert call(_desc([10]), packed=B.pack_ranges([(0, 0, 11)])) == -4
+    assert call(_desc([10]), m=None) == -1
+    assert lib.hg_attn_partial_static(None, None, 0, None, None, None, None) == -1
+    assert call(_desc([10]), packed=None, n=0, m=None, l=None, o=None) == 0  # nothing to do
+    # 64 KV heads x 2000 one-token ranges: 128k segment records of 520 bytes, far beyond 16 MiB
+    many = [(0, i, i + 1) for i in range(2000)]
+    big = _desc([100000], hq=64, hkv=64)
+    sz = ctypes.c_size_t()
+    pm = B.pack_ranges(many)
+    assert lib.hg_attn_partial_workspace_size(ctypes.byref(big), pm, len(many), ctypes.byref(sz)) == 0
+    assert sz.value > (16 << 20)
+    assert call(big, packed=pm, n=len(many)) == -5
 
 
 def test_strerror_is_total(lib):
