@@ -90,6 +90,21 @@ def _time_loop(step, steps, warmup, torch):
     return e0.elapsed_time(e1) / steps, wall_ms / steps
 
 
+def _settle(step, settle_ms, torch):
+    """Untimed: keep the device under this step's load for settle_ms before anything is timed.
+    Measured on MI355X, the first 0.2 s of sustained streaming after a pause run about 5 % slower
+    than what follows (the kernel's duration along a 200-step loop that started cold: 2206, 2180,
+    2154, 2172, 2097, 2098, 2097 ... us per tenth), so a timed region that starts cold mixes two
+    regimes.  The timed steps themselves are unchanged."""
+    if settle_ms <= 0:
+        return
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < settle_ms:
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
+
+
 def _time_each(step, iters, warmup, torch, hg):
     """`iters` iterations, each with its own event pair around the step and (recorded by the
     library on the same stream) around the streaming kernel inside it.  Returns two lists of
@@ -252,8 +267,11 @@ def _routes(w, spec, steps, warmup, torch, hg, W, binding, desc, packed, out, ls
     return {
         "steps_each": n,
         "concat_route": {"logits_us": logits_ms * 1e3, "concat_us": concat_ms * 1e3, "us": (logits_ms + concat_ms) * 1e3,
+                         "logits_bytes": Hq * ltok * 4,
                          "logits_gbps_on_k_bytes": k_bytes / (logits_ms * 1e-3) / 1e9,
-                         "concat_gbps_on_v_and_logit_bytes": (k_bytes + Hq * ltok * 4) / (concat_ms * 1e-3) / 1e9},
+                         "logits_gbps_on_bytes_moved": (k_bytes + Hq * ltok * 4) / (logits_ms * 1e-3) / 1e9,
+                         # hg_attn_concat reads the logits twice: once for the groups' maxima and sums, once with the V rows
+                         "concat_gbps_on_bytes_moved": (k_bytes + 2 * Hq * ltok * 4) / (concat_ms * 1e-3) / 1e9},
         "post_qk_route": {"offloaded_fraction": 0.8, "top_k": top_k, "topk_us": pq_topk_ms * 1e3, "us": pq_step_ms * 1e3},
         "pre_qk_route": {"offloaded_fraction": 0.8, "listed_tokens": top_k, "us": pre_step_ms * 1e3},
         "proxy_query": dict(proxy, offloaded_fraction=0.8),
@@ -261,7 +279,8 @@ def _routes(w, spec, steps, warmup, torch, hg, W, binding, desc, packed, out, ls
     }
 
 
-def run_workload(index, torch, hg, W, *, steps=0, warmup=0, iters=100, cpu_baseline=True, routes=False, route_steps=20):
+def run_workload(index, torch, hg, W, *, steps=0, warmup=0, iters=100, cpu_baseline=True, routes=False, route_steps=20,
+                 settle_ms=0):
     """Full measurement block of one workload.  steps > 0: also the bracketed loop of exactly
     `steps` steps (the headline), with the kernel's event pairs recorded during those steps."""
     from paper_2604_18529_amd import hg_attn as binding
@@ -292,6 +311,7 @@ def run_workload(index, torch, hg, W, *, steps=0, warmup=0, iters=100, cpu_basel
         "workgroups": n_workgroups, "kv_bytes": kv_bytes,
     }
     loop_kernel_ms = None
+    _settle(step, settle_ms, torch)
     if steps > 0:
         # the headline loop: kernel event pairs are recorded by the library during these very steps
         for _ in range(warmup):
@@ -408,6 +428,35 @@ def run_tiny(torch, hg, W, iters=200, sets=64):
             "note": "launch-bound: three launches per step (one for the unsplit path); microseconds only"}
 
 
+def run_memory_probe(torch, hg, read_bytes=7516192768, reps=5):
+    """What this memory system gives a one-pass read stream with the streaming kernels' access
+    pattern, alone and next to writes (hg_attn_calibration_stream): the practical ceiling the
+    kernels are tuned against, and the cost of writes that trickle out next to the stream against
+    writes that go out in rare bursts.  read_bytes defaults to the K bytes of opt30b-b4-128k."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    src = torch.zeros(read_bytes + cus * 32768 + 65536, dtype=torch.uint8, device="cuda:0")
+    dst = torch.zeros(read_bytes // 8 + (1 << 20), dtype=torch.uint8, device="cuda:0")
+    iters = read_bytes // 16 // cus // 2048  # workgroup iterations of 32 KiB
+    rows = []
+
+    def timed(wvec, burst, nt):
+        def call():
+            hg.hg_attn_calibration_stream(src, read_bytes, dst, wvec, burst, nt)
+        ms, _ = _time_loop(call, reps, 2, torch)
+        written = (iters // burst) * burst * wvec * 16 * cus if wvec else 0
+        rows.append({"write_share": "none" if not wvec else "1/%d of the bytes" % (2048 // wvec), "burst_iterations": burst if wvec else None,
+                     "streaming_stores": bool(nt) if wvec else None, "written_bytes": written, "us": ms * 1e3,
+                     "read_gbps": iters * cus * 32768 / (ms * 1e-3) / 1e9})
+
+    timed(0, 1, 0)
+    for wvec in (32, 256):
+        for burst in (1, 16, 64, 128, 224, 448):
+            for nt in (0, 1):
+                timed(wvec, burst, nt)
+    timed(0, 1, 0)
+    return {"read_bytes": iters * cus * 32768, "workgroups": cus, "iterations_per_workgroup": iters, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -418,6 +467,8 @@ def main():
     ap.add_argument("--others", type=str, default="2,4,1,0",
                     help="comma list of further workloads: the in-bar ones (2, 3, 4) get the full block, 1 a short one, 0 the tiny one ('' for none)")
     ap.add_argument("--iters", type=int, default=100, help="iterations of the per-iteration timing pass (>= 100 by default)")
+    ap.add_argument("--settle-ms", type=float, default=400.0,
+                    help="untimed milliseconds of the step's own load before the warm-up steps of every workload (0: none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--routes", choices=("none", "headline", "all"), default="headline",
                     help="time the widened rows (concat, Post-QK^T, Pre-QK^T, proxy query, paged cache) on the headline workload, on every in-bar workload, or not at all")
@@ -425,6 +476,8 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run the library's plain 1 GiB device copy three times (known traffic: the "
                          "yardstick profiler byte counters are scaled by)")
+    ap.add_argument("--memory-probe", action="store_true",
+                    help="only run the plain read stream next to writes (hg_attn_calibration_stream) and print its table")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (across GPUs the path shards by (sequence, KV head), "
@@ -440,6 +493,10 @@ def main():
     hg.load_library()
     hg.hg_attn_set_span_tokens(args.span_tokens)
 
+    if args.memory_probe:
+        print(json.dumps({"memory_probe": run_memory_probe(torch, hg), "library_build_id": hg.hg_attn_build_id()}))
+        return
+
     if args.calibration_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)
@@ -450,7 +507,7 @@ def main():
 
     cpu = not args.no_cpu_baseline
     head = run_workload(args.workload, torch, hg, W, steps=args.steps, warmup=args.warmup, iters=args.iters, cpu_baseline=cpu,
-                        routes=args.routes != "none")
+                        routes=args.routes != "none", settle_ms=args.settle_ms)
     in_bar, short = [], []
     for tok in [t for t in args.others.split(",") if t.strip()]:
         i = int(tok)
@@ -460,11 +517,13 @@ def main():
         if i == 0:
             short.append(run_tiny(torch, hg, W))
         elif i in IN_BAR:
-            in_bar.append(run_workload(i, torch, hg, W, iters=args.iters, cpu_baseline=cpu, routes=args.routes == "all"))
+            in_bar.append(run_workload(i, torch, hg, W, iters=args.iters, cpu_baseline=cpu, routes=args.routes == "all",
+                                       settle_ms=args.settle_ms))
         else:
             # (a loop of 200 steps as well: between 150-us kernels the event pairs of the
             # per-iteration pass cost a visible share of the step)
-            r = run_workload(i, torch, hg, W, steps=200, warmup=20, iters=args.iters, cpu_baseline=False, routes=False)
+            r = run_workload(i, torch, hg, W, steps=200, warmup=20, iters=args.iters, cpu_baseline=False, routes=False,
+                             settle_ms=args.settle_ms)
             short.append({k: r[k] for k in ("workload", "kv_bytes", "us_per_layer", "gbps", "frac_hbm_peak", "step_us",
                                             "stream_kernel_us", "full_path_us", "graph_replay_us")})
 
@@ -475,6 +534,7 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "settle_ms": args.settle_ms,  # untimed load before the warm-up steps (see _settle)
         "ms_per_step": head["us_per_layer"] / 1e3,
         "us_per_layer": head["us_per_layer"],
         "frac_hbm_peak": head["frac_hbm_peak"],

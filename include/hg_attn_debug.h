@@ -53,6 +53,28 @@ hg_status hg_attn_profile_stop(float *total_ms, int32_t *launches);
  */
 hg_status hg_attn_calibration_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/*
+ * Measurement aid: a one-pass read stream with the access pattern of the streaming kernels (one
+ * workgroup of 256 threads per compute unit, non-temporal 16-byte loads, 32 KiB per workgroup
+ * iteration, the workgroups' shares starting 32 KiB further apart than they are long), alone or
+ * next to writes.  It shows what this memory system gives such a stream -- the practical ceiling
+ * the kernels are tuned against -- and what writes next to it cost.
+ *
+ *   src, read_bytes   DEVICE, 16-byte aligned; the kernel reads floor(read_bytes / 16 / CUs / 2048)
+ *                     * 2048 vectors per workgroup; src must hold read_bytes + CUs * 32 KiB.
+ *                     Fill it with zeros.
+ *   dst               DEVICE, 16-byte aligned, or NULL when nothing is written; must hold
+ *                     iterations * write_vectors_per_iteration * 16 bytes per workgroup
+ *                     (at most read_bytes * write_vectors_per_iteration / 2048 in all) and 16 bytes at least.
+ *   write_vectors_per_iteration   0 .. 2048: 16-byte vectors written per 32 KiB read, on average
+ *                     (32 = 1/64 of the bytes, 256 = 1/8).
+ *   burst_iterations  >= 1: the writes of that many iterations go out together, as one contiguous
+ *                     run per workgroup (1 = a trickle; a burst that never completes is not written).
+ *   streaming_stores  non-zero: non-temporal stores.
+ */
+hg_status hg_attn_calibration_stream(const void *src, size_t read_bytes, void *dst, int32_t write_vectors_per_iteration,
+                                     int32_t burst_iterations, int32_t streaming_stores, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

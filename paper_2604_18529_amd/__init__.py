@@ -27,6 +27,7 @@ _API = (
     "hg_attn_profile_start",
     "hg_attn_profile_stop",
     "hg_attn_calibration_copy",
+    "hg_attn_calibration_stream",
     "pack_ranges",
     "make_desc",
     "hg_strerror",

@@ -958,6 +958,22 @@ hg_status hg_attn_calibration_copy(void *dst, const void *src, size_t bytes, voi
     return launch_status("calibration copy");
 }
 
+hg_status hg_attn_calibration_stream(const void *src, size_t read_bytes, void *dst, int32_t write_vectors_per_iteration,
+                                     int32_t burst_iterations, int32_t streaming_stores, void *stream)
+{
+    if (!src) return HG_ERR_NULL;
+    if ((uintptr_t)src % 16 || (uintptr_t)dst % 16) return HG_ERR_SHAPE;
+    if (write_vectors_per_iteration < 0 || write_vectors_per_iteration > 2048 || burst_iterations < 1) return HG_ERR_SHAPE;
+    if (write_vectors_per_iteration > 0 && !dst) return HG_ERR_NULL;
+    const size_t n_wg = (size_t)compute_units();
+    const size_t share_vec = read_bytes / 16 / n_wg / 2048 * 2048;  // whole 32 KiB iterations
+    if (share_vec == 0 || share_vec / 2048 > 0x7fffffff / 2048) return HG_ERR_SHAPE;
+    HG_LAUNCH(hg_calibration_stream_kernel, dim3((unsigned)n_wg), dim3(256), static_cast<hipStream_t>(stream),
+              static_cast<const hg_u32x4 *>(src), share_vec, static_cast<hg_u32x4 *>(dst), (int)write_vectors_per_iteration,
+              (int)burst_iterations, (int)streaming_stores);
+    return launch_status("calibration stream");
+}
+
 hg_status hg_attn_profile_start(int32_t max_calls, int32_t repeat)
 {
     if (max_calls < 0 || max_calls > 65536 || repeat < 1 || repeat > 1024) return HG_ERR_SHAPE;

@@ -281,4 +281,42 @@ __global__ __launch_bounds__(256) void hg_calibration_copy_kernel(hg_u32x4 *dst,
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+// One-pass read stream, alone or next to writes: what this memory system gives the access pattern
+// of the streaming kernels (one workgroup per compute unit, non-temporal 16-byte loads, 32 KiB per
+// workgroup iteration, starts 32 KiB further apart than the shares are long).  With wvec > 0 every
+// workgroup also writes wvec 16-byte vectors per iteration on average, issued as one contiguous
+// burst of burst * wvec vectors every `burst` iterations (streaming stores if nt).
+__global__ __launch_bounds__(256) void hg_calibration_stream_kernel(const hg_u32x4 *src, size_t share_vec, hg_u32x4 *dst, int wvec,
+                                                                  int burst, int nt)
+{
+    constexpr int U = 8;
+    const hg_u32x4 *base = src + (size_t)blockIdx.x * (share_vec + 2048);
+    const int iters = (int)(share_vec / (256 * U));
+    hg_u32x4 *out = dst + (size_t)blockIdx.x * (size_t)iters * (size_t)wvec;
+    hg_u32x4 acc = {0u, 0u, 0u, 0u};
+    int next_burst = burst - 1;
+    for (int it = 0; it < iters; ++it) {
+        hg_u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(base + (size_t)it * (256 * U) + u * 256 + threadIdx.x);
+        hg_u32x4 x = v[0];
+#pragma unroll
+        for (int u = 1; u < U; ++u) x ^= v[u];
+        acc ^= x;
+        if (wvec > 0 && it == next_burst) {
+            const int n = burst * wvec;
+            hg_u32x4 *to = out + (size_t)(it / burst) * (size_t)n;
+            for (int i = threadIdx.x; i < n; i += 256) {
+                if (nt)
+                    __builtin_nontemporal_store(acc, to + i);
+                else
+                    to[i] = acc;
+            }
+            next_burst += burst;
+        }
+    }
+    // (keeps the loads alive; never true for the zero-filled source a caller passes)
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345678u) dst[0] = acc;
+}
+
 }  // namespace hg

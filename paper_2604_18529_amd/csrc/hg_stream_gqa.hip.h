@@ -44,6 +44,22 @@ constexpr int kGqaAfterSeed = 3;    // filter mode: first evaluation of the shar
 constexpr int kGqaSetsPerHead = 64;  // filter mode: values a workgroup may publish per head (one per lane position and wave)
 constexpr int kGqaMaxPeers = 32;         // filter mode: workgroups whose published values a shared bound is taken from
 constexpr int kGqaStage = 64;            // filter mode: survivors staged in LDS per (wave, head) between write-outs
+// Logits mode: as in the vector kernel, stores that trickle out next to the read stream cost far
+// more than their bytes, so the logits are collected in an LDS window (96 KiB laid out
+// [valid head][tokens + 4]: the fewer heads, the more tokens it holds) that all four waves write
+// out together, between two LDS-only barriers, when it is full; it runs on across the ranges of a
+// stream.  With 8 query heads per KV head the window holds 2944 tokens; the logits are then an
+// eighth of all bytes moved, and what remains above the bare scan is close to what writing them in
+// a phase of their own costs.
+constexpr int kGqaRingFloats = 24576;
+constexpr int kGqaIterTokens = HG_GQA_WAVES * kGqaBlockTokens;  // tokens of one workgroup iteration
+
+__device__ __forceinline__ void gqa_workgroup_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 
 typedef _Float16 hg_h8 __attribute__((ext_vector_type(8)));
 typedef __bf16 hg_b8 __attribute__((ext_vector_type(8)));
@@ -143,7 +159,7 @@ __device__ __forceinline__ void wave_lds_handover()
 // registers instead of scratch memory: a scratch access inside the loop would make every wait for
 // K rows a wait for all memory operations in flight.
 template <int MODE, bool PAGED, bool BF16, int FJ = 2>
-__global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 2 : 1) void hg_partial_gqa_kernel(const PartialArgs a)
+__global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter && MODE != kModeLogits ? 2 : 1) void hg_partial_gqa_kernel(const PartialArgs a)
 {
     constexpr int D = 128;
     constexpr int kMergeBytes = kGqaWaves * kGqaHeads * (D + 2) * 4;
@@ -158,6 +174,35 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     // filter mode: survivors wait here, per wave and head, until a run of them is written out
     __shared__ float stage_val[MODE == kModeFilter ? kGqaWaves * kGqaHeads * kGqaStage : 1];
     __shared__ int32_t stage_col[MODE == kModeFilter ? kGqaWaves * kGqaHeads * kGqaStage : 1];
+
+    __shared__ __align__(16) float lring[MODE == kModeLogits ? kGqaRingFloats : 1];  // logits mode: the window
+    // logits mode: tokens in the window, tokens it holds and floats per head (+ 4: the four row
+    // groups of an LDS store then fall on different banks), the index in `logits` of its first
+    // token for the chunk's first head (row * ltok + column), the valid heads of its chunk.  Uniform.
+    int win_fill = 0, win_tokens = 0, win_stride = 0, win_nh = 0;
+    int64_t win_at = 0;
+    auto flush_window = [&]() __attribute__((always_inline)) {
+        typedef float wf4 __attribute__((ext_vector_type(4)));
+        typedef float wf4u __attribute__((ext_vector_type(4), aligned(4)));
+        gqa_workgroup_lds_barrier();  // the window is complete
+        for (int g = 0; g < win_nh; ++g) {
+            float *dst = a.logits + win_at + (int64_t)g * a.ws.ltok;
+            for (int c = 4 * (int)threadIdx.x; c < win_fill; c += 4 * kGqaBlock) {
+                const wf4 vals = *reinterpret_cast<const wf4 *>(lring + g * win_stride + c);
+                if (c + 4 <= win_fill) {
+                    const wf4u out = vals;
+                    __builtin_nontemporal_store(out, reinterpret_cast<wf4u *>(dst + c));
+                } else {
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        if (c + x < win_fill) dst[c + x] = vals[x];
+                }
+            }
+        }
+        gqa_workgroup_lds_barrier();  // copied: the window is free again
+        win_at += win_fill;
+        win_fill = 0;
+    };
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: block loop control stays scalar
@@ -184,6 +229,18 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     const int g0 = chunk * kGqaHeads;
     const int nh = min(kGqaHeads, a.ws.group - g0);
     const int h0 = hk * a.ws.group + g0;
+
+    if constexpr (MODE == kModeLogits) {
+        // does this segment go on where the window ends?  Otherwise the window is written out first.
+        const int64_t seg_at = (int64_t)h0 * a.ws.ltok + seg_col0;
+        if (win_fill > 0 && (seg_at != win_at + win_fill || nh != win_nh)) flush_window();
+        if (win_fill == 0) {
+            win_at = seg_at;
+            win_nh = nh;
+            win_tokens = (kGqaRingFloats / nh - 4) / kGqaIterTokens * kGqaIterTokens;
+            win_stride = win_tokens + 4;
+        }
+    }
 
     // Q as A operand: lane l holds head l%16, channels 8*(4kk + l/16)..+7 for kk = 0..3
     hg_u32x4 qa[4];
@@ -256,7 +313,27 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     };
 
     // The 8 K-row loads and the 8 V-row loads of one 32-token block (8 KiB each per wave).
+    // Statistics mode on a contiguous cache: a lane's 16-byte load of token n, channel chunk
+    // 4 kk + rg IS its B operand of MFMA kk, so K needs no trip through LDS (a load instruction
+    // then covers 16 rows x 64 bytes instead of 4 whole rows; the byte counters show no extra
+    // traffic, and the block got about 1 % faster).  Without the non-temporal hint the same loads
+    // lost 10 %.
+    constexpr bool kDirectK = MODE == kModeStats && !PAGED;
+    const uint32_t lane_off_d = (uint32_t)n * row_b32 + (uint32_t)rg * 16u;   // direct K: token n of a half, chunk rg of a group of four
+    const uint32_t last_row_off = (uint32_t)(t1 - 1 - t0) * row_b32;
     auto load_k = [&](int tb, hg_u32x4(&kreg)[8], const int(&pg)[8]) __attribute__((always_inline)) {
+        if constexpr (kDirectK) {
+            // every lane fetches its own B operands: token tb + 16 hf + n, channels 8 (4 kk + rg) .. + 7
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int hf = i >> 2, kk = i & 3;
+                const uint32_t off = (uint32_t)(tb - t0 + 16 * hf) * row_b32 + lane_off_d + (uint32_t)kk * 64u;
+                const uint32_t last = last_row_off + (uint32_t)rg * 16u + (uint32_t)kk * 64u;
+                const char *src = kbase + (off < last ? off : last);
+                kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const hg_u32x4 *>(src));
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const char *src = PAGED ? kbase + paged_offset(tb + 4 * i + rg, pg[i]) : kbase + flat_offset(tb, 4 * i, lane_off);
@@ -390,10 +467,12 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     // has been consumed, so a wave always has 8-16 KiB in flight while it computes.
     auto compute_block = [&](int tb, int tb_next, hg_u32x4(&kreg)[8], hg_u32x4(&vreg)[8]) __attribute__((always_inline)) {
         // K: registers -> LDS (row per token) -> B operands (token per lane)
+        if constexpr (!kDirectK) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<hg_u32x4 *>(kls + (4 * i + rg) * kGqaKRow + n * 16) = kreg[i];
-        wave_lds_handover();
+            for (int i = 0; i < 8; ++i)
+                *reinterpret_cast<hg_u32x4 *>(kls + (4 * i + rg) * kGqaKRow + n * 16) = kreg[i];
+            wave_lds_handover();
+        }
         if constexpr (PAGED && MODE == kModeStats) {
             // Pages three blocks ahead, requested before this block's loads: the registers are not
             // touched again until the rotation at the end of the block, a whole block later, so the
@@ -408,7 +487,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
         // flight is unknown at compile time, the wait for this block's rows becomes a wait for all
         // loads, and the second register buffer buys nothing.
         constexpr bool kAlwaysAhead = !PAGED && (MODE == kModeLogits || MODE == kModeFilter);
-        if (kAlwaysAhead || tb_next < t1) {
+        if (!kDirectK && (kAlwaysAhead || tb_next < t1)) {
             load_k(tb_next, kreg, pg1);
             if constexpr (PAGED && (MODE == kModeLogits || MODE == kModeFilter)) {  // blocks are loaded in order: pages of the one after
                 if (tb_next + kStride < t1) lookup(tb_next + kStride, pg1);
@@ -438,41 +517,37 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
                 s[hf] = hg_f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
-                    hg_u32x4 raw = *reinterpret_cast<const hg_u32x4 *>(kls + (16 * hf + n) * kGqaKRow + (4 * kk + rg) * 16);
+                    hg_u32x4 raw;
+                    if constexpr (kDirectK)
+                        raw = kreg[4 * hf + kk];
+                    else
+                        raw = *reinterpret_cast<const hg_u32x4 *>(kls + (16 * hf + n) * kGqaKRow + (4 * kk + rg) * 16);
                     s[hf] = mfma_16x16x32<BF16>(qa[kk], raw, s[hf]);
                 }
+            }
+            if constexpr (kDirectK) {
+                if (tb_next < t1) load_k(tb_next, kreg, pg1);  // the operands are consumed: request the next block's
             }
         }
 
         if constexpr (MODE == kModeLogits) {
-            // export: lane (n, rg) holds heads 4rg..4rg+3 of tokens tb + n and tb + 16 + n.  The
-            // tile goes through the (idle) P staging area as [head][32 tokens] so that a lane can
-            // store four consecutive tokens of one head: a wave store instruction then writes
-            // 8 heads x 128 bytes instead of 64-byte pieces.
-            float *stile = reinterpret_cast<float *>(pls);
+            // export: lane (n, rg) holds heads 4rg..4rg+3 of tokens tb + n and tb + 16 + n; they go
+            // to the window at the tokens' places.  (A block past the segment's end, which the paired
+            // loop may run, takes no part; every wave makes the same decision for the same
+            // workgroup iteration.)
+            if (tb < t1) {
+                if (win_fill + kGqaIterTokens > win_tokens) flush_window();
+                float *buf = lring + win_fill + wave * kGqaBlockTokens + n;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                stile[(4 * rg + r) * 32 + n] = s[0][r] * a.qscale;
-                stile[(4 * rg + r) * 32 + 16 + n] = s[1][r] * a.qscale;
-            }
-            wave_lds_handover();
-            typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const int head = 8 * half + (lane >> 3), tq = 4 * (lane & 7);  // 8 lanes per head
-                if (head < nh && tb + tq < t1) {
-                    const hg_f4 vals = *reinterpret_cast<const hg_f4 *>(stile + head * 32 + tq);
-                    float *dst = a.logits + (int64_t)(h0 + head) * a.ws.ltok + col0 + (tb - t0) + tq;
-                    if (tb + tq + 4 <= t1) {
-                        *reinterpret_cast<f4u *>(dst) = vals;
-                    } else {
-#pragma unroll
-                        for (int x = 0; x < 4; ++x)
-                            if (tb + tq + x < t1) dst[x] = vals[x];
+                for (int r = 0; r < 4; ++r) {
+                    if (4 * rg + r < nh) {
+                        buf[(4 * rg + r) * win_stride] = s[0][r] * a.qscale;
+                        buf[(4 * rg + r) * win_stride + 16] = s[1][r] * a.qscale;
                     }
                 }
+                win_fill += kGqaIterTokens;
             }
-            wave_lds_handover();  // the next block overwrites the staging areas
+            wave_lds_handover();  // the next block overwrites the K staging area
             return;
         }
         if constexpr (MODE == kModeFilter) {
@@ -879,7 +954,20 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
             }
         }
     }
-    if constexpr (MODE == kModeLogits) return;  // nothing to merge or record
+    if constexpr (MODE == kModeLogits) {
+        // A wave without tokens in the segment's last workgroup iteration still takes that
+        // iteration's step, so that all waves agree on the window; then the part of the last
+        // iteration beyond the segment's end is given back.
+        const int n_tok = seg_t1 - seg_t0;
+        const int n_iters = (n_tok + kGqaIterTokens - 1) / kGqaIterTokens;
+        const int mine = n_tok > wave * kGqaBlockTokens ? (n_tok - wave * kGqaBlockTokens + kGqaIterTokens - 1) / kGqaIterTokens : 0;
+        if (mine < n_iters) {
+            if (win_fill + kGqaIterTokens > win_tokens) flush_window();
+            win_fill += kGqaIterTokens;
+        }
+        win_fill -= n_iters * kGqaIterTokens - n_tok;
+        return;  // nothing to merge or record
+    }
     if constexpr (MODE == kModeFilter) {
         flush_staged();
         if (n == 0) {
@@ -921,6 +1009,9 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter ? 
     }
     __syncthreads();  // the next segment reuses the staging areas
     });
+    if constexpr (MODE == kModeLogits) {
+        if (win_fill > 0) flush_window();
+    }
 }
 
 }  // namespace hg

@@ -39,12 +39,72 @@ __device__ __forceinline__ float group_softmax_max(const float *gs_m, int64_t ba
 
 // (One workgroup per compute unit is launched on long inputs, so the register allocator is told
 // that two waves per SIMD is all the occupancy this kernel wants.)
+// Logits mode.  Measured on MI355X, stores that trickle out next to a saturating read stream cost
+// the memory system far more than their share of the bytes: the scan that wrote its 128 bytes per
+// wave and iteration ran at 67 % of the HBM peak where the same scan without stores reaches 86 %,
+// with no extra traffic in the byte counters; what costs is every switch between reading and
+// writing, not the bytes.  So the logits are collected in LDS (a window of up to 32768 logits per
+// head chunk, 128 KiB), and only when the window is full do all four waves stop reading and write
+// it out together, in runs of up to 128 KiB per head with streaming stores; then they go on
+// reading.  The window runs on across segment boundaries as long as the next segment's logits
+// continue where the window ends in the rows of `logits` (the next range of the same stream; with
+// one head per stream also the next stream), so a ragged table does not mean more write-outs.
+#ifndef HG_VALU_ROUND_FLOATS
+#define HG_VALU_ROUND_FLOATS 32768
+#endif
+constexpr int kValuRoundFloats = HG_VALU_ROUND_FLOATS;  // logits in the window, all heads of the chunk together
+
+template <int GT, int CH>
+struct ValuRound {
+    static constexpr int kIterTokens = kValuWaves * CH;  // tokens of one workgroup iteration
+    static constexpr int kTokens = kValuRoundFloats / GT / kIterTokens * kIterTokens;  // tokens the window holds per head
+    static_assert(kTokens >= kIterTokens, "the window holds at least one workgroup iteration");
+};
+
+__device__ __forceinline__ void workgroup_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 template <typename TR, int GT, int U, int MODE, bool PAGED>
 __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2))) void hg_partial_kernel(const PartialArgs a)
 {
     constexpr int D = TR::D, EPL = TR::EPL, NV = TR::NV, EPV = TR::EPV, ES = TR::ES;
     constexpr int LPR = TR::LPR, RPW = TR::RPW;
     constexpr int CH = RPW * U;  // tokens one wave takes per iteration
+    using Round = ValuRound<GT, CH>;
+    __shared__ __align__(16) float ring[MODE == kModeLogits ? GT * Round::kTokens : 1];  // logits mode: the window, [head][token]
+    // logits mode: tokens in the window, the index in `logits` of its first token for the chunk's
+    // first head (row * ltok + column), and the valid heads of its chunk.  Uniform.
+    int win_fill = 0, win_nh = 0;
+    int64_t win_at = 0;
+    // all waves write the window's win_fill tokens per head to the rows of `logits` (1 KiB per wave
+    // and store instruction), between two barriers: the window is complete before anybody copies,
+    // and copied before anybody overwrites it
+    auto flush_window = [&]() __attribute__((always_inline)) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+        workgroup_lds_barrier();
+        for (int g = 0; g < win_nh; ++g) {
+            float *dst = a.logits + win_at + (int64_t)g * a.ws.ltok;
+            for (int c = 4 * (int)threadIdx.x; c < win_fill; c += 4 * kValuBlock) {
+                const f4 vals = *reinterpret_cast<const f4 *>(ring + g * Round::kTokens + c);
+                if (c + 4 <= win_fill) {
+                    const f4u out = vals;
+                    __builtin_nontemporal_store(out, reinterpret_cast<f4u *>(dst + c));
+                } else {
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        if (c + x < win_fill) dst[c + x] = vals[x];
+                }
+            }
+        }
+        workgroup_lds_barrier();
+        win_at += win_fill;
+        win_fill = 0;
+    };
 
     __shared__ float sm[kValuWaves][GT][D + 2];
     // filter mode (one head per stream): each wave's bound, and the survivors waiting to be written out
@@ -75,6 +135,16 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
     const int g0 = chunk * GT;                              // first head of this chunk inside its group
     const int nh = min(GT, a.ws.group - g0);                // valid heads in this chunk
     const int h0 = hk * a.ws.group + g0;                    // first query head
+
+    if constexpr (MODE == kModeLogits) {
+        // does this segment go on where the window ends?  Otherwise the window is written out first.
+        const int64_t seg_at = (int64_t)h0 * a.ws.ltok + seg_col0;
+        if (win_fill > 0 && (seg_at != win_at + win_fill || nh != win_nh)) flush_window();
+        if (win_fill == 0) {
+            win_at = seg_at;
+            win_nh = nh;
+        }
+    }
 
     // q fragments, scaled into the log2 domain (natural-log domain when exporting logits)
     float qf[GT][EPL];
@@ -176,6 +246,7 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
         __syncthreads();
     }
 
+    int it = 0;  // logits mode: this wave's iteration inside the segment
     for (int tb = t0 + first; tb < t1; tb += kStep) {
         typename TR::Raw kraw[U][NV], vraw[U][NV];
         bool valid[U];
@@ -234,16 +305,20 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
 
         if constexpr (MODE == kModeLogits) {
             // Every lane of a group holds all GT*U logits of the group's U tokens.  Lane `sub`
-            // stores entry (g, u) = (idx / U, idx % U), idx = pass * LPR + sub, so one store
-            // instruction of the wave writes U * RPW consecutive tokens (128 bytes or more) of
-            // each head instead of one token per group.
+            // puts entry (g, u) = (idx / U, idx % U), idx = pass * LPR + sub, into this round's
+            // buffer at the token's place, so one LDS store instruction of the wave covers U * RPW
+            // consecutive tokens of a head.  (Tokens past the segment's end leave their place
+            // unwritten; only the segment's tokens are copied out.)
             constexpr int kPasses = (GT * U + LPR - 1) / LPR;
+            // (every wave makes the same decision for the same workgroup iteration)
+            if (win_fill + Round::kIterTokens > Round::kTokens) flush_window();
+            float *buf = ring + win_fill + wave * CH;
 #pragma unroll
             for (int pass = 0; pass < kPasses; ++pass) {
                 const int idx = pass * LPR + sub;
                 float val = 0.f;
                 bool ok = false;
-                int tok = t0;
+                int place = 0;
 #pragma unroll
                 for (int g = 0; g < GT; ++g)
 #pragma unroll
@@ -251,10 +326,12 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
                         if (g * U + u >= pass * LPR && g * U + u < (pass + 1) * LPR && idx == g * U + u) {
                             val = s[g][u];
                             ok = valid[u] && g < nh;
-                            tok = tokc[u];
+                            place = g * Round::kTokens + RPW * u + grp;
                         }
-                if (ok) a.logits[(int64_t)(h0 + idx / U) * a.ws.ltok + col0 + (tok - t0)] = val;
+                if (ok) buf[place] = val;
             }
+            ++it;
+            win_fill += Round::kIterTokens;
         }
 
         if constexpr (MODE == kModeFilter) {
@@ -371,7 +448,18 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
             for (int u = 0; u < U; ++u) pg[u] = pg_next[u];
         }
     }
-    if constexpr (MODE == kModeLogits) return;  // nothing to merge or record
+    if constexpr (MODE == kModeLogits) {
+        // A wave without tokens in the segment's last workgroup iteration still takes that
+        // iteration's step, so that all waves agree on the window; then the part of the last
+        // iteration beyond the segment's end is given back.
+        const int n_iters = (seg_t1 - seg_t0 + Round::kIterTokens - 1) / Round::kIterTokens;
+        if (it < n_iters) {
+            if (win_fill + Round::kIterTokens > Round::kTokens) flush_window();
+            win_fill += Round::kIterTokens;
+        }
+        win_fill -= n_iters * Round::kIterTokens - (seg_t1 - seg_t0);
+        return;  // nothing to merge or record
+    }
     if constexpr (MODE == kModeFilter) {
         flush_staged();
         if (lane == 0) a.surv_cnt[(slot * kValuWaves + wave) * GT] = (int32_t)written;
@@ -422,6 +510,9 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
     }
     __syncthreads();  // the next segment reuses sm
     });
+    if constexpr (MODE == kModeLogits) {
+        if (win_fill > 0) flush_window();
+    }
 }
 
 }  // namespace hg

@@ -109,6 +109,7 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_set_topk_mode.argtypes = [i32]
     lib.hg_attn_profile_start.argtypes = [i32, i32]
     lib.hg_attn_calibration_copy.argtypes = [vp, vp, sz, vp]
+    lib.hg_attn_calibration_stream.argtypes = [vp, sz, vp, i32, i32, i32, vp]
     lib.hg_attn_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
     lib.hg_attn_profile_times.argtypes = [ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32)]
     for name in (
@@ -117,7 +118,7 @@ def load_library() -> ctypes.CDLL:
         "hg_attn_merge2_workspace_size", "hg_attn_merge2", "hg_attn_gather_workspace_size", "hg_attn_gather",
         "hg_attn_topk_workspace_size", "hg_attn_topk",
         "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_span_tokens", "hg_attn_set_topk_mode",
-        "hg_attn_profile_start", "hg_attn_profile_stop", "hg_attn_calibration_copy",
+        "hg_attn_profile_start", "hg_attn_profile_stop", "hg_attn_calibration_copy", "hg_attn_calibration_stream",
         "hg_sched_init", "hg_sched_step", "hg_attn_logits_workspace_size", "hg_attn_logits", "hg_attn_select_workspace_size", "hg_attn_select", "hg_attn_concat_workspace_size", "hg_attn_concat",
     ):
         getattr(lib, name).restype = ctypes.c_int
@@ -273,6 +274,15 @@ def hg_attn_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) 
     with torch.cuda.device(src.device):
         st = load_library().hg_attn_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_handle(stream))
     _check(st, "hg_attn_calibration_copy")
+
+
+def hg_attn_calibration_stream(src: torch.Tensor, read_bytes: int, dst: Optional[torch.Tensor] = None, write_vectors: int = 0,
+                               burst_iterations: int = 1, streaming_stores: bool = False, stream=None) -> None:
+    """Plain read stream of `read_bytes` bytes of src, optionally next to writes into dst (see the debug header)."""
+    with torch.cuda.device(src.device):
+        st = load_library().hg_attn_calibration_stream(src.data_ptr(), int(read_bytes), _ptr(dst), int(write_vectors),
+                                                       int(burst_iterations), int(bool(streaming_stores)), _stream_handle(stream))
+    _check(st, "hg_attn_calibration_stream")
 
 
 def hg_attn_partial_workspace_size(desc, packed) -> int:

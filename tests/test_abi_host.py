@@ -50,7 +50,7 @@ def test_exports_every_declared_function(lib):
             "hg_attn_build_id"} <= method
     # process-wide knobs and blocking measurement aids live in the debug header only
     assert {"hg_attn_set_span_tokens", "hg_attn_set_topk_mode", "hg_attn_profile_start", "hg_attn_profile_times",
-            "hg_attn_profile_stop", "hg_attn_calibration_copy"} <= aids
+            "hg_attn_profile_stop", "hg_attn_calibration_copy", "hg_attn_calibration_stream"} <= aids
     assert not (method & aids)
     for n in sorted(method | aids):
         assert hasattr(lib, n), "library does not export %s" % n
@@ -84,6 +84,21 @@ def test_static_scratch_entry_point_validates_like_partial(lib):
     assert lib.hg_attn_partial_workspace_size(ctypes.byref(big), pm, len(many), ctypes.byref(sz)) == 0
     assert sz.value > (16 << 20)
     assert call(big, packed=pm, n=len(many)) == -5
+
+
+def test_measurement_aids_validate_their_arguments(lib):
+    assert lib.hg_attn_calibration_stream(None, 1 << 30, FAKE, 32, 1, 0, None) == -1
+    assert lib.hg_attn_calibration_stream(FAKE, 1 << 30, None, 32, 1, 0, None) == -1   # writes need a destination
+    assert lib.hg_attn_calibration_stream(FAKE + 4, 1 << 30, FAKE, 0, 1, 0, None) == -2  # misaligned
+    assert lib.hg_attn_calibration_stream(FAKE, 1 << 30, FAKE, 4096, 1, 0, None) == -2
+    assert lib.hg_attn_calibration_stream(FAKE, 1 << 30, FAKE, 32, 0, 0, None) == -2
+    assert lib.hg_attn_calibration_stream(FAKE, 1000, FAKE, 0, 1, 0, None) == -2       # less than one iteration per workgroup
+    assert lib.hg_attn_calibration_copy(None, FAKE, 16, None) == -1
+    assert lib.hg_attn_calibration_copy(FAKE, FAKE * 2, 8, None) == -2
+    assert lib.hg_attn_profile_start(-1, 1) == -2 and lib.hg_attn_profile_start(1, 0) == -2
+    n = ctypes.c_int32(-1)
+    assert lib.hg_attn_profile_times(None, 4, ctypes.byref(n)) == -1
+    assert lib.hg_attn_profile_times(None, 0, ctypes.byref(n)) == 0 and n.value == 0
 
 
 def test_strerror_is_total(lib):
