@@ -13,10 +13,12 @@ namespace hg {
 // percent of the matrix cores and the kernel is bandwidth-bound again.
 //
 // Per wave and per block of 32 tokens:
-//   K   8 coalesced 16-byte loads per lane (4 whole rows per instruction) -> wave-private LDS
-//       (rows padded to 272 bytes) -> read back "token per lane": lane l gets token l%16,
-//       channels 8*(4kk + l/16)..+7, which IS the B operand of MFMA kk (the contraction runs
-//       over channels, and Q is laid out with the same channel grouping as A operand).
+//   K   the B operand of MFMA kk is "token per lane": lane l holds token l%16, channels
+//       8*(4kk + l/16)..+7 (the contraction runs over channels, and Q is laid out with the same
+//       channel grouping as A operand).  Statistics mode on a contiguous cache loads exactly
+//       those 16 bytes per lane (a load instruction then covers 16 rows x 64 bytes); the other
+//       modes and paged caches take 8 coalesced 16-byte loads per lane (4 whole rows per
+//       instruction) -> wave-private LDS (rows padded to 288 bytes) -> read back token per lane.
 //       S = Q.K^T lands as: lane (n = l%16, rg = l/16) holds heads 4rg..4rg+3 of token n.
 //   softmax  row max over the 16 token lanes by DPP, running (m, l) per head, P = exp2(S - m).
 //       P is split into an fp16 head and an fp16 remainder (p = ph + pl to ~22 bits), so the
@@ -31,7 +33,8 @@ namespace hg {
 
 constexpr int kGqaHeads = 16;            // query heads per workgroup (M of the MFMA)
 constexpr int kGqaBlockTokens = 32;      // tokens per wave iteration (K of the P.V MFMA)
-constexpr int kGqaKRow = 272;            // padded LDS row: 256 bytes + 16 so that 16 rows spread over all banks
+constexpr int kGqaKRow = 288;            // padded LDS row: 256 bytes + 32 (the bank-conflict counter reads zero with it; with + 16 the
+                                         // 16-byte reads of 16 rows collided in pairs -- though neither shows in the kernels' times)
 constexpr int kGqaKBytes = kGqaBlockTokens * kGqaKRow;
 constexpr int kGqaPBytes = kGqaHeads * kGqaBlockTokens * 2;
 constexpr int kGqaWaveBytes = kGqaKBytes + 2 * kGqaPBytes;
@@ -315,9 +318,10 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter &&
     // The 8 K-row loads and the 8 V-row loads of one 32-token block (8 KiB each per wave).
     // Statistics mode on a contiguous cache: a lane's 16-byte load of token n, channel chunk
     // 4 kk + rg IS its B operand of MFMA kk, so K needs no trip through LDS (a load instruction
-    // then covers 16 rows x 64 bytes instead of 4 whole rows; the byte counters show no extra
-    // traffic, and the block got about 1 % faster).  Without the non-temporal hint the same loads
-    // lost 10 %.
+    // then covers 16 rows x 64 bytes instead of 4 whole rows).  Measured on the 1M-token workload
+    // in one GPU session: statistics mode 618 -> 611 us; without the non-temporal hint the same
+    // loads lost 10 %.  The K-only modes, which keep two blocks of K in flight, lose with it
+    // (logits 442 -> 462 us, filter scan 326 -> 368 us) and keep the LDS path.
     constexpr bool kDirectK = MODE == kModeStats && !PAGED;
     const uint32_t lane_off_d = (uint32_t)n * row_b32 + (uint32_t)rg * 16u;   // direct K: token n of a half, chunk rg of a group of four
     const uint32_t last_row_off = (uint32_t)(t1 - 1 - t0) * row_b32;
@@ -526,7 +530,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter &&
                 }
             }
             if constexpr (kDirectK) {
-                if (tb_next < t1) load_k(tb_next, kreg, pg1);  // the operands are consumed: request the next block's
+                if (kAlwaysAhead || tb_next < t1) load_k(tb_next, kreg, pg1);  // the operands are consumed: request the next rows
             }
         }
 
