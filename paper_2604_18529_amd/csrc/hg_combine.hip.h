@@ -224,8 +224,13 @@ __global__ __launch_bounds__(kReduceBlock) void hg_concat_reduce_kernel(const Co
     const int stream = hk * a.ws.n_chunks + chunk;
     const int r0 = group_entry(a.groups, gi), r1 = group_entry(a.groups, gi + 1);
 
+    // A group of many ranges deals its ranges to the slices, a group of few ranges the records of
+    // each range (a range is cut into a handful of segments, a group into up to dozens of ranges:
+    // slices over the records of one range at a time left those ranges as one chain of dependent
+    // round trips).
+    const bool by_range = r1 - r0 >= S;
     float ot = 0.f;
-    for (int r = r0; r < r1; ++r) {
+    for (int r = r0 + (by_range ? sl : 0); r < r1; r += by_range ? S : 1) {
         const int pre0 = table_entry(a.tab, r).pre, pre1 = table_entry(a.tab, r + 1).pre;
         if (pre1 == pre0) continue;
         const int64_t p0 = (int64_t)stream * a.ws.ltok + pre0, p1 = (int64_t)stream * a.ws.ltok + pre1;
@@ -233,7 +238,7 @@ __global__ __launch_bounds__(kReduceBlock) void hg_concat_reduce_kernel(const Co
         const int n_rec = (int)((p1 - 1) / a.ws.span - w0) + 1;
         const int64_t rec0 = (w0 + (int64_t)stream * a.tab.n_ranges + r) * a.ws.gt + gl;
 #pragma unroll 4
-        for (int i = sl; i < n_rec; i += S) ot += a.ws_o[(rec0 + (int64_t)i * a.ws.gt) * D + c];
+        for (int i = by_range ? 0 : sl; i < n_rec; i += by_range ? 1 : S) ot += a.ws_o[(rec0 + (int64_t)i * a.ws.gt) * D + c];
     }
     s_o[sl][c] = ot;
     __syncthreads();

@@ -93,6 +93,27 @@ def test_every_kernel_instance(dtype, d, group):
     _run(w, what="%s d=%d G=%d" % (dtype, d, group))
 
 
+@pytest.mark.parametrize("dtype,d,hq,hkv", [("f16", 128, 3, 3), ("f16", 64, 2, 2), ("f32", 128, 8, 2), ("f16", 128, 16, 2), ("bf16", 128, 6, 1)],
+                         ids=["mha-f16-d128", "mha-f16-d64", "vector-kernel-4-heads", "matrix-core-8-heads", "matrix-core-6-heads-bf16"])
+@pytest.mark.parametrize("span", [0, 64, 50048])
+def test_logits_window_long_streams_many_ranges(dtype, d, hq, hkv, span):
+    """The logits are collected in an LDS window that is written out when full and runs on across
+    range boundaries: streams far longer than the window (32768 logits per head chunk in the vector
+    kernel, fewer with several heads; 1472-12160 tokens in the matrix-core kernel), cut into many
+    ragged ranges, under spans that start windows in the middle of a stream.  The output starts as
+    NaN, so a column that is never written, or written from a stale window, shows."""
+    spec = W.WorkloadSpec("window", 2, hq, hkv, d, dtype, 70000, 90000, "dirichlet", 23, seed=77 + hq + d)
+    w = W.make_workload(spec, DEV)
+    for ranges in (w.ranges, [r for i, r in enumerate(w.ranges) if i % 5 != 2][::-1]):  # tiling; with gaps, in reverse order
+        hg.hg_attn_set_span_tokens(span)
+        ltok = sum(e - b for (_, b, e) in ranges)
+        lg = torch.full((hq, ltok), float("nan"), dtype=torch.float32, device=DEV)
+        hg.hg_attn_logits(w.q, w.k, w.v, w.seq_lens, ranges, w.scale, logits=lg)
+        torch.cuda.synchronize()
+        assert not torch.isnan(lg).any()
+        _check_logits(w, ranges, lg)
+
+
 def test_concat_equals_statistics_route():
     """The paper's concatenate-then-softmax and the (m, l, O) merge are the same function."""
     spec = W.WorkloadSpec("same", 2, 8, 2, 128, "f16", 3000, 4000, "dirichlet", 6, seed=31)
