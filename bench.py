@@ -270,8 +270,7 @@ def _routes(w, spec, steps, warmup, torch, hg, W, binding, desc, packed, out, ls
                          "logits_bytes": Hq * ltok * 4,
                          "logits_gbps_on_k_bytes": k_bytes / (logits_ms * 1e-3) / 1e9,
                          "logits_gbps_on_bytes_moved": (k_bytes + Hq * ltok * 4) / (logits_ms * 1e-3) / 1e9,
-                         # hg_attn_concat reads the logits twice: once for the groups' maxima and sums, once with the V rows
-                         "concat_gbps_on_bytes_moved": (k_bytes + 2 * Hq * ltok * 4) / (concat_ms * 1e-3) / 1e9},
+                         "concat_gbps_on_bytes_moved": (k_bytes + Hq * ltok * 4) / (concat_ms * 1e-3) / 1e9},  # V + the logits
         "post_qk_route": {"offloaded_fraction": 0.8, "top_k": top_k, "topk_us": pq_topk_ms * 1e3, "us": pq_step_ms * 1e3},
         "pre_qk_route": {"offloaded_fraction": 0.8, "listed_tokens": top_k, "us": pre_step_ms * 1e3},
         "proxy_query": dict(proxy, offloaded_fraction=0.8),

@@ -187,7 +187,9 @@ hg_status hg_attn_logits(const hg_attn_desc *desc, const hg_range *ranges, int32
  * hg_attn_concat -- the paper-literal Token Concatenator (Section 4.2.3; Section 4.6 step 5):
  * the logits of a group's ranges are taken as ONE vector (they are adjacent columns of `logits`
  * because a group's ranges are consecutive table entries), ONE softmax is applied over it, and
- * the scores weight the V rows of those ranges.  Reads V and the logits; K and q are not read.
+ * the scores weight the V rows of those ranges.  Reads V and the logits, each once; K and q are
+ * not read.  (The softmax over the whole vector is evaluated piecewise with running maxima and an
+ * exact merge of the pieces, so the logits need no pass of their own.)
  *
  *   ranges     HOST  the table the logits were produced with (same order).
  *   logits     DEVICE [n_q_heads][ltok] fp32 as written by hg_attn_logits (or by any other

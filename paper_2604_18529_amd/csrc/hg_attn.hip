@@ -69,7 +69,7 @@ struct Plan {
     std::vector<RangeEntry> entries;  // n_ranges + 1 (sentinel)
     // workspace sections (byte offsets)
     size_t off_m = 0, off_l = 0, off_o = 0, off_tab = 0, total = 0;
-    size_t off_gs_m = 0, off_gs_l = 0, off_groups = 0;  // concat path only
+    size_t off_groups = 0;  // concat path only
 };
 
 constexpr int kMaxDevices = 64;
@@ -488,16 +488,11 @@ hg_status run(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, i
     return launch_status("segment reduce kernel");
 }
 
-// Workspace of hg_attn_concat: the streaming sections, then the group softmax partials and the
-// group table.
+// Workspace of hg_attn_concat: the streaming sections, then the group table.
 void add_concat_sections(Plan &p, int32_t n_groups, int32_t n_q_heads)
 {
+    (void)n_q_heads;
     size_t off = p.total;
-    const size_t gs = (size_t)n_groups * (size_t)n_q_heads * kConcatSlices * sizeof(float);
-    p.off_gs_m = off;
-    off += align_up(gs);
-    p.off_gs_l = off;
-    off += align_up(gs);
     p.off_groups = off;
     if (n_groups > kInlineGroups) off += align_up(((size_t)n_groups + 1) * sizeof(int32_t));
     p.total = off;
@@ -1202,8 +1197,6 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
     add_concat_sections(p, n_groups, desc->n_q_heads);
     st = check_workspace(workspace, ws_bytes, p.total);
     if (st != HG_OK) return st;
-    for (int32_t i = 0; i < n_groups; ++i)
-        for (int32_t r = group_ptr[i]; r < group_ptr[i + 1]; ++r) p.entries[r].grp = i;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     char *ws = static_cast<char *>(workspace);
 
@@ -1213,22 +1206,8 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
     if (st != HG_OK) return st;
     fill_stream_args(desc, p, ws, pa);
     pa.logits = const_cast<float *>(logits);
-    float *gs_m = reinterpret_cast<float *>(ws + p.off_gs_m), *gs_l = reinterpret_cast<float *>(ws + p.off_gs_l);
-    pa.gs_m = gs_m;
-    pa.gs_l = gs_l;
-
-    ConcatStatsArgs sa;
-    std::memset(&sa, 0, sizeof(sa));
-    st = stage_groups(group_ptr, n_groups, reinterpret_cast<int32_t *>(ws + p.off_groups), stream, sa.groups);
-    if (st != HG_OK) return st;
-    sa.logits = logits;
-    sa.gs_m = gs_m;
-    sa.gs_l = gs_l;
-    sa.ltok = p.ws.ltok;
-    sa.n_q_heads = desc->n_q_heads;
-    sa.tab = pa.tab;
-    HG_LAUNCH(hg_concat_stats_kernel, dim3(kConcatSlices, (unsigned)desc->n_q_heads, (unsigned)n_groups), dim3(256), stream, sa);
-    st = launch_status("concat stats kernel");
+    GroupTable groups;
+    st = stage_groups(group_ptr, n_groups, reinterpret_cast<int32_t *>(ws + p.off_groups), stream, groups);
     if (st != HG_OK) return st;
 
     if (p.n_workgroups > 0) {
@@ -1239,13 +1218,13 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
 
     ConcatReduceArgs ra;
     std::memset(&ra, 0, sizeof(ra));
+    ra.ws_m = pa.ws_m;
+    ra.ws_l = pa.ws_l;
     ra.ws_o = pa.ws_o;
-    ra.gs_m = gs_m;
-    ra.gs_l = gs_l;
     ra.out = out;
     ra.lse = lse_out;
     ra.ws = p.ws;
-    ra.groups = sa.groups;
+    ra.groups = groups;
     ra.tab = pa.tab;
     dim3 rgrid((unsigned)n_groups, (unsigned)desc->n_q_heads);
     if (desc->head_dim == 128)

@@ -1,5 +1,5 @@
-// Small combining kernels: segment reduce, exact merge, the concat path's statistics and reduce,
-// table uploads and the calibration copy.
+// Small combining kernels: segment reduce, exact merge, the concat path's reduce, table uploads
+// and the calibration kernels.
 #pragma once
 
 #include "hg_common.hip.h"
@@ -135,88 +135,16 @@ __global__ __launch_bounds__(kReduceBlock) void hg_merge_kernel(const MergeArgs 
 
 __device__ __forceinline__ int group_entry(const GroupTable &g, int i) { return g.ext ? g.ext[i] : g.inl[i]; }
 
-// Partial (max, sum of exp) of one slice of a group's logits row.  The ranges of a group are
-// consecutive table entries, so their logits are one contiguous piece [c0, c1) of the row: the
-// concatenation the paper describes is already how the logits are stored.
-// Grid (kConcatSlices, n_q_heads, n_groups), 256 threads.
-__global__ __launch_bounds__(256) void hg_concat_stats_kernel(const ConcatStatsArgs a)
-{
-    __shared__ float s_red[4];
-    const int z = blockIdx.x, h = blockIdx.y, gi = blockIdx.z;
-    const int c0 = table_entry(a.tab, group_entry(a.groups, gi)).pre;
-    const int c1 = table_entry(a.tab, group_entry(a.groups, gi + 1)).pre;
-    const int per = (c1 - c0 + kConcatSlices - 1) / kConcatSlices;
-    const int b = c0 + z * per < c1 ? c0 + z * per : c1;
-    const int e = b + per < c1 ? b + per : c1;
-    const float *row = a.logits + (int64_t)h * a.ltok;
-
-    // One pass: every thread folds its logits into a running (max, sum) pair.  Whole chunks of
-    // 4096 logits go four 16-byte loads per thread at a time (each load instruction of a wave is
-    // one contiguous KiB; the loads need 4-byte alignment only), sixteen values per rescale; the
-    // rest of the slice goes in groups of four with clamped single loads.
-    typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
-    float mx = kNegBig, lt = 0.f;
-    int i0 = b;
-    for (; i0 + 4096 <= e; i0 += 4096) {
-        f4u x[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) x[u] = *reinterpret_cast<const f4u *>(row + i0 + 4 * ((int)threadIdx.x + 256 * u));
-        float mn = mx;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                x[u][j] *= kLog2e;
-                mn = fmaxf(mn, x[u][j]);
-            }
-        }
-        float sum = 0.f;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) sum += (fast_exp2(x[u][0] - mn) + fast_exp2(x[u][1] - mn)) + (fast_exp2(x[u][2] - mn) + fast_exp2(x[u][3] - mn));
-        lt = lt * fast_exp2(mx - mn) + sum;
-        mx = mn;
-    }
-    for (int i = i0 + 4 * (int)threadIdx.x; i < e; i += 4 * 256) {
-        float x[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) x[j] = row[i + j < e ? i + j : e - 1] * kLog2e * 1.f;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) x[j] = i + j < e ? x[j] : kNegBig;
-        const float mn = fmaxf(fmaxf(mx, fmaxf(x[0], x[1])), fmaxf(x[2], x[3]));
-        lt = lt * fast_exp2(mx - mn) + ((fast_exp2(x[0] - mn) + fast_exp2(x[1] - mn)) + (fast_exp2(x[2] - mn) + fast_exp2(x[3] - mn)));
-        mx = mn;
-    }
-#pragma unroll
-    for (int step = 32; step >= 1; step >>= 1) {
-        const float mo = __shfl_xor(mx, step, 64), lo = __shfl_xor(lt, step, 64);
-        const float mn = fmaxf(mx, mo);
-        lt = lt * fast_exp2(mx - mn) + lo * fast_exp2(mo - mn);
-        mx = mn;
-    }
-    __shared__ float s_l[4];
-    if ((threadIdx.x & 63) == 0) {
-        s_red[threadIdx.x >> 6] = mx;
-        s_l[threadIdx.x >> 6] = lt;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const float M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
-        float L = 0.f;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) L += s_l[w] * fast_exp2(s_red[w] - M);
-        const int64_t idx = ((int64_t)gi * a.n_q_heads + h) * kConcatSlices + z;
-        a.gs_m[idx] = M;
-        a.gs_l[idx] = L;
-    }
-}
-
-// out[group][head] = (sum of the exp(s - M).v records of all segments of the group's ranges) / L,
-// lse = M + log L, with (M, L) the group's global softmax statistics.  Grid (n_groups, n_q_heads).
+// out[group][head] = exact merge of the (m, l, O) records of all segments of the group's ranges,
+// normalised; lse = M + log L.  The ranges of a group are consecutive table entries, so their
+// logits are one contiguous piece of the row: the concatenation the paper describes is how the
+// logits are stored, and merging the records of its pieces is the one softmax over it.
+// Grid (n_groups, n_q_heads).  A group of many ranges deals its ranges to the slices, a group of
+// few ranges the records of each range.
 template <int D>
 __global__ __launch_bounds__(kReduceBlock) void hg_concat_reduce_kernel(const ConcatReduceArgs a)
 {
     constexpr int S = kReduceBlock / D;
-    __shared__ float s_o[S][D];
     const int gi = blockIdx.x, h = blockIdx.y;
     const int c = threadIdx.x % D, sl = threadIdx.x / D;
     const int hk = h / a.ws.group, gidx = h - hk * a.ws.group;
@@ -224,12 +152,8 @@ __global__ __launch_bounds__(kReduceBlock) void hg_concat_reduce_kernel(const Co
     const int stream = hk * a.ws.n_chunks + chunk;
     const int r0 = group_entry(a.groups, gi), r1 = group_entry(a.groups, gi + 1);
 
-    // A group of many ranges deals its ranges to the slices, a group of few ranges the records of
-    // each range (a range is cut into a handful of segments, a group into up to dozens of ranges:
-    // slices over the records of one range at a time left those ranges as one chain of dependent
-    // round trips).
     const bool by_range = r1 - r0 >= S;
-    float ot = 0.f;
+    float mx = kNegBig, lt = 0.f, ot = 0.f;  // log2 units
     for (int r = r0 + (by_range ? sl : 0); r < r1; r += by_range ? S : 1) {
         const int pre0 = table_entry(a.tab, r).pre, pre1 = table_entry(a.tab, r + 1).pre;
         if (pre1 == pre0) continue;
@@ -238,24 +162,21 @@ __global__ __launch_bounds__(kReduceBlock) void hg_concat_reduce_kernel(const Co
         const int n_rec = (int)((p1 - 1) / a.ws.span - w0) + 1;
         const int64_t rec0 = (w0 + (int64_t)stream * a.tab.n_ranges + r) * a.ws.gt + gl;
 #pragma unroll 4
-        for (int i = by_range ? 0 : sl; i < n_rec; i += by_range ? 1 : S) ot += a.ws_o[(rec0 + (int64_t)i * a.ws.gt) * D + c];
+        for (int i = by_range ? 0 : sl; i < n_rec; i += by_range ? 1 : S) {
+            const int64_t th = rec0 + (int64_t)i * a.ws.gt;
+            const float mi = a.ws_m[th], li = a.ws_l[th], oi = a.ws_o[th * D + c];
+            const float mn = fmaxf(mx, mi);
+            const float wa = fast_exp2(mx - mn), wb = fast_exp2(mi - mn);
+            lt = lt * wa + li * wb;
+            ot = ot * wa + oi * wb;
+            mx = mn;
+        }
     }
-    s_o[sl][c] = ot;
-    __syncthreads();
-    if (sl != 0) return;
-    ot = 0.f;
-#pragma unroll
-    for (int i = 0; i < S; ++i) ot += s_o[i][c];
+    if (!combine_slices<D>(mx, lt, ot, c, sl)) return;
     const int64_t gh = (int64_t)gi * a.ws.n_q_heads + h;
-    float mx = kNegBig, lt = 0.f;  // the group's global maximum and sum of exp
-    for (int z = 0; z < kConcatSlices; ++z) {
-        const float mi = a.gs_m[gh * kConcatSlices + z], li = a.gs_l[gh * kConcatSlices + z];
-        const float mn = fmaxf(mx, mi);
-        lt = lt * fast_exp2(mx - mn) + li * fast_exp2(mi - mn);
-        mx = mn;
-    }
-    a.out[gh * D + c] = lt > 0.f ? ot / lt : 0.f;
-    if (c == 0 && a.lse) a.lse[gh] = lt > 0.f ? mx * kLn2 + logf(lt) : -INFINITY;
+    const bool empty = !(lt > 0.f);
+    a.out[gh * D + c] = empty ? 0.f : ot / lt;
+    if (c == 0 && a.lse) a.lse[gh] = empty ? -INFINITY : mx * kLn2 + logf(lt);
 }
 
 // ---- table upload (host tables reach the device through kernel arguments only) ----------------

@@ -10,7 +10,7 @@
 //   hg_combine.hip.h       hg_segment_reduce_kernel (segment records -> range triple or, for the
 //                          unsplit path, normalised output), hg_merge_kernel (exact recombination
 //                          of range triples: Section 4.2.3, Token Concatenator, in statistics
-//                          form), the concat path's statistics and reduce kernels, table uploads.
+//                          form), the concat path's reduce kernel, table uploads.
 //   hg_select.hip.h        hg_select_kernel: Post-QK^T top-k selection.
 //
 // Work distribution.  The tokens of all ranges, repeated for every stream (KV head x chunk of
@@ -60,18 +60,16 @@ constexpr float kLn2 = 0.6931471805599453f;
 // exp2(marker - marker) = 1 multiplies an all-zero state instead of producing NaN.
 constexpr float kNegBig = -3.0e38f;
 
-// pre = number of tokens in the ranges before this one (prefix sum of the range lengths);
-// grp = the concatenation group the range belongs to (used by the concat path only).
+// pre = number of tokens in the ranges before this one (prefix sum of the range lengths).
 struct RangeEntry {
-    int32_t seq, begin, end, pre, grp;
+    int32_t seq, begin, end, pre, pad;
 };
 
 // What a streaming kernel instance does with the rows it reads.
 constexpr int kModeStats = 0;   // K and V -> (m, l, O) records                     (hg_attn_partial / hg_attn_full)
 constexpr int kModeLogits = 1;  // K only  -> raw scaled logits                     (hg_attn_logits)
-constexpr int kModeConcat = 2;  // V and given logits + group softmax stats -> sum p.v records  (hg_attn_concat)
+constexpr int kModeConcat = 2;  // V and given logits -> (m, l, O) records over those logits     (hg_attn_concat)
 constexpr int kModeFilter = 3;  // K only  -> logits at or above a running lower bound of the k-th largest, densely (hg_attn_topk)
-constexpr int kConcatSlices = 32;  // partial (max, sum) records per (group, head) of the concat path
 
 // The range table travels by value in the kernel arguments when it is small; otherwise `ext`
 // points at a device copy.  Entry n_ranges is a sentinel whose pre is ltok.
@@ -122,7 +120,6 @@ struct PartialArgs {
     int32_t direct, normalise;
     float *out_m, *out_l, *out_o;
     float *logits;                         // [Hq][ltok]: written in logits mode, read in concat mode
-    const float *gs_m, *gs_l;              // concat mode: [n_groups][Hq][kConcatSlices] partial (max in log2 units, sum)
     // filter mode: every segment is cut into n_sub consecutive sub-spans (one per wave); the
     // survivors of sub-span j of head h -- logit and column, in ascending column order -- are
     // written to surv_val / surv_col [Hq][ltok] starting at the sub-span's own first column, and
@@ -180,17 +177,8 @@ struct MergeArgs {
     GroupTable tab_b;
 };
 
-struct ConcatStatsArgs {
-    const float *logits;  // [Hq][ltok], natural-log units
-    float *gs_m, *gs_l;   // [n_groups][Hq][kConcatSlices]
-    int32_t ltok, n_q_heads;
-    GroupTable groups;    // CSR over ranges
-    RangeTable tab;
-};
-
 struct ConcatReduceArgs {
-    const float *ws_o;        // segment records [slot][gt][D]: sums of p.v
-    const float *gs_m, *gs_l;
+    const float *ws_m, *ws_l, *ws_o;  // segment records over the given logits, m in log2 units
     float *out, *lse;
     WorkSplit ws;
     GroupTable groups;

@@ -257,15 +257,13 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter &&
         }
     }
 
-    // concat mode: global softmax maximum (log2 units) of this lane's head n, and its logits
-    // row (lrow[tok] is the logit of token tok)
-    float gmax = 0.f;
+    // concat mode: the logits row of this lane's head n (lrow[tok] is the logit of token tok), and
+    // the running maximum and sum of that head, in log2 units, kept in A-operand order (the four
+    // lanes of a head hold the same maximum and each its own part of the sum)
     const float *lrow = nullptr;
+    float m_a = kNegBig, l_a = 0.f;
     if constexpr (MODE == kModeConcat) {
         const int h = h0 + (n < nh ? n : 0);
-        const int64_t base = ((int64_t)e.grp * a.ws.n_q_heads + h) * kConcatSlices;
-        gmax = kNegBig;
-        for (int z = 0; z < kConcatSlices; ++z) gmax = fmaxf(gmax, a.gs_m[base + z]);
         lrow = a.logits + (int64_t)h * a.ws.ltok + (col0 - t0);
     }
 
@@ -273,7 +271,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter &&
     hg_f4 o[8];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        m[r] = MODE == kModeConcat ? 0.f : kNegBig;  // concat records are plain sums
+        m[r] = kNegBig;
         lsum[r] = 0.f;
     }
 #pragma unroll
@@ -804,10 +802,10 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter &&
         wave_lds_handover();  // the next block overwrites the K and P staging areas
     };
 
-    // Concat mode block: the numerators exp(s - M) of the ONE softmax over the group's concatenated
-    // logits come straight from memory in A-operand order (lane: head n, tokens tb + 8rg .. + 7);
-    // they lie in (0, 1], so the fp16 head + remainder keeps them to ~22 bits.  The division by the
-    // global sum happens once, in the reduce kernel.
+    // Concat mode block: the given logits come straight from memory in A-operand order (lane: head
+    // n, tokens tb + 8rg .. + 7) and take the place of q.k in an online softmax; the weights lie in
+    // (0, 1], so the fp16 head + remainder keeps them to ~22 bits.  The records of all segments of a
+    // group are merged exactly by the reduce kernel: the one softmax over the concatenated logits.
     // The 8 logits a lane needs for block tb are requested with the V rows of that block: two
     // 16-byte loads when the block is full (they need 4-byte alignment only), clamped single loads
     // in the last block of a segment.  The branch is wave-uniform, so neither side has to wait for
@@ -831,17 +829,40 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter &&
         }
     };
     auto concat_block = [&](int tb, int tb_next, hg_u32x4(&vreg)[8], float(&sv)[8]) __attribute__((always_inline)) {
+        // online softmax over the given logits, as in the statistics mode over q.k: a new maximum of
+        // some head (rare after the first blocks; a wave-uniform branch) rescales that head's sum and,
+        // through 64 bytes of LDS, its accumulators, which live in the lanes of the result tile
+        float sl[8], bm = -INFINITY;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int tok = tb + 8 * rg + x;
+            sl[x] = (tok < t1 && n < nh) ? sv[x] * kLog2e : -INFINITY;
+            bm = fmaxf(bm, sl[x]);
+        }
+        if (__builtin_amdgcn_ballot_w64(bm > m_a) != 0) {
+            bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
+            bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+            const float m_new = fmaxf(m_a, bm);
+            const float alpha = fast_exp2(m_a - m_new);
+            m_a = m_new;
+            l_a *= alpha;
+            float *al = reinterpret_cast<float *>(pls);  // (the P staging area is idle in this mode)
+            if (rg == 0) al[n] = alpha;
+            wave_lds_handover();
+            const hg_f4 a4 = *reinterpret_cast<const hg_f4 *>(al + 4 * rg);
+#pragma unroll
+            for (int nb = 0; nb < 8; ++nb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o[nb][r] *= a4[r];
+            wave_lds_handover();
+        }
         hg_u32x4 hi_raw, lo_raw;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-            float pj[2];
-#pragma unroll
-            for (int x = 0; x < 2; ++x) {
-                const int tok = tb + 8 * rg + 2 * jj + x;
-                pj[x] = fast_exp2(sv[2 * jj + x] * kLog2e - gmax) * ((tok < t1 && n < nh) ? 1.f : 0.f);
-            }
+            const float p0 = fast_exp2(sl[2 * jj] - m_a), p1 = fast_exp2(sl[2 * jj + 1] - m_a);
+            l_a += p0 + p1;
             uint32_t hi_w, lo_w;
-            split_weights<BF16>(pj[0], pj[1], hi_w, lo_w);
+            split_weights<BF16>(p0, p1, hi_w, lo_w);
             hi_raw[jj] = hi_w;
             lo_raw[jj] = lo_w;
         }
@@ -987,12 +1008,22 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter &&
     float(*sm)[kGqaHeads][D + 2] = reinterpret_cast<float(*)[kGqaHeads][D + 2]>(smem);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        const float lrow = row16_sum(lsum[r]);
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb) sm[wave][4 * rg + r][8 * n + nb] = o[nb][r];
-        if (n == 0) {
-            sm[wave][4 * rg + r][D] = m[r];
-            sm[wave][4 * rg + r][D + 1] = lrow;
+        if constexpr (MODE != kModeConcat) {
+            const float lrow = row16_sum(lsum[r]);
+            if (n == 0) {
+                sm[wave][4 * rg + r][D] = m[r];
+                sm[wave][4 * rg + r][D + 1] = lrow;
+            }
+        }
+    }
+    if constexpr (MODE == kModeConcat) {  // maximum and sum of head n sit in the four lanes of that head
+        float lt = l_a + __shfl_xor(l_a, 16, 64);
+        lt += __shfl_xor(lt, 32, 64);
+        if (rg == 0) {
+            sm[wave][n][D] = m_a;
+            sm[wave][n][D + 1] = lt;
         }
     }
     __syncthreads();

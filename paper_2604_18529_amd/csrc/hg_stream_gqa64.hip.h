@@ -62,14 +62,12 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         }
     }
 
-    // concat mode: global softmax maximum (log2 units) of this lane's head n, and its logits row
-    float gmax = 0.f;
+    // concat mode: the logits row of this lane's head n, and the running maximum and sum of that
+    // head (log2 units) in A-operand order, as in the head_dim 128 kernel
     const float *lrow = nullptr;
+    float m_a = kNegBig, l_a = 0.f;
     if constexpr (MODE == kModeConcat) {
         const int h = h0 + (n < nh ? n : 0);
-        const int64_t base = ((int64_t)e.grp * a.ws.n_q_heads + h) * kConcatSlices;
-        gmax = kNegBig;
-        for (int z = 0; z < kConcatSlices; ++z) gmax = fmaxf(gmax, a.gs_m[base + z]);
         lrow = a.logits + (int64_t)h * a.ws.ltok + (col0 - t0);
     }
 
@@ -77,7 +75,7 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     hg_f4 o[8];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        m[r] = MODE == kModeConcat ? 0.f : kNegBig;  // concat records are plain sums
+        m[r] = kNegBig;
         lsum[r] = 0.f;
     }
 #pragma unroll
@@ -270,8 +268,8 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         wave_lds_handover();  // the next block overwrites the K and P staging areas
     };
 
-    // Concat mode block: numerators exp(s - M) of the one softmax over the concatenated logits,
-    // read in A-operand order (lane: head n, tokens tb + 8rg .. + 7) as in the head_dim 128 kernel.
+    // Concat mode block: the given logits, read in A-operand order (lane: head n, tokens
+    // tb + 8rg .. + 7), take the place of q.k in an online softmax, as in the head_dim 128 kernel.
     // The 8 logits a lane needs for block tb (head n, tokens tb + 8rg .. + 7) are requested with the
     // V rows of that block, two 16-byte loads when the block is full (they need 4-byte alignment
     // only), clamped single loads in the last block of a segment.  The branch is wave-uniform, so
@@ -295,17 +293,38 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
         }
     };
     auto concat_block = [&](int tb, int tb_next, hg_u32x4(&vreg)[4], float(&sv)[8]) __attribute__((always_inline)) {
+        // online softmax over the given logits (see the head_dim 128 kernel)
+        float sl[8], bm = -INFINITY;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int tok = tb + 8 * rg + x;
+            sl[x] = (tok < t1 && n < nh) ? sv[x] * kLog2e : -INFINITY;
+            bm = fmaxf(bm, sl[x]);
+        }
+        if (__builtin_amdgcn_ballot_w64(bm > m_a) != 0) {
+            bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
+            bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+            const float m_new = fmaxf(m_a, bm);
+            const float alpha = fast_exp2(m_a - m_new);
+            m_a = m_new;
+            l_a *= alpha;
+            float *al = reinterpret_cast<float *>(pls);  // (the P staging area is idle in this mode)
+            if (rg == 0) al[n] = alpha;
+            wave_lds_handover();
+            const hg_f4 a4 = *reinterpret_cast<const hg_f4 *>(al + 4 * rg);
+#pragma unroll
+            for (int nb = 0; nb < 8; ++nb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o[nb][r] *= a4[r];
+            wave_lds_handover();
+        }
         hg_u32x4 hi_raw, lo_raw;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-            float pj[2];
-#pragma unroll
-            for (int x = 0; x < 2; ++x) {
-                const int tok = tb + 8 * rg + 2 * jj + x;
-                pj[x] = fast_exp2(sv[2 * jj + x] * kLog2e - gmax) * ((tok < t1 && n < nh) ? 1.f : 0.f);
-            }
+            const float p0 = fast_exp2(sl[2 * jj] - m_a), p1 = fast_exp2(sl[2 * jj + 1] - m_a);
+            l_a += p0 + p1;
             uint32_t hi_w, lo_w;
-            split_weights<BF16>(pj[0], pj[1], hi_w, lo_w);
+            split_weights<BF16>(p0, p1, hi_w, lo_w);
             hi_raw[jj] = hi_w;
             lo_raw[jj] = lo_w;
         }
@@ -393,15 +412,25 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 ? 2 : 1) void hg_partial_
     float(*sm)[kGqaHeads][D + 2] = reinterpret_cast<float(*)[kGqaHeads][D + 2]>(smem);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        const float lrow = row16_sum(lsum[r]);
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb) {
             const float both = o[nb][r] + __shfl_xor(o[nb][r], 8, 64);
             if (!odd) sm[wave][4 * rg + r][8 * n + nb] = both;
         }
-        if (n == 0) {
-            sm[wave][4 * rg + r][D] = m[r];
-            sm[wave][4 * rg + r][D + 1] = lrow;
+        if constexpr (MODE != kModeConcat) {
+            const float lrow = row16_sum(lsum[r]);
+            if (n == 0) {
+                sm[wave][4 * rg + r][D] = m[r];
+                sm[wave][4 * rg + r][D + 1] = lrow;
+            }
+        }
+    }
+    if constexpr (MODE == kModeConcat) {  // maximum and sum of head n sit in the four lanes of that head
+        float lt = l_a + __shfl_xor(l_a, 16, 64);
+        lt += __shfl_xor(lt, 32, 64);
+        if (rg == 0) {
+            sm[wave][n][D] = m_a;
+            sm[wave][n][D + 1] = lt;
         }
     }
     __syncthreads();

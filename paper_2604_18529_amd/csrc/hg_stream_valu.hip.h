@@ -27,16 +27,6 @@ __device__ __forceinline__ void merge_state(float &m, float &l, float *acc, floa
     for (int i = 0; i < N; ++i) acc[i] = acc[i] * wa + acc_b[i] * wb;
 }
 
-// Global softmax maximum (log2 units) of (concat group, query head) from the kConcatSlices
-// partial records.  Computed by one wave cooperatively.
-__device__ __forceinline__ float group_softmax_max(const float *gs_m, int64_t base, int lane)
-{
-    float m = lane < kConcatSlices ? gs_m[base + lane] : kNegBig;
-#pragma unroll
-    for (int step = 32; step >= 1; step >>= 1) m = fmaxf(m, __shfl_xor(m, step, 64));
-    return m;
-}
-
 // (One workgroup per compute unit is launched on long inputs, so the register allocator is told
 // that two waves per SIMD is all the occupancy this kernel wants.)
 // Logits mode.  Measured on MI355X, stores that trickle out next to a saturating read stream cost
@@ -163,23 +153,20 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
         }
     }
 
-    // concat mode: the group's global softmax maximum per head (the division by the global sum
-    // happens once, in the reduce kernel), and the logits rows
-    float gmax[GT];
+    // concat mode: the rows of the given logits (lrow[g][tok] is the logit of token tok)
     const float *lrow[GT];
     if constexpr (MODE == kModeConcat) {
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
             const int h = h0 + (g < nh ? g : 0);
-            gmax[g] = group_softmax_max(a.gs_m, ((int64_t)e.grp * a.ws.n_q_heads + h) * kConcatSlices, lane);
-            lrow[g] = a.logits + (int64_t)h * a.ws.ltok + (col0 - t0);  // lrow[g][tok] is the logit of token tok
+            lrow[g] = a.logits + (int64_t)h * a.ws.ltok + (col0 - t0);
         }
     }
 
     float m[GT], l[GT], acc[GT][EPL];
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
-        m[g] = MODE == kModeConcat ? 0.f : kNegBig;  // concat records are plain sums: equal maxima, weight 1
+        m[g] = kNegBig;
         l[g] = 0.f;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) acc[g][i] = 0.f;
@@ -286,6 +273,13 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
 
         // logits of the U tokens of this lane group, for every head of the chunk
         float s[GT][U];
+        if constexpr (MODE == kModeConcat) {
+            // the given logits take the place of q.k (natural-log units -> log2 units)
+#pragma unroll
+            for (int g = 0; g < GT; ++g)
+#pragma unroll
+                for (int u = 0; u < U; ++u) s[g][u] = valid[u] ? sv[g][u] * kLog2e : -INFINITY;
+        }
         if constexpr (MODE != kModeConcat) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -399,38 +393,24 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
 
         if constexpr (MODE != kModeLogits && MODE != kModeFilter) {
         float p[GT][U];
-        if constexpr (MODE == kModeStats) {
-            // online softmax update
+        // online softmax update (concat mode: over the given logits; the records of all segments of a
+        // group are merged exactly afterwards, which is the one softmax over the concatenated logits)
 #pragma unroll
-            for (int g = 0; g < GT; ++g) {
-                float mx = m[g];
+        for (int g = 0; g < GT; ++g) {
+            float mx = m[g];
 #pragma unroll
-                for (int u = 0; u < U; ++u) mx = fmaxf(mx, s[g][u]);
-                const float alpha = fast_exp2(m[g] - mx);
-                m[g] = mx;
-                float ls = 0.f;
+            for (int u = 0; u < U; ++u) mx = fmaxf(mx, s[g][u]);
+            const float alpha = fast_exp2(m[g] - mx);
+            m[g] = mx;
+            float ls = 0.f;
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    p[g][u] = fast_exp2(s[g][u] - mx);
-                    ls += p[g][u];
-                }
-                l[g] = l[g] * alpha + ls;
-#pragma unroll
-                for (int i = 0; i < EPL; ++i) acc[g][i] *= alpha;
+            for (int u = 0; u < U; ++u) {
+                p[g][u] = fast_exp2(s[g][u] - mx);
+                ls += p[g][u];
             }
-        } else {
-            // numerators exp(s - M) of the ONE softmax over the concatenated logits of the group
-            // (the mask is applied as a product so that every logit load stays unconditional)
+            l[g] = l[g] * alpha + ls;
 #pragma unroll
-            for (int g = 0; g < GT; ++g) {
-                float ls = 0.f;
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    p[g][u] = fast_exp2(sv[g][u] * kLog2e - gmax[g]) * (valid[u] ? 1.f : 0.f);
-                    ls += p[g][u];
-                }
-                l[g] += ls;
-            }
+            for (int i = 0; i < EPL; ++i) acc[g][i] *= alpha;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
