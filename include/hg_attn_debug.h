@@ -26,8 +26,11 @@ hg_status hg_attn_set_span_tokens(int32_t span_tokens);
  * least 128 tokens per kept token; with grouped queries it needs four or more query heads per
  * KV head and ranges long enough for several workgroups -- two for top_k <= 96, three for <= 144,
  * six for 256 -- to share each (range, KV head) pair),
- * 1 = the filtering scan wherever it exists, 2 = never.  The results are the same.  Process-wide;
- * not thread-safe against concurrent calls. */
+ * 1 = the filtering scan wherever it exists, 2 = never, 3 = as 1, but with the survivors gathered
+ * into dense lists and selected by the staged kernels (what the library does by itself only when
+ * the lists of a group do not fit the one-launch selection: very many ranges per group, groups
+ * beyond 2^20 tokens).  The results are the same.  Process-wide; not thread-safe against
+ * concurrent calls. */
 hg_status hg_attn_set_topk_mode(int32_t mode);
 
 /*

@@ -33,7 +33,7 @@ namespace {
 using namespace hg;
 
 int g_forced_span_tokens = 0;
-int g_topk_mode = 0;  // hg_attn_set_topk_mode: 0 = choose, 1 = filter scan wherever it exists, 2 = never
+int g_topk_mode = 0;  // hg_attn_set_topk_mode: 0 = choose, 1 = filter scan wherever it exists, 2 = never, 3 = as 1 with the staged selection behind it
 
 // Optional timing of the streaming kernel alone: event pairs recorded on the caller's stream
 // right around its launch (hg_attn_profile_start / hg_attn_profile_stop).
@@ -540,6 +540,7 @@ constexpr int kSelectMaxParts = 64;
 // arguments), then the candidate values and columns of the two-stage path.
 struct SelectPlan {
     int32_t parts = 1;
+    int64_t longest = 0;     // tokens of the longest group
     int32_t parts2 = 0;      // > 0: a middle stage reduces parts * top_k candidates to parts2 * top_k
     bool fast_first = true;  // fast path possible in the direct / candidates launch: top_k and elements per workgroup fit
     bool fast_final = true;  // the same for the launch that selects among the candidates
@@ -554,6 +555,7 @@ void select_parts(const hg_range *ranges, const int32_t *group_ptr, int32_t n_gr
         for (int32_t r = group_ptr[i]; r < group_ptr[i + 1]; ++r) n += ranges[r].end - ranges[r].begin;
         longest = std::max(longest, n);
     }
+    sp.longest = longest;
     sp.parts = (int32_t)std::min<int64_t>(kSelectMaxParts, std::max<int64_t>(1, (longest + kSelectRegTokens - 1) / kSelectRegTokens));
     sp.fast_first = top_k <= kSelectFastKeep && (longest + sp.parts - 1) / sp.parts <= kSelectRegTokens;
     // More candidates than one workgroup of the fast path holds: a middle stage brings them down to
@@ -623,11 +625,8 @@ void launch_select(const hg_attn_desc *desc, const SelectArgs &sa, dim3 grid, bo
         launch_select_variant<STAGE, false>(desc, sa, grid, stream);
 }
 
-// The launches of a selection whose tables (sa.tab, sa.groups) and input (sa.logits, or the dense
-// survivor lists sa.dense_*) are in place: one kernel for short groups, else candidates per part,
-// an optional middle stage, and the final selection among the candidates.
-hg_status select_stages(const hg_attn_desc *desc, const Plan &p, const SelectPlan &sp, SelectArgs &sa, int32_t n_groups,
-                        int32_t top_k, int32_t *sel, float *m, float *l, float *o, char *ws, hipStream_t stream)
+void fill_select_args(const hg_attn_desc *desc, const Plan &p, const SelectPlan &sp, SelectArgs &sa, int32_t top_k, int32_t *sel,
+                      float *m, float *l, float *o)
 {
     sa.v = desc->v;
     fill_pages(desc, sa.pages);
@@ -643,6 +642,15 @@ hg_status select_stages(const hg_attn_desc *desc, const Plan &p, const SelectPla
     sa.l = l;
     sa.o = o;
     sa.parts = sp.parts;
+}
+
+// The launches of a selection whose tables (sa.tab, sa.groups) and input (sa.logits, or the dense
+// survivor lists sa.dense_*) are in place: one kernel for short groups, else candidates per part,
+// an optional middle stage, and the final selection among the candidates.
+hg_status select_stages(const hg_attn_desc *desc, const Plan &p, const SelectPlan &sp, SelectArgs &sa, int32_t n_groups,
+                        int32_t top_k, int32_t *sel, float *m, float *l, float *o, char *ws, hipStream_t stream)
+{
+    fill_select_args(desc, p, sp, sa, top_k, sel, m, l, o);
     dim3 grid((unsigned)n_groups, (unsigned)desc->n_q_heads);
     if (sp.parts == 1) {
         launch_select<kSelectDirect>(desc, sa, grid, sp.fast_first, stream);
@@ -673,6 +681,34 @@ hg_status select_stages(const hg_attn_desc *desc, const Plan &p, const SelectPla
     }
     launch_select<kSelectFromCands>(desc, sa, grid, sp.fast_final, stream);
     return launch_status("selection kernel (final)");
+}
+
+// The selection behind a filter pass in one launch (sa.surv_*, sa.tail_*, sa.ws in place).
+hg_status select_survivors(const hg_attn_desc *desc, const Plan &p, const SelectPlan &sp, SelectArgs &sa, int32_t n_groups,
+                           int32_t top_k, int32_t *sel, float *m, float *l, float *o, char *ws, hipStream_t stream)
+{
+    fill_select_args(desc, p, sp, sa, top_k, sel, m, l, o);
+    if (sp.parts > 1) {
+        sa.cand_val = reinterpret_cast<float *>(ws + sp.off_cand_val);
+        sa.cand_col = reinterpret_cast<int32_t *>(ws + sp.off_cand_col);
+    }
+    const dim3 grid((unsigned)((int64_t)n_groups * desc->n_q_heads), (unsigned)sa.tail_parts), block(kSelectFastBlock);
+    if (desc->head_dim == 128) {
+        if (desc->dtype == HG_F16)
+            HG_LAUNCH((hg_select_survivors_kernel<Traits<128, kDtF16>>), grid, block, stream, sa);
+        else if (desc->dtype == HG_BF16)
+            HG_LAUNCH((hg_select_survivors_kernel<Traits<128, kDtBf16>>), grid, block, stream, sa);
+        else
+            HG_LAUNCH((hg_select_survivors_kernel<Traits<128, kDtF32>>), grid, block, stream, sa);
+    } else {
+        if (desc->dtype == HG_F16)
+            HG_LAUNCH((hg_select_survivors_kernel<Traits<64, kDtF16>>), grid, block, stream, sa);
+        else if (desc->dtype == HG_BF16)
+            HG_LAUNCH((hg_select_survivors_kernel<Traits<64, kDtBf16>>), grid, block, stream, sa);
+        else
+            HG_LAUNCH((hg_select_survivors_kernel<Traits<64, kDtF32>>), grid, block, stream, sa);
+    }
+    return launch_status("selection kernel (survivor lists)");
 }
 
 // hg_attn_topk: the scan that keeps only logits which can still be among a group's top_k (filter
@@ -716,7 +752,7 @@ constexpr int32_t kFilterMinQueryGroupGqa = 4;
 bool filter_chosen(const hg_attn_desc *d, int32_t top_k, const Plan &p, int32_t n_groups)
 {
     if (!filter_supported(d, top_k)) return false;
-    if (g_topk_mode == 1) return true;
+    if (g_topk_mode == 1 || g_topk_mode == 3) return true;
     const int64_t ltok = p.ws.ltok;
     if (!use_gqa_kernel(d)) return ltok >= kFilterMinTokensPerKeptValu * top_k * std::max<int32_t>(n_groups, 1);
     const int64_t n_ranges = std::max<int64_t>((int64_t)p.entries.size() - 1, 1);
@@ -737,6 +773,9 @@ static_assert(HG_FILTER_WG_PER_CU == 1, "with another value the plan of the two-
 
 struct TopkPlan {
     bool fused = false;
+    bool tail = false;      // fused: one selection kernel reads the filter pass's lists (else compaction + staged selection)
+    int32_t tail_parts = 1; // its workgroups per (group, head)
+    size_t off_tail_cnt = 0, n_tail = 0;
     int32_t n_sub = 0, chunks = 1;
     size_t off_logits = 0;  // unfused: all logits [Hq][ltok]
     size_t off_surv_val = 0, off_surv_col = 0, off_surv_cnt = 0, off_dense_val = 0, off_dense_col = 0, off_dense_cnt = 0;
@@ -745,7 +784,29 @@ struct TopkPlan {
     size_t total = 0;
 };
 
-TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, int32_t n_groups, int32_t top_k)
+// Whether hg_select_survivors_kernel can take the selection behind a filter pass: the items of
+// every (group, head) -- sub-span lists in column order; a range of n tokens lies in at most
+// (n - 1) / span + 2 workgroups' spans -- fit its table, the longest row fits its slices and the
+// candidates of all slices fit one fast-path workgroup.
+bool survivors_kernel_fits(const hg_range *ranges, const int32_t *group_ptr, int32_t n_groups, const Plan &p, const SelectPlan &sp,
+                           int32_t n_sub, int32_t top_k)
+{
+    if (top_k > kSelectFastKeep || (int64_t)sp.parts * top_k > kSelectRegTokens) return false;
+    if (sp.longest > (int64_t)sp.parts * kSelectRegTokens) return false;
+    if ((int64_t)n_groups * p.ws.n_q_heads > 0x7fffffff) return false;  // its grid: one column per (group, head)
+    for (int32_t i = 0; i < n_groups; ++i) {
+        int64_t items = 0;
+        for (int32_t r = group_ptr[i]; r < group_ptr[i + 1]; ++r) {
+            const int64_t n = ranges[r].end - ranges[r].begin;
+            if (n > 0) items += ((n - 1) / std::max<int32_t>(p.ws.span, 1) + 2) * n_sub;
+        }
+        if (items > kSurvivorItems) return false;
+    }
+    return true;
+}
+
+TopkPlan plan_topk(const hg_attn_desc *d, const hg_range *ranges, const int32_t *group_ptr, const Plan &p, const SelectPlan &sp,
+                   int32_t n_groups, int32_t top_k)
 {
     TopkPlan tp;
     tp.fused = filter_chosen(d, top_k, p, n_groups);
@@ -757,6 +818,9 @@ TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, i
     } else {
         tp.n_sub = filter_sub_spans(d);
         const int64_t pairs = std::max<int64_t>(1, (int64_t)n_groups * d->n_q_heads);
+        tp.tail = g_topk_mode != 3 && survivors_kernel_fits(ranges, group_ptr, n_groups, p, sp, tp.n_sub, top_k);
+        // as many workgroups per pair as fill the device about once (four fit a compute unit)
+        tp.tail_parts = (int32_t)std::min<int64_t>(sp.parts, std::max<int64_t>(1, 4 * (int64_t)compute_units() / pairs));
         // (every workgroup of a pair repeats the scan of the counts: up to 8 per pair, 512 in all,
         // measured against 1-64 per pair)
         tp.chunks = (int32_t)std::min<int64_t>(8, std::max<int64_t>(1, 512 / pairs));
@@ -764,10 +828,12 @@ TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, i
         off += rows;
         tp.off_surv_col = off;
         off += rows;
-        tp.off_dense_val = off;
-        off += rows;
-        tp.off_dense_col = off;
-        off += rows;
+        if (!tp.tail) {
+            tp.off_dense_val = off;
+            off += rows;
+            tp.off_dense_col = off;
+            off += rows;
+        }
         tp.n_counts = (size_t)p.n_slots * (size_t)tp.n_sub * (size_t)p.ws.gt;
         tp.n_bounds = (size_t)p.n_slots * (size_t)p.ws.gt * 64;
         tp.off_surv_cnt = off;
@@ -776,6 +842,9 @@ TopkPlan plan_topk(const hg_attn_desc *d, const Plan &p, const SelectPlan &sp, i
         off += align_up(tp.n_bounds * 4);
         tp.off_dense_cnt = off;
         off += align_up((size_t)std::max<int32_t>(n_groups, 1) * (size_t)d->n_q_heads * 4);
+        tp.n_tail = (size_t)std::max<int32_t>(n_groups, 1) * (size_t)d->n_q_heads;
+        tp.off_tail_cnt = off;
+        off += align_up(tp.n_tail * 4);
     }
     tp.total = off;
     return tp;
@@ -911,7 +980,7 @@ hg_status hg_attn_set_span_tokens(int32_t span_tokens)
 
 hg_status hg_attn_set_topk_mode(int32_t mode)
 {
-    if (mode < 0 || mode > 2) return HG_ERR_SHAPE;
+    if (mode < 0 || mode > 3) return HG_ERR_SHAPE;
     g_topk_mode = mode;
     return HG_OK;
 }
@@ -1299,7 +1368,7 @@ hg_status hg_attn_topk_workspace_size(const hg_attn_desc *desc, const hg_range *
     st = make_plan(desc, ranges, n_ranges, p, topk_workgroups_per_cu(desc, top_k));
     if (st != HG_OK) return st;
     const SelectPlan sp = plan_select(ranges, n_ranges, group_ptr, n_groups, desc->n_q_heads, top_k);
-    *bytes = plan_topk(desc, p, sp, n_groups, top_k).total;
+    *bytes = plan_topk(desc, ranges, group_ptr, p, sp, n_groups, top_k).total;
     return HG_OK;
 }
 
@@ -1321,7 +1390,7 @@ hg_status hg_attn_topk(const hg_attn_desc *desc, const hg_range *ranges, int32_t
     if (st != HG_OK) return st;
     const SelectPlan sp = plan_select(ranges, n_ranges, group_ptr, n_groups, desc->n_q_heads, top_k);
     if ((int64_t)n_groups * sp.parts > 0x7fffffff) return HG_ERR_SHAPE;
-    const TopkPlan tp = plan_topk(desc, p, sp, n_groups, top_k);
+    const TopkPlan tp = plan_topk(desc, ranges, group_ptr, p, sp, n_groups, top_k);
     st = check_workspace(workspace, ws_bytes, tp.total);
     if (st != HG_OK) return st;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
@@ -1362,6 +1431,8 @@ hg_status hg_attn_topk(const hg_attn_desc *desc, const hg_range *ranges, int32_t
     pa.filter_rank = (top_k + filter_sets(desc) - 1) / filter_sets(desc) - 1;  // every set keeps rank + 1 logits
     pa.filter_k = top_k;
     pa.gbound = reinterpret_cast<uint32_t *>(ws + tp.off_gbound);
+    pa.tail_cnt = reinterpret_cast<uint32_t *>(ws + tp.off_tail_cnt);
+    pa.n_tail = tp.tail ? (int64_t)tp.n_tail : 0;
     if (p.n_workgroups > 0) {
         if (use_gqa_kernel(desc)) {  // (the vector kernel shares no bounds)
             const unsigned fill_blocks = (unsigned)std::min<size_t>(1024, (tp.n_bounds + 255) / 256);
@@ -1370,6 +1441,16 @@ hg_status hg_attn_topk(const hg_attn_desc *desc, const hg_range *ranges, int32_t
         launch_filter(desc, pa, sgrid, stream);
         st = launch_status("filter kernel");
         if (st != HG_OK) return st;
+    }
+    if (tp.tail) {
+        sa.surv_val = pa.surv_val;
+        sa.surv_col = pa.surv_col;
+        sa.surv_cnt = pa.surv_cnt;
+        sa.tail_cnt = pa.tail_cnt;
+        sa.n_sub = tp.n_sub;
+        sa.tail_parts = tp.tail_parts;
+        sa.ws = p.ws;
+        return select_survivors(desc, p, sp, sa, n_groups, top_k, sel, m, l, o, ws, stream);
     }
     CompactArgs ca;
     std::memset(&ca, 0, sizeof(ca));

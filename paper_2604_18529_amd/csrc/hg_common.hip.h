@@ -132,6 +132,10 @@ struct PartialArgs {
     // 0 (below every key) before the launch.  An entry is what its workgroup has published so far
     // (see the filter mode).
     uint32_t *gbound;
+    // filter mode: words the first workgroup sets to zero for the selection that follows the scan
+    // (its count of finished workgroups per (group, head))
+    uint32_t *tail_cnt;
+    int64_t n_tail;
     WorkSplit ws;
     RangeTable tab;
 };
@@ -216,6 +220,14 @@ struct SelectArgs {
     // entries is selected by the one-workgroup stage (launched first) and skipped by the staged
     // kernels; a longer list the other way round.  0: no such split.
     int32_t direct_limit, pad3;
+    // hg_select_survivors_kernel: the filter pass's own lists (see PartialArgs), the split they were
+    // written under, the workgroups per (group, head) of this launch and their count of finished
+    // ones (zero at the start)
+    const float *surv_val;
+    const int32_t *surv_col, *surv_cnt;
+    uint32_t *tail_cnt;
+    int32_t n_sub, tail_parts;
+    WorkSplit ws;
     GroupTable groups;
     RangeTable tab;
 };

@@ -86,11 +86,11 @@ __device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t v)
     return inc - v;
 }
 
-// Fast path of steps 1-2 (see the top of the file).  row[0..n) with n <= kSelectRegTokens and
-// keep <= kSelectFastKeep.  On success the kept columns (ascending) and logits are in s_cols /
-// s_vals and the function returns true; otherwise nothing has been decided and the caller runs
-// the radix passes over the row.  The return value is uniform; every thread of the workgroup
-// must call it.
+// Fast path of steps 1-2 (see the top of the file) with R elements per thread: a row of
+// n <= R * kSelectFastBlock elements, keep <= kSelectFastKeep.  On success the kept elements'
+// places in the row (ascending) and their logits are in s_cols / s_vals and the function returns
+// true; otherwise nothing has been decided and the caller runs the radix passes over the row.
+// The return value is uniform; every thread of the workgroup must call it.
 struct SelectFastLds {
     uint32_t cand[kSelectCandCap];                           // keys of the elements at or above the bound
     uint32_t cnt[kSelectRegs * (kSelectFastBlock / 64)];     // kept elements per (e, wave), then their scan
@@ -100,17 +100,31 @@ struct SelectFastLds {
     uint32_t count;
 };
 
-__device__ __forceinline__ bool select_fast(const float *__restrict__ row, int n, int keep, const int32_t *col_map,
-                                            int col_base, SelectFastLds &f, int32_t *s_cols, float *s_vals)
+// The row a selection reads from: val(i) is element i.
+// gather(x, n) loads the elements of the fast path's thread: x[e] = element e * BLOCK + tid, the
+// row's last element in the slots past its end.
+struct RowDirect {
+    const float *row;
+    __device__ __forceinline__ float operator()(int i) const { return row[i]; }
+    template <int R, int BLOCK>
+    __device__ __forceinline__ void gather(float (&x)[R], int n) const
+    {
+#pragma unroll
+        for (int e = 0; e < R; ++e) {
+            const int i = e * BLOCK + (int)threadIdx.x;
+            x[e] = row[i < n ? i : n - 1];
+        }
+    }
+};
+
+template <int R, typename ROW>
+__device__ __forceinline__ bool select_fast_r(const ROW &val, int n, int keep, SelectFastLds &f, int32_t *s_cols, float *s_vals)
 {
-    constexpr int BLOCK = kSelectFastBlock, NW = BLOCK / 64, R = kSelectRegs, G = kSelectSubMax;
+    constexpr int BLOCK = kSelectFastBlock, NW = BLOCK / 64, G = kSelectSubMax;
+    static_assert(R <= kSelectRegs && R % G == 0 && (R * NW) % 64 == 0, "elements per thread");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float x[R];
-#pragma unroll
-    for (int e = 0; e < R; ++e) {
-        const int i = e * BLOCK + tid;
-        x[e] = row[i < n ? i : n - 1];
-    }
+    val.template gather<R, BLOCK>(x, n);
     if (tid == 0) f.count = 0u;
     if (tid < 256) f.hist[0][tid] = 0u;
     if (tid < R * NW) f.cnt[tid] = 0u;  // most (e, wave) rows will hold nothing at or above T
@@ -259,18 +273,18 @@ __device__ __forceinline__ bool select_fast(const float *__restrict__ row, int n
         }
     }
     __syncthreads();
-    if (wave == 0) {  // exclusive scan of the R * NW = 256 counts, 4 per lane
-        static_assert(R * NW == 256, "four counts per lane of one wave");
-        uint32_t c4[4], mine4 = 0;
+    if (wave == 0) {  // exclusive scan of the R * NW counts, PER per lane
+        constexpr int PER = R * NW / 64;
+        uint32_t c4[PER], mine4 = 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            c4[j] = f.cnt[4 * lane + j];
+        for (int j = 0; j < PER; ++j) {
+            c4[j] = f.cnt[PER * lane + j];
             mine4 += c4[j];
         }
         uint32_t before = wave_exclusive_scan(mine4);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            f.cnt[4 * lane + j] = before;
+        for (int j = 0; j < PER; ++j) {
+            f.cnt[PER * lane + j] = before;
             before += c4[j];
         }
     }
@@ -286,8 +300,7 @@ __device__ __forceinline__ bool select_fast(const float *__restrict__ row, int n
             const uint32_t eq_before = (base >> 16) + (uint32_t)__builtin_popcountll(be & below);
             if (gt || (eq && eq_before < k_eq)) {
                 const uint32_t pos = gt_before + (eq_before < k_eq ? eq_before : k_eq);
-                const int i = e * BLOCK + tid;
-                s_cols[pos] = col_map ? col_map[i] : col_base + i;
+                s_cols[pos] = e * BLOCK + tid;
                 s_vals[pos] = x[e];
             }
         }
@@ -296,17 +309,247 @@ __device__ __forceinline__ bool select_fast(const float *__restrict__ row, int n
     return true;
 }
 
+template <typename ROW>
+__device__ __forceinline__ bool select_fast(const ROW &val, int n, int keep, SelectFastLds &f, int32_t *s_cols, float *s_vals)
+{
+    return select_fast_r<kSelectRegs>(val, n, keep, f, s_cols, s_vals);
+}
+
+// The same with half the elements per thread for rows of at most half the capacity -- what a
+// filter pass usually leaves of a million tokens: every step is a loop over a thread's elements.
+template <typename ROW>
+__device__ __forceinline__ bool select_fast_by_length(const ROW &val, int n, int keep, SelectFastLds &f, int32_t *s_cols, float *s_vals)
+{
+    if (n <= kSelectRegTokens / 2) return select_fast_r<kSelectRegs / 2>(val, n, keep, f, s_cols, s_vals);
+    return select_fast_r<kSelectRegs>(val, n, keep, f, s_cols, s_vals);
+}
+
+// Steps 1-2 by radix passes over the row (any n, any keep <= kMaxTopK): the kept elements' places
+// in the row (ascending) and their logits go to s_cols / s_vals.  Every thread of the workgroup
+// must call it.
+struct SelectRadixLds {
+    uint32_t hist[256];
+    uint32_t wave[kSelectBlock / 64];
+    uint32_t prefix, krem;
+};
+
+template <int BLOCK, typename ROW>
+__device__ __forceinline__ void select_radix(const ROW &val, int n, int keep, SelectRadixLds &rl, int32_t *s_cols, float *s_vals)
+{
+    const int tid = threadIdx.x;
+    // 1. radix select
+    uint32_t prefix = 0, mask = 0, krem = (uint32_t)keep;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) rl.hist[tid] = 0;
+        __syncthreads();
+        for (int i0 = 0; i0 < n; i0 += 8 * BLOCK) {  // eight loads in flight per thread
+            float x[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int i = i0 + j * BLOCK + tid;
+                x[j] = val(i < n ? i : n - 1);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t u = order_key(x[j]);
+                if (i0 + j * BLOCK + tid < n && (u & mask) == prefix) atomicAdd(&rl.hist[(u >> shift) & 255u], 1u);
+            }
+        }
+        __syncthreads();
+        // the digit d with  #(digits > d) < krem <= #(digits >= d):  scan the bins from the top
+        {
+            const uint32_t cnt = tid < 256 ? rl.hist[255 - tid] : 0u;
+            uint32_t total;
+            const uint32_t above = block_exclusive_scan<BLOCK>(cnt, rl.wave, total);
+            if (tid < 256 && above < krem && above + cnt >= krem) {
+                rl.prefix = prefix | ((uint32_t)(255 - tid) << shift);
+                rl.krem = krem - above;
+            }
+        }
+        __syncthreads();
+        prefix = rl.prefix;
+        krem = rl.krem;
+        mask |= 0xffu << shift;
+    }
+    const uint32_t T = prefix, k_eq = krem;  // keep every key > T and the first k_eq keys == T
+
+    // 2. ordered compaction of the kept elements; every thread owns kRun consecutive elements of a
+    //    chunk, so one block scan serves kRun * BLOCK elements
+    constexpr int kRun = 8;
+    uint32_t run_gt = 0, run_eq = 0;
+    for (int base = 0; base < n; base += kRun * BLOCK) {
+        const int i0 = base + kRun * tid;
+        float x[kRun];
+        uint32_t cnt = 0;  // low half: keys > T, high half: keys == T
+#pragma unroll
+        for (int j = 0; j < kRun; ++j) {
+            x[j] = val(i0 + j < n ? i0 + j : n - 1);
+            const uint32_t u = order_key(x[j]);
+            if (i0 + j < n) cnt += (u > T ? 1u : 0u) + (u == T ? 0x10000u : 0u);
+        }
+        uint32_t total;
+        const uint32_t scan = block_exclusive_scan<BLOCK>(cnt, rl.wave, total);
+        uint32_t gt_before = run_gt + (scan & 0xffffu), eq_before = run_eq + (scan >> 16);
+#pragma unroll
+        for (int j = 0; j < kRun; ++j) {
+            const uint32_t u = order_key(x[j]);
+            const bool in = i0 + j < n, gt = in && u > T, eq = in && u == T;
+            if (gt || (eq && eq_before < k_eq)) {
+                const uint32_t pos = gt_before + (eq_before < k_eq ? eq_before : k_eq);
+                s_cols[pos] = i0 + j;
+                s_vals[pos] = x[j];
+            }
+            gt_before += gt ? 1u : 0u;
+            eq_before += eq ? 1u : 0u;
+        }
+        run_gt += total & 0xffffu;
+        run_eq += total >> 16;
+    }
+    __syncthreads();
+}
+
+// Step 3: the kept logits s_vals[0..keep) with their logits columns s_cols[0..keep) (keep >= 1,
+// ascending columns, every thread having written the entries j = tid, tid + BLOCK, ... itself or
+// a barrier having passed since) are folded with their V rows into the triple of (group, head)
+// pair gh; the kept tokens go to a.sel.  s_red: BLOCK / 64 floats, s_acc: BLOCK / 64 rows of D.
+template <typename TR, int BLOCK>
+__device__ __forceinline__ void fold_kept(const SelectArgs &a, int64_t gh, int h, int r0, int r1, int keep, int32_t *s_cols,
+                                          float *s_vals, float *s_red, float (*s_acc)[TR::D])
+{
+    constexpr int D = TR::D, EPL = TR::EPL, NV = TR::NV, EPV = TR::EPV, ES = TR::ES, NW = BLOCK / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // 3a. m = max kept logit; weights; l
+    float mx = -INFINITY;
+    for (int j = tid; j < keep; j += BLOCK) mx = fmaxf(mx, s_vals[j]);
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1) mx = fmaxf(mx, __shfl_xor(mx, step, 64));
+    if (lane == 0) s_red[wave] = mx;
+    __syncthreads();
+    mx = s_red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) mx = fmaxf(mx, s_red[w]);
+    __syncthreads();
+    float lt = 0.f;
+    const int seq = table_entry(a.tab, r0).seq;
+    for (int j = tid; j < keep; j += BLOCK) {
+        const float w = fast_exp2((s_vals[j] - mx) * kLog2e);
+        lt += w;
+        // column -> token position: the range of the group that holds the column
+        const int col = s_cols[j];
+        int lo = r0, hi = r1;  // pre[lo] <= col < pre[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (table_entry(a.tab, mid).pre <= col)
+                lo = mid;
+            else
+                hi = mid;
+        }
+        const RangeEntry e = table_entry(a.tab, lo);
+        const int tok = e.begin + (col - e.pre);
+        s_cols[j] = tok;
+        s_vals[j] = w;
+        if (a.sel) a.sel[gh * a.top_k + j] = tok;
+    }
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1) lt += __shfl_xor(lt, step, 64);
+    if (lane == 0) s_red[wave] = lt;
+    __syncthreads();
+    lt = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) lt += s_red[w];
+
+    // 3b. gather the kept V rows: lane group grp of wave `wave` takes kept entries
+    //     RPW * wave + grp, + RPW * NW, ...
+    constexpr int LPR = TR::LPR, RPW = TR::RPW;
+    const int sub = lane % LPR, grp = lane / LPR;
+    const int hk = h / a.group;
+    // contiguous cache: the (sequence, KV head) slab; paged cache: the head's offset inside a block
+    const bool paged = a.pages.table != nullptr;
+    const char *vbase = static_cast<const char *>(a.v) + ((paged ? 0 : (int64_t)seq * a.stride_b) + (int64_t)hk * a.stride_h) * ES;
+    const int64_t row_bytes = a.stride_t * ES;
+    const int32_t *table = paged ? a.pages.table + (int64_t)seq * a.pages.max_blocks : nullptr;
+    float acc[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+    // (four rows per lane group in flight: the rows are scattered over the cache, every load is a
+    // full memory latency, and with top_k = 128 the 8 waves need four rounds)
+    constexpr int kRowsAhead = 4;
+    for (int j0 = RPW * wave + grp; j0 < keep; j0 += kRowsAhead * RPW * NW) {
+        typename TR::Raw raw[kRowsAhead][NV];
+        float w[kRowsAhead];
+#pragma unroll
+        for (int u = 0; u < kRowsAhead; ++u) {
+            const int j = j0 + u * RPW * NW;
+            const bool ok = j < keep;
+            w[u] = ok ? s_vals[j] : -1.f;  // (an entry past the end re-reads the first row and is not added; real weights are >= 0)
+            const int tok = s_cols[ok ? j : j0];
+            const char *vrow = paged ? vbase + paged_row_offset(table[tok >> a.pages.shift], tok, a.pages.mask, (uint32_t)(a.stride_b * ES), (uint32_t)row_bytes)
+                                     : vbase + (int64_t)tok * row_bytes;
+#pragma unroll
+            for (int jj = 0; jj < NV; ++jj) raw[u][jj] = TR::template load<false>(vrow, sub, jj);
+        }
+#pragma unroll
+        for (int u = 0; u < kRowsAhead; ++u) {
+            float vf[EPL];
+#pragma unroll
+            for (int jj = 0; jj < NV; ++jj) TR::widen(raw[u][jj], &vf[jj * EPV]);
+            if (w[u] >= 0.f) {
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) acc[i] = fmaf(w[u], vf[i], acc[i]);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+#pragma unroll
+        for (int step = LPR; step <= 32; step <<= 1) acc[i] += __shfl_xor(acc[i], step, 64);
+    }
+    if (grp == 0) {
+#pragma unroll
+        for (int jj = 0; jj < NV; ++jj)
+#pragma unroll
+            for (int i = 0; i < EPV; ++i) s_acc[wave][TR::vec_offset(sub, jj) + i] = acc[jj * EPV + i];
+    }
+    __syncthreads();
+    if (tid < D) {
+        float ot = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) ot += s_acc[w][tid];
+        a.o[gh * D + tid] = ot;
+    }
+    if (tid == 0) {
+        a.m[gh] = mx;
+        a.l[gh] = lt;
+    }
+}
+
+// The triple of a (group, head) pair with nothing to select from, and its list of kept tokens.
+template <int D, int BLOCK>
+__device__ __forceinline__ void write_empty_selection(const SelectArgs &a, int64_t gh)
+{
+    const int tid = threadIdx.x;
+    if (a.sel)
+        for (int j = tid; j < a.top_k; j += BLOCK) a.sel[gh * a.top_k + j] = -1;
+    if (tid < D) a.o[gh * D + tid] = 0.f;
+    if (tid == 0) {
+        a.m[gh] = -INFINITY;
+        a.l[gh] = 0.f;
+    }
+}
+
+// A pad of a candidate slot is the NaN with every bit set: its key is 0, below -inf, and it fails
+// every float comparison, so no stage ever prefers it to a real logit, masked (-inf) ones included.
+__device__ __forceinline__ float candidate_pad() { return __uint_as_float(0xffffffffu); }
+
 template <typename TR, int STAGE, bool FAST>
 __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_select_kernel(const SelectArgs a)
 {
-    constexpr int D = TR::D, EPL = TR::EPL, NV = TR::NV, EPV = TR::EPV, ES = TR::ES;
+    constexpr int D = TR::D;
     constexpr int BLOCK = FAST ? kSelectFastBlock : kSelectBlock;
     constexpr int KEEP_CAP = FAST ? kSelectFastKeep : kMaxTopK;  // the host picks FAST variants for top_k <= kSelectFastKeep only
     constexpr int NW = BLOCK / 64;
-    __shared__ uint32_t s_hist[256];
-    __shared__ uint32_t s_wave[NW];
-    __shared__ uint32_t s_prefix, s_krem;
-    __shared__ int32_t s_cols[KEEP_CAP];   // kept columns, later their token positions
+    __shared__ SelectRadixLds s_radix;
+    __shared__ int32_t s_cols[KEEP_CAP];   // kept elements' places in the row, then their columns, then their token positions
     __shared__ float s_vals[KEEP_CAP];     // kept logits, later their weights
     __shared__ float s_red[NW];
     __shared__ float s_acc[NW][D];
@@ -317,7 +560,6 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
     const int n_parts = STAGE == kSelectCandidates ? a.parts : STAGE == kSelectMidCands ? a.parts2 : 1;
     const int gi = blockIdx.x / n_parts;
     const int part = blockIdx.x - gi * n_parts;
-    const int lane = tid & 63, wave = tid >> 6;
     const int r0 = group_entry(a.groups, gi), r1 = group_entry(a.groups, gi + 1);
     const int c0 = table_entry(a.tab, r0).pre, c1 = table_entry(a.tab, r1).pre;
     const int64_t gh = (int64_t)gi * a.n_q_heads + h;
@@ -373,103 +615,35 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
     float *const out_val = STAGE == kSelectMidCands ? a.cand2_val : a.cand_val;
     int32_t *const out_col = STAGE == kSelectMidCands ? a.cand2_col : a.cand_col;
     if constexpr (kEmits) {
-        // pad the part's candidate slots; the kept ones are overwritten below.  A pad is the NaN
-        // with every bit set: its key is 0, below -inf, and it fails every float comparison, so no
-        // stage ever prefers it to a real logit, masked (-inf) ones included.
+        // pad the part's candidate slots; the kept ones are overwritten below
         const int64_t base = (gh * n_parts + part) * (int64_t)a.top_k;
         for (int j = tid + keep; j < a.top_k; j += BLOCK) {
-            out_val[base + j] = __uint_as_float(0xffffffffu);
+            out_val[base + j] = candidate_pad();
             out_col[base + j] = 0;
         }
         if (n == 0) return;
     } else {
-        if (a.sel)
-            for (int j = tid + keep; j < a.top_k; j += BLOCK) a.sel[gh * a.top_k + j] = -1;
         if (n == 0) {
-            if (tid < D) a.o[gh * D + tid] = 0.f;
-            if (tid == 0) {
-                a.m[gh] = -INFINITY;
-                a.l[gh] = 0.f;
-            }
+            write_empty_selection<D, BLOCK>(a, gh);
             return;
         }
+        if (a.sel)
+            for (int j = tid + keep; j < a.top_k; j += BLOCK) a.sel[gh * a.top_k + j] = -1;
     }
 
     // the host launches a FAST variant only when every workgroup has n <= kSelectRegTokens
+    const RowDirect val{row};
     bool decided = false;
     if constexpr (FAST) {
-        if (keep <= kSelectFastKeep) decided = select_fast(row, n, keep, col_map, col_base, *reinterpret_cast<SelectFastLds *>(s_fast_raw), s_cols, s_vals);
+        if (keep <= kSelectFastKeep) decided = select_fast(val, n, keep, *reinterpret_cast<SelectFastLds *>(s_fast_raw), s_cols, s_vals);
     }
-    if (!decided) {
-        // 1. radix select
-        uint32_t prefix = 0, mask = 0, krem = (uint32_t)keep;
-        for (int shift = 24; shift >= 0; shift -= 8) {
-            if (tid < 256) s_hist[tid] = 0;
-            __syncthreads();
-            for (int i0 = 0; i0 < n; i0 += 8 * BLOCK) {  // eight loads in flight per thread
-                float x[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int i = i0 + j * BLOCK + tid;
-                    x[j] = row[i < n ? i : n - 1];
-                }
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint32_t u = order_key(x[j]);
-                    if (i0 + j * BLOCK + tid < n && (u & mask) == prefix) atomicAdd(&s_hist[(u >> shift) & 255u], 1u);
-                }
-            }
-            __syncthreads();
-            // the digit d with  #(digits > d) < krem <= #(digits >= d):  scan the bins from the top
-            {
-                const uint32_t cnt = tid < 256 ? s_hist[255 - tid] : 0u;
-                uint32_t total;
-                const uint32_t above = block_exclusive_scan<BLOCK>(cnt, s_wave, total);
-                if (tid < 256 && above < krem && above + cnt >= krem) {
-                    s_prefix = prefix | ((uint32_t)(255 - tid) << shift);
-                    s_krem = krem - above;
-                }
-            }
-            __syncthreads();
-            prefix = s_prefix;
-            krem = s_krem;
-            mask |= 0xffu << shift;
-        }
-        const uint32_t T = prefix, k_eq = krem;  // keep every key > T and the first k_eq keys == T
-
-        // 2. ordered compaction of the kept columns; every thread owns kRun consecutive columns of a
-        //    chunk, so one block scan serves kRun * 1024 elements
-        constexpr int kRun = 8;
-        uint32_t run_gt = 0, run_eq = 0;
-        for (int base = 0; base < n; base += kRun * BLOCK) {
-            const int i0 = base + kRun * tid;
-            float x[kRun];
-            uint32_t cnt = 0;  // low half: keys > T, high half: keys == T
-#pragma unroll
-            for (int j = 0; j < kRun; ++j) {
-                x[j] = row[i0 + j < n ? i0 + j : n - 1];
-                const uint32_t u = order_key(x[j]);
-                if (i0 + j < n) cnt += (u > T ? 1u : 0u) + (u == T ? 0x10000u : 0u);
-            }
-            uint32_t total;
-            const uint32_t scan = block_exclusive_scan<BLOCK>(cnt, s_wave, total);
-            uint32_t gt_before = run_gt + (scan & 0xffffu), eq_before = run_eq + (scan >> 16);
-#pragma unroll
-            for (int j = 0; j < kRun; ++j) {
-                const uint32_t u = order_key(x[j]);
-                const bool in = i0 + j < n, gt = in && u > T, eq = in && u == T;
-                if (gt || (eq && eq_before < k_eq)) {
-                    const uint32_t pos = gt_before + (eq_before < k_eq ? eq_before : k_eq);
-                    s_cols[pos] = col_map ? col_map[i0 + j] : col_base + i0 + j;
-                    s_vals[pos] = x[j];
-                }
-                gt_before += gt ? 1u : 0u;
-                eq_before += eq ? 1u : 0u;
-            }
-            run_gt += total & 0xffffu;
-            run_eq += total >> 16;
-        }
-        __syncthreads();
+    if (!decided) select_radix<BLOCK>(val, n, keep, s_radix, s_cols, s_vals);
+    // Place in the row -> logits column, for the kept elements only and all at once (a look-up
+    // where an element is found to be kept would cost one memory latency per step of that loop,
+    // one after the other).  Every thread rewrites the entries it reads again below.
+    for (int j = tid; j < keep; j += BLOCK) {
+        const int i = s_cols[j];
+        s_cols[j] = col_map ? col_map[i] : col_base + i;
     }
 
     if constexpr (kEmits) {
@@ -480,96 +654,186 @@ __global__ __launch_bounds__(FAST ? kSelectFastBlock : kSelectBlock) void hg_sel
         }
         return;
     }
+    fold_kept<TR, BLOCK>(a, gh, h, r0, r1, keep, s_cols, s_vals, s_red, s_acc);
+}
 
-    // 3a. m = max kept logit; weights; l
-    float mx = -INFINITY;
-    for (int j = tid; j < keep; j += BLOCK) mx = fmaxf(mx, s_vals[j]);
+// ---- hg_select_survivors_kernel -------------------------------------------------------------------
+//
+// Selection straight from the lists a filter pass leaves (hg_attn_topk): per (group, head) the
+// survivors sit in one short list per (segment, sub-span) -- an *item* -- at the sub-span's own
+// columns.  In column order the items form one virtual row; an exclusive scan of their counts
+// (kept in LDS: at most kSurvivorItems items, which the host checks) gives every item's place in
+// it, and element i of the row is found by bisection over those places.  A row of at most
+// kSelectRegTokens elements -- the rule: a filter pass lets a fraction of a per cent through -- is
+// selected and folded by one workgroup.  A longer row is cut into slices of that size, dealt to the
+// tail_parts workgroups of the pair; each writes its slices' top_k candidates, and the workgroup
+// that finishes last (a counter in global memory that the filter pass has cleared; no workgroup
+// waits for another) selects among the candidates of all and folds.  The host launches as many
+// workgroups per pair as fill the device once: idle ones cost nothing then, and a row that the
+// bounds failed on (ascending logits) still has the whole device working on it.
+constexpr int kSurvivorItems = 2048;
+
+typedef __attribute__((address_space(3))) const int32_t *LdsConstI32;
+
+struct RowSurvivors {
+    const float *vals;      // the head's row of surv_val
+    LdsConstI32 isrc, idst; // per item: first column of its list, place in the virtual row
+    int n_items, lo;        // element i of the slice is element lo + i of the virtual row
+    // Where element i sits in the head's rows of surv_val / surv_col: the last item x with
+    // idst[x] <= lo + i (empty items share their successor's place).  A fixed number of steps
+    // without branches, so that the searches for a thread's elements run side by side.
+    __device__ __forceinline__ int place(int i) const
+    {
+        const int pos = lo + i;
+        int x = 0;
 #pragma unroll
-    for (int step = 32; step >= 1; step >>= 1) mx = fmaxf(mx, __shfl_xor(mx, step, 64));
-    if (lane == 0) s_red[wave] = mx;
-    __syncthreads();
-    mx = s_red[0];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) mx = fmaxf(mx, s_red[w]);
-    __syncthreads();
-    float lt = 0.f;
-    const int seq = table_entry(a.tab, r0).seq;
-    for (int j = tid; j < keep; j += BLOCK) {
-        const float w = fast_exp2((s_vals[j] - mx) * kLog2e);
-        lt += w;
-        // column -> token position: the range of the group that holds the column
-        const int col = s_cols[j];
-        int lo = r0, hi = r1;  // pre[lo] <= col < pre[hi]
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (table_entry(a.tab, mid).pre <= col)
-                lo = mid;
-            else
-                hi = mid;
+        for (int step = kSurvivorItems / 2; step >= 1; step >>= 1) {
+            const int y = x + step;
+            x = idst[y < n_items ? y : n_items] <= pos ? y : x;  // (idst[n_items], the total, is above every element)
         }
-        const RangeEntry e = table_entry(a.tab, lo);
-        const int tok = e.begin + (col - e.pre);
-        s_cols[j] = tok;
-        s_vals[j] = w;
-        if (a.sel) a.sel[gh * a.top_k + j] = tok;
+        return isrc[x] + (pos - idst[x]);
     }
+    __device__ __forceinline__ float operator()(int i) const { return vals[place(i)]; }
+    // The searches of all R elements step by step together: R independent LDS reads per step
+    // instead of R chains of dependent ones.
+    template <int R, int BLOCK>
+    __device__ __forceinline__ void gather(float (&x)[R], int n) const
+    {
+        int pos[R], at[R];
 #pragma unroll
-    for (int step = 32; step >= 1; step >>= 1) lt += __shfl_xor(lt, step, 64);
-    if (lane == 0) s_red[wave] = lt;
-    __syncthreads();
-    lt = 0.f;
+        for (int e = 0; e < R; ++e) {
+            const int i = e * BLOCK + (int)threadIdx.x;
+            pos[e] = lo + (i < n ? i : n - 1);
+            at[e] = 0;
+        }
+        int top = 1;  // uniform: the largest power of two below n_items
+        while (2 * top < n_items) top *= 2;
+        for (int step = top; step >= 1; step >>= 1) {
 #pragma unroll
-    for (int w = 0; w < NW; ++w) lt += s_red[w];
-
-    // 3b. gather the kept V rows: lane group grp of wave `wave` takes kept entries
-    //     4*wave + grp, + 64, + 128, ...
-    constexpr int LPR = TR::LPR, RPW = TR::RPW;
-    const int sub = lane % LPR, grp = lane / LPR;
-    const int hk = h / a.group;
-    // contiguous cache: the (sequence, KV head) slab; paged cache: the head's offset inside a block
-    const bool paged = a.pages.table != nullptr;
-    const char *vbase = static_cast<const char *>(a.v) + ((paged ? 0 : (int64_t)seq * a.stride_b) + (int64_t)hk * a.stride_h) * ES;
-    const int64_t row_bytes = a.stride_t * ES;
-    const int32_t *table = paged ? a.pages.table + (int64_t)seq * a.pages.max_blocks : nullptr;
-    float acc[EPL];
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
-    for (int j = RPW * wave + grp; j < keep; j += RPW * NW) {
-        const float w = s_vals[j];
-        const int tok = s_cols[j];
-        const char *vrow = paged ? vbase + paged_row_offset(table[tok >> a.pages.shift], tok, a.pages.mask, (uint32_t)(a.stride_b * ES), (uint32_t)row_bytes)
-                                 : vbase + (int64_t)tok * row_bytes;
-        float vf[EPL];
-#pragma unroll
-        for (int jj = 0; jj < NV; ++jj) {
-            typename TR::Raw raw = TR::template load<false>(vrow, sub, jj);
-            TR::widen(raw, &vf[jj * EPV]);
+            for (int e = 0; e < R; ++e) {
+                const int y = at[e] + step;
+                at[e] = idst[y < n_items ? y : n_items] <= pos[e] ? y : at[e];
+            }
         }
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) acc[i] = fmaf(w, vf[i], acc[i]);
+        for (int e = 0; e < R; ++e) x[e] = vals[isrc[at[e]] + (pos[e] - idst[at[e]])];
     }
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) {
-#pragma unroll
-        for (int step = LPR; step <= 32; step <<= 1) acc[i] += __shfl_xor(acc[i], step, 64);
+};
+
+template <typename TR>
+__global__ __launch_bounds__(kSelectFastBlock) void hg_select_survivors_kernel(const SelectArgs a)
+{
+    constexpr int D = TR::D, BLOCK = kSelectFastBlock, NW = BLOCK / 64;
+    __shared__ SelectRadixLds s_radix;
+    __shared__ int32_t s_cols[kSelectFastKeep];
+    __shared__ float s_vals[kSelectFastKeep];
+    __shared__ float s_red[NW];
+    __shared__ float s_acc[NW][D];
+    __shared__ SelectFastLds s_fast;
+    __shared__ int32_t s_isrc[kSurvivorItems], s_idst[kSurvivorItems + 1];
+    __shared__ uint32_t s_ticket;
+
+    // Grid (pair, part): the workgroups that take a pair's first slice -- with short rows the only
+    // ones with anything to do -- come first in the launch order and next to each other, so they
+    // start at once and spread over the whole device.
+    const int tid = threadIdx.x, part = blockIdx.y;
+    const int gi = blockIdx.x / a.n_q_heads, h = blockIdx.x - gi * a.n_q_heads;
+    const int r0 = group_entry(a.groups, gi), r1 = group_entry(a.groups, gi + 1);
+    const int64_t gh = blockIdx.x;
+    const int hk = h / a.ws.group, gl = h - hk * a.ws.group;
+    const int chunk = gl / a.ws.gt, g = gl - chunk * a.ws.gt;
+    const int64_t s = (int64_t)hk * a.ws.n_chunks + chunk;  // this head's stream
+    const int64_t row = (int64_t)h * a.ws.ltok;
+
+    // the items of the pair in column order: ranges of the group, workgroups of the filter pass
+    // that held a segment of the range, sub-spans of the segment
+    int n_items = 0;
+    uint32_t running = 0;
+    for (int r = r0; r < r1; ++r) {
+        const int pre = table_entry(a.tab, r).pre, pre_next = table_entry(a.tab, r + 1).pre;
+        if (pre_next == pre) continue;
+        const int64_t p_first = s * a.ws.ltok + pre, p_last = s * a.ws.ltok + pre_next - 1;
+        const int64_t w_first = p_first / a.ws.span, w_last = p_last / a.ws.span;
+        const int n_it = (int)(w_last - w_first + 1) * a.n_sub;
+        for (int base = 0; base < n_it; base += BLOCK) {
+            const int i = base + tid;
+            uint32_t c = 0;
+            int src = 0;
+            if (i < n_it) {
+                const int64_t w = w_first + i / a.n_sub;
+                const int j = i % a.n_sub;
+                // the segment of workgroup w inside range r, in columns of the concatenated ranges
+                const int64_t lo = w * a.ws.span - s * a.ws.ltok, hi = lo + a.ws.span;
+                const int x0 = lo > pre ? (int)lo : pre, x1 = hi < pre_next ? (int)hi : pre_next;
+                const int sub_len = filter_sub_len(x1 - x0, a.n_sub);
+                src = x0 + (j * sub_len < x1 - x0 ? j * sub_len : x1 - x0);
+                const int64_t slot = w + s * a.tab.n_ranges + r;
+                c = (uint32_t)a.surv_cnt[(slot * a.n_sub + j) * a.ws.gt + g];
+            }
+            uint32_t total;
+            const uint32_t before = block_exclusive_scan<BLOCK>(c, s_radix.wave, total);
+            if (i < n_it && n_items + i < kSurvivorItems) {
+                s_isrc[n_items + i] = src;
+                s_idst[n_items + i] = (int32_t)(running + before);
+            }
+            running += total;
+        }
+        n_items += n_it;
     }
-    if (grp == 0) {
-#pragma unroll
-        for (int jj = 0; jj < NV; ++jj)
-#pragma unroll
-            for (int i = 0; i < EPV; ++i) s_acc[wave][TR::vec_offset(sub, jj) + i] = acc[jj * EPV + i];
-    }
+    if (n_items > kSurvivorItems) n_items = kSurvivorItems;  // (the host launches this kernel only when they fit)
+    if (tid == 0) s_idst[n_items] = (int32_t)running;
     __syncthreads();
-    if (tid < D) {
-        float ot = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) ot += s_acc[w][tid];
-        a.o[gh * D + tid] = ot;
+    // (a.parts slices hold the longest group: the host has checked that)
+    const int total = running < (uint32_t)a.parts * kSelectRegTokens ? (int)running : a.parts * kSelectRegTokens;
+    if (total == 0) {
+        if (part == 0) write_empty_selection<D, BLOCK>(a, gh);
+        return;
     }
-    if (tid == 0) {
-        a.m[gh] = mx;
-        a.l[gh] = lt;
+    const int n_slices = (total + kSelectRegTokens - 1) / kSelectRegTokens;
+    if (part >= n_slices) return;
+
+    const bool single = n_slices == 1;
+
+    RowSurvivors val{a.surv_val + row, (LdsConstI32)s_isrc, (LdsConstI32)s_idst, n_items, 0};
+    const int64_t cand_base = gh * a.parts * (int64_t)a.top_k;
+    int keep;
+    for (int slice = part;;) {
+        val.lo = slice * kSelectRegTokens;
+        const int n = total - val.lo < kSelectRegTokens ? total - val.lo : kSelectRegTokens;
+        keep = n < a.top_k ? n : a.top_k;
+        if (!select_fast_by_length(val, n, keep, s_fast, s_cols, s_vals)) select_radix<BLOCK>(val, n, keep, s_radix, s_cols, s_vals);
+        // place in the slice -> logits column (every thread rewrites the entries it reads again below)
+        for (int j = tid; j < keep; j += BLOCK) s_cols[j] = a.surv_col[row + val.place(s_cols[j])];
+        if (single) break;
+        // this slice's candidates, padded to top_k
+        for (int j = tid; j < a.top_k; j += BLOCK) {
+            a.cand_val[cand_base + (int64_t)slice * a.top_k + j] = j < keep ? s_vals[j] : candidate_pad();
+            a.cand_col[cand_base + (int64_t)slice * a.top_k + j] = j < keep ? s_cols[j] : 0;
+        }
+        __syncthreads();  // s_cols / s_vals are free again
+        slice += a.tail_parts;
+        if (slice >= n_slices) break;
     }
+    if (!single) {
+        // This workgroup's slices are done.  Its candidates become visible to the device, then it
+        // takes a ticket; the workgroup that draws the last one sees the candidates of all and
+        // selects among them.
+        __threadfence();
+        __syncthreads();
+        if (tid == 0) s_ticket = atomicAdd(a.tail_cnt + gh, 1u);
+        __syncthreads();
+        const uint32_t active = (uint32_t)(n_slices < a.tail_parts ? n_slices : a.tail_parts);
+        if (s_ticket != active - 1) return;
+        __threadfence();
+        const RowDirect cands{a.cand_val + cand_base};
+        const int n = n_slices * a.top_k;
+        keep = total < a.top_k ? total : a.top_k;
+        if (!select_fast(cands, n, keep, s_fast, s_cols, s_vals)) select_radix<BLOCK>(cands, n, keep, s_radix, s_cols, s_vals);
+        for (int j = tid; j < keep; j += BLOCK) s_cols[j] = a.cand_col[cand_base + s_cols[j]];
+    }
+    if (a.sel)
+        for (int j = tid + keep; j < a.top_k; j += BLOCK) a.sel[gh * a.top_k + j] = -1;
+    fold_kept<TR, BLOCK>(a, gh, h, r0, r1, keep, s_cols, s_vals, s_red, s_acc);
 }
 
 // ---- hg_survivor_compact_kernel ------------------------------------------------------------------

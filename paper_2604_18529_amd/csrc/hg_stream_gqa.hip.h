@@ -214,6 +214,11 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter &&
     char *kls = smem + wave * kGqaWaveBytes;
     char *pls = kls + kGqaKBytes;
 
+    if constexpr (MODE == kModeFilter) {
+        // the selection that follows counts its finished workgroups from zero
+        if (blockIdx.x == 0)
+            for (int64_t i = threadIdx.x; i < a.n_tail; i += blockDim.x) a.tail_cnt[i] = 0u;
+    }
     for_each_segment(a.ws, a.tab, [&](int stream, int r_idx, const RangeEntry &e, int seg_t0, int seg_t1, int seg_col0, int64_t slot) __attribute__((always_inline)) {
     // Tokens [t0, t1) this wave works on and the column of t0: the whole segment, whose 32-token
     // blocks the waves take in turn -- or, in filter mode, the wave's own consecutive sub-span, so
@@ -464,6 +469,54 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter &&
         wave_lds_handover();
     };
 
+    // Shared bound, first half: request the peers' values of the head this 16-lane row evaluates
+    // (head 4 * wave + rg, this lane's position n).  Buffer loads that go to the device-wide cache
+    // (sc1), not atomic loads: those complete one by one, these are all in flight together.  The
+    // buffer is the peers' part of the array; beyond it a load returns 0.
+    auto request_peer_values = [&](uint32_t(&key)[kGqaMaxPeers]) __attribute__((always_inline)) {
+        if constexpr (MODE == kModeFilter) {
+            uint32_t *gb = a.gbound;
+            const int hh = 4 * wave + rg;
+            const uint64_t peers_at = reinterpret_cast<uint64_t>(gb + gb_first * (kGqaHeads * kGqaSetsPerHead));
+            const uint64_t peers_uni = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(peers_at >> 32)) << 32) |
+                                       (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)peers_at);
+            const __amdgpu_buffer_rsrc_t peers = __builtin_amdgcn_make_buffer_rsrc(
+                reinterpret_cast<void *>(peers_uni), 0, __builtin_amdgcn_readfirstlane(n_peers) * (kGqaHeads * kGqaSetsPerHead * 4), kRawBufferFlags);
+#pragma unroll
+            for (int j = 0; j < kGqaMaxPeers; ++j) {
+                // one value of each of up to 32 peers, or four (the waves') of each of up to 8
+                const int one = (j * kGqaHeads + hh) * kGqaSetsPerHead + n;
+                const int four = ((j / kGqaWaves) * kGqaHeads + hh) * kGqaSetsPerHead + (j % kGqaWaves) * 16 + n;
+                key[j] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(peers, (per_wave ? four : one) * 4, 0, kCacheSc1);
+            }
+        }
+    };
+    // Second half: the largest 16-bit key that top_k of the row's values reach becomes the head's
+    // bound; the other waves pick it up from LDS during the next blocks.
+    auto evaluate_peer_values = [&](uint32_t(&key)[kGqaMaxPeers]) __attribute__((always_inline)) {
+        if constexpr (MODE == kModeFilter) {
+            const int hh = 4 * wave + rg;
+#pragma unroll
+            for (int j = 0; j < kGqaMaxPeers; ++j) key[j] >>= 16;
+            uint32_t tw = 0u;
+#pragma unroll 1
+            for (int b = 15; b >= 0; --b) {
+                const uint32_t c = tw | (1u << b);
+                uint32_t reach = 0;
+#pragma unroll
+                for (int p = 0; p < kGqaMaxPeers; ++p) reach += key[p] >= c ? 1u : 0u;
+                reach = row16_sum_u32(reach);
+                if (reach >= (uint32_t)a.filter_k) tw = c;
+            }
+            tw <<= 16;
+            if (n == 0 && hh < nh) lds_publish(&wtau[hh], tw > order_key(-INFINITY) ? key_to_float(tw) : -INFINITY);
+            // bounds of this lane's own heads: this wave's are current, the others' as of
+            // their last refresh
+#pragma unroll
+            for (int r = 0; r < 4; ++r) tau[r] = fmaxf(tau[r], lds_peek(&wtau[4 * rg + r]));
+        }
+    };
+
     // One block.  Software pipeline with a single register buffer: the K rows of the next block
     // are requested as soon as this block's K sits in LDS, its V rows as soon as this block's V
     // has been consumed, so a wave always has 8-16 KiB in flight while it computes.
@@ -670,42 +723,9 @@ __global__ __launch_bounds__(kGqaBlock, kGqaWaves <= 4 && MODE != kModeFilter &&
                 published = false;
                 if (n_peers > 0) {
                     pickup = 2;
-                    uint32_t *gb = a.gbound;
-                    const int hh = 4 * wave + rg;  // the head this 16-lane row evaluates
-                    // the peers' values of this head and lane position (upper halves of the keys).
-                    // Buffer loads that go to the device-wide cache (sc1), not atomic loads: those
-                    // complete one by one, these are all in flight together.  The buffer is the
-                    // peers' part of the array; beyond it a load returns 0.
-                    const uint64_t peers_at = reinterpret_cast<uint64_t>(gb + gb_first * (kGqaHeads * kGqaSetsPerHead));
-                    const uint64_t peers_uni = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(peers_at >> 32)) << 32) |
-                                               (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)peers_at);
-                    const __amdgpu_buffer_rsrc_t peers = __builtin_amdgcn_make_buffer_rsrc(
-                        reinterpret_cast<void *>(peers_uni), 0, __builtin_amdgcn_readfirstlane(n_peers) * (kGqaHeads * kGqaSetsPerHead * 4), kRawBufferFlags);
                     uint32_t key[kGqaMaxPeers];
-#pragma unroll
-                    for (int j = 0; j < kGqaMaxPeers; ++j) {
-                        // one value of each of up to 32 peers, or four (the waves') of each of up to 8
-                        const int one = (j * kGqaHeads + hh) * kGqaSetsPerHead + n;
-                        const int four = ((j / kGqaWaves) * kGqaHeads + hh) * kGqaSetsPerHead + (j % kGqaWaves) * 16 + n;
-                        key[j] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(peers, (per_wave ? four : one) * 4, 0, kCacheSc1) >> 16;
-                    }
-                    // largest 16-bit key that top_k of the row's values reach
-                    uint32_t tw = 0u;
-#pragma unroll 1
-                    for (int b = 15; b >= 0; --b) {
-                        const uint32_t c = tw | (1u << b);
-                        uint32_t reach = 0;
-#pragma unroll
-                        for (int p = 0; p < kGqaMaxPeers; ++p) reach += key[p] >= c ? 1u : 0u;
-                        reach = row16_sum_u32(reach);
-                        if (reach >= (uint32_t)a.filter_k) tw = c;
-                    }
-                    tw <<= 16;
-                    if (n == 0 && hh < nh) lds_publish(&wtau[hh], tw > order_key(-INFINITY) ? key_to_float(tw) : -INFINITY);
-                    // bounds of this lane's own heads: this wave's are current, the others' as of
-                    // their last refresh
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) tau[r] = fmaxf(tau[r], lds_peek(&wtau[4 * rg + r]));
+                    request_peer_values(key);
+                    evaluate_peer_values(key);
                 } else {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {

@@ -107,6 +107,11 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane % LPR, grp = lane / LPR;
 
+    if constexpr (MODE == kModeFilter) {
+        // the selection that follows counts its finished workgroups from zero
+        if (blockIdx.x == 0)
+            for (int64_t i = threadIdx.x; i < a.n_tail; i += blockDim.x) a.tail_cnt[i] = 0u;
+    }
     for_each_segment(a.ws, a.tab, [&](int stream, int r_idx, const RangeEntry &e, int seg_t0, int seg_t1, int seg_col0, int64_t slot) __attribute__((always_inline)) {
     // Tokens [t0, t1) the waves share iteration by iteration and the column of t0 -- or, in filter
     // mode, this wave's own consecutive sub-span, so that what it appends is in column order.

@@ -25,12 +25,14 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.fixture(autouse=True, params=["scan", "auto"])
+@pytest.fixture(autouse=True, params=["scan", "scan-staged", "auto"])
 def _modes(request):
     """Every test runs with the filtering scan forced wherever it exists (the inputs here are far
-    shorter than what the library would choose it for) and with the library's own choice."""
+    shorter than what the library would choose it for) -- once with the one-launch selection from
+    the scan's own lists behind it, once with the compaction and the staged selection that the
+    library falls back to when those lists do not fit -- and with the library's own choice."""
     hg.hg_attn_set_span_tokens(0)
-    hg.hg_attn_set_topk_mode(1 if request.param == "scan" else 0)
+    hg.hg_attn_set_topk_mode({"scan": 1, "scan-staged": 3, "auto": 0}[request.param])
     yield
     hg.hg_attn_set_span_tokens(0)
     hg.hg_attn_set_topk_mode(0)
@@ -170,6 +172,26 @@ def test_long_and_short_survivor_lists_in_one_call(group):
     w.k[0, 0, :, 0] = (torch.arange(N, device=DEV) // 16).to(torch.float16)  # exact in fp16 up to 2048
     for top_k in (50, 256):
         _check_exact(w, [(0, 0, N), (1, 0, 11000), (1, 11000, N)], [0, 1, 3], top_k, "G=%d k=%d" % (group, top_k))
+
+
+@pytest.mark.parametrize("batch", [8, 9])
+def test_more_slices_than_selection_workgroups(batch):
+    """Many (group, head) pairs, so that the selection behind the scan launches two workgroups
+    per pair (8 sequences x 64 heads) or one (9 sequences), and one sequence whose logits rise
+    with the token index: its 40000 survivors per head are three slices, which the workgroups
+    take in turn before the last one to finish selects among the candidates of all."""
+    N, group, hkv = 40000, 8, 8
+    spec = W.WorkloadSpec("topkslices", batch, group * hkv, hkv, 128, "f16", N, N, "none", seed=133)
+    w = W.make_workload(spec, DEV)
+    W.make_dyadic_(w, seed=134)
+    w.scale = 0.125
+    b = batch - 2
+    w.q[b].zero_()
+    w.q[b, :, 0] = 1.0
+    w.k[b].zero_()
+    w.k[b, :, :, 0] = (torch.arange(N, device=DEV) // 32).to(torch.float16)  # exact in fp16 up to 2048
+    ranges = [(i, 0, N) for i in range(batch)]
+    _check_exact(w, ranges, list(range(batch + 1)), 128, "B=%d" % batch)
 
 
 @pytest.mark.parametrize("dtype,d,group", [("f16", 128, 8), ("bf16", 128, 4), ("f16", 128, 3), ("f16", 128, 1), ("f16", 64, 4)])
