@@ -244,7 +244,8 @@ hg_status hg_attn_select(const hg_attn_desc *desc, const hg_range *ranges, int32
  *
  *   ranges, group_ptr, top_k, sel, m, l, o   as for hg_attn_select.
  *   workspace   DEVICE, 256-byte aligned, hg_attn_topk_workspace_size bytes: room for the worst
- *               case of the scan (4 x 4 bytes per (query head, token of the ranges)).
+ *               case of the scan (2 x 4 bytes per (query head, token of the ranges); 4 x 4 with
+ *               very many ranges per group or groups beyond 2^20 tokens).
  *   The filtering scan exists for top_k <= 256 (contiguous and paged caches), for one query head
  *   per KV head (any storage type) and for 16-bit storage with head_dim 128 and two or more query
  *   heads per KV head; it is chosen when the groups are long (see hg_attn_set_topk_mode).  Other cases

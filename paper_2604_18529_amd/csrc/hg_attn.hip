@@ -819,8 +819,8 @@ TopkPlan plan_topk(const hg_attn_desc *d, const hg_range *ranges, const int32_t 
         tp.n_sub = filter_sub_spans(d);
         const int64_t pairs = std::max<int64_t>(1, (int64_t)n_groups * d->n_q_heads);
         tp.tail = g_topk_mode != 3 && survivors_kernel_fits(ranges, group_ptr, n_groups, p, sp, tp.n_sub, top_k);
-        // as many workgroups per pair as fill the device about once (four fit a compute unit)
-        tp.tail_parts = (int32_t)std::min<int64_t>(sp.parts, std::max<int64_t>(1, 4 * (int64_t)compute_units() / pairs));
+        // as many workgroups per pair as fill the device about once (two fit a compute unit)
+        tp.tail_parts = (int32_t)std::min<int64_t>(sp.parts, std::max<int64_t>(1, 2 * (int64_t)compute_units() / pairs));
         // (every workgroup of a pair repeats the scan of the counts: up to 8 per pair, 512 in all,
         // measured against 1-64 per pair)
         tp.chunks = (int32_t)std::min<int64_t>(8, std::max<int64_t>(1, 512 / pairs));

@@ -109,9 +109,10 @@ def test_random_case(case):
     check_triples(sm, sl, so, rm, rl, ro, what + " select")
 
     # the one-call executor stage: the same kept tokens as logits -> select on the logits the library
-    # itself computes (filtering scan forced on even cases, where it exists), and the triple of the
-    # oracle's listed-token routine over that list
-    hg.hg_attn_set_topk_mode(1 if case % 2 == 0 else 0)
+    # itself computes (filtering scan forced on two cases of three, where it exists: once with the
+    # one-launch selection behind it, once with the staged one), and the triple of the oracle's
+    # listed-token routine over that list
+    hg.hg_attn_set_topk_mode((1, 3, 0)[case % 3])
     try:
         tsel, tm, tl, to = hg.hg_attn_topk(w.q, k_dev, v_dev, w.seq_lens, ranges, gp, top_k, w.scale, block_table=table)
     finally:
