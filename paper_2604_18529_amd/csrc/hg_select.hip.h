@@ -1,4 +1,5 @@
-// Post-QK^T selection kernel.
+// Post-QK^T selection kernels: hg_select_kernel (from logits rows, staged for long groups),
+// hg_select_survivors_kernel (from the lists a filter pass leaves), hg_survivor_compact_kernel.
 #pragma once
 
 #include "hg_common.hip.h"
@@ -40,6 +41,9 @@ namespace hg {
 //      counts before its wave row plus the kept lanes below it.
 // Inputs that defeat the bound (sorted rows, masked rows full of -inf, too many candidates) fall
 // back to the radix passes over the row; the result is the same either way.
+// In every path the kept elements' columns are looked up only after the selection, all at once,
+// and the fold keeps four V rows per lane group in flight: both are memory latencies that would
+// otherwise line up one behind the other.
 
 constexpr int kSelectFastBlock = 512;                             // threads of the FAST variants (8 waves)
 constexpr int kSelectRegs = 32;                                   // elements per thread of the fast path
@@ -720,8 +724,8 @@ struct RowSurvivors {
     }
 };
 
-// (Compiled for two workgroups per compute unit: with several hundred (group, head) pairs the
-// launch is a round and a quarter instead of two and a half -- 52 -> 37 us at 640 pairs.)
+// (Compiled for two workgroups per compute unit: several hundred (group, head) pairs then fit the
+// device in one and a quarter passes instead of two and a half -- 52 -> 37 us at 640 pairs.)
 template <typename TR>
 __global__ __launch_bounds__(kSelectFastBlock, 4) void hg_select_survivors_kernel(const SelectArgs a)
 {
