@@ -175,6 +175,14 @@ hg_status check_ranges(const hg_attn_desc *d, const hg_range *ranges, int32_t n_
 #endif
 bool use_gqa_kernel(const hg_attn_desc *d) { return d->dtype != HG_F32 && d->n_q_heads / d->n_kv_heads >= HG_GQA_MIN_GROUP; }
 
+// Workgroups per compute unit of hg_attn_concat.  The matrix-core kernel for 128-byte rows is bound
+// by instruction issue in this mode (its waves wait for memory 6 % of the time: per byte it does
+// twice the work of the 256-byte-row kernel), and one wave per SIMD has nobody to hand the issue
+// slot to; with two workgroups per compute unit it ran in 125 us instead of 143 (8 sequences x
+// 64k tokens, 32 query heads on 8 KV heads), with three or four in 146 and 159.  Every other
+// kernel was faster or level with one (256-byte rows, 8 query heads per KV head: 350 against 367 us).
+int concat_workgroups_per_cu(const hg_attn_desc *d) { return use_gqa_kernel(d) && d->head_dim == 64 ? 2 : 1; }
+
 int32_t pick_group_tile(const hg_attn_desc *d)
 {
     const int32_t group = d->n_q_heads / d->n_kv_heads;
@@ -1240,7 +1248,7 @@ hg_status hg_attn_concat_workspace_size(const hg_attn_desc *desc, const hg_range
     st = check_ranges(desc, ranges, n_ranges);
     if (st != HG_OK) return st;
     Plan p;
-    st = make_plan(desc, ranges, n_ranges, p);
+    st = make_plan(desc, ranges, n_ranges, p, concat_workgroups_per_cu(desc));
     if (st != HG_OK) return st;
     add_concat_sections(p, n_groups, desc->n_q_heads);
     *bytes = p.total;
@@ -1260,7 +1268,7 @@ hg_status hg_attn_concat(const hg_attn_desc *desc, const hg_range *ranges, int32
     if (n_groups == 0) return HG_OK;
     if (!out) return HG_ERR_NULL;
     Plan p;
-    st = make_plan(desc, ranges, n_ranges, p);
+    st = make_plan(desc, ranges, n_ranges, p, concat_workgroups_per_cu(desc));
     if (st != HG_OK) return st;
     if (p.ws.total > 0 && !logits) return HG_ERR_NULL;
     add_concat_sections(p, n_groups, desc->n_q_heads);
