@@ -420,11 +420,22 @@ def run_tiny(torch, hg, W, iters=200, sets=64):
         turn[0] += 1
         hg.hg_attn_full(q, k, v, w.seq_lens, w.scale, out=out, want_lse=False, workspace=fws, desc=desc)
 
+    pws = torch.empty(max(binding.hg_attn_partial_merge_workspace_size(copies[0][3], packed, w.group_ptr), 256), dtype=torch.uint8,
+                      device=dev)
+
+    def one_call_step():  # the same outputs through hg_attn_partial_merge: one launch at this size
+        q, k, v, desc, _ = copies[turn[0] % sets]
+        turn[0] += 1
+        hg.hg_attn_partial_merge(q, k, v, w.seq_lens, packed, w.group_ptr, w.scale, m=m, l=l, o=o, out=out, want_lse=False,
+                                 workspace=pws, desc=desc)
+
     step_ms, kernel_ms = _time_each(step, iters, 10, torch, hg)
     full_ms, _ = _time_each(full_step, iters, 10, torch, hg)
+    one_ms, _ = _time_each(one_call_step, iters, 10, torch, hg)
     return {"workload": spec.name, "kv_bytes": w.kv_bytes, "buffer_sets": sets, "step_us": _stats(step_ms, 1e3),
             "stream_kernel_us": _stats(kernel_ms, 1e3), "full_path_us": _stats(full_ms, 1e3),
-            "note": "launch-bound: three launches per step (one for the unsplit path); microseconds only"}
+            "partial_merge_one_call_us": _stats(one_ms, 1e3),
+            "note": "launch-bound: three launches per step (one for the unsplit path and for hg_attn_partial_merge); microseconds only"}
 
 
 def run_memory_probe(torch, hg, read_bytes=7516192768, reps=5):

@@ -145,6 +145,25 @@ hg_status hg_attn_merge(const float *m, const float *l, const float *o, const in
                         size_t ws_bytes, void *stream);
 
 /*
+ * hg_attn_partial_merge -- hg_attn_partial followed by hg_attn_merge in one call (Sections 4.2.2
+ * and 4.2.3 on one device: the triples of every range and the recombined output of every group),
+ * for callers that want both.  The results are those of the two calls (the merged output up to
+ * the order of summation).  group_ptr must cover the ranges exactly (group_ptr[0] == 0,
+ * group_ptr[n_groups] == n_ranges).  When the input is small -- one query head per lane group
+ * (32-bit storage, or 16-bit storage without a query group), a contiguous cache, at most 16
+ * groups and 64 ranges, few enough (group, KV head) pairs for one workgroup each and few enough
+ * tokens per group for a workgroup to stream them in the time a launch takes -- the whole call
+ * is one kernel launch instead of three; otherwise it runs the two calls' kernels.
+ *   workspace   DEVICE, 256-byte aligned, hg_attn_partial_merge_workspace_size bytes.
+ *   Other arguments as for hg_attn_partial and hg_attn_merge; lse_out may be NULL.
+ */
+hg_status hg_attn_partial_merge_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges,
+                                               const int32_t *group_ptr, int32_t n_groups, size_t *bytes);
+hg_status hg_attn_partial_merge(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, const int32_t *group_ptr,
+                                int32_t n_groups, float *m, float *l, float *o, float *out, float *lse_out, void *workspace,
+                                size_t ws_bytes, void *stream);
+
+/*
  * hg_attn_merge2 -- the same recombination over the triples of TWO producers, each with its own
  * arrays and CSR (Section 4.2.3; Section 4.6 step 5: the concatenator joins what the executor of
  * the offloaded tokens returns with what the executor of the resident tokens computed): group i

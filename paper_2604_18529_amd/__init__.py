@@ -8,6 +8,7 @@ the package (for example to reach ``workloads``) does not require the built libr
 _API = (
     "hg_attn_partial",
     "hg_attn_partial_static",
+    "hg_attn_partial_merge",
     "hg_attn_profile_times",
     "hg_attn_build_id",
     "hg_attn_merge",

@@ -961,6 +961,55 @@ hg_status merge_sets(const float *m, const float *l, const float *o, const int32
     return launch_status("merge kernel");
 }
 
+// hg_attn_partial_merge in one launch: the FUSED variant of the vector kernel, one workgroup per
+// (group, stream).  A workgroup alone streams about 28 KiB per microsecond, and the launches it
+// saves (segment reduce, merge, and the gaps between three kernels) are worth some 12 us: beyond
+// kFusedMaxBytes of K and V rows per (group, KV head) the three-kernel path is faster.
+constexpr int64_t kFusedMaxBytes = 320 << 10;
+
+bool fused_single_launch(const hg_attn_desc *d, const hg_range *ranges, int32_t n_ranges, const int32_t *group_ptr,
+                         int32_t n_groups, const Plan &p)
+{
+    if (use_gqa_kernel(d) || d->block_table) return false;
+    if (n_groups < 1 || n_groups > kFusedGroups || n_ranges > kInlineRanges) return false;
+    const int64_t n_streams = (int64_t)d->n_kv_heads * p.ws.n_chunks;
+    if (n_streams * n_groups > compute_units()) return false;
+    const int64_t row_bytes = 2 * (int64_t)d->head_dim * (d->dtype == HG_F32 ? 4 : 2);  // a K row and a V row
+    for (int32_t i = 0; i < n_groups; ++i) {
+        int64_t tokens = 0;
+        for (int32_t r = group_ptr[i]; r < group_ptr[i + 1]; ++r) tokens += ranges[r].end - ranges[r].begin;
+        if (tokens * row_bytes > kFusedMaxBytes) return false;
+    }
+    return true;
+}
+
+template <typename TR>
+void launch_valu_fused(const PartialArgs &a, int gt, dim3 grid, hipStream_t stream)
+{
+    if constexpr (TR::DT != kDtF32) {
+        HG_LAUNCH((hg_partial_kernel<TR, 1, HG_VALU_U, kModeStats, false, true>), grid, dim3(kValuBlock), stream, a);
+        return;
+    }
+    switch (gt) {
+    case 1: HG_LAUNCH((hg_partial_kernel<TR, 1, HG_VALU_U, kModeStats, false, true>), grid, dim3(kValuBlock), stream, a); break;
+    case 2: HG_LAUNCH((hg_partial_kernel<TR, 2, HG_VALU_U, kModeStats, false, true>), grid, dim3(kValuBlock), stream, a); break;
+    case 4: HG_LAUNCH((hg_partial_kernel<TR, 4, 2, kModeStats, false, true>), grid, dim3(kValuBlock), stream, a); break;
+    default: HG_LAUNCH((hg_partial_kernel<TR, 8, 2, kModeStats, false, true>), grid, dim3(kValuBlock), stream, a); break;
+    }
+}
+
+hg_status partial_merge_plan(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, const int32_t *group_ptr,
+                             int32_t n_groups, Plan &p)
+{
+    hg_status st = check_desc(desc);
+    if (st != HG_OK) return st;
+    st = check_ranges(desc, ranges, n_ranges);
+    if (st != HG_OK) return st;
+    st = check_concat_groups(ranges, n_ranges, group_ptr, n_groups);
+    if (st != HG_OK) return st;
+    return make_plan(desc, ranges, n_ranges, p);
+}
+
 }  // namespace
 
 extern "C" {
@@ -1561,6 +1610,68 @@ hg_status hg_attn_merge(const float *m, const float *l, const float *o, const in
 {
     return merge_sets(m, l, o, group_ptr, nullptr, nullptr, nullptr, nullptr, n_groups, n_q_heads, head_dim, out, lse_out,
                       workspace, ws_bytes, stream_v);
+}
+
+hg_status hg_attn_partial_merge_workspace_size(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges,
+                                               const int32_t *group_ptr, int32_t n_groups, size_t *bytes)
+{
+    if (!bytes) return HG_ERR_NULL;
+    Plan p;
+    const hg_status st = partial_merge_plan(desc, ranges, n_ranges, group_ptr, n_groups, p);
+    if (st != HG_OK) return st;
+    *bytes = align_up(p.total) + merge_ws_bytes(n_groups);  // the two calls' workspaces, one behind the other
+    return HG_OK;
+}
+
+hg_status hg_attn_partial_merge(const hg_attn_desc *desc, const hg_range *ranges, int32_t n_ranges, const int32_t *group_ptr,
+                                int32_t n_groups, float *m, float *l, float *o, float *out, float *lse_out, void *workspace,
+                                size_t ws_bytes, void *stream_v)
+{
+    Plan p;
+    hg_status st = partial_merge_plan(desc, ranges, n_ranges, group_ptr, n_groups, p);
+    if (st != HG_OK) return st;
+    if (n_groups == 0) return HG_OK;
+    if (!out || (n_ranges > 0 && (!m || !l || !o))) return HG_ERR_NULL;
+    const size_t first = align_up(p.total);
+    st = check_workspace(workspace, ws_bytes, first + merge_ws_bytes(n_groups));
+    if (st != HG_OK) return st;
+    if (fused_single_launch(desc, ranges, n_ranges, group_ptr, n_groups, p)) {
+        hipStream_t stream = static_cast<hipStream_t>(stream_v);
+        PartialArgs pa;
+        std::memset(&pa, 0, sizeof(pa));
+        st = stage_table(p, n_ranges, static_cast<char *>(workspace), stream, pa.tab);  // (fits the kernel arguments: nothing is launched)
+        if (st != HG_OK) return st;
+        fill_stream_args(desc, p, nullptr, pa);
+        pa.direct = 1;
+        pa.out_m = m;
+        pa.out_l = l;
+        pa.out_o = o;
+        pa.fused_n_groups = n_groups;
+        std::memcpy(pa.fused_groups, group_ptr, ((size_t)n_groups + 1) * sizeof(int32_t));
+        pa.merged_out = out;
+        pa.merged_lse = lse_out;
+        const dim3 grid((unsigned)((int64_t)desc->n_kv_heads * p.ws.n_chunks * n_groups));
+        if (desc->head_dim == 128) {
+            if (desc->dtype == HG_F16)
+                launch_valu_fused<Traits<128, kDtF16>>(pa, p.ws.gt, grid, stream);
+            else if (desc->dtype == HG_BF16)
+                launch_valu_fused<Traits<128, kDtBf16>>(pa, p.ws.gt, grid, stream);
+            else
+                launch_valu_fused<Traits<128, kDtF32>>(pa, p.ws.gt, grid, stream);
+        } else {
+            if (desc->dtype == HG_F16)
+                launch_valu_fused<Traits<64, kDtF16>>(pa, p.ws.gt, grid, stream);
+            else if (desc->dtype == HG_BF16)
+                launch_valu_fused<Traits<64, kDtBf16>>(pa, p.ws.gt, grid, stream);
+            else
+                launch_valu_fused<Traits<64, kDtF32>>(pa, p.ws.gt, grid, stream);
+        }
+        return launch_status("fused partial and merge kernel");
+    }
+    st = run(desc, ranges, n_ranges, 0, m, l, o, workspace, first, stream_v);
+    if (st != HG_OK) return st;
+    return merge_sets(m, l, o, group_ptr, nullptr, nullptr, nullptr, nullptr, n_groups, desc->n_q_heads, desc->head_dim, out,
+                      lse_out, static_cast<char *>(workspace) + first, ws_bytes - first, stream_v);
 }
 
 hg_status hg_attn_merge2_workspace_size(int32_t n_groups, size_t *bytes)

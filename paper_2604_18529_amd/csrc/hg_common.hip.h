@@ -29,6 +29,7 @@
 namespace hg {
 
 constexpr int kInlineRanges = 64;   // range-table entries carried inside the kernel arguments
+constexpr int kFusedGroups = 16;    // groups of a launch in which one workgroup takes a whole (group, stream)
 constexpr int kInlineGroups = 256;  // CSR offsets carried inside the merge kernel's arguments
 constexpr int kUploadRanges = 128;  // entries per table-upload launch
 constexpr int kUploadInts = 512;
@@ -136,6 +137,12 @@ struct PartialArgs {
     // (its count of finished workgroups per (group, head))
     uint32_t *tail_cnt;
     int64_t n_tail;
+    // FUSED variant of the vector kernel (hg_attn_partial_merge on small inputs): workgroup
+    // (group i, stream) takes the ranges fused_groups[i] .. fused_groups[i + 1] - 1 one after the
+    // other, writes their triples itself and the group's merged output at the end
+    int32_t fused_n_groups;
+    int32_t fused_groups[kFusedGroups + 1];
+    float *merged_out, *merged_lse;  // [n_groups][Hq][D], [n_groups][Hq] or NULL
     WorkSplit ws;
     RangeTable tab;
 };
@@ -435,6 +442,23 @@ struct Traits {
         }
     }
 };
+
+// The FUSED walk: workgroup blockIdx.x = stream * n_groups + group visits the group's ranges in
+// order.  f as in for_each_segment (a whole range is one segment; the slot is unused: results are
+// written directly); empty(stream, range index) is called for a range without tokens.
+template <typename F, typename E>
+__device__ __forceinline__ void for_each_range_of_group(const PartialArgs &a, F &&f, E &&empty)
+{
+    const int gi = (int)(blockIdx.x % (unsigned)a.fused_n_groups), s = (int)(blockIdx.x / (unsigned)a.fused_n_groups);
+    const int r0 = a.fused_groups[gi], r1 = a.fused_groups[gi + 1];
+    for (int r = r0; r < r1; ++r) {
+        const RangeEntry e = table_entry(a.tab, r);
+        if (e.end == e.begin)
+            empty(s, r);
+        else
+            f(s, r, e, e.begin, e.end, e.pre, (int64_t)0);
+    }
+}
 
 // Result of one segment for one (head, channel): a record for the reduce kernel, or, in direct
 // mode, the caller's triple / normalised output itself.  mx in log2 units.

@@ -58,9 +58,13 @@ __device__ __forceinline__ void workgroup_lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <typename TR, int GT, int U, int MODE, bool PAGED>
+// FUSED (statistics mode, contiguous cache; hg_attn_partial_merge on small inputs): a workgroup takes
+// all ranges of one (group, stream), writes their triples itself and, at the end, the group's
+// merged output -- partial, segment reduce and merge in one launch.
+template <typename TR, int GT, int U, int MODE, bool PAGED, bool FUSED = false>
 __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2))) void hg_partial_kernel(const PartialArgs a)
 {
+    static_assert(!FUSED || (MODE == kModeStats && !PAGED), "the fused walk exists for the statistics mode on a contiguous cache");
     constexpr int D = TR::D, EPL = TR::EPL, NV = TR::NV, EPV = TR::EPV, ES = TR::ES;
     constexpr int LPR = TR::LPR, RPW = TR::RPW;
     constexpr int CH = RPW * U;  // tokens one wave takes per iteration
@@ -112,7 +116,17 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
         if (blockIdx.x == 0)
             for (int64_t i = threadIdx.x; i < a.n_tail; i += blockDim.x) a.tail_cnt[i] = 0u;
     }
-    for_each_segment(a.ws, a.tab, [&](int stream, int r_idx, const RangeEntry &e, int seg_t0, int seg_t1, int seg_col0, int64_t slot) __attribute__((always_inline)) {
+    // FUSED: the group's running merge, per (head, channel) this thread owns (log2 units, as the
+    // segment results)
+    constexpr int kOwn = (GT * D + kValuBlock - 1) / kValuBlock;
+    float f_m[kOwn], f_l[kOwn], f_o[kOwn];
+#pragma unroll
+    for (int it = 0; it < kOwn; ++it) {
+        f_m[it] = kNegBig;
+        f_l[it] = 0.f;
+        f_o[it] = 0.f;
+    }
+    auto segment = [&](int stream, int r_idx, const RangeEntry &e, int seg_t0, int seg_t1, int seg_col0, int64_t slot) __attribute__((always_inline)) {
     // Tokens [t0, t1) the waves share iteration by iteration and the column of t0 -- or, in filter
     // mode, this wave's own consecutive sub-span, so that what it appends is in column order.
     int t0 = seg_t0, t1 = seg_t1, col0 = seg_col0;
@@ -493,8 +507,62 @@ __global__ __launch_bounds__(kValuBlock) __attribute__((amdgpu_waves_per_eu(1, 2
         }
         write_segment_result<D>(a, slot * GT + g, r_idx, h0 + g, c, mx, lt, ot);
     }
+    if constexpr (FUSED) {
+        // the same results again, folded into the group's running merge
+#pragma unroll
+        for (int it = 0; it < kOwn; ++it) {
+            const int idx = (int)threadIdx.x + it * kValuBlock;
+            const int g = idx / D, c = idx - g * D;
+            if (idx >= GT * D || g >= nh) continue;
+            float mx = kNegBig;
+#pragma unroll
+            for (int w = 0; w < kValuWaves; ++w) mx = fmaxf(mx, sm[w][g][D]);
+            float lt = 0.f, ot = 0.f;
+#pragma unroll
+            for (int w = 0; w < kValuWaves; ++w) {
+                const float wt = fast_exp2(sm[w][g][D] - mx);
+                lt += wt * sm[w][g][D + 1];
+                ot += wt * sm[w][g][c];
+            }
+            const float m_new = fmaxf(f_m[it], mx);
+            const float w_old = fast_exp2(f_m[it] - m_new), w_seg = fast_exp2(mx - m_new);
+            f_l[it] = f_l[it] * w_old + lt * w_seg;
+            f_o[it] = f_o[it] * w_old + ot * w_seg;
+            f_m[it] = m_new;
+        }
+    }
     __syncthreads();  // the next segment reuses sm
-    });
+    };
+    if constexpr (FUSED) {
+        const int gi = (int)(blockIdx.x % (unsigned)a.fused_n_groups), stream = (int)(blockIdx.x / (unsigned)a.fused_n_groups);
+        const int hk = stream / a.ws.n_chunks, g0 = (stream - hk * a.ws.n_chunks) * GT;
+        const int nh = min(GT, a.ws.group - g0), h0 = hk * a.ws.group + g0;
+        for_each_range_of_group(a, segment, [&](int, int r_idx) __attribute__((always_inline)) {
+            // a range without tokens: m = -inf, l = 0, O = 0
+            for (int idx = threadIdx.x; idx < GT * D; idx += kValuBlock) {
+                const int g = idx / D, c = idx - g * D;
+                if (g >= nh) continue;
+                const int64_t rh = (int64_t)r_idx * a.ws.n_q_heads + h0 + g;
+                a.out_o[rh * D + c] = 0.f;
+                if (c == 0) {
+                    a.out_m[rh] = -INFINITY;
+                    a.out_l[rh] = 0.f;
+                }
+            }
+        });
+#pragma unroll
+        for (int it = 0; it < kOwn; ++it) {
+            const int idx = (int)threadIdx.x + it * kValuBlock;
+            const int g = idx / D, c = idx - g * D;
+            if (idx >= GT * D || g >= nh) continue;
+            const int64_t gh = (int64_t)gi * a.ws.n_q_heads + h0 + g;
+            const bool none = f_l[it] <= 0.f;  // a group without tokens
+            a.merged_out[gh * D + c] = none ? 0.f : f_o[it] / f_l[it];
+            if (c == 0 && a.merged_lse) a.merged_lse[gh] = none ? -INFINITY : f_m[it] * kLn2 + logf(f_l[it]);
+        }
+    } else {
+        for_each_segment(a.ws, a.tab, segment);
+    }
     if constexpr (MODE == kModeLogits) {
         if (win_fill > 0) flush_window();
     }

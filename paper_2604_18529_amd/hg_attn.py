@@ -86,6 +86,8 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_partial_workspace_size.argtypes = [D, R, i32, ctypes.POINTER(sz)]
     lib.hg_attn_partial.argtypes = [D, R, i32, vp, vp, vp, vp, sz, vp]
     lib.hg_attn_partial_static.argtypes = [D, R, i32, vp, vp, vp, vp]
+    lib.hg_attn_partial_merge_workspace_size.argtypes = [D, R, i32, vp, i32, ctypes.POINTER(sz)]
+    lib.hg_attn_partial_merge.argtypes = [D, R, i32, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.hg_attn_merge_workspace_size.argtypes = [i32, ctypes.POINTER(sz)]
     lib.hg_attn_merge.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.hg_attn_topk_workspace_size.argtypes = [D, R, i32, vp, i32, i32, ctypes.POINTER(sz)]
@@ -114,7 +116,7 @@ def load_library() -> ctypes.CDLL:
     lib.hg_attn_profile_times.argtypes = [ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32)]
     for name in (
         "hg_attn_partial_workspace_size", "hg_attn_partial", "hg_attn_partial_static", "hg_attn_profile_times",
-        "hg_attn_merge_workspace_size", "hg_attn_merge",
+        "hg_attn_merge_workspace_size", "hg_attn_merge", "hg_attn_partial_merge_workspace_size", "hg_attn_partial_merge",
         "hg_attn_merge2_workspace_size", "hg_attn_merge2", "hg_attn_gather_workspace_size", "hg_attn_gather",
         "hg_attn_topk_workspace_size", "hg_attn_topk",
         "hg_attn_full_workspace_size", "hg_attn_full", "hg_attn_plan", "hg_attn_set_span_tokens", "hg_attn_set_topk_mode",
@@ -348,6 +350,55 @@ def hg_attn_partial_static(q, k, v, seq_lens, ranges, scale=None, *, m=None, l=N
     _note_stream(stream, m, l, o)
     del keep
     return m, l, o
+
+
+def hg_attn_partial_merge_workspace_size(desc, packed_ranges, group_ptr) -> int:
+    gp = np.ascontiguousarray(group_ptr, dtype=np.int32)
+    sz = ctypes.c_size_t()
+    _check(load_library().hg_attn_partial_merge_workspace_size(ctypes.byref(desc), packed_ranges, _n_ranges(packed_ranges),
+                                                               gp.ctypes.data, gp.size - 1, ctypes.byref(sz)),
+           "hg_attn_partial_merge_workspace_size")
+    return sz.value
+
+
+def hg_attn_partial_merge(q, k, v, seq_lens, ranges, group_ptr, scale=None, *, m=None, l=None, o=None, out=None, lse=None,
+                          want_lse=True, workspace=None, stream=None, desc=None, block_table=None):
+    """hg_attn_partial and hg_attn_merge in one call (one kernel launch on small inputs).
+    Returns (m, l, o, out, lse)."""
+    lib = load_library()
+    if desc is None:
+        desc, keep = make_desc(q, k, v, seq_lens, scale, block_table)
+    else:
+        keep = None
+    packed = pack_ranges(ranges)
+    R = _n_ranges(packed)
+    gp = np.ascontiguousarray(group_ptr, dtype=np.int32)
+    if gp.ndim != 1 or gp.size < 1:
+        raise ValueError("group_ptr must be CSR offsets [n_groups+1]")
+    n_groups = gp.size - 1
+    dev = q.device
+    Hq, d = q.shape[1], q.shape[2]
+    if m is None:
+        m = torch.empty((R, Hq), dtype=torch.float32, device=dev)
+    if l is None:
+        l = torch.empty((R, Hq), dtype=torch.float32, device=dev)
+    if o is None:
+        o = torch.empty((R, Hq, d), dtype=torch.float32, device=dev)
+    if out is None:
+        out = torch.empty((n_groups, Hq, d), dtype=torch.float32, device=dev)
+    if lse is None and want_lse:
+        lse = torch.empty((n_groups, Hq), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace, ws_bytes = _workspace(hg_attn_partial_merge_workspace_size(desc, packed, gp), dev, None)
+    else:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(dev):
+        st = lib.hg_attn_partial_merge(ctypes.byref(desc), packed, R, gp.ctypes.data, n_groups, _ptr(m), _ptr(l), _ptr(o),
+                                       _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, _stream_handle(stream))
+    _check(st, "hg_attn_partial_merge")
+    _note_stream(stream, m, l, o, out, lse, workspace)
+    del keep
+    return m, l, o, out, lse
 
 
 def hg_attn_merge(m, l, o, group_ptr, *, out=None, lse=None, want_lse=True, workspace=None, stream=None):

@@ -86,6 +86,38 @@ def test_static_scratch_entry_point_validates_like_partial(lib):
     assert call(big, packed=pm, n=len(many)) == -5
 
 
+def test_partial_merge_validates_before_any_launch(lib):
+    """hg_attn_partial_merge: the checks of both calls it stands for, on the host, before anything
+    is enqueued (compute_units() is not asked for: without a GPU nothing may touch the runtime)."""
+    good = B.pack_ranges([(0, 0, 10), (0, 10, 20)])
+    gp = np.array([0, 2], dtype=np.int32)
+
+    def call(desc, packed=good, n=2, groups=gp.ctypes.data, g=1, m=FAKE, l=FAKE, o=FAKE, out=FAKE, ws=FAKE * 16, ws_bytes=1 << 40):
+        return lib.hg_attn_partial_merge(ctypes.byref(desc), packed, n, groups, g, m, l, o, out, None, ws, ws_bytes, None)
+
+    assert call(_desc([20], dtype=7)) == -3
+    assert call(_desc([20], d=96)) == -2
+    assert call(_desc([20]), packed=B.pack_ranges([(0, 0, 10), (0, 10, 21)])) == -4
+    assert call(_desc([20]), groups=None) == -1
+    assert call(_desc([20]), groups=np.array([0, 1], dtype=np.int32).ctypes.data) == -4  # the groups must cover the ranges
+    assert call(_desc([20]), groups=np.array([1, 2], dtype=np.int32).ctypes.data) == -4
+    assert call(_desc([20]), out=None) == -1
+    assert call(_desc([20]), m=None) == -1
+    assert call(_desc([20]), g=70000) == -2
+    sz = ctypes.c_size_t()
+    assert lib.hg_attn_partial_merge_workspace_size(ctypes.byref(_desc([20])), good, 2, gp.ctypes.data, 1, ctypes.byref(sz)) == 0
+    assert lib.hg_attn_partial_merge_workspace_size(ctypes.byref(_desc([20])), good, 2, gp.ctypes.data, 1, None) == -1
+    big = _desc([5000000], hq=64, hkv=64)
+    pm = B.pack_ranges([(0, 0, 5000000)])
+    assert lib.hg_attn_partial_merge_workspace_size(ctypes.byref(big), pm, 1, np.array([0, 1], dtype=np.int32).ctypes.data, 1,
+                                                    ctypes.byref(sz)) == 0
+    assert sz.value > 4096
+    assert lib.hg_attn_partial_merge(ctypes.byref(big), pm, 1, np.array([0, 1], dtype=np.int32).ctypes.data, 1, FAKE, FAKE, FAKE,
+                                     FAKE, None, FAKE * 16, 64, None) == -5  # workspace too small
+    assert call(_desc([20]), packed=None, n=0, groups=np.array([0], dtype=np.int32).ctypes.data, g=0, m=None, l=None, o=None,
+                out=None) == 0  # nothing to do
+
+
 def test_measurement_aids_validate_their_arguments(lib):
     assert lib.hg_attn_calibration_stream(None, 1 << 30, FAKE, 32, 1, 0, None) == -1
     assert lib.hg_attn_calibration_stream(FAKE, 1 << 30, None, 32, 1, 0, None) == -1   # writes need a destination
