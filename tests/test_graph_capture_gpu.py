@@ -133,3 +133,49 @@ def test_selection_flows_replay_from_a_graph(mode):
     finally:
         hg.hg_attn_set_span_tokens(0)
         hg.hg_attn_set_topk_mode(0)
+
+
+def test_partial_merge_one_launch_path_replays_from_a_graph():
+    """hg_attn_partial_merge on an input small enough for its one-launch path, recorded once and
+    replayed with new queries: every replay equals the eager call and the oracle."""
+    hg.hg_attn_set_span_tokens(0)
+    w = W.make_workload(W.WORKLOADS[0], DEV)
+    spec = W.WORKLOADS[0]
+    desc, keep = hg.make_desc(w.q, w.k, w.v, w.seq_lens, w.scale)
+    packed = hg.pack_ranges(w.ranges)
+    R, Hq, d = len(w.ranges), spec.n_q_heads, spec.head_dim
+    m = torch.empty((R, Hq), dtype=torch.float32, device=DEV)
+    l = torch.empty_like(m)
+    o = torch.empty((R, Hq, d), dtype=torch.float32, device=DEV)
+    out = torch.empty((spec.batch, Hq, d), dtype=torch.float32, device=DEV)
+    lse = torch.empty((spec.batch, Hq), dtype=torch.float32, device=DEV)
+    ws = torch.empty(max(binding.hg_attn_partial_merge_workspace_size(desc, packed, w.group_ptr), 256), dtype=torch.uint8, device=DEV)
+
+    def step():
+        hg.hg_attn_partial_merge(w.q, w.k, w.v, w.seq_lens, packed, w.group_ptr, w.scale, m=m, l=l, o=o, out=out, lse=lse,
+                                 workspace=ws, desc=desc)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(84)
+    for rep in range(3):
+        w.q.copy_(torch.randn(w.q.shape, generator=gen, device=DEV, dtype=torch.float32))
+        out.zero_(); m.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        g_out, g_lse, g_m = out.clone(), lse.clone(), m.clone()
+        out.zero_(); m.zero_()
+        step()
+        torch.cuda.synchronize()
+        assert torch.equal(g_out, out) and torch.equal(g_lse, lse) and torch.equal(g_m, m), "replay %d" % rep
+        ref, rlse = oracle.attn_full(to_np(w.q), *kv_np(w), w.seq_lens, w.scale)
+        check_out(g_out, g_lse, ref, rlse, "graph replay %d" % rep)
+    del keep
