@@ -149,7 +149,7 @@ hg_status hg_attn_merge(const float *m, const float *l, const float *o, const in
  * and 4.2.3 on one device: the triples of every range and the recombined output of every group),
  * for callers that want both.  The results are those of the two calls (the merged output up to
  * the order of summation).  group_ptr must cover the ranges exactly (group_ptr[0] == 0,
- * group_ptr[n_groups] == n_ranges).  When the input is small -- one query head per lane group
+ * group_ptr[n_groups] == n_ranges) and the ranges of a group belong to one sequence.  When the input is small -- one query head per lane group
  * (32-bit storage, or 16-bit storage without a query group), a contiguous cache, at most 16
  * groups and 64 ranges, few enough (group, KV head) pairs for one workgroup each and few enough
  * tokens per group for a workgroup to stream them in the time a launch takes -- the whole call

@@ -82,6 +82,9 @@ def test_random_case(case):
     out, lse = hg.hg_attn_merge(m, l, o, gp)
     ref, rlse = oracle.attn_merge(mo, lo, oo, gp)
     check_out(out, lse, ref, rlse, what + " merge")
+    pm, pl, po, pout, plse = hg.hg_attn_partial_merge(w.q, k_dev, v_dev, w.seq_lens, ranges, gp, w.scale, block_table=table)
+    check_triples(pm, pl, po, mo, lo, oo, what + " partial_merge triples")
+    check_out(pout, plse, ref, rlse, what + " partial_merge")
     fout, flse = hg.hg_attn_full(w.q, k_dev, v_dev, w.seq_lens, w.scale, block_table=table)
     fref, frlse = oracle.attn_full(qn, kn, vn, w.seq_lens, w.scale)
     check_out(fout, flse, fref, frlse, what + " full")
